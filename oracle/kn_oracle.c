@@ -1,0 +1,269 @@
+/*
+ * kn_oracle.c -- CPU oracle for the KiloNeRF rendering path (TEST INFRASTRUCTURE).
+ *
+ * Written from the paper's definitions, one function per step, no blocking, fusion or
+ * reordering.  Only tests, the smoke check and the benchmark's cpu_baseline leg use it.
+ * Build: gcc -O2 -ffp-contract=off -fPIC -shared (add -fopenmp for the threaded build;
+ * the loops over independent rays / points are the only parallel ones).
+ *
+ * Readings of the paper taken here (each is also pinned by a CPU test):
+ *  - Eq. 4 is printed without the minus sign; alpha = 1 - exp(-sigma*delta) is used, the
+ *    only reading under which constant density gives transmittance exp(-sigma*distance).
+ *  - delta is the constant lattice spacing `step` for every sample (Sec. 3.4: K fixes the
+ *    distance between sampled points); skipped samples do not stretch it.
+ *  - Lattice points sit at the middle of each step: t_k = t_near + (k + 1/2) * step.
+ *  - The 3-D cell index of Eq. 6 is linearised x slowest, z fastest; cells are half open,
+ *    so a point on the upper face of the AABB is outside.
+ *  - The network receives the global position x (Eq. 7), not a cell-local one.
+ *  - Encoding gamma_L(p) = [p, sin(2^k p), cos(2^k p) for k = 0..L-1] without a factor
+ *    of pi (3 + 6L values; 63 for L = 10 and 27 for L = 4).
+ *  - Layers: e_x -> H ReLU -> H ReLU -> (1 + H): output 0 is the density, passed through
+ *    ReLU; outputs 1..H are the feature vector, no activation; [feature, gamma(d)] -> H
+ *    ReLU -> 3 sigmoid (Sec. 3.2, "Network Architecture").
+ *  - Early termination (Sec. 3.4): after sample i has been blended, stop if T < eps
+ *    (strictly); eps = 0 turns it off.  The background colour is added with weight T.
+ */
+#include "kn_oracle.h"
+
+#include <math.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+#define KNO_MAX_H   256
+#define KNO_MAX_ENC 128
+
+int kno_num_threads(void)
+{
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
+
+int64_t kno_params_per_net(int32_t H, int32_t L_pos, int32_t L_dir)
+{
+    int64_t ex = 3 + 6 * (int64_t)L_pos, ed = 3 + 6 * (int64_t)L_dir;
+    return (ex * H + H) + ((int64_t)H * H + H) + ((int64_t)H * (H + 1) + (H + 1)) +
+           ((H + ed) * H + H) + ((int64_t)H * 3 + 3);
+}
+
+void kno_posenc(const float p[3], int32_t L, double *out)
+{
+    for (int a = 0; a < 3; ++a) out[a] = (double)p[a];
+    for (int k = 0; k < L; ++k) {
+        double f = ldexp(1.0, k); /* 2^k */
+        for (int a = 0; a < 3; ++a) {
+            out[3 + 6 * k + a] = sin(f * (double)p[a]);
+            out[3 + 6 * k + 3 + a] = cos(f * (double)p[a]);
+        }
+    }
+}
+
+int32_t kno_grid_index(const float bmin[3], const float bmax[3], const int32_t res[3],
+                       const float x[3])
+{
+    int32_t idx[3];
+    for (int a = 0; a < 3; ++a) {
+        /* Eq. 6 evaluated literally in fp32: cell size first, then the quotient. */
+        float extent = bmax[a] - bmin[a];
+        float cell = extent / (float)res[a];
+        float rel = x[a] - bmin[a];
+        float u = rel / cell;
+        float fl = floorf(u);
+        if (!(fl >= 0.0f) || !(fl < (float)res[a])) return -1; /* also rejects NaN */
+        idx[a] = (int32_t)fl;
+    }
+    return (idx[0] * res[1] + idx[1]) * res[2] + idx[2];
+}
+
+int kno_cell_ids(const kno_scene *s, const float *points, int64_t M, int32_t *ids)
+{
+    if (!s || (M > 0 && (!points || !ids))) return -1;
+    for (int64_t m = 0; m < M; ++m)
+        ids[m] = kno_grid_index(s->aabb_min, s->aabb_max, s->res, points + 3 * m);
+    return 0;
+}
+
+int kno_bucket(const int32_t *ids, int64_t M, int32_t N, int32_t *counts, int32_t *offsets,
+               int32_t *perm)
+{
+    if (N < 0 || M < 0 || !counts || !offsets || (M > 0 && (!ids || !perm))) return -1;
+    for (int32_t n = 0; n <= N; ++n) counts[n] = 0;
+    for (int64_t m = 0; m < M; ++m) {
+        int32_t b = ids[m] < 0 ? N : ids[m];
+        if (b > N) return -1;
+        counts[b] += 1;
+    }
+    offsets[0] = 0;
+    for (int32_t n = 0; n <= N; ++n) offsets[n + 1] = offsets[n] + counts[n];
+    int32_t *cursor = (int32_t *)malloc(sizeof(int32_t) * (size_t)(N + 1));
+    if (!cursor) return -2;
+    for (int32_t n = 0; n <= N; ++n) cursor[n] = offsets[n];
+    for (int64_t m = 0; m < M; ++m) { /* ascending m => stable */
+        int32_t b = ids[m] < 0 ? N : ids[m];
+        perm[cursor[b]++] = (int32_t)m;
+    }
+    free(cursor);
+    return 0;
+}
+
+/* y[o] = b[o] + sum_i in[i] * W[i][o], W stored row = input, column = output. */
+static void affine(const float *W, const float *b, const double *in, int n_in, int n_out,
+                   double *out)
+{
+    for (int o = 0; o < n_out; ++o) {
+        double acc = (double)b[o];
+        for (int i = 0; i < n_in; ++i) acc += in[i] * (double)W[(size_t)i * n_out + o];
+        out[o] = acc;
+    }
+}
+
+static double relu(double v) { return v > 0.0 ? v : 0.0; }
+
+int kno_mlp(const kno_scene *s, int32_t n, const float x[3], const float d[3], double *sigma,
+            double *rgb)
+{
+    const int H = s->hidden;
+    const int ex = 3 + 6 * s->L_pos, ed = 3 + 6 * s->L_dir;
+    if (H < 1 || H > KNO_MAX_H || ex > KNO_MAX_ENC || ed > KNO_MAX_ENC) return -1;
+    const int64_t P = kno_params_per_net(H, s->L_pos, s->L_dir);
+    const float *w = s->weights + (size_t)n * (size_t)P;
+    const float *W1 = w;                 const float *b1 = W1 + (size_t)ex * H;
+    const float *W2 = b1 + H;            const float *b2 = W2 + (size_t)H * H;
+    const float *W3 = b2 + H;            const float *b3 = W3 + (size_t)H * (H + 1);
+    const float *W4 = b3 + (H + 1);      const float *b4 = W4 + (size_t)(H + ed) * H;
+    const float *W5 = b4 + H;            const float *b5 = W5 + (size_t)H * 3;
+
+    double gx[KNO_MAX_ENC], in4[KNO_MAX_H + KNO_MAX_ENC];
+    double h1[KNO_MAX_H], h2[KNO_MAX_H], o3[KNO_MAX_H + 1], h4[KNO_MAX_H], o5[3];
+
+    kno_posenc(x, s->L_pos, gx);
+    affine(W1, b1, gx, ex, H, h1);
+    for (int i = 0; i < H; ++i) h1[i] = relu(h1[i]);
+    affine(W2, b2, h1, H, H, h2);
+    for (int i = 0; i < H; ++i) h2[i] = relu(h2[i]);
+    affine(W3, b3, h2, H, H + 1, o3);
+    *sigma = relu(o3[0]);
+    for (int i = 0; i < H; ++i) in4[i] = o3[1 + i]; /* feature vector: no activation */
+    kno_posenc(d, s->L_dir, in4 + H);
+    affine(W4, b4, in4, H + ed, H, h4);
+    for (int i = 0; i < H; ++i) h4[i] = relu(h4[i]);
+    affine(W5, b5, h4, H, 3, o5);
+    for (int c = 0; c < 3; ++c) rgb[c] = 1.0 / (1.0 + exp(-o5[c]));
+    return 0;
+}
+
+int kno_eval_points(const kno_scene *s, const float *points, const float *dirs, int64_t M,
+                    double *sigma, double *rgb, int32_t *ids)
+{
+    if (!s || (M > 0 && (!points || !dirs || !sigma || !rgb))) return -1;
+    int err = 0;
+#ifdef _OPENMP
+#pragma omp parallel for schedule(dynamic, 256)
+#endif
+    for (int64_t m = 0; m < M; ++m) {
+        int32_t id = kno_grid_index(s->aabb_min, s->aabb_max, s->res, points + 3 * m);
+        if (ids) ids[m] = id;
+        if (id < 0) {
+            sigma[m] = 0.0;
+            rgb[3 * m] = rgb[3 * m + 1] = rgb[3 * m + 2] = 0.0;
+        } else if (kno_mlp(s, id, points + 3 * m, dirs + 3 * m, sigma + m, rgb + 3 * m) != 0) {
+            err = -1;
+        }
+    }
+    return err;
+}
+
+/* Position of lattice point k on a ray: t_k = t_near + (k + 1/2) step, x = o + t_k d,
+ * each as one fused multiply-add in fp32 (never accumulated along the ray). */
+static void lattice_point(const float o[3], const float d[3], float t_near, float step, int32_t k,
+                          float x[3])
+{
+    float t = fmaf((float)k + 0.5f, step, t_near);
+    for (int a = 0; a < 3; ++a) x[a] = fmaf(t, d[a], o[a]);
+}
+
+static int sample_is_kept(const kno_scene *s, const float x[3])
+{
+    if (kno_grid_index(s->aabb_min, s->aabb_max, s->res, x) < 0) return 0; /* outside the AABB */
+    if (s->occ_res[0] == 0) return 1;                                      /* no occupancy grid */
+    int32_t v = kno_grid_index(s->aabb_min, s->aabb_max, s->occ_res, x);
+    return v >= 0 && s->occupancy[v] != 0;
+}
+
+int32_t kno_march(const kno_scene *s, const float o[3], const float d[3], float t_near,
+                  float step, int32_t K, int32_t *ks)
+{
+    int32_t n = 0;
+    for (int32_t k = 0; k < K; ++k) {
+        float x[3];
+        lattice_point(o, d, t_near, step, k, x);
+        if (sample_is_kept(s, x)) ks[n++] = k;
+    }
+    return n;
+}
+
+int32_t kno_composite(const double *sigma, const double *rgb, int32_t n, double step, double eps,
+                      const double bg[3], double out[3], double *T_out, double *margin_out)
+{
+    double T = 1.0, C[3] = {0.0, 0.0, 0.0}, margin = INFINITY;
+    int32_t used = 0;
+    for (int32_t i = 0; i < n; ++i) {
+        double alpha = 1.0 - exp(-sigma[i] * step);          /* Eq. 4 (sign restored) */
+        for (int c = 0; c < 3; ++c) C[c] += T * alpha * rgb[3 * i + c]; /* Eq. 2 */
+        T *= (1.0 - alpha);                                   /* Eq. 3 */
+        ++used;
+        if (eps > 0.0) {
+            double mg = fabs(T - eps) / eps;
+            if (mg < margin) margin = mg;
+            if (T < eps) break;                               /* Sec. 3.4, ERT */
+        }
+    }
+    for (int c = 0; c < 3; ++c) out[c] = C[c] + T * bg[c];
+    if (T_out) *T_out = T;
+    if (margin_out) *margin_out = margin;
+    return used;
+}
+
+int kno_render(const kno_scene *s, const float *rays_o, const float *rays_d, int64_t R,
+               float t_near, float step, int32_t K, float term_eps, const float bg[3],
+               double *rgb_out, int32_t *n_eval, double *T_final, double *margin)
+{
+    if (!s || K < 0 || (R > 0 && (!rays_o || !rays_d || !rgb_out)) || !bg) return -1;
+    int err = 0;
+#ifdef _OPENMP
+#pragma omp parallel for schedule(dynamic, 16)
+#endif
+    for (int64_t r = 0; r < R; ++r) {
+        const float *o = rays_o + 3 * r, *d = rays_d + 3 * r;
+        const double eps = (double)term_eps, dstep = (double)step;
+        double T = 1.0, C[3] = {0.0, 0.0, 0.0}, mg_min = INFINITY;
+        int32_t used = 0;
+        for (int32_t k = 0; k < K; ++k) {
+            float x[3];
+            lattice_point(o, d, t_near, step, k, x);
+            if (!sample_is_kept(s, x)) continue;
+            int32_t id = kno_grid_index(s->aabb_min, s->aabb_max, s->res, x);
+            double sg, col[3];
+            if (kno_mlp(s, id, x, d, &sg, col) != 0) { err = -1; break; }
+            double alpha = 1.0 - exp(-sg * dstep);
+            for (int c = 0; c < 3; ++c) C[c] += T * alpha * col[c];
+            T *= (1.0 - alpha);
+            ++used;
+            if (eps > 0.0) {
+                double mg = fabs(T - eps) / eps;
+                if (mg < mg_min) mg_min = mg;
+                if (T < eps) break;
+            }
+        }
+        for (int c = 0; c < 3; ++c) rgb_out[3 * r + c] = C[c] + T * (double)bg[c];
+        if (n_eval) n_eval[r] = used;
+        if (T_final) T_final[r] = T;
+        if (margin) margin[r] = mg_min;
+    }
+    return err;
+}

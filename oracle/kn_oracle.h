@@ -1,0 +1,96 @@
+/*
+ * kn_oracle.h -- CPU oracle for the KiloNeRF rendering path (TEST INFRASTRUCTURE).
+ *
+ * A plain, slow, single-source C implementation of what the rendering path of
+ * "KiloNeRF: Speeding up Neural Radiance Fields with Thousands of Tiny MLPs"
+ * computes.  It exists only to check the HIP library: tests, the smoke check and
+ * the cpu_baseline leg of the benchmark may call it; the product path never does.
+ * It shares no code with the HIP path.
+ *
+ * Precision: everything that decides an integer (sample lattice position, cell
+ * index, occupancy voxel) is taken in fp32 with one fixed operation sequence,
+ * because the index is only well defined for one precision.  Everything else
+ * (positional encoding, the affine layers, activations, compositing) runs in
+ * fp64 on the fp32 inputs.
+ *
+ * All pointers are host pointers.  No function allocates memory that outlives
+ * the call.  Return value 0 = ok, negative = invalid argument.
+ */
+#ifndef KN_ORACLE_H
+#define KN_ORACLE_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct {
+    int32_t res[3];          /* network grid r = (rx, ry, rz)           (Sec. 3.2)   */
+    float   aabb_min[3];     /* b_min                                    (Sec. 3.2)   */
+    float   aabb_max[3];     /* b_max                                                 */
+    int32_t hidden;          /* H: units per hidden layer (32 in the paper, Sec. 3.2) */
+    int32_t L_pos, L_dir;    /* frequencies of the encoding of x and of d             */
+    const float *weights;    /* N * kno_params_per_net(H, L_pos, L_dir) values        */
+    int32_t occ_res[3];      /* occupancy grid resolution, all 0 = no grid            */
+    const uint8_t *occupancy;/* occ_res[0]*occ_res[1]*occ_res[2] bytes, x slowest     */
+} kno_scene;
+
+/* Number of parameters of one tiny MLP.  Layers (Sec. 3.2, "Network Architecture"):
+ * L1 e_x->H, L2 H->H, L3 H->1+H (density, feature), L4 H+e_d->H, L5 H->3,
+ * e_x = 3+6*L_pos, e_d = 3+6*L_dir; each layer has a bias. */
+int64_t kno_params_per_net(int32_t hidden, int32_t L_pos, int32_t L_dir);
+
+/* gamma_L(p) of a 3-vector: [p, then per k: sin(2^k p) (3), cos(2^k p) (3)].  out has 3+6L. */
+void kno_posenc(const float p[3], int32_t L, double *out);
+
+/* Spatial binning g(x) (Sec. 3.2, Eq. 6) for a grid of resolution res over the
+ * scene AABB, fp32: per axis floor((x-bmin)/((bmax-bmin)/r)).  Returns the linear
+ * index (ix*ry+iy)*rz+iz, or -1 if x falls outside [bmin,bmax) on any axis. */
+int32_t kno_grid_index(const float bmin[3], const float bmax[3], const int32_t res[3],
+                       const float x[3]);
+
+/* Point -> network id for M points (ids[m] = -1 outside). */
+int kno_cell_ids(const kno_scene *s, const float *points, int64_t M, int32_t *ids);
+
+/* Stable bucketing by network id: counts[N+1] (slot N counts id=-1), offsets[N+2]
+ * (exclusive scan, offsets[N+1]=M), perm[M]: sample indices ordered by id with -1 last,
+ * equal ids keep ascending sample index. */
+int kno_bucket(const int32_t *ids, int64_t M, int32_t N, int32_t *counts, int32_t *offsets,
+               int32_t *perm);
+
+/* One network n on one input (Sec. 3.2, Eq. 7): sigma, rgb[3]. */
+int kno_mlp(const kno_scene *s, int32_t n, const float x[3], const float d[3],
+            double *sigma, double *rgb);
+
+/* eval_grouped: per point, cell id then its network.  Outside points: id -1, sigma 0, rgb 0. */
+int kno_eval_points(const kno_scene *s, const float *points, const float *dirs, int64_t M,
+                    double *sigma, double *rgb, int32_t *ids);
+
+/* Sample lattice of one ray with empty-space skipping (Sec. 3.4): writes the step indices
+ * k in [0,K) whose point lies inside the AABB in an occupied voxel, ascending; returns
+ * how many (<= K). */
+int32_t kno_march(const kno_scene *s, const float o[3], const float d[3], float t_near,
+                  float step, int32_t K, int32_t *ks);
+
+/* Front-to-back alpha blending with early termination (Sec. 3.1 Eq. 2-4, Sec. 3.4):
+ * n samples (sigma, rgb) of constant spacing step.  Returns the number of samples
+ * composited (n unless terminated early); out[3] = C + T*bg, *T_out = final T,
+ * *margin_out = min over composited samples of |T_i - eps| / eps (inf if eps == 0). */
+int32_t kno_composite(const double *sigma, const double *rgb, int32_t n, double step, double eps,
+                      const double bg[3], double out[3], double *T_out, double *margin_out);
+
+/* Render R rays.  rgb_out R*3.  Optional per-ray outputs (nullable): n_eval (samples
+ * evaluated = composited), T_final, margin (see kno_composite).  Samples behind the
+ * termination point are never evaluated. */
+int kno_render(const kno_scene *s, const float *rays_o, const float *rays_d, int64_t R,
+               float t_near, float step, int32_t K, float term_eps, const float bg[3],
+               double *rgb_out, int32_t *n_eval, double *T_final, double *margin);
+
+/* Number of threads the loops over rays / points use (1 unless built with OpenMP). */
+int kno_num_threads(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif
