@@ -1,0 +1,178 @@
+/*
+ * kilonerf.h -- C ABI of the MI355X (gfx950) implementation of the KiloNeRF rendering path.
+ *
+ * Paper: "KiloNeRF: Speeding up Neural Radiance Fields with Thousands of Tiny MLPs".
+ * The library evaluates a regular grid of tiny per-cell MLPs on ray samples and composites
+ * them into pixels.  Every step runs in hand-written HIP kernels; there is no CPU fallback.
+ *
+ * Conventions
+ *  - "dev" pointers are HIP device pointers on the device that was current when the scene
+ *    was created; "host" pointers are ordinary host memory.  The library only borrows
+ *    caller buffers for the duration of a call (scene inputs: see kn_scene_create).
+ *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls enqueue
+ *    work on it and return without waiting unless stated otherwise.
+ *  - Every function returns 0 (KN_OK) or a negative kn_status.  Arguments are validated on
+ *    the host before anything is launched; sizes of 0 are valid and do nothing.
+ *  - Positions and directions are fp32, row-major (n, 3).  Directions must have unit length:
+ *    the sample spacing along a ray is `step` only then.
+ *
+ * Canonical weight layout (what the caller supplies): for network n = (ix*ry + iy)*rz + iz the
+ * P = kn_params_per_net(...) values
+ *     W1[ex][H] b1[H]  W2[H][H] b2[H]  W3[H][1+H] b3[1+H]  W4[H+ed][H] b4[H]  W5[H][3] b5[3]
+ * with W[row = input][column = output], ex = 3+6*L_pos, ed = 3+6*L_dir.  Column 0 of layer 3 is
+ * the density, columns 1..H the feature vector; rows 0..H-1 of layer 4 take the feature vector,
+ * rows H.. take gamma(d).  Activations (Sec. 3.2 "Network Architecture"): ReLU after layers
+ * 1, 2, 4 and on the density; none on the feature vector; sigmoid on the colour.
+ * Encoding gamma_L(p) = [p_x p_y p_z, then for k = 0..L-1: sin(2^k p) (xyz), cos(2^k p) (xyz)].
+ */
+#ifndef KILONERF_H
+#define KILONERF_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    KN_OK = 0,
+    KN_E_INVALID_ARG = -1, /* null pointer, negative size, bad grid, non-finite parameter   */
+    KN_E_UNSUPPORTED = -2, /* valid request this build has no kernel for (H, dtype, limits) */
+    KN_E_WORKSPACE = -3,   /* workspace missing, misaligned or smaller than required        */
+    KN_E_HIP = -4,         /* a HIP runtime call failed (see kn_last_hip_error)             */
+    KN_E_NO_DEVICE = -5    /* no usable gfx950 device                                        */
+} kn_status;
+
+typedef enum { KN_F32 = 0, KN_F16 = 1, KN_BF16 = 2 } kn_dtype;
+
+/* Scene = AABB + network grid + per-cell MLP weights + optional occupancy grid (Sec. 3.2, 3.4). */
+typedef struct {
+    int32_t res[3];          /* network grid r = (rx, ry, rz), each >= 1, product <= 65535       */
+    float aabb_min[3];       /* b_min                                                             */
+    float aabb_max[3];       /* b_max, > b_min per axis                                           */
+    int32_t hidden;          /* H: 32 or 64                                                       */
+    int32_t L_pos, L_dir;    /* encoding frequencies; this build supports (10, 4)                 */
+    int32_t wdtype;          /* kn_dtype of `weights`.  KN_F32: fp32 arithmetic on the vector     */
+                             /* ALUs.  KN_F16 / KN_BF16: 16-bit weights and activations on the    */
+                             /* matrix cores with fp32 accumulation                               */
+    const void *weights;     /* dev, N*P elements of wdtype in the canonical layout               */
+    int32_t occ_res[3];      /* occupancy grid resolution; all 0 = no grid (whole AABB occupied)  */
+    const uint8_t *occupancy;/* dev, occ_res[0]*occ_res[1]*occ_res[2] bytes (0 = empty), x slowest*/
+} kn_scene_desc;
+
+typedef struct kn_scene kn_scene; /* opaque */
+
+/* Counters of one kn_render call (filled when requested; forces a stream synchronise). */
+typedef struct {
+    int64_t rays;             /* R                                                             */
+    int64_t waves;            /* passes of the march -> bucket -> MLP -> blend loop            */
+    int64_t samples_evaluated;/* samples pushed through the networks (incl. ones behind the    */
+                              /* termination point inside a wave)                              */
+    int64_t samples_blended;  /* samples that entered Eq. 2 (what the method itself evaluates) */
+    int64_t slots;            /* sample slots sorted over all waves (incl. unused ones)        */
+} kn_render_stats;
+
+const char *kn_error_string(int status);
+/* hipError_t of the most recent failed HIP call on this thread (0 if none). */
+int kn_last_hip_error(void);
+
+/* Number of parameters of one network in the canonical layout; -1 for invalid arguments. */
+int64_t kn_params_per_net(int32_t hidden, int32_t L_pos, int32_t L_dir);
+
+/*
+ * Create a scene on the current HIP device.  Validates the descriptor, then allocates (hipMalloc)
+ * and fills, on `stream`, the library's own device copies: the occupancy grid packed to bits and,
+ * for 16-bit types, the weights re-ordered into matrix-core operand order.  For KN_F32 the
+ * caller's `weights` buffer itself is used and must stay valid and unchanged for the scene's
+ * lifetime; for the other inputs the caller's buffers may be released once `stream` has
+ * completed the work enqueued by this call.  This is the only call that allocates device memory.
+ */
+int kn_scene_create(const kn_scene_desc *desc, void *stream, kn_scene **out);
+int kn_scene_destroy(kn_scene *scene); /* waits for the device, frees the library's copies */
+
+/* Workspace size (bytes) that kn_bucket / kn_eval_grouped need for up to max_points points and
+ * kn_render for up to max_rays rays; pass 0 for the one not needed.  The workspace is a dev
+ * buffer, 256-byte aligned, owned by the caller; calls sharing one workspace must not overlap. */
+int kn_workspace_bytes(const kn_scene *scene, int64_t max_points, int64_t max_rays, int64_t *out_bytes);
+
+/* Eq. 6: network index of M points.  ids[m] = (ix*ry + iy)*rz + iz, or -1 outside [b_min, b_max).
+ * fp32 arithmetic exactly as written in Eq. 6: floor((x - b_min) / ((b_max - b_min) / r)). */
+int kn_cell_ids(const kn_scene *scene, void *stream, const float *points /*dev M*3*/, int64_t M,
+                int32_t *ids /*dev M*/);
+
+/* Sec. 3.5 ("order the input batch such that subsequent inputs are processed by the same
+ * network"): stable bucketing of M ids in [-1, N).  counts[N+1] (slot N = outside), offsets[N+2]
+ * (exclusive scan of counts), perm[M] = sample indices sorted by id, -1 last, ties by index.
+ * counts / offsets may be NULL.  M <= 2^30. */
+int kn_bucket(const kn_scene *scene, void *stream, const int32_t *ids /*dev M*/, int64_t M,
+              int32_t *counts /*dev N+1, nullable*/, int32_t *offsets /*dev N+2, nullable*/,
+              int32_t *perm /*dev M*/, void *workspace, int64_t workspace_bytes);
+
+/* Eq. 7: (c, sigma) = f_theta(g(x))(x, d) for M points: cell assignment, bucketing, then the
+ * fused per-network MLP (encoding + 5 layers) over each bucket.  Outputs in caller order; points
+ * outside the AABB get sigma = 0, rgb = 0, id = -1.  cell_id / counts / perm are optional
+ * outputs as in kn_cell_ids / kn_bucket. */
+int kn_eval_grouped(const kn_scene *scene, void *stream, const float *points /*dev M*3*/,
+                    const float *dirs /*dev M*3*/, int64_t M, float *sigma /*dev M*/,
+                    float *rgb /*dev M*3*/, int32_t *cell_id /*dev M, nullable*/,
+                    int32_t *counts /*dev N+1, nullable*/, int32_t *perm /*dev M, nullable*/,
+                    void *workspace, int64_t workspace_bytes);
+
+/* Sec. 3.4 sampling with empty-space skipping, one stage on its own: for each ray, starting at
+ * lattice index k_begin[r] (0 if NULL), collect up to S kept samples.  Lattice: t_k = t_near +
+ * (k + 1/2)*step, x_k = o + t_k*d (fp32, one fused multiply-add each), k < K; a sample is kept
+ * iff x_k is inside the AABB and its occupancy voxel is non-zero.  out_k[r*S + j] = j-th kept
+ * index (unused slots -1), out_count[r] = kept, out_k_next[r] (nullable) = where to resume
+ * (K when the ray is exhausted). */
+int kn_march(const kn_scene *scene, void *stream, const float *rays_o /*dev R*3*/,
+             const float *rays_d /*dev R*3*/, int64_t R, float t_near, float step, int32_t K,
+             const int32_t *k_begin /*dev R, nullable*/, int32_t S, int32_t *out_k /*dev R*S*/,
+             int32_t *out_count /*dev R*/, int32_t *out_k_next /*dev R, nullable*/);
+
+/* Eq. 2-4 with early ray termination (Sec. 3.4), one stage on its own: ray r owns samples
+ * offsets[r] .. offsets[r+1]-1 of sigma / rgb in front-to-back order; alpha = 1 - exp(-sigma*step),
+ * C += T*alpha*c, T *= 1 - alpha, stop after a sample leaves T < term_eps (0 = never);
+ * rgb_out = C + T*bg.  T_out / n_used are optional per-ray outputs. */
+int kn_composite(void *stream, const float *sigma /*dev*/, const float *rgb /*dev n*3*/,
+                 const int32_t *offsets /*dev R+1*/, int64_t R, float step, float term_eps,
+                 const float bg[3] /*host*/, float *rgb_out /*dev R*3*/, float *T_out /*dev R, nullable*/,
+                 int32_t *n_used /*dev R, nullable*/);
+
+/* The whole path (Sec. 3.1 Eq. 1-4, Sec. 3.2, Sec. 3.4): render R rays.  Samples are taken in
+ * waves from near to far; rays whose transmittance fell below term_eps, or that ran out of
+ * lattice points, drop out between waves.  The result per ray equals the sequential definition
+ * (march, evaluate, blend, stop at T < term_eps) regardless of how waves are cut.
+ * R*2^ceil(log2 K) must be <= 2^32.  The call synchronises `stream` between waves. */
+int kn_render(const kn_scene *scene, void *stream, const float *rays_o /*dev R*3*/,
+              const float *rays_d /*dev R*3, unit*/, int64_t R, float t_near, float step,
+              int32_t K /*max lattice points per ray*/, float term_eps /*0 = off*/,
+              const float bg[3] /*host*/, float *rgb_out /*dev R*3*/,
+              kn_render_stats *stats /*host, nullable*/, void *workspace, int64_t workspace_bytes);
+
+/* Tuning knobs of kn_render (process-wide, for experiments; defaults are used otherwise):
+ * samples per ray in the first wave, and the slot budget per ray that later waves share out
+ * among the surviving rays.  Values <= 0 restore the default. */
+int kn_set_render_params(int32_t first_wave_samples, int32_t slots_per_ray);
+
+/* Per-stage device time of kn_render / kn_eval_grouped, measured with HIP events recorded on the
+ * caller's stream around each stage (process-wide switch, off by default).  While enabled,
+ * kn_eval_grouped also synchronises the stream before returning.  kn_profile_read copies the
+ * totals accumulated since the last reset. */
+typedef struct {
+    double ms_cell;        /* point -> cell id (kn_eval_grouped only; fused into marching in kn_render) */
+    double ms_march;       /* marching + empty-space skipping                                          */
+    double ms_bucket;      /* radix passes, bucket boundaries, tile list                               */
+    double ms_mlp;         /* the fused grouped-MLP kernel                                             */
+    double ms_blend;       /* blending + early termination + live-ray compaction                       */
+    int64_t mlp_launches;  /* launches of the grouped-MLP kernel                                       */
+    int64_t mlp_samples;   /* samples those launches evaluated                                         */
+    int64_t bucket_keys;   /* keys sorted (incl. unused slots)                                         */
+    int64_t calls;         /* kn_render + kn_eval_grouped calls                                        */
+} kn_profile;
+int kn_profile_enable(int on);
+int kn_profile_read(kn_profile *out /*host*/, int reset);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

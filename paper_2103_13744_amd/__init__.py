@@ -1,0 +1,262 @@
+"""Python binding of libkilonerf_hip.so: argument marshalling only.
+
+Every step of the rendering path (cell assignment, bucketing, the grouped tiny MLPs, marching,
+blending) runs in the HIP kernels behind the C ABI declared in ``include/kilonerf.h``; this
+module turns torch device tensors into pointers, sizes and a stream handle and checks status
+codes.  There is no CPU or PyTorch fallback: if the library is missing or a call fails, an
+exception is raised.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libkilonerf_hip.so")
+
+KN_F32, KN_F16, KN_BF16 = 0, 1, 2
+DTYPES = {"f32": KN_F32, "f16": KN_F16, "bf16": KN_BF16}
+
+EXPORTS = ["kn_error_string", "kn_last_hip_error", "kn_params_per_net", "kn_scene_create", "kn_scene_destroy",
+           "kn_workspace_bytes", "kn_cell_ids", "kn_bucket", "kn_eval_grouped", "kn_march", "kn_composite",
+           "kn_render", "kn_set_render_params", "kn_profile_enable", "kn_profile_read"]
+
+
+class KnError(RuntimeError):
+    pass
+
+
+class SceneDesc(C.Structure):
+    _fields_ = [("res", C.c_int32 * 3), ("aabb_min", C.c_float * 3), ("aabb_max", C.c_float * 3),
+                ("hidden", C.c_int32), ("L_pos", C.c_int32), ("L_dir", C.c_int32), ("wdtype", C.c_int32),
+                ("weights", C.c_void_p), ("occ_res", C.c_int32 * 3), ("occupancy", C.c_void_p)]
+
+
+class RenderStats(C.Structure):
+    _fields_ = [("rays", C.c_int64), ("waves", C.c_int64), ("samples_evaluated", C.c_int64),
+                ("samples_blended", C.c_int64), ("slots", C.c_int64)]
+
+
+class Profile(C.Structure):
+    _fields_ = [("ms_cell", C.c_double), ("ms_march", C.c_double), ("ms_bucket", C.c_double), ("ms_mlp", C.c_double),
+                ("ms_blend", C.c_double), ("mlp_launches", C.c_int64), ("mlp_samples", C.c_int64),
+                ("bucket_keys", C.c_int64), ("calls", C.c_int64)]
+
+
+_lib = None
+
+
+def load_library(build_if_missing: bool = True):
+    """dlopen the in-tree library (building it first only if it does not exist)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        if not build_if_missing:
+            raise KnError("libkilonerf_hip.so has not been built (run paper_2103_13744_amd/build.py)")
+        from .build import build
+        build(force=True)
+    L = C.CDLL(LIB_PATH)
+    vp, i32, i64, f32 = C.c_void_p, C.c_int32, C.c_int64, C.c_float
+    L.kn_error_string.restype = C.c_char_p
+    L.kn_error_string.argtypes = [C.c_int]
+    L.kn_last_hip_error.restype = C.c_int
+    L.kn_params_per_net.restype = i64
+    L.kn_params_per_net.argtypes = [i32, i32, i32]
+    L.kn_scene_create.argtypes = [C.POINTER(SceneDesc), vp, C.POINTER(vp)]
+    L.kn_scene_destroy.argtypes = [vp]
+    L.kn_workspace_bytes.argtypes = [vp, i64, i64, C.POINTER(i64)]
+    L.kn_cell_ids.argtypes = [vp, vp, vp, i64, vp]
+    L.kn_bucket.argtypes = [vp, vp, vp, i64, vp, vp, vp, vp, i64]
+    L.kn_eval_grouped.argtypes = [vp, vp, vp, vp, i64, vp, vp, vp, vp, vp, vp, i64]
+    L.kn_march.argtypes = [vp, vp, vp, vp, i64, f32, f32, i32, vp, i32, vp, vp, vp]
+    L.kn_composite.argtypes = [vp, vp, vp, vp, i64, f32, f32, C.POINTER(f32 * 3), vp, vp, vp]
+    L.kn_render.argtypes = [vp, vp, vp, vp, i64, f32, f32, i32, f32, C.POINTER(f32 * 3), vp,
+                            C.POINTER(RenderStats), vp, i64]
+    L.kn_set_render_params.argtypes = [i32, i32]
+    L.kn_profile_enable.argtypes = [C.c_int]
+    L.kn_profile_read.argtypes = [C.POINTER(Profile), C.c_int]
+    _lib = L
+    return L
+
+
+def _check(rc: int, what: str):
+    if rc != 0:
+        L = load_library()
+        raise KnError("%s failed: %s (status %d, hip error %d)" %
+                      (what, L.kn_error_string(rc).decode(), rc, L.kn_last_hip_error()))
+
+
+def _ptr(t, dtype=None, allow_none=False):
+    import torch
+    if t is None:
+        if allow_none:
+            return None
+        raise KnError("missing tensor argument")
+    if not t.is_cuda or not t.is_contiguous():
+        raise KnError("tensor arguments must be contiguous device tensors")
+    if dtype is not None and t.dtype != dtype:
+        raise KnError("expected dtype %s, got %s" % (dtype, t.dtype))
+    return t.data_ptr()
+
+
+def _stream():
+    import torch
+    return torch.cuda.current_stream().cuda_stream
+
+
+def params_per_net(hidden: int, L_pos: int = 10, L_dir: int = 4) -> int:
+    return int(load_library().kn_params_per_net(hidden, L_pos, L_dir))
+
+
+def set_render_params(first_wave_samples: int = 0, slots_per_ray: int = 0):
+    _check(load_library().kn_set_render_params(first_wave_samples, slots_per_ray), "kn_set_render_params")
+
+
+def profile_enable(on: bool):
+    _check(load_library().kn_profile_enable(1 if on else 0), "kn_profile_enable")
+
+
+def profile_read(reset: bool = True) -> dict:
+    p = Profile()
+    _check(load_library().kn_profile_read(C.byref(p), 1 if reset else 0), "kn_profile_read")
+    return {k: getattr(p, k) for k, _ in Profile._fields_}
+
+
+class Scene:
+    """Device-resident KiloNeRF scene.  ``weights``: device tensor (N, P) of float32 / float16 /
+    bfloat16 in the canonical layout; ``occupancy``: device uint8 tensor (ox, oy, oz) or None."""
+
+    def __init__(self, res, aabb_min, aabb_max, hidden, weights, occupancy=None, L_pos=10, L_dir=4):
+        import torch
+        self.L = load_library()
+        wd = {torch.float32: KN_F32, torch.float16: KN_F16, torch.bfloat16: KN_BF16}.get(weights.dtype)
+        if wd is None:
+            raise KnError("unsupported weight dtype %s" % weights.dtype)
+        d = SceneDesc()
+        d.res[:] = [int(v) for v in res]
+        d.aabb_min[:] = [float(v) for v in aabb_min]
+        d.aabb_max[:] = [float(v) for v in aabb_max]
+        d.hidden, d.L_pos, d.L_dir, d.wdtype = int(hidden), int(L_pos), int(L_dir), wd
+        d.weights = _ptr(weights)
+        if occupancy is None:
+            d.occ_res[:] = [0, 0, 0]
+            d.occupancy = None
+        else:
+            d.occ_res[:] = list(occupancy.shape)
+            d.occupancy = _ptr(occupancy, torch.uint8)
+        self.N = int(res[0]) * int(res[1]) * int(res[2])
+        self.hidden = int(hidden)
+        self.device = weights.device
+        self._keep = (weights, occupancy)     # KN_F32 scenes borrow the weight buffer
+        h = C.c_void_p()
+        _check(self.L.kn_scene_create(C.byref(d), _stream(), C.byref(h)), "kn_scene_create")
+        self.h = h
+        self._ws = None
+
+    def close(self):
+        if getattr(self, "h", None):
+            self.L.kn_scene_destroy(self.h)
+            self.h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    # -- workspace -----------------------------------------------------------------------
+    def workspace_bytes(self, max_points=0, max_rays=0) -> int:
+        out = C.c_int64()
+        _check(self.L.kn_workspace_bytes(self.h, int(max_points), int(max_rays), C.byref(out)), "kn_workspace_bytes")
+        return out.value
+
+    def _workspace(self, max_points=0, max_rays=0):
+        import torch
+        need = self.workspace_bytes(max_points, max_rays)
+        if self._ws is None or self._ws.numel() < need:
+            self._ws = torch.empty(need, dtype=torch.uint8, device=self.device)
+        return self._ws
+
+    # -- stages --------------------------------------------------------------------------
+    def cell_ids(self, points):
+        import torch
+        M = points.shape[0]
+        ids = torch.empty(M, dtype=torch.int32, device=self.device)
+        _check(self.L.kn_cell_ids(self.h, _stream(), _ptr(points, torch.float32) if M else None, M,
+                                  _ptr(ids) if M else None), "kn_cell_ids")
+        return ids
+
+    def bucket(self, ids):
+        import torch
+        M = ids.shape[0]
+        counts = torch.empty(self.N + 1, dtype=torch.int32, device=self.device)
+        offsets = torch.empty(self.N + 2, dtype=torch.int32, device=self.device)
+        perm = torch.empty(M, dtype=torch.int32, device=self.device)
+        ws = self._workspace(max_points=max(M, 1))
+        _check(self.L.kn_bucket(self.h, _stream(), _ptr(ids, torch.int32) if M else None, M, _ptr(counts),
+                                _ptr(offsets), _ptr(perm) if M else None, _ptr(ws), ws.numel()), "kn_bucket")
+        return counts, offsets, perm
+
+    def eval_grouped(self, points, dirs, want_aux=False, out=None):
+        import torch
+        M = points.shape[0]
+        if out is None:
+            sigma = torch.empty(M, dtype=torch.float32, device=self.device)
+            rgb = torch.empty((M, 3), dtype=torch.float32, device=self.device)
+        else:
+            sigma, rgb = out
+        ids = counts = perm = None
+        if want_aux:
+            ids = torch.empty(M, dtype=torch.int32, device=self.device)
+            counts = torch.empty(self.N + 1, dtype=torch.int32, device=self.device)
+            perm = torch.empty(M, dtype=torch.int32, device=self.device)
+        ws = self._workspace(max_points=max(M, 1))
+        p = (lambda t: _ptr(t) if (t is not None and M) else None)
+        _check(self.L.kn_eval_grouped(self.h, _stream(), p(points), p(dirs), M, p(sigma), p(rgb), p(ids),
+                                      _ptr(counts, allow_none=True), p(perm), _ptr(ws), ws.numel()), "kn_eval_grouped")
+        if want_aux:
+            return sigma, rgb, ids, counts, perm
+        return sigma, rgb
+
+    def march(self, rays_o, rays_d, t_near, step, K, S=None, k_begin=None):
+        import torch
+        R = rays_o.shape[0]
+        S = int(K if S is None else S)
+        out_k = torch.empty((R, S), dtype=torch.int32, device=self.device)
+        cnt = torch.empty(R, dtype=torch.int32, device=self.device)
+        nxt = torch.empty(R, dtype=torch.int32, device=self.device)
+        _check(self.L.kn_march(self.h, _stream(), _ptr(rays_o, torch.float32), _ptr(rays_d, torch.float32), R,
+                               float(t_near), float(step), int(K), _ptr(k_begin, allow_none=True), S, _ptr(out_k),
+                               _ptr(cnt), _ptr(nxt)), "kn_march")
+        return out_k, cnt, nxt
+
+    def render(self, rays_o, rays_d, t_near, step, K, term_eps=0.0, bg=(0.0, 0.0, 0.0), want_stats=False, out=None):
+        import torch
+        R = rays_o.shape[0]
+        rgb = torch.empty((R, 3), dtype=torch.float32, device=self.device) if out is None else out
+        ws = self._workspace(max_rays=max(R, 1))
+        st = RenderStats()
+        bgc = (C.c_float * 3)(*[float(v) for v in bg])
+        _check(self.L.kn_render(self.h, _stream(), _ptr(rays_o, torch.float32) if R else None,
+                                _ptr(rays_d, torch.float32) if R else None, R, float(t_near), float(step), int(K),
+                                float(term_eps), C.byref(bgc), _ptr(rgb) if R else None,
+                                C.byref(st) if want_stats else None, _ptr(ws), ws.numel()), "kn_render")
+        if want_stats:
+            return rgb, {k: getattr(st, k) for k, _ in RenderStats._fields_}
+        return rgb
+
+
+def composite(sigma, rgb, offsets, step, term_eps=0.0, bg=(0.0, 0.0, 0.0)):
+    import torch
+    L = load_library()
+    R = offsets.shape[0] - 1
+    out = torch.empty((R, 3), dtype=torch.float32, device=offsets.device)
+    T = torch.empty(R, dtype=torch.float32, device=offsets.device)
+    used = torch.empty(R, dtype=torch.int32, device=offsets.device)
+    bgc = (C.c_float * 3)(*[float(v) for v in bg])
+    n = sigma.shape[0]
+    _check(L.kn_composite(_stream(), _ptr(sigma, torch.float32) if n else None, _ptr(rgb, torch.float32) if n else None,
+                          _ptr(offsets, torch.int32), R, float(step), float(term_eps), C.byref(bgc), _ptr(out), _ptr(T),
+                          _ptr(used)), "kn_composite")
+    return out, T, used

@@ -1,0 +1,262 @@
+// Host side of the C ABI: scene objects, validation, workspace sizing, kn_eval_grouped.
+#include "kn_common.h"
+
+#include <math.h>
+#include <new>
+#include <string.h>
+
+thread_local int g_kn_last_hip_error = 0;
+
+int kn_cell_keys(const kn_scene *sc, hipStream_t st, const float *points, int64_t M, int32_t *ids, int32_t *keys);
+int64_t kn_render_ws_bytes(const kn_scene *sc, int64_t R);
+int kn_mlp_f32_launch(const kn_scene *sc, hipStream_t st, const KnSampleSrc &src, const KnBucketOut &b, int64_t max_tiles,
+                      float *sigma, float *rgb);
+int kn_mlp_mfma_launch(const kn_scene *sc, hipStream_t st, const KnSampleSrc &src, const KnBucketOut &b, int64_t max_tiles,
+                       float *sigma, float *rgb);
+int kn_mlp_mfma_tile_len(const kn_scene *sc);
+
+kn_profile g_kn_profile = {};
+bool g_kn_profile_on = false;
+static hipEvent_t g_events[8];
+static bool g_events_ready = false;
+
+KnStageTimer::KnStageTimer(hipStream_t s) : st(s), on(g_kn_profile_on), n(0)
+{
+    if (on && !g_events_ready) {
+        for (auto &e : g_events)
+            if (hipEventCreate(&e) != hipSuccess) on = false;
+        g_events_ready = on;
+    }
+}
+void KnStageTimer::mark()
+{
+    if (on && n < 8) (void)hipEventRecord(g_events[n++], st);
+}
+float KnStageTimer::elapsed(int i) const
+{
+    float ms = 0.0f;
+    if (on && i + 1 < n) (void)hipEventElapsedTime(&ms, g_events[i], g_events[i + 1]);
+    return ms;
+}
+
+extern "C" int kn_profile_enable(int on)
+{
+    g_kn_profile_on = on != 0;
+    return KN_OK;
+}
+
+extern "C" int kn_profile_read(kn_profile *out, int reset)
+{
+    if (!out) return KN_E_INVALID_ARG;
+    *out = g_kn_profile;
+    if (reset) g_kn_profile = kn_profile{};
+    return KN_OK;
+}
+
+namespace {
+
+// one thread packs 32 consecutive voxels into one word (bit i of word w = voxel 32*w + i)
+__global__ void k_pack_occupancy(const uint8_t *__restrict__ occ, int64_t n_vox, uint32_t *__restrict__ bits)
+{
+    const int64_t w = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (w * 32 >= n_vox) return;
+    uint32_t v = 0;
+    for (int i = 0; i < 32; ++i) {
+        const int64_t j = w * 32 + i;
+        if (j < n_vox && occ[j] != 0) v |= (1u << i);
+    }
+    bits[w] = v;
+}
+
+// zero the outputs of the points that fell outside the AABB (bucket N of the sorted list)
+__global__ void k_zero_outside(const int32_t *__restrict__ perm, const int32_t *__restrict__ offsets, int32_t N, int64_t M,
+                               float *__restrict__ sigma, float *__restrict__ rgb)
+{
+    const int64_t first = offsets[N];
+    const int64_t j = first + (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (j >= M) return;
+    const int64_t idx = perm[j];
+    sigma[idx] = 0.0f;
+    rgb[3 * idx] = rgb[3 * idx + 1] = rgb[3 * idx + 2] = 0.0f;
+}
+
+bool make_grid(const float bmin[3], const float bmax[3], const int32_t res[3], KnGrid &g)
+{
+    for (int a = 0; a < 3; ++a) {
+        if (res[a] < 1 || !isfinite(bmin[a]) || !isfinite(bmax[a]) || !(bmax[a] > bmin[a])) return false;
+        const float extent = bmax[a] - bmin[a];
+        const float cell = extent / (float)res[a]; // Eq. 6: (b_max - b_min) / r in fp32
+        if (!isfinite(cell) || !(cell > 0.0f)) return false;
+        g.bmin[a] = bmin[a];
+        g.cell[a] = cell;
+        g.res[a] = res[a];
+    }
+    return true;
+}
+
+} // namespace
+
+extern "C" const char *kn_error_string(int status)
+{
+    switch (status) {
+    case KN_OK: return "ok";
+    case KN_E_INVALID_ARG: return "invalid argument";
+    case KN_E_UNSUPPORTED: return "unsupported configuration";
+    case KN_E_WORKSPACE: return "workspace missing, misaligned or too small";
+    case KN_E_HIP: return "HIP runtime error";
+    case KN_E_NO_DEVICE: return "no usable gfx950 device";
+    default: return "unknown status";
+    }
+}
+
+extern "C" int kn_last_hip_error(void) { return g_kn_last_hip_error; }
+
+extern "C" int64_t kn_params_per_net(int32_t H, int32_t L_pos, int32_t L_dir)
+{
+    if (H < 1 || L_pos < 0 || L_dir < 0 || H > 4096 || L_pos > 64 || L_dir > 64) return -1;
+    const int64_t ex = 3 + 6 * (int64_t)L_pos, ed = 3 + 6 * (int64_t)L_dir, h = H;
+    return (ex * h + h) + (h * h + h) + (h * (h + 1) + (h + 1)) + ((h + ed) * h + h) + (h * 3 + 3);
+}
+
+static int validate_desc(const kn_scene_desc *d)
+{
+    if (!d || !d->weights) return KN_E_INVALID_ARG;
+    KnGrid g;
+    if (!make_grid(d->aabb_min, d->aabb_max, d->res, g)) return KN_E_INVALID_ARG;
+    const int64_t n = (int64_t)d->res[0] * d->res[1] * d->res[2];
+    if (n > 65535) return KN_E_UNSUPPORTED;
+    if (d->wdtype != KN_F32 && d->wdtype != KN_F16 && d->wdtype != KN_BF16) return KN_E_INVALID_ARG;
+    if (d->hidden < 1 || d->L_pos < 0 || d->L_dir < 0) return KN_E_INVALID_ARG;
+    if ((d->hidden != 32 && d->hidden != 64) || d->L_pos != 10 || d->L_dir != 4) return KN_E_UNSUPPORTED;
+    const bool any = d->occ_res[0] || d->occ_res[1] || d->occ_res[2];
+    if (any) {
+        if (!d->occupancy) return KN_E_INVALID_ARG;
+        if (!make_grid(d->aabb_min, d->aabb_max, d->occ_res, g)) return KN_E_INVALID_ARG;
+        const int64_t v = (int64_t)d->occ_res[0] * d->occ_res[1] * d->occ_res[2];
+        if (v > 0x7fffffffLL) return KN_E_UNSUPPORTED;
+    }
+    return KN_OK;
+}
+
+extern "C" int kn_scene_create(const kn_scene_desc *desc, void *stream, kn_scene **out)
+{
+    if (!out) return KN_E_INVALID_ARG;
+    *out = nullptr;
+    KN_TRY(validate_desc(desc));
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess) return KN_E_NO_DEVICE;
+    hipDeviceProp_t prop;
+    KN_HIP(hipGetDeviceProperties(&prop, dev));
+    if (strncmp(prop.gcnArchName, "gfx950", 6) != 0) return KN_E_NO_DEVICE;
+
+    kn_scene *sc = new (std::nothrow) kn_scene();
+    if (!sc) return KN_E_INVALID_ARG;
+    sc->desc = *desc;
+    sc->N = desc->res[0] * desc->res[1] * desc->res[2];
+    sc->P = kn_params_per_net(desc->hidden, desc->L_pos, desc->L_dir);
+    sc->device = dev;
+    make_grid(desc->aabb_min, desc->aabb_max, desc->res, sc->net_grid);
+    sc->has_occ = desc->occ_res[0] != 0;
+    sc->occ_bits = nullptr;
+    sc->packed_w = nullptr;
+    sc->packed_halfs_per_net = 0;
+    hipStream_t st = (hipStream_t)stream;
+    int rc = KN_OK;
+    if (sc->has_occ) {
+        make_grid(desc->aabb_min, desc->aabb_max, desc->occ_res, sc->occ_grid);
+        const int64_t vox = (int64_t)desc->occ_res[0] * desc->occ_res[1] * desc->occ_res[2];
+        const int64_t words = kn_div_up(vox, 32);
+        if (hipMalloc((void **)&sc->occ_bits, (size_t)words * 4) != hipSuccess) {
+            rc = KN_E_HIP;
+        } else {
+            hipLaunchKernelGGL(k_pack_occupancy, dim3((unsigned)kn_div_up(words, 256)), dim3(256), 0, st, desc->occupancy, vox,
+                               sc->occ_bits);
+            if (hipGetLastError() != hipSuccess) rc = KN_E_HIP;
+        }
+    } else {
+        sc->occ_grid = sc->net_grid;
+    }
+    if (rc == KN_OK && desc->wdtype != KN_F32) rc = kn_mlp_pack_weights(sc, st);
+    if (rc != KN_OK) {
+        kn_scene_destroy(sc);
+        return rc;
+    }
+    *out = sc;
+    return KN_OK;
+}
+
+extern "C" int kn_scene_destroy(kn_scene *sc)
+{
+    if (!sc) return KN_OK;
+    (void)hipDeviceSynchronize();
+    if (sc->occ_bits) (void)hipFree(sc->occ_bits);
+    if (sc->packed_w) (void)hipFree(sc->packed_w);
+    delete sc;
+    return KN_OK;
+}
+
+int kn_mlp_tile_len(const kn_scene *sc) { return sc->desc.wdtype == KN_F32 ? 256 : kn_mlp_mfma_tile_len(sc); }
+
+int kn_mlp_launch(const kn_scene *sc, hipStream_t st, const KnSampleSrc &src, const KnBucketOut &b, int64_t M, float *sigma,
+                  float *rgb)
+{
+    if (M <= 0) return KN_OK;
+    const int64_t max_tiles = kn_max_tiles(M, sc->N, kn_mlp_tile_len(sc));
+    if (sc->desc.wdtype == KN_F32) return kn_mlp_f32_launch(sc, st, src, b, max_tiles, sigma, rgb);
+    return kn_mlp_mfma_launch(sc, st, src, b, max_tiles, sigma, rgb);
+}
+
+static int64_t eval_ws_bytes(const kn_scene *sc, int64_t M)
+{
+    return kn_align_up((M > 0 ? M : 1) * 4, 256) + kn_bucket_ws_bytes(M, sc->N);
+}
+
+extern "C" int kn_workspace_bytes(const kn_scene *sc, int64_t max_points, int64_t max_rays, int64_t *out_bytes)
+{
+    if (!sc || !out_bytes || max_points < 0 || max_rays < 0) return KN_E_INVALID_ARG;
+    if (max_points > (1ll << 30) || max_rays > (1ll << 30)) return KN_E_UNSUPPORTED;
+    int64_t a = max_points > 0 ? eval_ws_bytes(sc, max_points) : 0;
+    int64_t b = max_rays > 0 ? kn_render_ws_bytes(sc, max_rays) : 0;
+    *out_bytes = (a > b ? a : b) + 256;
+    return KN_OK;
+}
+
+extern "C" int kn_eval_grouped(const kn_scene *sc, void *stream, const float *points, const float *dirs, int64_t M,
+                               float *sigma, float *rgb, int32_t *cell_id, int32_t *counts, int32_t *perm, void *workspace,
+                               int64_t workspace_bytes)
+{
+    if (!sc || M < 0 || (M > 0 && (!points || !dirs || !sigma || !rgb))) return KN_E_INVALID_ARG;
+    if (M > (1ll << 30)) return KN_E_UNSUPPORTED;
+    if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < eval_ws_bytes(sc, M)) return KN_E_WORKSPACE;
+    hipStream_t st = (hipStream_t)stream;
+    KnCarver ws(workspace, workspace_bytes);
+    int32_t *keys = ws.carve<int32_t>(M);
+    if (!ws.ok()) return KN_E_WORKSPACE;
+    KnStageTimer tm(st);
+    tm.mark();
+    KN_TRY(kn_cell_keys(sc, st, points, M, cell_id, keys));
+    tm.mark();
+    KnBucketOut bo;
+    KN_TRY(kn_bucket_run(st, keys, M, sc->N, kn_mlp_tile_len(sc), counts, nullptr, perm, ws, &bo));
+    if (M == 0) return KN_OK;
+    tm.mark();
+    KnSampleSrc src{};
+    src.points = points;
+    src.dirs = dirs;
+    KN_TRY(kn_mlp_launch(sc, st, src, bo, M, sigma, rgb));
+    hipLaunchKernelGGL(k_zero_outside, dim3((unsigned)kn_div_up(M, 256)), dim3(256), 0, st, bo.perm, bo.offsets, sc->N, M, sigma,
+                       rgb);
+    KN_CHECK_LAUNCH();
+    tm.mark();
+    if (tm.on) {
+        KN_HIP(hipStreamSynchronize(st));
+        g_kn_profile.ms_cell += tm.elapsed(0);
+        g_kn_profile.ms_bucket += tm.elapsed(1);
+        g_kn_profile.ms_mlp += tm.elapsed(2);
+        g_kn_profile.mlp_launches += 1;
+        g_kn_profile.mlp_samples += M; // includes points outside the AABB (they cost no MLP work)
+        g_kn_profile.bucket_keys += M;
+        g_kn_profile.calls += 1;
+    }
+    return KN_OK;
+}

@@ -1,0 +1,462 @@
+// Point -> cell assignment (Eq. 6) and stable bucketing of samples by network id (Sec. 3.5:
+// inputs are ordered so that consecutive inputs belong to the same network).
+//
+// Bucketing is a least-significant-digit radix sort on 8-bit digits of the key (network id, with
+// N standing for "outside"), each pass = per-block digit histogram -> exclusive scan of the
+// (digit, block) table -> stable scatter.  Inside a block, stability comes from ranking each
+// 64-element row of a wavefront with ballot-built peer masks and wave-private LDS counters.
+// Bucket counts and the tile list of the grouped MLP are then read off the sorted keys.
+#include "kn_common.h"
+
+namespace {
+
+constexpr int RS_THREADS = 256;
+constexpr int RS_ROWS = 16;                       // 64-element rows per wavefront
+constexpr int RS_WAVES = RS_THREADS / KN_WAVE;    // 4
+constexpr int RS_TILE = RS_THREADS * RS_ROWS;     // 4096 keys per block
+constexpr int SCAN_THREADS = 256;
+constexpr int SCAN_ITEMS = 8;
+constexpr int SCAN_TILE = SCAN_THREADS * SCAN_ITEMS;
+
+// ---------------------------------------------------------------------------------------------
+__global__ void k_fill_i32(int32_t *p, int64_t n, int32_t v)
+{
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = v;
+}
+
+__global__ void k_cell_ids(const float *__restrict__ pts, int64_t M, KnGrid g, int32_t *__restrict__ ids,
+                           int32_t *__restrict__ keys, int32_t N)
+{
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= M) return;
+    float x = pts[3 * i], y = pts[3 * i + 1], z = pts[3 * i + 2];
+    int32_t id = kn_grid_index(g, x, y, z);
+    if (ids) ids[i] = id;
+    if (keys) keys[i] = id < 0 ? N : id;
+}
+
+__global__ void k_ids_to_keys(const int32_t *__restrict__ ids, int64_t M, int32_t N, int32_t *__restrict__ keys)
+{
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= M) return;
+    int32_t id = ids[i];
+    keys[i] = (id < 0 || id > N) ? N : id;
+}
+
+// ---------------------------------------------------------------------------------------------
+// block-wide exclusive scan helper (256 threads), returns the exclusive prefix of v and the total
+__device__ __forceinline__ int32_t block_exclusive_scan(int32_t v, int32_t *lds /*RS_WAVES+1*/, int32_t &total)
+{
+    const int lane = threadIdx.x & (KN_WAVE - 1), w = threadIdx.x / KN_WAVE;
+    int32_t inc = v;
+#pragma unroll
+    for (int d = 1; d < KN_WAVE; d <<= 1) {
+        int32_t o = __shfl_up(inc, d, KN_WAVE);
+        if (lane >= d) inc += o;
+    }
+    __syncthreads(); // protects lds reuse between consecutive calls
+    if (lane == KN_WAVE - 1) lds[w] = inc;
+    __syncthreads();
+    int32_t wbase = 0, tot = 0;
+#pragma unroll
+    for (int i = 0; i < SCAN_THREADS / KN_WAVE; ++i) {
+        int32_t s = lds[i];
+        if (i < w) wbase += s;
+        tot += s;
+    }
+    total = tot;
+    return wbase + inc - v;
+}
+
+__global__ void __launch_bounds__(SCAN_THREADS) k_scan_sums(const int32_t *__restrict__ in, int64_t n,
+                                                            int32_t *__restrict__ sums)
+{
+    __shared__ int32_t lds[8];
+    int64_t base = (int64_t)blockIdx.x * SCAN_TILE + (int64_t)threadIdx.x * SCAN_ITEMS;
+    int32_t s = 0;
+#pragma unroll
+    for (int i = 0; i < SCAN_ITEMS; ++i)
+        if (base + i < n) s += in[base + i];
+    int32_t total;
+    block_exclusive_scan(s, lds, total);
+    if (threadIdx.x == 0) sums[blockIdx.x] = total;
+}
+
+__global__ void __launch_bounds__(SCAN_THREADS) k_scan_apply(const int32_t *__restrict__ in, int32_t *__restrict__ out,
+                                                             int64_t n, const int32_t *__restrict__ sums,
+                                                             int32_t n_sums, int32_t *__restrict__ total_out)
+{
+    __shared__ int32_t lds[8];
+    // prefix of the block sums in front of this block (and the grand total for block 0)
+    int32_t before = 0, all = 0;
+    for (int32_t i = threadIdx.x; i < n_sums; i += SCAN_THREADS) {
+        int32_t s = sums[i];
+        all += s;
+        if (i < (int32_t)blockIdx.x) before += s;
+    }
+    int32_t tot_before, tot_all;
+    block_exclusive_scan(before, lds, tot_before);
+    block_exclusive_scan(all, lds, tot_all);
+    if (blockIdx.x == 0 && threadIdx.x == 0 && total_out) *total_out = tot_all;
+
+    int64_t base = (int64_t)blockIdx.x * SCAN_TILE + (int64_t)threadIdx.x * SCAN_ITEMS;
+    int32_t v[SCAN_ITEMS], s = 0;
+#pragma unroll
+    for (int i = 0; i < SCAN_ITEMS; ++i) {
+        v[i] = (base + i < n) ? in[base + i] : 0;
+        s += v[i];
+    }
+    int32_t dummy;
+    int32_t run = tot_before + block_exclusive_scan(s, lds, dummy);
+#pragma unroll
+    for (int i = 0; i < SCAN_ITEMS; ++i) {
+        if (base + i < n) out[base + i] = run;
+        run += v[i];
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// radix pass, step 1: digit histogram of each 4096-key block -> table[digit * n_blocks + block]
+__global__ void __launch_bounds__(RS_THREADS) k_radix_hist(const int32_t *__restrict__ keys, int64_t M, int shift,
+                                                           int32_t n_blocks, int32_t *__restrict__ table)
+{
+    __shared__ int32_t hist[256];
+    hist[threadIdx.x] = 0;
+    __syncthreads();
+    int64_t base = (int64_t)blockIdx.x * RS_TILE;
+#pragma unroll 4
+    for (int r = 0; r < RS_ROWS; ++r) {
+        int64_t i = base + (int64_t)r * RS_THREADS + threadIdx.x;
+        if (i < M) atomicAdd(&hist[((uint32_t)keys[i] >> shift) & 255u], 1);
+    }
+    __syncthreads();
+    table[(int64_t)threadIdx.x * n_blocks + blockIdx.x] = hist[threadIdx.x];
+}
+
+// radix pass, step 3: stable scatter.  Wavefront w of block b owns keys
+// [b*4096 + w*1024, +1024) as 16 rows of 64; order of keys = (block, wave, row, lane).
+__global__ void __launch_bounds__(RS_THREADS)
+    k_radix_scatter(const int32_t *__restrict__ keys_in, const int32_t *__restrict__ vals_in,
+                    int32_t *__restrict__ keys_out, int32_t *__restrict__ vals_out, int64_t M, int shift,
+                    int32_t n_blocks, const int32_t *__restrict__ table_scanned)
+{
+    __shared__ int32_t cnt[RS_WAVES][256];
+    const int lane = threadIdx.x & (KN_WAVE - 1), w = threadIdx.x / KN_WAVE;
+#pragma unroll
+    for (int i = 0; i < RS_WAVES; ++i) cnt[i][threadIdx.x] = 0;
+    __syncthreads();
+
+    const int64_t wbase = (int64_t)blockIdx.x * RS_TILE + (int64_t)w * (RS_ROWS * KN_WAVE);
+    const uint64_t lt_mask = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
+    int32_t key[RS_ROWS], rank[RS_ROWS];
+
+#pragma unroll
+    for (int r = 0; r < RS_ROWS; ++r) {
+        const int64_t i = wbase + r * KN_WAVE + lane;
+        const bool valid = i < M;
+        key[r] = valid ? keys_in[i] : 0;
+        const uint32_t d = ((uint32_t)key[r] >> shift) & 255u;
+        uint64_t peers = __ballot(valid);
+#pragma unroll
+        for (int b = 0; b < 8; ++b) {
+            const bool bit = (d >> b) & 1u;
+            const uint64_t m = __ballot(bit);
+            peers &= bit ? m : ~m;
+        }
+        int32_t prior = 0;
+        if (valid) prior = cnt[w][d];
+        __builtin_amdgcn_wave_barrier();
+        const int n_peers = __popcll(peers);
+        const bool leader = valid && (lane == 63 - __clzll(peers));
+        if (leader) cnt[w][d] = prior + n_peers;
+        __builtin_amdgcn_wave_barrier();
+        rank[r] = prior + __popcll(peers & lt_mask);
+    }
+    __syncthreads();
+    {
+        // thread d: turn per-wave digit counts into global base positions
+        const int d = threadIdx.x;
+        int32_t run = table_scanned[(int64_t)d * n_blocks + blockIdx.x];
+#pragma unroll
+        for (int i = 0; i < RS_WAVES; ++i) {
+            int32_t c = cnt[i][d];
+            cnt[i][d] = run;
+            run += c;
+        }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int r = 0; r < RS_ROWS; ++r) {
+        const int64_t i = wbase + r * KN_WAVE + lane;
+        if (i < M) {
+            const uint32_t d = ((uint32_t)key[r] >> shift) & 255u;
+            const int32_t dst = cnt[w][d] + rank[r];
+            if (keys_out) keys_out[dst] = key[r];
+            vals_out[dst] = vals_in ? vals_in[i] : (int32_t)i;
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// start[key] = first position of `key` in the sorted list (start[] pre-filled with -1)
+__global__ void k_find_starts(const int32_t *__restrict__ sorted_keys, int64_t M, int32_t *__restrict__ start)
+{
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= M) return;
+    int32_t k = sorted_keys[i];
+    if (i == 0 || sorted_keys[i - 1] != k) start[k] = (int32_t)i;
+}
+
+// One block: resolve empty buckets (start = next non-empty start), then counts, offsets, tiles.
+constexpr int FIN_THREADS = 1024;
+__global__ void __launch_bounds__(FIN_THREADS)
+    k_finalize_buckets(int32_t *__restrict__ start /*N+1, in: first position or -1; out: offsets*/, int32_t N,
+                       int32_t M, int32_t tile_len, int32_t *__restrict__ counts /*N+1*/,
+                       int32_t *__restrict__ offsets /*N+2*/, KnTile *__restrict__ tiles,
+                       int32_t *__restrict__ n_tiles, int32_t *__restrict__ user_counts,
+                       int32_t *__restrict__ user_offsets)
+{
+    __shared__ int32_t sa[FIN_THREADS];
+    __shared__ int32_t sb[FIN_THREADS];
+    const int t = threadIdx.x;
+    const int n_entries = N + 1;
+    const int per = (n_entries + FIN_THREADS - 1) / FIN_THREADS;
+    const int lo = min(t * per, n_entries), hi = min(lo + per, n_entries);
+
+    // first defined start inside my chunk; starts of non-empty buckets increase with the key, so
+    // "next defined start to the right" is a suffix minimum
+    int32_t first = 0x7fffffff;
+    for (int i = lo; i < hi; ++i) {
+        int32_t s = start[i];
+        if (s >= 0) { first = s; break; }
+    }
+    sa[t] = first;
+    __syncthreads();
+    for (int d = 1; d < FIN_THREADS; d <<= 1) {
+        int32_t o = (t + d < FIN_THREADS) ? sa[t + d] : 0x7fffffff;
+        __syncthreads();
+        sa[t] = min(sa[t], o);
+        __syncthreads();
+    }
+    int32_t nxt = (t + 1 < FIN_THREADS) ? sa[t + 1] : 0x7fffffff;
+    if (nxt == 0x7fffffff) nxt = M;
+    for (int i = hi - 1; i >= lo; --i) { // resolve right-to-left inside the chunk
+        int32_t s = start[i];
+        if (s >= 0) nxt = s; else start[i] = nxt;
+    }
+    __syncthreads();
+    // counts, offsets, and number of tiles of my chunk (bucket N = outside gets no tiles)
+    int32_t my_tiles = 0;
+    for (int i = lo; i < hi; ++i) {
+        int32_t a = start[i];
+        int32_t b = (i + 1 < n_entries) ? start[i + 1] : M;
+        int32_t c = b - a;
+        counts[i] = c;
+        offsets[i] = a;
+        if (user_counts) user_counts[i] = c;
+        if (user_offsets) user_offsets[i] = a;
+        if (i < N) my_tiles += (c + tile_len - 1) / tile_len;
+    }
+    if (t == 0) {
+        offsets[n_entries] = M;
+        if (user_offsets) user_offsets[n_entries] = M;
+    }
+    sb[t] = my_tiles;
+    __syncthreads();
+    for (int d = 1; d < FIN_THREADS; d <<= 1) { // inclusive prefix sum
+        int32_t o = (t >= d) ? sb[t - d] : 0;
+        __syncthreads();
+        sb[t] += o;
+        __syncthreads();
+    }
+    int32_t tbase = sb[t] - my_tiles;
+    if (t == FIN_THREADS - 1) *n_tiles = sb[t];
+    for (int i = lo; i < hi && i < N; ++i) {
+        int32_t a = start[i];
+        int32_t b = (i + 1 < n_entries) ? start[i + 1] : M;
+        for (int32_t s = a; s < b; s += tile_len) {
+            KnTile tl;
+            tl.net = i;
+            tl.start = s;
+            tl.len = min(tile_len, b - s);
+            tl.pad = 0;
+            tiles[tbase++] = tl;
+        }
+    }
+}
+
+int launch_1d(int64_t n, int threads, dim3 &grid)
+{
+    int64_t blocks = kn_div_up(n, threads);
+    if (blocks > 0x7fffffffLL) return KN_E_UNSUPPORTED;
+    grid = dim3((unsigned)blocks);
+    return KN_OK;
+}
+
+} // namespace
+
+// ---------------------------------------------------------------------------------------------
+int kn_fill_i32(hipStream_t st, int32_t *p, int64_t n, int32_t v)
+{
+    if (n <= 0) return KN_OK;
+    dim3 grid;
+    KN_TRY(launch_1d(n, 256, grid));
+    hipLaunchKernelGGL(k_fill_i32, grid, dim3(256), 0, st, p, n, v);
+    KN_CHECK_LAUNCH();
+    return KN_OK;
+}
+
+int64_t kn_scan_tmp_len(int64_t n) { return kn_div_up(n > 0 ? n : 1, SCAN_TILE); }
+
+int kn_exclusive_scan_i32(hipStream_t st, const int32_t *in, int32_t *out, int64_t n, int32_t *tmp, int32_t *total)
+{
+    if (n <= 0) {
+        if (total) KN_TRY(kn_fill_i32(st, total, 1, 0));
+        return KN_OK;
+    }
+    int64_t nb = kn_div_up(n, SCAN_TILE);
+    if (nb > (1 << 24)) return KN_E_UNSUPPORTED;
+    hipLaunchKernelGGL(k_scan_sums, dim3((unsigned)nb), dim3(SCAN_THREADS), 0, st, in, n, tmp);
+    KN_CHECK_LAUNCH();
+    hipLaunchKernelGGL(k_scan_apply, dim3((unsigned)nb), dim3(SCAN_THREADS), 0, st, in, out, n, tmp, (int32_t)nb, total);
+    KN_CHECK_LAUNCH();
+    return KN_OK;
+}
+
+static int radix_passes(int32_t N)
+{
+    int bits = 1;
+    while ((1ll << bits) < (int64_t)N + 1) ++bits;
+    return (bits + 7) / 8;
+}
+
+int64_t kn_max_tiles(int64_t M, int32_t N, int32_t tile_len)
+{
+    return M / tile_len + (M < N ? M : N) + 1;
+}
+
+int64_t kn_bucket_ws_bytes(int64_t M, int32_t N)
+{
+    // mirrors the carve() sequence of kn_bucket_run (with the smallest tile length in use)
+    KnCarver c((void *)256, INT64_MAX / 2);
+    int64_t nblk = kn_div_up(M > 0 ? M : 1, RS_TILE);
+    c.carve<int32_t>(M);               // keys ping
+    c.carve<int32_t>(M);               // keys pong / sorted keys
+    c.carve<int32_t>(M);               // vals ping
+    c.carve<int32_t>(M);               // vals pong / perm
+    c.carve<int32_t>(256 * nblk);      // digit table
+    c.carve<int32_t>(256 * nblk);      // scanned digit table
+    c.carve<int32_t>(kn_scan_tmp_len(256 * nblk));
+    c.carve<int32_t>(N + 1);           // start
+    c.carve<int32_t>(N + 1);           // counts
+    c.carve<int32_t>(N + 2);           // offsets
+    c.carve<KnTile>(kn_max_tiles(M, N, 64));
+    c.carve<int32_t>(1);               // n_tiles
+    return c.used;
+}
+
+int kn_bucket_run(hipStream_t st, int32_t *keys, int64_t M, int32_t N, int32_t tile_len, int32_t *user_counts,
+                  int32_t *user_offsets, int32_t *user_perm, KnCarver &ws, KnBucketOut *out)
+{
+    if (M < 0 || M > (1ll << 30) || N < 1 || tile_len < 64) return KN_E_INVALID_ARG;
+    const int64_t nblk = kn_div_up(M > 0 ? M : 1, RS_TILE);
+    int32_t *keys_a = ws.carve<int32_t>(M);
+    int32_t *keys_b = ws.carve<int32_t>(M);
+    int32_t *vals_a = ws.carve<int32_t>(M);
+    int32_t *vals_b = ws.carve<int32_t>(M);
+    int32_t *table = ws.carve<int32_t>(256 * nblk);
+    int32_t *table_s = ws.carve<int32_t>(256 * nblk);
+    int32_t *scan_tmp = ws.carve<int32_t>(kn_scan_tmp_len(256 * nblk));
+    int32_t *start = ws.carve<int32_t>(N + 1);
+    int32_t *counts = ws.carve<int32_t>(N + 1);
+    int32_t *offsets = ws.carve<int32_t>(N + 2);
+    KnTile *tiles = ws.carve<KnTile>(kn_max_tiles(M, N, 64));
+    int32_t *n_tiles = ws.carve<int32_t>(1);
+    if (!ws.ok()) return KN_E_WORKSPACE;
+
+    const int passes = radix_passes(N);
+    const int32_t *kin = keys;
+    const int32_t *vin = nullptr;
+    int32_t *sorted_keys = keys_b;
+    int32_t *perm = vals_b;
+    if (M > 0) {
+        for (int p = 0; p < passes; ++p) {
+            const bool last = (p == passes - 1);
+            int32_t *kout = (p & 1) ? keys_a : keys_b;
+            int32_t *vout = (p & 1) ? vals_a : vals_b;
+            if (last && user_perm) vout = user_perm;
+            hipLaunchKernelGGL(k_radix_hist, dim3((unsigned)nblk), dim3(RS_THREADS), 0, st, kin, M, 8 * p, (int32_t)nblk, table);
+            KN_CHECK_LAUNCH();
+            KN_TRY(kn_exclusive_scan_i32(st, table, table_s, 256 * nblk, scan_tmp, nullptr));
+            hipLaunchKernelGGL(k_radix_scatter, dim3((unsigned)nblk), dim3(RS_THREADS), 0, st, kin, vin, kout, vout, M,
+                               8 * p, (int32_t)nblk, table_s);
+            KN_CHECK_LAUNCH();
+            kin = kout;
+            vin = vout;
+            sorted_keys = kout;
+            perm = vout;
+        }
+    }
+    KN_TRY(kn_fill_i32(st, start, N + 1, -1));
+    if (M > 0) {
+        dim3 grid;
+        KN_TRY(launch_1d(M, 256, grid));
+        hipLaunchKernelGGL(k_find_starts, grid, dim3(256), 0, st, sorted_keys, M, start);
+        KN_CHECK_LAUNCH();
+    }
+    hipLaunchKernelGGL(k_finalize_buckets, dim3(1), dim3(FIN_THREADS), 0, st, start, N, (int32_t)M, tile_len, counts,
+                       offsets, tiles, n_tiles, user_counts, user_offsets);
+    KN_CHECK_LAUNCH();
+    out->perm = perm;
+    out->counts = counts;
+    out->offsets = offsets;
+    out->tiles = tiles;
+    out->n_tiles = n_tiles;
+    return KN_OK;
+}
+
+// ---------------------------------------------------------------------------------------------
+// C ABI: stage entry points of this file
+extern "C" int kn_cell_ids(const kn_scene *sc, void *stream, const float *points, int64_t M, int32_t *ids)
+{
+    if (!sc || M < 0 || (M > 0 && (!points || !ids))) return KN_E_INVALID_ARG;
+    if (M == 0) return KN_OK;
+    dim3 grid;
+    KN_TRY(launch_1d(M, 256, grid));
+    hipLaunchKernelGGL(k_cell_ids, grid, dim3(256), 0, (hipStream_t)stream, points, M, sc->net_grid, ids,
+                       (int32_t *)nullptr, sc->N);
+    KN_CHECK_LAUNCH();
+    return KN_OK;
+}
+
+// used by kn_eval_grouped: ids (optional) and sort keys in one pass over the points
+int kn_cell_keys(const kn_scene *sc, hipStream_t st, const float *points, int64_t M, int32_t *ids, int32_t *keys)
+{
+    if (M == 0) return KN_OK;
+    dim3 grid;
+    KN_TRY(launch_1d(M, 256, grid));
+    hipLaunchKernelGGL(k_cell_ids, grid, dim3(256), 0, st, points, M, sc->net_grid, ids, keys, sc->N);
+    KN_CHECK_LAUNCH();
+    return KN_OK;
+}
+
+extern "C" int kn_bucket(const kn_scene *sc, void *stream, const int32_t *ids, int64_t M, int32_t *counts,
+                         int32_t *offsets, int32_t *perm, void *workspace, int64_t workspace_bytes)
+{
+    if (!sc || M < 0 || (M > 0 && (!ids || !perm))) return KN_E_INVALID_ARG;
+    if (M > (1ll << 30)) return KN_E_UNSUPPORTED;
+    if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < kn_bucket_ws_bytes(M, sc->N) + kn_align_up(M * 4, 256))
+        return KN_E_WORKSPACE;
+    hipStream_t st = (hipStream_t)stream;
+    KnCarver ws(workspace, workspace_bytes);
+    int32_t *keys = ws.carve<int32_t>(M);
+    if (M > 0) {
+        dim3 grid;
+        KN_TRY(launch_1d(M, 256, grid));
+        hipLaunchKernelGGL(k_ids_to_keys, grid, dim3(256), 0, st, ids, M, sc->N, keys);
+        KN_CHECK_LAUNCH();
+    }
+    KnBucketOut bo;
+    return kn_bucket_run(st, keys, M, sc->N, 64, counts, offsets, perm, ws, &bo);
+}

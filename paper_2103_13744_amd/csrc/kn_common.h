@@ -1,0 +1,154 @@
+// Internal declarations shared by the HIP translation units of libkilonerf_hip.so.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "kilonerf.h"
+
+#define KN_WAVE 64
+
+// Uniform grid over the scene AABB (Sec. 3.2).  `cell` is the fp32 quotient (b_max - b_min) / r
+// computed once on the host, so that Eq. 6 is evaluated as floor((x - b_min) / cell) with the
+// same two roundings everywhere.
+struct KnGrid {
+    float bmin[3];
+    float cell[3];
+    int32_t res[3];
+};
+
+// One unit of work of the grouped MLP kernels: `len` consecutive entries of the sorted sample
+// list, all belonging to network `net`.
+struct KnTile {
+    int32_t net;
+    int32_t start;
+    int32_t len;
+    int32_t pad;
+};
+
+struct kn_scene {
+    kn_scene_desc desc;
+    int32_t N;             // number of networks
+    int64_t P;             // parameters per network
+    int device;
+    KnGrid net_grid;
+    KnGrid occ_grid;
+    bool has_occ;
+    uint32_t *occ_bits;    // device, one bit per voxel, linear voxel index = bit index
+    void *packed_w;        // device, matrix-core operand order (16-bit types only)
+    int64_t packed_halfs_per_net;
+};
+
+// Host-side launch helpers ----------------------------------------------------------------------
+extern thread_local int g_kn_last_hip_error;
+#define KN_HIP(call)                                        \
+    do {                                                    \
+        hipError_t e_ = (call);                             \
+        if (e_ != hipSuccess) {                             \
+            g_kn_last_hip_error = (int)e_;                  \
+            return KN_E_HIP;                                \
+        }                                                   \
+    } while (0)
+#define KN_CHECK_LAUNCH() KN_HIP(hipGetLastError())
+#define KN_TRY(expr)                  \
+    do {                              \
+        int s_ = (expr);              \
+        if (s_ != KN_OK) return s_;   \
+    } while (0)
+
+static inline int64_t kn_align_up(int64_t v, int64_t a) { return (v + a - 1) / a * a; }
+static inline int64_t kn_div_up(int64_t a, int64_t b) { return (a + b - 1) / b; }
+
+// Bump allocator over the caller's workspace: carve() returns nullptr once the space is exhausted.
+struct KnCarver {
+    char *base;
+    int64_t size, used;
+    KnCarver(void *p, int64_t bytes) : base((char *)p), size(bytes), used(0) {}
+    template <typename T> T *carve(int64_t n)
+    {
+        int64_t bytes = kn_align_up((n > 0 ? n : 1) * (int64_t)sizeof(T), 256);
+        T *p = (base && used + bytes <= size) ? (T *)(base + used) : nullptr;
+        used += bytes;
+        return p;
+    }
+    bool ok() const { return base != nullptr && used <= size; }
+};
+
+// Device helpers --------------------------------------------------------------------------------
+// Eq. 6 for one point; returns the linear index (x slowest) or -1 outside / non-finite.
+__device__ __forceinline__ int32_t kn_grid_index(const KnGrid &g, float x, float y, float z)
+{
+    float ux = (x - g.bmin[0]) / g.cell[0];
+    float uy = (y - g.bmin[1]) / g.cell[1];
+    float uz = (z - g.bmin[2]) / g.cell[2];
+    float fx = floorf(ux), fy = floorf(uy), fz = floorf(uz);
+    bool in = (fx >= 0.0f) && (fx < (float)g.res[0]) && (fy >= 0.0f) && (fy < (float)g.res[1]) &&
+              (fz >= 0.0f) && (fz < (float)g.res[2]);
+    if (!in) return -1;
+    return ((int32_t)fx * g.res[1] + (int32_t)fy) * g.res[2] + (int32_t)fz;
+}
+
+// Lattice point k of a ray (Sec. 3.4): t_k = t_near + (k + 1/2) step, x = o + t_k d.
+__device__ __forceinline__ void kn_lattice_point(float ox, float oy, float oz, float dx, float dy,
+                                                 float dz, float t_near, float step, int32_t k,
+                                                 float &x, float &y, float &z)
+{
+    float t = fmaf((float)k + 0.5f, step, t_near);
+    x = fmaf(t, dx, ox);
+    y = fmaf(t, dy, oy);
+    z = fmaf(t, dz, oz);
+}
+
+// Stage entry points implemented across the translation units (host functions) -----------------
+int64_t kn_bucket_ws_bytes(int64_t M, int32_t N);
+int64_t kn_max_tiles(int64_t M, int32_t N, int32_t tile_len);
+
+struct KnBucketOut {
+    const int32_t *perm;    // M sorted sample indices
+    const int32_t *counts;  // N+1
+    const int32_t *offsets; // N+2
+    const KnTile *tiles;    // up to kn_max_tiles entries
+    const int32_t *n_tiles; // device scalar
+};
+
+// Sorts `keys` (values in [0, N], N = outside/unused) stably, fills perm/counts/offsets/tiles in
+// workspace memory (or the user's buffers where given).  keys may be overwritten.
+int kn_bucket_run(hipStream_t st, int32_t *keys, int64_t M, int32_t N, int32_t tile_len,
+                  int32_t *user_counts, int32_t *user_offsets, int32_t *user_perm, KnCarver &ws,
+                  KnBucketOut *out);
+
+// Sample source of the grouped MLP kernels: either explicit points/dirs (eval_grouped) or the
+// packed (ray, k) records of a render wave.
+struct KnSampleSrc {
+    const float *points;   // M*3 or nullptr
+    const float *dirs;     // M*3 or nullptr
+    const uint32_t *rec;   // per slot: ray_slot << kbits | k   (render)
+    const float *rays_o;   // R*3
+    const float *rays_d;   // R*3
+    const int32_t *live;   // live index -> ray id (render)
+    float t_near, step;
+    int32_t kbits;
+};
+
+int kn_mlp_launch(const kn_scene *sc, hipStream_t st, const KnSampleSrc &src, const KnBucketOut &b,
+                  int64_t M, float *sigma, float *rgb);
+int kn_mlp_pack_weights(kn_scene *sc, hipStream_t st);
+int kn_mlp_tile_len(const kn_scene *sc);
+
+int kn_fill_i32(hipStream_t st, int32_t *p, int64_t n, int32_t v);
+int kn_exclusive_scan_i32(hipStream_t st, const int32_t *in, int32_t *out, int64_t n, int32_t *tmp /* kn_scan_tmp_len(n) */,
+                          int32_t *total /*dev, nullable*/);
+int64_t kn_scan_tmp_len(int64_t n);
+
+// Optional per-stage timing with HIP events on the caller's stream (see kn_profile in the header).
+struct KnStageTimer {
+    hipStream_t st;
+    bool on;
+    int n;
+    KnStageTimer(hipStream_t s);
+    void mark();                 // record the next boundary event
+    // after the stream has been synchronised: elapsed ms between boundaries i and i+1
+    float elapsed(int i) const;
+};
+extern kn_profile g_kn_profile;
+extern bool g_kn_profile_on;

@@ -1,0 +1,413 @@
+// Grouped tiny-MLP evaluation on the matrix cores (scenes with KN_F16 / KN_BF16 weights).
+//
+// One wavefront evaluates one tile (<= 256 consecutive entries of the sorted sample list, all of
+// one network): encoding, the five layers of Sec. 3.2 and the output activations in one kernel
+// (the paper's Sec. 3.5 fuses the whole network evaluation into one kernel as well; everything
+// below that sentence is this library's own design for 64-wide wavefronts and MFMA).
+//
+// Formulation.  Every layer is computed transposed, out^T = W^T * act^T, with
+// v_mfma_f32_16x16x32_{f16,bf16}: the A operand is a 16(out) x 32(in) block of W^T, the B operand
+// a 32(in) x 16(samples) block of activations, the accumulator a 16(out) x 16(samples) tile in
+// fp32.  In that orientation lane (n = lane%16, g = lane/16) of the accumulator holds outputs
+// 16t+4g+{0..3} of sample n, and the same lane must supply 8 inputs of sample n to the next MFMA;
+// so accumulators are activated, rounded to 16 bit, packed and used as the next B operand in
+// place, with no shuffle and no LDS round trip.  Which input sits in which of the 8 slots of a
+// lane is a free choice as long as the weight block uses the same order: weights are re-ordered
+// once per scene (k_pack_weights) into that "slot order".
+//
+// Slot order (kb = 32-input block, g = lane/16, j = 0..7):
+//   hidden vector : feature 16*(2kb + j/4) + 4g + j%4   (= what the accumulators hold)
+//   gamma(x), 64 slots: g < 3: axis g, frequency 4kb + j/2, sin for even j, cos for odd j;
+//                       g = 3: kb 0: x f8, x f9, y f8, y f9 (sin, cos each);
+//                              kb 1: z f8, z f9, then x, y, z, 1 (the 1 multiplies the bias b1)
+//   gamma(d), 32 slots: g < 3: axis g, frequency j/2, sin/cos;  g = 3: dx, dy, dz, 1 (bias b4), 0 x 4
+// Biases b1 and b4 ride in the constant-1 slots; b2, b3, b5 initialise the accumulators.
+//
+// Density and colour.  Layer 3's density row and layer 5's three colour rows would each waste a
+// 16-row output tile.  Instead four sample tiles (64 samples) share one extra accumulator: for
+// sample tile u the density row is placed at row 4u+3 and the colour rows at 4u+0..2 (the weight
+// block is masked to those rows), and all eight MFMAs accumulate into the same tile.  Afterwards
+// lane l holds (r, g, b, sigma) pre-activations of sample l of the 64, one sample per lane.
+//
+// Encoding.  sin/cos of 2^f * p come from v_sin_f32 / v_cos_f32 at three "restart" frequencies
+// per lane and the double-angle recurrence in between (fp32), which is far inside the 16-bit
+// rounding of the operands.
+#include "kn_common.h"
+#include "kn_mlp_shared.h"
+
+namespace {
+
+typedef _Float16 h8 __attribute__((ext_vector_type(8)));
+typedef _Float16 h2 __attribute__((ext_vector_type(2)));
+typedef __bf16 b8 __attribute__((ext_vector_type(8)));
+typedef __bf16 b2 __attribute__((ext_vector_type(2)));
+typedef short s2 __attribute__((ext_vector_type(2)));
+typedef float f2 __attribute__((ext_vector_type(2)));
+typedef float f4 __attribute__((ext_vector_type(4)));
+typedef unsigned u4 __attribute__((ext_vector_type(4)));
+
+constexpr int MLP_TILE_LEN = 256;
+
+template <int H> struct Lay {
+    static constexpr int HT = H / 16, HK = H / 32;
+    static constexpr int L1 = 0;                          // (t, kb) -> L1 + 2t + kb
+    static constexpr int L2 = L1 + 2 * HT;                // (t, kb) -> L2 + t*HK + kb
+    static constexpr int L3 = L2 + HT * HK;               // feature rows
+    static constexpr int LS = L3 + HT * HK;               // density row, (kb)
+    static constexpr int L4 = LS + HK;                    // (t, kb) -> L4 + t*(HK+1) + kb, kb = HK: gamma(d)
+    static constexpr int L5 = L4 + HT * (HK + 1);         // colour rows, (kb)
+    static constexpr int NBLK = L5 + HK;
+    static constexpr int TAIL_FLOATS = 2 * H + 4;         // b2[H], b3 feature[H], b5[3], b3 density
+    static constexpr int HALFS = NBLK * 512 + TAIL_FLOATS * 2;
+    // canonical offsets
+    static constexpr int oW1 = 0, ob1 = 63 * H, oW2 = ob1 + H, ob2 = oW2 + H * H, oW3 = ob2 + H,
+                         ob3 = oW3 + H * (H + 1), oW4 = ob3 + H + 1, ob4 = oW4 + (H + 27) * H, oW5 = ob4 + H,
+                         ob5 = oW5 + 3 * H;
+};
+
+__host__ __device__ inline int hid_feat(int kb, int g, int j) { return 16 * (2 * kb + j / 4) + 4 * g + j % 4; }
+
+// canonical row of W1 behind slot (kb, g, j); 63 = the bias slot
+__host__ __device__ inline int l1_row(int kb, int g, int j)
+{
+    if (g < 3) return 3 + 6 * (4 * kb + j / 2) + 3 * (j & 1) + g;
+    const int p = 4 * kb + j / 2; // pair index 0..7 of the fourth lane group
+    if (p < 6) return 3 + 6 * (8 + (p & 1)) + 3 * (j & 1) + p / 2;
+    return (p == 6) ? (j & 1) : ((j & 1) ? 63 : 2);
+}
+
+// canonical row of W4 (relative to its first gamma(d) row) behind slot (g, j): -1 = bias, -2 = zero
+__host__ __device__ inline int dir_row(int g, int j)
+{
+    if (g < 3) return 3 + 6 * (j / 2) + 3 * (j & 1) + g;
+    if (j < 3) return j;
+    return j == 3 ? -1 : -2;
+}
+
+// source element (canonical index) of packed 16-bit element e of one network; -1 = zero
+template <int H> __device__ int pack_source(int e)
+{
+    using L = Lay<H>;
+    const int blk = e >> 9, lane = (e >> 3) & 63, j = e & 7, m = lane & 15, g = lane >> 4;
+    if (blk < L::L2) {
+        const int t = (blk - L::L1) >> 1, kb = (blk - L::L1) & 1, col = 16 * t + m, r = l1_row(kb, g, j);
+        return r < 63 ? L::oW1 + r * H + col : L::ob1 + col;
+    }
+    if (blk < L::L3) {
+        const int t = (blk - L::L2) / L::HK, kb = (blk - L::L2) % L::HK;
+        return L::oW2 + hid_feat(kb, g, j) * H + 16 * t + m;
+    }
+    if (blk < L::LS) {
+        const int t = (blk - L::L3) / L::HK, kb = (blk - L::L3) % L::HK;
+        return L::oW3 + hid_feat(kb, g, j) * (H + 1) + 1 + 16 * t + m;
+    }
+    if (blk < L::L4) {
+        const int kb = blk - L::LS;
+        return (m & 3) == 3 ? L::oW3 + hid_feat(kb, g, j) * (H + 1) : -1;
+    }
+    if (blk < L::L5) {
+        const int t = (blk - L::L4) / (L::HK + 1), kb = (blk - L::L4) % (L::HK + 1), col = 16 * t + m;
+        if (kb < L::HK) return L::oW4 + hid_feat(kb, g, j) * H + col;
+        const int r = dir_row(g, j);
+        if (r == -2) return -1;
+        return r == -1 ? L::ob4 + col : L::oW4 + (H + r) * H + col;
+    }
+    const int kb = blk - L::L5;
+    return (m & 3) < 3 ? L::oW5 + hid_feat(kb, g, j) * 3 + (m & 3) : -1;
+}
+
+template <int H> __device__ int tail_source(int q)
+{
+    using L = Lay<H>;
+    if (q < H) return L::ob2 + q;
+    if (q < 2 * H) return L::ob3 + 1 + (q - H);
+    if (q < 2 * H + 3) return L::ob5 + (q - 2 * H);
+    return L::ob3;
+}
+
+__device__ __forceinline__ float half_bits_to_float(uint16_t v, bool bf)
+{
+    if (bf) return __uint_as_float((uint32_t)v << 16);
+    return (float)__builtin_bit_cast(_Float16, v);
+}
+
+template <int H>
+__global__ void k_pack_weights(const uint16_t *__restrict__ w, int64_t P, int32_t N, bool bf, uint16_t *__restrict__ packed)
+{
+    using L = Lay<H>;
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int64_t per = L::NBLK * 512 + L::TAIL_FLOATS;
+    if (i >= per * N) return;
+    const int64_t net = i / per;
+    const int e = (int)(i - net * per);
+    const uint16_t *src = w + net * P;
+    uint16_t *dst = packed + net * (int64_t)L::HALFS;
+    if (e < L::NBLK * 512) {
+        const int s = pack_source<H>(e);
+        dst[e] = s < 0 ? (uint16_t)0 : src[s];
+    } else {
+        const int q = e - L::NBLK * 512;
+        const float v = half_bits_to_float(src[tail_source<H>(q)], bf);
+        ((float *)(dst + L::NBLK * 512))[q] = v;
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+template <bool BF> __device__ __forceinline__ f4 mfma(u4 a, u4 b, f4 c)
+{
+    if constexpr (BF)
+        return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(b8, a), __builtin_bit_cast(b8, b), c, 0, 0, 0);
+    else
+        return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(h8, a), __builtin_bit_cast(h8, b), c, 0, 0, 0);
+}
+
+template <bool BF> __device__ __forceinline__ unsigned pk(float a, float b)
+{
+    f2 v = {a, b};
+    if constexpr (BF)
+        return __builtin_bit_cast(unsigned, __builtin_convertvector(v, b2));
+    else
+        return __builtin_bit_cast(unsigned, __builtin_convertvector(v, h2));
+}
+
+// ReLU on two packed 16-bit floats: as signed 16-bit integers every negative float is negative
+__device__ __forceinline__ unsigned relu2(unsigned v)
+{
+    return __builtin_bit_cast(unsigned, __builtin_elementwise_max(__builtin_bit_cast(s2, v), (s2){0, 0}));
+}
+
+// accumulators of one layer (HT tiles) -> B operands of the next (HK blocks)
+template <int H, bool BF, bool RELU> __device__ __forceinline__ void pack_acts(const f4 *acc, u4 *B)
+{
+#pragma unroll
+    for (int kb = 0; kb < H / 32; ++kb) {
+        unsigned r0 = pk<BF>(acc[2 * kb][0], acc[2 * kb][1]);
+        unsigned r1 = pk<BF>(acc[2 * kb][2], acc[2 * kb][3]);
+        unsigned r2 = pk<BF>(acc[2 * kb + 1][0], acc[2 * kb + 1][1]);
+        unsigned r3 = pk<BF>(acc[2 * kb + 1][2], acc[2 * kb + 1][3]);
+        if (RELU) { r0 = relu2(r0); r1 = relu2(r1); r2 = relu2(r2); r3 = relu2(r3); }
+        B[kb] = (u4){r0, r1, r2, r3};
+    }
+}
+
+// sin and cos of 2*pi*rev
+__device__ __forceinline__ void sincos_rev(float rev, float &s, float &c)
+{
+    const float f = __builtin_amdgcn_fractf(rev);
+    s = __builtin_amdgcn_sinf(f);
+    c = __builtin_amdgcn_cosf(f);
+}
+__device__ __forceinline__ void double_angle(float s, float c, float &s2o, float &c2o)
+{
+    s2o = 2.0f * s * c;
+    c2o = fmaf(-2.0f * s, s, 1.0f);
+}
+
+constexpr float INV_2PI = 0.15915494309189535f;
+
+template <int H, bool BF, bool AREG, int WAVES>
+__global__ void __launch_bounds__(WAVES *KN_WAVE)
+    k_mlp_mfma(const uint16_t *__restrict__ packed, KnSampleSrc src, const int32_t *__restrict__ perm,
+               const KnTile *__restrict__ tiles, const int32_t *__restrict__ n_tiles, float *__restrict__ sigma,
+               float *__restrict__ rgb)
+{
+    using L = Lay<H>;
+    constexpr int HT = L::HT, HK = L::HK, NBLK = L::NBLK;
+    __shared__ f4 stage[WAVES][2][KN_WAVE];
+    __shared__ u4 wlds[AREG ? 1 : WAVES * NBLK * KN_WAVE];
+
+    const int wave = threadIdx.x / KN_WAVE, lane = threadIdx.x & (KN_WAVE - 1);
+    const int n = lane & 15, g = lane >> 4;
+    const int tile = blockIdx.x * WAVES + wave;
+    if (tile >= *n_tiles) return;
+    const KnTile tl = tiles[tile];
+    const u4 *__restrict__ wp = (const u4 *)(packed + (int64_t)tl.net * L::HALFS);
+
+    // weights: registers (AREG) or this wave's private LDS copy
+    u4 areg[AREG ? NBLK : 1];
+    u4 *wl = &wlds[AREG ? 0 : wave * NBLK * KN_WAVE];
+    if constexpr (AREG) {
+#pragma unroll
+        for (int b = 0; b < NBLK; ++b) areg[b] = wp[b * KN_WAVE + lane];
+    } else {
+        for (int b = 0; b < NBLK; ++b) wl[b * KN_WAVE + lane] = wp[b * KN_WAVE + lane];
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+    }
+    auto A = [&](int b) -> u4 {
+        if constexpr (AREG) return areg[b]; else return wl[b * KN_WAVE + lane];
+    };
+    const float *__restrict__ tail = (const float *)(wp + NBLK * KN_WAVE);
+    f4 bias2[HT], bias3[HT];
+#pragma unroll
+    for (int t = 0; t < HT; ++t) {
+        bias2[t] = *(const f4 *)(tail + 16 * t + 4 * g);
+        bias3[t] = *(const f4 *)(tail + H + 16 * t + 4 * g);
+    }
+    const f4 bias_out = *(const f4 *)(tail + 2 * H);
+    const f4 zero4 = {0.0f, 0.0f, 0.0f, 0.0f};
+    const u4 zero_u4 = {0u, 0u, 0u, 0u};
+    const int mrow = n >> 2; // the A-operand row of this lane is n; rows 4u..4u+3 belong to sample tile u
+
+    // per-lane encoding constants
+    const bool role3 = (g == 3);
+    const float m0 = role3 ? 256.0f * INV_2PI : INV_2PI;
+    const float m2 = role3 ? 256.0f * INV_2PI : 4.0f * INV_2PI;
+    const float m4 = role3 ? 256.0f * INV_2PI : 16.0f * INV_2PI;
+
+    for (int base = 0; base < tl.len; base += KN_WAVE) {
+        const int j = base + lane;
+        const bool active = j < tl.len;
+        const int32_t idx = perm[tl.start + (active ? j : 0)];
+        {
+            float x, y, z, dx, dy, dz;
+            kn_load_sample(src, idx, x, y, z, dx, dy, dz);
+            stage[wave][0][lane] = (f4){x, y, z, 0.0f};
+            stage[wave][1][lane] = (f4){dx, dy, dz, 0.0f};
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+
+        f4 out = bias_out;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            if (base + 16 * u < tl.len) {
+                const f4 Pp = stage[wave][0][16 * u + n];
+                const f4 Dd = stage[wave][1][16 * u + n];
+                u4 Bx[2], Bd;
+                {
+                    const float c = g == 0 ? Pp[0] : (g == 1 ? Pp[1] : Pp[2]);
+                    const float c0 = role3 ? Pp[0] : c, c2 = role3 ? Pp[1] : c;
+                    float s[8], k[8];
+                    sincos_rev(c0 * m0, s[0], k[0]);
+                    double_angle(s[0], k[0], s[1], k[1]);
+                    sincos_rev(c2 * m2, s[2], k[2]);
+                    double_angle(s[2], k[2], s[3], k[3]);
+                    sincos_rev(c * m4, s[4], k[4]);
+                    double_angle(s[4], k[4], s[5], k[5]);
+                    double_angle(s[5], k[5], s[6], k[6]);
+                    double_angle(s[6], k[6], s[7], k[7]);
+                    unsigned p[8];
+#pragma unroll
+                    for (int q = 0; q < 8; ++q) p[q] = pk<BF>(s[q], k[q]);
+                    const unsigned id0 = pk<BF>(Pp[0], Pp[1]), id1 = pk<BF>(Pp[2], 1.0f);
+                    p[6] = role3 ? id0 : p[6];
+                    p[7] = role3 ? id1 : p[7];
+                    Bx[0] = (u4){p[0], p[1], p[2], p[3]};
+                    Bx[1] = (u4){p[4], p[5], p[6], p[7]};
+                }
+                {
+                    const float c = g == 0 ? Dd[0] : (g == 1 ? Dd[1] : Dd[2]);
+                    float s[4], k[4];
+                    sincos_rev(c * INV_2PI, s[0], k[0]);
+                    double_angle(s[0], k[0], s[1], k[1]);
+                    double_angle(s[1], k[1], s[2], k[2]);
+                    double_angle(s[2], k[2], s[3], k[3]);
+                    const unsigned id0 = pk<BF>(Dd[0], Dd[1]), id1 = pk<BF>(Dd[2], 1.0f);
+                    Bd = (u4){role3 ? id0 : pk<BF>(s[0], k[0]), role3 ? id1 : pk<BF>(s[1], k[1]),
+                              role3 ? 0u : pk<BF>(s[2], k[2]), role3 ? 0u : pk<BF>(s[3], k[3])};
+                }
+                f4 acc[HT];
+                u4 Bh[HK];
+                // layer 1: gamma(x) -> H, ReLU (bias through the constant-1 slot)
+#pragma unroll
+                for (int t = 0; t < HT; ++t) {
+                    acc[t] = mfma<BF>(A(L::L1 + 2 * t), Bx[0], zero4);
+                    acc[t] = mfma<BF>(A(L::L1 + 2 * t + 1), Bx[1], acc[t]);
+                }
+                pack_acts<H, BF, true>(acc, Bh);
+                // layer 2: H -> H, ReLU
+#pragma unroll
+                for (int t = 0; t < HT; ++t) {
+                    acc[t] = bias2[t];
+#pragma unroll
+                    for (int kb = 0; kb < HK; ++kb) acc[t] = mfma<BF>(A(L::L2 + t * HK + kb), Bh[kb], acc[t]);
+                }
+                pack_acts<H, BF, true>(acc, Bh);
+                // layer 3: H -> feature (no activation) and density (row 4u+3 of the shared tile)
+#pragma unroll
+                for (int t = 0; t < HT; ++t) {
+                    acc[t] = bias3[t];
+#pragma unroll
+                    for (int kb = 0; kb < HK; ++kb) acc[t] = mfma<BF>(A(L::L3 + t * HK + kb), Bh[kb], acc[t]);
+                }
+#pragma unroll
+                for (int kb = 0; kb < HK; ++kb) out = mfma<BF>(mrow == u ? A(L::LS + kb) : zero_u4, Bh[kb], out);
+                pack_acts<H, BF, false>(acc, Bh);
+                // layer 4: [feature, gamma(d)] -> H, ReLU (bias through the constant-1 slot)
+#pragma unroll
+                for (int t = 0; t < HT; ++t) {
+                    acc[t] = mfma<BF>(A(L::L4 + t * (HK + 1) + HK), Bd, zero4);
+#pragma unroll
+                    for (int kb = 0; kb < HK; ++kb) acc[t] = mfma<BF>(A(L::L4 + t * (HK + 1) + kb), Bh[kb], acc[t]);
+                }
+                pack_acts<H, BF, true>(acc, Bh);
+                // layer 5: H -> colour rows 4u+0..2 of the shared tile
+#pragma unroll
+                for (int kb = 0; kb < HK; ++kb) out = mfma<BF>(mrow == u ? A(L::L5 + kb) : zero_u4, Bh[kb], out);
+            }
+        }
+        __builtin_amdgcn_wave_barrier(); // staging buffer is rewritten by the next iteration
+
+        if (active) {
+            sigma[idx] = fmaxf(out[3], 0.0f);
+            float *o = rgb + 3 * (int64_t)idx;
+#pragma unroll
+            for (int c = 0; c < 3; ++c)
+                o[c] = __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-1.4426950408889634f * out[c]));
+        }
+    }
+}
+
+template <int H, bool BF, bool AREG, int WAVES>
+int launch(const kn_scene *sc, hipStream_t st, const KnSampleSrc &src, const KnBucketOut &b, int64_t max_tiles, float *sigma,
+           float *rgb)
+{
+    const int64_t blocks = kn_div_up(max_tiles, WAVES);
+    if (blocks > 0x7fffffffLL) return KN_E_UNSUPPORTED;
+    hipLaunchKernelGGL((k_mlp_mfma<H, BF, AREG, WAVES>), dim3((unsigned)blocks), dim3(WAVES * KN_WAVE), 0, st,
+                       (const uint16_t *)sc->packed_w, src, b.perm, b.tiles, b.n_tiles, sigma, rgb);
+    KN_CHECK_LAUNCH();
+    return KN_OK;
+}
+
+} // namespace
+
+int kn_mlp_mfma_tile_len(const kn_scene *) { return MLP_TILE_LEN; }
+
+int kn_mlp_pack_weights(kn_scene *sc, hipStream_t st)
+{
+    const int H = sc->desc.hidden;
+    const bool bf = sc->desc.wdtype == KN_BF16;
+    const int64_t halfs = H == 32 ? Lay<32>::HALFS : Lay<64>::HALFS;
+    const int64_t per = H == 32 ? Lay<32>::NBLK * 512 + Lay<32>::TAIL_FLOATS : Lay<64>::NBLK * 512 + Lay<64>::TAIL_FLOATS;
+    sc->packed_halfs_per_net = halfs;
+    KN_HIP(hipMalloc(&sc->packed_w, (size_t)(halfs * 2 * sc->N)));
+    const int64_t total = per * sc->N;
+    const int64_t blocks = kn_div_up(total, 256);
+    if (blocks > 0x7fffffffLL) return KN_E_UNSUPPORTED;
+    const uint16_t *w = (const uint16_t *)sc->desc.weights;
+    if (H == 32)
+        hipLaunchKernelGGL(k_pack_weights<32>, dim3((unsigned)blocks), dim3(256), 0, st, w, sc->P, sc->N, bf,
+                           (uint16_t *)sc->packed_w);
+    else
+        hipLaunchKernelGGL(k_pack_weights<64>, dim3((unsigned)blocks), dim3(256), 0, st, w, sc->P, sc->N, bf,
+                           (uint16_t *)sc->packed_w);
+    KN_CHECK_LAUNCH();
+    return KN_OK;
+}
+
+int kn_mlp_mfma_launch(const kn_scene *sc, hipStream_t st, const KnSampleSrc &src, const KnBucketOut &b, int64_t max_tiles,
+                       float *sigma, float *rgb)
+{
+    if (max_tiles <= 0) return KN_OK;
+    const bool bf = sc->desc.wdtype == KN_BF16;
+    if (sc->desc.hidden == 32)
+        return bf ? launch<32, true, true, 4>(sc, st, src, b, max_tiles, sigma, rgb)
+                  : launch<32, false, true, 4>(sc, st, src, b, max_tiles, sigma, rgb);
+    if (sc->desc.hidden == 64)
+        return bf ? launch<64, true, false, 2>(sc, st, src, b, max_tiles, sigma, rgb)
+                  : launch<64, false, false, 2>(sc, st, src, b, max_tiles, sigma, rgb);
+    return KN_E_UNSUPPORTED;
+}

@@ -1,0 +1,344 @@
+"""Parity of the HIP path against the CPU oracle, element by element, through the C ABI.
+
+Bars: cell ids, bucket counts and the sample permutation bit-exact; fp32 outputs within 1e-4
+absolute; 16-bit matrix-core outputs within 2e-2 absolute (density: 2e-2 absolute + 2e-2 relative,
+because its scale is free).  Rays whose transmittance comes within a few percent of the
+termination threshold may legitimately stop one sample earlier or later than the oracle; the
+skipped / extra sample contributes at most eps, so those rays are compared at tolerance + eps.
+"""
+import math
+
+import numpy as np
+import pytest
+
+import kn_synth as ks
+import oracle
+from kn_synth import configs
+from tests.util import cuda, make_pair, scene_dict
+
+pytestmark = pytest.mark.gpu
+
+TOL = {"f32": 1e-4, "f16": 2e-2, "bf16": 2e-2}
+
+
+def log(*a):
+    print(*a, flush=True)
+
+
+# ------------------------------------------------------------------ a2: cell ids
+@pytest.mark.parametrize("res,lo,hi", [((2, 2, 2), (0, 0, 0), (1, 1, 1)), ((3, 4, 5), (-1, 0, 0.5), (1, 2, 4.5)),
+                                       ((10, 16, 10), (-0.67, -1.07, -0.67), (0.67, 1.07, 0.67)),
+                                       ((16, 16, 16), (-1, -1, -1), (1, 1, 1)), ((32, 32, 32), (0, 0, 0), (1, 1, 1))])
+def test_cell_ids_bit_exact(res, lo, hi):
+    log("cell ids", res)
+    sc = scene_dict(res, lo, hi, 32, "f32", 1)
+    dev, orc = make_pair(sc)
+    g = ks.rng(17)
+    lo_, hi_ = np.array(lo), np.array(hi)
+    M = 200_003
+    pts = (lo_ - 0.05 + g.random((M, 3)) * (hi_ - lo_ + 0.1)).astype(np.float32)
+    # points exactly on cell faces and on the box faces
+    faces = lo_ + (hi_ - lo_) * g.integers(0, np.array(res) + 1, size=(5000, 3)) / np.array(res)
+    pts[:5000] = faces.astype(np.float32)
+    pts[5000] = [np.nan, 0, 0]
+    pts[5001] = [np.inf, 0, 0]
+    got = dev.cell_ids(cuda(pts)).cpu().numpy()
+    want = orc.cell_ids(pts)
+    np.testing.assert_array_equal(got, want)
+    assert (want < 0).sum() > 100 and len(np.unique(want)) > 0.9 * int(np.prod(res))
+
+
+# ------------------------------------------------------------------ a3: bucketing
+@pytest.mark.parametrize("N,M,mode", [(8, 0, "uniform"), (8, 1, "uniform"), (8, 63, "uniform"), (8, 4097, "uniform"),
+                                      (4096, 300_001, "uniform"), (4096, 500_000, "skew"), (4096, 70_000, "single"),
+                                      (4096, 5000, "outside"), (32768, 1_000_003, "uniform"), (60, 10_000, "uniform")])
+def test_bucket_bit_exact(N, M, mode):
+    log("bucket", N, M, mode)
+    res = {8: (2, 2, 2), 4096: (16, 16, 16), 32768: (32, 32, 32), 60: (3, 4, 5)}[N]
+    dev, _ = make_pair(scene_dict(res, (0, 0, 0), (1, 1, 1), 32, "f32", 1))
+    g = ks.rng(23 + N + M)
+    if mode == "uniform":
+        ids = g.integers(-1, N, size=M)
+    elif mode == "skew":
+        hot = g.integers(0, N, size=20)
+        ids = np.where(g.random(M) < 0.9, hot[g.integers(0, 20, size=M)], g.integers(-1, N, size=M))
+    elif mode == "single":
+        ids = np.full(M, 1234)
+    else:
+        ids = np.full(M, -1)
+    ids = ids.astype(np.int32)
+    counts, offsets, perm = dev.bucket(cuda(ids))
+    c, o, p = oracle.bucket(ids, N)
+    np.testing.assert_array_equal(counts.cpu().numpy(), c)
+    np.testing.assert_array_equal(offsets.cpu().numpy(), o)
+    np.testing.assert_array_equal(perm.cpu().numpy(), p)
+
+
+# ------------------------------------------------------------------ a4: grouped MLP through eval_grouped
+def check_eval(sc, pts, dirs, sample=None, tol=None, sigma_unit=1.0):
+    """sigma_unit: density scale of the scene (the factor its density head was multiplied by);
+    the density tolerance is stated in that unit."""
+    import torch
+    dev, orc = make_pair(sc, threads=True)
+    tol = TOL[sc["wdtype"]] if tol is None else tol
+    sg, rgb, ids, counts, perm = dev.eval_grouped(cuda(pts), cuda(dirs), want_aux=True)
+    torch.cuda.synchronize()
+    ids_o = orc.cell_ids(pts)
+    np.testing.assert_array_equal(ids.cpu().numpy(), ids_o)
+    c, o, p = oracle.bucket(ids_o, orc.N)
+    np.testing.assert_array_equal(counts.cpu().numpy(), c)
+    np.testing.assert_array_equal(perm.cpu().numpy(), p)
+    sel = np.arange(len(pts)) if sample is None else sample
+    s_o, c_o, _ = orc.eval_points(pts[sel], dirs[sel])
+    s_g, c_g = sg.cpu().numpy()[sel].astype(np.float64), rgb.cpu().numpy()[sel].astype(np.float64)
+    err_c = np.abs(c_g - c_o).max()
+    s_g, s_o = s_g / sigma_unit, s_o / sigma_unit
+    err_s = (np.abs(s_g - s_o) / (1.0 + (0 if tol < 1e-3 else 1) * np.abs(s_o))).max()
+    log("  eval %s H=%d M=%d: max |rgb err| %.3g, max sigma err (abs or abs/(1+|s|)) %.3g" %
+        (sc["wdtype"], sc["hidden"], len(pts), err_c, err_s))
+    assert err_c <= tol and err_s <= tol
+    outside = ids_o[sel] < 0
+    assert np.all(s_g[outside] == 0) and np.all(c_g[outside] == 0)
+    return dev
+
+
+@pytest.mark.parametrize("H", [32, 64])
+def test_eval_grouped_fp32(H):
+    sc = scene_dict((2, 2, 2), (0, 0, 0), (1, 1, 1), H, "f32", 5)
+    M = 20_011
+    pts = ks.uniform_points(M, 1, lo=(-0.05,) * 3, hi=(1.05,) * 3)
+    check_eval(sc, pts, ks.sphere_dirs(M, 2))
+
+
+def test_eval_grouped_fp32_noncubic_grid():
+    sc = scene_dict((10, 16, 10), (-0.67, -1.07, -0.67), (0.67, 1.07, 0.67), 32, "f32", 6)   # the Lego grid of Sec. 4.3
+    M = 30_000
+    pts = ks.uniform_points(M, 3, lo=(-0.7, -1.1, -0.7), hi=(0.7, 1.1, 0.7))
+    check_eval(sc, pts, ks.sphere_dirs(M, 4))
+
+
+@pytest.mark.parametrize("wdtype,H", [("f16", 32), ("bf16", 32), ("f16", 64), ("bf16", 64)])
+def test_eval_grouped_matrix_cores(wdtype, H):
+    sc = scene_dict((4, 4, 4), (-1, -1, -1), (1, 1, 1), H, wdtype, 7)
+    M = 50_021
+    pts = ks.uniform_points(M, 5, lo=(-1.02,) * 3, hi=(1.02,) * 3)
+    check_eval(sc, pts, ks.sphere_dirs(M, 6))
+
+
+def test_eval_grouped_density_scaled_and_tiny_groups():
+    # sigma_scale as in the render workload; 16^3 networks with few points each => many partial tiles
+    sc = scene_dict((16, 16, 16), (-1, -1, -1), (1, 1, 1), 32, "f16", 8, sigma_scale=100.0)
+    M = 40_000
+    pts = ks.uniform_points(M, 7, lo=(-1,) * 3, hi=(1,) * 3)
+    check_eval(sc, pts, ks.sphere_dirs(M, 8), sigma_unit=100.0)
+
+
+def test_eval_grouped_empty_and_permutation_invariance():
+    import torch
+    sc = scene_dict((4, 4, 4), (0, 0, 0), (1, 1, 1), 32, "f16", 9)
+    dev, _ = make_pair(sc)
+    e = torch.empty((0, 3), dtype=torch.float32, device="cuda")
+    sg, rgb = dev.eval_grouped(e, e)
+    assert sg.numel() == 0 and rgb.numel() == 0
+    M = 30_000
+    pts, dirs = ks.uniform_points(M, 1), ks.sphere_dirs(M, 2)
+    s1, c1 = [t.cpu().numpy() for t in dev.eval_grouped(cuda(pts), cuda(dirs))]
+    p = ks.rng(3).permutation(M)
+    s2, c2 = [t.cpu().numpy() for t in dev.eval_grouped(cuda(pts[p]), cuda(dirs[p]))]
+    np.testing.assert_array_equal(s2, s1[p])      # each sample's arithmetic is independent of its tile mates
+    np.testing.assert_array_equal(c2, c1[p])
+
+
+# ------------------------------------------------------------------ a1: marching
+def test_march_bit_exact_and_resumable():
+    cfg = configs.config3(40, 40)
+    dev, orc = make_pair(cfg["scene"])
+    o, d = cfg["rays_o"], cfg["rays_d"]
+    K = cfg["K"]
+    out_k, cnt, nxt = dev.march(cuda(o), cuda(d), cfg["t_near"], cfg["step"], K)
+    out_k, cnt = out_k.cpu().numpy(), cnt.cpu().numpy()
+    total = 0
+    for r in range(len(o)):
+        want = orc.march(o[r], d[r], cfg["t_near"], cfg["step"], K)
+        assert cnt[r] == len(want), r
+        np.testing.assert_array_equal(out_k[r, :cnt[r]], want)
+        assert np.all(out_k[r, cnt[r]:] == -1)
+        total += len(want)
+    assert total > 5000
+    # in chunks of 5 samples, resuming where the previous chunk stopped
+    kb = cuda(np.zeros(len(o), np.int32))
+    got = [[] for _ in range(len(o))]
+    for _ in range(K):
+        ck, cc, kb = dev.march(cuda(o), cuda(d), cfg["t_near"], cfg["step"], K, S=5, k_begin=kb)
+        ck, cc = ck.cpu().numpy(), cc.cpu().numpy()
+        for r in np.nonzero(cc)[0]:
+            got[r] += ck[r, :cc[r]].tolist()
+        if cc.sum() == 0:
+            break
+    for r in range(0, len(o), 7):
+        assert got[r] == out_k[r, :cnt[r]].tolist()
+
+
+def test_march_without_grid_and_axis_parallel_rays():
+    cfg = configs.config1(24, 24)
+    dev, orc = make_pair(cfg["scene"])
+    o, d = cfg["rays_o"].copy(), cfg["rays_d"].copy()
+    o[:4] = [[-1, 0.3, 0.6], [0.5, 0.5, -2], [0.2, 3, 0.2], [0.5, 1.0, 0.5]]
+    d[:4] = [[1, 0, 0], [0, 0, 1], [0, -1, 0], [1, 0, 0]]        # zero components; last one rides the upper face
+    out_k, cnt, _ = dev.march(cuda(o), cuda(d), 0.25, 1 / 16, 80)
+    out_k, cnt = out_k.cpu().numpy(), cnt.cpu().numpy()
+    for r in range(len(o)):
+        want = orc.march(o[r], d[r], 0.25, 1 / 16, 80)
+        assert cnt[r] == len(want), r
+        np.testing.assert_array_equal(out_k[r, :cnt[r]], want)
+    assert cnt[0] == 16 and cnt[3] == 0
+
+
+# ------------------------------------------------------------------ a5: blending
+def test_composite_stage():
+    import paper_2103_13744_amd as kn
+    g = ks.rng(31)
+    R = 3000
+    n = g.integers(0, 40, size=R)
+    n[:3] = 0
+    off = np.concatenate([[0], np.cumsum(n)]).astype(np.int32)
+    sg = g.uniform(0, 60, size=off[-1]).astype(np.float32)
+    col = g.random((off[-1], 3)).astype(np.float32)
+    for eps in (0.0, 0.01):
+        out, T, used = kn.composite(cuda(sg), cuda(col), cuda(off), 0.05, eps, (1.0, 0.5, 0.25))
+        out, T, used = out.cpu().numpy(), T.cpu().numpy(), used.cpu().numpy()
+        for r in range(R):
+            o_, T_, u_, mg = oracle.composite(sg[off[r]:off[r + 1]], col[off[r]:off[r + 1]], 0.05, eps, (1.0, 0.5, 0.25))
+            if mg > 1e-3:
+                assert used[r] == u_
+                assert np.abs(out[r] - o_).max() < 1e-5 and abs(T[r] - T_) < 1e-6
+            else:
+                assert abs(used[r] - u_) <= 1 and np.abs(out[r] - o_).max() < 1e-5 + eps
+
+
+# ------------------------------------------------------------------ a1-a6: render
+def render_check(cfg, sel=None, margin=None):
+    """Render on the device, compare (a subset of) pixels with the oracle."""
+    import torch
+    sc = cfg["scene"]
+    tol = TOL[sc["wdtype"]]
+    margin = (1e-3 if sc["wdtype"] == "f32" else 0.08) if margin is None else margin
+    dev, orc = make_pair(sc, threads=True)
+    o, d = cfg["rays_o"], cfg["rays_d"]
+    img, stats = dev.render(cuda(o), cuda(d), cfg["t_near"], cfg["step"], cfg["K"], cfg["term_eps"], cfg["bg"], want_stats=True)
+    torch.cuda.synchronize()
+    img = img.cpu().numpy().astype(np.float64)
+    sel = np.arange(len(o)) if sel is None else sel
+    ref, n_eval, T, mg = orc.render(o[sel], d[sel], cfg["t_near"], cfg["step"], cfg["K"], cfg["term_eps"], cfg["bg"])
+    err = np.abs(img[sel] - ref).max(axis=1)
+    straddle = mg < margin
+    log("  render %s: %d rays, waves %d, evaluated %d, blended %d; oracle blended (subset) %d; max err %.3g "
+        "(straddling rays: %d, max err there %.3g)" % (cfg["name"], len(o), stats["waves"], stats["samples_evaluated"],
+                                                     stats["samples_blended"], n_eval.sum(), err[~straddle].max(),
+                                                     straddle.sum(), err[straddle].max() if straddle.any() else 0))
+    assert err[~straddle].max() <= tol
+    if straddle.any():
+        assert err[straddle].max() <= tol + cfg["term_eps"]
+    assert straddle.mean() < (0.002 if sc["wdtype"] == "f32" else 0.2)
+    assert stats["rays"] == len(o) and stats["samples_evaluated"] >= stats["samples_blended"]
+    if sel is None or len(sel) == len(o):
+        if not straddle.any():
+            assert stats["samples_blended"] == n_eval.sum()
+        else:
+            assert abs(stats["samples_blended"] - n_eval.sum()) <= straddle.sum()
+    return dev, img, stats
+
+
+def test_render_config1_fp32():
+    cfg = configs.config1()
+    render_check(cfg)
+
+
+def test_render_config1_fp32_with_termination():
+    cfg = configs.config1(48, 48)
+    cfg["scene"] = scene_dict((2, 2, 2), (0, 0, 0), (1, 1, 1), 32, "f32", 77, sigma_scale=60.0)
+    cfg["term_eps"] = 0.01
+    cfg["bg"] = (1.0, 1.0, 1.0)
+    render_check(cfg)
+
+
+@pytest.mark.parametrize("wdtype", ["f16", "bf16"])
+def test_render_config3_small(wdtype):
+    cfg = configs.config3(96, 96, wdtype=wdtype)
+    render_check(cfg)
+
+
+def test_render_config3_fp32_weights():
+    cfg = configs.config3(64, 64, wdtype="f32")
+    render_check(cfg)
+
+
+def test_render_config5_small():
+    cfg = configs.config5(96, 54, net_res=8, occ_res=128)
+    render_check(cfg)
+
+
+def test_render_is_independent_of_wave_cut_and_deterministic():
+    import paper_2103_13744_amd as kn
+    cfg = configs.config3(80, 80)
+    dev, _ = make_pair(cfg["scene"])
+    o, d = cuda(cfg["rays_o"]), cuda(cfg["rays_d"])
+    args = (cfg["t_near"], cfg["step"], cfg["K"], cfg["term_eps"], cfg["bg"])
+    imgs = []
+    try:
+        for first, slots in ((8, 8), (8, 8), (1, 1), (3, 5), (64, 64)):
+            kn.set_render_params(first, slots)
+            img, st = dev.render(o, d, *args, want_stats=True)
+            imgs.append((img.cpu().numpy(), st))
+    finally:
+        kn.set_render_params(0, 0)
+    for img, st in imgs[1:]:
+        np.testing.assert_array_equal(img, imgs[0][0])
+        assert st["samples_blended"] == imgs[0][1]["samples_blended"]
+    assert imgs[2][1]["waves"] > imgs[0][1]["waves"] > imgs[4][1]["waves"] >= 1
+
+
+def test_render_edge_cases():
+    import torch
+    cfg = configs.config3(16, 16)
+    sc = dict(cfg["scene"])
+    # nothing occupied -> background everywhere
+    sc["occupancy"] = np.zeros((8, 8, 8), np.uint8)
+    dev, _ = make_pair(sc)
+    img = dev.render(cuda(cfg["rays_o"]), cuda(cfg["rays_d"]), cfg["t_near"], cfg["step"], cfg["K"], 0.01, (0.25, 0.5, 0.75))
+    np.testing.assert_array_equal(img.cpu().numpy(), np.tile(np.float32([0.25, 0.5, 0.75]), (256, 1)))
+    # zero rays, zero lattice points
+    e = torch.empty((0, 3), dtype=torch.float32, device="cuda")
+    assert dev.render(e, e, 1.0, 0.1, 16).shape == (0, 3)
+    img = dev.render(cuda(cfg["rays_o"]), cuda(cfg["rays_d"]), cfg["t_near"], cfg["step"], 0, 0.0, (1, 0, 0))
+    np.testing.assert_array_equal(img.cpu().numpy(), np.tile(np.float32([1, 0, 0]), (256, 1)))
+
+
+# ------------------------------------------------------------------ full-size workloads (sampled comparison)
+def test_full_config2_sampled():
+    cfg = configs.config2()
+    M = len(cfg["points"])
+    sel = ks.rng(99).choice(M, size=20_000, replace=False)
+    check_eval(cfg["scene"], cfg["points"], cfg["dirs"], sample=sel)
+
+
+def test_full_config4_sampled():
+    cfg = configs.config4()
+    M = len(cfg["points"])
+    sel = ks.rng(98).choice(M, size=20_000, replace=False)
+    check_eval(cfg["scene"], cfg["points"], cfg["dirs"], sample=sel)
+
+
+def test_full_config3_sampled():
+    cfg = configs.config3()
+    R = len(cfg["rays_o"])
+    sel = np.sort(ks.rng(97).choice(R, size=6000, replace=False))
+    _, img, stats = render_check(cfg, sel=sel)
+    assert stats["samples_blended"] > 1_000_000
+
+
+def test_full_config5_sampled():
+    cfg = configs.config5()
+    R = len(cfg["rays_o"])
+    sel = np.sort(ks.rng(96).choice(R, size=3000, replace=False))
+    render_check(cfg, sel=sel)
