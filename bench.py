@@ -1,0 +1,145 @@
+#!/usr/bin/env python3
+"""Benchmark of the KiloNeRF rendering path on one MI355X.
+
+A step = one pass of the whole path (march + empty-space skipping, bucketing, grouped MLP, blending
+with early termination, wave loop) over one 800x800 frame of the synthetic 16^3-network scene
+(workload "cfg3"); the camera cycles through 8 poses on a ring.  Rays, weights and the occupancy
+grid are resident in HBM before the timed region.  Prints one JSON line.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_MFMA_16BIT = 2.5e15   # FLOP/s, dense fp16 / bf16 MFMA, MI355X
+PEAK_HBM = 8.0e12          # B/s
+FLOP_PER_SAMPLE = {32: 12160, 64: 36608}
+
+
+def cpu_baseline(cfg_fn, poses, budget_s=12.0):
+    """Time the oracle (threaded build, all host cores) on whole frames of the same workload."""
+    from oracle import OracleScene
+    cfg = cfg_fn(poses[0])
+    s = cfg["scene"]
+    orc = OracleScene(s["res"], s["aabb_min"], s["aabb_max"], s["hidden"], s["weights"], s["occupancy"], threads=True)
+    samples, t_total, frames = 0, 0.0, 0
+    for az in poses:
+        c = cfg_fn(az)
+        t0 = time.perf_counter()
+        _, n_eval, _, _ = orc.render(c["rays_o"], c["rays_d"], c["t_near"], c["step"], c["K"], c["term_eps"], c["bg"])
+        t_total += time.perf_counter() - t0
+        samples += int(n_eval.sum())
+        frames += 1
+        if t_total >= budget_s:
+            break
+    return {"value": samples / t_total, "unit": "samples/s", "cores": orc.num_threads(), "kind": "oracle",
+            "sample": "%d whole 800x800 frame(s) of the same scene (%d blended samples, %.1f s)" % (frames, samples, t_total),
+            "frames_per_sec": frames / t_total}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=40)
+    ap.add_argument("--warmup", type=int, default=8)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--wdtype", default="f16")
+    ap.add_argument("--size", type=int, default=800)
+    a = ap.parse_args()
+    if a.gpus != 1:
+        print("bench.py: this build runs on one GPU only (rays would shard across GPUs; see DESIGN.md); use --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import paper_2103_13744_amd as kn
+    from kn_synth import configs
+
+    torch.cuda.set_device(0)
+    kn.load_library(build_if_missing=True)
+    poses = [45.0 * i for i in range(8)]
+    cfg_fn = lambda az: configs.config3(a.size, a.size, azimuth=az, wdtype=a.wdtype)
+    cfg = cfg_fn(poses[0])
+    sc = cfg["scene"]
+    dt = {"f32": torch.float32, "f16": torch.float16, "bf16": torch.bfloat16}[a.wdtype]
+    scene = kn.Scene(sc["res"], sc["aabb_min"], sc["aabb_max"], sc["hidden"], torch.from_numpy(sc["weights"]).to(dt).cuda(),
+                     torch.from_numpy(sc["occupancy"]).cuda())
+    rays = []
+    for az in poses:
+        o, d = configs.camera_rays(a.size, a.size, 40.0, 4.0, az, 30.0)
+        rays.append((torch.from_numpy(o).cuda(), torch.from_numpy(d).cuda()))
+    R = a.size * a.size
+    out = torch.empty((R, 3), dtype=torch.float32, device="cuda")
+    args = (cfg["t_near"], cfg["step"], cfg["K"], cfg["term_eps"], cfg["bg"])
+
+    # per-pose sample counts (untimed)
+    stats = []
+    for o, d in rays:
+        _, st = scene.render(o, d, *args, want_stats=True, out=out)
+        stats.append(st)
+    for i in range(a.warmup):
+        scene.render(*rays[i % 8], *args, out=out)
+    torch.cuda.synchronize()
+
+    kn.profile_enable(True)
+    kn.profile_read(reset=True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(a.steps):
+        scene.render(*rays[i % 8], *args, out=out)
+    torch.cuda.synchronize()
+    dt_s = time.perf_counter() - t0
+    prof = kn.profile_read(reset=True)
+    kn.profile_enable(False)
+
+    blended = sum(stats[i % 8]["samples_blended"] for i in range(a.steps))
+    evaluated = sum(stats[i % 8]["samples_evaluated"] for i in range(a.steps))
+    waves = sum(stats[i % 8]["waves"] for i in range(a.steps))
+    H = sc["hidden"]
+    stage_ms = {k: prof[k] for k in ("ms_march", "ms_bucket", "ms_mlp", "ms_blend")}
+    mlp_s = prof["ms_mlp"] * 1e-3
+    mlp_tflops = FLOP_PER_SAMPLE[H] * prof["mlp_samples"] / mlp_s / 1e12 if mlp_s > 0 else 0.0
+    roof_mlp = {"kernel": "k_mlp_mfma (fused grouped MLP)", "bound": "mfma", "achieved": mlp_tflops,
+                "peak": PEAK_MFMA_16BIT / 1e12, "unit": "TFLOP/s", "frac": mlp_tflops * 1e12 / PEAK_MFMA_16BIT,
+                "traffic": None, "avg_launch_ms": prof["ms_mlp"] / max(prof["mlp_launches"], 1),
+                "launches": prof["mlp_launches"], "samples_per_launch": prof["mlp_samples"] / max(prof["mlp_launches"], 1)}
+    # marching: algorithmic bytes = 24 B per ray read once per frame + 8 B (key, record) per kept sample written
+    # + the packed occupancy grid read once per frame
+    occ_bytes = int(np.prod(sc["occupancy"].shape)) / 8
+    march_bytes = a.steps * (24.0 * R + occ_bytes) + 8.0 * prof["mlp_samples"]
+    march_s = prof["ms_march"] * 1e-3
+    roof_march = {"kernel": "k_march_wave (march + empty-space skipping)", "bound": "hbm",
+                  "achieved": march_bytes / march_s / 1e9 if march_s > 0 else 0.0, "peak": PEAK_HBM / 1e9, "unit": "GB/s",
+                  "frac": march_bytes / march_s / PEAK_HBM if march_s > 0 else 0.0, "traffic": None,
+                  "avg_launch_ms": prof["ms_march"] / max(prof["mlp_launches"], 1)}
+    dominant = max(stage_ms, key=stage_ms.get)
+    roofline = dict(roof_march if dominant == "ms_march" else roof_mlp)
+    res = {
+        "metric": "MLP sample evals/sec + frames/sec at 800x800",
+        "value": blended / dt_s, "unit": "samples/s",
+        "n_gpus": 1, "steps": a.steps, "warmup": a.warmup, "ms_per_step": dt_s * 1e3 / a.steps,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": a.wdtype, "data": "synthetic",
+        "config": {"workload": "cfg3: %dx%d render, 16^3 networks (H=32), 256^3 occupancy grid (8%% occupied), "
+                               "step diag/512, eps 0.01, 8 camera poses" % (a.size, a.size)},
+        "frames_per_sec": a.steps / dt_s,
+        "samples_blended_per_frame": blended / a.steps, "samples_evaluated_per_frame": evaluated / a.steps,
+        "waves_per_frame": waves / a.steps,
+        "stage_ms_per_frame": {k: v / a.steps for k, v in stage_ms.items()},
+        "dominant_stage": dominant,
+        "roofline": roofline,
+        "roofline_mlp": roof_mlp, "roofline_march": roof_march,
+    }
+    if not a.no_cpu_baseline:
+        res["cpu_baseline"] = cpu_baseline(cfg_fn, poses)
+    print(json.dumps(res))
+
+
+if __name__ == "__main__":
+    main()

@@ -51,6 +51,9 @@ def load_library(build_if_missing: bool = True):
     global _lib
     if _lib is not None:
         return _lib
+    # torch ships its own HIP runtime; it must be the one already loaded when the library is opened,
+    # so that device pointers and streams created by torch are valid inside the library
+    import torch  # noqa: F401
     if not os.path.exists(LIB_PATH):
         if not build_if_missing:
             raise KnError("libkilonerf_hip.so has not been built (run paper_2103_13744_amd/build.py)")
