@@ -68,6 +68,42 @@ __global__ void k_pack_occupancy(const uint8_t *__restrict__ occ, int64_t n_vox,
     bits[w] = v;
 }
 
+// skip field, step 1: 0 for blocks of 4^3 voxels that contain an occupied voxel, 255 otherwise
+__global__ void k_skip_seed(const uint8_t *__restrict__ occ, int ox, int oy, int oz, int sx, int sy, int sz,
+                            uint8_t *__restrict__ dist)
+{
+    const int64_t c = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (c >= (int64_t)sx * sy * sz) return;
+    const int cz = (int)(c % sz), cy = (int)((c / sz) % sy), cx = (int)(c / ((int64_t)sz * sy));
+    bool any = false;
+    for (int x = cx * KN_SKIP_BLOCK; x < min((cx + 1) * KN_SKIP_BLOCK, ox) && !any; ++x)
+        for (int y = cy * KN_SKIP_BLOCK; y < min((cy + 1) * KN_SKIP_BLOCK, oy) && !any; ++y)
+            for (int z = cz * KN_SKIP_BLOCK; z < min((cz + 1) * KN_SKIP_BLOCK, oz); ++z)
+                if (occ[((int64_t)x * oy + y) * oz + z] != 0) { any = true; break; }
+    dist[c] = any ? 0 : 255;
+}
+
+// skip field, step 2 (repeated): one Jacobi sweep of d = min(d, 1 + min over the 26 neighbours);
+// after n sweeps every value <= n is the exact Chebyshev distance
+__global__ void k_skip_sweep(const uint8_t *__restrict__ in, int sx, int sy, int sz, uint8_t *__restrict__ out)
+{
+    const int64_t c = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (c >= (int64_t)sx * sy * sz) return;
+    const int cz = (int)(c % sz), cy = (int)((c / sz) % sy), cx = (int)(c / ((int64_t)sz * sy));
+    int best = in[c];
+    for (int x = max(cx - 1, 0); x <= min(cx + 1, sx - 1); ++x)
+        for (int y = max(cy - 1, 0); y <= min(cy + 1, sy - 1); ++y)
+            for (int z = max(cz - 1, 0); z <= min(cz + 1, sz - 1); ++z)
+                best = min(best, (int)in[((int64_t)x * sy + y) * sz + z] + 1);
+    out[c] = (uint8_t)min(best, 255);
+}
+
+__global__ void k_skip_cap(uint8_t *__restrict__ d, int64_t n)
+{
+    const int64_t c = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (c < n && d[c] > KN_SKIP_MAX) d[c] = KN_SKIP_MAX;
+}
+
 // zero the outputs of the points that fell outside the AABB (bucket N of the sorted list)
 __global__ void k_zero_outside(const int32_t *__restrict__ perm, const int32_t *__restrict__ offsets, int32_t N, int64_t M,
                                float *__restrict__ sigma, float *__restrict__ rgb)
@@ -160,6 +196,8 @@ extern "C" int kn_scene_create(const kn_scene_desc *desc, void *stream, kn_scene
     sc->occ_bits = nullptr;
     sc->packed_w = nullptr;
     sc->packed_halfs_per_net = 0;
+    sc->skip_dist = nullptr;
+    sc->skip_res[0] = sc->skip_res[1] = sc->skip_res[2] = 0;
     hipStream_t st = (hipStream_t)stream;
     int rc = KN_OK;
     if (sc->has_occ) {
@@ -172,6 +210,28 @@ extern "C" int kn_scene_create(const kn_scene_desc *desc, void *stream, kn_scene
             hipLaunchKernelGGL(k_pack_occupancy, dim3((unsigned)kn_div_up(words, 256)), dim3(256), 0, st, desc->occupancy, vox,
                                sc->occ_bits);
             if (hipGetLastError() != hipSuccess) rc = KN_E_HIP;
+        }
+        if (rc == KN_OK) { // skip field: seed, KN_SKIP_MAX sweeps (ping-pong), cap
+            int sr[3];
+            for (int a = 0; a < 3; ++a) sr[a] = sc->skip_res[a] = (int)kn_div_up(desc->occ_res[a], KN_SKIP_BLOCK);
+            const int64_t cells = (int64_t)sr[0] * sr[1] * sr[2];
+            uint8_t *tmp = nullptr;
+            if (hipMalloc((void **)&sc->skip_dist, (size_t)cells) != hipSuccess ||
+                hipMalloc((void **)&tmp, (size_t)cells) != hipSuccess) {
+                rc = KN_E_HIP;
+            } else {
+                const dim3 grid((unsigned)kn_div_up(cells, 256)), block(256);
+                hipLaunchKernelGGL(k_skip_seed, grid, block, 0, st, desc->occupancy, desc->occ_res[0], desc->occ_res[1],
+                                   desc->occ_res[2], sr[0], sr[1], sr[2], sc->skip_dist);
+                uint8_t *a = sc->skip_dist, *b = tmp;
+                for (int it = 0; it < KN_SKIP_MAX; ++it) { // even count: the result ends in skip_dist
+                    hipLaunchKernelGGL(k_skip_sweep, grid, block, 0, st, a, sr[0], sr[1], sr[2], b);
+                    uint8_t *t = a; a = b; b = t;
+                }
+                hipLaunchKernelGGL(k_skip_cap, grid, block, 0, st, sc->skip_dist, cells);
+                if (hipGetLastError() != hipSuccess || hipStreamSynchronize(st) != hipSuccess) rc = KN_E_HIP;
+            }
+            if (tmp) (void)hipFree(tmp);
         }
     } else {
         sc->occ_grid = sc->net_grid;
@@ -191,6 +251,7 @@ extern "C" int kn_scene_destroy(kn_scene *sc)
     (void)hipDeviceSynchronize();
     if (sc->occ_bits) (void)hipFree(sc->occ_bits);
     if (sc->packed_w) (void)hipFree(sc->packed_w);
+    if (sc->skip_dist) (void)hipFree(sc->skip_dist);
     delete sc;
     return KN_OK;
 }
@@ -237,12 +298,13 @@ extern "C" int kn_eval_grouped(const kn_scene *sc, void *stream, const float *po
     KN_TRY(kn_cell_keys(sc, st, points, M, cell_id, keys));
     tm.mark();
     KnBucketOut bo;
-    KN_TRY(kn_bucket_run(st, keys, M, sc->N, kn_mlp_tile_len(sc), counts, nullptr, perm, ws, &bo));
+    KN_TRY(kn_bucket_run(st, keys, M, nullptr, sc->N, kn_mlp_tile_len(sc), counts, nullptr, perm, ws, &bo));
     if (M == 0) return KN_OK;
     tm.mark();
     KnSampleSrc src{};
     src.points = points;
     src.dirs = dirs;
+    src.out4 = nullptr;
     KN_TRY(kn_mlp_launch(sc, st, src, bo, M, sigma, rgb));
     hipLaunchKernelGGL(k_zero_outside, dim3((unsigned)kn_div_up(M, 256)), dim3(256), 0, st, bo.perm, bo.offsets, sc->N, M, sigma,
                        rgb);

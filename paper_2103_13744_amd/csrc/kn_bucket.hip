@@ -10,6 +10,13 @@
 
 namespace {
 
+// The number of keys is either known on the host, or (render waves) only on the device; in the
+// second case the host passes an upper bound for grid sizing and a pointer to the real count.
+__device__ __forceinline__ int64_t real_count(int64_t m_bound, const int32_t *m_dev)
+{
+    return m_dev ? (int64_t)*m_dev : m_bound;
+}
+
 constexpr int RS_THREADS = 256;
 constexpr int RS_ROWS = 16;                       // 64-element rows per wavefront
 constexpr int RS_WAVES = RS_THREADS / KN_WAVE;    // 4
@@ -117,31 +124,50 @@ __global__ void __launch_bounds__(SCAN_THREADS) k_scan_apply(const int32_t *__re
 }
 
 // ---------------------------------------------------------------------------------------------
-// radix pass, step 1: digit histogram of each 4096-key block -> table[digit * n_blocks + block]
-__global__ void __launch_bounds__(RS_THREADS) k_radix_hist(const int32_t *__restrict__ keys, int64_t M, int shift,
-                                                           int32_t n_blocks, int32_t *__restrict__ table)
+// radix pass, step 1: digit histogram of each 4096-key block -> table[digit * n_blocks + block].
+// With `grp` given, the block also adds its counts to per-digit sums over groups of GRP_BLOCKS
+// blocks and to per-digit totals (integer atomics: the sums do not depend on arrival order), from
+// which the scatter kernel derives its own base offsets without a separate scan of the table.
+constexpr int GRP_BLOCKS = 32;
+__global__ void __launch_bounds__(RS_THREADS) k_radix_hist(const int32_t *__restrict__ keys, int64_t M_bound,
+                                                           const int32_t *__restrict__ M_dev, int shift,
+                                                           int32_t n_blocks, int32_t *__restrict__ table,
+                                                           int32_t *__restrict__ grp, int32_t n_grp,
+                                                           int32_t *__restrict__ tot)
 {
     __shared__ int32_t hist[256];
+    const int64_t M = real_count(M_bound, M_dev);
+    int64_t base = (int64_t)blockIdx.x * RS_TILE;
+    if (grp && base >= M) return; // nobody reads this block's table column in that mode
     hist[threadIdx.x] = 0;
     __syncthreads();
-    int64_t base = (int64_t)blockIdx.x * RS_TILE;
 #pragma unroll 4
     for (int r = 0; r < RS_ROWS; ++r) {
         int64_t i = base + (int64_t)r * RS_THREADS + threadIdx.x;
         if (i < M) atomicAdd(&hist[((uint32_t)keys[i] >> shift) & 255u], 1);
     }
     __syncthreads();
-    table[(int64_t)threadIdx.x * n_blocks + blockIdx.x] = hist[threadIdx.x];
+    const int32_t h = hist[threadIdx.x];
+    table[(int64_t)threadIdx.x * n_blocks + blockIdx.x] = h;
+    if (grp && h) {
+        atomicAdd(&grp[(int64_t)threadIdx.x * n_grp + blockIdx.x / GRP_BLOCKS], h);
+        atomicAdd(&tot[threadIdx.x], h);
+    }
 }
 
 // radix pass, step 3: stable scatter.  Wavefront w of block b owns keys
 // [b*4096 + w*1024, +1024) as 16 rows of 64; order of keys = (block, wave, row, lane).
 __global__ void __launch_bounds__(RS_THREADS)
     k_radix_scatter(const int32_t *__restrict__ keys_in, const int32_t *__restrict__ vals_in,
-                    int32_t *__restrict__ keys_out, int32_t *__restrict__ vals_out, int64_t M, int shift,
-                    int32_t n_blocks, const int32_t *__restrict__ table_scanned)
+                    int32_t *__restrict__ keys_out, int32_t *__restrict__ vals_out, int64_t M_bound,
+                    const int32_t *__restrict__ M_dev, int shift, int32_t n_blocks,
+                    const int32_t *__restrict__ table /*scanned if grp == nullptr, raw counts otherwise*/,
+                    const int32_t *__restrict__ grp, int32_t n_grp, const int32_t *__restrict__ tot)
 {
     __shared__ int32_t cnt[RS_WAVES][256];
+    __shared__ int32_t scan_lds[8];
+    const int64_t M = real_count(M_bound, M_dev);
+    if ((int64_t)blockIdx.x * RS_TILE >= M) return;
     const int lane = threadIdx.x & (KN_WAVE - 1), w = threadIdx.x / KN_WAVE;
 #pragma unroll
     for (int i = 0; i < RS_WAVES; ++i) cnt[i][threadIdx.x] = 0;
@@ -177,7 +203,17 @@ __global__ void __launch_bounds__(RS_THREADS)
     {
         // thread d: turn per-wave digit counts into global base positions
         const int d = threadIdx.x;
-        int32_t run = table_scanned[(int64_t)d * n_blocks + blockIdx.x];
+        int32_t run;
+        if (grp) {
+            // keys with smaller digits + same digit in earlier groups + same digit earlier in my group
+            int32_t all;
+            run = block_exclusive_scan(tot[d], scan_lds, all);
+            const int g = blockIdx.x / GRP_BLOCKS;
+            for (int gg = 0; gg < g; ++gg) run += grp[(int64_t)d * n_grp + gg];
+            for (int bb = g * GRP_BLOCKS; bb < (int)blockIdx.x; ++bb) run += table[(int64_t)d * n_blocks + bb];
+        } else {
+            run = table[(int64_t)d * n_blocks + blockIdx.x];
+        }
 #pragma unroll
         for (int i = 0; i < RS_WAVES; ++i) {
             int32_t c = cnt[i][d];
@@ -199,9 +235,19 @@ __global__ void __launch_bounds__(RS_THREADS)
 }
 
 // ---------------------------------------------------------------------------------------------
-// start[key] = first position of `key` in the sorted list (start[] pre-filled with -1)
-__global__ void k_find_starts(const int32_t *__restrict__ sorted_keys, int64_t M, int32_t *__restrict__ start)
+// zero the atomic tables and preset the bucket starts to "undefined"
+__global__ void k_bucket_init(int32_t *__restrict__ zeros, int64_t n_zeros, int32_t *__restrict__ start, int64_t n_start)
 {
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n_zeros) zeros[i] = 0;
+    if (i < n_start) start[i] = -1;
+}
+
+// start[key] = first position of `key` in the sorted list (start[] pre-filled with -1)
+__global__ void k_find_starts(const int32_t *__restrict__ sorted_keys, int64_t M_bound, const int32_t *__restrict__ M_dev,
+                              int32_t *__restrict__ start)
+{
+    const int64_t M = real_count(M_bound, M_dev);
     int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= M) return;
     int32_t k = sorted_keys[i];
@@ -209,26 +255,35 @@ __global__ void k_find_starts(const int32_t *__restrict__ sorted_keys, int64_t M
 }
 
 // One block: resolve empty buckets (start = next non-empty start), then counts, offsets, tiles.
+// STAGED: the N+1 bucket starts are held in LDS (dynamic, (N+1) ints) instead of global memory.
 constexpr int FIN_THREADS = 1024;
+constexpr int FIN_MAX_STAGED = 12288;
+template <bool STAGED>
 __global__ void __launch_bounds__(FIN_THREADS)
-    k_finalize_buckets(int32_t *__restrict__ start /*N+1, in: first position or -1; out: offsets*/, int32_t N,
-                       int32_t M, int32_t tile_len, int32_t *__restrict__ counts /*N+1*/,
-                       int32_t *__restrict__ offsets /*N+2*/, KnTile *__restrict__ tiles,
-                       int32_t *__restrict__ n_tiles, int32_t *__restrict__ user_counts,
+    k_finalize_buckets(int32_t *__restrict__ start /*N+1, in: first position or -1; out (unstaged): offsets*/, int32_t N,
+                       int32_t M_bound, const int32_t *__restrict__ M_dev, int32_t tile_len,
+                       int32_t *__restrict__ counts /*N+1*/, int32_t *__restrict__ offsets /*N+2*/,
+                       KnTile *__restrict__ tiles, int32_t *__restrict__ n_tiles, int32_t *__restrict__ user_counts,
                        int32_t *__restrict__ user_offsets)
 {
+    extern __shared__ int32_t staged[];
     __shared__ int32_t sa[FIN_THREADS];
     __shared__ int32_t sb[FIN_THREADS];
+    const int32_t M = (int32_t)real_count(M_bound, M_dev);
     const int t = threadIdx.x;
     const int n_entries = N + 1;
     const int per = (n_entries + FIN_THREADS - 1) / FIN_THREADS;
     const int lo = min(t * per, n_entries), hi = min(lo + per, n_entries);
-
+    int32_t *st = STAGED ? staged : start;
+    if (STAGED) {
+        for (int e = t; e < n_entries; e += FIN_THREADS) staged[e] = start[e];
+        __syncthreads();
+    }
     // first defined start inside my chunk; starts of non-empty buckets increase with the key, so
     // "next defined start to the right" is a suffix minimum
     int32_t first = 0x7fffffff;
     for (int i = lo; i < hi; ++i) {
-        int32_t s = start[i];
+        int32_t s = st[i];
         if (s >= 0) { first = s; break; }
     }
     sa[t] = first;
@@ -242,25 +297,28 @@ __global__ void __launch_bounds__(FIN_THREADS)
     int32_t nxt = (t + 1 < FIN_THREADS) ? sa[t + 1] : 0x7fffffff;
     if (nxt == 0x7fffffff) nxt = M;
     for (int i = hi - 1; i >= lo; --i) { // resolve right-to-left inside the chunk
-        int32_t s = start[i];
-        if (s >= 0) nxt = s; else start[i] = nxt;
+        int32_t s = st[i];
+        if (s >= 0) nxt = s; else st[i] = nxt;
     }
     __syncthreads();
-    // counts, offsets, and number of tiles of my chunk (bucket N = outside gets no tiles)
-    int32_t my_tiles = 0;
-    for (int i = lo; i < hi; ++i) {
-        int32_t a = start[i];
-        int32_t b = (i + 1 < n_entries) ? start[i + 1] : M;
-        int32_t c = b - a;
-        counts[i] = c;
-        offsets[i] = a;
-        if (user_counts) user_counts[i] = c;
-        if (user_offsets) user_offsets[i] = a;
-        if (i < N) my_tiles += (c + tile_len - 1) / tile_len;
+    // counts and offsets (entry-parallel), number of tiles of my chunk (bucket N = outside gets none)
+    for (int e = t; e < n_entries; e += FIN_THREADS) {
+        const int32_t a = st[e];
+        const int32_t b = (e + 1 < n_entries) ? st[e + 1] : M;
+        counts[e] = b - a;
+        offsets[e] = a;
+        if (user_counts) user_counts[e] = b - a;
+        if (user_offsets) user_offsets[e] = a;
     }
     if (t == 0) {
         offsets[n_entries] = M;
         if (user_offsets) user_offsets[n_entries] = M;
+    }
+    int32_t my_tiles = 0;
+    for (int i = lo; i < hi && i < N; ++i) {
+        const int32_t a = st[i];
+        const int32_t b = (i + 1 < n_entries) ? st[i + 1] : M;
+        my_tiles += (b - a + tile_len - 1) / tile_len;
     }
     sb[t] = my_tiles;
     __syncthreads();
@@ -273,8 +331,8 @@ __global__ void __launch_bounds__(FIN_THREADS)
     int32_t tbase = sb[t] - my_tiles;
     if (t == FIN_THREADS - 1) *n_tiles = sb[t];
     for (int i = lo; i < hi && i < N; ++i) {
-        int32_t a = start[i];
-        int32_t b = (i + 1 < n_entries) ? start[i + 1] : M;
+        const int32_t a = st[i];
+        const int32_t b = (i + 1 < n_entries) ? st[i + 1] : M;
         for (int32_t s = a; s < b; s += tile_len) {
             KnTile tl;
             tl.net = i;
@@ -336,83 +394,105 @@ int64_t kn_max_tiles(int64_t M, int32_t N, int32_t tile_len)
     return M / tile_len + (M < N ? M : N) + 1;
 }
 
+constexpr int64_t SELF_BASE_MAX_BLOCKS = 8192; // beyond this the (digit, block) table is scanned instead
+
+struct BucketWs {
+    int32_t *keys_a, *keys_b, *vals_a, *vals_b, *table, *table_s, *scan_tmp, *atomics, *start, *counts, *offsets, *n_tiles;
+    KnTile *tiles;
+    int64_t nblk, n_grp, n_atomics;
+};
+
+static void carve_bucket(KnCarver &c, int64_t M, int32_t N, BucketWs &w)
+{
+    w.nblk = kn_div_up(M > 0 ? M : 1, RS_TILE);
+    w.n_grp = kn_div_up(w.nblk, GRP_BLOCKS);
+    w.n_atomics = 4 * (256 * w.n_grp + 256); // group sums + totals, for up to 4 passes
+    w.keys_a = c.carve<int32_t>(M);
+    w.keys_b = c.carve<int32_t>(M);
+    w.vals_a = c.carve<int32_t>(M);
+    w.vals_b = c.carve<int32_t>(M);
+    w.table = c.carve<int32_t>(256 * w.nblk);
+    w.table_s = c.carve<int32_t>(256 * w.nblk);
+    w.scan_tmp = c.carve<int32_t>(kn_scan_tmp_len(256 * w.nblk));
+    w.atomics = c.carve<int32_t>(w.n_atomics);
+    w.start = c.carve<int32_t>(N + 1);
+    w.counts = c.carve<int32_t>(N + 1);
+    w.offsets = c.carve<int32_t>(N + 2);
+    w.tiles = c.carve<KnTile>(kn_max_tiles(M, N, 64));
+    w.n_tiles = c.carve<int32_t>(1);
+}
+
 int64_t kn_bucket_ws_bytes(int64_t M, int32_t N)
 {
-    // mirrors the carve() sequence of kn_bucket_run (with the smallest tile length in use)
     KnCarver c((void *)256, INT64_MAX / 2);
-    int64_t nblk = kn_div_up(M > 0 ? M : 1, RS_TILE);
-    c.carve<int32_t>(M);               // keys ping
-    c.carve<int32_t>(M);               // keys pong / sorted keys
-    c.carve<int32_t>(M);               // vals ping
-    c.carve<int32_t>(M);               // vals pong / perm
-    c.carve<int32_t>(256 * nblk);      // digit table
-    c.carve<int32_t>(256 * nblk);      // scanned digit table
-    c.carve<int32_t>(kn_scan_tmp_len(256 * nblk));
-    c.carve<int32_t>(N + 1);           // start
-    c.carve<int32_t>(N + 1);           // counts
-    c.carve<int32_t>(N + 2);           // offsets
-    c.carve<KnTile>(kn_max_tiles(M, N, 64));
-    c.carve<int32_t>(1);               // n_tiles
+    BucketWs w;
+    carve_bucket(c, M, N, w);
     return c.used;
 }
 
-int kn_bucket_run(hipStream_t st, int32_t *keys, int64_t M, int32_t N, int32_t tile_len, int32_t *user_counts,
-                  int32_t *user_offsets, int32_t *user_perm, KnCarver &ws, KnBucketOut *out)
+int kn_bucket_run(hipStream_t st, int32_t *keys, int64_t M, const int32_t *M_dev, int32_t N, int32_t tile_len,
+                  int32_t *user_counts, int32_t *user_offsets, int32_t *user_perm, KnCarver &ws, KnBucketOut *out)
 {
     if (M < 0 || M > (1ll << 30) || N < 1 || tile_len < 64) return KN_E_INVALID_ARG;
-    const int64_t nblk = kn_div_up(M > 0 ? M : 1, RS_TILE);
-    int32_t *keys_a = ws.carve<int32_t>(M);
-    int32_t *keys_b = ws.carve<int32_t>(M);
-    int32_t *vals_a = ws.carve<int32_t>(M);
-    int32_t *vals_b = ws.carve<int32_t>(M);
-    int32_t *table = ws.carve<int32_t>(256 * nblk);
-    int32_t *table_s = ws.carve<int32_t>(256 * nblk);
-    int32_t *scan_tmp = ws.carve<int32_t>(kn_scan_tmp_len(256 * nblk));
-    int32_t *start = ws.carve<int32_t>(N + 1);
-    int32_t *counts = ws.carve<int32_t>(N + 1);
-    int32_t *offsets = ws.carve<int32_t>(N + 2);
-    KnTile *tiles = ws.carve<KnTile>(kn_max_tiles(M, N, 64));
-    int32_t *n_tiles = ws.carve<int32_t>(1);
+    BucketWs w;
+    carve_bucket(ws, M, N, w);
     if (!ws.ok()) return KN_E_WORKSPACE;
+    const int64_t nblk = w.nblk;
+    const bool self_base = nblk <= SELF_BASE_MAX_BLOCKS;
 
     const int passes = radix_passes(N);
     const int32_t *kin = keys;
     const int32_t *vin = nullptr;
-    int32_t *sorted_keys = keys_b;
-    int32_t *perm = vals_b;
+    int32_t *sorted_keys = w.keys_b;
+    int32_t *perm = w.vals_b;
+    {
+        const int64_t n_init = w.n_atomics > N + 1 ? w.n_atomics : N + 1;
+        dim3 grid;
+        KN_TRY(launch_1d(n_init, 256, grid));
+        hipLaunchKernelGGL(k_bucket_init, grid, dim3(256), 0, st, w.atomics, w.n_atomics, w.start, (int64_t)N + 1);
+        KN_CHECK_LAUNCH();
+    }
     if (M > 0) {
         for (int p = 0; p < passes; ++p) {
             const bool last = (p == passes - 1);
-            int32_t *kout = (p & 1) ? keys_a : keys_b;
-            int32_t *vout = (p & 1) ? vals_a : vals_b;
+            int32_t *kout = (p & 1) ? w.keys_a : w.keys_b;
+            int32_t *vout = (p & 1) ? w.vals_a : w.vals_b;
             if (last && user_perm) vout = user_perm;
-            hipLaunchKernelGGL(k_radix_hist, dim3((unsigned)nblk), dim3(RS_THREADS), 0, st, kin, M, 8 * p, (int32_t)nblk, table);
+            int32_t *grp = self_base ? w.atomics + p * (256 * w.n_grp + 256) : nullptr;
+            int32_t *tot = self_base ? grp + 256 * w.n_grp : nullptr;
+            hipLaunchKernelGGL(k_radix_hist, dim3((unsigned)nblk), dim3(RS_THREADS), 0, st, kin, M, M_dev, 8 * p, (int32_t)nblk,
+                               w.table, grp, (int32_t)w.n_grp, tot);
             KN_CHECK_LAUNCH();
-            KN_TRY(kn_exclusive_scan_i32(st, table, table_s, 256 * nblk, scan_tmp, nullptr));
-            hipLaunchKernelGGL(k_radix_scatter, dim3((unsigned)nblk), dim3(RS_THREADS), 0, st, kin, vin, kout, vout, M,
-                               8 * p, (int32_t)nblk, table_s);
+            const int32_t *tbl = w.table;
+            if (!self_base) {
+                KN_TRY(kn_exclusive_scan_i32(st, w.table, w.table_s, 256 * nblk, w.scan_tmp, nullptr));
+                tbl = w.table_s;
+            }
+            hipLaunchKernelGGL(k_radix_scatter, dim3((unsigned)nblk), dim3(RS_THREADS), 0, st, kin, vin, kout, vout, M, M_dev,
+                               8 * p, (int32_t)nblk, tbl, grp, (int32_t)w.n_grp, tot);
             KN_CHECK_LAUNCH();
             kin = kout;
             vin = vout;
             sorted_keys = kout;
             perm = vout;
         }
-    }
-    KN_TRY(kn_fill_i32(st, start, N + 1, -1));
-    if (M > 0) {
         dim3 grid;
         KN_TRY(launch_1d(M, 256, grid));
-        hipLaunchKernelGGL(k_find_starts, grid, dim3(256), 0, st, sorted_keys, M, start);
+        hipLaunchKernelGGL(k_find_starts, grid, dim3(256), 0, st, sorted_keys, M, M_dev, w.start);
         KN_CHECK_LAUNCH();
     }
-    hipLaunchKernelGGL(k_finalize_buckets, dim3(1), dim3(FIN_THREADS), 0, st, start, N, (int32_t)M, tile_len, counts,
-                       offsets, tiles, n_tiles, user_counts, user_offsets);
+    if (N + 1 <= FIN_MAX_STAGED)
+        hipLaunchKernelGGL(k_finalize_buckets<true>, dim3(1), dim3(FIN_THREADS), (size_t)(N + 1) * sizeof(int32_t), st, w.start,
+                           N, (int32_t)M, M_dev, tile_len, w.counts, w.offsets, w.tiles, w.n_tiles, user_counts, user_offsets);
+    else
+        hipLaunchKernelGGL(k_finalize_buckets<false>, dim3(1), dim3(FIN_THREADS), 0, st, w.start, N, (int32_t)M, M_dev, tile_len,
+                           w.counts, w.offsets, w.tiles, w.n_tiles, user_counts, user_offsets);
     KN_CHECK_LAUNCH();
     out->perm = perm;
-    out->counts = counts;
-    out->offsets = offsets;
-    out->tiles = tiles;
-    out->n_tiles = n_tiles;
+    out->counts = w.counts;
+    out->offsets = w.offsets;
+    out->tiles = w.tiles;
+    out->n_tiles = w.n_tiles;
     return KN_OK;
 }
 
@@ -458,5 +538,5 @@ extern "C" int kn_bucket(const kn_scene *sc, void *stream, const int32_t *ids, i
         KN_CHECK_LAUNCH();
     }
     KnBucketOut bo;
-    return kn_bucket_run(st, keys, M, sc->N, 64, counts, offsets, perm, ws, &bo);
+    return kn_bucket_run(st, keys, M, nullptr, sc->N, 64, counts, offsets, perm, ws, &bo);
 }

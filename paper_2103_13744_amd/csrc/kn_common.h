@@ -37,7 +37,14 @@ struct kn_scene {
     uint32_t *occ_bits;    // device, one bit per voxel, linear voxel index = bit index
     void *packed_w;        // device, matrix-core operand order (16-bit types only)
     int64_t packed_halfs_per_net;
+    // Coarse skip field over the occupancy grid: one byte per block of KN_SKIP_BLOCK^3 voxels holding
+    // the Chebyshev distance, in blocks, to the nearest block with an occupied voxel (0 = occupied
+    // block, capped at KN_SKIP_MAX).  Lets marching jump over provably empty lattice points.
+    uint8_t *skip_dist;    // device, skip_res[0]*[1]*[2] bytes, x slowest; nullptr without occupancy
+    int32_t skip_res[3];
 };
+#define KN_SKIP_BLOCK 4
+#define KN_SKIP_MAX 32
 
 // Host-side launch helpers ----------------------------------------------------------------------
 extern thread_local int g_kn_last_hip_error;
@@ -112,8 +119,9 @@ struct KnBucketOut {
 };
 
 // Sorts `keys` (values in [0, N], N = outside/unused) stably, fills perm/counts/offsets/tiles in
-// workspace memory (or the user's buffers where given).  keys may be overwritten.
-int kn_bucket_run(hipStream_t st, int32_t *keys, int64_t M, int32_t N, int32_t tile_len,
+// workspace memory (or the user's buffers where given).  keys may be overwritten.  If M_dev is
+// given, M is only an upper bound (grid and workspace sizing) and *M_dev the real count.
+int kn_bucket_run(hipStream_t st, int32_t *keys, int64_t M, const int32_t *M_dev, int32_t N, int32_t tile_len,
                   int32_t *user_counts, int32_t *user_offsets, int32_t *user_perm, KnCarver &ws,
                   KnBucketOut *out);
 
@@ -122,12 +130,12 @@ int kn_bucket_run(hipStream_t st, int32_t *keys, int64_t M, int32_t N, int32_t t
 struct KnSampleSrc {
     const float *points;   // M*3 or nullptr
     const float *dirs;     // M*3 or nullptr
-    const uint32_t *rec;   // per slot: ray_slot << kbits | k   (render)
+    const uint32_t *rec;   // per sample: ray << kbits | k   (render)
     const float *rays_o;   // R*3
     const float *rays_d;   // R*3
-    const int32_t *live;   // live index -> ray id (render)
     float t_near, step;
     int32_t kbits;
+    float *out4;           // render: (r, g, b, sigma) per sample, 16 bytes each; nullptr = separate sigma / rgb arrays
 };
 
 int kn_mlp_launch(const kn_scene *sc, hipStream_t st, const KnSampleSrc &src, const KnBucketOut &b,

@@ -85,9 +85,20 @@ __global__ void __launch_bounds__(KN_WAVE) k_mlp_f32(const float *__restrict__ w
         float o5[3];
         affine_f32<H, 3>(W5, b5, a, o5);
         if (active) {
-            sigma[idx] = sg;
+            float col[3];
 #pragma unroll
-            for (int c = 0; c < 3; ++c) rgb[3 * (int64_t)idx + c] = 1.0f / (1.0f + expf(-o5[c]));
+            for (int c = 0; c < 3; ++c) col[c] = 1.0f / (1.0f + expf(-o5[c]));
+            if (src.out4) {
+                float *o = src.out4 + 4 * (int64_t)idx;
+                o[0] = col[0];
+                o[1] = col[1];
+                o[2] = col[2];
+                o[3] = sg;
+            } else {
+                sigma[idx] = sg;
+#pragma unroll
+                for (int c = 0; c < 3; ++c) rgb[3 * (int64_t)idx + c] = col[c];
+            }
         }
     }
 }

@@ -351,11 +351,20 @@ __global__ void __launch_bounds__(WAVES *KN_WAVE)
         __builtin_amdgcn_wave_barrier(); // staging buffer is rewritten by the next iteration
 
         if (active) {
-            sigma[idx] = fmaxf(out[3], 0.0f);
-            float *o = rgb + 3 * (int64_t)idx;
+            const float sg = fmaxf(out[3], 0.0f);
+            float col[3];
 #pragma unroll
             for (int c = 0; c < 3; ++c)
-                o[c] = __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-1.4426950408889634f * out[c]));
+                col[c] = __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-1.4426950408889634f * out[c]));
+            if (src.out4) {
+                *(f4 *)(src.out4 + 4 * (int64_t)idx) = (f4){col[0], col[1], col[2], sg};
+            } else {
+                sigma[idx] = sg;
+                float *o = rgb + 3 * (int64_t)idx;
+                o[0] = col[0];
+                o[1] = col[1];
+                o[2] = col[2];
+            }
         }
     }
 }

@@ -1,20 +1,30 @@
 // Ray marching with empty-space skipping, alpha blending with early ray termination, and the
 // wave loop that ties them to bucketing and the grouped MLP (Sec. 3.1 Eq. 1-4, Sec. 3.4).
 //
-// A wave gives every live ray up to S sample slots.  Slot j of live ray i is entry j*n_live + i of
-// the wave's arrays, so that marching, the networks' output scatter and blending all touch
-// consecutive addresses for consecutive rays.  Unused slots carry the key N ("no network").
+// A wave gives every live ray up to S samples.  Marching is cooperative: a group of MARCH_G lanes
+// owns one ray and tests MARCH_G consecutive lattice points per iteration, so the latency of the
+// dependent index arithmetic + occupancy load is paid once per MARCH_G points.  A coarse skip field
+// (Chebyshev distance, in blocks of 4^3 voxels, to the nearest occupied block) lets a group jump
+// over lattice points that provably lie in empty blocks; every point that could be kept is still
+// tested with the exact arithmetic of Eq. 6, so the kept set equals the plain per-point definition.
+// Kept samples go to a per-ray row, rows are compacted (scan of the per-ray counts) into a dense
+// ray-major sample list, and only that list is bucketed and evaluated.
 #include "kn_common.h"
 
 #include <math.h>
 
-int kn_cell_keys(const kn_scene *sc, hipStream_t st, const float *points, int64_t M, int32_t *ids, int32_t *keys);
-
 namespace {
+
+constexpr int MARCH_G = 16;
 
 struct MarchParams {
     KnGrid net, occ;
     const uint32_t *occ_bits;
+    const uint8_t *skip_dist;
+    int32_t skip_res[3];
+    float skip_inv[3];   // 1 / (edge of a skip block) per axis
+    float skip_edge_min; // shortest edge of a skip block
+    float skip_margin;   // safety margin on the jump radius (position rounding)
     int32_t has_occ;
     float t_near, step;
     int32_t K;
@@ -89,51 +99,120 @@ __device__ __forceinline__ void clip_ray(const KnGrid &g, const float o[3], cons
     float b = ceilf((tmax - t_near) / step - 0.5f) + 3.0f;
     a = fminf(fmaxf(a, 0.0f), (float)K); // NaN -> 0
     b = fminf(fmaxf(b, 0.0f), (float)K);
-    if (!(tmin <= tmax)) { // empty or NaN: keep NaN conservative (full range), empty -> nothing
+    if (!(tmin <= tmax)) { // empty -> nothing; NaN -> stay conservative (full range)
         if (tmin > tmax) { a = 0.0f; b = 0.0f; } else { a = 0.0f; b = (float)K; }
     }
     k_lo = (int32_t)a;
     k_hi = (int32_t)b;
 }
 
+// Exact test of one lattice point (Sec. 3.4): inside the AABB and in an occupied voxel.  The
+// occupancy voxel is looked up first; Eq. 6 for the network grid is only evaluated for points
+// that pass it.  cell = network id of a kept point.
 __device__ __forceinline__ bool sample_kept(const MarchParams &p, const GridFast &gn, const GridFast &go, float x, float y,
                                             float z, int32_t &cell)
 {
+    if (p.has_occ) {
+        const int32_t v = grid_index_fast(go, x, y, z);
+        if (v < 0) return false;
+        if (!((p.occ_bits[(uint32_t)v >> 5] >> (v & 31)) & 1u)) return false;
+    }
     cell = grid_index_fast(gn, x, y, z);
-    if (cell < 0) return false;
-    if (!p.has_occ) return true;
-    const int32_t v = grid_index_fast(go, x, y, z);
-    if (v < 0) return false;
-    return (p.occ_bits[(uint32_t)v >> 5] >> (v & 31)) & 1u;
+    return cell >= 0;
+}
+
+// Cooperative march of one ray by a group of MARCH_G lanes (all lanes of the group call this with
+// the same arguments; gl = lane index inside the group).  Collects up to S kept lattice indices in
+// [k, k_hi), in ascending order, through emit(j, kk, cell).  Returns the number collected and
+// leaves in k the index to resume at (>= k_hi: the ray is exhausted).
+template <typename Emit>
+__device__ __forceinline__ int32_t march_group(const MarchParams &p, const GridFast &gn, const GridFast &go,
+                                               const float o[3], const float d[3], int32_t &k, int32_t k_hi, int32_t S,
+                                               int gl, Emit emit)
+{
+    const int lane = threadIdx.x & (KN_WAVE - 1);
+    const int gshift = lane & ~(MARCH_G - 1);
+    const uint32_t gmask = (MARCH_G == 32) ? 0xffffffffu : ((1u << MARCH_G) - 1u);
+    // distance covered by one lattice step, and the jump length per skip-field unit, in steps
+    const float dlen = sqrtf(d[0] * d[0] + d[1] * d[1] + d[2] * d[2]);
+    const float inv_step_len = 1.0f / (p.step * dlen);
+    const float jump_a = p.skip_edge_min * inv_step_len;
+    const float jump_b = (p.skip_margin + 1e-6f * (fabsf(o[0]) + fabsf(o[1]) + fabsf(o[2]))) * inv_step_len + 1.0f;
+    const bool use_skip = p.skip_dist != nullptr && isfinite(inv_step_len);
+    int32_t n = 0;
+    while (k < k_hi && n < S) {
+        const int32_t kk = k + gl;
+        bool kept = false;
+        int32_t cell = -1;
+        int32_t reach = 0; // all lattice indices in [kk, reach) are known not to be kept
+        if (kk < k_hi) {
+            float x, y, z;
+            kn_lattice_point(o[0], o[1], o[2], d[0], d[1], d[2], p.t_near, p.step, kk, x, y, z);
+            int32_t dist = 0;
+            if (use_skip) {
+                const float cx = floorf((x - p.occ.bmin[0]) * p.skip_inv[0]);
+                const float cy = floorf((y - p.occ.bmin[1]) * p.skip_inv[1]);
+                const float cz = floorf((z - p.occ.bmin[2]) * p.skip_inv[2]);
+                if (cx >= 0.0f && cx < (float)p.skip_res[0] && cy >= 0.0f && cy < (float)p.skip_res[1] && cz >= 0.0f &&
+                    cz < (float)p.skip_res[2])
+                    dist = p.skip_dist[((int32_t)cx * p.skip_res[1] + (int32_t)cy) * p.skip_res[2] + (int32_t)cz];
+            }
+            if (dist >= 2) {
+                // Blocks within Chebyshev distance dist-1 of this point's block are empty, hence so is every
+                // point within Euclidean distance (dist-1) * edge (minus a rounding margin) of it.
+                const float nj = floorf((float)(dist - 1) * jump_a - jump_b);
+                reach = kk + 1 + (int32_t)fmaxf(nj, 0.0f);
+            } else {
+                kept = sample_kept(p, gn, go, x, y, z, cell);
+                reach = kept ? kk : kk + 1;
+            }
+        }
+        const uint32_t mask = (uint32_t)(__ballot(kept) >> gshift) & gmask;
+        const int rank = __popc(mask & ((1u << gl) - 1u));
+        const int tot = __popc(mask);
+        const int room = S - n;
+        if (kept && rank < room) emit(n + rank, kk, cell);
+        if (tot > room) {
+            // the first kept sample that did not fit is where the next wave resumes
+            const uint32_t over = (uint32_t)(__ballot(kept && rank == room) >> gshift) & gmask;
+            k = k + (__ffs(over) - 1);
+            n = S;
+            break;
+        }
+        n += tot;
+        // frontier: every index of this chunk was tested or skipped; the farthest jump that starts inside
+        // the chunk extends the known-empty range beyond it
+        int32_t far = reach;
+#pragma unroll
+        for (int off = MARCH_G / 2; off > 0; off >>= 1) far = max(far, __shfl_xor(far, off, KN_WAVE));
+        k = max(k + MARCH_G, far);
+    }
+    return n;
 }
 
 // ---------------------------------------------------------------------------------------------
-// stage kernel behind kn_march: one thread per ray, explicit output arrays
-__global__ void k_march_stage(MarchParams p, const float *__restrict__ rays_o, const float *__restrict__ rays_d, int64_t R,
-                              const int32_t *__restrict__ k_begin, int32_t S, int32_t *__restrict__ out_k,
-                              int32_t *__restrict__ out_count, int32_t *__restrict__ out_k_next)
+// stage kernel behind kn_march: MARCH_G lanes per ray, explicit output arrays
+__global__ void __launch_bounds__(256)
+    k_march_stage(MarchParams p, const float *__restrict__ rays_o, const float *__restrict__ rays_d, int64_t R,
+                  const int32_t *__restrict__ k_begin, int32_t S, int32_t *__restrict__ out_k, int32_t *__restrict__ out_count,
+                  int32_t *__restrict__ out_k_next)
 {
-    const int64_t r = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int64_t r = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) / MARCH_G;
+    const int gl = threadIdx.x & (MARCH_G - 1);
     if (r >= R) return;
     const float o[3] = {rays_o[3 * r], rays_o[3 * r + 1], rays_o[3 * r + 2]};
     const float d[3] = {rays_d[3 * r], rays_d[3 * r + 1], rays_d[3 * r + 2]};
     const GridFast gn = make_fast(p.net), go = make_fast(p.occ);
     int32_t k_lo, k_hi;
     clip_ray(p.net, o, d, p.t_near, p.step, p.K, k_lo, k_hi);
-    int32_t k = k_begin ? max(k_begin[r], 0) : 0;
-    k = max(k, k_lo);
-    int32_t n = 0;
-    for (; k < k_hi && n < S; ++k) {
-        float x, y, z;
-        kn_lattice_point(o[0], o[1], o[2], d[0], d[1], d[2], p.t_near, p.step, k, x, y, z);
-        int32_t cell;
-        if (sample_kept(p, gn, go, x, y, z, cell)) out_k[r * S + n++] = k;
+    int32_t k = max(k_begin ? max(k_begin[r], 0) : 0, k_lo);
+    int32_t *row = out_k + r * S;
+    const int32_t n = march_group(p, gn, go, o, d, k, k_hi, S, gl, [&](int j, int32_t kk, int32_t) { row[j] = kk; });
+    for (int32_t j = n + gl; j < S; j += MARCH_G) row[j] = -1;
+    if (gl == 0) {
+        out_count[r] = n;
+        if (out_k_next) out_k_next[r] = (k >= k_hi) ? p.K : k;
     }
-    // ran out of candidate indices: the ray is exhausted
-    const int32_t k_next = (k >= k_hi) ? p.K : k;
-    for (int32_t j = n; j < S; ++j) out_k[r * S + j] = -1;
-    out_count[r] = n;
-    if (out_k_next) out_k_next[r] = k_next;
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -145,8 +224,10 @@ struct RayState {
     int32_t *k_end;    // R
 };
 
+// clip every ray against the AABB; rays that cannot hit it get the background right away
 __global__ void k_render_init(MarchParams p, const float *__restrict__ rays_o, const float *__restrict__ rays_d, int64_t R,
-                              RayState s, int32_t *__restrict__ live)
+                              RayState s, int32_t *__restrict__ alive, float bg0, float bg1, float bg2,
+                              float *__restrict__ rgb_out)
 {
     const int64_t r = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (r >= R) return;
@@ -158,64 +239,107 @@ __global__ void k_render_init(MarchParams p, const float *__restrict__ rays_o, c
     s.C[3 * r] = s.C[3 * r + 1] = s.C[3 * r + 2] = 0.0f;
     s.k_next[r] = k_lo;
     s.k_end[r] = k_hi;
-    live[r] = (int32_t)r;
+    const bool lives = k_lo < k_hi;
+    alive[r] = lives ? 1 : 0;
+    if (!lives) {
+        rgb_out[3 * r] = bg0;
+        rgb_out[3 * r + 1] = bg1;
+        rgb_out[3 * r + 2] = bg2;
+    }
 }
 
-// one thread per live ray: collect up to S kept samples, write key + record per slot
-__global__ void k_march_wave(MarchParams p, const float *__restrict__ rays_o, const float *__restrict__ rays_d,
-                             const int32_t *__restrict__ live, int32_t n_live, int32_t S, int32_t kbits, int32_t N,
-                             RayState s, int32_t *__restrict__ keys, uint32_t *__restrict__ rec, int32_t *__restrict__ cnt)
+// first live list: ray ids of the rays that survived the clip, in ascending order
+__global__ void k_first_live(const int32_t *__restrict__ alive, const int32_t *__restrict__ pos, int64_t R,
+                             int32_t *__restrict__ live_out, int32_t *__restrict__ alive_out)
 {
-    const int32_t i = blockIdx.x * blockDim.x + threadIdx.x;
+    const int64_t r = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (r < R && alive[r]) {
+        live_out[pos[r]] = (int32_t)r;
+        alive_out[pos[r]] = 1;
+    }
+}
+
+// MARCH_G lanes per live ray: collect up to S kept samples into row i of the wave's row buffers
+__global__ void __launch_bounds__(256)
+    k_march_wave(MarchParams p, const float *__restrict__ rays_o, const float *__restrict__ rays_d,
+                 const int32_t *__restrict__ live, const int32_t *__restrict__ alive, int32_t n_live, int32_t S,
+                 int32_t kbits, RayState s, int32_t *__restrict__ row_keys, uint32_t *__restrict__ row_rec,
+                 int32_t *__restrict__ cnt, unsigned long long *__restrict__ counters)
+{
+    const int32_t i = (int32_t)(((int64_t)blockIdx.x * blockDim.x + threadIdx.x) / MARCH_G);
+    const int gl = threadIdx.x & (MARCH_G - 1);
+    if (blockIdx.x == 0 && threadIdx.x == 0) counters[2] = 0ull; // survivors of this wave, counted by the blend kernel
     if (i >= n_live) return;
+    if (!alive[i]) { // retired rows stay in the list until the next compaction
+        if (gl == 0) cnt[i] = 0;
+        return;
+    }
     const int32_t r = live[i];
     const float o[3] = {rays_o[3 * (int64_t)r], rays_o[3 * (int64_t)r + 1], rays_o[3 * (int64_t)r + 2]};
     const float d[3] = {rays_d[3 * (int64_t)r], rays_d[3 * (int64_t)r + 1], rays_d[3 * (int64_t)r + 2]};
     const GridFast gn = make_fast(p.net), go = make_fast(p.occ);
     int32_t k = s.k_next[r];
     const int32_t k_hi = s.k_end[r];
-    int32_t n = 0;
-    for (; k < k_hi && n < S; ++k) {
-        float x, y, z;
-        kn_lattice_point(o[0], o[1], o[2], d[0], d[1], d[2], p.t_near, p.step, k, x, y, z);
-        int32_t cell;
-        if (sample_kept(p, gn, go, x, y, z, cell)) {
-            const int64_t slot = (int64_t)n * n_live + i;
-            keys[slot] = cell;
-            rec[slot] = ((uint32_t)r << kbits) | (uint32_t)k;
-            ++n;
-        }
+    int32_t *kr = row_keys + (int64_t)i * S;
+    uint32_t *rr = row_rec + (int64_t)i * S;
+    const int32_t n = march_group(p, gn, go, o, d, k, k_hi, S, gl, [&](int j, int32_t kk, int32_t cell) {
+        kr[j] = cell;
+        rr[j] = ((uint32_t)r << kbits) | (uint32_t)kk;
+    });
+    if (gl == 0) {
+        s.k_next[r] = k;
+        cnt[i] = n;
     }
-    s.k_next[r] = k;
-    cnt[i] = n;
-    for (int32_t j = n; j < S; ++j) keys[(int64_t)j * n_live + i] = N;
 }
 
-// one thread per live ray: Eq. 2-4 over this wave's samples, early termination, retire finished rays
+// rows -> dense ray-major sample list: sample j of live ray i goes to off[i] + j
+__global__ void k_compact_samples(const int32_t *__restrict__ row_keys, const uint32_t *__restrict__ row_rec,
+                                  const int32_t *__restrict__ cnt, const int32_t *__restrict__ off, int32_t n_live,
+                                  int32_t S, int32_t *__restrict__ keys, uint32_t *__restrict__ rec)
+{
+    const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int64_t i = t / S;
+    const int32_t j = (int32_t)(t - i * S);
+    if (i >= n_live || j >= cnt[i]) return;
+    const int64_t dst = (int64_t)off[i] + j;
+    keys[dst] = row_keys[t];
+    rec[dst] = row_rec[t];
+}
+
+// one thread per live ray: Eq. 2-4 over this wave's samples, early termination, retire finished rays.
+// Samples are fetched eight at a time before they enter the (sequential) recurrence.
 __global__ void k_composite_wave(const int32_t *__restrict__ live, int32_t n_live, const int32_t *__restrict__ cnt,
-                                 const float *__restrict__ sigma, const float *__restrict__ rgb, float step, float eps,
+                                 const int32_t *__restrict__ off, const float *__restrict__ out4, float step, float eps,
                                  float bg0, float bg1, float bg2, RayState s, float *__restrict__ rgb_out,
                                  int32_t *__restrict__ alive, unsigned long long *__restrict__ counters)
 {
+    typedef float f4 __attribute__((ext_vector_type(4)));
     const int32_t i = blockIdx.x * blockDim.x + threadIdx.x;
-    int32_t blended = 0, evaluated = 0;
-    if (i < n_live) {
+    int32_t blended = 0, evaluated = 0, survivors = 0;
+    if (i < n_live && alive[i]) {
         const int32_t r = live[i];
         const int32_t n = cnt[i];
+        const f4 *smp = (const f4 *)out4 + off[i];
         float T = s.T[r];
         float c0 = s.C[3 * (int64_t)r], c1 = s.C[3 * (int64_t)r + 1], c2 = s.C[3 * (int64_t)r + 2];
         bool dead = false;
-        for (int32_t j = 0; j < n; ++j) {
-            const int64_t slot = (int64_t)j * n_live + i;
-            const float sg = sigma[slot];
-            const float alpha = 1.0f - expf(-sg * step);
-            const float wgt = T * alpha;
-            c0 = fmaf(wgt, rgb[3 * slot], c0);
-            c1 = fmaf(wgt, rgb[3 * slot + 1], c1);
-            c2 = fmaf(wgt, rgb[3 * slot + 2], c2);
-            T *= (1.0f - alpha);
-            ++blended;
-            if (eps > 0.0f && T < eps) { dead = true; break; }
+        for (int32_t j0 = 0; j0 < n && !dead; j0 += 8) {
+            f4 v[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) v[u] = (j0 + u < n) ? smp[j0 + u] : (f4){0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                if (j0 + u < n && !dead) {
+                    const float alpha = 1.0f - expf(-v[u][3] * step);
+                    const float wgt = T * alpha;
+                    c0 = fmaf(wgt, v[u][0], c0);
+                    c1 = fmaf(wgt, v[u][1], c1);
+                    c2 = fmaf(wgt, v[u][2], c2);
+                    T *= (1.0f - alpha);
+                    ++blended;
+                    if (eps > 0.0f && T < eps) dead = true;
+                }
+            }
         }
         evaluated = n;
         const bool exhausted = s.k_next[r] >= s.k_end[r];
@@ -225,30 +349,37 @@ __global__ void k_composite_wave(const int32_t *__restrict__ live, int32_t n_liv
             s.C[3 * (int64_t)r] = c0;
             s.C[3 * (int64_t)r + 1] = c1;
             s.C[3 * (int64_t)r + 2] = c2;
+            survivors = 1;
         } else {
             rgb_out[3 * (int64_t)r] = fmaf(T, bg0, c0);
             rgb_out[3 * (int64_t)r + 1] = fmaf(T, bg1, c1);
             rgb_out[3 * (int64_t)r + 2] = fmaf(T, bg2, c2);
+            alive[i] = 0;
         }
-        alive[i] = lives ? 1 : 0;
     }
-    // wave-level sums -> two atomics per wavefront
+    // wave-level sums -> at most three atomics per wavefront
 #pragma unroll
     for (int d = KN_WAVE / 2; d > 0; d >>= 1) {
         blended += __shfl_down(blended, d, KN_WAVE);
         evaluated += __shfl_down(evaluated, d, KN_WAVE);
+        survivors += __shfl_down(survivors, d, KN_WAVE);
     }
-    if ((threadIdx.x & (KN_WAVE - 1)) == 0 && (blended | evaluated)) {
-        atomicAdd(&counters[0], (unsigned long long)evaluated);
-        atomicAdd(&counters[1], (unsigned long long)blended);
+    if ((threadIdx.x & (KN_WAVE - 1)) == 0) {
+        if (evaluated) atomicAdd(&counters[0], (unsigned long long)evaluated);
+        if (blended) atomicAdd(&counters[1], (unsigned long long)blended);
+        if (survivors) atomicAdd(&counters[2], (unsigned long long)survivors);
     }
 }
 
 __global__ void k_compact_live(const int32_t *__restrict__ live_in, const int32_t *__restrict__ alive,
-                               const int32_t *__restrict__ pos, int32_t n_live, int32_t *__restrict__ live_out)
+                               const int32_t *__restrict__ pos, int32_t n_live, int32_t *__restrict__ live_out,
+                               int32_t *__restrict__ alive_out)
 {
     const int32_t i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < n_live && alive[i]) live_out[pos[i]] = live_in[i];
+    if (i < n_live && alive[i]) {
+        live_out[pos[i]] = live_in[i];
+        alive_out[pos[i]] = 1;
+    }
 }
 
 // stage kernel behind kn_composite: explicit per-ray sample ranges
@@ -285,14 +416,25 @@ MarchParams make_params(const kn_scene *sc, float t_near, float step, int32_t K)
     p.occ = sc->has_occ ? sc->occ_grid : sc->net_grid;
     p.occ_bits = sc->occ_bits;
     p.has_occ = sc->has_occ ? 1 : 0;
+    p.skip_dist = sc->has_occ ? sc->skip_dist : nullptr;
+    p.skip_edge_min = INFINITY;
+    float mag = 0.0f;
+    for (int a = 0; a < 3; ++a) {
+        p.skip_res[a] = sc->skip_res[a];
+        const float edge = p.occ.cell[a] * (float)KN_SKIP_BLOCK;
+        p.skip_inv[a] = 1.0f / edge;
+        p.skip_edge_min = fminf(p.skip_edge_min, edge);
+        mag = fmaxf(mag, fabsf(p.occ.bmin[a]) + p.occ.cell[a] * (float)p.occ.res[a]);
+    }
+    p.skip_margin = 1e-3f * p.skip_edge_min + 4e-6f * mag;
     p.t_near = t_near;
     p.step = step;
     p.K = K;
     return p;
 }
 
-int g_first_wave_samples = 8;
-int g_slots_per_ray = 8;
+int g_first_wave_samples = 12;
+int g_slots_per_ray = 12;
 
 bool finite_pos(float v) { return isfinite(v) && v > 0.0f; }
 
@@ -300,8 +442,8 @@ bool finite_pos(float v) { return isfinite(v) && v > 0.0f; }
 
 extern "C" int kn_set_render_params(int32_t first_wave_samples, int32_t slots_per_ray)
 {
-    g_first_wave_samples = first_wave_samples > 0 ? first_wave_samples : 8;
-    g_slots_per_ray = slots_per_ray > 0 ? slots_per_ray : 8;
+    g_first_wave_samples = first_wave_samples > 0 ? first_wave_samples : 12;
+    g_slots_per_ray = slots_per_ray > 0 ? slots_per_ray : 12;
     if (g_slots_per_ray < g_first_wave_samples) g_slots_per_ray = g_first_wave_samples;
     return KN_OK;
 }
@@ -313,11 +455,11 @@ static int kbits_for(int32_t K)
     return b;
 }
 
-// layout of the render workspace; returns total bytes (pointers valid only if ws.ok())
+// layout of the render workspace
 struct RenderWs {
-    int32_t *live_a, *live_b, *cnt, *alive, *pos, *scan_tmp, *n_live_dev, *keys;
-    uint32_t *rec;
-    float *T, *C, *sigma, *rgb;
+    int32_t *live_a, *live_b, *cnt, *off, *alive_a, *alive_b, *pos, *scan_tmp, *n_live_dev, *n_samples_dev, *row_keys, *keys;
+    uint32_t *row_rec, *rec;
+    float *T, *C, *out4;
     int32_t *k_next, *k_end;
     unsigned long long *counters;
 };
@@ -327,19 +469,23 @@ static void carve_render(KnCarver &ws, int64_t R, int64_t slots, RenderWs &w)
     w.live_a = ws.carve<int32_t>(R);
     w.live_b = ws.carve<int32_t>(R);
     w.cnt = ws.carve<int32_t>(R);
-    w.alive = ws.carve<int32_t>(R);
+    w.off = ws.carve<int32_t>(R);
+    w.alive_a = ws.carve<int32_t>(R);
+    w.alive_b = ws.carve<int32_t>(R);
     w.pos = ws.carve<int32_t>(R);
     w.scan_tmp = ws.carve<int32_t>(kn_scan_tmp_len(R));
     w.n_live_dev = ws.carve<int32_t>(1);
+    w.n_samples_dev = ws.carve<int32_t>(1);
     w.T = ws.carve<float>(R);
     w.C = ws.carve<float>(3 * R);
     w.k_next = ws.carve<int32_t>(R);
     w.k_end = ws.carve<int32_t>(R);
-    w.counters = ws.carve<unsigned long long>(2);
+    w.counters = ws.carve<unsigned long long>(4);
+    w.row_keys = ws.carve<int32_t>(slots);
+    w.row_rec = ws.carve<uint32_t>(slots);
     w.keys = ws.carve<int32_t>(slots);
     w.rec = ws.carve<uint32_t>(slots);
-    w.sigma = ws.carve<float>(slots);
-    w.rgb = ws.carve<float>(3 * slots);
+    w.out4 = ws.carve<float>(4 * slots);
 }
 
 int64_t kn_render_ws_bytes(const kn_scene *sc, int64_t R)
@@ -358,8 +504,9 @@ extern "C" int kn_march(const kn_scene *sc, void *stream, const float *rays_o, c
     if (!sc || R < 0 || K < 0 || S < 1 || !isfinite(t_near) || !finite_pos(step)) return KN_E_INVALID_ARG;
     if (R > 0 && (!rays_o || !rays_d || !out_k || !out_count)) return KN_E_INVALID_ARG;
     if (R == 0) return KN_OK;
-    if (kn_div_up(R, 256) > 0x7fffffffLL) return KN_E_UNSUPPORTED;
-    hipLaunchKernelGGL(k_march_stage, dim3((unsigned)kn_div_up(R, 256)), dim3(256), 0, (hipStream_t)stream,
+    const int64_t blocks = kn_div_up(R * MARCH_G, 256);
+    if (blocks > 0x7fffffffLL) return KN_E_UNSUPPORTED;
+    hipLaunchKernelGGL(k_march_stage, dim3((unsigned)blocks), dim3(256), 0, (hipStream_t)stream,
                        make_params(sc, t_near, step, K), rays_o, rays_d, R, k_begin, S, out_k, out_count, out_k_next);
     KN_CHECK_LAUNCH();
     return KN_OK;
@@ -391,7 +538,7 @@ extern "C" int kn_render(const kn_scene *sc, void *stream, const float *rays_o, 
     }
     if (R == 0) return KN_OK;
     const int kbits = kbits_for(K > 1 ? K : 2);
-    if (R > (1ll << (32 - kbits)) || R > 0x7fffffffLL / g_slots_per_ray) return KN_E_UNSUPPORTED;
+    if (R > (1ll << (32 - kbits)) || R > 0x7fffffffLL / g_slots_per_ray / MARCH_G) return KN_E_UNSUPPORTED;
     if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < kn_render_ws_bytes(sc, R)) return KN_E_WORKSPACE;
 
     hipStream_t st = (hipStream_t)stream;
@@ -405,9 +552,21 @@ extern "C" int kn_render(const kn_scene *sc, void *stream, const float *rays_o, 
     const MarchParams p = make_params(sc, t_near, step, K);
     RayState rs{w.T, w.C, w.k_next, w.k_end};
     const unsigned rblocks = (unsigned)kn_div_up(R, 256);
-    hipLaunchKernelGGL(k_render_init, dim3(rblocks), dim3(256), 0, st, p, rays_o, rays_d, R, rs, w.live_a);
+    KnStageTimer tm0(st);
+    tm0.mark();
+    hipLaunchKernelGGL(k_render_init, dim3(rblocks), dim3(256), 0, st, p, rays_o, rays_d, R, rs, w.alive_b, bg[0], bg[1], bg[2],
+                       rgb_out);
     KN_CHECK_LAUNCH();
-    KN_TRY(kn_fill_i32(st, (int32_t *)w.counters, 4, 0));
+    KN_TRY(kn_exclusive_scan_i32(st, w.alive_b, w.pos, R, w.scan_tmp, w.n_live_dev));
+    hipLaunchKernelGGL(k_first_live, dim3(rblocks), dim3(256), 0, st, w.alive_b, w.pos, R, w.live_a, w.alive_a);
+    KN_CHECK_LAUNCH();
+    KN_TRY(kn_fill_i32(st, (int32_t *)w.counters, 8, 0));
+    tm0.mark();
+    int32_t first = 0;
+    KN_HIP(hipMemcpyAsync(&first, w.n_live_dev, sizeof(int32_t), hipMemcpyDeviceToHost, st));
+    KN_HIP(hipStreamSynchronize(st));
+    if (tm0.on) g_kn_profile.ms_march += tm0.elapsed(0);
+    if (first < 0 || first > R) return KN_E_HIP;
 
     KnSampleSrc src{};
     src.points = nullptr;
@@ -418,38 +577,53 @@ extern "C" int kn_render(const kn_scene *sc, void *stream, const float *rays_o, 
     src.t_near = t_near;
     src.step = step;
     src.kbits = kbits;
+    src.out4 = w.out4;
 
     const int tile_len = kn_mlp_tile_len(sc);
-    int32_t *live = w.live_a, *live_next = w.live_b;
-    int64_t n_live = R, waves = 0, slots_total = 0;
-    while (n_live > 0) {
-        int64_t S = budget / n_live;
-        if (S < g_first_wave_samples) S = g_first_wave_samples;
-        if (S > K) S = K;
-        if (S < 1) S = 1;
-        const int64_t Mw = n_live * S;
-        const unsigned lblocks = (unsigned)kn_div_up(n_live, 256);
+    int32_t *live = w.live_a, *live_next = w.live_b, *alive = w.alive_a, *alive_next = w.alive_b;
+    int64_t n_rows = first;  // entries of the live list (some may already be retired)
+    int64_t n_alive = first; // rays still being rendered
+    int64_t waves = 0, slots_total = 0;
+    int64_t S_sched = g_first_wave_samples;
+    while (n_alive > 0) {
         KnStageTimer tm(st);
         tm.mark();
-        hipLaunchKernelGGL(k_march_wave, dim3(lblocks), dim3(256), 0, st, p, rays_o, rays_d, live, (int32_t)n_live, (int32_t)S,
-                           kbits, sc->N, rs, w.keys, w.rec, w.cnt);
+        if (n_alive * 2 < n_rows) { // drop retired rows once they are the majority
+            KN_TRY(kn_exclusive_scan_i32(st, alive, w.pos, n_rows, w.scan_tmp, nullptr));
+            hipLaunchKernelGGL(k_compact_live, dim3((unsigned)kn_div_up(n_rows, 256)), dim3(256), 0, st, live, alive, w.pos,
+                               (int32_t)n_rows, live_next, alive_next);
+            KN_CHECK_LAUNCH();
+            int32_t *t = live; live = live_next; live_next = t;
+            t = alive; alive = alive_next; alive_next = t;
+            n_rows = n_alive;
+        }
+        // samples per ray in this wave: triples from wave to wave, bounded by the slot budget
+        int64_t S = S_sched;
+        if (S > budget / n_rows) S = budget / n_rows;
+        if (S > K) S = K;
+        if (S < 1) S = 1;
+        const int64_t Mw = n_rows * S; // upper bound of this wave's sample count
+        const unsigned lblocks = (unsigned)kn_div_up(n_rows, 256);
+        hipLaunchKernelGGL(k_march_wave, dim3((unsigned)kn_div_up(n_rows * MARCH_G, 256)), dim3(256), 0, st, p, rays_o, rays_d,
+                           live, alive, (int32_t)n_rows, (int32_t)S, kbits, rs, w.row_keys, w.row_rec, w.cnt, w.counters);
+        KN_CHECK_LAUNCH();
+        KN_TRY(kn_exclusive_scan_i32(st, w.cnt, w.off, n_rows, w.scan_tmp, w.n_samples_dev));
+        hipLaunchKernelGGL(k_compact_samples, dim3((unsigned)kn_div_up(Mw, 256)), dim3(256), 0, st, w.row_keys, w.row_rec, w.cnt,
+                           w.off, (int32_t)n_rows, (int32_t)S, w.keys, w.rec);
         KN_CHECK_LAUNCH();
         tm.mark();
         KnCarver bws((char *)workspace + bucket_base, workspace_bytes - bucket_base);
         KnBucketOut bo;
-        KN_TRY(kn_bucket_run(st, w.keys, Mw, sc->N, tile_len, nullptr, nullptr, nullptr, bws, &bo));
+        KN_TRY(kn_bucket_run(st, w.keys, Mw, w.n_samples_dev, sc->N, tile_len, nullptr, nullptr, nullptr, bws, &bo));
         tm.mark();
-        KN_TRY(kn_mlp_launch(sc, st, src, bo, Mw, w.sigma, w.rgb));
+        KN_TRY(kn_mlp_launch(sc, st, src, bo, Mw, nullptr, nullptr));
         tm.mark();
-        hipLaunchKernelGGL(k_composite_wave, dim3(lblocks), dim3(256), 0, st, live, (int32_t)n_live, w.cnt, w.sigma, w.rgb, step,
-                           term_eps, bg[0], bg[1], bg[2], rs, rgb_out, w.alive, w.counters);
-        KN_CHECK_LAUNCH();
-        KN_TRY(kn_exclusive_scan_i32(st, w.alive, w.pos, n_live, w.scan_tmp, w.n_live_dev));
-        hipLaunchKernelGGL(k_compact_live, dim3(lblocks), dim3(256), 0, st, live, w.alive, w.pos, (int32_t)n_live, live_next);
+        hipLaunchKernelGGL(k_composite_wave, dim3(lblocks), dim3(256), 0, st, live, (int32_t)n_rows, w.cnt, w.off, w.out4, step,
+                           term_eps, bg[0], bg[1], bg[2], rs, rgb_out, alive, w.counters);
         KN_CHECK_LAUNCH();
         tm.mark();
-        int32_t next = 0;
-        KN_HIP(hipMemcpyAsync(&next, w.n_live_dev, sizeof(int32_t), hipMemcpyDeviceToHost, st));
+        unsigned long long next = 0;
+        KN_HIP(hipMemcpyAsync(&next, w.counters + 2, sizeof(next), hipMemcpyDeviceToHost, st));
         KN_HIP(hipStreamSynchronize(st));
         if (tm.on) {
             g_kn_profile.ms_march += tm.elapsed(0);
@@ -457,13 +631,12 @@ extern "C" int kn_render(const kn_scene *sc, void *stream, const float *rays_o, 
             g_kn_profile.ms_mlp += tm.elapsed(2);
             g_kn_profile.ms_blend += tm.elapsed(3);
             g_kn_profile.mlp_launches += 1;
-            g_kn_profile.bucket_keys += Mw;
         }
-        if (next < 0 || next > n_live) return KN_E_HIP; // cannot happen; guards the loop
+        if ((int64_t)next > n_alive) return KN_E_HIP; // cannot happen; guards the loop
         ++waves;
         slots_total += Mw;
-        n_live = next;
-        int32_t *t = live; live = live_next; live_next = t;
+        n_alive = (int64_t)next;
+        if (S_sched < K) S_sched *= 3;
     }
     if (g_kn_profile_on || stats) {
         unsigned long long c[2];
@@ -471,6 +644,7 @@ extern "C" int kn_render(const kn_scene *sc, void *stream, const float *rays_o, 
         KN_HIP(hipStreamSynchronize(st));
         if (g_kn_profile_on) {
             g_kn_profile.mlp_samples += (int64_t)c[0];
+            g_kn_profile.bucket_keys += (int64_t)c[0];
             g_kn_profile.calls += 1;
         }
         if (stats) {
