@@ -126,14 +126,14 @@ __global__ void __launch_bounds__(SCAN_THREADS) k_scan_apply(const int32_t *__re
 // ---------------------------------------------------------------------------------------------
 // radix pass, step 1: digit histogram of each 4096-key block -> table[digit * n_blocks + block].
 // With `grp` given, the block also adds its counts to per-digit sums over groups of GRP_BLOCKS
-// blocks and to per-digit totals (integer atomics: the sums do not depend on arrival order), from
-// which the scatter kernel derives its own base offsets without a separate scan of the table.
+// blocks (integer atomics: the sums do not depend on arrival order), from which the scatter kernel
+// derives its own base offsets without a separate scan of the table.  Counters that many blocks
+// hit share few cache lines, and same-line atomics serialise, so nothing finer is accumulated.
 constexpr int GRP_BLOCKS = 32;
 __global__ void __launch_bounds__(RS_THREADS) k_radix_hist(const int32_t *__restrict__ keys, int64_t M_bound,
                                                            const int32_t *__restrict__ M_dev, int shift,
                                                            int32_t n_blocks, int32_t *__restrict__ table,
-                                                           int32_t *__restrict__ grp, int32_t n_grp,
-                                                           int32_t *__restrict__ tot)
+                                                           int32_t *__restrict__ grp, int32_t n_grp)
 {
     __shared__ int32_t hist[256];
     const int64_t M = real_count(M_bound, M_dev);
@@ -141,18 +141,19 @@ __global__ void __launch_bounds__(RS_THREADS) k_radix_hist(const int32_t *__rest
     if (grp && base >= M) return; // nobody reads this block's table column in that mode
     hist[threadIdx.x] = 0;
     __syncthreads();
-#pragma unroll 4
+    int32_t kv[RS_ROWS];
+#pragma unroll
     for (int r = 0; r < RS_ROWS; ++r) {
-        int64_t i = base + (int64_t)r * RS_THREADS + threadIdx.x;
-        if (i < M) atomicAdd(&hist[((uint32_t)keys[i] >> shift) & 255u], 1);
+        const int64_t i = base + (int64_t)r * RS_THREADS + threadIdx.x;
+        kv[r] = (i < M) ? keys[i] : -1;
     }
+#pragma unroll
+    for (int r = 0; r < RS_ROWS; ++r)
+        if (kv[r] >= 0) atomicAdd(&hist[((uint32_t)kv[r] >> shift) & 255u], 1);
     __syncthreads();
     const int32_t h = hist[threadIdx.x];
     table[(int64_t)threadIdx.x * n_blocks + blockIdx.x] = h;
-    if (grp && h) {
-        atomicAdd(&grp[(int64_t)threadIdx.x * n_grp + blockIdx.x / GRP_BLOCKS], h);
-        atomicAdd(&tot[threadIdx.x], h);
-    }
+    if (grp && h) atomicAdd(&grp[(int64_t)threadIdx.x * n_grp + blockIdx.x / GRP_BLOCKS], h);
 }
 
 // radix pass, step 3: stable scatter.  Wavefront w of block b owns keys
@@ -162,7 +163,7 @@ __global__ void __launch_bounds__(RS_THREADS)
                     int32_t *__restrict__ keys_out, int32_t *__restrict__ vals_out, int64_t M_bound,
                     const int32_t *__restrict__ M_dev, int shift, int32_t n_blocks,
                     const int32_t *__restrict__ table /*scanned if grp == nullptr, raw counts otherwise*/,
-                    const int32_t *__restrict__ grp, int32_t n_grp, const int32_t *__restrict__ tot)
+                    const int32_t *__restrict__ grp, int32_t n_grp)
 {
     __shared__ int32_t cnt[RS_WAVES][256];
     __shared__ int32_t scan_lds[8];
@@ -171,17 +172,65 @@ __global__ void __launch_bounds__(RS_THREADS)
     const int lane = threadIdx.x & (KN_WAVE - 1), w = threadIdx.x / KN_WAVE;
 #pragma unroll
     for (int i = 0; i < RS_WAVES; ++i) cnt[i][threadIdx.x] = 0;
+    // thread d: global position of this block's first key with digit d (loads issued before the ranking
+    // loop so that their latency overlaps with it)
+    int32_t digit_base;
+    {
+        const int d = threadIdx.x;
+        if (grp) {
+            // keys with smaller digits + same digit in earlier groups + same digit earlier in my group
+            const int g = blockIdx.x / GRP_BLOCKS;
+            const int g_used = (int)((M + (int64_t)RS_TILE * GRP_BLOCKS - 1) / ((int64_t)RS_TILE * GRP_BLOCKS));
+            int32_t total = 0, before = 0;
+            // fixed-size batches of independent loads: a loop with a data-dependent trip count would pay one
+            // memory round trip per element
+            const int32_t *gp = grp + (int64_t)d * n_grp;
+            for (int g0 = 0; g0 < g_used; g0 += 16) {
+                int32_t v[16];
+#pragma unroll
+                for (int u = 0; u < 16; ++u) v[u] = gp[min(g0 + u, n_grp - 1)]; // unconditional loads batch up
+#pragma unroll
+                for (int u = 0; u < 16; ++u) v[u] = (g0 + u < g_used) ? v[u] : 0;
+#pragma unroll
+                for (int u = 0; u < 16; ++u) {
+                    total += v[u];
+                    if (g0 + u < g) before += v[u];
+                }
+            }
+            {
+                const int32_t *tp = table + (int64_t)d * n_blocks + g * GRP_BLOCKS;
+                const int in_grp = (int)blockIdx.x - g * GRP_BLOCKS;
+                int32_t v[GRP_BLOCKS];
+#pragma unroll
+                for (int u = 0; u < GRP_BLOCKS; ++u) v[u] = tp[min(u, max(in_grp - 1, 0))];
+#pragma unroll
+                for (int u = 0; u < GRP_BLOCKS; ++u) v[u] = (u < in_grp) ? v[u] : 0;
+#pragma unroll
+                for (int u = 0; u < GRP_BLOCKS; ++u) before += v[u];
+            }
+            int32_t all;
+            digit_base = block_exclusive_scan(total, scan_lds, all) + before;
+        } else {
+            digit_base = table[(int64_t)d * n_blocks + blockIdx.x];
+        }
+    }
     __syncthreads();
 
     const int64_t wbase = (int64_t)blockIdx.x * RS_TILE + (int64_t)w * (RS_ROWS * KN_WAVE);
     const uint64_t lt_mask = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
-    int32_t key[RS_ROWS], rank[RS_ROWS];
+    int32_t key[RS_ROWS], rank[RS_ROWS], val[RS_ROWS];
 
+    // all loads first: the ranking loop below contains scheduling barriers that loads cannot cross
+#pragma unroll
+    for (int r = 0; r < RS_ROWS; ++r) {
+        const int64_t i = min(wbase + r * KN_WAVE + lane, M - 1);
+        key[r] = keys_in[i];
+        val[r] = vals_in ? vals_in[i] : (int32_t)i;
+    }
 #pragma unroll
     for (int r = 0; r < RS_ROWS; ++r) {
         const int64_t i = wbase + r * KN_WAVE + lane;
         const bool valid = i < M;
-        key[r] = valid ? keys_in[i] : 0;
         const uint32_t d = ((uint32_t)key[r] >> shift) & 255u;
         uint64_t peers = __ballot(valid);
 #pragma unroll
@@ -201,19 +250,9 @@ __global__ void __launch_bounds__(RS_THREADS)
     }
     __syncthreads();
     {
-        // thread d: turn per-wave digit counts into global base positions
+        // thread d: per-wave digit counts -> global positions of each wave's first key with digit d
         const int d = threadIdx.x;
-        int32_t run;
-        if (grp) {
-            // keys with smaller digits + same digit in earlier groups + same digit earlier in my group
-            int32_t all;
-            run = block_exclusive_scan(tot[d], scan_lds, all);
-            const int g = blockIdx.x / GRP_BLOCKS;
-            for (int gg = 0; gg < g; ++gg) run += grp[(int64_t)d * n_grp + gg];
-            for (int bb = g * GRP_BLOCKS; bb < (int)blockIdx.x; ++bb) run += table[(int64_t)d * n_blocks + bb];
-        } else {
-            run = table[(int64_t)d * n_blocks + blockIdx.x];
-        }
+        int32_t run = digit_base;
 #pragma unroll
         for (int i = 0; i < RS_WAVES; ++i) {
             int32_t c = cnt[i][d];
@@ -229,118 +268,97 @@ __global__ void __launch_bounds__(RS_THREADS)
             const uint32_t d = ((uint32_t)key[r] >> shift) & 255u;
             const int32_t dst = cnt[w][d] + rank[r];
             if (keys_out) keys_out[dst] = key[r];
-            vals_out[dst] = vals_in ? vals_in[i] : (int32_t)i;
+            vals_out[dst] = val[r];
         }
     }
 }
 
 // ---------------------------------------------------------------------------------------------
-// zero the atomic tables and preset the bucket starts to "undefined"
-__global__ void k_bucket_init(int32_t *__restrict__ zeros, int64_t n_zeros, int32_t *__restrict__ start, int64_t n_start)
-{
-    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < n_zeros) zeros[i] = 0;
-    if (i < n_start) start[i] = -1;
-}
-
-// start[key] = first position of `key` in the sorted list (start[] pre-filled with -1)
-__global__ void k_find_starts(const int32_t *__restrict__ sorted_keys, int64_t M_bound, const int32_t *__restrict__ M_dev,
-                              int32_t *__restrict__ start)
+// offsets[n] = first position of bucket n in the sorted list, for all n in [0, N+1] (offsets[N+1] = M).
+// Each boundary of the sorted keys defines the offsets of every bucket between the two keys (empty
+// buckets included), so each entry is written exactly once; runs of empty buckets are filled by
+// the whole wavefront together.
+__global__ void __launch_bounds__(256)
+    k_bucket_offsets(const int32_t *__restrict__ sorted_keys, int64_t M_bound, const int32_t *__restrict__ M_dev, int32_t N,
+                     int32_t *__restrict__ offsets, int32_t *__restrict__ user_offsets)
 {
     const int64_t M = real_count(M_bound, M_dev);
-    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= M) return;
-    int32_t k = sorted_keys[i];
-    if (i == 0 || sorted_keys[i - 1] != k) start[k] = (int32_t)i;
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int lane = threadIdx.x & (KN_WAVE - 1);
+    if (M == 0) {
+        if (blockIdx.x == 0)
+            for (int32_t n = threadIdx.x; n <= N + 1; n += blockDim.x) {
+                offsets[n] = 0;
+                if (user_offsets) user_offsets[n] = 0;
+            }
+        return;
+    }
+    if ((int64_t)blockIdx.x * blockDim.x >= M) return;
+    const bool valid = i < M;
+    const int32_t k = valid ? sorted_keys[i] : 0;
+    const int32_t prev = (!valid || i == 0) ? -1 : sorted_keys[i - 1];
+    const bool boundary = valid && k != prev;
+    if (boundary) {
+        offsets[k] = (int32_t)i;
+        if (user_offsets) user_offsets[k] = (int32_t)i;
+    }
+    // empty buckets prev+1 .. k-1 take the same offset; after the last key everything up to N+1 takes M
+    const bool last = valid && i == M - 1;
+    unsigned long long gaps = __ballot(boundary && k - prev > 1);
+    while (gaps) {
+        const int src = __ffsll((long long)gaps) - 1;
+        gaps &= gaps - 1;
+        const int32_t lo = __shfl(prev, src, KN_WAVE) + 1, hi = __shfl(k, src, KN_WAVE);
+        const int32_t val = (int32_t)__shfl((int)i, src, KN_WAVE);
+        for (int32_t n = lo + lane; n < hi; n += KN_WAVE) {
+            offsets[n] = val;
+            if (user_offsets) user_offsets[n] = val;
+        }
+    }
+    const unsigned long long tail = __ballot(last);
+    if (tail) {
+        const int src = __ffsll((long long)tail) - 1;
+        const int32_t lo = __shfl(k, src, KN_WAVE) + 1;
+        for (int32_t n = lo + lane; n <= N + 1; n += KN_WAVE) {
+            offsets[n] = (int32_t)M;
+            if (user_offsets) user_offsets[n] = (int32_t)M;
+        }
+    }
 }
 
-// One block: resolve empty buckets (start = next non-empty start), then counts, offsets, tiles.
-// STAGED: the N+1 bucket starts are held in LDS (dynamic, (N+1) ints) instead of global memory.
-constexpr int FIN_THREADS = 1024;
-constexpr int FIN_MAX_STAGED = 12288;
-template <bool STAGED>
-__global__ void __launch_bounds__(FIN_THREADS)
-    k_finalize_buckets(int32_t *__restrict__ start /*N+1, in: first position or -1; out (unstaged): offsets*/, int32_t N,
-                       int32_t M_bound, const int32_t *__restrict__ M_dev, int32_t tile_len,
-                       int32_t *__restrict__ counts /*N+1*/, int32_t *__restrict__ offsets /*N+2*/,
-                       KnTile *__restrict__ tiles, int32_t *__restrict__ n_tiles, int32_t *__restrict__ user_counts,
-                       int32_t *__restrict__ user_offsets)
+// counts and the tile list of the grouped MLP, one thread per bucket.  Tile slots are handed out
+// with one atomic per wavefront (the order of tiles is free; nothing observable depends on it).
+__global__ void __launch_bounds__(256)
+    k_bucket_tiles(const int32_t *__restrict__ offsets, int32_t N, int32_t tile_len, int32_t *__restrict__ counts,
+                   int32_t *__restrict__ user_counts, KnTile *__restrict__ tiles, int32_t *__restrict__ n_tiles)
 {
-    extern __shared__ int32_t staged[];
-    __shared__ int32_t sa[FIN_THREADS];
-    __shared__ int32_t sb[FIN_THREADS];
-    const int32_t M = (int32_t)real_count(M_bound, M_dev);
-    const int t = threadIdx.x;
-    const int n_entries = N + 1;
-    const int per = (n_entries + FIN_THREADS - 1) / FIN_THREADS;
-    const int lo = min(t * per, n_entries), hi = min(lo + per, n_entries);
-    int32_t *st = STAGED ? staged : start;
-    if (STAGED) {
-        for (int e = t; e < n_entries; e += FIN_THREADS) staged[e] = start[e];
-        __syncthreads();
+    const int32_t n = blockIdx.x * blockDim.x + threadIdx.x;
+    const int lane = threadIdx.x & (KN_WAVE - 1);
+    int32_t a = 0, c = 0;
+    if (n <= N) {
+        a = offsets[n];
+        c = offsets[n + 1] - a;
+        counts[n] = c;
+        if (user_counts) user_counts[n] = c;
     }
-    // first defined start inside my chunk; starts of non-empty buckets increase with the key, so
-    // "next defined start to the right" is a suffix minimum
-    int32_t first = 0x7fffffff;
-    for (int i = lo; i < hi; ++i) {
-        int32_t s = st[i];
-        if (s >= 0) { first = s; break; }
+    const int32_t mine = (n < N) ? (c + tile_len - 1) / tile_len : 0; // bucket N (outside / unused) gets none
+    int32_t inc = mine;
+#pragma unroll
+    for (int d = 1; d < KN_WAVE; d <<= 1) {
+        const int32_t o = __shfl_up(inc, d, KN_WAVE);
+        if (lane >= d) inc += o;
     }
-    sa[t] = first;
-    __syncthreads();
-    for (int d = 1; d < FIN_THREADS; d <<= 1) {
-        int32_t o = (t + d < FIN_THREADS) ? sa[t + d] : 0x7fffffff;
-        __syncthreads();
-        sa[t] = min(sa[t], o);
-        __syncthreads();
-    }
-    int32_t nxt = (t + 1 < FIN_THREADS) ? sa[t + 1] : 0x7fffffff;
-    if (nxt == 0x7fffffff) nxt = M;
-    for (int i = hi - 1; i >= lo; --i) { // resolve right-to-left inside the chunk
-        int32_t s = st[i];
-        if (s >= 0) nxt = s; else st[i] = nxt;
-    }
-    __syncthreads();
-    // counts and offsets (entry-parallel), number of tiles of my chunk (bucket N = outside gets none)
-    for (int e = t; e < n_entries; e += FIN_THREADS) {
-        const int32_t a = st[e];
-        const int32_t b = (e + 1 < n_entries) ? st[e + 1] : M;
-        counts[e] = b - a;
-        offsets[e] = a;
-        if (user_counts) user_counts[e] = b - a;
-        if (user_offsets) user_offsets[e] = a;
-    }
-    if (t == 0) {
-        offsets[n_entries] = M;
-        if (user_offsets) user_offsets[n_entries] = M;
-    }
-    int32_t my_tiles = 0;
-    for (int i = lo; i < hi && i < N; ++i) {
-        const int32_t a = st[i];
-        const int32_t b = (i + 1 < n_entries) ? st[i + 1] : M;
-        my_tiles += (b - a + tile_len - 1) / tile_len;
-    }
-    sb[t] = my_tiles;
-    __syncthreads();
-    for (int d = 1; d < FIN_THREADS; d <<= 1) { // inclusive prefix sum
-        int32_t o = (t >= d) ? sb[t - d] : 0;
-        __syncthreads();
-        sb[t] += o;
-        __syncthreads();
-    }
-    int32_t tbase = sb[t] - my_tiles;
-    if (t == FIN_THREADS - 1) *n_tiles = sb[t];
-    for (int i = lo; i < hi && i < N; ++i) {
-        const int32_t a = st[i];
-        const int32_t b = (i + 1 < n_entries) ? st[i + 1] : M;
-        for (int32_t s = a; s < b; s += tile_len) {
-            KnTile tl;
-            tl.net = i;
-            tl.start = s;
-            tl.len = min(tile_len, b - s);
-            tl.pad = 0;
-            tiles[tbase++] = tl;
-        }
+    const int32_t wave_total = __shfl(inc, KN_WAVE - 1, KN_WAVE);
+    int32_t base = 0;
+    if (lane == 0 && wave_total > 0) base = atomicAdd(n_tiles, wave_total);
+    base = __shfl(base, 0, KN_WAVE) + inc - mine;
+    for (int32_t t = 0; t < mine; ++t) {
+        KnTile tl;
+        tl.net = n;
+        tl.start = a + t * tile_len;
+        tl.len = min(tile_len, c - t * tile_len);
+        tl.pad = 0;
+        tiles[base + t] = tl;
     }
 }
 
@@ -397,7 +415,7 @@ int64_t kn_max_tiles(int64_t M, int32_t N, int32_t tile_len)
 constexpr int64_t SELF_BASE_MAX_BLOCKS = 8192; // beyond this the (digit, block) table is scanned instead
 
 struct BucketWs {
-    int32_t *keys_a, *keys_b, *vals_a, *vals_b, *table, *table_s, *scan_tmp, *atomics, *start, *counts, *offsets, *n_tiles;
+    int32_t *keys_a, *keys_b, *vals_a, *vals_b, *table, *table_s, *scan_tmp, *atomics, *counts, *offsets, *n_tiles;
     KnTile *tiles;
     int64_t nblk, n_grp, n_atomics;
 };
@@ -406,7 +424,7 @@ static void carve_bucket(KnCarver &c, int64_t M, int32_t N, BucketWs &w)
 {
     w.nblk = kn_div_up(M > 0 ? M : 1, RS_TILE);
     w.n_grp = kn_div_up(w.nblk, GRP_BLOCKS);
-    w.n_atomics = 4 * (256 * w.n_grp + 256); // group sums + totals, for up to 4 passes
+    w.n_atomics = 4 * 256 * w.n_grp + 1; // per-digit group sums for up to 4 passes, then the tile counter
     w.keys_a = c.carve<int32_t>(M);
     w.keys_b = c.carve<int32_t>(M);
     w.vals_a = c.carve<int32_t>(M);
@@ -415,11 +433,10 @@ static void carve_bucket(KnCarver &c, int64_t M, int32_t N, BucketWs &w)
     w.table_s = c.carve<int32_t>(256 * w.nblk);
     w.scan_tmp = c.carve<int32_t>(kn_scan_tmp_len(256 * w.nblk));
     w.atomics = c.carve<int32_t>(w.n_atomics);
-    w.start = c.carve<int32_t>(N + 1);
     w.counts = c.carve<int32_t>(N + 1);
     w.offsets = c.carve<int32_t>(N + 2);
     w.tiles = c.carve<KnTile>(kn_max_tiles(M, N, 64));
-    w.n_tiles = c.carve<int32_t>(1);
+    w.n_tiles = w.atomics ? w.atomics + 4 * 256 * w.n_grp : nullptr;
 }
 
 int64_t kn_bucket_ws_bytes(int64_t M, int32_t N)
@@ -445,23 +462,16 @@ int kn_bucket_run(hipStream_t st, int32_t *keys, int64_t M, const int32_t *M_dev
     const int32_t *vin = nullptr;
     int32_t *sorted_keys = w.keys_b;
     int32_t *perm = w.vals_b;
-    {
-        const int64_t n_init = w.n_atomics > N + 1 ? w.n_atomics : N + 1;
-        dim3 grid;
-        KN_TRY(launch_1d(n_init, 256, grid));
-        hipLaunchKernelGGL(k_bucket_init, grid, dim3(256), 0, st, w.atomics, w.n_atomics, w.start, (int64_t)N + 1);
-        KN_CHECK_LAUNCH();
-    }
+    KN_TRY(kn_fill_i32(st, w.atomics, w.n_atomics, 0));
     if (M > 0) {
         for (int p = 0; p < passes; ++p) {
             const bool last = (p == passes - 1);
             int32_t *kout = (p & 1) ? w.keys_a : w.keys_b;
             int32_t *vout = (p & 1) ? w.vals_a : w.vals_b;
             if (last && user_perm) vout = user_perm;
-            int32_t *grp = self_base ? w.atomics + p * (256 * w.n_grp + 256) : nullptr;
-            int32_t *tot = self_base ? grp + 256 * w.n_grp : nullptr;
+            int32_t *grp = self_base ? w.atomics + p * 256 * w.n_grp : nullptr;
             hipLaunchKernelGGL(k_radix_hist, dim3((unsigned)nblk), dim3(RS_THREADS), 0, st, kin, M, M_dev, 8 * p, (int32_t)nblk,
-                               w.table, grp, (int32_t)w.n_grp, tot);
+                               w.table, grp, (int32_t)w.n_grp);
             KN_CHECK_LAUNCH();
             const int32_t *tbl = w.table;
             if (!self_base) {
@@ -469,25 +479,23 @@ int kn_bucket_run(hipStream_t st, int32_t *keys, int64_t M, const int32_t *M_dev
                 tbl = w.table_s;
             }
             hipLaunchKernelGGL(k_radix_scatter, dim3((unsigned)nblk), dim3(RS_THREADS), 0, st, kin, vin, kout, vout, M, M_dev,
-                               8 * p, (int32_t)nblk, tbl, grp, (int32_t)w.n_grp, tot);
+                               8 * p, (int32_t)nblk, tbl, grp, (int32_t)w.n_grp);
             KN_CHECK_LAUNCH();
             kin = kout;
             vin = vout;
             sorted_keys = kout;
             perm = vout;
         }
+    }
+    {
         dim3 grid;
-        KN_TRY(launch_1d(M, 256, grid));
-        hipLaunchKernelGGL(k_find_starts, grid, dim3(256), 0, st, sorted_keys, M, M_dev, w.start);
+        KN_TRY(launch_1d(M > 0 ? M : 1, 256, grid));
+        hipLaunchKernelGGL(k_bucket_offsets, grid, dim3(256), 0, st, sorted_keys, M, M_dev, N, w.offsets, user_offsets);
+        KN_CHECK_LAUNCH();
+        hipLaunchKernelGGL(k_bucket_tiles, dim3((unsigned)kn_div_up(N + 1, 256)), dim3(256), 0, st, w.offsets, N, tile_len,
+                           w.counts, user_counts, w.tiles, w.n_tiles);
         KN_CHECK_LAUNCH();
     }
-    if (N + 1 <= FIN_MAX_STAGED)
-        hipLaunchKernelGGL(k_finalize_buckets<true>, dim3(1), dim3(FIN_THREADS), (size_t)(N + 1) * sizeof(int32_t), st, w.start,
-                           N, (int32_t)M, M_dev, tile_len, w.counts, w.offsets, w.tiles, w.n_tiles, user_counts, user_offsets);
-    else
-        hipLaunchKernelGGL(k_finalize_buckets<false>, dim3(1), dim3(FIN_THREADS), 0, st, w.start, N, (int32_t)M, M_dev, tile_len,
-                           w.counts, w.offsets, w.tiles, w.n_tiles, user_counts, user_offsets);
-    KN_CHECK_LAUNCH();
     out->perm = perm;
     out->counts = w.counts;
     out->offsets = w.offsets;

@@ -121,6 +121,58 @@ __device__ __forceinline__ bool sample_kept(const MarchParams &p, const GridFast
     return cell >= 0;
 }
 
+// Jump length bookkeeping shared by the two users of the skip field.  A point whose block has
+// Chebyshev distance dist >= 2 to the nearest occupied block lies in an empty block, and so does
+// every point within Euclidean distance (dist-1) * (shortest block edge) of it, minus a rounding
+// margin: jump(dist) is how many further lattice indices that covers.
+struct SkipJump {
+    float a, b;
+    bool use;
+    __device__ __forceinline__ SkipJump(const MarchParams &p, const float o[3], const float d[3])
+    {
+        const float dlen = sqrtf(d[0] * d[0] + d[1] * d[1] + d[2] * d[2]);
+        const float inv_step_len = 1.0f / (p.step * dlen); // 1 / distance covered by one lattice step
+        a = p.skip_edge_min * inv_step_len;
+        b = (p.skip_margin + 1e-6f * (fabsf(o[0]) + fabsf(o[1]) + fabsf(o[2]))) * inv_step_len + 1.0f;
+        use = p.skip_dist != nullptr && isfinite(inv_step_len);
+    }
+    __device__ __forceinline__ int32_t jump(int32_t dist) const { return (int32_t)fmaxf(floorf((float)(dist - 1) * a - b), 0.0f); }
+};
+
+// skip-field value at a point; -1 = the point is (up to rounding) outside the field
+__device__ __forceinline__ int32_t skip_lookup(const MarchParams &p, float x, float y, float z)
+{
+    const float cx = floorf((x - p.occ.bmin[0]) * p.skip_inv[0]);
+    const float cy = floorf((y - p.occ.bmin[1]) * p.skip_inv[1]);
+    const float cz = floorf((z - p.occ.bmin[2]) * p.skip_inv[2]);
+    if (cx >= 0.0f && cx < (float)p.skip_res[0] && cy >= 0.0f && cy < (float)p.skip_res[1] && cz >= 0.0f &&
+        cz < (float)p.skip_res[2])
+        return p.skip_dist[((int32_t)cx * p.skip_res[1] + (int32_t)cy) * p.skip_res[2] + (int32_t)cz];
+    return -1;
+}
+
+// One thread walks a ray through provably empty space: returns the first index in [k, k_hi) whose
+// point is not known to be empty (or k_hi).  No index it passes over can be a kept sample.
+__device__ __forceinline__ int32_t skip_to_content(const MarchParams &p, const GridFast &go, const float o[3],
+                                                   const float d[3], int32_t k, int32_t k_hi)
+{
+    const SkipJump sj(p, o, d);
+    if (!sj.use) return k;
+    while (k < k_hi) {
+        float x, y, z;
+        kn_lattice_point(o[0], o[1], o[2], d[0], d[1], d[2], p.t_near, p.step, k, x, y, z);
+        const int32_t dist = skip_lookup(p, x, y, z);
+        if (dist >= 2) {
+            k += 1 + sj.jump(dist);
+        } else if (dist < 0 && grid_index_fast(go, x, y, z) < 0) {
+            k += 1; // exactly outside the AABB (the clip range starts a little before the box)
+        } else {
+            break;
+        }
+    }
+    return min(k, k_hi);
+}
+
 // Cooperative march of one ray by a group of MARCH_G lanes (all lanes of the group call this with
 // the same arguments; gl = lane index inside the group).  Collects up to S kept lattice indices in
 // [k, k_hi), in ascending order, through emit(j, kk, cell).  Returns the number collected and
@@ -133,12 +185,7 @@ __device__ __forceinline__ int32_t march_group(const MarchParams &p, const GridF
     const int lane = threadIdx.x & (KN_WAVE - 1);
     const int gshift = lane & ~(MARCH_G - 1);
     const uint32_t gmask = (MARCH_G == 32) ? 0xffffffffu : ((1u << MARCH_G) - 1u);
-    // distance covered by one lattice step, and the jump length per skip-field unit, in steps
-    const float dlen = sqrtf(d[0] * d[0] + d[1] * d[1] + d[2] * d[2]);
-    const float inv_step_len = 1.0f / (p.step * dlen);
-    const float jump_a = p.skip_edge_min * inv_step_len;
-    const float jump_b = (p.skip_margin + 1e-6f * (fabsf(o[0]) + fabsf(o[1]) + fabsf(o[2]))) * inv_step_len + 1.0f;
-    const bool use_skip = p.skip_dist != nullptr && isfinite(inv_step_len);
+    const SkipJump sj(p, o, d);
     int32_t n = 0;
     while (k < k_hi && n < S) {
         const int32_t kk = k + gl;
@@ -148,20 +195,9 @@ __device__ __forceinline__ int32_t march_group(const MarchParams &p, const GridF
         if (kk < k_hi) {
             float x, y, z;
             kn_lattice_point(o[0], o[1], o[2], d[0], d[1], d[2], p.t_near, p.step, kk, x, y, z);
-            int32_t dist = 0;
-            if (use_skip) {
-                const float cx = floorf((x - p.occ.bmin[0]) * p.skip_inv[0]);
-                const float cy = floorf((y - p.occ.bmin[1]) * p.skip_inv[1]);
-                const float cz = floorf((z - p.occ.bmin[2]) * p.skip_inv[2]);
-                if (cx >= 0.0f && cx < (float)p.skip_res[0] && cy >= 0.0f && cy < (float)p.skip_res[1] && cz >= 0.0f &&
-                    cz < (float)p.skip_res[2])
-                    dist = p.skip_dist[((int32_t)cx * p.skip_res[1] + (int32_t)cy) * p.skip_res[2] + (int32_t)cz];
-            }
+            const int32_t dist = sj.use ? skip_lookup(p, x, y, z) : 0; // < 2 (incl. outside): exact test
             if (dist >= 2) {
-                // Blocks within Chebyshev distance dist-1 of this point's block are empty, hence so is every
-                // point within Euclidean distance (dist-1) * edge (minus a rounding margin) of it.
-                const float nj = floorf((float)(dist - 1) * jump_a - jump_b);
-                reach = kk + 1 + (int32_t)fmaxf(nj, 0.0f);
+                reach = kk + 1 + sj.jump(dist);
             } else {
                 kept = sample_kept(p, gn, go, x, y, z, cell);
                 reach = kept ? kk : kk + 1;
@@ -235,6 +271,8 @@ __global__ void k_render_init(MarchParams p, const float *__restrict__ rays_o, c
     const float d[3] = {rays_d[3 * r], rays_d[3 * r + 1], rays_d[3 * r + 2]};
     int32_t k_lo, k_hi;
     clip_ray(p.net, o, d, p.t_near, p.step, p.K, k_lo, k_hi);
+    // walk through provably empty space up to the first lattice point that is near occupied blocks
+    k_lo = skip_to_content(p, make_fast(p.occ), o, d, k_lo, k_hi);
     s.T[r] = 1.0f;
     s.C[3 * r] = s.C[3 * r + 1] = s.C[3 * r + 2] = 0.0f;
     s.k_next[r] = k_lo;
@@ -264,11 +302,10 @@ __global__ void __launch_bounds__(256)
     k_march_wave(MarchParams p, const float *__restrict__ rays_o, const float *__restrict__ rays_d,
                  const int32_t *__restrict__ live, const int32_t *__restrict__ alive, int32_t n_live, int32_t S,
                  int32_t kbits, RayState s, int32_t *__restrict__ row_keys, uint32_t *__restrict__ row_rec,
-                 int32_t *__restrict__ cnt, unsigned long long *__restrict__ counters)
+                 int32_t *__restrict__ cnt)
 {
     const int32_t i = (int32_t)(((int64_t)blockIdx.x * blockDim.x + threadIdx.x) / MARCH_G);
     const int gl = threadIdx.x & (MARCH_G - 1);
-    if (blockIdx.x == 0 && threadIdx.x == 0) counters[2] = 0ull; // survivors of this wave, counted by the blend kernel
     if (i >= n_live) return;
     if (!alive[i]) { // retired rows stay in the list until the next compaction
         if (gl == 0) cnt[i] = 0;
@@ -306,15 +343,21 @@ __global__ void k_compact_samples(const int32_t *__restrict__ row_keys, const ui
     rec[dst] = row_rec[t];
 }
 
-// one thread per live ray: Eq. 2-4 over this wave's samples, early termination, retire finished rays.
-// Samples are fetched eight at a time before they enter the (sequential) recurrence.
-__global__ void k_composite_wave(const int32_t *__restrict__ live, int32_t n_live, const int32_t *__restrict__ cnt,
-                                 const int32_t *__restrict__ off, const float *__restrict__ out4, float step, float eps,
-                                 float bg0, float bg1, float bg2, RayState s, float *__restrict__ rgb_out,
-                                 int32_t *__restrict__ alive, unsigned long long *__restrict__ counters)
+// MARCH_G lanes per live ray: Eq. 2-4 over this wave's samples, early termination, retire finished
+// rays.  The lanes fetch 16 consecutive samples and turn densities into alphas in parallel; the
+// blend itself is the sequential recurrence of the definition (same operation order for every
+// wave cut), run redundantly by all lanes of the group on values broadcast through LDS.
+__global__ void __launch_bounds__(256)
+    k_composite_wave(const int32_t *__restrict__ live, int32_t n_live, const int32_t *__restrict__ cnt,
+                     const int32_t *__restrict__ off, const float *__restrict__ out4, float step, float eps, float bg0,
+                     float bg1, float bg2, RayState s, float *__restrict__ rgb_out, int32_t *__restrict__ alive,
+                     int32_t *__restrict__ partials /*3 * gridDim.x*/)
 {
     typedef float f4 __attribute__((ext_vector_type(4)));
-    const int32_t i = blockIdx.x * blockDim.x + threadIdx.x;
+    __shared__ f4 stage[256];
+    const int32_t i = (int32_t)(((int64_t)blockIdx.x * blockDim.x + threadIdx.x) / MARCH_G);
+    const int gl = threadIdx.x & (MARCH_G - 1);
+    f4 *grp_stage = stage + (threadIdx.x & ~(MARCH_G - 1));
     int32_t blended = 0, evaluated = 0, survivors = 0;
     if (i < n_live && alive[i]) {
         const int32_t r = live[i];
@@ -323,41 +366,49 @@ __global__ void k_composite_wave(const int32_t *__restrict__ live, int32_t n_liv
         float T = s.T[r];
         float c0 = s.C[3 * (int64_t)r], c1 = s.C[3 * (int64_t)r + 1], c2 = s.C[3 * (int64_t)r + 2];
         bool dead = false;
-        for (int32_t j0 = 0; j0 < n && !dead; j0 += 8) {
-            f4 v[8];
-#pragma unroll
-            for (int u = 0; u < 8; ++u) v[u] = (j0 + u < n) ? smp[j0 + u] : (f4){0.0f, 0.0f, 0.0f, 0.0f};
-#pragma unroll
-            for (int u = 0; u < 8; ++u) {
-                if (j0 + u < n && !dead) {
-                    const float alpha = 1.0f - expf(-v[u][3] * step);
-                    const float wgt = T * alpha;
-                    c0 = fmaf(wgt, v[u][0], c0);
-                    c1 = fmaf(wgt, v[u][1], c1);
-                    c2 = fmaf(wgt, v[u][2], c2);
-                    T *= (1.0f - alpha);
-                    ++blended;
-                    if (eps > 0.0f && T < eps) dead = true;
-                }
+        for (int32_t j0 = 0; j0 < n && !dead; j0 += MARCH_G) {
+            f4 v = (j0 + gl < n) ? smp[j0 + gl] : (f4){0.0f, 0.0f, 0.0f, 0.0f};
+            v[3] = 1.0f - expf(-v[3] * step); // alpha (Eq. 4)
+            __builtin_amdgcn_wave_barrier();
+            grp_stage[gl] = v;
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+            const int m = min(MARCH_G, n - j0);
+            for (int u = 0; u < m; ++u) {
+                const f4 q = grp_stage[u];
+                const float wgt = T * q[3];
+                c0 = fmaf(wgt, q[0], c0);
+                c1 = fmaf(wgt, q[1], c1);
+                c2 = fmaf(wgt, q[2], c2);
+                T *= (1.0f - q[3]);
+                ++blended;
+                if (eps > 0.0f && T < eps) { dead = true; break; }
             }
         }
-        evaluated = n;
         const bool exhausted = s.k_next[r] >= s.k_end[r];
         const bool lives = !dead && !exhausted;
-        if (lives) {
-            s.T[r] = T;
-            s.C[3 * (int64_t)r] = c0;
-            s.C[3 * (int64_t)r + 1] = c1;
-            s.C[3 * (int64_t)r + 2] = c2;
-            survivors = 1;
+        if (gl == 0) {
+            evaluated = n;
+            if (lives) {
+                s.T[r] = T;
+                s.C[3 * (int64_t)r] = c0;
+                s.C[3 * (int64_t)r + 1] = c1;
+                s.C[3 * (int64_t)r + 2] = c2;
+                survivors = 1;
+            } else {
+                rgb_out[3 * (int64_t)r] = fmaf(T, bg0, c0);
+                rgb_out[3 * (int64_t)r + 1] = fmaf(T, bg1, c1);
+                rgb_out[3 * (int64_t)r + 2] = fmaf(T, bg2, c2);
+                alive[i] = 0;
+            }
         } else {
-            rgb_out[3 * (int64_t)r] = fmaf(T, bg0, c0);
-            rgb_out[3 * (int64_t)r + 1] = fmaf(T, bg1, c1);
-            rgb_out[3 * (int64_t)r + 2] = fmaf(T, bg2, c2);
-            alive[i] = 0;
+            blended = 0;
         }
     }
-    // wave-level sums -> at most three atomics per wavefront
+    // block-level sums -> one plain store per block and counter (same-address atomics from tens of
+    // thousands of wavefronts would serialise); k_sum_partials adds them up afterwards
+    __shared__ int32_t red[3][256 / KN_WAVE];
 #pragma unroll
     for (int d = KN_WAVE / 2; d > 0; d >>= 1) {
         blended += __shfl_down(blended, d, KN_WAVE);
@@ -365,9 +416,53 @@ __global__ void k_composite_wave(const int32_t *__restrict__ live, int32_t n_liv
         survivors += __shfl_down(survivors, d, KN_WAVE);
     }
     if ((threadIdx.x & (KN_WAVE - 1)) == 0) {
-        if (evaluated) atomicAdd(&counters[0], (unsigned long long)evaluated);
-        if (blended) atomicAdd(&counters[1], (unsigned long long)blended);
-        if (survivors) atomicAdd(&counters[2], (unsigned long long)survivors);
+        red[0][threadIdx.x / KN_WAVE] = evaluated;
+        red[1][threadIdx.x / KN_WAVE] = blended;
+        red[2][threadIdx.x / KN_WAVE] = survivors;
+    }
+    __syncthreads();
+    if (threadIdx.x < 3) {
+        int32_t v = 0;
+#pragma unroll
+        for (int w = 0; w < 256 / KN_WAVE; ++w) v += red[threadIdx.x][w];
+        partials[(int64_t)threadIdx.x * gridDim.x + blockIdx.x] = v;
+    }
+}
+
+// one block: counters[0] += evaluated, counters[1] += blended, counters[2] = survivors of this wave
+__global__ void __launch_bounds__(256) k_sum_partials(const int32_t *__restrict__ partials, int32_t n_blocks,
+                                                      unsigned long long *__restrict__ counters)
+{
+    __shared__ unsigned long long red[3][256 / KN_WAVE];
+    unsigned long long v[3] = {0ull, 0ull, 0ull};
+    for (int32_t b0 = 0; b0 < n_blocks; b0 += 256 * 8) { // batches of independent loads
+        int32_t t[3][8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int32_t b = b0 + u * 256 + threadIdx.x;
+#pragma unroll
+            for (int c = 0; c < 3; ++c) { // unconditional (clamped) loads batch up
+                const int32_t q = partials[(int64_t)c * n_blocks + min(b, n_blocks - 1)];
+                t[c][u] = (b < n_blocks) ? q : 0;
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u)
+#pragma unroll
+            for (int c = 0; c < 3; ++c) v[c] += (unsigned long long)t[c][u];
+    }
+#pragma unroll
+    for (int c = 0; c < 3; ++c) {
+#pragma unroll
+        for (int d = KN_WAVE / 2; d > 0; d >>= 1) v[c] += __shfl_down(v[c], d, KN_WAVE);
+        if ((threadIdx.x & (KN_WAVE - 1)) == 0) red[c][threadIdx.x / KN_WAVE] = v[c];
+    }
+    __syncthreads();
+    if (threadIdx.x < 3) {
+        unsigned long long t = 0ull;
+#pragma unroll
+        for (int w = 0; w < 256 / KN_WAVE; ++w) t += red[threadIdx.x][w];
+        if (threadIdx.x == 2) counters[2] = t; else counters[threadIdx.x] += t;
     }
 }
 
@@ -457,7 +552,7 @@ static int kbits_for(int32_t K)
 
 // layout of the render workspace
 struct RenderWs {
-    int32_t *live_a, *live_b, *cnt, *off, *alive_a, *alive_b, *pos, *scan_tmp, *n_live_dev, *n_samples_dev, *row_keys, *keys;
+    int32_t *partials, *live_a, *live_b, *cnt, *off, *alive_a, *alive_b, *pos, *scan_tmp, *n_live_dev, *n_samples_dev, *row_keys, *keys;
     uint32_t *row_rec, *rec;
     float *T, *C, *out4;
     int32_t *k_next, *k_end;
@@ -466,6 +561,7 @@ struct RenderWs {
 
 static void carve_render(KnCarver &ws, int64_t R, int64_t slots, RenderWs &w)
 {
+    w.partials = ws.carve<int32_t>(3 * kn_div_up(R * MARCH_G, 256));
     w.live_a = ws.carve<int32_t>(R);
     w.live_b = ws.carve<int32_t>(R);
     w.cnt = ws.carve<int32_t>(R);
@@ -603,9 +699,8 @@ extern "C" int kn_render(const kn_scene *sc, void *stream, const float *rays_o, 
         if (S > K) S = K;
         if (S < 1) S = 1;
         const int64_t Mw = n_rows * S; // upper bound of this wave's sample count
-        const unsigned lblocks = (unsigned)kn_div_up(n_rows, 256);
         hipLaunchKernelGGL(k_march_wave, dim3((unsigned)kn_div_up(n_rows * MARCH_G, 256)), dim3(256), 0, st, p, rays_o, rays_d,
-                           live, alive, (int32_t)n_rows, (int32_t)S, kbits, rs, w.row_keys, w.row_rec, w.cnt, w.counters);
+                           live, alive, (int32_t)n_rows, (int32_t)S, kbits, rs, w.row_keys, w.row_rec, w.cnt);
         KN_CHECK_LAUNCH();
         KN_TRY(kn_exclusive_scan_i32(st, w.cnt, w.off, n_rows, w.scan_tmp, w.n_samples_dev));
         hipLaunchKernelGGL(k_compact_samples, dim3((unsigned)kn_div_up(Mw, 256)), dim3(256), 0, st, w.row_keys, w.row_rec, w.cnt,
@@ -618,8 +713,11 @@ extern "C" int kn_render(const kn_scene *sc, void *stream, const float *rays_o, 
         tm.mark();
         KN_TRY(kn_mlp_launch(sc, st, src, bo, Mw, nullptr, nullptr));
         tm.mark();
-        hipLaunchKernelGGL(k_composite_wave, dim3(lblocks), dim3(256), 0, st, live, (int32_t)n_rows, w.cnt, w.off, w.out4, step,
-                           term_eps, bg[0], bg[1], bg[2], rs, rgb_out, alive, w.counters);
+        hipLaunchKernelGGL(k_composite_wave, dim3((unsigned)kn_div_up(n_rows * MARCH_G, 256)), dim3(256), 0, st, live, (int32_t)n_rows, w.cnt, w.off, w.out4, step,
+                           term_eps, bg[0], bg[1], bg[2], rs, rgb_out, alive, w.partials);
+        KN_CHECK_LAUNCH();
+        hipLaunchKernelGGL(k_sum_partials, dim3(1), dim3(256), 0, st, w.partials, (int32_t)kn_div_up(n_rows * MARCH_G, 256),
+                           w.counters);
         KN_CHECK_LAUNCH();
         tm.mark();
         unsigned long long next = 0;
