@@ -62,7 +62,7 @@ typedef struct {
 
 typedef struct kn_scene kn_scene; /* opaque */
 
-/* Counters of one kn_render call (filled when requested; forces a stream synchronise). */
+/* Counters of one kn_render call (filled when requested). */
 typedef struct {
     int64_t rays;             /* R                                                             */
     int64_t waves;            /* passes of the march -> bucket -> MLP -> blend loop            */
@@ -142,7 +142,9 @@ int kn_composite(void *stream, const float *sigma /*dev*/, const float *rgb /*de
  * waves from near to far; rays whose transmittance fell below term_eps, or that ran out of
  * lattice points, drop out between waves.  The result per ray equals the sequential definition
  * (march, evaluate, blend, stop at T < term_eps) regardless of how waves are cut.
- * R*2^ceil(log2 K) must be <= 2^32.  The call synchronises `stream` between waves. */
+ * R*2^ceil(log2 K) must be <= 2^32.  The call waits (on the host) for each wave's live-ray count before it
+ * enqueues the next wave; when it returns, the last wave has been enqueued but `stream` may still be running.
+ * Calls on the same scene must not overlap. */
 int kn_render(const kn_scene *scene, void *stream, const float *rays_o /*dev R*3*/,
               const float *rays_d /*dev R*3, unit*/, int64_t R, float t_near, float step,
               int32_t K /*max lattice points per ray*/, float term_eps /*0 = off*/,
@@ -155,9 +157,9 @@ int kn_render(const kn_scene *scene, void *stream, const float *rays_o /*dev R*3
 int kn_set_render_params(int32_t first_wave_samples, int32_t slots_per_ray);
 
 /* Per-stage device time of kn_render / kn_eval_grouped, measured with HIP events recorded on the
- * caller's stream around each stage (process-wide switch, off by default).  While enabled,
- * kn_eval_grouped also synchronises the stream before returning.  kn_profile_read copies the
- * totals accumulated since the last reset. */
+ * caller's stream around each stage (process-wide switch, off by default).  Recording does not
+ * synchronise; kn_profile_read synchronises the recorded stream, settles all pending intervals and
+ * copies the totals accumulated since the last reset. */
 typedef struct {
     double ms_cell;        /* point -> cell id (kn_eval_grouped only; fused into marching in kn_render) */
     double ms_march;       /* marching + empty-space skipping                                          */

@@ -17,26 +17,61 @@ int kn_mlp_mfma_tile_len(const kn_scene *sc);
 
 kn_profile g_kn_profile = {};
 bool g_kn_profile_on = false;
-static hipEvent_t g_events[8];
+// Event ring shared by all calls: intervals are settled (one stream synchronise, then
+// hipEventElapsedTime for each recorded interval) only when the ring is full, when another stream
+// starts recording, or when the totals are read.
+constexpr int KN_N_EVENTS = 1024;
+static hipEvent_t g_events[KN_N_EVENTS];
+static int g_event_stage[KN_N_EVENTS];
+static int g_n_events = 0;
+static hipStream_t g_event_stream = nullptr;
 static bool g_events_ready = false;
 
-KnStageTimer::KnStageTimer(hipStream_t s) : st(s), on(g_kn_profile_on), n(0)
+static int settle_events()
+{
+    if (g_n_events >= 2) {
+        KN_HIP(hipStreamSynchronize(g_event_stream));
+        for (int i = 1; i < g_n_events; ++i) {
+            float ms = 0.0f;
+            if (g_event_stage[i] == KN_ST_NONE || hipEventElapsedTime(&ms, g_events[i - 1], g_events[i]) != hipSuccess)
+                continue;
+            switch (g_event_stage[i]) {
+            case KN_ST_CELL: g_kn_profile.ms_cell += ms; break;
+            case KN_ST_MARCH: g_kn_profile.ms_march += ms; break;
+            case KN_ST_BUCKET: g_kn_profile.ms_bucket += ms; break;
+            case KN_ST_MLP: g_kn_profile.ms_mlp += ms; break;
+            case KN_ST_BLEND: g_kn_profile.ms_blend += ms; break;
+            default: break;
+            }
+        }
+    }
+    g_n_events = 0;
+    return KN_OK;
+}
+
+KnStageTimer::KnStageTimer(hipStream_t s) : st(s), on(g_kn_profile_on)
 {
     if (on && !g_events_ready) {
         for (auto &e : g_events)
             if (hipEventCreate(&e) != hipSuccess) on = false;
         g_events_ready = on;
     }
+    if (on && g_n_events > 0 && g_event_stream != s) (void)settle_events();
+    g_event_stream = s;
 }
-void KnStageTimer::mark()
+void KnStageTimer::mark(int stage_id)
 {
-    if (on && n < 8) (void)hipEventRecord(g_events[n++], st);
-}
-float KnStageTimer::elapsed(int i) const
-{
-    float ms = 0.0f;
-    if (on && i + 1 < n) (void)hipEventElapsedTime(&ms, g_events[i], g_events[i + 1]);
-    return ms;
+    if (!on) return;
+    if (g_n_events == KN_N_EVENTS) {
+        (void)settle_events();
+        if (stage_id != KN_ST_NONE) { // re-open the interval that the settle cut short
+            g_event_stage[0] = KN_ST_NONE;
+            (void)hipEventRecord(g_events[0], st);
+            g_n_events = 1;
+        }
+    }
+    g_event_stage[g_n_events] = stage_id;
+    (void)hipEventRecord(g_events[g_n_events++], st);
 }
 
 extern "C" int kn_profile_enable(int on)
@@ -48,6 +83,7 @@ extern "C" int kn_profile_enable(int on)
 extern "C" int kn_profile_read(kn_profile *out, int reset)
 {
     if (!out) return KN_E_INVALID_ARG;
+    KN_TRY(settle_events());
     *out = g_kn_profile;
     if (reset) g_kn_profile = kn_profile{};
     return KN_OK;
@@ -198,6 +234,19 @@ extern "C" int kn_scene_create(const kn_scene_desc *desc, void *stream, kn_scene
     sc->packed_halfs_per_net = 0;
     sc->skip_dist = nullptr;
     sc->skip_res[0] = sc->skip_res[1] = sc->skip_res[2] = 0;
+    sc->mailbox_host = nullptr;
+    sc->mailbox_dev = nullptr;
+    sc->mailbox_seq = 0;
+    {
+        void *hp = nullptr, *dp = nullptr;
+        if (hipHostMalloc(&hp, 64, hipHostMallocMapped) == hipSuccess && hipHostGetDevicePointer(&dp, hp, 0) == hipSuccess) {
+            memset(hp, 0, 64);
+            sc->mailbox_host = (volatile unsigned long long *)hp;
+            sc->mailbox_dev = (unsigned long long *)dp;
+        } else if (hp) {
+            (void)hipHostFree(hp);
+        }
+    }
     hipStream_t st = (hipStream_t)stream;
     int rc = KN_OK;
     if (sc->has_occ) {
@@ -252,6 +301,7 @@ extern "C" int kn_scene_destroy(kn_scene *sc)
     if (sc->occ_bits) (void)hipFree(sc->occ_bits);
     if (sc->packed_w) (void)hipFree(sc->packed_w);
     if (sc->skip_dist) (void)hipFree(sc->skip_dist);
+    if (sc->mailbox_host) (void)hipHostFree((void *)sc->mailbox_host);
     delete sc;
     return KN_OK;
 }
@@ -294,13 +344,13 @@ extern "C" int kn_eval_grouped(const kn_scene *sc, void *stream, const float *po
     int32_t *keys = ws.carve<int32_t>(M);
     if (!ws.ok()) return KN_E_WORKSPACE;
     KnStageTimer tm(st);
-    tm.mark();
+    tm.begin();
     KN_TRY(kn_cell_keys(sc, st, points, M, cell_id, keys));
-    tm.mark();
+    tm.mark(KN_ST_CELL);
     KnBucketOut bo;
     KN_TRY(kn_bucket_run(st, keys, M, nullptr, sc->N, kn_mlp_tile_len(sc), counts, nullptr, perm, ws, &bo));
     if (M == 0) return KN_OK;
-    tm.mark();
+    tm.mark(KN_ST_BUCKET);
     KnSampleSrc src{};
     src.points = points;
     src.dirs = dirs;
@@ -309,12 +359,8 @@ extern "C" int kn_eval_grouped(const kn_scene *sc, void *stream, const float *po
     hipLaunchKernelGGL(k_zero_outside, dim3((unsigned)kn_div_up(M, 256)), dim3(256), 0, st, bo.perm, bo.offsets, sc->N, M, sigma,
                        rgb);
     KN_CHECK_LAUNCH();
-    tm.mark();
+    tm.mark(KN_ST_MLP);
     if (tm.on) {
-        KN_HIP(hipStreamSynchronize(st));
-        g_kn_profile.ms_cell += tm.elapsed(0);
-        g_kn_profile.ms_bucket += tm.elapsed(1);
-        g_kn_profile.ms_mlp += tm.elapsed(2);
         g_kn_profile.mlp_launches += 1;
         g_kn_profile.mlp_samples += M; // includes points outside the AABB (they cost no MLP work)
         g_kn_profile.bucket_keys += M;

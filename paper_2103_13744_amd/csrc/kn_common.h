@@ -42,6 +42,11 @@ struct kn_scene {
     // block, capped at KN_SKIP_MAX).  Lets marching jump over provably empty lattice points.
     uint8_t *skip_dist;    // device, skip_res[0]*[1]*[2] bytes, x slowest; nullptr without occupancy
     int32_t skip_res[3];
+    // Host-visible mailbox (pinned, device-mapped): kn_render's kernels post the live-ray count of a
+    // wave here, {sequence number, value}, and the host polls it instead of draining the stream.
+    volatile unsigned long long *mailbox_host;
+    unsigned long long *mailbox_dev;
+    unsigned long long mailbox_seq;
 };
 #define KN_SKIP_BLOCK 4
 #define KN_SKIP_MAX 32
@@ -149,14 +154,16 @@ int kn_exclusive_scan_i32(hipStream_t st, const int32_t *in, int32_t *out, int64
 int64_t kn_scan_tmp_len(int64_t n);
 
 // Optional per-stage timing with HIP events on the caller's stream (see kn_profile in the header).
+// begin() records a start event, mark(stage) an event that closes an interval charged to `stage`.
+// Elapsed times are read later, in batches (kn_profile_read forces it), so recording does not
+// synchronise the stream.
+enum KnStage { KN_ST_CELL = 0, KN_ST_MARCH, KN_ST_BUCKET, KN_ST_MLP, KN_ST_BLEND, KN_ST_NONE };
 struct KnStageTimer {
     hipStream_t st;
     bool on;
-    int n;
     KnStageTimer(hipStream_t s);
-    void mark();                 // record the next boundary event
-    // after the stream has been synchronised: elapsed ms between boundaries i and i+1
-    float elapsed(int i) const;
+    void begin() { mark(KN_ST_NONE); }
+    void mark(int stage_id);
 };
 extern kn_profile g_kn_profile;
 extern bool g_kn_profile_on;

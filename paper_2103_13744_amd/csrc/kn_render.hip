@@ -13,6 +13,8 @@
 
 #include <math.h>
 
+#include <chrono>
+
 namespace {
 
 constexpr int MARCH_G = 16;
@@ -287,10 +289,20 @@ __global__ void k_render_init(MarchParams p, const float *__restrict__ rays_o, c
 }
 
 // first live list: ray ids of the rays that survived the clip, in ascending order
+// {value, then sequence number} into the host-visible mailbox; the host polls the sequence number
+__device__ __forceinline__ void post_mailbox(unsigned long long *mailbox, unsigned long long seq, unsigned long long value)
+{
+    if (!mailbox) return;
+    __hip_atomic_store(&mailbox[1], value, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+    __hip_atomic_store(&mailbox[0], seq, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
+}
+
 __global__ void k_first_live(const int32_t *__restrict__ alive, const int32_t *__restrict__ pos, int64_t R,
-                             int32_t *__restrict__ live_out, int32_t *__restrict__ alive_out)
+                             int32_t *__restrict__ live_out, int32_t *__restrict__ alive_out,
+                             const int32_t *__restrict__ n_live, unsigned long long *mailbox, unsigned long long seq)
 {
     const int64_t r = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (r == 0) post_mailbox(mailbox, seq, (unsigned long long)*n_live);
     if (r < R && alive[r]) {
         live_out[pos[r]] = (int32_t)r;
         alive_out[pos[r]] = 1;
@@ -431,7 +443,8 @@ __global__ void __launch_bounds__(256)
 
 // one block: counters[0] += evaluated, counters[1] += blended, counters[2] = survivors of this wave
 __global__ void __launch_bounds__(256) k_sum_partials(const int32_t *__restrict__ partials, int32_t n_blocks,
-                                                      unsigned long long *__restrict__ counters)
+                                                      unsigned long long *__restrict__ counters,
+                                                      unsigned long long *mailbox, unsigned long long seq)
 {
     __shared__ unsigned long long red[3][256 / KN_WAVE];
     unsigned long long v[3] = {0ull, 0ull, 0ull};
@@ -463,6 +476,15 @@ __global__ void __launch_bounds__(256) k_sum_partials(const int32_t *__restrict_
 #pragma unroll
         for (int w = 0; w < 256 / KN_WAVE; ++w) t += red[threadIdx.x][w];
         if (threadIdx.x == 2) counters[2] = t; else counters[threadIdx.x] += t;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        // running totals ride along so that the host never has to read the counters back
+        if (mailbox) {
+            __hip_atomic_store(&mailbox[2], counters[0], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+            __hip_atomic_store(&mailbox[3], counters[1], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+        }
+        post_mailbox(mailbox, seq, counters[2]);
     }
 }
 
@@ -540,6 +562,35 @@ extern "C" int kn_set_render_params(int32_t first_wave_samples, int32_t slots_pe
     g_first_wave_samples = first_wave_samples > 0 ? first_wave_samples : 12;
     g_slots_per_ray = slots_per_ray > 0 ? slots_per_ray : 12;
     if (g_slots_per_ray < g_first_wave_samples) g_slots_per_ray = g_first_wave_samples;
+    return KN_OK;
+}
+
+// Wait for the mailbox to show `seq` (spinning on pinned memory is much cheaper than draining the
+// stream); falls back to a stream synchronise + device read when there is no mailbox or it stays silent.
+static int wait_count(const kn_scene *sc, hipStream_t st, unsigned long long seq, const void *dev_value, size_t dev_bytes,
+                      long long *out)
+{
+    if (sc->mailbox_host) {
+        const auto t0 = std::chrono::steady_clock::now();
+        long long spins = 0;
+        while (true) {
+            if (__atomic_load_n((const unsigned long long *)&sc->mailbox_host[0], __ATOMIC_ACQUIRE) == seq) {
+                *out = (long long)__atomic_load_n((const unsigned long long *)&sc->mailbox_host[1], __ATOMIC_RELAXED);
+                return KN_OK;
+            }
+            if ((++spins & 0x3ff) == 0) {
+                if (hipStreamQuery(st) == hipSuccess && // stream drained: the post is there or will never come
+                    __atomic_load_n((const unsigned long long *)&sc->mailbox_host[0], __ATOMIC_ACQUIRE) != seq)
+                    break;
+                if (std::chrono::steady_clock::now() - t0 > std::chrono::seconds(20)) break;
+            }
+        }
+    }
+    unsigned long long v64 = 0;
+    int32_t v32 = 0;
+    KN_HIP(hipMemcpyAsync(dev_bytes == 8 ? (void *)&v64 : (void *)&v32, dev_value, dev_bytes, hipMemcpyDeviceToHost, st));
+    KN_HIP(hipStreamSynchronize(st));
+    *out = dev_bytes == 8 ? (long long)v64 : (long long)v32;
     return KN_OK;
 }
 
@@ -648,20 +699,21 @@ extern "C" int kn_render(const kn_scene *sc, void *stream, const float *rays_o, 
     const MarchParams p = make_params(sc, t_near, step, K);
     RayState rs{w.T, w.C, w.k_next, w.k_end};
     const unsigned rblocks = (unsigned)kn_div_up(R, 256);
-    KnStageTimer tm0(st);
-    tm0.mark();
+    KnStageTimer tm(st);
+    tm.begin();
     hipLaunchKernelGGL(k_render_init, dim3(rblocks), dim3(256), 0, st, p, rays_o, rays_d, R, rs, w.alive_b, bg[0], bg[1], bg[2],
                        rgb_out);
     KN_CHECK_LAUNCH();
     KN_TRY(kn_exclusive_scan_i32(st, w.alive_b, w.pos, R, w.scan_tmp, w.n_live_dev));
-    hipLaunchKernelGGL(k_first_live, dim3(rblocks), dim3(256), 0, st, w.alive_b, w.pos, R, w.live_a, w.alive_a);
-    KN_CHECK_LAUNCH();
+    kn_scene *scm = const_cast<kn_scene *>(sc); // the mailbox sequence number is the only mutable scene state
     KN_TRY(kn_fill_i32(st, (int32_t *)w.counters, 8, 0));
-    tm0.mark();
-    int32_t first = 0;
-    KN_HIP(hipMemcpyAsync(&first, w.n_live_dev, sizeof(int32_t), hipMemcpyDeviceToHost, st));
-    KN_HIP(hipStreamSynchronize(st));
-    if (tm0.on) g_kn_profile.ms_march += tm0.elapsed(0);
+    unsigned long long seq = ++scm->mailbox_seq;
+    hipLaunchKernelGGL(k_first_live, dim3(rblocks), dim3(256), 0, st, w.alive_b, w.pos, R, w.live_a, w.alive_a, w.n_live_dev,
+                       sc->mailbox_dev, seq);
+    KN_CHECK_LAUNCH();
+    tm.mark(KN_ST_MARCH);
+    long long first = 0;
+    KN_TRY(wait_count(sc, st, seq, w.n_live_dev, sizeof(int32_t), &first));
     if (first < 0 || first > R) return KN_E_HIP;
 
     KnSampleSrc src{};
@@ -682,8 +734,7 @@ extern "C" int kn_render(const kn_scene *sc, void *stream, const float *rays_o, 
     int64_t waves = 0, slots_total = 0;
     int64_t S_sched = g_first_wave_samples;
     while (n_alive > 0) {
-        KnStageTimer tm(st);
-        tm.mark();
+        tm.begin();
         if (n_alive * 2 < n_rows) { // drop retired rows once they are the majority
             KN_TRY(kn_exclusive_scan_i32(st, alive, w.pos, n_rows, w.scan_tmp, nullptr));
             hipLaunchKernelGGL(k_compact_live, dim3((unsigned)kn_div_up(n_rows, 256)), dim3(256), 0, st, live, alive, w.pos,
@@ -706,40 +757,39 @@ extern "C" int kn_render(const kn_scene *sc, void *stream, const float *rays_o, 
         hipLaunchKernelGGL(k_compact_samples, dim3((unsigned)kn_div_up(Mw, 256)), dim3(256), 0, st, w.row_keys, w.row_rec, w.cnt,
                            w.off, (int32_t)n_rows, (int32_t)S, w.keys, w.rec);
         KN_CHECK_LAUNCH();
-        tm.mark();
+        tm.mark(KN_ST_MARCH);
         KnCarver bws((char *)workspace + bucket_base, workspace_bytes - bucket_base);
         KnBucketOut bo;
         KN_TRY(kn_bucket_run(st, w.keys, Mw, w.n_samples_dev, sc->N, tile_len, nullptr, nullptr, nullptr, bws, &bo));
-        tm.mark();
+        tm.mark(KN_ST_BUCKET);
         KN_TRY(kn_mlp_launch(sc, st, src, bo, Mw, nullptr, nullptr));
-        tm.mark();
+        tm.mark(KN_ST_MLP);
         hipLaunchKernelGGL(k_composite_wave, dim3((unsigned)kn_div_up(n_rows * MARCH_G, 256)), dim3(256), 0, st, live, (int32_t)n_rows, w.cnt, w.off, w.out4, step,
                            term_eps, bg[0], bg[1], bg[2], rs, rgb_out, alive, w.partials);
         KN_CHECK_LAUNCH();
+        seq = ++scm->mailbox_seq;
         hipLaunchKernelGGL(k_sum_partials, dim3(1), dim3(256), 0, st, w.partials, (int32_t)kn_div_up(n_rows * MARCH_G, 256),
-                           w.counters);
+                           w.counters, sc->mailbox_dev, seq);
         KN_CHECK_LAUNCH();
-        tm.mark();
-        unsigned long long next = 0;
-        KN_HIP(hipMemcpyAsync(&next, w.counters + 2, sizeof(next), hipMemcpyDeviceToHost, st));
-        KN_HIP(hipStreamSynchronize(st));
-        if (tm.on) {
-            g_kn_profile.ms_march += tm.elapsed(0);
-            g_kn_profile.ms_bucket += tm.elapsed(1);
-            g_kn_profile.ms_mlp += tm.elapsed(2);
-            g_kn_profile.ms_blend += tm.elapsed(3);
-            g_kn_profile.mlp_launches += 1;
-        }
-        if ((int64_t)next > n_alive) return KN_E_HIP; // cannot happen; guards the loop
+        tm.mark(KN_ST_BLEND);
+        long long next = 0;
+        KN_TRY(wait_count(sc, st, seq, w.counters + 2, sizeof(unsigned long long), &next));
+        if (tm.on) g_kn_profile.mlp_launches += 1;
+        if (next < 0 || next > n_alive) return KN_E_HIP; // cannot happen; guards the loop
         ++waves;
         slots_total += Mw;
         n_alive = (int64_t)next;
         if (S_sched < K) S_sched *= 3;
     }
     if (g_kn_profile_on || stats) {
-        unsigned long long c[2];
-        KN_HIP(hipMemcpyAsync(c, w.counters, sizeof(c), hipMemcpyDeviceToHost, st));
-        KN_HIP(hipStreamSynchronize(st));
+        unsigned long long c[2] = {0ull, 0ull};
+        if (waves > 0 && sc->mailbox_host && __atomic_load_n((const unsigned long long *)&sc->mailbox_host[0], __ATOMIC_ACQUIRE) == seq) {
+            c[0] = __atomic_load_n((const unsigned long long *)&sc->mailbox_host[2], __ATOMIC_RELAXED);
+            c[1] = __atomic_load_n((const unsigned long long *)&sc->mailbox_host[3], __ATOMIC_RELAXED);
+        } else if (waves > 0) {
+            KN_HIP(hipMemcpyAsync(c, w.counters, sizeof(c), hipMemcpyDeviceToHost, st));
+            KN_HIP(hipStreamSynchronize(st));
+        }
         if (g_kn_profile_on) {
             g_kn_profile.mlp_samples += (int64_t)c[0];
             g_kn_profile.bucket_keys += (int64_t)c[0];
