@@ -42,6 +42,40 @@ def cpu_baseline(cfg_fn, poses, budget_s=12.0):
             "frames_per_sec": frames / t_total}
 
 
+def isolated_mlp(kn, torch, wdtype, iters=10):
+    """cfg2: the grouped-MLP kernel on its own (2^22 uniform points, 16^3 networks), through kn_eval_grouped."""
+    from kn_synth import configs
+    cfg = configs.config2(wdtype=wdtype)
+    sc = cfg["scene"]
+    dt = {"f16": torch.float16, "bf16": torch.bfloat16}[wdtype]
+    scene = kn.Scene(sc["res"], sc["aabb_min"], sc["aabb_max"], sc["hidden"], torch.from_numpy(sc["weights"]).to(dt).cuda())
+    pts, dirs = torch.from_numpy(cfg["points"]).cuda(), torch.from_numpy(cfg["dirs"]).cuda()
+    M = pts.shape[0]
+    out = (torch.empty(M, dtype=torch.float32, device="cuda"), torch.empty((M, 3), dtype=torch.float32, device="cuda"))
+    for _ in range(3):
+        scene.eval_grouped(pts, dirs, out=out)
+    torch.cuda.synchronize()
+    kn.profile_enable(True)
+    kn.profile_read(reset=True)
+    t0 = time.perf_counter()
+    for _ in range(iters):
+        scene.eval_grouped(pts, dirs, out=out)
+    torch.cuda.synchronize()
+    dt_s = time.perf_counter() - t0
+    prof = kn.profile_read(reset=True)
+    kn.profile_enable(False)
+    mlp_ms = prof["ms_mlp"] / iters
+    tflops = FLOP_PER_SAMPLE[sc["hidden"]] * M / (mlp_ms * 1e-3) / 1e12
+    # algorithmic bytes per point of the whole call: x, d read twice (cell ids, MLP) is not credited: 12 + 12 in, 16 out,
+    # key/perm traffic of the bucketing 16
+    return {"workload": "cfg2: 2^22 points, 16^3 networks, %s" % wdtype, "points": M,
+            "ms_eval_grouped": dt_s * 1e3 / iters, "ms_cell_ids": prof["ms_cell"] / iters,
+            "ms_bucket": prof["ms_bucket"] / iters, "ms_mlp_kernel": mlp_ms,
+            "mlp_evals_per_sec": M / (mlp_ms * 1e-3), "mlp_tflops": tflops, "mlp_frac_of_mfma_peak": tflops * 1e12 / PEAK_MFMA_16BIT,
+            "bucket_gbps_algorithmic": 16.0 * M / (prof["ms_bucket"] / iters * 1e-3) / 1e9,
+            "mlp_hbm_gbps_algorithmic": (24.0 + 4.0 + 16.0 + 3.5) * M / (mlp_ms * 1e-3) / 1e9}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -50,6 +84,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--wdtype", default="f16")
     ap.add_argument("--size", type=int, default=800)
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one plain 1 GiB device copy (reference point for FETCH_SIZE / WRITE_SIZE counters)")
     a = ap.parse_args()
     if a.gpus != 1:
         print("bench.py: this build runs on one GPU only (rays would shard across GPUs; see DESIGN.md); use --gpus 1",
@@ -145,6 +181,16 @@ def main():
         "roofline": roofline,
         "roofline_mlp": roof_mlp, "roofline_march": roof_march,
     }
+    if a.calibrate_copy:
+        src_buf = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
+        dst_buf = torch.empty_like(src_buf)
+        dst_buf.copy_(src_buf)
+        torch.cuda.synchronize()
+        del src_buf, dst_buf
+    if a.wdtype in ("f16", "bf16"):
+        del scene
+        torch.cuda.empty_cache()
+        res["isolated_mlp"] = isolated_mlp(kn, torch, a.wdtype)
     if not a.no_cpu_baseline:
         res["cpu_baseline"] = cpu_baseline(cfg_fn, poses)
     print(json.dumps(res))

@@ -13,7 +13,8 @@ OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libkilonerf_hip.so")
 SOURCES = ["kn_api.hip", "kn_bucket.hip", "kn_mlp_f32.hip", "kn_mlp_mfma.hip", "kn_render.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-fPIC", "-std=c++17", "-ffp-contract=off", "-Wall", "-Wno-unused-function",
-         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-I", INCLUDE, "-I", CSRC]
+         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-mllvm", "-amdgpu-mfma-vgpr-form=1",
+         "-I", INCLUDE, "-I", CSRC]
 
 
 def _compile(src: str) -> str:

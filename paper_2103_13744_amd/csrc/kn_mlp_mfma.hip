@@ -35,6 +35,8 @@
 #include "kn_common.h"
 #include "kn_mlp_shared.h"
 
+#include <stdlib.h>
+
 namespace {
 
 typedef _Float16 h8 __attribute__((ext_vector_type(8)));
@@ -255,15 +257,21 @@ __global__ void __launch_bounds__(WAVES *KN_WAVE)
     const float m2 = role3 ? 256.0f * INV_2PI : 4.0f * INV_2PI;
     const float m4 = role3 ? 256.0f * INV_2PI : 16.0f * INV_2PI;
 
+    // inputs of the first 64 samples (software pipeline: the loads for chunk i+1 are issued before the
+    // arithmetic of chunk i, so the perm -> record -> ray chain of dependent loads is hidden)
+    int32_t idx_next = perm[tl.start + min(lane, tl.len - 1)];
+    float nx, ny, nz, ndx, ndy, ndz;
+    kn_load_sample(src, idx_next, nx, ny, nz, ndx, ndy, ndz);
+
     for (int base = 0; base < tl.len; base += KN_WAVE) {
         const int j = base + lane;
         const bool active = j < tl.len;
-        const int32_t idx = perm[tl.start + (active ? j : 0)];
-        {
-            float x, y, z, dx, dy, dz;
-            kn_load_sample(src, idx, x, y, z, dx, dy, dz);
-            stage[wave][0][lane] = (f4){x, y, z, 0.0f};
-            stage[wave][1][lane] = (f4){dx, dy, dz, 0.0f};
+        const int32_t idx = idx_next;
+        stage[wave][0][lane] = (f4){nx, ny, nz, 0.0f};
+        stage[wave][1][lane] = (f4){ndx, ndy, ndz, 0.0f};
+        if (base + KN_WAVE < tl.len) {
+            idx_next = perm[tl.start + min(j + KN_WAVE, tl.len - 1)];
+            kn_load_sample(src, idx_next, nx, ny, nz, ndx, ndy, ndz);
         }
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
@@ -272,7 +280,7 @@ __global__ void __launch_bounds__(WAVES *KN_WAVE)
         f4 out = bias_out;
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
-            if (base + 16 * u < tl.len) {
+            { // all four sample tiles are always computed: straight-line code lets the scheduler interleave them
                 const f4 Pp = stage[wave][0][16 * u + n];
                 const f4 Dd = stage[wave][1][16 * u + n];
                 u4 Bx[2], Bd;
@@ -383,7 +391,16 @@ int launch(const kn_scene *sc, hipStream_t st, const KnSampleSrc &src, const KnB
 
 } // namespace
 
-int kn_mlp_mfma_tile_len(const kn_scene *) { return MLP_TILE_LEN; }
+int kn_mlp_mfma_tile_len(const kn_scene *)
+{
+    static int len = 0;
+    if (!len) { // KN_MLP_TILE: experiment knob (multiple of 64), read once
+        const char *e = getenv("KN_MLP_TILE");
+        const int v = e ? atoi(e) : 0;
+        len = (v >= 64 && v <= 4096 && v % 64 == 0) ? v : MLP_TILE_LEN;
+    }
+    return len;
+}
 
 int kn_mlp_pack_weights(kn_scene *sc, hipStream_t st)
 {
