@@ -7,7 +7,8 @@
 
 thread_local int g_kn_last_hip_error = 0;
 
-int kn_cell_keys(const kn_scene *sc, hipStream_t st, const float *points, int64_t M, int32_t *ids, int32_t *keys);
+int kn_cell_keys(const kn_scene *sc, hipStream_t st, const float *points, int64_t M, int32_t *ids, int32_t *keys,
+                 int32_t *zero, int64_t n_zero);
 int64_t kn_render_ws_bytes(const kn_scene *sc, int64_t R);
 int kn_mlp_f32_launch(const kn_scene *sc, hipStream_t st, const KnSampleSrc &src, const KnBucketOut &b, int64_t max_tiles,
                       float *sigma, float *rgb);
@@ -345,10 +346,13 @@ extern "C" int kn_eval_grouped(const kn_scene *sc, void *stream, const float *po
     if (!ws.ok()) return KN_E_WORKSPACE;
     KnStageTimer tm(st);
     tm.begin();
-    KN_TRY(kn_cell_keys(sc, st, points, M, cell_id, keys));
+    int32_t *scratch = nullptr;
+    int64_t n_scratch = 0;
+    kn_bucket_scratch(ws, M, sc->N, &scratch, &n_scratch);
+    KN_TRY(kn_cell_keys(sc, st, points, M, cell_id, keys, scratch, scratch ? n_scratch : 0));
     tm.mark(KN_ST_CELL);
     KnBucketOut bo;
-    KN_TRY(kn_bucket_run(st, keys, M, nullptr, sc->N, kn_mlp_tile_len(sc), counts, nullptr, perm, ws, &bo));
+    KN_TRY(kn_bucket_run(st, keys, M, nullptr, sc->N, kn_mlp_tile_len(sc), counts, nullptr, perm, ws, &bo, scratch != nullptr));
     if (M == 0) return KN_OK;
     tm.mark(KN_ST_BUCKET);
     KnSampleSrc src{};

@@ -18,7 +18,10 @@ __device__ __forceinline__ int64_t real_count(int64_t m_bound, const int32_t *m_
 }
 
 constexpr int RS_THREADS = 256;
-constexpr int RS_ROWS = 16;                       // 64-element rows per wavefront
+#ifndef KN_RS_ROWS
+#define KN_RS_ROWS 16
+#endif
+constexpr int RS_ROWS = KN_RS_ROWS;               // 64-element rows per wavefront
 constexpr int RS_WAVES = RS_THREADS / KN_WAVE;    // 4
 constexpr int RS_TILE = RS_THREADS * RS_ROWS;     // 4096 keys per block
 constexpr int SCAN_THREADS = 256;
@@ -33,9 +36,10 @@ __global__ void k_fill_i32(int32_t *p, int64_t n, int32_t v)
 }
 
 __global__ void k_cell_ids(const float *__restrict__ pts, int64_t M, KnGrid g, int32_t *__restrict__ ids,
-                           int32_t *__restrict__ keys, int32_t N)
+                           int32_t *__restrict__ keys, int32_t N, int32_t *__restrict__ zero, int64_t n_zero)
 {
     int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n_zero) zero[i] = 0; // scratch counters of the sort that follows
     if (i >= M) return;
     float x = pts[3 * i], y = pts[3 * i + 1], z = pts[3 * i + 2];
     int32_t id = kn_grid_index(g, x, y, z);
@@ -447,8 +451,17 @@ int64_t kn_bucket_ws_bytes(int64_t M, int32_t N)
     return c.used;
 }
 
+void kn_bucket_scratch(KnCarver ws, int64_t M, int32_t N, int32_t **atomics, int64_t *n_atomics)
+{
+    BucketWs w;
+    carve_bucket(ws, M, N, w);
+    *atomics = w.atomics;
+    *n_atomics = w.n_atomics;
+}
+
 int kn_bucket_run(hipStream_t st, int32_t *keys, int64_t M, const int32_t *M_dev, int32_t N, int32_t tile_len,
-                  int32_t *user_counts, int32_t *user_offsets, int32_t *user_perm, KnCarver &ws, KnBucketOut *out)
+                  int32_t *user_counts, int32_t *user_offsets, int32_t *user_perm, KnCarver &ws, KnBucketOut *out,
+                  bool atomics_zeroed)
 {
     if (M < 0 || M > (1ll << 30) || N < 1 || tile_len < 64) return KN_E_INVALID_ARG;
     BucketWs w;
@@ -462,7 +475,7 @@ int kn_bucket_run(hipStream_t st, int32_t *keys, int64_t M, const int32_t *M_dev
     const int32_t *vin = nullptr;
     int32_t *sorted_keys = w.keys_b;
     int32_t *perm = w.vals_b;
-    KN_TRY(kn_fill_i32(st, w.atomics, w.n_atomics, 0));
+    if (!atomics_zeroed) KN_TRY(kn_fill_i32(st, w.atomics, w.n_atomics, 0));
     if (M > 0) {
         for (int p = 0; p < passes; ++p) {
             const bool last = (p == passes - 1);
@@ -513,18 +526,19 @@ extern "C" int kn_cell_ids(const kn_scene *sc, void *stream, const float *points
     dim3 grid;
     KN_TRY(launch_1d(M, 256, grid));
     hipLaunchKernelGGL(k_cell_ids, grid, dim3(256), 0, (hipStream_t)stream, points, M, sc->net_grid, ids,
-                       (int32_t *)nullptr, sc->N);
+                       (int32_t *)nullptr, sc->N, (int32_t *)nullptr, (int64_t)0);
     KN_CHECK_LAUNCH();
     return KN_OK;
 }
 
 // used by kn_eval_grouped: ids (optional) and sort keys in one pass over the points
-int kn_cell_keys(const kn_scene *sc, hipStream_t st, const float *points, int64_t M, int32_t *ids, int32_t *keys)
+int kn_cell_keys(const kn_scene *sc, hipStream_t st, const float *points, int64_t M, int32_t *ids, int32_t *keys,
+                 int32_t *zero, int64_t n_zero)
 {
-    if (M == 0) return KN_OK;
+    if (M == 0 && n_zero == 0) return KN_OK;
     dim3 grid;
-    KN_TRY(launch_1d(M, 256, grid));
-    hipLaunchKernelGGL(k_cell_ids, grid, dim3(256), 0, st, points, M, sc->net_grid, ids, keys, sc->N);
+    KN_TRY(launch_1d(M > n_zero ? M : n_zero, 256, grid));
+    hipLaunchKernelGGL(k_cell_ids, grid, dim3(256), 0, st, points, M, sc->net_grid, ids, keys, sc->N, zero, n_zero);
     KN_CHECK_LAUNCH();
     return KN_OK;
 }

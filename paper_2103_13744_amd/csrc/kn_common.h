@@ -111,6 +111,41 @@ __device__ __forceinline__ void kn_lattice_point(float ox, float oy, float oz, f
     z = fmaf(t, dz, oz);
 }
 
+// Block-wide sum and exclusive prefix sum for blocks of up to 1024 threads (shuffles inside a
+// wavefront, `lds` (16 ints) across wavefronts).  Every thread of the block must call them.
+__device__ __forceinline__ int32_t kn_block_sum(int32_t v, int32_t *lds)
+{
+#pragma unroll
+    for (int d = KN_WAVE / 2; d > 0; d >>= 1) v += __shfl_xor(v, d, KN_WAVE);
+    __syncthreads();
+    if ((threadIdx.x & (KN_WAVE - 1)) == 0) lds[threadIdx.x / KN_WAVE] = v;
+    __syncthreads();
+    int32_t all = 0;
+    for (int w = 0; w < (int)(blockDim.x / KN_WAVE); ++w) all += lds[w];
+    return all;
+}
+__device__ __forceinline__ int32_t kn_block_exclusive_scan(int32_t v, int32_t *lds, int32_t &total)
+{
+    const int lane = threadIdx.x & (KN_WAVE - 1), wv = threadIdx.x / KN_WAVE;
+    int32_t inc = v;
+#pragma unroll
+    for (int d = 1; d < KN_WAVE; d <<= 1) {
+        const int32_t o = __shfl_up(inc, d, KN_WAVE);
+        if (lane >= d) inc += o;
+    }
+    __syncthreads();
+    if (lane == KN_WAVE - 1) lds[wv] = inc;
+    __syncthreads();
+    int32_t before = 0, all = 0;
+    for (int w = 0; w < (int)(blockDim.x / KN_WAVE); ++w) {
+        const int32_t s = lds[w];
+        all += s;
+        if (w < wv) before += s;
+    }
+    total = all;
+    return before + inc - v;
+}
+
 // Stage entry points implemented across the translation units (host functions) -----------------
 int64_t kn_bucket_ws_bytes(int64_t M, int32_t N);
 int64_t kn_max_tiles(int64_t M, int32_t N, int32_t tile_len);
@@ -126,9 +161,13 @@ struct KnBucketOut {
 // Sorts `keys` (values in [0, N], N = outside/unused) stably, fills perm/counts/offsets/tiles in
 // workspace memory (or the user's buffers where given).  keys may be overwritten.  If M_dev is
 // given, M is only an upper bound (grid and workspace sizing) and *M_dev the real count.
+// With atomics_zeroed the caller has already cleared the scratch counters that kn_bucket_scratch reports.
 int kn_bucket_run(hipStream_t st, int32_t *keys, int64_t M, const int32_t *M_dev, int32_t N, int32_t tile_len,
                   int32_t *user_counts, int32_t *user_offsets, int32_t *user_perm, KnCarver &ws,
-                  KnBucketOut *out);
+                  KnBucketOut *out, bool atomics_zeroed = false);
+// The scratch counters (to be zero before the sort) that kn_bucket_run will carve from `ws` when it
+// is called with a carver in this same state, so that a caller's own kernel can clear them.
+void kn_bucket_scratch(KnCarver ws, int64_t M, int32_t N, int32_t **atomics, int64_t *n_atomics);
 
 // Sample source of the grouped MLP kernels: either explicit points/dirs (eval_grouped) or the
 // packed (ray, k) records of a render wave.

@@ -262,33 +262,58 @@ struct RayState {
     int32_t *k_end;    // R
 };
 
-// clip every ray against the AABB; rays that cannot hit it get the background right away
-__global__ void k_render_init(MarchParams p, const float *__restrict__ rays_o, const float *__restrict__ rays_d, int64_t R,
-                              RayState s, int32_t *__restrict__ alive, float bg0, float bg1, float bg2,
-                              float *__restrict__ rgb_out)
+constexpr int RAY_BLOCK = 1024; // threads per block of the two set-up kernels
+
+// Sum over the blocks in front of this one of per-block counts written by the previous kernel
+// (each thread takes a strided share; the loads are independent).
+__device__ __forceinline__ int32_t prefix_of_block_sums(const int32_t *__restrict__ blk_sum, int32_t *lds)
 {
-    const int64_t r = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (r >= R) return;
-    const float o[3] = {rays_o[3 * r], rays_o[3 * r + 1], rays_o[3 * r + 2]};
-    const float d[3] = {rays_d[3 * r], rays_d[3 * r + 1], rays_d[3 * r + 2]};
-    int32_t k_lo, k_hi;
-    clip_ray(p.net, o, d, p.t_near, p.step, p.K, k_lo, k_hi);
-    // walk through provably empty space up to the first lattice point that is near occupied blocks
-    k_lo = skip_to_content(p, make_fast(p.occ), o, d, k_lo, k_hi);
-    s.T[r] = 1.0f;
-    s.C[3 * r] = s.C[3 * r + 1] = s.C[3 * r + 2] = 0.0f;
-    s.k_next[r] = k_lo;
-    s.k_end[r] = k_hi;
-    const bool lives = k_lo < k_hi;
-    alive[r] = lives ? 1 : 0;
-    if (!lives) {
-        rgb_out[3 * r] = bg0;
-        rgb_out[3 * r + 1] = bg1;
-        rgb_out[3 * r + 2] = bg2;
+    int32_t acc = 0;
+    for (int b0 = 0; b0 < (int)blockIdx.x; b0 += RAY_BLOCK * 4) {
+        int32_t v[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) v[u] = blk_sum[min(b0 + u * RAY_BLOCK + (int)threadIdx.x, (int)blockIdx.x)];
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+            if (b0 + u * RAY_BLOCK + (int)threadIdx.x < (int)blockIdx.x) acc += v[u];
     }
+    return kn_block_sum(acc, lds);
 }
 
-// first live list: ray ids of the rays that survived the clip, in ascending order
+// clip every ray against the AABB and walk it to the first lattice point near content; rays that
+// cannot produce a sample get the background right away.  Writes per-block counts of live rays.
+__global__ void __launch_bounds__(RAY_BLOCK)
+    k_render_init(MarchParams p, const float *__restrict__ rays_o, const float *__restrict__ rays_d, int64_t R, RayState s,
+                  int32_t *__restrict__ alive, int32_t *__restrict__ blk_sum, float bg0, float bg1, float bg2,
+                  float *__restrict__ rgb_out, int32_t *__restrict__ zero, int32_t n_zero)
+{
+    __shared__ int32_t lds[RAY_BLOCK / KN_WAVE];
+    const int64_t r = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (r < n_zero) zero[r] = 0; // per-call counters
+    int32_t lives = 0;
+    if (r < R) {
+        const float o[3] = {rays_o[3 * r], rays_o[3 * r + 1], rays_o[3 * r + 2]};
+        const float d[3] = {rays_d[3 * r], rays_d[3 * r + 1], rays_d[3 * r + 2]};
+        int32_t k_lo, k_hi;
+        clip_ray(p.net, o, d, p.t_near, p.step, p.K, k_lo, k_hi);
+        // walk through provably empty space up to the first lattice point that is near occupied blocks
+        k_lo = skip_to_content(p, make_fast(p.occ), o, d, k_lo, k_hi);
+        s.T[r] = 1.0f;
+        s.C[3 * r] = s.C[3 * r + 1] = s.C[3 * r + 2] = 0.0f;
+        s.k_next[r] = k_lo;
+        s.k_end[r] = k_hi;
+        lives = k_lo < k_hi ? 1 : 0;
+        alive[r] = lives;
+        if (!lives) {
+            rgb_out[3 * r] = bg0;
+            rgb_out[3 * r + 1] = bg1;
+            rgb_out[3 * r + 2] = bg2;
+        }
+    }
+    const int32_t total = kn_block_sum(lives, lds);
+    if (threadIdx.x == 0) blk_sum[blockIdx.x] = total;
+}
+
 // {value, then sequence number} into the host-visible mailbox; the host polls the sequence number
 __device__ __forceinline__ void post_mailbox(unsigned long long *mailbox, unsigned long long seq, unsigned long long value)
 {
@@ -297,15 +322,26 @@ __device__ __forceinline__ void post_mailbox(unsigned long long *mailbox, unsign
     __hip_atomic_store(&mailbox[0], seq, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
 }
 
-__global__ void k_first_live(const int32_t *__restrict__ alive, const int32_t *__restrict__ pos, int64_t R,
-                             int32_t *__restrict__ live_out, int32_t *__restrict__ alive_out,
-                             const int32_t *__restrict__ n_live, unsigned long long *mailbox, unsigned long long seq)
+// first live list: ray ids of the rays that survived k_render_init, in ascending order (same blocks
+// as k_render_init; position = live rays in earlier blocks + rank inside the block)
+__global__ void __launch_bounds__(RAY_BLOCK)
+    k_first_live(const int32_t *__restrict__ alive, const int32_t *__restrict__ blk_sum, int64_t R,
+                 int32_t *__restrict__ live_out, int32_t *__restrict__ alive_out, int32_t *__restrict__ n_live,
+                 unsigned long long *mailbox, unsigned long long seq)
 {
+    __shared__ int32_t lds[RAY_BLOCK / KN_WAVE];
     const int64_t r = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (r == 0) post_mailbox(mailbox, seq, (unsigned long long)*n_live);
-    if (r < R && alive[r]) {
-        live_out[pos[r]] = (int32_t)r;
-        alive_out[pos[r]] = 1;
+    const int32_t before = prefix_of_block_sums(blk_sum, lds);
+    const int32_t a = r < R ? alive[r] : 0;
+    int32_t total;
+    const int32_t pos = before + kn_block_exclusive_scan(a, lds, total);
+    if (a) {
+        live_out[pos] = (int32_t)r;
+        alive_out[pos] = 1;
+    }
+    if (blockIdx.x == gridDim.x - 1 && threadIdx.x == 0) {
+        *n_live = before + total;
+        post_mailbox(mailbox, seq, (unsigned long long)(before + total));
     }
 }
 
@@ -344,9 +380,11 @@ __global__ void __launch_bounds__(256)
 // rows -> dense ray-major sample list: sample j of live ray i goes to off[i] + j
 __global__ void k_compact_samples(const int32_t *__restrict__ row_keys, const uint32_t *__restrict__ row_rec,
                                   const int32_t *__restrict__ cnt, const int32_t *__restrict__ off, int32_t n_live,
-                                  int32_t S, int32_t *__restrict__ keys, uint32_t *__restrict__ rec)
+                                  int32_t S, int32_t *__restrict__ keys, uint32_t *__restrict__ rec,
+                                  int32_t *__restrict__ zero, int64_t n_zero)
 {
     const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (t < n_zero) zero[t] = 0; // scratch counters of the sort that follows
     const int64_t i = t / S;
     const int32_t j = (int32_t)(t - i * S);
     if (i >= n_live || j >= cnt[i]) return;
@@ -603,7 +641,7 @@ static int kbits_for(int32_t K)
 
 // layout of the render workspace
 struct RenderWs {
-    int32_t *partials, *live_a, *live_b, *cnt, *off, *alive_a, *alive_b, *pos, *scan_tmp, *n_live_dev, *n_samples_dev, *row_keys, *keys;
+    int32_t *partials, *blk_sum, *live_a, *live_b, *cnt, *off, *alive_a, *alive_b, *pos, *scan_tmp, *n_live_dev, *n_samples_dev, *row_keys, *keys;
     uint32_t *row_rec, *rec;
     float *T, *C, *out4;
     int32_t *k_next, *k_end;
@@ -613,6 +651,7 @@ struct RenderWs {
 static void carve_render(KnCarver &ws, int64_t R, int64_t slots, RenderWs &w)
 {
     w.partials = ws.carve<int32_t>(3 * kn_div_up(R * MARCH_G, 256));
+    w.blk_sum = ws.carve<int32_t>(kn_div_up(R, RAY_BLOCK) + 1);
     w.live_a = ws.carve<int32_t>(R);
     w.live_b = ws.carve<int32_t>(R);
     w.cnt = ws.carve<int32_t>(R);
@@ -698,18 +737,16 @@ extern "C" int kn_render(const kn_scene *sc, void *stream, const float *rays_o, 
 
     const MarchParams p = make_params(sc, t_near, step, K);
     RayState rs{w.T, w.C, w.k_next, w.k_end};
-    const unsigned rblocks = (unsigned)kn_div_up(R, 256);
+    const unsigned rblocks = (unsigned)kn_div_up(R, RAY_BLOCK);
     KnStageTimer tm(st);
     tm.begin();
-    hipLaunchKernelGGL(k_render_init, dim3(rblocks), dim3(256), 0, st, p, rays_o, rays_d, R, rs, w.alive_b, bg[0], bg[1], bg[2],
-                       rgb_out);
-    KN_CHECK_LAUNCH();
-    KN_TRY(kn_exclusive_scan_i32(st, w.alive_b, w.pos, R, w.scan_tmp, w.n_live_dev));
     kn_scene *scm = const_cast<kn_scene *>(sc); // the mailbox sequence number is the only mutable scene state
-    KN_TRY(kn_fill_i32(st, (int32_t *)w.counters, 8, 0));
+    hipLaunchKernelGGL(k_render_init, dim3(rblocks), dim3(RAY_BLOCK), 0, st, p, rays_o, rays_d, R, rs, w.alive_b, w.blk_sum,
+                       bg[0], bg[1], bg[2], rgb_out, (int32_t *)w.counters, 8);
+    KN_CHECK_LAUNCH();
     unsigned long long seq = ++scm->mailbox_seq;
-    hipLaunchKernelGGL(k_first_live, dim3(rblocks), dim3(256), 0, st, w.alive_b, w.pos, R, w.live_a, w.alive_a, w.n_live_dev,
-                       sc->mailbox_dev, seq);
+    hipLaunchKernelGGL(k_first_live, dim3(rblocks), dim3(RAY_BLOCK), 0, st, w.alive_b, w.blk_sum, R, w.live_a, w.alive_a,
+                       w.n_live_dev, sc->mailbox_dev, seq);
     KN_CHECK_LAUNCH();
     tm.mark(KN_ST_MARCH);
     long long first = 0;
@@ -754,22 +791,27 @@ extern "C" int kn_render(const kn_scene *sc, void *stream, const float *rays_o, 
                            live, alive, (int32_t)n_rows, (int32_t)S, kbits, rs, w.row_keys, w.row_rec, w.cnt);
         KN_CHECK_LAUNCH();
         KN_TRY(kn_exclusive_scan_i32(st, w.cnt, w.off, n_rows, w.scan_tmp, w.n_samples_dev));
-        hipLaunchKernelGGL(k_compact_samples, dim3((unsigned)kn_div_up(Mw, 256)), dim3(256), 0, st, w.row_keys, w.row_rec, w.cnt,
-                           w.off, (int32_t)n_rows, (int32_t)S, w.keys, w.rec);
+        KnCarver bws((char *)workspace + bucket_base, workspace_bytes - bucket_base);
+        int32_t *scratch = nullptr;
+        int64_t n_scratch = 0;
+        kn_bucket_scratch(bws, Mw, sc->N, &scratch, &n_scratch);
+        const int64_t cthreads = Mw > n_scratch ? Mw : n_scratch;
+        hipLaunchKernelGGL(k_compact_samples, dim3((unsigned)kn_div_up(cthreads, 256)), dim3(256), 0, st, w.row_keys, w.row_rec,
+                           w.cnt, w.off, (int32_t)n_rows, (int32_t)S, w.keys, w.rec, scratch, scratch ? n_scratch : 0);
         KN_CHECK_LAUNCH();
         tm.mark(KN_ST_MARCH);
-        KnCarver bws((char *)workspace + bucket_base, workspace_bytes - bucket_base);
         KnBucketOut bo;
-        KN_TRY(kn_bucket_run(st, w.keys, Mw, w.n_samples_dev, sc->N, tile_len, nullptr, nullptr, nullptr, bws, &bo));
+        KN_TRY(kn_bucket_run(st, w.keys, Mw, w.n_samples_dev, sc->N, tile_len, nullptr, nullptr, nullptr, bws, &bo,
+                             scratch != nullptr));
         tm.mark(KN_ST_BUCKET);
         KN_TRY(kn_mlp_launch(sc, st, src, bo, Mw, nullptr, nullptr));
         tm.mark(KN_ST_MLP);
-        hipLaunchKernelGGL(k_composite_wave, dim3((unsigned)kn_div_up(n_rows * MARCH_G, 256)), dim3(256), 0, st, live, (int32_t)n_rows, w.cnt, w.off, w.out4, step,
-                           term_eps, bg[0], bg[1], bg[2], rs, rgb_out, alive, w.partials);
+        const int32_t cblocks = (int32_t)kn_div_up(n_rows * MARCH_G, 256);
+        hipLaunchKernelGGL(k_composite_wave, dim3((unsigned)cblocks), dim3(256), 0, st, live, (int32_t)n_rows, w.cnt, w.off,
+                           w.out4, step, term_eps, bg[0], bg[1], bg[2], rs, rgb_out, alive, w.partials);
         KN_CHECK_LAUNCH();
         seq = ++scm->mailbox_seq;
-        hipLaunchKernelGGL(k_sum_partials, dim3(1), dim3(256), 0, st, w.partials, (int32_t)kn_div_up(n_rows * MARCH_G, 256),
-                           w.counters, sc->mailbox_dev, seq);
+        hipLaunchKernelGGL(k_sum_partials, dim3(1), dim3(256), 0, st, w.partials, cblocks, w.counters, sc->mailbox_dev, seq);
         KN_CHECK_LAUNCH();
         tm.mark(KN_ST_BLEND);
         long long next = 0;
