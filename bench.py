@@ -84,6 +84,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--wdtype", default="f16")
     ap.add_argument("--size", type=int, default=800)
+    ap.add_argument("--wave", default="", help="first_wave_samples,slots_per_ray,growth (experiment knob)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (reference point for FETCH_SIZE / WRITE_SIZE counters)")
     a = ap.parse_args()
@@ -100,6 +101,8 @@ def main():
 
     torch.cuda.set_device(0)
     kn.load_library(build_if_missing=True)
+    if a.wave:
+        kn.set_render_params(*[int(v) for v in a.wave.split(",")])
     poses = [45.0 * i for i in range(8)]
     cfg_fn = lambda az: configs.config3(a.size, a.size, azimuth=az, wdtype=a.wdtype)
     cfg = cfg_fn(poses[0])

@@ -152,9 +152,10 @@ int kn_render(const kn_scene *scene, void *stream, const float *rays_o /*dev R*3
               kn_render_stats *stats /*host, nullable*/, void *workspace, int64_t workspace_bytes);
 
 /* Tuning knobs of kn_render (process-wide, for experiments; defaults are used otherwise):
- * samples per ray in the first wave, and the slot budget per ray that later waves share out
- * among the surviving rays.  Values <= 0 restore the default. */
-int kn_set_render_params(int32_t first_wave_samples, int32_t slots_per_ray);
+ * samples per ray in the first wave, the slot budget per ray (workspace size; later waves share
+ * the budget out among the surviving rays), and the factor by which the samples per ray grow from
+ * one wave to the next.  Values <= 0 restore the default. */
+int kn_set_render_params(int32_t first_wave_samples, int32_t slots_per_ray, int32_t wave_growth);
 
 /* Per-stage device time of kn_render / kn_eval_grouped, measured with HIP events recorded on the
  * caller's stream around each stage (process-wide switch, off by default).  Recording does not

@@ -76,7 +76,7 @@ def load_library(build_if_missing: bool = True):
     L.kn_composite.argtypes = [vp, vp, vp, vp, i64, f32, f32, C.POINTER(f32 * 3), vp, vp, vp]
     L.kn_render.argtypes = [vp, vp, vp, vp, i64, f32, f32, i32, f32, C.POINTER(f32 * 3), vp,
                             C.POINTER(RenderStats), vp, i64]
-    L.kn_set_render_params.argtypes = [i32, i32]
+    L.kn_set_render_params.argtypes = [i32, i32, i32]
     L.kn_profile_enable.argtypes = [C.c_int]
     L.kn_profile_read.argtypes = [C.POINTER(Profile), C.c_int]
     _lib = L
@@ -112,8 +112,8 @@ def params_per_net(hidden: int, L_pos: int = 10, L_dir: int = 4) -> int:
     return int(load_library().kn_params_per_net(hidden, L_pos, L_dir))
 
 
-def set_render_params(first_wave_samples: int = 0, slots_per_ray: int = 0):
-    _check(load_library().kn_set_render_params(first_wave_samples, slots_per_ray), "kn_set_render_params")
+def set_render_params(first_wave_samples: int = 0, slots_per_ray: int = 0, wave_growth: int = 0):
+    _check(load_library().kn_set_render_params(first_wave_samples, slots_per_ray, wave_growth), "kn_set_render_params")
 
 
 def profile_enable(on: bool):

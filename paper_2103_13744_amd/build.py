@@ -17,9 +17,16 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-fPIC", "-std=c++17", "-ffp-contract=o
          "-I", INCLUDE, "-I", CSRC]
 
 
+# The matrix-core MLP kernel uses the VALU "times two" output modifier in its double-angle recurrence; the
+# compiler only emits it with flushed fp32 denormals, without IEEE mode, and when signed zeros / NaNs need
+# no special care.  Only that file gets these flags; the index arithmetic elsewhere stays strict.
+PER_FILE_FLAGS = {"kn_mlp_mfma.hip": ["-fgpu-flush-denormals-to-zero", "-fno-signed-zeros", "-fno-honor-nans",
+                                      "-mno-amdgpu-ieee"]}
+
+
 def _compile(src: str) -> str:
     obj = os.path.join(OBJ, src.replace(".hip", ".o"))
-    extra = os.environ.get("KN_EXTRA_HIPCC_FLAGS", "").split()
+    extra = os.environ.get("KN_EXTRA_HIPCC_FLAGS", "").split() + PER_FILE_FLAGS.get(src, [])
     subprocess.run(["hipcc", *FLAGS, *extra, "-c", os.path.join(CSRC, src), "-o", obj], check=True)
     return obj
 

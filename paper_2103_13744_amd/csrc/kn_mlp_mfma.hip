@@ -192,36 +192,51 @@ template <int H, bool BF, bool RELU> __device__ __forceinline__ void pack_acts(c
     }
 }
 
-// sin and cos of 2*pi*rev
-__device__ __forceinline__ void sincos_rev(float rev, float &s, float &c)
+// s = sin, m = -cos of 2*pi*rev
+__device__ __forceinline__ void sincos_rev(float rev, float &s, float &m)
 {
     const float f = __builtin_amdgcn_fractf(rev);
     s = __builtin_amdgcn_sinf(f);
-    c = __builtin_amdgcn_cosf(f);
+    m = -__builtin_amdgcn_cosf(f);
 }
-__device__ __forceinline__ void double_angle(float s, float c, float &s2o, float &c2o)
+// (sin a, -cos a) -> (sin 2a, -cos 2a).  Written so that each line is one VALU instruction with the
+// "times two" output modifier (this file is compiled with flushed fp32 denormals and without IEEE mode).
+__device__ __forceinline__ void double_angle(float s, float m, float &s2o, float &m2o)
 {
-    s2o = 2.0f * s * c;
-    c2o = fmaf(-2.0f * s, s, 1.0f);
+    s2o = (-s * m) * 2.0f;
+    m2o = fmaf(s, s, -0.5f) * 2.0f;
 }
 
 constexpr float INV_2PI = 0.15915494309189535f;
 
+#ifndef KN_MLP_WPE
+#define KN_MLP_WPE 3
+#endif
 template <int H, bool BF, bool AREG, int WAVES>
-__global__ void __launch_bounds__(WAVES *KN_WAVE)
+__global__ void __launch_bounds__(WAVES *KN_WAVE) __attribute__((amdgpu_waves_per_eu(AREG ? KN_MLP_WPE : 1, AREG ? KN_MLP_WPE : 1)))
     k_mlp_mfma(const uint16_t *__restrict__ packed, KnSampleSrc src, const int32_t *__restrict__ perm,
                const KnTile *__restrict__ tiles, const int32_t *__restrict__ n_tiles, float *__restrict__ sigma,
                float *__restrict__ rgb)
 {
     using L = Lay<H>;
     constexpr int HT = L::HT, HK = L::HK, NBLK = L::NBLK;
-    __shared__ f4 stage[WAVES][2][KN_WAVE];
+    // Staging buffer: for each of the 64 samples of a chunk and each of the 4 lane groups, the 8 words that
+    // lane group needs, so a lane reads its operands without selecting:
+    //   [0..3] pre-scaled angles (revolutions) of the three restart points of gamma(x) and of gamma(d)
+    //   [4..7] (group 3 only) the packed 16-bit pairs (x,y), (z,1), (dx,dy), (dz,1) that sit in its slots
+    __shared__ f4 stage[WAVES][4][2][KN_WAVE]; // [lane group][half][sample]: conflict-free for writers and readers
     __shared__ u4 wlds[AREG ? 1 : WAVES * NBLK * KN_WAVE];
 
     const int wave = threadIdx.x / KN_WAVE, lane = threadIdx.x & (KN_WAVE - 1);
     const int n = lane & 15, g = lane >> 4;
-    const int tile = blockIdx.x * WAVES + wave;
-    if (tile >= *n_tiles) return;
+    const unsigned m3 = (g == 3) ? 0xffffffffu : 0u; // bit mask of lane group 3, for branch-free selects
+    const int mrow = n >> 2; // the A-operand row of this lane is n; rows 4u..4u+3 belong to sample tile u
+    const f4 zero4 = {0.0f, 0.0f, 0.0f, 0.0f};
+    const u4 zero_u4 = {0u, 0u, 0u, 0u};
+    // every wavefront strides over the tile list: the grid is sized to fill the chip once, so no time
+    // goes into retiring and dispatching a workgroup per tile
+    const int total_tiles = *n_tiles;
+    for (int tile = blockIdx.x * WAVES + wave; tile < total_tiles; tile += gridDim.x * WAVES) {
     const KnTile tl = tiles[tile];
     const u4 *__restrict__ wp = (const u4 *)(packed + (int64_t)tl.net * L::HALFS);
 
@@ -239,6 +254,23 @@ __global__ void __launch_bounds__(WAVES *KN_WAVE)
     auto A = [&](int b) -> u4 {
         if constexpr (AREG) return areg[b]; else return wl[b * KN_WAVE + lane];
     };
+    // density / colour blocks restricted to the four output rows of sample tile u (AREG: kept in registers)
+    u4 a_sig[AREG ? 4 : 1][HK], a_col[AREG ? 4 : 1][HK];
+    if constexpr (AREG) {
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+#pragma unroll
+            for (int kb = 0; kb < HK; ++kb) {
+                a_sig[u][kb] = mrow == u ? areg[L::LS + kb] : zero_u4;
+                a_col[u][kb] = mrow == u ? areg[L::L5 + kb] : zero_u4;
+            }
+    }
+    auto Asig = [&](int u, int kb) -> u4 {
+        if constexpr (AREG) return a_sig[u][kb]; else return mrow == u ? A(L::LS + kb) : zero_u4;
+    };
+    auto Acol = [&](int u, int kb) -> u4 {
+        if constexpr (AREG) return a_col[u][kb]; else return mrow == u ? A(L::L5 + kb) : zero_u4;
+    };
     const float *__restrict__ tail = (const float *)(wp + NBLK * KN_WAVE);
     f4 bias2[HT], bias3[HT];
 #pragma unroll
@@ -247,31 +279,58 @@ __global__ void __launch_bounds__(WAVES *KN_WAVE)
         bias3[t] = *(const f4 *)(tail + H + 16 * t + 4 * g);
     }
     const f4 bias_out = *(const f4 *)(tail + 2 * H);
-    const f4 zero4 = {0.0f, 0.0f, 0.0f, 0.0f};
-    const u4 zero_u4 = {0u, 0u, 0u, 0u};
-    const int mrow = n >> 2; // the A-operand row of this lane is n; rows 4u..4u+3 belong to sample tile u
 
-    // per-lane encoding constants
-    const bool role3 = (g == 3);
-    const float m0 = role3 ? 256.0f * INV_2PI : INV_2PI;
-    const float m2 = role3 ? 256.0f * INV_2PI : 4.0f * INV_2PI;
-    const float m4 = role3 ? 256.0f * INV_2PI : 16.0f * INV_2PI;
+    // Input pipeline.  A sample's inputs sit behind a chain of dependent loads (sorted position -> sample
+    // index -> [render: packed (ray, k) record -> ray origin and direction]); each level is issued one
+    // chunk of 64 samples ahead of the next, so a level's operands have arrived by the time the following
+    // level needs them: chunk c is computed while the last level of chunk c+1, the record of chunk c+2 and
+    // the index of chunk c+3 are in flight.
+    const bool from_rays = src.points == nullptr;
+    auto sorted_pos = [&](int chunk) { return tl.start + min(chunk * KN_WAVE + lane, tl.len - 1); };
+    auto load_record = [&](int32_t i) -> uint32_t { return from_rays ? src.rec[i] : 0u; };
+    struct Raw { float a[3], b[3]; }; // eval: point, direction; render: ray origin, ray direction
+    auto load_raw = [&](int32_t i, uint32_t r) -> Raw {
+        Raw q;
+        const float *pa = from_rays ? src.rays_o + 3 * (int64_t)(r >> src.kbits) : src.points + 3 * (int64_t)i;
+        const float *pb = from_rays ? src.rays_d + 3 * (int64_t)(r >> src.kbits) : src.dirs + 3 * (int64_t)i;
+#pragma unroll
+        for (int c = 0; c < 3; ++c) { q.a[c] = pa[c]; q.b[c] = pb[c]; }
+        return q;
+    };
+    auto finish = [&](const Raw &q, uint32_t r, float &x, float &y, float &z) {
+        if (from_rays)
+            kn_lattice_point(q.a[0], q.a[1], q.a[2], q.b[0], q.b[1], q.b[2], src.t_near, src.step,
+                             (int32_t)(r & ((1u << src.kbits) - 1u)), x, y, z);
+        else { x = q.a[0]; y = q.a[1]; z = q.a[2]; }
+    };
+    int32_t idx0 = perm[sorted_pos(0)], idx1 = perm[sorted_pos(1)], idx2 = perm[sorted_pos(2)];
+    uint32_t rec0 = load_record(idx0), rec1 = load_record(idx1);
+    Raw raw0 = load_raw(idx0, rec0);
 
-    // inputs of the first 64 samples (software pipeline: the loads for chunk i+1 are issued before the
-    // arithmetic of chunk i, so the perm -> record -> ray chain of dependent loads is hidden)
-    int32_t idx_next = perm[tl.start + min(lane, tl.len - 1)];
-    float nx, ny, nz, ndx, ndy, ndz;
-    kn_load_sample(src, idx_next, nx, ny, nz, ndx, ndy, ndz);
-
-    for (int base = 0; base < tl.len; base += KN_WAVE) {
+    for (int base = 0, chunk = 0; base < tl.len; base += KN_WAVE, ++chunk) {
         const int j = base + lane;
         const bool active = j < tl.len;
-        const int32_t idx = idx_next;
-        stage[wave][0][lane] = (f4){nx, ny, nz, 0.0f};
-        stage[wave][1][lane] = (f4){ndx, ndy, ndz, 0.0f};
-        if (base + KN_WAVE < tl.len) {
-            idx_next = perm[tl.start + min(j + KN_WAVE, tl.len - 1)];
-            kn_load_sample(src, idx_next, nx, ny, nz, ndx, ndy, ndz);
+        const int32_t idx = idx0;
+        float nx, ny, nz;
+        finish(raw0, rec0, nx, ny, nz);
+        const float ndx = raw0.b[0], ndy = raw0.b[1], ndz = raw0.b[2];
+        // next levels for the following chunks (their operands were loaded one iteration ago)
+        raw0 = load_raw(idx1, rec1);
+        rec0 = rec1;
+        rec1 = load_record(idx2);
+        idx0 = idx1;
+        idx1 = idx2;
+        idx2 = perm[sorted_pos(chunk + 3)];
+        {
+            // lane groups 0..2 encode one axis each at frequencies 0..7 (restarts at 2^0, 2^2, 2^4) and the
+            // direction at 0..3; group 3 encodes frequencies 8, 9 of all three axes (restarts at 2^8)
+            const float p3[3] = {nx, ny, nz}, d3[3] = {ndx, ndy, ndz};
+#pragma unroll
+            for (int a = 0; a < 3; ++a)
+                stage[wave][a][0][lane] = (f4){p3[a] * INV_2PI, p3[a] * (4.0f * INV_2PI), p3[a] * (16.0f * INV_2PI), d3[a] * INV_2PI};
+            stage[wave][3][0][lane] = (f4){nx * (256.0f * INV_2PI), ny * (256.0f * INV_2PI), nz * (256.0f * INV_2PI), 0.0f};
+            const u4 ident = {pk<BF>(nx, ny), pk<BF>(nz, 1.0f), pk<BF>(ndx, ndy), pk<BF>(ndz, 1.0f)};
+            stage[wave][3][1][lane] = __builtin_bit_cast(f4, ident);
         }
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
@@ -281,40 +340,38 @@ __global__ void __launch_bounds__(WAVES *KN_WAVE)
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
             { // all four sample tiles are always computed: straight-line code lets the scheduler interleave them
-                const f4 Pp = stage[wave][0][16 * u + n];
-                const f4 Dd = stage[wave][1][16 * u + n];
+                const f4 ang = stage[wave][g][0][16 * u + n];
+                const u4 ident = __builtin_bit_cast(u4, stage[wave][g][1][16 * u + n]); // meaningful in group 3 only
                 u4 Bx[2], Bd;
                 {
-                    const float c = g == 0 ? Pp[0] : (g == 1 ? Pp[1] : Pp[2]);
-                    const float c0 = role3 ? Pp[0] : c, c2 = role3 ? Pp[1] : c;
-                    float s[8], k[8];
-                    sincos_rev(c0 * m0, s[0], k[0]);
-                    double_angle(s[0], k[0], s[1], k[1]);
-                    sincos_rev(c2 * m2, s[2], k[2]);
-                    double_angle(s[2], k[2], s[3], k[3]);
-                    sincos_rev(c * m4, s[4], k[4]);
-                    double_angle(s[4], k[4], s[5], k[5]);
-                    double_angle(s[5], k[5], s[6], k[6]);
-                    double_angle(s[6], k[6], s[7], k[7]);
+                    // s[q] = sin, m[q] = -cos of the q-th angle of this lane; doubling keeps that form:
+                    // sin 2a = 2 sin a cos a, -cos 2a = 2 (sin^2 a - 1/2), one instruction each
+                    float s[8], m[8];
+                    sincos_rev(ang[0], s[0], m[0]);
+                    double_angle(s[0], m[0], s[1], m[1]);
+                    sincos_rev(ang[1], s[2], m[2]);
+                    double_angle(s[2], m[2], s[3], m[3]);
+                    sincos_rev(ang[2], s[4], m[4]);
+                    double_angle(s[4], m[4], s[5], m[5]);
+                    double_angle(s[5], m[5], s[6], m[6]);
+                    double_angle(s[6], m[6], s[7], m[7]);
                     unsigned p[8];
 #pragma unroll
-                    for (int q = 0; q < 8; ++q) p[q] = pk<BF>(s[q], k[q]);
-                    const unsigned id0 = pk<BF>(Pp[0], Pp[1]), id1 = pk<BF>(Pp[2], 1.0f);
-                    p[6] = role3 ? id0 : p[6];
-                    p[7] = role3 ? id1 : p[7];
+                    for (int q = 0; q < 8; ++q) p[q] = pk<BF>(s[q], -m[q]);
+                    p[6] = (ident[0] & m3) | (p[6] & ~m3);
+                    p[7] = (ident[1] & m3) | (p[7] & ~m3);
                     Bx[0] = (u4){p[0], p[1], p[2], p[3]};
                     Bx[1] = (u4){p[4], p[5], p[6], p[7]};
                 }
                 {
-                    const float c = g == 0 ? Dd[0] : (g == 1 ? Dd[1] : Dd[2]);
-                    float s[4], k[4];
-                    sincos_rev(c * INV_2PI, s[0], k[0]);
-                    double_angle(s[0], k[0], s[1], k[1]);
-                    double_angle(s[1], k[1], s[2], k[2]);
-                    double_angle(s[2], k[2], s[3], k[3]);
-                    const unsigned id0 = pk<BF>(Dd[0], Dd[1]), id1 = pk<BF>(Dd[2], 1.0f);
-                    Bd = (u4){role3 ? id0 : pk<BF>(s[0], k[0]), role3 ? id1 : pk<BF>(s[1], k[1]),
-                              role3 ? 0u : pk<BF>(s[2], k[2]), role3 ? 0u : pk<BF>(s[3], k[3])};
+                    float s[4], m[4];
+                    sincos_rev(ang[3], s[0], m[0]);
+                    double_angle(s[0], m[0], s[1], m[1]);
+                    double_angle(s[1], m[1], s[2], m[2]);
+                    double_angle(s[2], m[2], s[3], m[3]);
+                    // group 3: slots 0..3 hold dx, dy, dz, 1; its slots 4..7 meet zero weights, any finite value does
+                    Bd = (u4){(ident[2] & m3) | (pk<BF>(s[0], -m[0]) & ~m3), (ident[3] & m3) | (pk<BF>(s[1], -m[1]) & ~m3),
+                              pk<BF>(s[2], -m[2]), pk<BF>(s[3], -m[3])};
                 }
                 f4 acc[HT];
                 u4 Bh[HK];
@@ -341,7 +398,7 @@ __global__ void __launch_bounds__(WAVES *KN_WAVE)
                     for (int kb = 0; kb < HK; ++kb) acc[t] = mfma<BF>(A(L::L3 + t * HK + kb), Bh[kb], acc[t]);
                 }
 #pragma unroll
-                for (int kb = 0; kb < HK; ++kb) out = mfma<BF>(mrow == u ? A(L::LS + kb) : zero_u4, Bh[kb], out);
+                for (int kb = 0; kb < HK; ++kb) out = mfma<BF>(Asig(u, kb), Bh[kb], out);
                 pack_acts<H, BF, false>(acc, Bh);
                 // layer 4: [feature, gamma(d)] -> H, ReLU (bias through the constant-1 slot)
 #pragma unroll
@@ -353,7 +410,7 @@ __global__ void __launch_bounds__(WAVES *KN_WAVE)
                 pack_acts<H, BF, true>(acc, Bh);
                 // layer 5: H -> colour rows 4u+0..2 of the shared tile
 #pragma unroll
-                for (int kb = 0; kb < HK; ++kb) out = mfma<BF>(mrow == u ? A(L::L5 + kb) : zero_u4, Bh[kb], out);
+                for (int kb = 0; kb < HK; ++kb) out = mfma<BF>(Acol(u, kb), Bh[kb], out);
             }
         }
         __builtin_amdgcn_wave_barrier(); // staging buffer is rewritten by the next iteration
@@ -375,14 +432,21 @@ __global__ void __launch_bounds__(WAVES *KN_WAVE)
             }
         }
     }
+    __builtin_amdgcn_wave_barrier(); // the staging buffer is reused by the next tile
+    }
 }
 
 template <int H, bool BF, bool AREG, int WAVES>
 int launch(const kn_scene *sc, hipStream_t st, const KnSampleSrc &src, const KnBucketOut &b, int64_t max_tiles, float *sigma,
            float *rgb)
 {
-    const int64_t blocks = kn_div_up(max_tiles, WAVES);
-    if (blocks > 0x7fffffffLL) return KN_E_UNSUPPORTED;
+    int64_t blocks = kn_div_up(max_tiles, WAVES);
+    static int cap = 0;
+    if (!cap) { // KN_MLP_BLOCKS: experiment knob, read once
+        const char *e = getenv("KN_MLP_BLOCKS");
+        cap = e && atoi(e) > 0 ? atoi(e) : 256 * 3;
+    }
+    if (blocks > cap) blocks = cap;
     hipLaunchKernelGGL((k_mlp_mfma<H, BF, AREG, WAVES>), dim3((unsigned)blocks), dim3(WAVES * KN_WAVE), 0, st,
                        (const uint16_t *)sc->packed_w, src, b.perm, b.tiles, b.n_tiles, sigma, rgb);
     KN_CHECK_LAUNCH();

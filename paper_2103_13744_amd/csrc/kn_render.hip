@@ -590,13 +590,15 @@ MarchParams make_params(const kn_scene *sc, float t_near, float step, int32_t K)
 
 int g_first_wave_samples = 12;
 int g_slots_per_ray = 12;
+int g_wave_growth = 3;
 
 bool finite_pos(float v) { return isfinite(v) && v > 0.0f; }
 
 } // namespace
 
-extern "C" int kn_set_render_params(int32_t first_wave_samples, int32_t slots_per_ray)
+extern "C" int kn_set_render_params(int32_t first_wave_samples, int32_t slots_per_ray, int32_t wave_growth)
 {
+    g_wave_growth = wave_growth >= 2 ? wave_growth : 3;
     g_first_wave_samples = first_wave_samples > 0 ? first_wave_samples : 12;
     g_slots_per_ray = slots_per_ray > 0 ? slots_per_ray : 12;
     if (g_slots_per_ray < g_first_wave_samples) g_slots_per_ray = g_first_wave_samples;
@@ -821,7 +823,7 @@ extern "C" int kn_render(const kn_scene *sc, void *stream, const float *rays_o, 
         ++waves;
         slots_total += Mw;
         n_alive = (int64_t)next;
-        if (S_sched < K) S_sched *= 3;
+        if (S_sched < K) S_sched *= g_wave_growth;
     }
     if (g_kn_profile_on || stats) {
         unsigned long long c[2] = {0ull, 0ull};
