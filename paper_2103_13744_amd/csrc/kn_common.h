@@ -165,6 +165,24 @@ struct KnBucketOut {
 int kn_bucket_run(hipStream_t st, int32_t *keys, int64_t M, const int32_t *M_dev, int32_t N, int32_t tile_len,
                   int32_t *user_counts, int32_t *user_offsets, int32_t *user_perm, KnCarver &ws,
                   KnBucketOut *out, bool atomics_zeroed = false);
+// Unstable grouping of a render wave's samples (row layout: row i holds cnt[i] samples in slots i*S ..).
+// out->perm lists slot numbers group by group, in no particular order inside a group or between groups;
+// out->counts / out->offsets are not produced.
+//
+// `hist` (N ints) must be zero before the wave's histogram is accumulated and `cursor` (the N ints behind
+// it) before kn_group_run.  For N <= KN_GROUP_FUSED_MAX_BINS the caller may accumulate the histogram itself
+// (hist_ready) and has to clear both arrays after the run; for larger N kn_group_run counts the keys itself
+// and leaves the histogram zero.
+constexpr int KN_GROUP_FUSED_MAX_BINS = 8192;
+struct KnGroupWs {
+    int32_t *hist, *cursor, *n_tiles, *perm;
+    KnTile *tiles;
+};
+int64_t kn_group_ws_bytes(int64_t slots, int32_t N);
+void kn_group_carve(KnCarver &ws, int64_t slots, int32_t N, KnGroupWs *w);
+int kn_group_run(hipStream_t st, const int32_t *row_keys, const int32_t *cnt, int64_t n_rows, int32_t S, int32_t N,
+                 int32_t tile_len, const KnGroupWs &w, bool hist_ready, KnBucketOut *out);
+
 // The scratch counters (to be zero before the sort) that kn_bucket_run will carve from `ws` when it
 // is called with a carver in this same state, so that a caller's own kernel can clear them.
 void kn_bucket_scratch(KnCarver ws, int64_t M, int32_t N, int32_t **atomics, int64_t *n_atomics);

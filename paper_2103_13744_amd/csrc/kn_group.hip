@@ -1,0 +1,363 @@
+// Grouping of a render wave's samples by network (Sec. 3.2 "Implementation": points are ordered so
+// that the inputs of one network are contiguous before the networks are evaluated).
+//
+// The renderer does not need the stable order that kn_bucket guarantees: a sample's network output does
+// not depend on where it sits inside its group, nor on the order of the groups.  Samples of neighbouring
+// rays fall into few cells, so instead of sorting the keys every workgroup counts the keys of a contiguous
+// range of rows in LDS and touches global memory only for the bins it met:
+//   histogram   per-network sample counts of the wave.  Small grids: accumulated by the marching kernel
+//               itself; otherwise by k_group_pass<0>.
+//   offsets     exclusive prefix sums of the histogram and the tile list.  Small grids: every workgroup of
+//               the fill pass derives the offsets it needs from the histogram, the first few also write the
+//               tiles; otherwise k_group_tiles.
+//   fill        a workgroup reserves, per bin it met, a range inside the group with one integer atomic and
+//               writes the slot numbers of its samples there.
+//
+// Input is the wave's row layout: row i holds cnt[i] samples in slots i*S .. i*S + cnt[i] - 1.
+#include "kn_common.h"
+
+namespace {
+
+constexpr int GROUP_THREADS = 256;
+constexpr int GROUP_MAX_BINS = 32768;               // bins of one LDS window (larger grids: window by window)
+constexpr int GROUP_LIST = 512;                     // bins a workgroup can list as touched before it visits all
+
+#ifdef KN_GROUP_TIMING
+__device__ unsigned long long kn_group_timing[8][4096][8];
+#define GT(k) do { if (threadIdx.x == 0 && blockIdx.x < 4096 && dbg < 8) kn_group_timing[dbg][blockIdx.x][k] = wall_clock64(); } while (0)
+#else
+#define GT(k)
+#endif
+
+// tiles of one group: the owner lane has written the first; groups of several tiles are finished by the
+// whole wavefront (every lane of the wavefront must call this, with its own group or nt == 0)
+__device__ __forceinline__ void write_tiles(KnTile *__restrict__ tiles, int32_t b, int32_t off, int32_t c, int32_t nt,
+                                            int32_t tpos, int32_t tile_len, int lane)
+{
+    if (nt > 0) tiles[tpos] = KnTile{b, off, min(tile_len, c), 0};
+    unsigned long long big = __ballot(nt > 1);
+    while (big) {
+        const int srcl = __builtin_ctzll(big);
+        big &= big - 1;
+        const int32_t gb = __shfl(b, srcl, KN_WAVE), go = __shfl(off, srcl, KN_WAVE), gc = __shfl(c, srcl, KN_WAVE);
+        const int32_t gt = __shfl(tpos, srcl, KN_WAVE), gn = __shfl(nt, srcl, KN_WAVE);
+        for (int32_t k = 1 + lane; k < gn; k += KN_WAVE)
+            tiles[gt + k] = KnTile{gb, go + k * tile_len, min(tile_len, gc - k * tile_len), 0};
+    }
+}
+
+// MODE 0: add this workgroup's key counts to `global` (the histogram).
+// MODE 1: `global` holds each group's absolute fill cursor; reserve and fill this workgroup's ranges of `perm`.
+// MODE 2: (N <= KN_GROUP_FUSED_MAX_BINS) `hist` holds the finished histogram and `global` zeroed fill counters:
+//         derive the group offsets here (groups are laid out in the order bin % 256, bin / 256), reserve and
+//         fill; the first N / 256 workgroups also write the tile list.
+//
+// A workgroup covers rows_per_block consecutive rows, 256 >> g_log2 of them at a time with 1 << g_log2 lanes
+// per row.  A lane reads its row four keys at a time (chunks g, g + G, ...), and a run of equal keys inside a
+// chunk (consecutive samples of a ray mostly share their cell) costs one LDS atomic.
+template <int MODE>
+__global__ void __launch_bounds__(GROUP_THREADS)
+    k_group_pass(const int32_t *__restrict__ row_keys, const int32_t *__restrict__ cnt, int32_t n_rows, int32_t S,
+                 int32_t rows_per_block, int g_log2, int32_t N, int32_t bins_cap, int32_t *__restrict__ global,
+                 int32_t *__restrict__ perm, const int32_t *__restrict__ hist, int32_t tile_len,
+                 KnTile *__restrict__ tiles, int32_t *__restrict__ n_tiles, int dbg)
+{
+    typedef int32_t i4 __attribute__((ext_vector_type(4)));
+    extern __shared__ int32_t bins[]; // [bins_cap], MODE 2: then the wave's histogram [N]
+    __shared__ int32_t touched[GROUP_LIST], touched_off[MODE == 2 ? GROUP_LIST : 1], n_touched, scan_lds[GROUP_THREADS / KN_WAVE];
+    const int tid = threadIdx.x, lane = tid & (KN_WAVE - 1);
+    const int G = 1 << g_log2, g = tid & (G - 1), sub = tid >> g_log2, rows_per_set = GROUP_THREADS >> g_log2;
+    const int32_t r0 = blockIdx.x * rows_per_block;
+    const int32_t nr = min(rows_per_block, n_rows - r0);
+    const bool vec = (S & 3) == 0; // rows start on 16-byte boundaries
+    const int32_t row_chunks = (S + 3) >> 2;
+    GT(0);
+
+    int32_t *hcl = bins + bins_cap; // MODE 2: the wave's histogram [N]
+    if constexpr (MODE == 2) {
+        for (int32_t b0 = 0; b0 < N; b0 += 8 * GROUP_THREADS) {
+            int32_t v[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) v[u] = hist[min(b0 + u * GROUP_THREADS + tid, N - 1)]; // loads issued together
+#pragma unroll
+            for (int u = 0; u < 8; ++u)
+                if (b0 + u * GROUP_THREADS + tid < N) hcl[b0 + u * GROUP_THREADS + tid] = v[u];
+        }
+    }
+
+    // four keys of chunk ch of the row at `base` (unconditional, clamped inside the row buffer)
+    auto load_chunk = [&](int64_t base, int32_t ch) -> i4 {
+        const int32_t c = min(ch, row_chunks - 1);
+        if (vec) return *(const i4 *)(row_keys + base + 4 * c);
+        i4 v;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) v[q] = row_keys[base + min(4 * c + q, S - 1)];
+        return v;
+    };
+    // runs of equal keys among the (up to four) samples j0.. of a chunk; f(key, first j, length) per run
+    auto chunk_runs = [&](i4 v, int32_t j0, int32_t c, int32_t w0, int32_t nb, auto &&f) {
+        int32_t run_key = -1, run_j = 0, run_len = 0;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            int32_t k = v[q] - w0;
+            if (j0 + q >= c || (uint32_t)k >= (uint32_t)nb) k = -1;
+            if (k == run_key) {
+                ++run_len;
+            } else {
+                if (run_key >= 0) f(run_key, run_j, run_len);
+                run_key = k;
+                run_j = j0 + q;
+                run_len = 1;
+            }
+        }
+        if (run_key >= 0) f(run_key, run_j, run_len);
+    };
+    auto sweep = [&](int32_t w0, int32_t nb, auto &&f) {
+        for (int32_t rs = 0; rs < nr; rs += rows_per_set) {
+            const int32_t row = rs + sub;
+            const int32_t i = r0 + min(row, nr - 1);
+            const int64_t base = (int64_t)i * S;
+            const int32_t c = row < nr ? cnt[i] : 0;
+            for (int32_t ch = g;; ch += 2 * G) {
+                const i4 va = load_chunk(base, ch), vb = load_chunk(base, ch + G); // issued before c is needed
+                if (4 * ch >= c) break;
+                chunk_runs(va, 4 * ch, c, w0, nb, [&](int32_t k, int32_t j, int32_t len) { f(k, base + j, len); });
+                chunk_runs(vb, 4 * (ch + G), c, w0, nb, [&](int32_t k, int32_t j, int32_t len) { f(k, base + j, len); });
+            }
+        }
+    };
+
+    for (int32_t w0 = 0; w0 < N; w0 += bins_cap) { // MODE 2: a single window
+        const int32_t nb = min(bins_cap, N - w0);
+        for (int32_t b = tid; b < nb; b += GROUP_THREADS) bins[b] = 0;
+        if (tid == 0) n_touched = 0;
+        __syncthreads();
+        if (nr > 0) sweep(w0, nb, [&](int32_t k, int64_t, int32_t len) { atomicAdd(&bins[k], len); });
+        __syncthreads();
+        GT(1);
+        int32_t fused_off0 = 0; // MODE 2: offset of the first group this thread laid out
+        // list the touched bins, so that the global atomics below are issued side by side
+        auto list_bin = [&](int32_t b, bool hit, int32_t off) {
+            const unsigned long long m = __ballot(hit);
+            if (m) {
+                int32_t at = 0;
+                if (lane == 0) at = atomicAdd(&n_touched, __builtin_popcountll(m));
+                at = __shfl(at, 0, KN_WAVE) + __builtin_popcountll(m & ((1ull << lane) - 1ull));
+                if (hit && at < GROUP_LIST) {
+                    touched[at] = b;
+                    if (MODE == 2) touched_off[at] = off;
+                }
+            }
+        };
+        if constexpr (MODE != 2) {
+            for (int32_t b0 = 0; b0 < nb; b0 += GROUP_THREADS) {
+                const int32_t b = b0 + tid;
+                list_bin(b, b < nb && bins[b] > 0, 0);
+            }
+        } else {
+            // exclusive offsets of all groups: thread t owns the bins t, t + 256, ... and lays them out in a row;
+            // the touched ones are listed together with their offsets
+            int32_t mine = 0;
+            for (int32_t b = tid; b < N; b += GROUP_THREADS) mine += hcl[b];
+            int32_t total;
+            int32_t off = kn_block_exclusive_scan(mine, scan_lds, total);
+            fused_off0 = off;
+            for (int32_t b0 = 0; b0 < N; b0 += GROUP_THREADS) { // uniform trip count: ballots inside
+                const int32_t b = b0 + tid;
+                list_bin(b, b < N && bins[b] > 0, off);
+                off += b < N ? hcl[b] : 0;
+            }
+            // tile list: slice k = the bins 256 k .. 256 k + 255, one workgroup per slice (tile positions follow
+            // the same layout order as the offsets)
+            for (int64_t slice = blockIdx.x; slice * GROUP_THREADS < N; slice += gridDim.x) {
+                const int32_t mine_b = (int32_t)slice * GROUP_THREADS + tid;
+                int32_t my_tiles = 0, tiles_before = 0, off_mine = fused_off0;
+                for (int32_t b = tid; b < N; b += GROUP_THREADS) {
+                    const int32_t c = hcl[b];
+                    const int32_t nt = (c + tile_len - 1) / tile_len;
+                    if (b < mine_b) {
+                        tiles_before += nt;
+                        off_mine += c;
+                    }
+                    my_tiles += nt;
+                }
+                const int32_t tpos = kn_block_exclusive_scan(my_tiles, scan_lds, total) + tiles_before;
+                if (slice == 0 && tid == 0) *n_tiles = total;
+                const int32_t c = mine_b < N ? hcl[mine_b] : 0;
+                write_tiles(tiles, mine_b, off_mine, c, (c + tile_len - 1) / tile_len, tpos, tile_len, lane);
+            }
+        }
+        __syncthreads();
+        const int32_t nt = n_touched;
+        const bool listed = nt <= GROUP_LIST; // otherwise all bins of the window are visited
+        const int32_t n_visit = listed ? nt : nb;
+        GT(2);
+        if constexpr (MODE == 0) {
+            for (int32_t q = tid; q < n_visit; q += GROUP_THREADS) {
+                const int32_t b = listed ? touched[q] : q;
+                const int32_t c = bins[b];
+                if (c) atomicAdd(&global[w0 + b], c);
+            }
+        } else {
+            // first position of this workgroup's range inside each group it met
+            if (MODE == 2 && !listed) { // more bins than the list holds: every thread walks the bins it laid out
+                int32_t off = fused_off0;
+                for (int32_t b = tid; b < N; b += GROUP_THREADS) {
+                    const int32_t c = bins[b];
+                    if (c) bins[b] = off + atomicAdd(&global[b], c);
+                    off += hcl[b];
+                }
+            } else {
+                for (int32_t q = tid; q < n_visit; q += GROUP_THREADS) {
+                    const int32_t b = listed ? touched[q] : q;
+                    const int32_t c = bins[b];
+                    if (c) bins[b] = (MODE == 2 ? touched_off[q] : 0) + atomicAdd(&global[w0 + b], c);
+                }
+            }
+            __syncthreads();
+            GT(3);
+            if (nr > 0)
+                sweep(w0, nb, [&](int32_t k, int64_t slot, int32_t len) {
+                    const int32_t pos = atomicAdd(&bins[k], len);
+                    for (int32_t t = 0; t < len; ++t) perm[pos + t] = (int32_t)slot + t;
+                });
+        }
+        __syncthreads();
+        GT(4);
+    }
+}
+
+// histogram -> group offsets (also the fill cursors) and the tile list; leaves the histogram zero for the next
+// use.  One workgroup; thread t owns the bins [t * per, (t + 1) * per).
+constexpr int TILES_CHUNK = 8;
+__global__ void __launch_bounds__(1024)
+    k_group_tiles(int32_t *__restrict__ hist, int32_t N, int32_t tile_len, int32_t *__restrict__ cursor,
+                  KnTile *__restrict__ tiles, int32_t *__restrict__ n_tiles)
+{
+    __shared__ int32_t lds[1024 / KN_WAVE];
+    const int lane = threadIdx.x & (KN_WAVE - 1);
+    const int32_t per = (N + 1023) / 1024;
+    const int32_t b0 = min(N, (int32_t)threadIdx.x * per), b1 = min(N, b0 + per);
+    int32_t samples = 0, my_tiles = 0;
+    for (int32_t c0 = b0; c0 < b1; c0 += TILES_CHUNK) {
+        int32_t c[TILES_CHUNK];
+#pragma unroll
+        for (int q = 0; q < TILES_CHUNK; ++q) c[q] = hist[min(c0 + q, N - 1)]; // loads issued together
+#pragma unroll
+        for (int q = 0; q < TILES_CHUNK; ++q)
+            if (c0 + q < b1) {
+                samples += c[q];
+                my_tiles += (c[q] + tile_len - 1) / tile_len;
+            }
+    }
+    int32_t total;
+    int32_t off = kn_block_exclusive_scan(samples, lds, total);
+    int32_t tpos = kn_block_exclusive_scan(my_tiles, lds, total);
+    if (threadIdx.x == 0) *n_tiles = total;
+    // all threads of a wavefront run the same number of chunk steps (bins past b1 count as empty)
+    for (int32_t c0 = b0; c0 < b0 + per; c0 += TILES_CHUNK) {
+        int32_t c[TILES_CHUNK];
+#pragma unroll
+        for (int q = 0; q < TILES_CHUNK; ++q) c[q] = hist[min(c0 + q, N - 1)];
+#pragma unroll
+        for (int q = 0; q < TILES_CHUNK; ++q) {
+            const int32_t b = c0 + q;
+            const int32_t cc = b < b1 ? c[q] : 0;
+            const int32_t nt = (cc + tile_len - 1) / tile_len;
+            if (b < b1) {
+                hist[b] = 0;
+                cursor[b] = off;
+            }
+            write_tiles(tiles, b, off, cc, nt, tpos, tile_len, lane);
+            off += cc;
+            tpos += nt;
+        }
+    }
+}
+
+} // namespace
+
+static void carve_group(KnCarver &c, int64_t slots, int32_t N, KnGroupWs &w)
+{
+    w.hist = c.carve<int32_t>(2 * (int64_t)N); // histogram, then the fill cursors
+    w.cursor = w.hist ? w.hist + N : nullptr;
+    w.n_tiles = c.carve<int32_t>(1);
+    w.perm = c.carve<int32_t>(slots);
+    w.tiles = c.carve<KnTile>(kn_max_tiles(slots, N, 64));
+}
+
+int64_t kn_group_ws_bytes(int64_t slots, int32_t N)
+{
+    KnCarver c((void *)256, INT64_MAX / 2);
+    KnGroupWs w;
+    carve_group(c, slots, N, w);
+    return c.used;
+}
+
+void kn_group_carve(KnCarver &ws, int64_t slots, int32_t N, KnGroupWs *w) { carve_group(ws, slots, N, *w); }
+
+int kn_group_run(hipStream_t st, const int32_t *row_keys, const int32_t *cnt, int64_t n_rows, int32_t S, int32_t N,
+                 int32_t tile_len, const KnGroupWs &w, bool hist_ready, KnBucketOut *out)
+{
+    if (n_rows < 0 || S < 1 || N < 1 || tile_len < 64 || n_rows * S > 0x7fffffffLL) return KN_E_INVALID_ARG;
+    if (!w.hist || !w.cursor || !w.n_tiles || !w.perm || !w.tiles) return KN_E_WORKSPACE;
+    const bool fused = N <= KN_GROUP_FUSED_MAX_BINS;
+    if (hist_ready && !fused) return KN_E_INVALID_ARG;
+    const int32_t bins_cap = N < GROUP_MAX_BINS ? N : GROUP_MAX_BINS;
+    // lanes per row: enough that a lane meets about two chunks of four keys
+    int g_log2 = 0;
+    while (g_log2 < 6 && (8 << g_log2) < S) ++g_log2;
+    const int64_t rows_per_set = GROUP_THREADS >> g_log2;
+    const int64_t rows = n_rows > 0 ? n_rows : 1;
+    const int64_t rows_per_block = kn_div_up(kn_div_up(rows, 1024), rows_per_set) * rows_per_set;
+    const int64_t blocks = kn_div_up(rows, rows_per_block);
+    if (blocks > 0x7fffffffLL) return KN_E_UNSUPPORTED;
+    const size_t lds_bytes = sizeof(int32_t) * (size_t)bins_cap * (fused ? 2 : 1);
+    static bool configured = false; // the kernels may need more dynamic LDS than the default limit
+    if (!configured) {
+        const int most = (int)(sizeof(int32_t) * GROUP_MAX_BINS);
+        KN_HIP(hipFuncSetAttribute((const void *)k_group_pass<0>, hipFuncAttributeMaxDynamicSharedMemorySize, most));
+        KN_HIP(hipFuncSetAttribute((const void *)k_group_pass<1>, hipFuncAttributeMaxDynamicSharedMemorySize, most));
+        KN_HIP(hipFuncSetAttribute((const void *)k_group_pass<2>, hipFuncAttributeMaxDynamicSharedMemorySize, most));
+        configured = true;
+    }
+#ifdef KN_GROUP_TIMING
+    static int dbg_launch = 0;
+#define DBG dbg_launch++
+#else
+#define DBG 0
+#endif
+    const dim3 grid((unsigned)blocks), block(GROUP_THREADS);
+    if (!hist_ready) { // n_rows == 0: the kernels find no samples and leave empty outputs
+        hipLaunchKernelGGL(k_group_pass<0>, grid, block, lds_bytes, st, row_keys, cnt, (int32_t)n_rows, S,
+                           (int32_t)rows_per_block, g_log2, N, bins_cap, w.hist, (int32_t *)nullptr,
+                           (const int32_t *)nullptr, tile_len, (KnTile *)nullptr, (int32_t *)nullptr, DBG);
+        KN_CHECK_LAUNCH();
+    }
+    if (fused) {
+        hipLaunchKernelGGL(k_group_pass<2>, grid, block, lds_bytes, st, row_keys, cnt, (int32_t)n_rows, S,
+                           (int32_t)rows_per_block, g_log2, N, bins_cap, w.cursor, w.perm, (const int32_t *)w.hist, tile_len,
+                           w.tiles, w.n_tiles, DBG);
+        KN_CHECK_LAUNCH();
+    } else {
+        hipLaunchKernelGGL(k_group_tiles, dim3(1), dim3(1024), 0, st, w.hist, N, tile_len, w.cursor, w.tiles, w.n_tiles);
+        KN_CHECK_LAUNCH();
+        hipLaunchKernelGGL(k_group_pass<1>, grid, block, lds_bytes, st, row_keys, cnt, (int32_t)n_rows, S,
+                           (int32_t)rows_per_block, g_log2, N, bins_cap, w.cursor, w.perm, (const int32_t *)nullptr, tile_len,
+                           (KnTile *)nullptr, (int32_t *)nullptr, DBG);
+        KN_CHECK_LAUNCH();
+    }
+    out->perm = w.perm;
+    out->counts = nullptr;
+    out->offsets = nullptr;
+    out->tiles = w.tiles;
+    out->n_tiles = w.n_tiles;
+    return KN_OK;
+}
+
+#ifdef KN_GROUP_TIMING
+extern "C" int kn_debug_group_timing(unsigned long long *out)
+{
+    return (int)hipMemcpyFromSymbol(out, HIP_SYMBOL(kn_group_timing), sizeof(unsigned long long) * 8 * 4096 * 8);
+}
+#endif

@@ -285,11 +285,13 @@ __device__ __forceinline__ int32_t prefix_of_block_sums(const int32_t *__restric
 __global__ void __launch_bounds__(RAY_BLOCK)
     k_render_init(MarchParams p, const float *__restrict__ rays_o, const float *__restrict__ rays_d, int64_t R, RayState s,
                   int32_t *__restrict__ alive, int32_t *__restrict__ blk_sum, float bg0, float bg1, float bg2,
-                  float *__restrict__ rgb_out, int32_t *__restrict__ zero, int32_t n_zero)
+                  float *__restrict__ rgb_out, int32_t *__restrict__ zero, int32_t n_zero, int32_t *__restrict__ hist,
+                  int32_t n_hist)
 {
     __shared__ int32_t lds[RAY_BLOCK / KN_WAVE];
     const int64_t r = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (r < n_zero) zero[r] = 0; // per-call counters
+    if (r < n_hist) hist[r] = 0; // histogram of the sample grouping (kept zero by its consumer afterwards)
     int32_t lives = 0;
     if (r < R) {
         const float o[3] = {rays_o[3 * r], rays_o[3 * r + 1], rays_o[3 * r + 2]};
@@ -345,52 +347,61 @@ __global__ void __launch_bounds__(RAY_BLOCK)
     }
 }
 
-// MARCH_G lanes per live ray: collect up to S kept samples into row i of the wave's row buffers
+// MARCH_G lanes per live ray: collect up to S kept samples into row i of the wave's row buffers.
+// With `hist` the workgroup also counts its samples per network in LDS (n_bins ints of dynamic LDS) and adds
+// the bins it touched to the global histogram that the grouping of this wave starts from.
+constexpr int MARCH_TOUCHED = 1024;
 __global__ void __launch_bounds__(256)
     k_march_wave(MarchParams p, const float *__restrict__ rays_o, const float *__restrict__ rays_d,
                  const int32_t *__restrict__ live, const int32_t *__restrict__ alive, int32_t n_live, int32_t S,
                  int32_t kbits, RayState s, int32_t *__restrict__ row_keys, uint32_t *__restrict__ row_rec,
-                 int32_t *__restrict__ cnt)
+                 int32_t *__restrict__ cnt, int32_t *__restrict__ hist, int32_t n_bins)
 {
+    extern __shared__ int32_t bins[]; // [n_bins] when hist is given
+    __shared__ int32_t touched[MARCH_TOUCHED], n_touched;
+    if (hist) {
+        for (int32_t b = threadIdx.x; b < n_bins; b += 256) bins[b] = 0;
+        if (threadIdx.x == 0) n_touched = 0;
+        __syncthreads();
+    }
     const int32_t i = (int32_t)(((int64_t)blockIdx.x * blockDim.x + threadIdx.x) / MARCH_G);
     const int gl = threadIdx.x & (MARCH_G - 1);
-    if (i >= n_live) return;
-    if (!alive[i]) { // retired rows stay in the list until the next compaction
-        if (gl == 0) cnt[i] = 0;
-        return;
+    if (i < n_live) {
+        if (!alive[i]) { // retired rows stay in the list until the next compaction
+            if (gl == 0) cnt[i] = 0;
+        } else {
+            const int32_t r = live[i];
+            const float o[3] = {rays_o[3 * (int64_t)r], rays_o[3 * (int64_t)r + 1], rays_o[3 * (int64_t)r + 2]};
+            const float d[3] = {rays_d[3 * (int64_t)r], rays_d[3 * (int64_t)r + 1], rays_d[3 * (int64_t)r + 2]};
+            const GridFast gn = make_fast(p.net), go = make_fast(p.occ);
+            int32_t k = s.k_next[r];
+            const int32_t k_hi = s.k_end[r];
+            int32_t *kr = row_keys + (int64_t)i * S;
+            uint32_t *rr = row_rec + (int64_t)i * S;
+            const int32_t n = march_group(p, gn, go, o, d, k, k_hi, S, gl, [&](int j, int32_t kk, int32_t cell) {
+                kr[j] = cell;
+                rr[j] = ((uint32_t)r << kbits) | (uint32_t)kk;
+                if (hist && atomicAdd(&bins[cell], 1) == 0) { // first sample of this workgroup in that bin
+                    const int32_t at = atomicAdd(&n_touched, 1);
+                    if (at < MARCH_TOUCHED) touched[at] = cell;
+                }
+            });
+            if (gl == 0) {
+                s.k_next[r] = k;
+                cnt[i] = n;
+            }
+        }
     }
-    const int32_t r = live[i];
-    const float o[3] = {rays_o[3 * (int64_t)r], rays_o[3 * (int64_t)r + 1], rays_o[3 * (int64_t)r + 2]};
-    const float d[3] = {rays_d[3 * (int64_t)r], rays_d[3 * (int64_t)r + 1], rays_d[3 * (int64_t)r + 2]};
-    const GridFast gn = make_fast(p.net), go = make_fast(p.occ);
-    int32_t k = s.k_next[r];
-    const int32_t k_hi = s.k_end[r];
-    int32_t *kr = row_keys + (int64_t)i * S;
-    uint32_t *rr = row_rec + (int64_t)i * S;
-    const int32_t n = march_group(p, gn, go, o, d, k, k_hi, S, gl, [&](int j, int32_t kk, int32_t cell) {
-        kr[j] = cell;
-        rr[j] = ((uint32_t)r << kbits) | (uint32_t)kk;
-    });
-    if (gl == 0) {
-        s.k_next[r] = k;
-        cnt[i] = n;
+    if (hist) {
+        __syncthreads();
+        const int32_t nt = n_touched;
+        const bool listed = nt <= MARCH_TOUCHED; // otherwise visit every bin
+        for (int32_t q = threadIdx.x; q < (listed ? nt : n_bins); q += 256) {
+            const int32_t b = listed ? touched[q] : q;
+            const int32_t c = bins[b];
+            if (c) atomicAdd(&hist[b], c);
+        }
     }
-}
-
-// rows -> dense ray-major sample list: sample j of live ray i goes to off[i] + j
-__global__ void k_compact_samples(const int32_t *__restrict__ row_keys, const uint32_t *__restrict__ row_rec,
-                                  const int32_t *__restrict__ cnt, const int32_t *__restrict__ off, int32_t n_live,
-                                  int32_t S, int32_t *__restrict__ keys, uint32_t *__restrict__ rec,
-                                  int32_t *__restrict__ zero, int64_t n_zero)
-{
-    const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (t < n_zero) zero[t] = 0; // scratch counters of the sort that follows
-    const int64_t i = t / S;
-    const int32_t j = (int32_t)(t - i * S);
-    if (i >= n_live || j >= cnt[i]) return;
-    const int64_t dst = (int64_t)off[i] + j;
-    keys[dst] = row_keys[t];
-    rec[dst] = row_rec[t];
 }
 
 // MARCH_G lanes per live ray: Eq. 2-4 over this wave's samples, early termination, retire finished
@@ -398,11 +409,13 @@ __global__ void k_compact_samples(const int32_t *__restrict__ row_keys, const ui
 // blend itself is the sequential recurrence of the definition (same operation order for every
 // wave cut), run redundantly by all lanes of the group on values broadcast through LDS.
 __global__ void __launch_bounds__(256)
-    k_composite_wave(const int32_t *__restrict__ live, int32_t n_live, const int32_t *__restrict__ cnt,
-                     const int32_t *__restrict__ off, const float *__restrict__ out4, float step, float eps, float bg0,
+    k_composite_wave(const int32_t *__restrict__ live, int32_t n_live, const int32_t *__restrict__ cnt, int32_t S,
+                     const float *__restrict__ out4, float step, float eps, float bg0,
                      float bg1, float bg2, RayState s, float *__restrict__ rgb_out, int32_t *__restrict__ alive,
-                     int32_t *__restrict__ partials /*3 * gridDim.x*/)
+                     int32_t *__restrict__ partials /*3 * gridDim.x*/, int32_t *__restrict__ zero, int32_t n_zero)
 {
+    // counters of the grouping that the next wave expects to be zero
+    for (int64_t z = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; z < n_zero; z += (int64_t)gridDim.x * blockDim.x) zero[z] = 0;
     typedef float f4 __attribute__((ext_vector_type(4)));
     __shared__ f4 stage[256];
     const int32_t i = (int32_t)(((int64_t)blockIdx.x * blockDim.x + threadIdx.x) / MARCH_G);
@@ -412,7 +425,7 @@ __global__ void __launch_bounds__(256)
     if (i < n_live && alive[i]) {
         const int32_t r = live[i];
         const int32_t n = cnt[i];
-        const f4 *smp = (const f4 *)out4 + off[i];
+        const f4 *smp = (const f4 *)out4 + (int64_t)i * S; // row i of the wave's slots
         float T = s.T[r];
         float c0 = s.C[3 * (int64_t)r], c1 = s.C[3 * (int64_t)r + 1], c2 = s.C[3 * (int64_t)r + 2];
         bool dead = false;
@@ -643,8 +656,8 @@ static int kbits_for(int32_t K)
 
 // layout of the render workspace
 struct RenderWs {
-    int32_t *partials, *blk_sum, *live_a, *live_b, *cnt, *off, *alive_a, *alive_b, *pos, *scan_tmp, *n_live_dev, *n_samples_dev, *row_keys, *keys;
-    uint32_t *row_rec, *rec;
+    int32_t *partials, *blk_sum, *live_a, *live_b, *cnt, *alive_a, *alive_b, *pos, *scan_tmp, *n_live_dev, *row_keys;
+    uint32_t *row_rec;
     float *T, *C, *out4;
     int32_t *k_next, *k_end;
     unsigned long long *counters;
@@ -657,13 +670,11 @@ static void carve_render(KnCarver &ws, int64_t R, int64_t slots, RenderWs &w)
     w.live_a = ws.carve<int32_t>(R);
     w.live_b = ws.carve<int32_t>(R);
     w.cnt = ws.carve<int32_t>(R);
-    w.off = ws.carve<int32_t>(R);
     w.alive_a = ws.carve<int32_t>(R);
     w.alive_b = ws.carve<int32_t>(R);
     w.pos = ws.carve<int32_t>(R);
     w.scan_tmp = ws.carve<int32_t>(kn_scan_tmp_len(R));
     w.n_live_dev = ws.carve<int32_t>(1);
-    w.n_samples_dev = ws.carve<int32_t>(1);
     w.T = ws.carve<float>(R);
     w.C = ws.carve<float>(3 * R);
     w.k_next = ws.carve<int32_t>(R);
@@ -671,8 +682,6 @@ static void carve_render(KnCarver &ws, int64_t R, int64_t slots, RenderWs &w)
     w.counters = ws.carve<unsigned long long>(4);
     w.row_keys = ws.carve<int32_t>(slots);
     w.row_rec = ws.carve<uint32_t>(slots);
-    w.keys = ws.carve<int32_t>(slots);
-    w.rec = ws.carve<uint32_t>(slots);
     w.out4 = ws.carve<float>(4 * slots);
 }
 
@@ -682,7 +691,7 @@ int64_t kn_render_ws_bytes(const kn_scene *sc, int64_t R)
     RenderWs w;
     const int64_t slots = R * g_slots_per_ray;
     carve_render(c, R, slots, w);
-    return c.used + kn_bucket_ws_bytes(slots, sc->N);
+    return c.used + kn_group_ws_bytes(slots, sc->N);
 }
 
 extern "C" int kn_march(const kn_scene *sc, void *stream, const float *rays_o, const float *rays_d, int64_t R, float t_near,
@@ -735,16 +744,22 @@ extern "C" int kn_render(const kn_scene *sc, void *stream, const float *rays_o, 
     const int64_t budget = R * g_slots_per_ray;
     carve_render(ws, R, budget, w);
     if (!ws.ok()) return KN_E_WORKSPACE;
-    const int64_t bucket_base = ws.used;
+    KnGroupWs gw;
+    kn_group_carve(ws, budget, sc->N, &gw);
+    if (!ws.ok()) return KN_E_WORKSPACE;
 
     const MarchParams p = make_params(sc, t_near, step, K);
     RayState rs{w.T, w.C, w.k_next, w.k_end};
     const unsigned rblocks = (unsigned)kn_div_up(R, RAY_BLOCK);
+    const int64_t n_hist = 2 * (int64_t)sc->N; // histogram and fill cursors of the sample grouping
+    const bool fused_hist = sc->N <= KN_GROUP_FUSED_MAX_BINS;
     KnStageTimer tm(st);
     tm.begin();
     kn_scene *scm = const_cast<kn_scene *>(sc); // the mailbox sequence number is the only mutable scene state
     hipLaunchKernelGGL(k_render_init, dim3(rblocks), dim3(RAY_BLOCK), 0, st, p, rays_o, rays_d, R, rs, w.alive_b, w.blk_sum,
-                       bg[0], bg[1], bg[2], rgb_out, (int32_t *)w.counters, 8);
+                       bg[0], bg[1], bg[2], rgb_out, (int32_t *)w.counters, 8, gw.hist, R >= n_hist ? (int32_t)n_hist : 0);
+    KN_CHECK_LAUNCH();
+    if (R < n_hist) KN_TRY(kn_fill_i32(st, gw.hist, n_hist, 0));
     KN_CHECK_LAUNCH();
     unsigned long long seq = ++scm->mailbox_seq;
     hipLaunchKernelGGL(k_first_live, dim3(rblocks), dim3(RAY_BLOCK), 0, st, w.alive_b, w.blk_sum, R, w.live_a, w.alive_a,
@@ -758,7 +773,7 @@ extern "C" int kn_render(const kn_scene *sc, void *stream, const float *rays_o, 
     KnSampleSrc src{};
     src.points = nullptr;
     src.dirs = nullptr;
-    src.rec = w.rec;
+    src.rec = w.row_rec;
     src.rays_o = rays_o;
     src.rays_d = rays_d;
     src.t_near = t_near;
@@ -789,28 +804,21 @@ extern "C" int kn_render(const kn_scene *sc, void *stream, const float *rays_o, 
         if (S > K) S = K;
         if (S < 1) S = 1;
         const int64_t Mw = n_rows * S; // upper bound of this wave's sample count
-        hipLaunchKernelGGL(k_march_wave, dim3((unsigned)kn_div_up(n_rows * MARCH_G, 256)), dim3(256), 0, st, p, rays_o, rays_d,
-                           live, alive, (int32_t)n_rows, (int32_t)S, kbits, rs, w.row_keys, w.row_rec, w.cnt);
-        KN_CHECK_LAUNCH();
-        KN_TRY(kn_exclusive_scan_i32(st, w.cnt, w.off, n_rows, w.scan_tmp, w.n_samples_dev));
-        KnCarver bws((char *)workspace + bucket_base, workspace_bytes - bucket_base);
-        int32_t *scratch = nullptr;
-        int64_t n_scratch = 0;
-        kn_bucket_scratch(bws, Mw, sc->N, &scratch, &n_scratch);
-        const int64_t cthreads = Mw > n_scratch ? Mw : n_scratch;
-        hipLaunchKernelGGL(k_compact_samples, dim3((unsigned)kn_div_up(cthreads, 256)), dim3(256), 0, st, w.row_keys, w.row_rec,
-                           w.cnt, w.off, (int32_t)n_rows, (int32_t)S, w.keys, w.rec, scratch, scratch ? n_scratch : 0);
+        hipLaunchKernelGGL(k_march_wave, dim3((unsigned)kn_div_up(n_rows * MARCH_G, 256)), dim3(256),
+                           fused_hist ? sizeof(int32_t) * (size_t)sc->N : 0, st, p, rays_o, rays_d, live, alive, (int32_t)n_rows,
+                           (int32_t)S, kbits, rs, w.row_keys, w.row_rec, w.cnt, fused_hist ? gw.hist : (int32_t *)nullptr,
+                           sc->N);
         KN_CHECK_LAUNCH();
         tm.mark(KN_ST_MARCH);
         KnBucketOut bo;
-        KN_TRY(kn_bucket_run(st, w.keys, Mw, w.n_samples_dev, sc->N, tile_len, nullptr, nullptr, nullptr, bws, &bo,
-                             scratch != nullptr));
+        KN_TRY(kn_group_run(st, w.row_keys, w.cnt, n_rows, (int32_t)S, sc->N, tile_len, gw, fused_hist, &bo));
         tm.mark(KN_ST_BUCKET);
         KN_TRY(kn_mlp_launch(sc, st, src, bo, Mw, nullptr, nullptr));
         tm.mark(KN_ST_MLP);
         const int32_t cblocks = (int32_t)kn_div_up(n_rows * MARCH_G, 256);
-        hipLaunchKernelGGL(k_composite_wave, dim3((unsigned)cblocks), dim3(256), 0, st, live, (int32_t)n_rows, w.cnt, w.off,
-                           w.out4, step, term_eps, bg[0], bg[1], bg[2], rs, rgb_out, alive, w.partials);
+        hipLaunchKernelGGL(k_composite_wave, dim3((unsigned)cblocks), dim3(256), 0, st, live, (int32_t)n_rows, w.cnt, (int32_t)S,
+                           w.out4, step, term_eps, bg[0], bg[1], bg[2], rs, rgb_out, alive, w.partials, gw.hist,
+                           fused_hist ? (int32_t)n_hist : 0);
         KN_CHECK_LAUNCH();
         seq = ++scm->mailbox_seq;
         hipLaunchKernelGGL(k_sum_partials, dim3(1), dim3(256), 0, st, w.partials, cblocks, w.counters, sc->mailbox_dev, seq);
