@@ -170,10 +170,10 @@ int kn_bucket_run(hipStream_t st, int32_t *keys, int64_t M, const int32_t *M_dev
 // out->counts / out->offsets are not produced.
 //
 // `hist` (N ints) must be zero before the wave's histogram is accumulated and `cursor` (the N ints behind
-// it) before kn_group_run.  For N <= KN_GROUP_FUSED_MAX_BINS the caller may accumulate the histogram itself
-// (hist_ready) and has to clear both arrays after the run; for larger N kn_group_run counts the keys itself
-// and leaves the histogram zero.
-constexpr int KN_GROUP_FUSED_MAX_BINS = 8192;
+// it) before kn_group_run.  Where kn_group_fused(N) holds (small grids) the caller may accumulate the
+// histogram itself (hist_ready) and has to clear both arrays after the run; otherwise kn_group_run counts
+// the keys itself and leaves the histogram zero.
+bool kn_group_fused(int32_t N);
 struct KnGroupWs {
     int32_t *hist, *cursor, *n_tiles, *perm;
     KnTile *tiles;

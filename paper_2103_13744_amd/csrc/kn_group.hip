@@ -15,11 +15,13 @@
 //
 // Input is the wave's row layout: row i holds cnt[i] samples in slots i*S .. i*S + cnt[i] - 1.
 #include "kn_common.h"
+#include <stdlib.h>
 
 namespace {
 
 constexpr int GROUP_THREADS = 256;
-constexpr int GROUP_MAX_BINS = 32768;               // bins of one LDS window (larger grids: window by window)
+constexpr int GROUP_MAX_BINS = 32768;     // bins of one LDS window (larger grids: window by window)
+constexpr int GROUP_FUSED_MAX_BINS = 8192; // largest grid whose histogram the fill pass scans by itself
 constexpr int GROUP_LIST = 512;                     // bins a workgroup can list as touched before it visits all
 
 #ifdef KN_GROUP_TIMING
@@ -48,7 +50,7 @@ __device__ __forceinline__ void write_tiles(KnTile *__restrict__ tiles, int32_t 
 
 // MODE 0: add this workgroup's key counts to `global` (the histogram).
 // MODE 1: `global` holds each group's absolute fill cursor; reserve and fill this workgroup's ranges of `perm`.
-// MODE 2: (N <= KN_GROUP_FUSED_MAX_BINS) `hist` holds the finished histogram and `global` zeroed fill counters:
+// MODE 2: (small grids, one window) `hist` holds the finished histogram and `global` zeroed fill counters:
 //         derive the group offsets here (groups are laid out in the order bin % 256, bin / 256), reserve and
 //         fill; the first N / 256 workgroups also write the tile list.
 //
@@ -277,6 +279,29 @@ __global__ void __launch_bounds__(1024)
 
 } // namespace
 
+// KN_GROUP_WINDOW / KN_GROUP_FUSED_MAX: test knobs (read once) that shrink the LDS window and the fused-scan
+// limit, so that small scenes reach the code paths of large network grids
+static int32_t group_window()
+{
+    static int32_t v = 0;
+    if (!v) {
+        const char *e = getenv("KN_GROUP_WINDOW");
+        const int x = e ? atoi(e) : 0;
+        v = (x >= 1 && x <= GROUP_MAX_BINS) ? x : GROUP_MAX_BINS;
+    }
+    return v;
+}
+bool kn_group_fused(int32_t N)
+{
+    static int32_t lim = -1;
+    if (lim < 0) {
+        const char *e = getenv("KN_GROUP_FUSED_MAX");
+        const int x = e ? atoi(e) : -1;
+        lim = (x >= 0 && x <= GROUP_FUSED_MAX_BINS) ? x : GROUP_FUSED_MAX_BINS;
+    }
+    return N <= lim && N <= group_window();
+}
+
 static void carve_group(KnCarver &c, int64_t slots, int32_t N, KnGroupWs &w)
 {
     w.hist = c.carve<int32_t>(2 * (int64_t)N); // histogram, then the fill cursors
@@ -301,9 +326,9 @@ int kn_group_run(hipStream_t st, const int32_t *row_keys, const int32_t *cnt, in
 {
     if (n_rows < 0 || S < 1 || N < 1 || tile_len < 64 || n_rows * S > 0x7fffffffLL) return KN_E_INVALID_ARG;
     if (!w.hist || !w.cursor || !w.n_tiles || !w.perm || !w.tiles) return KN_E_WORKSPACE;
-    const bool fused = N <= KN_GROUP_FUSED_MAX_BINS;
+    const bool fused = kn_group_fused(N);
     if (hist_ready && !fused) return KN_E_INVALID_ARG;
-    const int32_t bins_cap = N < GROUP_MAX_BINS ? N : GROUP_MAX_BINS;
+    const int32_t bins_cap = N < group_window() ? N : group_window();
     // lanes per row: enough that a lane meets about two chunks of four keys
     int g_log2 = 0;
     while (g_log2 < 6 && (8 << g_log2) < S) ++g_log2;

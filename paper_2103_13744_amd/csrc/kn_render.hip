@@ -350,7 +350,6 @@ __global__ void __launch_bounds__(RAY_BLOCK)
 // MARCH_G lanes per live ray: collect up to S kept samples into row i of the wave's row buffers.
 // With `hist` the workgroup also counts its samples per network in LDS (n_bins ints of dynamic LDS) and adds
 // the bins it touched to the global histogram that the grouping of this wave starts from.
-constexpr int MARCH_TOUCHED = 1024;
 __global__ void __launch_bounds__(256)
     k_march_wave(MarchParams p, const float *__restrict__ rays_o, const float *__restrict__ rays_d,
                  const int32_t *__restrict__ live, const int32_t *__restrict__ alive, int32_t n_live, int32_t S,
@@ -358,10 +357,8 @@ __global__ void __launch_bounds__(256)
                  int32_t *__restrict__ cnt, int32_t *__restrict__ hist, int32_t n_bins)
 {
     extern __shared__ int32_t bins[]; // [n_bins] when hist is given
-    __shared__ int32_t touched[MARCH_TOUCHED], n_touched;
     if (hist) {
         for (int32_t b = threadIdx.x; b < n_bins; b += 256) bins[b] = 0;
-        if (threadIdx.x == 0) n_touched = 0;
         __syncthreads();
     }
     const int32_t i = (int32_t)(((int64_t)blockIdx.x * blockDim.x + threadIdx.x) / MARCH_G);
@@ -381,10 +378,7 @@ __global__ void __launch_bounds__(256)
             const int32_t n = march_group(p, gn, go, o, d, k, k_hi, S, gl, [&](int j, int32_t kk, int32_t cell) {
                 kr[j] = cell;
                 rr[j] = ((uint32_t)r << kbits) | (uint32_t)kk;
-                if (hist && atomicAdd(&bins[cell], 1) == 0) { // first sample of this workgroup in that bin
-                    const int32_t at = atomicAdd(&n_touched, 1);
-                    if (at < MARCH_TOUCHED) touched[at] = cell;
-                }
+                if (hist) atomicAdd(&bins[cell], 1);
             });
             if (gl == 0) {
                 s.k_next[r] = k;
@@ -392,12 +386,9 @@ __global__ void __launch_bounds__(256)
             }
         }
     }
-    if (hist) {
+    if (hist) { // the few bins this workgroup met go to the global histogram
         __syncthreads();
-        const int32_t nt = n_touched;
-        const bool listed = nt <= MARCH_TOUCHED; // otherwise visit every bin
-        for (int32_t q = threadIdx.x; q < (listed ? nt : n_bins); q += 256) {
-            const int32_t b = listed ? touched[q] : q;
+        for (int32_t b = threadIdx.x; b < n_bins; b += 256) {
             const int32_t c = bins[b];
             if (c) atomicAdd(&hist[b], c);
         }
@@ -601,9 +592,13 @@ MarchParams make_params(const kn_scene *sc, float t_near, float step, int32_t K)
     return p;
 }
 
-int g_first_wave_samples = 12;
-int g_slots_per_ray = 12;
-int g_wave_growth = 3;
+// Wave schedule.  Most rays end (early termination or leaving the content) within their first few dozen
+// kept samples, and a wave costs several kernel launches whatever its size: a generous first wave and one
+// large step afterwards (the rest of the ray for the few survivors) measured fastest at 800x800.
+constexpr int DEFAULT_FIRST_WAVE = 48, DEFAULT_SLOTS = 48, DEFAULT_GROWTH = 32;
+int g_first_wave_samples = DEFAULT_FIRST_WAVE;
+int g_slots_per_ray = DEFAULT_SLOTS;
+int g_wave_growth = DEFAULT_GROWTH;
 
 bool finite_pos(float v) { return isfinite(v) && v > 0.0f; }
 
@@ -611,9 +606,9 @@ bool finite_pos(float v) { return isfinite(v) && v > 0.0f; }
 
 extern "C" int kn_set_render_params(int32_t first_wave_samples, int32_t slots_per_ray, int32_t wave_growth)
 {
-    g_wave_growth = wave_growth >= 2 ? wave_growth : 3;
-    g_first_wave_samples = first_wave_samples > 0 ? first_wave_samples : 12;
-    g_slots_per_ray = slots_per_ray > 0 ? slots_per_ray : 12;
+    g_wave_growth = wave_growth >= 2 ? wave_growth : DEFAULT_GROWTH;
+    g_first_wave_samples = first_wave_samples > 0 ? first_wave_samples : DEFAULT_FIRST_WAVE;
+    g_slots_per_ray = slots_per_ray > 0 ? slots_per_ray : DEFAULT_SLOTS;
     if (g_slots_per_ray < g_first_wave_samples) g_slots_per_ray = g_first_wave_samples;
     return KN_OK;
 }
@@ -752,7 +747,7 @@ extern "C" int kn_render(const kn_scene *sc, void *stream, const float *rays_o, 
     RayState rs{w.T, w.C, w.k_next, w.k_end};
     const unsigned rblocks = (unsigned)kn_div_up(R, RAY_BLOCK);
     const int64_t n_hist = 2 * (int64_t)sc->N; // histogram and fill cursors of the sample grouping
-    const bool fused_hist = sc->N <= KN_GROUP_FUSED_MAX_BINS;
+    const bool fused_hist = kn_group_fused(sc->N);
     KnStageTimer tm(st);
     tm.begin();
     kn_scene *scm = const_cast<kn_scene *>(sc); // the mailbox sequence number is the only mutable scene state

@@ -7,6 +7,7 @@ termination threshold may legitimately stop one sample earlier or later than the
 skipped / extra sample contributes at most eps, so those rays are compared at tolerance + eps.
 """
 import math
+import os
 
 import numpy as np
 import pytest
@@ -296,6 +297,33 @@ def test_render_is_independent_of_wave_cut_and_deterministic():
         np.testing.assert_array_equal(img, imgs[0][0])
         assert st["samples_blended"] == imgs[0][1]["samples_blended"]
     assert imgs[2][1]["waves"] > imgs[0][1]["waves"] > imgs[4][1]["waves"] >= 1
+
+
+def test_render_large_grid_code_paths(tmp_path):
+    """Grids too large for one LDS window are grouped window by window with separate histogram and
+    offset kernels; a child process forces those paths on a small scene and must produce the same image."""
+    import subprocess
+    import sys
+    cfg = configs.config3(64, 64)
+    dev, _ = make_pair(cfg["scene"])
+    o, d = cuda(cfg["rays_o"]), cuda(cfg["rays_d"])
+    args = (cfg["t_near"], cfg["step"], cfg["K"], cfg["term_eps"], cfg["bg"])
+    here = dev.render(o, d, *args).cpu().numpy()
+    out = tmp_path / "img.npy"
+    code = (
+        "import sys, numpy as np, torch\n"
+        "sys.path.insert(0, %r)\n"
+        "from kn_synth import configs\n"
+        "from tests.util import make_pair, cuda\n"
+        "cfg = configs.config3(64, 64)\n"
+        "dev, _ = make_pair(cfg['scene'])\n"
+        "o, d = cuda(cfg['rays_o']), cuda(cfg['rays_d'])\n"
+        "img = dev.render(o, d, cfg['t_near'], cfg['step'], cfg['K'], cfg['term_eps'], cfg['bg'])\n"
+        "np.save(%r, img.cpu().numpy())\n"
+    ) % (os.path.dirname(os.path.dirname(os.path.abspath(__file__))), str(out))
+    env = dict(os.environ, KN_GROUP_WINDOW="1000", KN_GROUP_FUSED_MAX="0")
+    subprocess.run([sys.executable, "-c", code], env=env, check=True, timeout=300)
+    np.testing.assert_array_equal(np.load(out), here)
 
 
 def test_render_edge_cases():
