@@ -48,7 +48,7 @@ typedef float f2 __attribute__((ext_vector_type(2)));
 typedef float f4 __attribute__((ext_vector_type(4)));
 typedef unsigned u4 __attribute__((ext_vector_type(4)));
 
-constexpr int MLP_TILE_LEN = 256;
+constexpr int MLP_TILE_LEN = 64; // one chunk: the unit in which work is dealt out to the wavefronts
 
 template <int H> struct Lay {
     static constexpr int HT = H / 16, HK = H / 32;
@@ -192,19 +192,21 @@ template <int H, bool BF, bool RELU> __device__ __forceinline__ void pack_acts(c
     }
 }
 
-// s = sin, m = -cos of 2*pi*rev
-__device__ __forceinline__ void sincos_rev(float rev, float &s, float &m)
+// s = sin, c = cos of 2*pi*rev.  The hardware takes revolutions and reduces the range itself for |rev| <= 256;
+// WRAP adds an explicit reduction for arguments that may exceed that.
+template <bool WRAP> __device__ __forceinline__ void sincos_rev(float rev, float &s, float &c)
 {
-    const float f = __builtin_amdgcn_fractf(rev);
+    const float f = WRAP ? __builtin_amdgcn_fractf(rev) : rev;
     s = __builtin_amdgcn_sinf(f);
-    m = -__builtin_amdgcn_cosf(f);
+    c = __builtin_amdgcn_cosf(f);
 }
-// (sin a, -cos a) -> (sin 2a, -cos 2a).  Written so that each line is one VALU instruction with the
-// "times two" output modifier (this file is compiled with flushed fp32 denormals and without IEEE mode).
-__device__ __forceinline__ void double_angle(float s, float m, float &s2o, float &m2o)
+// (sin a, cos a) -> (sin 2a, cos 2a) = (2 sin a cos a, 2 (1/2 - sin^2 a)).  Written so that each line is one
+// VALU instruction with the "times two" output modifier (this file is compiled with flushed fp32 denormals
+// and without IEEE mode).
+__device__ __forceinline__ void double_angle(float s, float c, float &s2o, float &c2o)
 {
-    s2o = (-s * m) * 2.0f;
-    m2o = fmaf(s, s, -0.5f) * 2.0f;
+    s2o = (s * c) * 2.0f;
+    c2o = fmaf(-s, s, 0.5f) * 2.0f;
 }
 
 constexpr float INV_2PI = 0.15915494309189535f;
@@ -212,7 +214,7 @@ constexpr float INV_2PI = 0.15915494309189535f;
 #ifndef KN_MLP_WPE
 #define KN_MLP_WPE 3
 #endif
-template <int H, bool BF, bool AREG, int WAVES>
+template <int H, bool BF, bool AREG, int WAVES, bool WRAP>
 __global__ void __launch_bounds__(WAVES *KN_WAVE) __attribute__((amdgpu_waves_per_eu(AREG ? KN_MLP_WPE : 1, AREG ? KN_MLP_WPE : 1)))
     k_mlp_mfma(const uint16_t *__restrict__ packed, KnSampleSrc src, const int32_t *__restrict__ perm,
                const KnTile *__restrict__ tiles, const int32_t *__restrict__ n_tiles, float *__restrict__ sigma,
@@ -233,60 +235,65 @@ __global__ void __launch_bounds__(WAVES *KN_WAVE) __attribute__((amdgpu_waves_pe
     const int mrow = n >> 2; // the A-operand row of this lane is n; rows 4u..4u+3 belong to sample tile u
     const f4 zero4 = {0.0f, 0.0f, 0.0f, 0.0f};
     const u4 zero_u4 = {0u, 0u, 0u, 0u};
-    // every wavefront strides over the tile list: the grid is sized to fill the chip once, so no time
-    // goes into retiring and dispatching a workgroup per tile
+    // The tile list is cut into one contiguous range per wavefront (tiles are chunks of at most 64 samples, so
+    // the ranges differ by one chunk at most).  Neighbouring tiles mostly belong to the same network: weights
+    // are fetched only when the network changes.
     const int total_tiles = *n_tiles;
-    for (int tile = blockIdx.x * WAVES + wave; tile < total_tiles; tile += gridDim.x * WAVES) {
-    const KnTile tl = tiles[tile];
-    const u4 *__restrict__ wp = (const u4 *)(packed + (int64_t)tl.net * L::HALFS);
+    const int total_waves = gridDim.x * WAVES;
+    const int wid = __builtin_amdgcn_readfirstlane(blockIdx.x * WAVES + wave);
+    const int t_lo = (int)((int64_t)wid * total_tiles / total_waves);
+    const int t_hi = (int)((int64_t)(wid + 1) * total_tiles / total_waves);
+    if (t_lo >= t_hi) return;
 
-    // weights: registers (AREG) or this wave's private LDS copy
     u4 areg[AREG ? NBLK : 1];
     u4 *wl = &wlds[AREG ? 0 : wave * NBLK * KN_WAVE];
-    if constexpr (AREG) {
-#pragma unroll
-        for (int b = 0; b < NBLK; ++b) areg[b] = wp[b * KN_WAVE + lane];
-    } else {
-        for (int b = 0; b < NBLK; ++b) wl[b * KN_WAVE + lane] = wp[b * KN_WAVE + lane];
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-        __builtin_amdgcn_wave_barrier();
-    }
     auto A = [&](int b) -> u4 {
         if constexpr (AREG) return areg[b]; else return wl[b * KN_WAVE + lane];
     };
     // density / colour blocks restricted to the four output rows of sample tile u (AREG: kept in registers)
     u4 a_sig[AREG ? 4 : 1][HK], a_col[AREG ? 4 : 1][HK];
-    if constexpr (AREG) {
-#pragma unroll
-        for (int u = 0; u < 4; ++u)
-#pragma unroll
-            for (int kb = 0; kb < HK; ++kb) {
-                a_sig[u][kb] = mrow == u ? areg[L::LS + kb] : zero_u4;
-                a_col[u][kb] = mrow == u ? areg[L::L5 + kb] : zero_u4;
-            }
-    }
     auto Asig = [&](int u, int kb) -> u4 {
         if constexpr (AREG) return a_sig[u][kb]; else return mrow == u ? A(L::LS + kb) : zero_u4;
     };
     auto Acol = [&](int u, int kb) -> u4 {
         if constexpr (AREG) return a_col[u][kb]; else return mrow == u ? A(L::L5 + kb) : zero_u4;
     };
-    const float *__restrict__ tail = (const float *)(wp + NBLK * KN_WAVE);
-    f4 bias2[HT], bias3[HT];
+    f4 bias2[HT], bias3[HT], bias_out;
+    auto load_network = [&](int32_t net) {
+        const u4 *__restrict__ wp = (const u4 *)(packed + (int64_t)net * L::HALFS);
+        if constexpr (AREG) {
 #pragma unroll
-    for (int t = 0; t < HT; ++t) {
-        bias2[t] = *(const f4 *)(tail + 16 * t + 4 * g);
-        bias3[t] = *(const f4 *)(tail + H + 16 * t + 4 * g);
-    }
-    const f4 bias_out = *(const f4 *)(tail + 2 * H);
+            for (int b = 0; b < NBLK; ++b) areg[b] = wp[b * KN_WAVE + lane];
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+#pragma unroll
+                for (int kb = 0; kb < HK; ++kb) {
+                    a_sig[u][kb] = mrow == u ? areg[L::LS + kb] : zero_u4;
+                    a_col[u][kb] = mrow == u ? areg[L::L5 + kb] : zero_u4;
+                }
+        } else {
+            __builtin_amdgcn_wave_barrier(); // earlier reads of this wave's LDS copy are done
+            for (int b = 0; b < NBLK; ++b) wl[b * KN_WAVE + lane] = wp[b * KN_WAVE + lane];
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+        }
+        const float *__restrict__ tail = (const float *)(wp + NBLK * KN_WAVE);
+#pragma unroll
+        for (int t = 0; t < HT; ++t) {
+            bias2[t] = *(const f4 *)(tail + 16 * t + 4 * g);
+            bias3[t] = *(const f4 *)(tail + H + 16 * t + 4 * g);
+        }
+        bias_out = *(const f4 *)(tail + 2 * H);
+    };
 
-    // Input pipeline.  A sample's inputs sit behind a chain of dependent loads (sorted position -> sample
-    // index -> [render: packed (ray, k) record -> ray origin and direction]); each level is issued one
-    // chunk of 64 samples ahead of the next, so a level's operands have arrived by the time the following
-    // level needs them: chunk c is computed while the last level of chunk c+1, the record of chunk c+2 and
-    // the index of chunk c+3 are in flight.
+    // Input pipeline.  A sample's inputs sit behind a chain of dependent loads (tile descriptor -> sorted
+    // position -> sample index -> [render: packed (ray, k) record -> ray origin and direction]); each level is
+    // issued one tile ahead of the next, so a level's operands have arrived by the time the following level
+    // needs them: tile t is computed while the last level of tile t+1, the record of t+2, the index of t+3 and
+    // the descriptor of t+4 are in flight.
     const bool from_rays = src.points == nullptr;
-    auto sorted_pos = [&](int chunk) { return tl.start + min(chunk * KN_WAVE + lane, tl.len - 1); };
+    auto descriptor = [&](int t) -> KnTile { return tiles[min(t, t_hi - 1)]; };
+    auto sorted_pos = [&](const KnTile &d) { return d.start + min(lane, d.len - 1); };
     auto load_record = [&](int32_t i) -> uint32_t { return from_rays ? src.rec[i] : 0u; };
     struct Raw { float a[3], b[3]; }; // eval: point, direction; render: ray origin, ray direction
     auto load_raw = [&](int32_t i, uint32_t r) -> Raw {
@@ -303,24 +310,34 @@ __global__ void __launch_bounds__(WAVES *KN_WAVE) __attribute__((amdgpu_waves_pe
                              (int32_t)(r & ((1u << src.kbits) - 1u)), x, y, z);
         else { x = q.a[0]; y = q.a[1]; z = q.a[2]; }
     };
-    int32_t idx0 = perm[sorted_pos(0)], idx1 = perm[sorted_pos(1)], idx2 = perm[sorted_pos(2)];
+    KnTile dsc0 = descriptor(t_lo), dsc1 = descriptor(t_lo + 1), dsc2 = descriptor(t_lo + 2), dsc3 = descriptor(t_lo + 3);
+    int32_t idx0 = perm[sorted_pos(dsc0)], idx1 = perm[sorted_pos(dsc1)], idx2 = perm[sorted_pos(dsc2)];
     uint32_t rec0 = load_record(idx0), rec1 = load_record(idx1);
     Raw raw0 = load_raw(idx0, rec0);
+    int32_t net_cur = -1;
 
-    for (int base = 0, chunk = 0; base < tl.len; base += KN_WAVE, ++chunk) {
-        const int j = base + lane;
-        const bool active = j < tl.len;
+    for (int t = t_lo; t < t_hi; ++t) {
+        const KnTile tl = dsc0;
+        if (tl.net != net_cur) { // uniform
+            load_network(tl.net);
+            net_cur = tl.net;
+        }
+        const bool active = lane < tl.len;
         const int32_t idx = idx0;
         float nx, ny, nz;
         finish(raw0, rec0, nx, ny, nz);
         const float ndx = raw0.b[0], ndy = raw0.b[1], ndz = raw0.b[2];
-        // next levels for the following chunks (their operands were loaded one iteration ago)
+        // next levels for the following tiles (their operands were loaded one iteration ago)
         raw0 = load_raw(idx1, rec1);
         rec0 = rec1;
         rec1 = load_record(idx2);
         idx0 = idx1;
         idx1 = idx2;
-        idx2 = perm[sorted_pos(chunk + 3)];
+        idx2 = perm[sorted_pos(dsc3)];
+        dsc0 = dsc1;
+        dsc1 = dsc2;
+        dsc2 = dsc3;
+        dsc3 = descriptor(t + 4);
         {
             // lane groups 0..2 encode one axis each at frequencies 0..7 (restarts at 2^0, 2^2, 2^4) and the
             // direction at 0..3; group 3 encodes frequencies 8, 9 of all three axes (restarts at 2^8)
@@ -344,20 +361,19 @@ __global__ void __launch_bounds__(WAVES *KN_WAVE) __attribute__((amdgpu_waves_pe
                 const u4 ident = __builtin_bit_cast(u4, stage[wave][g][1][16 * u + n]); // meaningful in group 3 only
                 u4 Bx[2], Bd;
                 {
-                    // s[q] = sin, m[q] = -cos of the q-th angle of this lane; doubling keeps that form:
-                    // sin 2a = 2 sin a cos a, -cos 2a = 2 (sin^2 a - 1/2), one instruction each
+                    // s[q] = sin, m[q] = cos of the q-th angle of this lane
                     float s[8], m[8];
-                    sincos_rev(ang[0], s[0], m[0]);
+                    sincos_rev<WRAP>(ang[0], s[0], m[0]);
                     double_angle(s[0], m[0], s[1], m[1]);
-                    sincos_rev(ang[1], s[2], m[2]);
+                    sincos_rev<WRAP>(ang[1], s[2], m[2]);
                     double_angle(s[2], m[2], s[3], m[3]);
-                    sincos_rev(ang[2], s[4], m[4]);
+                    sincos_rev<WRAP>(ang[2], s[4], m[4]);
                     double_angle(s[4], m[4], s[5], m[5]);
                     double_angle(s[5], m[5], s[6], m[6]);
                     double_angle(s[6], m[6], s[7], m[7]);
                     unsigned p[8];
 #pragma unroll
-                    for (int q = 0; q < 8; ++q) p[q] = pk<BF>(s[q], -m[q]);
+                    for (int q = 0; q < 8; ++q) p[q] = pk<BF>(s[q], m[q]);
                     p[6] = (ident[0] & m3) | (p[6] & ~m3);
                     p[7] = (ident[1] & m3) | (p[7] & ~m3);
                     Bx[0] = (u4){p[0], p[1], p[2], p[3]};
@@ -365,13 +381,13 @@ __global__ void __launch_bounds__(WAVES *KN_WAVE) __attribute__((amdgpu_waves_pe
                 }
                 {
                     float s[4], m[4];
-                    sincos_rev(ang[3], s[0], m[0]);
+                    sincos_rev<false>(ang[3], s[0], m[0]); // directions: |d| far below 256 revolutions
                     double_angle(s[0], m[0], s[1], m[1]);
                     double_angle(s[1], m[1], s[2], m[2]);
                     double_angle(s[2], m[2], s[3], m[3]);
                     // group 3: slots 0..3 hold dx, dy, dz, 1; its slots 4..7 meet zero weights, any finite value does
-                    Bd = (u4){(ident[2] & m3) | (pk<BF>(s[0], -m[0]) & ~m3), (ident[3] & m3) | (pk<BF>(s[1], -m[1]) & ~m3),
-                              pk<BF>(s[2], -m[2]), pk<BF>(s[3], -m[3])};
+                    Bd = (u4){(ident[2] & m3) | (pk<BF>(s[0], m[0]) & ~m3), (ident[3] & m3) | (pk<BF>(s[1], m[1]) & ~m3),
+                              pk<BF>(s[2], m[2]), pk<BF>(s[3], m[3])};
                 }
                 f4 acc[HT];
                 u4 Bh[HK];
@@ -432,8 +448,6 @@ __global__ void __launch_bounds__(WAVES *KN_WAVE) __attribute__((amdgpu_waves_pe
             }
         }
     }
-    __builtin_amdgcn_wave_barrier(); // the staging buffer is reused by the next tile
-    }
 }
 
 template <int H, bool BF, bool AREG, int WAVES>
@@ -447,24 +461,24 @@ int launch(const kn_scene *sc, hipStream_t st, const KnSampleSrc &src, const KnB
         cap = e && atoi(e) > 0 ? atoi(e) : 256 * 3;
     }
     if (blocks > cap) blocks = cap;
-    hipLaunchKernelGGL((k_mlp_mfma<H, BF, AREG, WAVES>), dim3((unsigned)blocks), dim3(WAVES * KN_WAVE), 0, st,
-                       (const uint16_t *)sc->packed_w, src, b.perm, b.tiles, b.n_tiles, sigma, rgb);
+    // positions are only ever evaluated inside the grid's box: its largest coordinate bounds the encoding's
+    // largest argument, 2^8 |p| / (2 pi) revolutions at the highest restart frequency
+    float reach = 0.0f;
+    for (int a = 0; a < 3; ++a)
+        reach = fmaxf(reach, fmaxf(fabsf(sc->desc.aabb_min[a]), fabsf(sc->desc.aabb_max[a])));
+    if (reach * (256.0f * INV_2PI) < 250.0f)
+        hipLaunchKernelGGL((k_mlp_mfma<H, BF, AREG, WAVES, false>), dim3((unsigned)blocks), dim3(WAVES * KN_WAVE), 0, st,
+                           (const uint16_t *)sc->packed_w, src, b.perm, b.tiles, b.n_tiles, sigma, rgb);
+    else
+        hipLaunchKernelGGL((k_mlp_mfma<H, BF, AREG, WAVES, true>), dim3((unsigned)blocks), dim3(WAVES * KN_WAVE), 0, st,
+                           (const uint16_t *)sc->packed_w, src, b.perm, b.tiles, b.n_tiles, sigma, rgb);
     KN_CHECK_LAUNCH();
     return KN_OK;
 }
 
 } // namespace
 
-int kn_mlp_mfma_tile_len(const kn_scene *)
-{
-    static int len = 0;
-    if (!len) { // KN_MLP_TILE: experiment knob (multiple of 64), read once
-        const char *e = getenv("KN_MLP_TILE");
-        const int v = e ? atoi(e) : 0;
-        len = (v >= 64 && v <= 4096 && v % 64 == 0) ? v : MLP_TILE_LEN;
-    }
-    return len;
-}
+int kn_mlp_mfma_tile_len(const kn_scene *) { return MLP_TILE_LEN; }
 
 int kn_mlp_pack_weights(kn_scene *sc, hipStream_t st)
 {

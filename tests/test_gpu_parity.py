@@ -126,6 +126,15 @@ def test_eval_grouped_matrix_cores(wdtype, H):
     check_eval(sc, pts, ks.sphere_dirs(M, 6))
 
 
+def test_eval_grouped_matrix_cores_large_box():
+    # coordinates large enough that 2^9 p leaves the range the sine hardware reduces by itself (f16 only: the
+    # raw coordinates are network inputs too, and rounding 45.0 to bf16 alone costs more than the tolerance)
+    sc = scene_dict((3, 2, 4), (-40, -10, 5), (40, 30, 45), 32, "f16", 17)
+    M = 20_003
+    pts = ks.uniform_points(M, 15, lo=(-41, -11, 4), hi=(41, 31, 46))
+    check_eval(sc, pts, ks.sphere_dirs(M, 16))
+
+
 def test_eval_grouped_density_scaled_and_tiny_groups():
     # sigma_scale as in the render workload; 16^3 networks with few points each => many partial tiles
     sc = scene_dict((16, 16, 16), (-1, -1, -1), (1, 1, 1), 32, "f16", 8, sigma_scale=100.0)
