@@ -4,6 +4,7 @@
 #include <math.h>
 #include <new>
 #include <string.h>
+#include <vector>
 
 thread_local int g_kn_last_hip_error = 0;
 
@@ -211,6 +212,39 @@ static int validate_desc(const kn_scene_desc *d)
     return KN_OK;
 }
 
+// Bounding box of the occupied skip blocks (distance 0), read back once at scene creation.
+static int content_box_from_skip_field(kn_scene *sc, int64_t cells)
+{
+    std::vector<uint8_t> h((size_t)cells);
+    if (hipMemcpy(h.data(), sc->skip_dist, (size_t)cells, hipMemcpyDeviceToHost) != hipSuccess) return KN_E_HIP;
+    int lo[3] = {INT32_MAX, INT32_MAX, INT32_MAX}, hi[3] = {-1, -1, -1};
+    const int *sr = sc->skip_res;
+    for (int x = 0; x < sr[0]; ++x)
+        for (int y = 0; y < sr[1]; ++y)
+            for (int z = 0; z < sr[2]; ++z)
+                if (h[((size_t)x * sr[1] + y) * sr[2] + z] == 0) {
+                    const int c[3] = {x, y, z};
+                    for (int a = 0; a < 3; ++a) {
+                        lo[a] = c[a] < lo[a] ? c[a] : lo[a];
+                        hi[a] = c[a] > hi[a] ? c[a] : hi[a];
+                    }
+                }
+    KnGrid &b = sc->content_box;
+    b = sc->occ_grid;
+    for (int a = 0; a < 3; ++a) {
+        if (hi[a] < 0) { // nothing occupied
+            b.res[a] = 0;
+            continue;
+        }
+        const int v0 = lo[a] * KN_SKIP_BLOCK;
+        int v1 = (hi[a] + 1) * KN_SKIP_BLOCK;
+        if (v1 > sc->occ_grid.res[a]) v1 = sc->occ_grid.res[a];
+        b.bmin[a] = sc->occ_grid.bmin[a] + sc->occ_grid.cell[a] * (float)v0;
+        b.res[a] = v1 - v0;
+    }
+    return KN_OK;
+}
+
 extern "C" int kn_scene_create(const kn_scene_desc *desc, void *stream, kn_scene **out)
 {
     if (!out) return KN_E_INVALID_ARG;
@@ -280,11 +314,13 @@ extern "C" int kn_scene_create(const kn_scene_desc *desc, void *stream, kn_scene
                 }
                 hipLaunchKernelGGL(k_skip_cap, grid, block, 0, st, sc->skip_dist, cells);
                 if (hipGetLastError() != hipSuccess || hipStreamSynchronize(st) != hipSuccess) rc = KN_E_HIP;
+                if (rc == KN_OK) rc = content_box_from_skip_field(sc, cells);
             }
             if (tmp) (void)hipFree(tmp);
         }
     } else {
         sc->occ_grid = sc->net_grid;
+        sc->content_box = sc->net_grid;
     }
     if (rc == KN_OK && desc->wdtype != KN_F32) rc = kn_mlp_pack_weights(sc, st);
     if (rc != KN_OK) {

@@ -42,6 +42,9 @@ struct kn_scene {
     // block, capped at KN_SKIP_MAX).  Lets marching jump over provably empty lattice points.
     uint8_t *skip_dist;    // device, skip_res[0]*[1]*[2] bytes, x slowest; nullptr without occupancy
     int32_t skip_res[3];
+    // Box around all occupied voxels, as a sub-grid of the occupancy grid (whole skip blocks; the network
+    // grid's box without occupancy; res = 0 when nothing is occupied): rays are clipped against it.
+    KnGrid content_box;
     // Host-visible mailbox (pinned, device-mapped): kn_render's kernels post the live-ray count of a
     // wave here, {sequence number, value}, and the host polls it instead of draining the stream.
     volatile unsigned long long *mailbox_host;

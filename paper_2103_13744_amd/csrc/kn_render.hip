@@ -21,6 +21,7 @@ constexpr int MARCH_G = 16;
 
 struct MarchParams {
     KnGrid net, occ;
+    KnGrid content; // box around everything occupied (res 0: nothing is); rays are clipped against it
     const uint32_t *occ_bits;
     const uint8_t *skip_dist;
     int32_t skip_res[3];
@@ -82,6 +83,10 @@ __device__ __forceinline__ int32_t grid_index_fast(const GridFast &g, float x, f
 __device__ __forceinline__ void clip_ray(const KnGrid &g, const float o[3], const float d[3], float t_near, float step,
                                          int32_t K, int32_t &k_lo, int32_t &k_hi)
 {
+    if (g.res[0] == 0) { // empty box
+        k_lo = k_hi = 0;
+        return;
+    }
     float tmin = -INFINITY, tmax = INFINITY;
 #pragma unroll
     for (int a = 0; a < 3; ++a) {
@@ -242,7 +247,7 @@ __global__ void __launch_bounds__(256)
     const float d[3] = {rays_d[3 * r], rays_d[3 * r + 1], rays_d[3 * r + 2]};
     const GridFast gn = make_fast(p.net), go = make_fast(p.occ);
     int32_t k_lo, k_hi;
-    clip_ray(p.net, o, d, p.t_near, p.step, p.K, k_lo, k_hi);
+    clip_ray(p.content, o, d, p.t_near, p.step, p.K, k_lo, k_hi);
     int32_t k = max(k_begin ? max(k_begin[r], 0) : 0, k_lo);
     int32_t *row = out_k + r * S;
     const int32_t n = march_group(p, gn, go, o, d, k, k_hi, S, gl, [&](int j, int32_t kk, int32_t) { row[j] = kk; });
@@ -297,7 +302,7 @@ __global__ void __launch_bounds__(RAY_BLOCK)
         const float o[3] = {rays_o[3 * r], rays_o[3 * r + 1], rays_o[3 * r + 2]};
         const float d[3] = {rays_d[3 * r], rays_d[3 * r + 1], rays_d[3 * r + 2]};
         int32_t k_lo, k_hi;
-        clip_ray(p.net, o, d, p.t_near, p.step, p.K, k_lo, k_hi);
+        clip_ray(p.content, o, d, p.t_near, p.step, p.K, k_lo, k_hi);
         // walk through provably empty space up to the first lattice point that is near occupied blocks
         k_lo = skip_to_content(p, make_fast(p.occ), o, d, k_lo, k_hi);
         s.T[r] = 1.0f;
@@ -573,6 +578,7 @@ MarchParams make_params(const kn_scene *sc, float t_near, float step, int32_t K)
     MarchParams p;
     p.net = sc->net_grid;
     p.occ = sc->has_occ ? sc->occ_grid : sc->net_grid;
+    p.content = sc->content_box;
     p.occ_bits = sc->occ_bits;
     p.has_occ = sc->has_occ ? 1 : 0;
     p.skip_dist = sc->has_occ ? sc->skip_dist : nullptr;
