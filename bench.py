@@ -21,6 +21,22 @@ PEAK_HBM = 8.0e12          # B/s
 FLOP_PER_SAMPLE = {32: 12160, 64: 36608}
 
 
+def read_traffic():
+    """HBM bytes per launch from the committed rocprofv3 counter summary (FETCH_SIZE / WRITE_SIZE runs of this
+    benchmark, scaled by the copy-kernel calibration stated in the file); {} if the file is absent."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic_cfg3_f16.txt")
+    out = {}
+    try:
+        with open(path) as f:
+            for line in f:
+                parts = line.split()
+                if len(parts) >= 2 and parts[0] == "traffic_bytes_per_launch":
+                    out[parts[1]] = float(parts[2])
+    except OSError:
+        pass
+    return out
+
+
 def cpu_baseline(cfg_fn, poses, budget_s=12.0):
     """Time the oracle (threaded build, all host cores) on whole frames of the same workload."""
     from oracle import OracleScene
@@ -28,15 +44,13 @@ def cpu_baseline(cfg_fn, poses, budget_s=12.0):
     s = cfg["scene"]
     orc = OracleScene(s["res"], s["aabb_min"], s["aabb_max"], s["hidden"], s["weights"], s["occupancy"], threads=True)
     samples, t_total, frames = 0, 0.0, 0
-    for az in poses:
-        c = cfg_fn(az)
+    while t_total < budget_s and frames < 64: # whole frames, cycling through the poses, until the time budget is used
+        c = cfg_fn(poses[frames % len(poses)])
         t0 = time.perf_counter()
         _, n_eval, _, _ = orc.render(c["rays_o"], c["rays_d"], c["t_near"], c["step"], c["K"], c["term_eps"], c["bg"])
         t_total += time.perf_counter() - t0
         samples += int(n_eval.sum())
         frames += 1
-        if t_total >= budget_s:
-            break
     return {"value": samples / t_total, "unit": "samples/s", "cores": orc.num_threads(), "kind": "oracle",
             "sample": "%d whole 800x800 frame(s) of the same scene (%d blended samples, %.1f s)" % (frames, samples, t_total),
             "frames_per_sec": frames / t_total}
@@ -127,47 +141,57 @@ def main():
         scene.render(*rays[i % 8], *args, out=out)
     torch.cuda.synchronize()
 
-    # timed region: K frames, the library's per-stage HIP events recorded on the stream as it goes
-    kn.profile_enable(True)
-    kn.profile_read(reset=True)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for i in range(a.steps):
-        scene.render(*rays[i % 8], *args, out=out)
-    torch.cuda.synchronize()
-    dt_s = time.perf_counter() - t0
-    prof = kn.profile_read(reset=True)
-    kn.profile_enable(False)
-    # the same K frames without the events, for reference
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for i in range(a.steps):
-        scene.render(*rays[i % 8], *args, out=out)
-    torch.cuda.synchronize()
-    dt_plain_s = time.perf_counter() - t0
+    def run_frames(profile_mode):
+        kn.profile_enable(profile_mode)
+        kn.profile_read(reset=True)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(a.steps):
+            scene.render(*rays[i % 8], *args, out=out)
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        prof = kn.profile_read(reset=True)
+        kn.profile_enable(0)
+        return dt, prof
+
+    # untimed: K frames with HIP events around every stage, to find the kernel that takes the most time
+    _, prof_all = run_frames(1)
+    stage_ms = {k: prof_all[k] for k in ("ms_setup", "ms_march", "ms_bucket", "ms_mlp", "ms_blend")}
+    dominant = max(("ms_march", "ms_bucket", "ms_mlp", "ms_blend"), key=lambda k: stage_ms[k])
+    # timed region: K frames, HIP events (recorded by the library on the stream it launches on) only around the
+    # dominant kernel, so that the measurement disturbs the frame as little as possible
+    mode = {"ms_mlp": 2, "ms_march": 3}.get(dominant, 1)
+    dt_s, prof = run_frames(mode)
+    # the same K frames without any events, for reference
+    dt_plain_s, _ = run_frames(0)
 
     blended = sum(stats[i % 8]["samples_blended"] for i in range(a.steps))
     evaluated = sum(stats[i % 8]["samples_evaluated"] for i in range(a.steps))
     waves = sum(stats[i % 8]["waves"] for i in range(a.steps))
+    launches = waves  # one launch of each per-wave kernel per wave
     H = sc["hidden"]
-    stage_ms = {k: prof[k] for k in ("ms_march", "ms_bucket", "ms_mlp", "ms_blend")}
-    mlp_s = prof["ms_mlp"] * 1e-3
-    mlp_tflops = FLOP_PER_SAMPLE[H] * prof["mlp_samples"] / mlp_s / 1e12 if mlp_s > 0 else 0.0
-    roof_mlp = {"kernel": "k_mlp_mfma (fused grouped MLP)", "bound": "mfma", "achieved": mlp_tflops,
-                "peak": PEAK_MFMA_16BIT / 1e12, "unit": "TFLOP/s", "frac": mlp_tflops * 1e12 / PEAK_MFMA_16BIT,
-                "traffic": None, "avg_launch_ms": prof["ms_mlp"] / max(prof["mlp_launches"], 1),
-                "launches": prof["mlp_launches"], "samples_per_launch": prof["mlp_samples"] / max(prof["mlp_launches"], 1)}
-    # marching: algorithmic bytes = 24 B per ray read once per frame + 8 B (key, record) per kept sample written
-    # + the packed occupancy grid read once per frame
-    occ_bytes = int(np.prod(sc["occupancy"].shape)) / 8
-    march_bytes = a.steps * (24.0 * R + occ_bytes) + 8.0 * prof["mlp_samples"]
-    march_s = prof["ms_march"] * 1e-3
-    roof_march = {"kernel": "k_march_wave (march + empty-space skipping)", "bound": "hbm",
-                  "achieved": march_bytes / march_s / 1e9 if march_s > 0 else 0.0, "peak": PEAK_HBM / 1e9, "unit": "GB/s",
-                  "frac": march_bytes / march_s / PEAK_HBM if march_s > 0 else 0.0, "traffic": None,
-                  "avg_launch_ms": prof["ms_march"] / max(prof["mlp_launches"], 1)}
-    dominant = max(stage_ms, key=stage_ms.get)
-    roofline = dict(roof_march if dominant == "ms_march" else roof_mlp)
+    traffic = read_traffic()
+
+    def roof_mlp(p):
+        s_ = p["ms_mlp"] * 1e-3
+        tf = FLOP_PER_SAMPLE[H] * evaluated / s_ / 1e12 if s_ > 0 else 0.0
+        return {"kernel": "k_mlp_mfma (fused grouped MLP)", "bound": "mfma", "achieved": tf, "peak": PEAK_MFMA_16BIT / 1e12,
+                "unit": "TFLOP/s", "frac": tf * 1e12 / PEAK_MFMA_16BIT, "traffic": traffic.get("k_mlp_mfma"),
+                "avg_launch_ms": p["ms_mlp"] / max(launches, 1), "launches": launches,
+                "samples_per_launch": evaluated / max(launches, 1)}
+
+    def roof_march(p):
+        # algorithmic bytes: 24 B per ray read + the packed occupancy grid read, once per frame, and 8 B (key,
+        # record) written per kept sample
+        occ_bytes = int(np.prod(sc["occupancy"].shape)) / 8
+        nbytes = a.steps * (occ_bytes + 24.0 * R) + 8.0 * evaluated
+        s_ = p["ms_march"] * 1e-3
+        return {"kernel": "k_march_wave (march + empty-space skipping)", "bound": "hbm",
+                "achieved": nbytes / s_ / 1e9 if s_ > 0 else 0.0, "peak": PEAK_HBM / 1e9, "unit": "GB/s",
+                "frac": nbytes / s_ / PEAK_HBM if s_ > 0 else 0.0, "traffic": traffic.get("k_march_wave"),
+                "avg_launch_ms": p["ms_march"] / max(launches, 1), "launches": launches}
+
+    roofline = roof_mlp(prof) if dominant == "ms_mlp" else roof_march(prof) if dominant == "ms_march" else roof_mlp(prof_all)
     res = {
         "metric": "MLP sample evals/sec + frames/sec at 800x800",
         "value": blended / dt_s, "unit": "samples/s",
@@ -176,13 +200,13 @@ def main():
         "config": {"workload": "cfg3: %dx%d render, 16^3 networks (H=32), 256^3 occupancy grid (8%% occupied), "
                                "step diag/512, eps 0.01, 8 camera poses" % (a.size, a.size)},
         "frames_per_sec": a.steps / dt_s,
-        "ms_per_step_without_stage_events": dt_plain_s * 1e3 / a.steps,
+        "ms_per_step_without_events": dt_plain_s * 1e3 / a.steps,
         "samples_blended_per_frame": blended / a.steps, "samples_evaluated_per_frame": evaluated / a.steps,
         "waves_per_frame": waves / a.steps,
         "stage_ms_per_frame": {k: v / a.steps for k, v in stage_ms.items()},
-        "dominant_stage": dominant,
+        "dominant_kernel_stage": dominant,
         "roofline": roofline,
-        "roofline_mlp": roof_mlp, "roofline_march": roof_march,
+        "roofline_mlp_all_events": roof_mlp(prof_all), "roofline_march_all_events": roof_march(prof_all),
     }
     if a.calibrate_copy:
         src_buf = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()

@@ -163,15 +163,18 @@ int kn_set_render_params(int32_t first_wave_samples, int32_t slots_per_ray, int3
  * copies the totals accumulated since the last reset. */
 typedef struct {
     double ms_cell;        /* point -> cell id (kn_eval_grouped only; fused into marching in kn_render) */
-    double ms_march;       /* marching + empty-space skipping                                          */
-    double ms_bucket;      /* radix passes, bucket boundaries, tile list                               */
+    double ms_march;       /* marching + empty-space skipping (kn_render: the per-wave marching kernel)  */
+    double ms_bucket;      /* ordering by network: radix passes / grouping passes, offsets, tile list   */
     double ms_mlp;         /* the fused grouped-MLP kernel                                             */
     double ms_blend;       /* blending + early termination + live-ray compaction                       */
     int64_t mlp_launches;  /* launches of the grouped-MLP kernel                                       */
     int64_t mlp_samples;   /* samples those launches evaluated                                         */
     int64_t bucket_keys;   /* keys sorted (incl. unused slots)                                         */
     int64_t calls;         /* kn_render + kn_eval_grouped calls                                        */
+    double ms_setup;       /* kn_render: ray clipping / first live list, and live-list compaction between waves */
 } kn_profile;
+/* on: 0 = off, 1 = every stage, 2 = only the grouped-MLP kernel, 3 = only the marching kernel (fewer events on
+ * the stream: less disturbance of the run that is being timed) */
 int kn_profile_enable(int on);
 int kn_profile_read(kn_profile *out /*host*/, int reset);
 

@@ -40,7 +40,7 @@ class RenderStats(C.Structure):
 class Profile(C.Structure):
     _fields_ = [("ms_cell", C.c_double), ("ms_march", C.c_double), ("ms_bucket", C.c_double), ("ms_mlp", C.c_double),
                 ("ms_blend", C.c_double), ("mlp_launches", C.c_int64), ("mlp_samples", C.c_int64),
-                ("bucket_keys", C.c_int64), ("calls", C.c_int64)]
+                ("bucket_keys", C.c_int64), ("calls", C.c_int64), ("ms_setup", C.c_double)]
 
 
 _lib = None
@@ -116,8 +116,9 @@ def set_render_params(first_wave_samples: int = 0, slots_per_ray: int = 0, wave_
     _check(load_library().kn_set_render_params(first_wave_samples, slots_per_ray, wave_growth), "kn_set_render_params")
 
 
-def profile_enable(on: bool):
-    _check(load_library().kn_profile_enable(1 if on else 0), "kn_profile_enable")
+def profile_enable(on):
+    """False / 0: off; True / 1: every stage; 2: only the grouped-MLP kernel; 3: only the marching kernel."""
+    _check(load_library().kn_profile_enable(int(on)), "kn_profile_enable")
 
 
 def profile_read(reset: bool = True) -> dict:

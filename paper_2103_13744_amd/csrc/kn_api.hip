@@ -19,6 +19,7 @@ int kn_mlp_mfma_tile_len(const kn_scene *sc);
 
 kn_profile g_kn_profile = {};
 bool g_kn_profile_on = false;
+static int g_only_stage = KN_ST_NONE; // != NONE: only this stage's intervals are recorded
 // Event ring shared by all calls: intervals are settled (one stream synchronise, then
 // hipEventElapsedTime for each recorded interval) only when the ring is full, when another stream
 // starts recording, or when the totals are read.
@@ -43,6 +44,7 @@ static int settle_events()
             case KN_ST_BUCKET: g_kn_profile.ms_bucket += ms; break;
             case KN_ST_MLP: g_kn_profile.ms_mlp += ms; break;
             case KN_ST_BLEND: g_kn_profile.ms_blend += ms; break;
+            case KN_ST_SETUP: g_kn_profile.ms_setup += ms; break;
             default: break;
             }
         }
@@ -64,6 +66,14 @@ KnStageTimer::KnStageTimer(hipStream_t s) : st(s), on(g_kn_profile_on)
 void KnStageTimer::mark(int stage_id)
 {
     if (!on) return;
+    if (g_only_stage != KN_ST_NONE) {
+        // the mark before the stage of interest opens its interval; everything else is dropped
+        const bool opens = g_only_stage == KN_ST_MLP ? stage_id == KN_ST_BUCKET
+                                                     : (stage_id == KN_ST_NONE || stage_id == KN_ST_SETUP);
+        const bool closes = stage_id == g_only_stage;
+        if (!opens && !closes) return;
+        if (opens) stage_id = KN_ST_NONE;
+    }
     if (g_n_events == KN_N_EVENTS) {
         (void)settle_events();
         if (stage_id != KN_ST_NONE) { // re-open the interval that the settle cut short
@@ -78,7 +88,9 @@ void KnStageTimer::mark(int stage_id)
 
 extern "C" int kn_profile_enable(int on)
 {
+    if (g_kn_profile_on) (void)settle_events();
     g_kn_profile_on = on != 0;
+    g_only_stage = on == 2 ? KN_ST_MLP : on == 3 ? KN_ST_MARCH : KN_ST_NONE;
     return KN_OK;
 }
 

@@ -217,7 +217,7 @@ int64_t kn_scan_tmp_len(int64_t n);
 // begin() records a start event, mark(stage) an event that closes an interval charged to `stage`.
 // Elapsed times are read later, in batches (kn_profile_read forces it), so recording does not
 // synchronise the stream.
-enum KnStage { KN_ST_CELL = 0, KN_ST_MARCH, KN_ST_BUCKET, KN_ST_MLP, KN_ST_BLEND, KN_ST_NONE };
+enum KnStage { KN_ST_CELL = 0, KN_ST_MARCH, KN_ST_BUCKET, KN_ST_MLP, KN_ST_BLEND, KN_ST_SETUP, KN_ST_NONE };
 struct KnStageTimer {
     hipStream_t st;
     bool on;

@@ -1,9 +1,11 @@
 // Grouped tiny-MLP evaluation on the matrix cores (scenes with KN_F16 / KN_BF16 weights).
 //
-// One wavefront evaluates one tile (<= 256 consecutive entries of the sorted sample list, all of
-// one network): encoding, the five layers of Sec. 3.2 and the output activations in one kernel
+// A wavefront evaluates tiles (<= 64 consecutive entries of the grouped sample list, all of one
+// network): encoding, the five layers of Sec. 3.2 and the output activations in one kernel
 // (the paper's Sec. 3.5 fuses the whole network evaluation into one kernel as well; everything
-// below that sentence is this library's own design for 64-wide wavefronts and MFMA).
+// below that sentence is this library's own design for 64-wide wavefronts and MFMA).  Every
+// wavefront takes a contiguous range of the tile list and re-fetches weights only when the network
+// changes from one tile to the next.
 //
 // Formulation.  Every layer is computed transposed, out^T = W^T * act^T, with
 // v_mfma_f32_16x16x32_{f16,bf16}: the A operand is a 16(out) x 32(in) block of W^T, the B operand
@@ -31,7 +33,9 @@
 //
 // Encoding.  sin/cos of 2^f * p come from v_sin_f32 / v_cos_f32 at three "restart" frequencies
 // per lane and the double-angle recurrence in between (fp32), which is far inside the 16-bit
-// rounding of the operands.
+// rounding of the operands.  The coordinates of the 64 samples of a tile are staged in LDS, scaled
+// to revolutions per restart frequency, so that each lane group reads exactly the operands of its
+// role.
 #include "kn_common.h"
 #include "kn_mlp_shared.h"
 

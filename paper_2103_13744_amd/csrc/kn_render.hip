@@ -766,7 +766,7 @@ extern "C" int kn_render(const kn_scene *sc, void *stream, const float *rays_o, 
     hipLaunchKernelGGL(k_first_live, dim3(rblocks), dim3(RAY_BLOCK), 0, st, w.alive_b, w.blk_sum, R, w.live_a, w.alive_a,
                        w.n_live_dev, sc->mailbox_dev, seq);
     KN_CHECK_LAUNCH();
-    tm.mark(KN_ST_MARCH);
+    tm.mark(KN_ST_SETUP);
     long long first = 0;
     KN_TRY(wait_count(sc, st, seq, w.n_live_dev, sizeof(int32_t), &first));
     if (first < 0 || first > R) return KN_E_HIP;
@@ -798,6 +798,7 @@ extern "C" int kn_render(const kn_scene *sc, void *stream, const float *rays_o, 
             int32_t *t = live; live = live_next; live_next = t;
             t = alive; alive = alive_next; alive_next = t;
             n_rows = n_alive;
+            tm.mark(KN_ST_SETUP);
         }
         // samples per ray in this wave: triples from wave to wave, bounded by the slot budget
         int64_t S = S_sched;
