@@ -218,6 +218,9 @@ constexpr float INV_2PI = 0.15915494309189535f;
 #ifndef KN_MLP_WPE
 #define KN_MLP_WPE 3
 #endif
+#ifdef KN_MLP_TIMING
+__device__ unsigned long long kn_mlp_timing[8 * 4096];
+#endif
 template <int H, bool BF, bool AREG, int WAVES, bool WRAP>
 __global__ void __launch_bounds__(WAVES *KN_WAVE) __attribute__((amdgpu_waves_per_eu(AREG ? KN_MLP_WPE : 1, AREG ? KN_MLP_WPE : 1)))
     k_mlp_mfma(const uint16_t *__restrict__ packed, KnSampleSrc src, const int32_t *__restrict__ perm,
@@ -242,11 +245,17 @@ __global__ void __launch_bounds__(WAVES *KN_WAVE) __attribute__((amdgpu_waves_pe
     // The tile list is cut into one contiguous range per wavefront (tiles are chunks of at most 64 samples, so
     // the ranges differ by one chunk at most).  Neighbouring tiles mostly belong to the same network: weights
     // are fetched only when the network changes.
+#ifdef KN_MLP_TIMING
+    const unsigned long long T0 = wall_clock64();
+    unsigned long long T1 = 0, T2 = 0;
+#endif
     const int total_tiles = *n_tiles;
     const int total_waves = gridDim.x * WAVES;
     const int wid = __builtin_amdgcn_readfirstlane(blockIdx.x * WAVES + wave);
-    const int t_lo = (int)((int64_t)wid * total_tiles / total_waves);
-    const int t_hi = (int)((int64_t)(wid + 1) * total_tiles / total_waves);
+    // (kept in scalar registers: tile descriptors are then fetched through the scalar cache, whose counter is
+    // separate from the one of the vector loads and stores in flight)
+    const int t_lo = __builtin_amdgcn_readfirstlane((int)((int64_t)wid * total_tiles / total_waves));
+    const int t_hi = __builtin_amdgcn_readfirstlane((int)((int64_t)(wid + 1) * total_tiles / total_waves));
     if (t_lo >= t_hi) return;
 
     u4 areg[AREG ? NBLK : 1];
@@ -319,18 +328,55 @@ __global__ void __launch_bounds__(WAVES *KN_WAVE) __attribute__((amdgpu_waves_pe
     uint32_t rec0 = load_record(idx0), rec1 = load_record(idx1);
     Raw raw0 = load_raw(idx0, rec0);
     int32_t net_cur = -1;
+    // Results of a tile are written in the next iteration, between its wait for the loads issued one iteration
+    // earlier and the loads it issues itself: the memory counter is in order, so a store must be older than
+    // every load that is going to be waited for, or the wait covers the store's full round trip as well.
+    f4 pend = zero4;
+    int32_t pend_idx = -1;
+    auto write_out = [&]() {
+        if (pend_idx >= 0) {
+            if (src.out4) {
+                *(f4 *)(src.out4 + 4 * (int64_t)pend_idx) = pend;
+            } else {
+                sigma[pend_idx] = pend[3];
+                float *o = rgb + 3 * (int64_t)pend_idx;
+                o[0] = pend[0];
+                o[1] = pend[1];
+                o[2] = pend[2];
+            }
+        }
+    };
+
+    // The hardware issues from the oldest ready wavefront first, so the wavefronts that share a SIMD would finish
+    // one after the other and the last one would run alone; a wavefront lowers its own issue priority as it gets
+    // through its range (in quarters), which lets the ones behind catch up and ends all of them together.
+    const int quarter = max((t_hi - t_lo + 3) >> 2, 1);
+    int next_drop = t_lo + quarter, prio = 3;
+    __builtin_amdgcn_s_setprio(3);
 
     for (int t = t_lo; t < t_hi; ++t) {
+        if (t == next_drop) { // uniform
+            next_drop += quarter;
+            --prio;
+            if (prio == 2) __builtin_amdgcn_s_setprio(2);
+            else if (prio == 1) __builtin_amdgcn_s_setprio(1);
+            else __builtin_amdgcn_s_setprio(0);
+        }
         const KnTile tl = dsc0;
         if (tl.net != net_cur) { // uniform
             load_network(tl.net);
             net_cur = tl.net;
         }
         const bool active = lane < tl.len;
+#ifdef KN_MLP_TIMING
+        if (t == t_lo) { T1 = wall_clock64(); }
+        if (t == t_lo + 1) { T2 = wall_clock64(); }
+#endif
         const int32_t idx = idx0;
         float nx, ny, nz;
         finish(raw0, rec0, nx, ny, nz);
         const float ndx = raw0.b[0], ndy = raw0.b[1], ndz = raw0.b[2];
+        write_out(); // after the loads of the last iteration have been waited for, before new ones are issued
         // next levels for the following tiles (their operands were loaded one iteration ago)
         raw0 = load_raw(idx1, rec1);
         rec0 = rec1;
@@ -341,7 +387,6 @@ __global__ void __launch_bounds__(WAVES *KN_WAVE) __attribute__((amdgpu_waves_pe
         dsc0 = dsc1;
         dsc1 = dsc2;
         dsc2 = dsc3;
-        dsc3 = descriptor(t + 4);
         {
             // lane groups 0..2 encode one axis each at frequencies 0..7 (restarts at 2^0, 2^2, 2^4) and the
             // direction at 0..3; group 3 encodes frequencies 8, 9 of all three axes (restarts at 2^8)
@@ -434,24 +479,25 @@ __global__ void __launch_bounds__(WAVES *KN_WAVE) __attribute__((amdgpu_waves_pe
             }
         }
         __builtin_amdgcn_wave_barrier(); // staging buffer is rewritten by the next iteration
+        // The next descriptor comes through the scalar cache, which shares its counter with LDS: fetched here,
+        // behind the last LDS read of the iteration, its latency is not part of any wait for staged data.
+        dsc3 = descriptor(t + 4);
 
-        if (active) {
+        // output activations; the store itself is issued at the top of the next iteration (see write_out)
+        {
             const float sg = fmaxf(out[3], 0.0f);
             float col[3];
 #pragma unroll
             for (int c = 0; c < 3; ++c)
                 col[c] = __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-1.4426950408889634f * out[c]));
-            if (src.out4) {
-                *(f4 *)(src.out4 + 4 * (int64_t)idx) = (f4){col[0], col[1], col[2], sg};
-            } else {
-                sigma[idx] = sg;
-                float *o = rgb + 3 * (int64_t)idx;
-                o[0] = col[0];
-                o[1] = col[1];
-                o[2] = col[2];
-            }
+            pend = (f4){col[0], col[1], col[2], sg};
+            pend_idx = active ? idx : -1;
         }
     }
+    write_out();
+#ifdef KN_MLP_TIMING
+    if (lane == 0 && wid < 4096) { unsigned long long *o = kn_mlp_timing + 8 * wid; o[0] = T0; o[1] = T1; o[2] = T2; o[3] = wall_clock64(); o[4] = t_hi - t_lo; }
+#endif
 }
 
 template <int H, bool BF, bool AREG, int WAVES>
@@ -482,6 +528,9 @@ int launch(const kn_scene *sc, hipStream_t st, const KnSampleSrc &src, const KnB
 
 } // namespace
 
+#ifdef KN_MLP_TIMING
+extern "C" int kn_debug_mlp_timing(unsigned long long *out) { return (int)hipMemcpyFromSymbol(out, HIP_SYMBOL(kn_mlp_timing), sizeof(unsigned long long) * 8 * 4096); }
+#endif
 int kn_mlp_mfma_tile_len(const kn_scene *) { return MLP_TILE_LEN; }
 
 int kn_mlp_pack_weights(kn_scene *sc, hipStream_t st)
