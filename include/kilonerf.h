@@ -174,7 +174,8 @@ typedef struct {
     double ms_setup;       /* kn_render: ray clipping / first live list, and live-list compaction between waves */
 } kn_profile;
 /* on: 0 = off, 1 = every stage, 2 = only the grouped-MLP kernel, 3 = only the marching kernel (fewer events on
- * the stream: less disturbance of the run that is being timed) */
+ * the stream: less disturbance of the run that is being timed; mlp_samples / bucket_keys / calls are not
+ * gathered in modes 2 and 3, because reading them back would make kn_render wait for the frame) */
 int kn_profile_enable(int on);
 int kn_profile_read(kn_profile *out /*host*/, int reset);
 

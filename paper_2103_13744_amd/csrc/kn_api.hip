@@ -19,7 +19,7 @@ int kn_mlp_mfma_tile_len(const kn_scene *sc);
 
 kn_profile g_kn_profile = {};
 bool g_kn_profile_on = false;
-static int g_only_stage = KN_ST_NONE; // != NONE: only this stage's intervals are recorded
+int g_only_stage = KN_ST_NONE; // != NONE: only this stage's intervals are recorded (and no sample counts)
 // Event ring shared by all calls: intervals are settled (one stream synchronise, then
 // hipEventElapsedTime for each recorded interval) only when the ring is full, when another stream
 // starts recording, or when the totals are read.

@@ -183,8 +183,9 @@ struct KnGroupWs {
 };
 int64_t kn_group_ws_bytes(int64_t slots, int32_t N);
 void kn_group_carve(KnCarver &ws, int64_t slots, int32_t N, KnGroupWs *w);
-int kn_group_run(hipStream_t st, const int32_t *row_keys, const int32_t *cnt, int64_t n_rows, int32_t S, int32_t N,
-                 int32_t tile_len, const KnGroupWs &w, bool hist_ready, KnBucketOut *out);
+// ctl (device): ctl[0] = number of rows, ctl[1] = S; max_rows: host-side upper bound of ctl[0] (sizes the grid).
+int kn_group_run(hipStream_t st, const int32_t *row_keys, const int32_t *cnt, const int32_t *ctl, int64_t max_rows,
+                 int32_t N, int32_t tile_len, const KnGroupWs &w, bool hist_ready, KnBucketOut *out);
 
 // The scratch counters (to be zero before the sort) that kn_bucket_run will carve from `ws` when it
 // is called with a carver in this same state, so that a caller's own kernel can clear them.
@@ -227,3 +228,4 @@ struct KnStageTimer {
 };
 extern kn_profile g_kn_profile;
 extern bool g_kn_profile_on;
+extern int g_only_stage; // KN_ST_NONE, or the one stage that is being timed (then sample counts are not gathered)

@@ -54,13 +54,13 @@ __device__ __forceinline__ void write_tiles(KnTile *__restrict__ tiles, int32_t 
 //         derive the group offsets here (groups are laid out in the order bin % 256, bin / 256), reserve and
 //         fill; the first N / 256 workgroups also write the tile list.
 //
-// A workgroup covers rows_per_block consecutive rows, 256 >> g_log2 of them at a time with 1 << g_log2 lanes
+// A workgroup covers an equal share of consecutive rows, 256 >> g_log2 of them at a time with 1 << g_log2 lanes
 // per row.  A lane reads its row four keys at a time (chunks g, g + G, ...), and a run of equal keys inside a
 // chunk (consecutive samples of a ray mostly share their cell) costs one LDS atomic.
 template <int MODE>
 __global__ void __launch_bounds__(GROUP_THREADS)
-    k_group_pass(const int32_t *__restrict__ row_keys, const int32_t *__restrict__ cnt, int32_t n_rows, int32_t S,
-                 int32_t rows_per_block, int g_log2, int32_t N, int32_t bins_cap, int32_t *__restrict__ global,
+    k_group_pass(const int32_t *__restrict__ row_keys, const int32_t *__restrict__ cnt, const int32_t *__restrict__ ctl,
+                 int32_t N, int32_t bins_cap, int32_t *__restrict__ global,
                  int32_t *__restrict__ perm, const int32_t *__restrict__ hist, int32_t tile_len,
                  KnTile *__restrict__ tiles, int32_t *__restrict__ n_tiles, int dbg)
 {
@@ -68,8 +68,14 @@ __global__ void __launch_bounds__(GROUP_THREADS)
     extern __shared__ int32_t bins[]; // [bins_cap], MODE 2: then the wave's histogram [N]
     __shared__ int32_t touched[GROUP_LIST], touched_off[MODE == 2 ? GROUP_LIST : 1], n_touched, scan_lds[GROUP_THREADS / KN_WAVE];
     const int tid = threadIdx.x, lane = tid & (KN_WAVE - 1);
+    // the wave's shape comes from device memory (ctl[0] rows of ctl[1] slots): the launch may have been enqueued
+    // before it was known.  Lanes per row: enough that a lane meets about two chunks of four keys.
+    const int32_t n_rows = ctl[0], S = ctl[1];
+    int g_log2 = 0;
+    while (g_log2 < 6 && (8 << g_log2) < S) ++g_log2;
     const int G = 1 << g_log2, g = tid & (G - 1), sub = tid >> g_log2, rows_per_set = GROUP_THREADS >> g_log2;
-    const int32_t r0 = blockIdx.x * rows_per_block;
+    const int32_t rows_per_block = ((n_rows + (int32_t)gridDim.x - 1) / (int32_t)gridDim.x + rows_per_set - 1) / rows_per_set * rows_per_set;
+    const int32_t r0 = min((int64_t)blockIdx.x * rows_per_block, (int64_t)n_rows);
     const int32_t nr = min(rows_per_block, n_rows - r0);
     const bool vec = (S & 3) == 0; // rows start on 16-byte boundaries
     const int32_t row_chunks = (S + 3) >> 2;
@@ -321,22 +327,16 @@ int64_t kn_group_ws_bytes(int64_t slots, int32_t N)
 
 void kn_group_carve(KnCarver &ws, int64_t slots, int32_t N, KnGroupWs *w) { carve_group(ws, slots, N, *w); }
 
-int kn_group_run(hipStream_t st, const int32_t *row_keys, const int32_t *cnt, int64_t n_rows, int32_t S, int32_t N,
-                 int32_t tile_len, const KnGroupWs &w, bool hist_ready, KnBucketOut *out)
+int kn_group_run(hipStream_t st, const int32_t *row_keys, const int32_t *cnt, const int32_t *ctl, int64_t max_rows,
+                 int32_t N, int32_t tile_len, const KnGroupWs &w, bool hist_ready, KnBucketOut *out)
 {
-    if (n_rows < 0 || S < 1 || N < 1 || tile_len < 64 || n_rows * S > 0x7fffffffLL) return KN_E_INVALID_ARG;
+    if (!ctl || max_rows < 0 || max_rows > 0x7fffffffLL || N < 1 || tile_len < 64) return KN_E_INVALID_ARG;
     if (!w.hist || !w.cursor || !w.n_tiles || !w.perm || !w.tiles) return KN_E_WORKSPACE;
     const bool fused = kn_group_fused(N);
     if (hist_ready && !fused) return KN_E_INVALID_ARG;
     const int32_t bins_cap = N < group_window() ? N : group_window();
-    // lanes per row: enough that a lane meets about two chunks of four keys
-    int g_log2 = 0;
-    while (g_log2 < 6 && (8 << g_log2) < S) ++g_log2;
-    const int64_t rows_per_set = GROUP_THREADS >> g_log2;
-    const int64_t rows = n_rows > 0 ? n_rows : 1;
-    const int64_t rows_per_block = kn_div_up(kn_div_up(rows, 1024), rows_per_set) * rows_per_set;
-    const int64_t blocks = kn_div_up(rows, rows_per_block);
-    if (blocks > 0x7fffffffLL) return KN_E_UNSUPPORTED;
+    int64_t blocks = kn_div_up(max_rows > 0 ? max_rows : 1, 16);
+    if (blocks > 1024) blocks = 1024;
     const size_t lds_bytes = sizeof(int32_t) * (size_t)bins_cap * (fused ? 2 : 1);
     static bool configured = false; // the kernels may need more dynamic LDS than the default limit
     if (!configured) {
@@ -353,23 +353,20 @@ int kn_group_run(hipStream_t st, const int32_t *row_keys, const int32_t *cnt, in
 #define DBG 0
 #endif
     const dim3 grid((unsigned)blocks), block(GROUP_THREADS);
-    if (!hist_ready) { // n_rows == 0: the kernels find no samples and leave empty outputs
-        hipLaunchKernelGGL(k_group_pass<0>, grid, block, lds_bytes, st, row_keys, cnt, (int32_t)n_rows, S,
-                           (int32_t)rows_per_block, g_log2, N, bins_cap, w.hist, (int32_t *)nullptr,
-                           (const int32_t *)nullptr, tile_len, (KnTile *)nullptr, (int32_t *)nullptr, DBG);
+    if (!hist_ready) { // no rows: the kernels find no samples and leave empty outputs
+        hipLaunchKernelGGL(k_group_pass<0>, grid, block, lds_bytes, st, row_keys, cnt, ctl, N, bins_cap, w.hist,
+                           (int32_t *)nullptr, (const int32_t *)nullptr, tile_len, (KnTile *)nullptr, (int32_t *)nullptr, DBG);
         KN_CHECK_LAUNCH();
     }
     if (fused) {
-        hipLaunchKernelGGL(k_group_pass<2>, grid, block, lds_bytes, st, row_keys, cnt, (int32_t)n_rows, S,
-                           (int32_t)rows_per_block, g_log2, N, bins_cap, w.cursor, w.perm, (const int32_t *)w.hist, tile_len,
-                           w.tiles, w.n_tiles, DBG);
+        hipLaunchKernelGGL(k_group_pass<2>, grid, block, lds_bytes, st, row_keys, cnt, ctl, N, bins_cap, w.cursor, w.perm,
+                           (const int32_t *)w.hist, tile_len, w.tiles, w.n_tiles, DBG);
         KN_CHECK_LAUNCH();
     } else {
         hipLaunchKernelGGL(k_group_tiles, dim3(1), dim3(1024), 0, st, w.hist, N, tile_len, w.cursor, w.tiles, w.n_tiles);
         KN_CHECK_LAUNCH();
-        hipLaunchKernelGGL(k_group_pass<1>, grid, block, lds_bytes, st, row_keys, cnt, (int32_t)n_rows, S,
-                           (int32_t)rows_per_block, g_log2, N, bins_cap, w.cursor, w.perm, (const int32_t *)nullptr, tile_len,
-                           (KnTile *)nullptr, (int32_t *)nullptr, DBG);
+        hipLaunchKernelGGL(k_group_pass<1>, grid, block, lds_bytes, st, row_keys, cnt, ctl, N, bins_cap, w.cursor, w.perm,
+                           (const int32_t *)nullptr, tile_len, (KnTile *)nullptr, (int32_t *)nullptr, DBG);
         KN_CHECK_LAUNCH();
     }
     out->perm = w.perm;

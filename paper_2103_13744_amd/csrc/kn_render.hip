@@ -321,6 +321,24 @@ __global__ void __launch_bounds__(RAY_BLOCK)
     if (threadIdx.x == 0) blk_sum[blockIdx.x] = total;
 }
 
+// Device-side description of a wave, written by the kernel that ends the previous one, so that the host can
+// enqueue a wave before it knows how many rays are left: ctl[0] = rows of the live list, ctl[1] = S (samples
+// per ray of this wave, = slots per row), ctl[2] = the schedule value S was derived from.
+struct WaveSchedule {
+    int32_t first, growth, K;
+    int64_t budget; // slots shared by the live rays of a wave
+};
+__device__ __forceinline__ void set_wave(int32_t *ctl, int32_t n_rows, int32_t s_sched, const WaveSchedule &sched)
+{
+    int64_t S = s_sched;
+    if (n_rows > 0 && S > sched.budget / n_rows) S = sched.budget / n_rows;
+    if (S > sched.K) S = sched.K;
+    if (S < 1) S = 1;
+    ctl[0] = n_rows;
+    ctl[1] = (int32_t)S;
+    ctl[2] = s_sched;
+}
+
 // {value, then sequence number} into the host-visible mailbox; the host polls the sequence number
 __device__ __forceinline__ void post_mailbox(unsigned long long *mailbox, unsigned long long seq, unsigned long long value)
 {
@@ -334,7 +352,7 @@ __device__ __forceinline__ void post_mailbox(unsigned long long *mailbox, unsign
 __global__ void __launch_bounds__(RAY_BLOCK)
     k_first_live(const int32_t *__restrict__ alive, const int32_t *__restrict__ blk_sum, int64_t R,
                  int32_t *__restrict__ live_out, int32_t *__restrict__ alive_out, int32_t *__restrict__ n_live,
-                 unsigned long long *mailbox, unsigned long long seq)
+                 int32_t *__restrict__ ctl, WaveSchedule sched, unsigned long long *mailbox, unsigned long long seq)
 {
     __shared__ int32_t lds[RAY_BLOCK / KN_WAVE];
     const int64_t r = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -348,6 +366,7 @@ __global__ void __launch_bounds__(RAY_BLOCK)
     }
     if (blockIdx.x == gridDim.x - 1 && threadIdx.x == 0) {
         *n_live = before + total;
+        set_wave(ctl, before + total, sched.first, sched);
         post_mailbox(mailbox, seq, (unsigned long long)(before + total));
     }
 }
@@ -357,11 +376,13 @@ __global__ void __launch_bounds__(RAY_BLOCK)
 // the bins it touched to the global histogram that the grouping of this wave starts from.
 __global__ void __launch_bounds__(256)
     k_march_wave(MarchParams p, const float *__restrict__ rays_o, const float *__restrict__ rays_d,
-                 const int32_t *__restrict__ live, const int32_t *__restrict__ alive, int32_t n_live, int32_t S,
+                 const int32_t *__restrict__ live, const int32_t *__restrict__ alive, const int32_t *__restrict__ ctl,
                  int32_t kbits, RayState s, int32_t *__restrict__ row_keys, uint32_t *__restrict__ row_rec,
                  int32_t *__restrict__ cnt, int32_t *__restrict__ hist, int32_t n_bins)
 {
     extern __shared__ int32_t bins[]; // [n_bins] when hist is given
+    const int32_t n_live = ctl[0], S = ctl[1];
+    if ((int64_t)blockIdx.x * (256 / MARCH_G) >= n_live) return; // the grid is sized for an upper bound of the rows
     if (hist) {
         for (int32_t b = threadIdx.x; b < n_bins; b += 256) bins[b] = 0;
         __syncthreads();
@@ -405,8 +426,8 @@ __global__ void __launch_bounds__(256)
 // blend itself is the sequential recurrence of the definition (same operation order for every
 // wave cut), run redundantly by all lanes of the group on values broadcast through LDS.
 __global__ void __launch_bounds__(256)
-    k_composite_wave(const int32_t *__restrict__ live, int32_t n_live, const int32_t *__restrict__ cnt, int32_t S,
-                     const float *__restrict__ out4, float step, float eps, float bg0,
+    k_composite_wave(const int32_t *__restrict__ live, const int32_t *__restrict__ ctl, int32_t rows_cap,
+                     const int32_t *__restrict__ cnt, const float *__restrict__ out4, float step, float eps, float bg0,
                      float bg1, float bg2, RayState s, float *__restrict__ rgb_out, int32_t *__restrict__ alive,
                      int32_t *__restrict__ partials /*3 * gridDim.x*/, int32_t *__restrict__ zero, int32_t n_zero)
 {
@@ -414,10 +435,14 @@ __global__ void __launch_bounds__(256)
     for (int64_t z = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; z < n_zero; z += (int64_t)gridDim.x * blockDim.x) zero[z] = 0;
     typedef float f4 __attribute__((ext_vector_type(4)));
     __shared__ f4 stage[256];
+    const int32_t n_live = ctl[0], S = ctl[1];
     const int32_t i = (int32_t)(((int64_t)blockIdx.x * blockDim.x + threadIdx.x) / MARCH_G);
     const int gl = threadIdx.x & (MARCH_G - 1);
     f4 *grp_stage = stage + (threadIdx.x & ~(MARCH_G - 1));
     int32_t blended = 0, evaluated = 0, survivors = 0;
+    // the grid covers rows_cap >= n_live rows; the flags of the rows beyond the list are cleared so that the
+    // compaction that follows can run over the same upper bound
+    if (i >= n_live && i < rows_cap && gl == 0) alive[i] = 0;
     if (i < n_live && alive[i]) {
         const int32_t r = live[i];
         const int32_t n = cnt[i];
@@ -489,9 +514,12 @@ __global__ void __launch_bounds__(256)
 }
 
 // one block: counters[0] += evaluated, counters[1] += blended, counters[2] = survivors of this wave
+// ... counters[3] += slots of this wave, counters[4] += 1 if the wave had rows; writes the next wave's control
 __global__ void __launch_bounds__(256) k_sum_partials(const int32_t *__restrict__ partials, int32_t n_blocks,
                                                       unsigned long long *__restrict__ counters,
-                                                      unsigned long long *mailbox, unsigned long long seq)
+                                                      const int32_t *__restrict__ ctl, int32_t *__restrict__ ctl_next,
+                                                      WaveSchedule sched, unsigned long long *mailbox,
+                                                      unsigned long long seq)
 {
     __shared__ unsigned long long red[3][256 / KN_WAVE];
     unsigned long long v[3] = {0ull, 0ull, 0ull};
@@ -526,10 +554,17 @@ __global__ void __launch_bounds__(256) k_sum_partials(const int32_t *__restrict_
     }
     __syncthreads();
     if (threadIdx.x == 0) {
+        counters[3] += (unsigned long long)ctl[0] * (unsigned long long)ctl[1];
+        counters[4] += ctl[0] > 0 ? 1ull : 0ull;
+        // the next wave: the survivors (the live list is compacted in between), schedule value grown
+        const int64_t grown = (int64_t)ctl[2] * sched.growth;
+        set_wave(ctl_next, (int32_t)counters[2], (int32_t)(grown < sched.K ? grown : sched.K), sched);
         // running totals ride along so that the host never has to read the counters back
         if (mailbox) {
             __hip_atomic_store(&mailbox[2], counters[0], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
             __hip_atomic_store(&mailbox[3], counters[1], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+            __hip_atomic_store(&mailbox[4], counters[3], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+            __hip_atomic_store(&mailbox[5], counters[4], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
         }
         post_mailbox(mailbox, seq, counters[2]);
     }
@@ -600,8 +635,11 @@ MarchParams make_params(const kn_scene *sc, float t_near, float step, int32_t K)
 
 // Wave schedule.  Most rays end (early termination or leaving the content) within their first few dozen
 // kept samples, and a wave costs several kernel launches whatever its size: a generous first wave and one
-// large step afterwards (the rest of the ray for the few survivors) measured fastest at 800x800.
-constexpr int DEFAULT_FIRST_WAVE = 48, DEFAULT_SLOTS = 48, DEFAULT_GROWTH = 32;
+// large step afterwards (the rest of the ray for the few survivors) measured fastest at 800x800.  The slot
+// budget (slots per ray of the frame, shared by the live rays of a wave) only sizes the workspace; when it
+// covers K slots for every ray that reaches content, the second wave is known to finish the frame and the
+// call returns without waiting for it.
+constexpr int DEFAULT_FIRST_WAVE = 48, DEFAULT_SLOTS = 128, DEFAULT_GROWTH = 32;
 int g_first_wave_samples = DEFAULT_FIRST_WAVE;
 int g_slots_per_ray = DEFAULT_SLOTS;
 int g_wave_growth = DEFAULT_GROWTH;
@@ -657,7 +695,7 @@ static int kbits_for(int32_t K)
 
 // layout of the render workspace
 struct RenderWs {
-    int32_t *partials, *blk_sum, *live_a, *live_b, *cnt, *alive_a, *alive_b, *pos, *scan_tmp, *n_live_dev, *row_keys;
+    int32_t *partials, *blk_sum, *live_a, *live_b, *cnt, *alive_a, *alive_b, *pos, *scan_tmp, *n_live_dev, *row_keys, *ctl;
     uint32_t *row_rec;
     float *T, *C, *out4;
     int32_t *k_next, *k_end;
@@ -680,7 +718,8 @@ static void carve_render(KnCarver &ws, int64_t R, int64_t slots, RenderWs &w)
     w.C = ws.carve<float>(3 * R);
     w.k_next = ws.carve<int32_t>(R);
     w.k_end = ws.carve<int32_t>(R);
-    w.counters = ws.carve<unsigned long long>(4);
+    w.counters = ws.carve<unsigned long long>(8);
+    w.ctl = ws.carve<int32_t>(8); // two wave-control blocks of 4 ints, used alternately
     w.row_keys = ws.carve<int32_t>(slots);
     w.row_rec = ws.carve<uint32_t>(slots);
     w.out4 = ws.carve<float>(4 * slots);
@@ -736,7 +775,9 @@ extern "C" int kn_render(const kn_scene *sc, void *stream, const float *rays_o, 
     }
     if (R == 0) return KN_OK;
     const int kbits = kbits_for(K > 1 ? K : 2);
-    if (R > (1ll << (32 - kbits)) || R > 0x7fffffffLL / g_slots_per_ray / MARCH_G) return KN_E_UNSUPPORTED;
+    if (R > (1ll << (32 - kbits)) || R > 0x7fffffffLL / g_slots_per_ray ||
+        R > 0x7fffffffLL / MARCH_G)
+        return KN_E_UNSUPPORTED; // slot numbers and row * lanes are 32-bit
     if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < kn_render_ws_bytes(sc, R)) return KN_E_WORKSPACE;
 
     hipStream_t st = (hipStream_t)stream;
@@ -757,19 +798,17 @@ extern "C" int kn_render(const kn_scene *sc, void *stream, const float *rays_o, 
     KnStageTimer tm(st);
     tm.begin();
     kn_scene *scm = const_cast<kn_scene *>(sc); // the mailbox sequence number is the only mutable scene state
+    const WaveSchedule sched{g_first_wave_samples, g_wave_growth, K > 0 ? K : 1, budget};
     hipLaunchKernelGGL(k_render_init, dim3(rblocks), dim3(RAY_BLOCK), 0, st, p, rays_o, rays_d, R, rs, w.alive_b, w.blk_sum,
-                       bg[0], bg[1], bg[2], rgb_out, (int32_t *)w.counters, 8, gw.hist, R >= n_hist ? (int32_t)n_hist : 0);
+                       bg[0], bg[1], bg[2], rgb_out, (int32_t *)w.counters, 16, gw.hist, R >= n_hist ? (int32_t)n_hist : 0);
     KN_CHECK_LAUNCH();
     if (R < n_hist) KN_TRY(kn_fill_i32(st, gw.hist, n_hist, 0));
-    KN_CHECK_LAUNCH();
+    if (R < 16) KN_TRY(kn_fill_i32(st, (int32_t *)w.counters, 16, 0));
     unsigned long long seq = ++scm->mailbox_seq;
     hipLaunchKernelGGL(k_first_live, dim3(rblocks), dim3(RAY_BLOCK), 0, st, w.alive_b, w.blk_sum, R, w.live_a, w.alive_a,
-                       w.n_live_dev, sc->mailbox_dev, seq);
+                       w.n_live_dev, w.ctl, sched, sc->mailbox_dev, seq);
     KN_CHECK_LAUNCH();
     tm.mark(KN_ST_SETUP);
-    long long first = 0;
-    KN_TRY(wait_count(sc, st, seq, w.n_live_dev, sizeof(int32_t), &first));
-    if (first < 0 || first > R) return KN_E_HIP;
 
     KnSampleSrc src{};
     src.points = nullptr;
@@ -784,63 +823,96 @@ extern "C" int kn_render(const kn_scene *sc, void *stream, const float *rays_o, 
 
     const int tile_len = kn_mlp_tile_len(sc);
     int32_t *live = w.live_a, *live_next = w.live_b, *alive = w.alive_a, *alive_next = w.alive_b;
-    int64_t n_rows = first;  // entries of the live list (some may already be retired)
-    int64_t n_alive = first; // rays still being rendered
-    int64_t waves = 0, slots_total = 0;
-    int64_t S_sched = g_first_wave_samples;
-    while (n_alive > 0) {
-        tm.begin();
-        if (n_alive * 2 < n_rows) { // drop retired rows once they are the majority
-            KN_TRY(kn_exclusive_scan_i32(st, alive, w.pos, n_rows, w.scan_tmp, nullptr));
-            hipLaunchKernelGGL(k_compact_live, dim3((unsigned)kn_div_up(n_rows, 256)), dim3(256), 0, st, live, alive, w.pos,
-                               (int32_t)n_rows, live_next, alive_next);
-            KN_CHECK_LAUNCH();
-            int32_t *t = live; live = live_next; live_next = t;
-            t = alive; alive = alive_next; alive_next = t;
-            n_rows = n_alive;
-            tm.mark(KN_ST_SETUP);
-        }
-        // samples per ray in this wave: triples from wave to wave, bounded by the slot budget
-        int64_t S = S_sched;
-        if (S > budget / n_rows) S = budget / n_rows;
-        if (S > K) S = K;
-        if (S < 1) S = 1;
-        const int64_t Mw = n_rows * S; // upper bound of this wave's sample count
-        hipLaunchKernelGGL(k_march_wave, dim3((unsigned)kn_div_up(n_rows * MARCH_G, 256)), dim3(256),
-                           fused_hist ? sizeof(int32_t) * (size_t)sc->N : 0, st, p, rays_o, rays_d, live, alive, (int32_t)n_rows,
-                           (int32_t)S, kbits, rs, w.row_keys, w.row_rec, w.cnt, fused_hist ? gw.hist : (int32_t *)nullptr,
-                           sc->N);
+    int wave_no = 0; // waves enqueued so far; wave i reads control block i % 2, its last kernel writes the other one
+    // The shape of a wave (rows, samples per ray) lives in device memory, so a wave can be enqueued before the
+    // host knows how many rays the previous one left: `rows_cap` is the host's upper bound, which sizes the grids.
+    auto march = [&](int64_t rows_cap) -> int {
+        const int32_t *ctl = w.ctl + 4 * (wave_no & 1);
+        hipLaunchKernelGGL(k_march_wave, dim3((unsigned)kn_div_up(rows_cap * MARCH_G, 256)), dim3(256),
+                           fused_hist ? sizeof(int32_t) * (size_t)sc->N : 0, st, p, rays_o, rays_d, live, alive, ctl, kbits, rs,
+                           w.row_keys, w.row_rec, w.cnt, fused_hist ? gw.hist : (int32_t *)nullptr, sc->N);
         KN_CHECK_LAUNCH();
         tm.mark(KN_ST_MARCH);
+        return KN_OK;
+    };
+    auto rest_of_wave = [&](int64_t rows_cap) -> int {
+        int32_t *ctl = w.ctl + 4 * (wave_no & 1), *ctl_next = w.ctl + 4 * ((wave_no + 1) & 1);
         KnBucketOut bo;
-        KN_TRY(kn_group_run(st, w.row_keys, w.cnt, n_rows, (int32_t)S, sc->N, tile_len, gw, fused_hist, &bo));
+        KN_TRY(kn_group_run(st, w.row_keys, w.cnt, ctl, rows_cap, sc->N, tile_len, gw, fused_hist, &bo));
         tm.mark(KN_ST_BUCKET);
-        KN_TRY(kn_mlp_launch(sc, st, src, bo, Mw, nullptr, nullptr));
+        KN_TRY(kn_mlp_launch(sc, st, src, bo, budget, nullptr, nullptr));
         tm.mark(KN_ST_MLP);
-        const int32_t cblocks = (int32_t)kn_div_up(n_rows * MARCH_G, 256);
-        hipLaunchKernelGGL(k_composite_wave, dim3((unsigned)cblocks), dim3(256), 0, st, live, (int32_t)n_rows, w.cnt, (int32_t)S,
+        const int32_t cblocks = (int32_t)kn_div_up(rows_cap * MARCH_G, 256);
+        hipLaunchKernelGGL(k_composite_wave, dim3((unsigned)cblocks), dim3(256), 0, st, live, ctl, (int32_t)rows_cap, w.cnt,
                            w.out4, step, term_eps, bg[0], bg[1], bg[2], rs, rgb_out, alive, w.partials, gw.hist,
                            fused_hist ? (int32_t)n_hist : 0);
         KN_CHECK_LAUNCH();
         seq = ++scm->mailbox_seq;
-        hipLaunchKernelGGL(k_sum_partials, dim3(1), dim3(256), 0, st, w.partials, cblocks, w.counters, sc->mailbox_dev, seq);
+        hipLaunchKernelGGL(k_sum_partials, dim3(1), dim3(256), 0, st, w.partials, cblocks, w.counters, ctl, ctl_next, sched,
+                           sc->mailbox_dev, seq);
         KN_CHECK_LAUNCH();
         tm.mark(KN_ST_BLEND);
-        long long next = 0;
-        KN_TRY(wait_count(sc, st, seq, w.counters + 2, sizeof(unsigned long long), &next));
         if (tm.on) g_kn_profile.mlp_launches += 1;
-        if (next < 0 || next > n_alive) return KN_E_HIP; // cannot happen; guards the loop
-        ++waves;
-        slots_total += Mw;
-        n_alive = (int64_t)next;
-        if (S_sched < K) S_sched *= g_wave_growth;
+        ++wave_no;
+        return KN_OK;
+    };
+    // drop the retired rows of the live list (deterministic order); works on the upper bound of its length
+    auto compact = [&](int64_t rows_cap) -> int {
+        tm.begin();
+        KN_TRY(kn_exclusive_scan_i32(st, alive, w.pos, rows_cap, w.scan_tmp, nullptr));
+        hipLaunchKernelGGL(k_compact_live, dim3((unsigned)kn_div_up(rows_cap, 256)), dim3(256), 0, st, live, alive, w.pos,
+                           (int32_t)rows_cap, live_next, alive_next);
+        KN_CHECK_LAUNCH();
+        int32_t *t = live; live = live_next; live_next = t;
+        t = alive; alive = alive_next; alive_next = t;
+        tm.mark(KN_ST_SETUP);
+        return KN_OK;
+    };
+
+    // first wave: its march is enqueued for all R rays while the host is still waiting for the number of live rays
+    tm.begin();
+    KN_TRY(march(R));
+    long long first = 0;
+    KN_TRY(wait_count(sc, st, seq, w.n_live_dev, sizeof(int32_t), &first));
+    if (first < 0 || first > R) return KN_E_HIP;
+    long long n_alive = first;
+    if (first > 0) {
+        KN_TRY(rest_of_wave(first));
+        int64_t list_cap = first; // upper bound of the length of the current live list
+        // Further waves.  The second one is enqueued right behind the first (its shape is computed on the device);
+        // after that the host looks at the survivor count before it enqueues more.
+        bool speculative = (int64_t)g_first_wave_samples < (int64_t)K;
+        // With K slots for each of the `first` rays the second wave takes every ray to its end: nothing to wait for
+        // (unless the caller wants the counters of this frame).
+        const bool second_wave_ends_it = speculative && first * (long long)K <= budget &&
+                                         (int64_t)g_first_wave_samples * g_wave_growth >= (int64_t)K;
+        const bool want_counts = (g_kn_profile_on && g_only_stage == KN_ST_NONE) || stats != nullptr;
+        while (true) {
+            if (wave_no == 2 && second_wave_ends_it && !want_counts) break;
+            int64_t next_cap = list_cap; // survivors <= rows of the list they come from
+            if (!speculative) {
+                KN_TRY(wait_count(sc, st, seq, w.counters + 2, sizeof(unsigned long long), &n_alive));
+                if (n_alive < 0 || n_alive > list_cap) return KN_E_HIP; // cannot happen; guards the loop
+                if (n_alive == 0) break;
+                next_cap = n_alive;
+            }
+            speculative = false;
+            KN_TRY(compact(list_cap)); // scans the old list, writes the new one
+            list_cap = next_cap;
+            tm.begin();
+            KN_TRY(march(list_cap));
+            KN_TRY(rest_of_wave(list_cap));
+        }
     }
-    if (g_kn_profile_on || stats) {
-        unsigned long long c[2] = {0ull, 0ull};
-        if (waves > 0 && sc->mailbox_host && __atomic_load_n((const unsigned long long *)&sc->mailbox_host[0], __ATOMIC_ACQUIRE) == seq) {
+    if ((g_kn_profile_on && g_only_stage == KN_ST_NONE) || stats) {
+        unsigned long long c[5] = {0ull, 0ull, 0ull, 0ull, 0ull}; // evaluated, blended, survivors, slots, waves
+        if (wave_no > 0 && sc->mailbox_host &&
+            __atomic_load_n((const unsigned long long *)&sc->mailbox_host[0], __ATOMIC_ACQUIRE) == seq) {
             c[0] = __atomic_load_n((const unsigned long long *)&sc->mailbox_host[2], __ATOMIC_RELAXED);
             c[1] = __atomic_load_n((const unsigned long long *)&sc->mailbox_host[3], __ATOMIC_RELAXED);
-        } else if (waves > 0) {
+            c[3] = __atomic_load_n((const unsigned long long *)&sc->mailbox_host[4], __ATOMIC_RELAXED);
+            c[4] = __atomic_load_n((const unsigned long long *)&sc->mailbox_host[5], __ATOMIC_RELAXED);
+        } else if (wave_no > 0) {
             KN_HIP(hipMemcpyAsync(c, w.counters, sizeof(c), hipMemcpyDeviceToHost, st));
             KN_HIP(hipStreamSynchronize(st));
         }
@@ -850,10 +922,10 @@ extern "C" int kn_render(const kn_scene *sc, void *stream, const float *rays_o, 
             g_kn_profile.calls += 1;
         }
         if (stats) {
-            stats->waves = waves;
+            stats->waves = (int64_t)c[4];
             stats->samples_evaluated = (int64_t)c[0];
             stats->samples_blended = (int64_t)c[1];
-            stats->slots = slots_total;
+            stats->slots = (int64_t)c[3];
         }
     }
     return KN_OK;
