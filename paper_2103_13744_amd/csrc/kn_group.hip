@@ -120,17 +120,32 @@ __global__ void __launch_bounds__(GROUP_THREADS)
         }
         if (run_key >= 0) f(run_key, run_j, run_len);
     };
+    // One pass over the rows of the workgroup.  The sample count and the first two chunks of the next set of rows
+    // are fetched before the current set is processed, so that only the first set waits for memory.
+    struct RowLoad { int32_t c; int64_t base; i4 va, vb; };
+    auto fetch_rows = [&](int32_t rs) -> RowLoad {
+        RowLoad q;
+        const int32_t row = rs + sub;
+        const int32_t i = r0 + min(row, nr - 1);
+        q.base = (int64_t)i * S;
+        q.c = row < nr ? cnt[i] : 0;
+        q.va = load_chunk(q.base, g);
+        q.vb = load_chunk(q.base, g + G);
+        return q;
+    };
     auto sweep = [&](int32_t w0, int32_t nb, auto &&f) {
+        RowLoad next = fetch_rows(0);
         for (int32_t rs = 0; rs < nr; rs += rows_per_set) {
-            const int32_t row = rs + sub;
-            const int32_t i = r0 + min(row, nr - 1);
-            const int64_t base = (int64_t)i * S;
-            const int32_t c = row < nr ? cnt[i] : 0;
-            for (int32_t ch = g;; ch += 2 * G) {
-                const i4 va = load_chunk(base, ch), vb = load_chunk(base, ch + G); // issued before c is needed
-                if (4 * ch >= c) break;
-                chunk_runs(va, 4 * ch, c, w0, nb, [&](int32_t k, int32_t j, int32_t len) { f(k, base + j, len); });
-                chunk_runs(vb, 4 * (ch + G), c, w0, nb, [&](int32_t k, int32_t j, int32_t len) { f(k, base + j, len); });
+            const RowLoad cur = next;
+            if (rs + rows_per_set < nr) next = fetch_rows(rs + rows_per_set);
+            i4 va = cur.va, vb = cur.vb;
+            for (int32_t ch = g; 4 * ch < cur.c; ch += 2 * G) {
+                if (ch != g) { // rows longer than two chunks per lane
+                    va = load_chunk(cur.base, ch);
+                    vb = load_chunk(cur.base, ch + G);
+                }
+                chunk_runs(va, 4 * ch, cur.c, w0, nb, [&](int32_t k, int32_t j, int32_t len) { f(k, cur.base + j, len); });
+                chunk_runs(vb, 4 * (ch + G), cur.c, w0, nb, [&](int32_t k, int32_t j, int32_t len) { f(k, cur.base + j, len); });
             }
         }
     };
@@ -140,6 +155,7 @@ __global__ void __launch_bounds__(GROUP_THREADS)
         for (int32_t b = tid; b < nb; b += GROUP_THREADS) bins[b] = 0;
         if (tid == 0) n_touched = 0;
         __syncthreads();
+        GT(5);
         if (nr > 0) sweep(w0, nb, [&](int32_t k, int64_t, int32_t len) { atomicAdd(&bins[k], len); });
         __syncthreads();
         GT(1);
@@ -170,11 +186,40 @@ __global__ void __launch_bounds__(GROUP_THREADS)
             int32_t total;
             int32_t off = kn_block_exclusive_scan(mine, scan_lds, total);
             fused_off0 = off;
-            for (int32_t b0 = 0; b0 < N; b0 += GROUP_THREADS) { // uniform trip count: ballots inside
-                const int32_t b = b0 + tid;
-                list_bin(b, b < N && bins[b] > 0, off);
-                off += b < N ? hcl[b] : 0;
+            GT(6);
+            for (int32_t b0 = 0; b0 < N; b0 += 4 * GROUP_THREADS) { // uniform trip count: ballots inside
+                // four bins per thread and step: the LDS reads are issued together, one list reservation per step
+                int32_t cnt_b[4], hist_b[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const int32_t b = b0 + u * GROUP_THREADS + tid;
+                    cnt_b[u] = b < N ? bins[b] : 0;
+                    hist_b[u] = b < N ? hcl[b] : 0;
+                }
+                unsigned long long m[4];
+                int32_t wave_hits = 0;
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    m[u] = __ballot(cnt_b[u] > 0);
+                    wave_hits += __builtin_popcountll(m[u]);
+                }
+                int32_t at = 0;
+                if (wave_hits) {
+                    if (lane == 0) at = atomicAdd(&n_touched, wave_hits);
+                    at = __shfl(at, 0, KN_WAVE);
+                }
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const int32_t mine_at = at + __builtin_popcountll(m[u] & ((1ull << lane) - 1ull));
+                    if (cnt_b[u] > 0 && mine_at < GROUP_LIST) {
+                        touched[mine_at] = b0 + u * GROUP_THREADS + tid;
+                        touched_off[mine_at] = off;
+                    }
+                    at += __builtin_popcountll(m[u]);
+                    off += hist_b[u];
+                }
             }
+            GT(7);
             // tile list: slice k = the bins 256 k .. 256 k + 255, one workgroup per slice (tile positions follow
             // the same layout order as the offsets)
             for (int64_t slice = blockIdx.x; slice * GROUP_THREADS < N; slice += gridDim.x) {
