@@ -374,42 +374,69 @@ __global__ void __launch_bounds__(RAY_BLOCK)
 // MARCH_G lanes per live ray: collect up to S kept samples into row i of the wave's row buffers.
 // With `hist` the workgroup also counts its samples per network in LDS (n_bins ints of dynamic LDS) and adds
 // the bins it touched to the global histogram that the grouping of this wave starts from.
+//
+// From the second wave on (`blk_off` given) the kernel also compacts the live list while it reads it: it runs over
+// the rows of the previous wave's list (`old_ctl`), the survivors among the 16 rows of a workgroup get the new row
+// numbers blk_off[workgroup] + rank (ascending, so the order of the list is kept), and the new list is written to
+// live_out / alive_out.  blk_off comes from k_sum_partials (prefix sums of the survivor counts that the blend of
+// the same 16-row groups left).
 __global__ void __launch_bounds__(256)
     k_march_wave(MarchParams p, const float *__restrict__ rays_o, const float *__restrict__ rays_d,
                  const int32_t *__restrict__ live, const int32_t *__restrict__ alive, const int32_t *__restrict__ ctl,
                  int32_t kbits, RayState s, int32_t *__restrict__ row_keys, uint32_t *__restrict__ row_rec,
-                 int32_t *__restrict__ cnt, int32_t *__restrict__ hist, int32_t n_bins)
+                 int32_t *__restrict__ cnt, int32_t *__restrict__ hist, int32_t n_bins, const int32_t *__restrict__ old_ctl,
+                 const int32_t *__restrict__ blk_off, int32_t *__restrict__ live_out, int32_t *__restrict__ alive_out)
 {
     extern __shared__ int32_t bins[]; // [n_bins] when hist is given
-    const int32_t n_live = ctl[0], S = ctl[1];
-    if ((int64_t)blockIdx.x * (256 / MARCH_G) >= n_live) return; // the grid is sized for an upper bound of the rows
+    __shared__ int32_t flags[256 / MARCH_G];
+    const int32_t n_in = blk_off ? old_ctl[0] : ctl[0]; // rows of the list that is read
+    const int32_t S = ctl[1];
+    if ((int64_t)blockIdx.x * (256 / MARCH_G) >= n_in) return; // the grid is sized for an upper bound of the rows
+    const int32_t i_in = (int32_t)(((int64_t)blockIdx.x * blockDim.x + threadIdx.x) / MARCH_G);
+    const int gl = threadIdx.x & (MARCH_G - 1), grp = threadIdx.x / MARCH_G;
+    const bool lives = i_in < n_in && alive[i_in] != 0;
+    int32_t i = i_in; // row of this ray in the wave's buffers
+    if (blk_off) {
+        if (gl == 0) flags[grp] = lives ? 1 : 0;
+        __syncthreads();
+        int32_t rank = 0, any = 0;
+#pragma unroll
+        for (int q = 0; q < 256 / MARCH_G; ++q) {
+            const int32_t f = flags[q];
+            any += f;
+            if (q < grp) rank += f;
+        }
+        if (any == 0) return; // (uniform) all 16 rays of the workgroup have retired
+        i = blk_off[blockIdx.x] + rank;
+    }
     if (hist) {
         for (int32_t b = threadIdx.x; b < n_bins; b += 256) bins[b] = 0;
         __syncthreads();
     }
-    const int32_t i = (int32_t)(((int64_t)blockIdx.x * blockDim.x + threadIdx.x) / MARCH_G);
-    const int gl = threadIdx.x & (MARCH_G - 1);
-    if (i < n_live) {
-        if (!alive[i]) { // retired rows stay in the list until the next compaction
-            if (gl == 0) cnt[i] = 0;
-        } else {
-            const int32_t r = live[i];
-            const float o[3] = {rays_o[3 * (int64_t)r], rays_o[3 * (int64_t)r + 1], rays_o[3 * (int64_t)r + 2]};
-            const float d[3] = {rays_d[3 * (int64_t)r], rays_d[3 * (int64_t)r + 1], rays_d[3 * (int64_t)r + 2]};
-            const GridFast gn = make_fast(p.net), go = make_fast(p.occ);
-            int32_t k = s.k_next[r];
-            const int32_t k_hi = s.k_end[r];
-            int32_t *kr = row_keys + (int64_t)i * S;
-            uint32_t *rr = row_rec + (int64_t)i * S;
-            const int32_t n = march_group(p, gn, go, o, d, k, k_hi, S, gl, [&](int j, int32_t kk, int32_t cell) {
-                kr[j] = cell;
-                rr[j] = ((uint32_t)r << kbits) | (uint32_t)kk;
-                if (hist) atomicAdd(&bins[cell], 1);
-            });
-            if (gl == 0) {
-                s.k_next[r] = k;
-                cnt[i] = n;
-            }
+    if (!lives) {
+        // without compaction retired rows stay in the list: they get no samples
+        if (!blk_off && i_in < n_in && gl == 0) cnt[i_in] = 0;
+    } else {
+        const int32_t r = live[i_in];
+        if (blk_off && gl == 0) {
+            live_out[i] = r;
+            alive_out[i] = 1;
+        }
+        const float o[3] = {rays_o[3 * (int64_t)r], rays_o[3 * (int64_t)r + 1], rays_o[3 * (int64_t)r + 2]};
+        const float d[3] = {rays_d[3 * (int64_t)r], rays_d[3 * (int64_t)r + 1], rays_d[3 * (int64_t)r + 2]};
+        const GridFast gn = make_fast(p.net), go = make_fast(p.occ);
+        int32_t k = s.k_next[r];
+        const int32_t k_hi = s.k_end[r];
+        int32_t *kr = row_keys + (int64_t)i * S;
+        uint32_t *rr = row_rec + (int64_t)i * S;
+        const int32_t n = march_group(p, gn, go, o, d, k, k_hi, S, gl, [&](int j, int32_t kk, int32_t cell) {
+            kr[j] = cell;
+            rr[j] = ((uint32_t)r << kbits) | (uint32_t)kk;
+            if (hist) atomicAdd(&bins[cell], 1);
+        });
+        if (gl == 0) {
+            s.k_next[r] = k;
+            cnt[i] = n;
         }
     }
     if (hist) { // the few bins this workgroup met go to the global histogram
@@ -518,8 +545,8 @@ __global__ void __launch_bounds__(256)
 __global__ void __launch_bounds__(256) k_sum_partials(const int32_t *__restrict__ partials, int32_t n_blocks,
                                                       unsigned long long *__restrict__ counters,
                                                       const int32_t *__restrict__ ctl, int32_t *__restrict__ ctl_next,
-                                                      WaveSchedule sched, unsigned long long *mailbox,
-                                                      unsigned long long seq)
+                                                      WaveSchedule sched, int32_t *__restrict__ blk_off,
+                                                      unsigned long long *mailbox, unsigned long long seq)
 {
     __shared__ unsigned long long red[3][256 / KN_WAVE];
     unsigned long long v[3] = {0ull, 0ull, 0ull};
@@ -553,6 +580,49 @@ __global__ void __launch_bounds__(256) k_sum_partials(const int32_t *__restrict_
         if (threadIdx.x == 2) counters[2] = t; else counters[threadIdx.x] += t;
     }
     __syncthreads();
+    // exclusive prefix sums of the survivors per 16-row group: the next wave's march compacts the list with them.
+    // Global memory is read and written with consecutive threads on consecutive entries; the contiguous 32 entries
+    // that a thread scans come through LDS (index + index / 32 keeps both access patterns free of bank conflicts).
+    if (counters[2] != 0) { // (uniform) no survivors: no further wave, nothing to compact
+        constexpr int PER = 32, ROUND = 256 * PER;
+        __shared__ int32_t tr[ROUND + ROUND / 32];
+        __shared__ int32_t scan_lds[256 / KN_WAVE];
+        const int32_t *surv = partials + 2 * (int64_t)n_blocks;
+        const int tid = threadIdx.x;
+        int32_t carry = 0;
+        for (int32_t b0 = 0; b0 < n_blocks; b0 += ROUND) {
+            int32_t v[PER];
+#pragma unroll
+            for (int u = 0; u < PER; ++u) v[u] = surv[min(b0 + u * 256 + tid, n_blocks - 1)]; // loads issued together
+#pragma unroll
+            for (int u = 0; u < PER; ++u) {
+                const int e = u * 256 + tid;
+                tr[e + (e >> 5)] = b0 + e < n_blocks ? v[u] : 0;
+            }
+            __syncthreads();
+            int32_t sum = 0;
+#pragma unroll
+            for (int u = 0; u < PER; ++u) {
+                v[u] = tr[PER * tid + u + tid];
+                sum += v[u];
+            }
+            int32_t total;
+            int32_t off = carry + kn_block_exclusive_scan(sum, scan_lds, total);
+#pragma unroll
+            for (int u = 0; u < PER; ++u) {
+                tr[PER * tid + u + tid] = off;
+                off += v[u];
+            }
+            carry += total;
+            __syncthreads();
+#pragma unroll
+            for (int u = 0; u < PER; ++u) {
+                const int e = u * 256 + tid;
+                if (b0 + e < n_blocks) blk_off[b0 + e] = tr[e + (e >> 5)];
+            }
+            __syncthreads();
+        }
+    }
     if (threadIdx.x == 0) {
         counters[3] += (unsigned long long)ctl[0] * (unsigned long long)ctl[1];
         counters[4] += ctl[0] > 0 ? 1ull : 0ull;
@@ -567,17 +637,6 @@ __global__ void __launch_bounds__(256) k_sum_partials(const int32_t *__restrict_
             __hip_atomic_store(&mailbox[5], counters[4], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
         }
         post_mailbox(mailbox, seq, counters[2]);
-    }
-}
-
-__global__ void k_compact_live(const int32_t *__restrict__ live_in, const int32_t *__restrict__ alive,
-                               const int32_t *__restrict__ pos, int32_t n_live, int32_t *__restrict__ live_out,
-                               int32_t *__restrict__ alive_out)
-{
-    const int32_t i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < n_live && alive[i]) {
-        live_out[pos[i]] = live_in[i];
-        alive_out[pos[i]] = 1;
     }
 }
 
@@ -695,7 +754,7 @@ static int kbits_for(int32_t K)
 
 // layout of the render workspace
 struct RenderWs {
-    int32_t *partials, *blk_sum, *live_a, *live_b, *cnt, *alive_a, *alive_b, *pos, *scan_tmp, *n_live_dev, *row_keys, *ctl;
+    int32_t *partials, *blk_sum, *blk_off, *live_a, *live_b, *cnt, *alive_a, *alive_b, *n_live_dev, *row_keys, *ctl;
     uint32_t *row_rec;
     float *T, *C, *out4;
     int32_t *k_next, *k_end;
@@ -706,13 +765,12 @@ static void carve_render(KnCarver &ws, int64_t R, int64_t slots, RenderWs &w)
 {
     w.partials = ws.carve<int32_t>(3 * kn_div_up(R * MARCH_G, 256));
     w.blk_sum = ws.carve<int32_t>(kn_div_up(R, RAY_BLOCK) + 1);
+    w.blk_off = ws.carve<int32_t>(kn_div_up(R * MARCH_G, 256));
     w.live_a = ws.carve<int32_t>(R);
     w.live_b = ws.carve<int32_t>(R);
     w.cnt = ws.carve<int32_t>(R);
     w.alive_a = ws.carve<int32_t>(R);
     w.alive_b = ws.carve<int32_t>(R);
-    w.pos = ws.carve<int32_t>(R);
-    w.scan_tmp = ws.carve<int32_t>(kn_scan_tmp_len(R));
     w.n_live_dev = ws.carve<int32_t>(1);
     w.T = ws.carve<float>(R);
     w.C = ws.carve<float>(3 * R);
@@ -826,12 +884,19 @@ extern "C" int kn_render(const kn_scene *sc, void *stream, const float *rays_o, 
     int wave_no = 0; // waves enqueued so far; wave i reads control block i % 2, its last kernel writes the other one
     // The shape of a wave (rows, samples per ray) lives in device memory, so a wave can be enqueued before the
     // host knows how many rays the previous one left: `rows_cap` is the host's upper bound, which sizes the grids.
-    auto march = [&](int64_t rows_cap) -> int {
-        const int32_t *ctl = w.ctl + 4 * (wave_no & 1);
-        hipLaunchKernelGGL(k_march_wave, dim3((unsigned)kn_div_up(rows_cap * MARCH_G, 256)), dim3(256),
+    // rows_in: upper bound of the rows of the list the march reads.  From the second wave on that is the previous
+    // wave's list, which the kernel compacts on the way (see k_march_wave); the new list is then the current one.
+    auto march = [&](int64_t rows_in, bool compacting) -> int {
+        const int32_t *ctl = w.ctl + 4 * (wave_no & 1), *old_ctl = w.ctl + 4 * ((wave_no + 1) & 1);
+        hipLaunchKernelGGL(k_march_wave, dim3((unsigned)kn_div_up(rows_in * MARCH_G, 256)), dim3(256),
                            fused_hist ? sizeof(int32_t) * (size_t)sc->N : 0, st, p, rays_o, rays_d, live, alive, ctl, kbits, rs,
-                           w.row_keys, w.row_rec, w.cnt, fused_hist ? gw.hist : (int32_t *)nullptr, sc->N);
+                           w.row_keys, w.row_rec, w.cnt, fused_hist ? gw.hist : (int32_t *)nullptr, sc->N, old_ctl,
+                           compacting ? w.blk_off : (const int32_t *)nullptr, live_next, alive_next);
         KN_CHECK_LAUNCH();
+        if (compacting) {
+            int32_t *t = live; live = live_next; live_next = t;
+            t = alive; alive = alive_next; alive_next = t;
+        }
         tm.mark(KN_ST_MARCH);
         return KN_OK;
     };
@@ -849,29 +914,16 @@ extern "C" int kn_render(const kn_scene *sc, void *stream, const float *rays_o, 
         KN_CHECK_LAUNCH();
         seq = ++scm->mailbox_seq;
         hipLaunchKernelGGL(k_sum_partials, dim3(1), dim3(256), 0, st, w.partials, cblocks, w.counters, ctl, ctl_next, sched,
-                           sc->mailbox_dev, seq);
+                           w.blk_off, sc->mailbox_dev, seq);
         KN_CHECK_LAUNCH();
         tm.mark(KN_ST_BLEND);
         if (tm.on) g_kn_profile.mlp_launches += 1;
         ++wave_no;
         return KN_OK;
     };
-    // drop the retired rows of the live list (deterministic order); works on the upper bound of its length
-    auto compact = [&](int64_t rows_cap) -> int {
-        tm.begin();
-        KN_TRY(kn_exclusive_scan_i32(st, alive, w.pos, rows_cap, w.scan_tmp, nullptr));
-        hipLaunchKernelGGL(k_compact_live, dim3((unsigned)kn_div_up(rows_cap, 256)), dim3(256), 0, st, live, alive, w.pos,
-                           (int32_t)rows_cap, live_next, alive_next);
-        KN_CHECK_LAUNCH();
-        int32_t *t = live; live = live_next; live_next = t;
-        t = alive; alive = alive_next; alive_next = t;
-        tm.mark(KN_ST_SETUP);
-        return KN_OK;
-    };
-
     // first wave: its march is enqueued for all R rays while the host is still waiting for the number of live rays
     tm.begin();
-    KN_TRY(march(R));
+    KN_TRY(march(R, false));
     long long first = 0;
     KN_TRY(wait_count(sc, st, seq, w.n_live_dev, sizeof(int32_t), &first));
     if (first < 0 || first > R) return KN_E_HIP;
@@ -897,10 +949,9 @@ extern "C" int kn_render(const kn_scene *sc, void *stream, const float *rays_o, 
                 next_cap = n_alive;
             }
             speculative = false;
-            KN_TRY(compact(list_cap)); // scans the old list, writes the new one
-            list_cap = next_cap;
             tm.begin();
-            KN_TRY(march(list_cap));
+            KN_TRY(march(list_cap, true)); // reads (and compacts) the old list
+            list_cap = next_cap;
             KN_TRY(rest_of_wave(list_cap));
         }
     }
