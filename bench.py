@@ -37,6 +37,41 @@ def read_traffic():
     return out
 
 
+def frames_in_flight(torch, scene, rays, args, R, steps, n, blended_per_frame):
+    """Supplementary: the same frames with `n` of them in flight, one stream, workspace and host thread each (frames
+    are independent; the kernels of one frame's launch gaps and tails overlap with the other frames' work).  The
+    headline value stays the one-frame-at-a-time figure, whose kernels can be timed one by one."""
+    import threading
+    outs = [torch.empty((R, 3), dtype=torch.float32, device="cuda") for _ in range(n)]
+    wss = [torch.empty(scene.workspace_bytes(max_rays=R), dtype=torch.uint8, device="cuda") for _ in range(n)]
+    streams = [torch.cuda.Stream() for _ in range(n)]
+    per = max(steps // n, 1)
+
+    def worker(t, count):
+        with torch.cuda.stream(streams[t]):
+            for i in range(count):
+                scene.render(*rays[(i * n + t) % 8], *args, out=outs[t], workspace=wss[t])
+
+    for t in range(n):
+        worker(t, 2)
+    torch.cuda.synchronize()
+    best = None
+    for _ in range(3):
+        th = [threading.Thread(target=worker, args=(t, per)) for t in range(n)]
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for x in th:
+            x.start()
+        for x in th:
+            x.join()
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        best = dt if best is None or dt < best else best
+    frames = per * n
+    return {"frames_in_flight": n, "frames": frames, "ms_per_frame": best * 1e3 / frames, "frames_per_sec": frames / best,
+            "samples_per_sec": blended_per_frame * frames / best}
+
+
 def cpu_baseline(cfg_fn, poses, budget_s=12.0):
     """Time the oracle (threaded build, all host cores) on whole frames of the same workload."""
     from oracle import OracleScene
@@ -99,6 +134,8 @@ def main():
     ap.add_argument("--wdtype", default="f16")
     ap.add_argument("--size", type=int, default=800)
     ap.add_argument("--wave", default="", help="first_wave_samples,slots_per_ray,growth (experiment knob)")
+    ap.add_argument("--in-flight", type=int, default=3,
+                    help="frames in flight (one stream and host thread each) of the supplementary throughput pass; 0 = skip")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (reference point for FETCH_SIZE / WRITE_SIZE counters)")
     a = ap.parse_args()
@@ -208,6 +245,8 @@ def main():
         "roofline": roofline,
         "roofline_mlp_all_events": roof_mlp(prof_all), "roofline_march_all_events": roof_march(prof_all),
     }
+    if a.in_flight > 1:
+        res["frames_in_flight"] = frames_in_flight(torch, scene, rays, args, R, a.steps, a.in_flight, blended / a.steps)
     if a.calibrate_copy:
         src_buf = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
         dst_buf = torch.empty_like(src_buf)

@@ -235,11 +235,15 @@ class Scene:
                                _ptr(cnt), _ptr(nxt)), "kn_march")
         return out_k, cnt, nxt
 
-    def render(self, rays_o, rays_d, t_near, step, K, term_eps=0.0, bg=(0.0, 0.0, 0.0), want_stats=False, out=None):
+    def render(self, rays_o, rays_d, t_near, step, K, term_eps=0.0, bg=(0.0, 0.0, 0.0), want_stats=False, out=None,
+               workspace=None):
+        """``workspace``: a uint8 device tensor of at least ``workspace_bytes(max_rays=R)`` bytes; by default one
+        cached workspace per scene is used.  Calls that are in flight at the same time (on different streams) need
+        a workspace each."""
         import torch
         R = rays_o.shape[0]
         rgb = torch.empty((R, 3), dtype=torch.float32, device=self.device) if out is None else out
-        ws = self._workspace(max_rays=max(R, 1))
+        ws = self._workspace(max_rays=max(R, 1)) if workspace is None else workspace
         st = RenderStats()
         bgc = (C.c_float * 3)(*[float(v) for v in bg])
         _check(self.L.kn_render(self.h, _stream(), _ptr(rays_o, torch.float32) if R else None,

@@ -281,15 +281,16 @@ extern "C" int kn_scene_create(const kn_scene_desc *desc, void *stream, kn_scene
     sc->packed_halfs_per_net = 0;
     sc->skip_dist = nullptr;
     sc->skip_res[0] = sc->skip_res[1] = sc->skip_res[2] = 0;
-    sc->mailbox_host = nullptr;
-    sc->mailbox_dev = nullptr;
-    sc->mailbox_seq = 0;
+    for (auto &m : sc->mailbox) m = KnMailbox{nullptr, nullptr, 0ull, nullptr, false};
     {
         void *hp = nullptr, *dp = nullptr;
-        if (hipHostMalloc(&hp, 64, hipHostMallocMapped) == hipSuccess && hipHostGetDevicePointer(&dp, hp, 0) == hipSuccess) {
-            memset(hp, 0, 64);
-            sc->mailbox_host = (volatile unsigned long long *)hp;
-            sc->mailbox_dev = (unsigned long long *)dp;
+        if (hipHostMalloc(&hp, 64 * KN_MAILBOXES, hipHostMallocMapped) == hipSuccess &&
+            hipHostGetDevicePointer(&dp, hp, 0) == hipSuccess) {
+            memset(hp, 0, 64 * KN_MAILBOXES);
+            for (int i = 0; i < KN_MAILBOXES; ++i) {
+                sc->mailbox[i].host = (volatile unsigned long long *)((char *)hp + 64 * i);
+                sc->mailbox[i].dev = (unsigned long long *)((char *)dp + 64 * i);
+            }
         } else if (hp) {
             (void)hipHostFree(hp);
         }
@@ -350,7 +351,7 @@ extern "C" int kn_scene_destroy(kn_scene *sc)
     if (sc->occ_bits) (void)hipFree(sc->occ_bits);
     if (sc->packed_w) (void)hipFree(sc->packed_w);
     if (sc->skip_dist) (void)hipFree(sc->skip_dist);
-    if (sc->mailbox_host) (void)hipHostFree((void *)sc->mailbox_host);
+    if (sc->mailbox[0].host) (void)hipHostFree((void *)sc->mailbox[0].host);
     delete sc;
     return KN_OK;
 }

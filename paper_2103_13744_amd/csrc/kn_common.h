@@ -2,6 +2,7 @@
 #pragma once
 
 #include <hip/hip_runtime.h>
+#include <mutex>
 #include <stdint.h>
 
 #include "kilonerf.h"
@@ -26,6 +27,15 @@ struct KnTile {
     int32_t pad;
 };
 
+constexpr int KN_MAILBOXES = 8;
+struct KnMailbox {
+    volatile unsigned long long *host; // nullptr: could not be allocated (the caller falls back to synchronising)
+    unsigned long long *dev;
+    unsigned long long seq;            // last sequence number handed out
+    hipStream_t stream;                // owner, once taken
+    bool taken;
+};
+
 struct kn_scene {
     kn_scene_desc desc;
     int32_t N;             // number of networks
@@ -45,11 +55,12 @@ struct kn_scene {
     // Box around all occupied voxels, as a sub-grid of the occupancy grid (whole skip blocks; the network
     // grid's box without occupancy; res = 0 when nothing is occupied): rays are clipped against it.
     KnGrid content_box;
-    // Host-visible mailbox (pinned, device-mapped): kn_render's kernels post the live-ray count of a
-    // wave here, {sequence number, value}, and the host polls it instead of draining the stream.
-    volatile unsigned long long *mailbox_host;
-    unsigned long long *mailbox_dev;
-    unsigned long long mailbox_seq;
+    // Host-visible mailboxes (pinned, device-mapped, 8 words each): kn_render's kernels post the live-ray count
+    // of a wave there, {sequence number, value, totals...}, and the host polls it instead of draining the stream.
+    // A mailbox belongs to one stream (posts of one stream arrive in order; posts of two streams would overwrite
+    // each other), so calls on up to KN_MAILBOXES different streams can be in flight on one scene.
+    KnMailbox mailbox[KN_MAILBOXES];
+    std::mutex mailbox_mutex;
 };
 #define KN_SKIP_BLOCK 4
 #define KN_SKIP_MAX 32

@@ -267,7 +267,7 @@ struct RayState {
     int32_t *k_end;    // R
 };
 
-constexpr int RAY_BLOCK = 1024; // threads per block of the two set-up kernels
+constexpr int RAY_BLOCK = 256;  // threads per block of the two set-up kernels
 
 // Sum over the blocks in front of this one of per-block counts written by the previous kernel
 // (each thread takes a strided share; the loads are independent).
@@ -716,22 +716,39 @@ extern "C" int kn_set_render_params(int32_t first_wave_samples, int32_t slots_pe
     return KN_OK;
 }
 
+// The mailbox of `stream` on this scene (taken on first use and kept); nullptr when there is none left or none at all.
+static KnMailbox *mailbox_for(kn_scene *sc, hipStream_t stream)
+{
+    std::lock_guard<std::mutex> lock(sc->mailbox_mutex);
+    KnMailbox *free_one = nullptr;
+    for (auto &m : sc->mailbox) {
+        if (!m.host) return nullptr;
+        if (m.taken && m.stream == stream) return &m;
+        if (!m.taken && !free_one) free_one = &m;
+    }
+    if (free_one) {
+        free_one->taken = true;
+        free_one->stream = stream;
+    }
+    return free_one;
+}
+
 // Wait for the mailbox to show `seq` (spinning on pinned memory is much cheaper than draining the
 // stream); falls back to a stream synchronise + device read when there is no mailbox or it stays silent.
-static int wait_count(const kn_scene *sc, hipStream_t st, unsigned long long seq, const void *dev_value, size_t dev_bytes,
+static int wait_count(const KnMailbox *mb, hipStream_t st, unsigned long long seq, const void *dev_value, size_t dev_bytes,
                       long long *out)
 {
-    if (sc->mailbox_host) {
+    if (mb) {
         const auto t0 = std::chrono::steady_clock::now();
         long long spins = 0;
         while (true) {
-            if (__atomic_load_n((const unsigned long long *)&sc->mailbox_host[0], __ATOMIC_ACQUIRE) == seq) {
-                *out = (long long)__atomic_load_n((const unsigned long long *)&sc->mailbox_host[1], __ATOMIC_RELAXED);
+            if (__atomic_load_n((const unsigned long long *)&mb->host[0], __ATOMIC_ACQUIRE) == seq) {
+                *out = (long long)__atomic_load_n((const unsigned long long *)&mb->host[1], __ATOMIC_RELAXED);
                 return KN_OK;
             }
             if ((++spins & 0x3ff) == 0) {
                 if (hipStreamQuery(st) == hipSuccess && // stream drained: the post is there or will never come
-                    __atomic_load_n((const unsigned long long *)&sc->mailbox_host[0], __ATOMIC_ACQUIRE) != seq)
+                    __atomic_load_n((const unsigned long long *)&mb->host[0], __ATOMIC_ACQUIRE) != seq)
                     break;
                 if (std::chrono::steady_clock::now() - t0 > std::chrono::seconds(20)) break;
             }
@@ -855,16 +872,19 @@ extern "C" int kn_render(const kn_scene *sc, void *stream, const float *rays_o, 
     const bool fused_hist = kn_group_fused(sc->N);
     KnStageTimer tm(st);
     tm.begin();
-    kn_scene *scm = const_cast<kn_scene *>(sc); // the mailbox sequence number is the only mutable scene state
+    KnMailbox *mb = mailbox_for(const_cast<kn_scene *>(sc), st); // the mailboxes are the only mutable scene state
+    unsigned long long *mb_dev = mb ? mb->dev : nullptr;
+    unsigned long long seq_local = 0; // sequence numbers without a mailbox (nobody reads them)
+    auto next_seq = [&]() -> unsigned long long { return mb ? ++mb->seq : ++seq_local; };
     const WaveSchedule sched{g_first_wave_samples, g_wave_growth, K > 0 ? K : 1, budget};
     hipLaunchKernelGGL(k_render_init, dim3(rblocks), dim3(RAY_BLOCK), 0, st, p, rays_o, rays_d, R, rs, w.alive_b, w.blk_sum,
                        bg[0], bg[1], bg[2], rgb_out, (int32_t *)w.counters, 16, gw.hist, R >= n_hist ? (int32_t)n_hist : 0);
     KN_CHECK_LAUNCH();
     if (R < n_hist) KN_TRY(kn_fill_i32(st, gw.hist, n_hist, 0));
     if (R < 16) KN_TRY(kn_fill_i32(st, (int32_t *)w.counters, 16, 0));
-    unsigned long long seq = ++scm->mailbox_seq;
+    unsigned long long seq = next_seq();
     hipLaunchKernelGGL(k_first_live, dim3(rblocks), dim3(RAY_BLOCK), 0, st, w.alive_b, w.blk_sum, R, w.live_a, w.alive_a,
-                       w.n_live_dev, w.ctl, sched, sc->mailbox_dev, seq);
+                       w.n_live_dev, w.ctl, sched, mb_dev, seq);
     KN_CHECK_LAUNCH();
     tm.mark(KN_ST_SETUP);
 
@@ -912,9 +932,9 @@ extern "C" int kn_render(const kn_scene *sc, void *stream, const float *rays_o, 
                            w.out4, step, term_eps, bg[0], bg[1], bg[2], rs, rgb_out, alive, w.partials, gw.hist,
                            fused_hist ? (int32_t)n_hist : 0);
         KN_CHECK_LAUNCH();
-        seq = ++scm->mailbox_seq;
+        seq = next_seq();
         hipLaunchKernelGGL(k_sum_partials, dim3(1), dim3(256), 0, st, w.partials, cblocks, w.counters, ctl, ctl_next, sched,
-                           w.blk_off, sc->mailbox_dev, seq);
+                           w.blk_off, mb_dev, seq);
         KN_CHECK_LAUNCH();
         tm.mark(KN_ST_BLEND);
         if (tm.on) g_kn_profile.mlp_launches += 1;
@@ -925,7 +945,7 @@ extern "C" int kn_render(const kn_scene *sc, void *stream, const float *rays_o, 
     tm.begin();
     KN_TRY(march(R, false));
     long long first = 0;
-    KN_TRY(wait_count(sc, st, seq, w.n_live_dev, sizeof(int32_t), &first));
+    KN_TRY(wait_count(mb, st, seq, w.n_live_dev, sizeof(int32_t), &first));
     if (first < 0 || first > R) return KN_E_HIP;
     long long n_alive = first;
     if (first > 0) {
@@ -943,7 +963,7 @@ extern "C" int kn_render(const kn_scene *sc, void *stream, const float *rays_o, 
             if (wave_no == 2 && second_wave_ends_it && !want_counts) break;
             int64_t next_cap = list_cap; // survivors <= rows of the list they come from
             if (!speculative) {
-                KN_TRY(wait_count(sc, st, seq, w.counters + 2, sizeof(unsigned long long), &n_alive));
+                KN_TRY(wait_count(mb, st, seq, w.counters + 2, sizeof(unsigned long long), &n_alive));
                 if (n_alive < 0 || n_alive > list_cap) return KN_E_HIP; // cannot happen; guards the loop
                 if (n_alive == 0) break;
                 next_cap = n_alive;
@@ -957,12 +977,12 @@ extern "C" int kn_render(const kn_scene *sc, void *stream, const float *rays_o, 
     }
     if ((g_kn_profile_on && g_only_stage == KN_ST_NONE) || stats) {
         unsigned long long c[5] = {0ull, 0ull, 0ull, 0ull, 0ull}; // evaluated, blended, survivors, slots, waves
-        if (wave_no > 0 && sc->mailbox_host &&
-            __atomic_load_n((const unsigned long long *)&sc->mailbox_host[0], __ATOMIC_ACQUIRE) == seq) {
-            c[0] = __atomic_load_n((const unsigned long long *)&sc->mailbox_host[2], __ATOMIC_RELAXED);
-            c[1] = __atomic_load_n((const unsigned long long *)&sc->mailbox_host[3], __ATOMIC_RELAXED);
-            c[3] = __atomic_load_n((const unsigned long long *)&sc->mailbox_host[4], __ATOMIC_RELAXED);
-            c[4] = __atomic_load_n((const unsigned long long *)&sc->mailbox_host[5], __ATOMIC_RELAXED);
+        if (wave_no > 0 && mb &&
+            __atomic_load_n((const unsigned long long *)&mb->host[0], __ATOMIC_ACQUIRE) == seq) {
+            c[0] = __atomic_load_n((const unsigned long long *)&mb->host[2], __ATOMIC_RELAXED);
+            c[1] = __atomic_load_n((const unsigned long long *)&mb->host[3], __ATOMIC_RELAXED);
+            c[3] = __atomic_load_n((const unsigned long long *)&mb->host[4], __ATOMIC_RELAXED);
+            c[4] = __atomic_load_n((const unsigned long long *)&mb->host[5], __ATOMIC_RELAXED);
         } else if (wave_no > 0) {
             KN_HIP(hipMemcpyAsync(c, w.counters, sizeof(c), hipMemcpyDeviceToHost, st));
             KN_HIP(hipStreamSynchronize(st));

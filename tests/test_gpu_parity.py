@@ -335,6 +335,42 @@ def test_render_large_grid_code_paths(tmp_path):
     np.testing.assert_array_equal(np.load(out), here)
 
 
+def test_render_calls_in_flight_on_one_scene():
+    """Calls on different streams (own workspace and output each) may overlap on one scene: every stream gets its
+    own host mailbox.  Each result must equal the one-at-a-time image of the same rays."""
+    import threading
+    import torch
+    cfg = configs.config3(96, 96)
+    dev, _ = make_pair(cfg["scene"])
+    args = (cfg["t_near"], cfg["step"], cfg["K"], cfg["term_eps"], cfg["bg"])
+    views = []
+    for az in (10.0, 100.0, 190.0):
+        o, d = configs.camera_rays(96, 96, 40.0, 4.0, az, 30.0)
+        o, d = cuda(o), cuda(d)
+        views.append((o, d, dev.render(o, d, *args).cpu().numpy()))
+    torch.cuda.synchronize()
+    R = 96 * 96
+    results = [None] * len(views)
+
+    def worker(t):
+        st = torch.cuda.Stream()
+        ws = torch.empty(dev.workspace_bytes(max_rays=R), dtype=torch.uint8, device="cuda")
+        out = torch.empty((R, 3), dtype=torch.float32, device="cuda")
+        with torch.cuda.stream(st):
+            for _ in range(20):
+                dev.render(views[t][0], views[t][1], *args, out=out, workspace=ws)
+        st.synchronize()
+        results[t] = out.cpu().numpy()
+
+    threads = [threading.Thread(target=worker, args=(t,)) for t in range(len(views))]
+    for x in threads:
+        x.start()
+    for x in threads:
+        x.join()
+    for t, (_, _, ref) in enumerate(views):
+        np.testing.assert_array_equal(results[t], ref)
+
+
 def test_render_edge_cases():
     import torch
     cfg = configs.config3(16, 16)
