@@ -142,9 +142,14 @@ int kn_composite(void *stream, const float *sigma /*dev*/, const float *rgb /*de
  * waves from near to far; rays whose transmittance fell below term_eps, or that ran out of
  * lattice points, drop out between waves.  The result per ray equals the sequential definition
  * (march, evaluate, blend, stop at T < term_eps) regardless of how waves are cut.
- * R*2^ceil(log2 K) must be <= 2^32.  The call waits (on the host) for each wave's live-ray count before it
- * enqueues the next wave; when it returns, the last wave has been enqueued but `stream` may still be running.
- * Calls on the same scene must not overlap. */
+ * R*2^ceil(log2 K) must be <= 2^32.  The call enqueues the first two waves without looking at their outcome
+ * (their shape is computed on the device) and reads the count of surviving rays on the host only to decide
+ * about further waves; when it returns, the last wave has been enqueued but `stream` may still be running
+ * (it does not wait at all when the slot budget guarantees that the second wave ends every ray and `stats`
+ * is NULL).  Work of successive calls on one stream is ordered as usual.  Calls on up to 8 different streams may
+ * be in flight on the same scene at the same time, each with a workspace and an output buffer of its own;
+ * kn_set_render_params and kn_profile_enable must not be called while calls are in flight, and with
+ * profiling on calls must not overlap. */
 int kn_render(const kn_scene *scene, void *stream, const float *rays_o /*dev R*3*/,
               const float *rays_d /*dev R*3, unit*/, int64_t R, float t_near, float step,
               int32_t K /*max lattice points per ray*/, float term_eps /*0 = off*/,

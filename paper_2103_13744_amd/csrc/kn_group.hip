@@ -82,16 +82,6 @@ __global__ void __launch_bounds__(GROUP_THREADS)
     GT(0);
 
     int32_t *hcl = bins + bins_cap; // MODE 2: the wave's histogram [N]
-    if constexpr (MODE == 2) {
-        for (int32_t b0 = 0; b0 < N; b0 += 8 * GROUP_THREADS) {
-            int32_t v[8];
-#pragma unroll
-            for (int u = 0; u < 8; ++u) v[u] = hist[min(b0 + u * GROUP_THREADS + tid, N - 1)]; // loads issued together
-#pragma unroll
-            for (int u = 0; u < 8; ++u)
-                if (b0 + u * GROUP_THREADS + tid < N) hcl[b0 + u * GROUP_THREADS + tid] = v[u];
-        }
-    }
 
     // four keys of chunk ch of the row at `base` (unconditional, clamped inside the row buffer)
     auto load_chunk = [&](int64_t base, int32_t ch) -> i4 {
@@ -126,15 +116,14 @@ __global__ void __launch_bounds__(GROUP_THREADS)
     auto fetch_rows = [&](int32_t rs) -> RowLoad {
         RowLoad q;
         const int32_t row = rs + sub;
-        const int32_t i = r0 + min(row, nr - 1);
+        const int32_t i = max(r0 + min(row, nr - 1), 0); // (a workgroup without rows reads row 0 and ignores it)
         q.base = (int64_t)i * S;
         q.c = row < nr ? cnt[i] : 0;
         q.va = load_chunk(q.base, g);
         q.vb = load_chunk(q.base, g + G);
         return q;
     };
-    auto sweep = [&](int32_t w0, int32_t nb, auto &&f) {
-        RowLoad next = fetch_rows(0);
+    auto sweep = [&](int32_t w0, int32_t nb, RowLoad next /* = fetch_rows(0) */, auto &&f) {
         for (int32_t rs = 0; rs < nr; rs += rows_per_set) {
             const RowLoad cur = next;
             if (rs + rows_per_set < nr) next = fetch_rows(rs + rows_per_set);
@@ -150,13 +139,26 @@ __global__ void __launch_bounds__(GROUP_THREADS)
         }
     };
 
+    // the first rows of the counting sweep are requested before the histogram is staged: one round trip for both
+    RowLoad first_rows = fetch_rows(0);
+    if constexpr (MODE == 2) {
+        for (int32_t b0 = 0; b0 < N; b0 += 8 * GROUP_THREADS) {
+            int32_t v[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) v[u] = hist[min(b0 + u * GROUP_THREADS + tid, N - 1)]; // loads issued together
+#pragma unroll
+            for (int u = 0; u < 8; ++u)
+                if (b0 + u * GROUP_THREADS + tid < N) hcl[b0 + u * GROUP_THREADS + tid] = v[u];
+        }
+    }
+
     for (int32_t w0 = 0; w0 < N; w0 += bins_cap) { // MODE 2: a single window
         const int32_t nb = min(bins_cap, N - w0);
         for (int32_t b = tid; b < nb; b += GROUP_THREADS) bins[b] = 0;
         if (tid == 0) n_touched = 0;
         __syncthreads();
         GT(5);
-        if (nr > 0) sweep(w0, nb, [&](int32_t k, int64_t, int32_t len) { atomicAdd(&bins[k], len); });
+        if (nr > 0) sweep(w0, nb, w0 == 0 ? first_rows : fetch_rows(0), [&](int32_t k, int64_t, int32_t len) { atomicAdd(&bins[k], len); });
         __syncthreads();
         GT(1);
         int32_t fused_off0 = 0; // MODE 2: offset of the first group this thread laid out
@@ -270,7 +272,7 @@ __global__ void __launch_bounds__(GROUP_THREADS)
             __syncthreads();
             GT(3);
             if (nr > 0)
-                sweep(w0, nb, [&](int32_t k, int64_t slot, int32_t len) {
+                sweep(w0, nb, fetch_rows(0), [&](int32_t k, int64_t slot, int32_t len) {
                     const int32_t pos = atomicAdd(&bins[k], len);
                     for (int32_t t = 0; t < len; ++t) perm[pos + t] = (int32_t)slot + t;
                 });

@@ -477,8 +477,14 @@ __global__ void __launch_bounds__(256)
         float T = s.T[r];
         float c0 = s.C[3 * (int64_t)r], c1 = s.C[3 * (int64_t)r + 1], c2 = s.C[3 * (int64_t)r + 2];
         bool dead = false;
+        f4 v_next = gl < n ? smp[gl] : (f4){0.0f, 0.0f, 0.0f, 0.0f};
         for (int32_t j0 = 0; j0 < n && !dead; j0 += MARCH_G) {
-            f4 v = (j0 + gl < n) ? smp[j0 + gl] : (f4){0.0f, 0.0f, 0.0f, 0.0f};
+            f4 v = v_next;
+            // the following 16 samples are requested before these are blended (clamped address: always a valid slot of
+            // the row buffer; the value is only used for j < n)
+            const int32_t jn = j0 + MARCH_G + gl;
+            v_next = smp[min(jn, S - 1)];
+            if (jn >= n) v_next = (f4){0.0f, 0.0f, 0.0f, 0.0f};
             v[3] = 1.0f - expf(-v[3] * step); // alpha (Eq. 4)
             __builtin_amdgcn_wave_barrier();
             grp_stage[gl] = v;
