@@ -52,6 +52,7 @@ typedef float f2 __attribute__((ext_vector_type(2)));
 typedef float f4 __attribute__((ext_vector_type(4)));
 typedef unsigned u4 __attribute__((ext_vector_type(4)));
 
+constexpr int MLP_WAVES = 4;     // wavefronts per workgroup (one per SIMD of a compute unit)
 constexpr int MLP_TILE_LEN = 64; // one chunk: the unit in which work is dealt out to the wavefronts
 
 template <int H> struct Lay {
@@ -221,8 +222,10 @@ constexpr float INV_2PI = 0.15915494309189535f;
 #ifdef KN_MLP_TIMING
 __device__ unsigned long long kn_mlp_timing[8 * 4096];
 #endif
-template <int H, bool BF, bool AREG, int WAVES, bool WRAP>
-__global__ void __launch_bounds__(WAVES *KN_WAVE) __attribute__((amdgpu_waves_per_eu(AREG ? KN_MLP_WPE : 1, AREG ? KN_MLP_WPE : 1)))
+// Weights stay in registers: 14 blocks (56 VGPRs) for H = 32, three wavefronts per SIMD; 40 blocks (160 VGPRs) for
+// H = 64, one wavefront per SIMD (the matrix-core operands are read straight from the register file either way).
+template <int H, bool BF, int WAVES, bool WRAP>
+__global__ void __launch_bounds__(WAVES *KN_WAVE) __attribute__((amdgpu_waves_per_eu(H == 32 ? KN_MLP_WPE : 1, H == 32 ? KN_MLP_WPE : 1)))
     k_mlp_mfma(const uint16_t *__restrict__ packed, KnSampleSrc src, const int32_t *__restrict__ perm,
                const KnTile *__restrict__ tiles, const int32_t *__restrict__ n_tiles, float *__restrict__ sigma,
                float *__restrict__ rgb)
@@ -234,7 +237,6 @@ __global__ void __launch_bounds__(WAVES *KN_WAVE) __attribute__((amdgpu_waves_pe
     //   [0..3] pre-scaled angles (revolutions) of the three restart points of gamma(x) and of gamma(d)
     //   [4..7] (group 3 only) the packed 16-bit pairs (x,y), (z,1), (dx,dy), (dz,1) that sit in its slots
     __shared__ f4 stage[WAVES][4][2][KN_WAVE]; // [lane group][half][sample]: conflict-free for writers and readers
-    __shared__ u4 wlds[AREG ? 1 : WAVES * NBLK * KN_WAVE];
 
     const int wave = threadIdx.x / KN_WAVE, lane = threadIdx.x & (KN_WAVE - 1);
     const int n = lane & 15, g = lane >> 4;
@@ -258,38 +260,30 @@ __global__ void __launch_bounds__(WAVES *KN_WAVE) __attribute__((amdgpu_waves_pe
     const int t_hi = __builtin_amdgcn_readfirstlane((int)((int64_t)(wid + 1) * total_tiles / total_waves));
     if (t_lo >= t_hi) return;
 
-    u4 areg[AREG ? NBLK : 1];
-    u4 *wl = &wlds[AREG ? 0 : wave * NBLK * KN_WAVE];
+    u4 areg[NBLK];
     auto A = [&](int b) -> u4 {
-        if constexpr (AREG) return areg[b]; else return wl[b * KN_WAVE + lane];
+        return areg[b];
     };
-    // density / colour blocks restricted to the four output rows of sample tile u (AREG: kept in registers)
-    u4 a_sig[AREG ? 4 : 1][HK], a_col[AREG ? 4 : 1][HK];
+    // density / colour blocks restricted to the four output rows of sample tile u
+    u4 a_sig[4][HK], a_col[4][HK];
     auto Asig = [&](int u, int kb) -> u4 {
-        if constexpr (AREG) return a_sig[u][kb]; else return mrow == u ? A(L::LS + kb) : zero_u4;
+        return a_sig[u][kb];
     };
     auto Acol = [&](int u, int kb) -> u4 {
-        if constexpr (AREG) return a_col[u][kb]; else return mrow == u ? A(L::L5 + kb) : zero_u4;
+        return a_col[u][kb];
     };
     f4 bias2[HT], bias3[HT], bias_out;
     auto load_network = [&](int32_t net) {
         const u4 *__restrict__ wp = (const u4 *)(packed + (int64_t)net * L::HALFS);
-        if constexpr (AREG) {
 #pragma unroll
-            for (int b = 0; b < NBLK; ++b) areg[b] = wp[b * KN_WAVE + lane];
+        for (int b = 0; b < NBLK; ++b) areg[b] = wp[b * KN_WAVE + lane];
 #pragma unroll
-            for (int u = 0; u < 4; ++u)
+        for (int u = 0; u < 4; ++u)
 #pragma unroll
-                for (int kb = 0; kb < HK; ++kb) {
-                    a_sig[u][kb] = mrow == u ? areg[L::LS + kb] : zero_u4;
-                    a_col[u][kb] = mrow == u ? areg[L::L5 + kb] : zero_u4;
-                }
-        } else {
-            __builtin_amdgcn_wave_barrier(); // earlier reads of this wave's LDS copy are done
-            for (int b = 0; b < NBLK; ++b) wl[b * KN_WAVE + lane] = wp[b * KN_WAVE + lane];
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-            __builtin_amdgcn_wave_barrier();
-        }
+            for (int kb = 0; kb < HK; ++kb) {
+                a_sig[u][kb] = mrow == u ? areg[L::LS + kb] : zero_u4;
+                a_col[u][kb] = mrow == u ? areg[L::L5 + kb] : zero_u4;
+            }
         const float *__restrict__ tail = (const float *)(wp + NBLK * KN_WAVE);
 #pragma unroll
         for (int t = 0; t < HT; ++t) {
@@ -500,7 +494,7 @@ __global__ void __launch_bounds__(WAVES *KN_WAVE) __attribute__((amdgpu_waves_pe
 #endif
 }
 
-template <int H, bool BF, bool AREG, int WAVES>
+template <int H, bool BF, int WAVES>
 int launch(const kn_scene *sc, hipStream_t st, const KnSampleSrc &src, const KnBucketOut &b, int64_t max_tiles, float *sigma,
            float *rgb)
 {
@@ -510,17 +504,19 @@ int launch(const kn_scene *sc, hipStream_t st, const KnSampleSrc &src, const KnB
         const char *e = getenv("KN_MLP_BLOCKS");
         cap = e && atoi(e) > 0 ? atoi(e) : 256 * 3;
     }
-    if (blocks > cap) blocks = cap;
+    // one workgroup of 4 wavefronts per compute unit and resident wavefront (H = 32: three per SIMD, H = 64: one)
+    const int fill = H == 32 ? cap : cap / 3;
+    if (blocks > fill) blocks = fill;
     // positions are only ever evaluated inside the grid's box: its largest coordinate bounds the encoding's
     // largest argument, 2^8 |p| / (2 pi) revolutions at the highest restart frequency
     float reach = 0.0f;
     for (int a = 0; a < 3; ++a)
         reach = fmaxf(reach, fmaxf(fabsf(sc->desc.aabb_min[a]), fabsf(sc->desc.aabb_max[a])));
     if (reach * (256.0f * INV_2PI) < 250.0f)
-        hipLaunchKernelGGL((k_mlp_mfma<H, BF, AREG, WAVES, false>), dim3((unsigned)blocks), dim3(WAVES * KN_WAVE), 0, st,
+        hipLaunchKernelGGL((k_mlp_mfma<H, BF, WAVES, false>), dim3((unsigned)blocks), dim3(WAVES * KN_WAVE), 0, st,
                            (const uint16_t *)sc->packed_w, src, b.perm, b.tiles, b.n_tiles, sigma, rgb);
     else
-        hipLaunchKernelGGL((k_mlp_mfma<H, BF, AREG, WAVES, true>), dim3((unsigned)blocks), dim3(WAVES * KN_WAVE), 0, st,
+        hipLaunchKernelGGL((k_mlp_mfma<H, BF, WAVES, true>), dim3((unsigned)blocks), dim3(WAVES * KN_WAVE), 0, st,
                            (const uint16_t *)sc->packed_w, src, b.perm, b.tiles, b.n_tiles, sigma, rgb);
     KN_CHECK_LAUNCH();
     return KN_OK;
@@ -561,10 +557,10 @@ int kn_mlp_mfma_launch(const kn_scene *sc, hipStream_t st, const KnSampleSrc &sr
     if (max_tiles <= 0) return KN_OK;
     const bool bf = sc->desc.wdtype == KN_BF16;
     if (sc->desc.hidden == 32)
-        return bf ? launch<32, true, true, 4>(sc, st, src, b, max_tiles, sigma, rgb)
-                  : launch<32, false, true, 4>(sc, st, src, b, max_tiles, sigma, rgb);
+        return bf ? launch<32, true, MLP_WAVES>(sc, st, src, b, max_tiles, sigma, rgb)
+                  : launch<32, false, MLP_WAVES>(sc, st, src, b, max_tiles, sigma, rgb);
     if (sc->desc.hidden == 64)
-        return bf ? launch<64, true, false, 2>(sc, st, src, b, max_tiles, sigma, rgb)
-                  : launch<64, false, false, 2>(sc, st, src, b, max_tiles, sigma, rgb);
+        return bf ? launch<64, true, MLP_WAVES>(sc, st, src, b, max_tiles, sigma, rgb)
+                  : launch<64, false, MLP_WAVES>(sc, st, src, b, max_tiles, sigma, rgb);
     return KN_E_UNSUPPORTED;
 }
