@@ -29,6 +29,10 @@ struct MarchParams {
     float skip_edge_min; // shortest edge of a skip block
     float skip_margin;   // safety margin on the jump radius (position rounding)
     int32_t has_occ;
+    // >= 0 on every axis: the occupancy grid refines the network grid by 2^net_shift[a] (same box), so that the
+    // network cell of a point is its voxel coordinate shifted right, exactly (scaling the cell edge by a power of two
+    // scales the fp32 quotient of Eq. 6 by the same power of two without a rounding difference)
+    int32_t net_shift[3];
     float t_near, step;
     int32_t K;
 };
@@ -64,6 +68,21 @@ __device__ __forceinline__ GridFast make_fast(const KnGrid &g)
     f.res1 = g.res[1];
     f.res2 = g.res[2];
     return f;
+}
+
+// Eq. 6 per axis: integer cell coordinates of a point, false when it is outside the grid
+__device__ __forceinline__ bool grid_coords_fast(const GridFast &g, float x, float y, float z, int32_t &ix, int32_t &iy,
+                                                 int32_t &iz)
+{
+    const float fx = axis_floor(x - g.bmin[0], g.cell[0], g.inv[0]);
+    const float fy = axis_floor(y - g.bmin[1], g.cell[1], g.inv[1]);
+    const float fz = axis_floor(z - g.bmin[2], g.cell[2], g.inv[2]);
+    const bool in = (fx >= 0.0f) && (fx < g.resf[0]) && (fy >= 0.0f) && (fy < g.resf[1]) && (fz >= 0.0f) &&
+                    (fz < g.resf[2]);
+    ix = (int32_t)fx;
+    iy = (int32_t)fy;
+    iz = (int32_t)fz;
+    return in;
 }
 
 __device__ __forceinline__ int32_t grid_index_fast(const GridFast &g, float x, float y, float z)
@@ -194,41 +213,87 @@ __device__ __forceinline__ int32_t march_group(const MarchParams &p, const GridF
     const uint32_t gmask = (MARCH_G == 32) ? 0xffffffffu : ((1u << MARCH_G) - 1u);
     const SkipJump sj(p, o, d);
     int32_t n = 0;
+    constexpr int SKIP_SHIFT = 2;
+    static_assert((1 << SKIP_SHIFT) == KN_SKIP_BLOCK, "skip blocks are 4 voxels wide");
+    constexpr int STEPS = 1; // lattice points per lane and iteration (2 halves the iterations but did not pay: the loop is bound by its ALU work)
     while (k < k_hi && n < S) {
-        const int32_t kk = k + gl;
-        bool kept = false;
-        int32_t cell = -1;
-        int32_t reach = 0; // all lattice indices in [kk, reach) are known not to be kept
-        if (kk < k_hi) {
-            float x, y, z;
-            kn_lattice_point(o[0], o[1], o[2], d[0], d[1], d[2], p.t_near, p.step, kk, x, y, z);
-            const int32_t dist = sj.use ? skip_lookup(p, x, y, z) : 0; // < 2 (incl. outside): exact test
-            if (dist >= 2) {
-                reach = kk + 1 + sj.jump(dist);
-            } else {
-                kept = sample_kept(p, gn, go, x, y, z, cell);
-                reach = kept ? kk : kk + 1;
+        bool kept[STEPS];
+        int32_t cell[STEPS], reach[STEPS], kk[STEPS];
+#pragma unroll
+        for (int c = 0; c < STEPS; ++c) {
+            kk[c] = k + c * MARCH_G + gl;
+            kept[c] = false;
+            cell[c] = -1;
+            reach[c] = 0; // all lattice indices in [kk, reach) are known not to be kept
+        }
+        float x[STEPS], y[STEPS], z[STEPS];
+        int32_t vox[STEPS], dist[STEPS], ix[STEPS], iy[STEPS], iz[STEPS];
+        uint32_t word[STEPS];
+        // The occupancy word is requested together with the skip-field byte (both addresses follow from the voxel
+        // coordinates of the point), for both points of the lane: one memory round trip per iteration.
+#pragma unroll
+        for (int c = 0; c < STEPS; ++c) {
+            vox[c] = 0;
+            word[c] = 0xffffffffu;
+            dist[c] = 0;
+            if (kk[c] < k_hi) {
+                kn_lattice_point(o[0], o[1], o[2], d[0], d[1], d[2], p.t_near, p.step, kk[c], x[c], y[c], z[c]);
+                if (p.has_occ) {
+                    const bool in = grid_coords_fast(go, x[c], y[c], z[c], ix[c], iy[c], iz[c]);
+                    vox[c] = in ? (ix[c] * go.res1 + iy[c]) * go.res2 + iz[c] : -1;
+                    word[c] = in ? p.occ_bits[(uint32_t)vox[c] >> 5] : 0u;
+                    if (sj.use) // -1: outside the grid, the point is dropped by the exact test below
+                        dist[c] = in ? (int32_t)p.skip_dist[((ix[c] >> SKIP_SHIFT) * p.skip_res[1] + (iy[c] >> SKIP_SHIFT)) *
+                                                                p.skip_res[2] + (iz[c] >> SKIP_SHIFT)]
+                                     : -1;
+                }
             }
         }
-        const uint32_t mask = (uint32_t)(__ballot(kept) >> gshift) & gmask;
-        const int rank = __popc(mask & ((1u << gl) - 1u));
-        const int tot = __popc(mask);
-        const int room = S - n;
-        if (kept && rank < room) emit(n + rank, kk, cell);
-        if (tot > room) {
-            // the first kept sample that did not fit is where the next wave resumes
-            const uint32_t over = (uint32_t)(__ballot(kept && rank == room) >> gshift) & gmask;
-            k = k + (__ffs(over) - 1);
-            n = S;
-            break;
+#pragma unroll
+        for (int c = 0; c < STEPS; ++c) {
+            if (kk[c] < k_hi) {
+                if (dist[c] >= 2) {
+                    reach[c] = kk[c] + 1 + sj.jump(dist[c]);
+                } else {
+                    if (vox[c] >= 0 && ((word[c] >> (vox[c] & 31)) & 1u)) { // Sec. 3.4: inside the AABB, occupied voxel
+                        if (p.has_occ && p.net_shift[0] >= 0)
+                            cell[c] = ((ix[c] >> p.net_shift[0]) * gn.res1 + (iy[c] >> p.net_shift[1])) * gn.res2 +
+                                      (iz[c] >> p.net_shift[2]);
+                        else
+                            cell[c] = grid_index_fast(gn, x[c], y[c], z[c]);
+                        kept[c] = cell[c] >= 0;
+                    }
+                    reach[c] = kept[c] ? kk[c] : kk[c] + 1;
+                }
+            }
         }
-        n += tot;
-        // frontier: every index of this chunk was tested or skipped; the farthest jump that starts inside
-        // the chunk extends the known-empty range beyond it
-        int32_t far = reach;
+        // kept points in ascending order
+        bool full = false;
+#pragma unroll
+        for (int c = 0; c < STEPS; ++c) {
+            if (full) break; // (uniform inside the group)
+            const uint32_t mask = (uint32_t)(__ballot(kept[c]) >> gshift) & gmask;
+            const int rank = __popc(mask & ((1u << gl) - 1u));
+            const int tot = __popc(mask);
+            const int room = S - n;
+            if (kept[c] && rank < room) emit(n + rank, kk[c], cell[c]);
+            if (tot > room) {
+                // the first kept sample that did not fit is where the next wave resumes
+                const uint32_t over = (uint32_t)(__ballot(kept[c] && rank == room) >> gshift) & gmask;
+                k = k + c * MARCH_G + (__ffs(over) - 1);
+                n = S;
+                full = true;
+            } else {
+                n += tot;
+            }
+        }
+        if (full) break;
+        // frontier: every index of these chunks was tested or skipped; the farthest jump that starts inside
+        // them extends the known-empty range beyond
+        int32_t far = max(reach[0], reach[STEPS - 1]);
 #pragma unroll
         for (int off = MARCH_G / 2; off > 0; off >>= 1) far = max(far, __shfl_xor(far, off, KN_WAVE));
-        k = max(k + MARCH_G, far);
+        k = max(k + STEPS * MARCH_G, far);
     }
     return n;
 }
@@ -692,6 +757,14 @@ MarchParams make_params(const kn_scene *sc, float t_near, float step, int32_t K)
         mag = fmaxf(mag, fabsf(p.occ.bmin[a]) + p.occ.cell[a] * (float)p.occ.res[a]);
     }
     p.skip_margin = 1e-3f * p.skip_edge_min + 4e-6f * mag;
+    for (int a = 0; a < 3; ++a) {
+        int sft = -1;
+        if (sc->has_occ)
+            for (int q = 0; q < 16; ++q)
+                if ((int64_t)p.net.res[a] << q == (int64_t)p.occ.res[a]) sft = q;
+        p.net_shift[a] = sft;
+    }
+    if (p.net_shift[0] < 0 || p.net_shift[1] < 0 || p.net_shift[2] < 0) p.net_shift[0] = p.net_shift[1] = p.net_shift[2] = -1;
     p.t_near = t_near;
     p.step = step;
     p.K = K;
