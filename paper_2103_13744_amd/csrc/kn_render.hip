@@ -513,15 +513,141 @@ __global__ void __launch_bounds__(256)
     }
 }
 
-// MARCH_G lanes per live ray: Eq. 2-4 over this wave's samples, early termination, retire finished
-// rays.  The lanes fetch 16 consecutive samples and turn densities into alphas in parallel; the
-// blend itself is the sequential recurrence of the definition (same operation order for every
-// wave cut), run redundantly by all lanes of the group on values broadcast through LDS.
+// Eq. 2-4 over this wave's samples, early termination, retiring of finished rays.  A wavefront owns 64 consecutive
+// rows.  Its lanes fetch the rows' next BLEND_CHUNK samples together (16 lanes per row and request, consecutive
+// addresses) and turn densities into alphas; the values go through LDS to the lane that owns the row, which runs
+// the blend as the sequential recurrence of the definition: one lane per ray, the same operation order for every
+// wave cut.  (Blending with 16 lanes per ray, all of them stepping through the recurrence on broadcast values, cost
+// 16 times the instructions.)
+constexpr int BLEND_CHUNK = 16;
+constexpr int BLEND_ROWS = 256; // rows per workgroup
 __global__ void __launch_bounds__(256)
     k_composite_wave(const int32_t *__restrict__ live, const int32_t *__restrict__ ctl, int32_t rows_cap,
                      const int32_t *__restrict__ cnt, const float *__restrict__ out4, float step, float eps, float bg0,
                      float bg1, float bg2, RayState s, float *__restrict__ rgb_out, int32_t *__restrict__ alive,
-                     int32_t *__restrict__ partials /*3 * gridDim.x*/, int32_t *__restrict__ zero, int32_t n_zero)
+                     int32_t *__restrict__ partials /*2 * gridDim.x: evaluated, blended*/,
+                     int32_t *__restrict__ surv16 /*survivors per group of 16 rows*/, int32_t *__restrict__ zero,
+                     int32_t n_zero)
+{
+    // counters of the grouping that the next wave expects to be zero
+    for (int64_t z = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; z < n_zero; z += (int64_t)gridDim.x * blockDim.x) zero[z] = 0;
+    typedef float f4 __attribute__((ext_vector_type(4)));
+    __shared__ f4 stage[256 / KN_WAVE][KN_WAVE][BLEND_CHUNK + 1]; // + 1: the owner lanes' reads spread over the banks
+    const int32_t n_live = ctl[0], S = ctl[1];
+    const int wave = threadIdx.x / KN_WAVE, lane = threadIdx.x & (KN_WAVE - 1);
+    const int32_t row0 = (int32_t)blockIdx.x * BLEND_ROWS + wave * KN_WAVE; // first row of this wavefront
+    const int32_t i = row0 + lane;
+    // the grid covers rows_cap >= n_live rows; the flags of the rows beyond the list are cleared so that the next
+    // wave's compaction can run over the same upper bound
+    if (i >= n_live && i < rows_cap) alive[i] = 0;
+    const bool mine = i < n_live && alive[i] != 0;
+    const int32_t r = mine ? live[i] : 0;
+    const int32_t n = mine ? cnt[i] : 0;
+    float T = 1.0f, c0 = 0.0f, c1 = 0.0f, c2 = 0.0f;
+    if (mine) {
+        T = s.T[r];
+        c0 = s.C[3 * (int64_t)r];
+        c1 = s.C[3 * (int64_t)r + 1];
+        c2 = s.C[3 * (int64_t)r + 2];
+    }
+    bool dead = false;
+    int32_t blended = 0;
+    const int sub = lane / BLEND_CHUNK, jl = lane % BLEND_CHUNK; // loader role: row sub, sub + 4, ...; sample jl of the chunk
+    for (int32_t j0 = 0; __ballot(mine && !dead && j0 < n) != 0ull; j0 += BLEND_CHUNK) {
+        // fetch: KN_WAVE / BLEND_CHUNK rows per request, all requests issued before the first use
+        f4 v[BLEND_CHUNK];
+#pragma unroll
+        for (int q = 0; q < BLEND_CHUNK; ++q) {
+            const int rl = q * (KN_WAVE / BLEND_CHUNK) + sub;        // row of the wavefront this lane loads for
+            const int32_t n_l = __shfl(n, rl, KN_WAVE);
+            const int32_t gone = __shfl((int32_t)dead, rl, KN_WAVE);
+            const bool need = j0 + jl < n_l && !gone;
+            const int64_t at = (int64_t)min(row0 + rl, n_live - 1) * S + min(j0 + jl, S - 1); // always a slot of the wave
+            v[q] = ((const f4 *)out4)[at];
+            if (!need) v[q] = (f4){0.0f, 0.0f, 0.0f, 0.0f};
+        }
+        __builtin_amdgcn_wave_barrier(); // the owners have finished reading the previous chunk
+#pragma unroll
+        for (int q = 0; q < BLEND_CHUNK; ++q) {
+            v[q][3] = 1.0f - expf(-v[q][3] * step); // alpha (Eq. 4)
+            stage[wave][q * (KN_WAVE / BLEND_CHUNK) + sub][jl] = v[q];
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        // blend: lane = row
+        const int m = min(BLEND_CHUNK, n - j0);
+        for (int u = 0; u < BLEND_CHUNK; ++u) {
+            if (__ballot(mine && !dead && u < m) == 0ull) break;
+            if (mine && !dead && u < m) {
+                const f4 q = stage[wave][lane][u];
+                const float wgt = T * q[3];
+                c0 = fmaf(wgt, q[0], c0);
+                c1 = fmaf(wgt, q[1], c1);
+                c2 = fmaf(wgt, q[2], c2);
+                T *= (1.0f - q[3]);
+                ++blended;
+                if (eps > 0.0f && T < eps) dead = true;
+            }
+        }
+    }
+    bool lives = false;
+    if (mine) {
+        const bool exhausted = s.k_next[r] >= s.k_end[r];
+        lives = !dead && !exhausted;
+        if (lives) {
+            s.T[r] = T;
+            s.C[3 * (int64_t)r] = c0;
+            s.C[3 * (int64_t)r + 1] = c1;
+            s.C[3 * (int64_t)r + 2] = c2;
+        } else {
+            rgb_out[3 * (int64_t)r] = fmaf(T, bg0, c0);
+            rgb_out[3 * (int64_t)r + 1] = fmaf(T, bg1, c1);
+            rgb_out[3 * (int64_t)r + 2] = fmaf(T, bg2, c2);
+            alive[i] = 0;
+        }
+    }
+    // survivors per group of 16 rows (the next wave's march compacts the list in those groups)
+    {
+        const unsigned long long sv = __ballot(lives);
+        if (lane < KN_WAVE / MARCH_G) {
+            const int32_t grp = row0 / MARCH_G + lane;
+            if ((int64_t)grp * MARCH_G < rows_cap) surv16[grp] = __builtin_popcountll((sv >> (MARCH_G * lane)) & ((1ull << MARCH_G) - 1ull));
+        }
+    }
+    // block-level sums -> one plain store per block and counter (same-address atomics from tens of
+    // thousands of wavefronts would serialise); k_sum_partials adds them up afterwards
+    int32_t evaluated = n;
+    __shared__ int32_t red[2][256 / KN_WAVE];
+#pragma unroll
+    for (int d = KN_WAVE / 2; d > 0; d >>= 1) {
+        blended += __shfl_down(blended, d, KN_WAVE);
+        evaluated += __shfl_down(evaluated, d, KN_WAVE);
+    }
+    if (lane == 0) {
+        red[0][wave] = evaluated;
+        red[1][wave] = blended;
+    }
+    __syncthreads();
+    if (threadIdx.x < 2) {
+        int32_t t = 0;
+#pragma unroll
+        for (int w = 0; w < 256 / KN_WAVE; ++w) t += red[threadIdx.x][w];
+        partials[(int64_t)threadIdx.x * gridDim.x + blockIdx.x] = t;
+    }
+}
+
+// The same blend with MARCH_G lanes per live ray, for waves of few rays with many samples each (the rest of a ray):
+// Eq. 2-4 over this wave's samples, early termination, retiring of finished rays.  The lanes fetch 16 consecutive samples and turn densities into alphas in parallel; the
+// blend itself is the sequential recurrence of the definition (same operation order for every
+// wave cut), run redundantly by all lanes of the group on values broadcast through LDS.
+__global__ void __launch_bounds__(256)
+    k_composite_group(const int32_t *__restrict__ live, const int32_t *__restrict__ ctl, int32_t rows_cap,
+                     const int32_t *__restrict__ cnt, const float *__restrict__ out4, float step, float eps, float bg0,
+                     float bg1, float bg2, RayState s, float *__restrict__ rgb_out, int32_t *__restrict__ alive,
+                     int32_t *__restrict__ partials /*2 * gridDim.x: evaluated, blended*/,
+                     int32_t *__restrict__ surv16 /*survivors per group of 16 rows = per workgroup*/,
+                     int32_t *__restrict__ zero, int32_t n_zero)
 {
     // counters of the grouping that the next wave expects to be zero
     for (int64_t z = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; z < n_zero; z += (int64_t)gridDim.x * blockDim.x) zero[z] = 0;
@@ -607,13 +733,17 @@ __global__ void __launch_bounds__(256)
         int32_t v = 0;
 #pragma unroll
         for (int w = 0; w < 256 / KN_WAVE; ++w) v += red[threadIdx.x][w];
-        partials[(int64_t)threadIdx.x * gridDim.x + blockIdx.x] = v;
+        if (threadIdx.x == 2) surv16[blockIdx.x] = v;
+        else partials[(int64_t)threadIdx.x * gridDim.x + blockIdx.x] = v;
     }
 }
 
 // one block: counters[0] += evaluated, counters[1] += blended, counters[2] = survivors of this wave
 // ... counters[3] += slots of this wave, counters[4] += 1 if the wave had rows; writes the next wave's control
-__global__ void __launch_bounds__(256) k_sum_partials(const int32_t *__restrict__ partials, int32_t n_blocks,
+// partials: evaluated and blended samples per workgroup of the blend (2 * n_cb); surv16: survivors per group of 16
+// rows (n_blocks groups)
+__global__ void __launch_bounds__(256) k_sum_partials(const int32_t *__restrict__ partials, int32_t n_cb,
+                                                      const int32_t *__restrict__ surv16, int32_t n_blocks,
                                                       unsigned long long *__restrict__ counters,
                                                       const int32_t *__restrict__ ctl, int32_t *__restrict__ ctl_next,
                                                       WaveSchedule sched, int32_t *__restrict__ blk_off,
@@ -621,16 +751,17 @@ __global__ void __launch_bounds__(256) k_sum_partials(const int32_t *__restrict_
 {
     __shared__ unsigned long long red[3][256 / KN_WAVE];
     unsigned long long v[3] = {0ull, 0ull, 0ull};
-    for (int32_t b0 = 0; b0 < n_blocks; b0 += 256 * 8) { // batches of independent loads
+    for (int32_t b0 = 0; b0 < max(n_blocks, n_cb); b0 += 256 * 8) { // batches of independent loads
         int32_t t[3][8];
 #pragma unroll
         for (int u = 0; u < 8; ++u) {
             const int32_t b = b0 + u * 256 + threadIdx.x;
-#pragma unroll
-            for (int c = 0; c < 3; ++c) { // unconditional (clamped) loads batch up
-                const int32_t q = partials[(int64_t)c * n_blocks + min(b, n_blocks - 1)];
-                t[c][u] = (b < n_blocks) ? q : 0;
-            }
+            // unconditional (clamped) loads batch up
+            const int32_t qe = partials[min(b, n_cb - 1)], qb = partials[(int64_t)n_cb + min(b, n_cb - 1)];
+            const int32_t qs = surv16[min(b, n_blocks - 1)];
+            t[0][u] = b < n_cb ? qe : 0;
+            t[1][u] = b < n_cb ? qb : 0;
+            t[2][u] = b < n_blocks ? qs : 0;
         }
 #pragma unroll
         for (int u = 0; u < 8; ++u)
@@ -658,7 +789,7 @@ __global__ void __launch_bounds__(256) k_sum_partials(const int32_t *__restrict_
         constexpr int PER = 32, ROUND = 256 * PER;
         __shared__ int32_t tr[ROUND + ROUND / 32];
         __shared__ int32_t scan_lds[256 / KN_WAVE];
-        const int32_t *surv = partials + 2 * (int64_t)n_blocks;
+        const int32_t *surv = surv16;
         const int tid = threadIdx.x;
         int32_t carry = 0;
         for (int32_t b0 = 0; b0 < n_blocks; b0 += ROUND) {
@@ -850,7 +981,7 @@ static int kbits_for(int32_t K)
 
 // layout of the render workspace
 struct RenderWs {
-    int32_t *partials, *blk_sum, *blk_off, *live_a, *live_b, *cnt, *alive_a, *alive_b, *n_live_dev, *row_keys, *ctl;
+    int32_t *partials, *surv16, *blk_sum, *blk_off, *live_a, *live_b, *cnt, *alive_a, *alive_b, *n_live_dev, *row_keys, *ctl;
     uint32_t *row_rec;
     float *T, *C, *out4;
     int32_t *k_next, *k_end;
@@ -859,7 +990,8 @@ struct RenderWs {
 
 static void carve_render(KnCarver &ws, int64_t R, int64_t slots, RenderWs &w)
 {
-    w.partials = ws.carve<int32_t>(3 * kn_div_up(R * MARCH_G, 256));
+    w.partials = ws.carve<int32_t>(2 * kn_div_up(R, MARCH_G));
+    w.surv16 = ws.carve<int32_t>(kn_div_up(R, MARCH_G));
     w.blk_sum = ws.carve<int32_t>(kn_div_up(R, RAY_BLOCK) + 1);
     w.blk_off = ws.carve<int32_t>(kn_div_up(R * MARCH_G, 256));
     w.live_a = ws.carve<int32_t>(R);
@@ -999,6 +1131,7 @@ extern "C" int kn_render(const kn_scene *sc, void *stream, const float *rays_o, 
         tm.mark(KN_ST_MARCH);
         return KN_OK;
     };
+    int64_t s_bound = g_first_wave_samples; // host-side upper bound of the samples per ray of the wave being enqueued
     auto rest_of_wave = [&](int64_t rows_cap) -> int {
         int32_t *ctl = w.ctl + 4 * (wave_no & 1), *ctl_next = w.ctl + 4 * ((wave_no + 1) & 1);
         KnBucketOut bo;
@@ -1006,18 +1139,27 @@ extern "C" int kn_render(const kn_scene *sc, void *stream, const float *rays_o, 
         tm.mark(KN_ST_BUCKET);
         KN_TRY(kn_mlp_launch(sc, st, src, bo, budget, nullptr, nullptr));
         tm.mark(KN_ST_MLP);
-        const int32_t cblocks = (int32_t)kn_div_up(rows_cap * MARCH_G, 256);
-        hipLaunchKernelGGL(k_composite_wave, dim3((unsigned)cblocks), dim3(256), 0, st, live, ctl, (int32_t)rows_cap, w.cnt,
-                           w.out4, step, term_eps, bg[0], bg[1], bg[2], rs, rgb_out, alive, w.partials, gw.hist,
-                           fused_hist ? (int32_t)n_hist : 0);
+        // many rays with few samples each: one lane per ray; few rays with many samples: 16 lanes per ray
+        const bool lane_per_ray = s_bound <= 4 * BLEND_CHUNK;
+        const int32_t groups = (int32_t)kn_div_up(rows_cap, MARCH_G);
+        const int32_t cblocks = lane_per_ray ? (int32_t)kn_div_up(rows_cap, BLEND_ROWS) : groups;
+        if (lane_per_ray)
+            hipLaunchKernelGGL(k_composite_wave, dim3((unsigned)cblocks), dim3(256), 0, st, live, ctl, (int32_t)rows_cap, w.cnt,
+                               w.out4, step, term_eps, bg[0], bg[1], bg[2], rs, rgb_out, alive, w.partials, w.surv16, gw.hist,
+                               fused_hist ? (int32_t)n_hist : 0);
+        else
+            hipLaunchKernelGGL(k_composite_group, dim3((unsigned)cblocks), dim3(256), 0, st, live, ctl, (int32_t)rows_cap, w.cnt,
+                               w.out4, step, term_eps, bg[0], bg[1], bg[2], rs, rgb_out, alive, w.partials, w.surv16, gw.hist,
+                               fused_hist ? (int32_t)n_hist : 0);
         KN_CHECK_LAUNCH();
         seq = next_seq();
-        hipLaunchKernelGGL(k_sum_partials, dim3(1), dim3(256), 0, st, w.partials, cblocks, w.counters, ctl, ctl_next, sched,
-                           w.blk_off, mb_dev, seq);
+        hipLaunchKernelGGL(k_sum_partials, dim3(1), dim3(256), 0, st, w.partials, cblocks, w.surv16, groups, w.counters, ctl,
+                           ctl_next, sched, w.blk_off, mb_dev, seq);
         KN_CHECK_LAUNCH();
         tm.mark(KN_ST_BLEND);
         if (tm.on) g_kn_profile.mlp_launches += 1;
         ++wave_no;
+        s_bound = s_bound * g_wave_growth < (int64_t)K ? s_bound * g_wave_growth : (int64_t)K;
         return KN_OK;
     };
     // first wave: its march is enqueued for all R rays while the host is still waiting for the number of live rays
