@@ -19,6 +19,7 @@ if ROOT not in sys.path:
 PEAK_MFMA_16BIT = 2.5e15   # FLOP/s, dense fp16 / bf16 MFMA, MI355X
 PEAK_HBM = 8.0e12          # B/s
 FLOP_PER_SAMPLE = {32: 12160, 64: 36608}
+VALU_SLOTS_PER_16_SAMPLES = {32: 125, 64: 190}
 
 
 def read_traffic():
@@ -212,10 +213,15 @@ def main():
     def roof_mlp(p):
         s_ = p["ms_mlp"] * 1e-3
         tf = FLOP_PER_SAMPLE[H] * evaluated / s_ / 1e12 if s_ > 0 else 0.0
+        # second view of the same kernel: its vector-ALU issue slots (counted in the generated code: 125 per 16 samples at
+        # H = 32, transcendental instructions counted twice) against what 1024 SIMDs can issue at 2.4 GHz, one slot per
+        # 4 cycles; the encoding and the 16-bit packing between layers, not the MFMAs, are what the kernel waits for
+        slots = VALU_SLOTS_PER_16_SAMPLES[H] / 16.0 * evaluated
+        valu_frac = slots / (s_ * 1024 * 2.4e9 / 4.0) if s_ > 0 else 0.0
         return {"kernel": "k_mlp_mfma (fused grouped MLP)", "bound": "mfma", "achieved": tf, "peak": PEAK_MFMA_16BIT / 1e12,
                 "unit": "TFLOP/s", "frac": tf * 1e12 / PEAK_MFMA_16BIT, "traffic": traffic.get("k_mlp_mfma"),
                 "avg_launch_ms": p["ms_mlp"] / max(launches, 1), "launches": launches,
-                "samples_per_launch": evaluated / max(launches, 1)}
+                "samples_per_launch": evaluated / max(launches, 1), "valu_issue_frac": valu_frac}
 
     def roof_march(p):
         # algorithmic bytes: 24 B per ray read + the packed occupancy grid read, once per frame, and 8 B (key,

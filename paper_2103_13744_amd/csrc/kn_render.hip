@@ -370,8 +370,6 @@ __global__ void __launch_bounds__(RAY_BLOCK)
         clip_ray(p.content, o, d, p.t_near, p.step, p.K, k_lo, k_hi);
         // walk through provably empty space up to the first lattice point that is near occupied blocks
         k_lo = skip_to_content(p, make_fast(p.occ), o, d, k_lo, k_hi);
-        s.T[r] = 1.0f;
-        s.C[3 * r] = s.C[3 * r + 1] = s.C[3 * r + 2] = 0.0f;
         s.k_next[r] = k_lo;
         s.k_end[r] = k_hi;
         lives = k_lo < k_hi ? 1 : 0;
@@ -527,7 +525,7 @@ __global__ void __launch_bounds__(256)
                      float bg1, float bg2, RayState s, float *__restrict__ rgb_out, int32_t *__restrict__ alive,
                      int32_t *__restrict__ partials /*2 * gridDim.x: evaluated, blended*/,
                      int32_t *__restrict__ surv16 /*survivors per group of 16 rows*/, int32_t *__restrict__ zero,
-                     int32_t n_zero)
+                     int32_t n_zero, int32_t first_wave)
 {
     // counters of the grouping that the next wave expects to be zero
     for (int64_t z = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; z < n_zero; z += (int64_t)gridDim.x * blockDim.x) zero[z] = 0;
@@ -543,8 +541,8 @@ __global__ void __launch_bounds__(256)
     const bool mine = i < n_live && alive[i] != 0;
     const int32_t r = mine ? live[i] : 0;
     const int32_t n = mine ? cnt[i] : 0;
-    float T = 1.0f, c0 = 0.0f, c1 = 0.0f, c2 = 0.0f;
-    if (mine) {
+    float T = 1.0f, c0 = 0.0f, c1 = 0.0f, c2 = 0.0f; // the state of a ray before its first wave
+    if (mine && !first_wave) {
         T = s.T[r];
         c0 = s.C[3 * (int64_t)r];
         c1 = s.C[3 * (int64_t)r + 1];
@@ -647,7 +645,7 @@ __global__ void __launch_bounds__(256)
                      float bg1, float bg2, RayState s, float *__restrict__ rgb_out, int32_t *__restrict__ alive,
                      int32_t *__restrict__ partials /*2 * gridDim.x: evaluated, blended*/,
                      int32_t *__restrict__ surv16 /*survivors per group of 16 rows = per workgroup*/,
-                     int32_t *__restrict__ zero, int32_t n_zero)
+                     int32_t *__restrict__ zero, int32_t n_zero, int32_t first_wave)
 {
     // counters of the grouping that the next wave expects to be zero
     for (int64_t z = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; z < n_zero; z += (int64_t)gridDim.x * blockDim.x) zero[z] = 0;
@@ -665,8 +663,13 @@ __global__ void __launch_bounds__(256)
         const int32_t r = live[i];
         const int32_t n = cnt[i];
         const f4 *smp = (const f4 *)out4 + (int64_t)i * S; // row i of the wave's slots
-        float T = s.T[r];
-        float c0 = s.C[3 * (int64_t)r], c1 = s.C[3 * (int64_t)r + 1], c2 = s.C[3 * (int64_t)r + 2];
+        float T = 1.0f, c0 = 0.0f, c1 = 0.0f, c2 = 0.0f; // the state of a ray before its first wave
+        if (!first_wave) {
+            T = s.T[r];
+            c0 = s.C[3 * (int64_t)r];
+            c1 = s.C[3 * (int64_t)r + 1];
+            c2 = s.C[3 * (int64_t)r + 2];
+        }
         bool dead = false;
         f4 v_next = gl < n ? smp[gl] : (f4){0.0f, 0.0f, 0.0f, 0.0f};
         for (int32_t j0 = 0; j0 < n && !dead; j0 += MARCH_G) {
@@ -1146,11 +1149,11 @@ extern "C" int kn_render(const kn_scene *sc, void *stream, const float *rays_o, 
         if (lane_per_ray)
             hipLaunchKernelGGL(k_composite_wave, dim3((unsigned)cblocks), dim3(256), 0, st, live, ctl, (int32_t)rows_cap, w.cnt,
                                w.out4, step, term_eps, bg[0], bg[1], bg[2], rs, rgb_out, alive, w.partials, w.surv16, gw.hist,
-                               fused_hist ? (int32_t)n_hist : 0);
+                               fused_hist ? (int32_t)n_hist : 0, wave_no == 0 ? 1 : 0);
         else
             hipLaunchKernelGGL(k_composite_group, dim3((unsigned)cblocks), dim3(256), 0, st, live, ctl, (int32_t)rows_cap, w.cnt,
                                w.out4, step, term_eps, bg[0], bg[1], bg[2], rs, rgb_out, alive, w.partials, w.surv16, gw.hist,
-                               fused_hist ? (int32_t)n_hist : 0);
+                               fused_hist ? (int32_t)n_hist : 0, wave_no == 0 ? 1 : 0);
         KN_CHECK_LAUNCH();
         seq = next_seq();
         hipLaunchKernelGGL(k_sum_partials, dim3(1), dim3(256), 0, st, w.partials, cblocks, w.surv16, groups, w.counters, ctl,
