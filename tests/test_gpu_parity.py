@@ -387,6 +387,26 @@ def test_render_edge_cases():
     np.testing.assert_array_equal(img.cpu().numpy(), np.tile(np.float32([1, 0, 0]), (256, 1)))
 
 
+def test_march_and_render_on_grids_that_do_not_nest():
+    """Non-cubic box, network grid (3, 5, 2), occupancy grid (20, 17, 9): neither a multiple of the other nor of
+    the skip block, so network cells cannot be derived from voxel coordinates by a shift."""
+    occ = ks.blob_occupancy((20, 17, 9), 6, 0.2, 991)
+    sc = configs._scene((3, 5, 2), (-1, 0, 0.5), (1, 2, 4.5), 32, "f32", 992, sigma_scale=5.0, occ=occ)
+    o, d = ks.camera_rays(36, 28, 50.0, 6.0, 35.0, 25.0, center=(0.0, 1.0, 2.5))
+    diag = math.sqrt(4 + 4 + 16)
+    cfg = dict(scene=sc, rays_o=o, rays_d=d, t_near=6.0 - diag / 2, step=diag / 96, K=96, term_eps=0.01,
+               bg=(0.2, 0.3, 0.4), name="non_nested_f32")
+    dev, img, stats = render_check(cfg)
+    assert stats["samples_blended"] > 1000
+    orc = make_pair(sc)[1]
+    out_k, cnt, _ = dev.march(cuda(o), cuda(d), cfg["t_near"], cfg["step"], 96)
+    out_k, cnt = out_k.cpu().numpy(), cnt.cpu().numpy()
+    for r in range(0, len(o), 3):
+        want = orc.march(o[r], d[r], cfg["t_near"], cfg["step"], 96)
+        assert cnt[r] == len(want), r
+        np.testing.assert_array_equal(out_k[r, :cnt[r]], want)
+
+
 # ------------------------------------------------------------------ full-size workloads (sampled comparison)
 def test_full_config2_sampled():
     cfg = configs.config2()
