@@ -52,9 +52,9 @@ typedef struct {
     float aabb_max[3];       /* b_max, > b_min per axis                                           */
     int32_t hidden;          /* H: 32 or 64                                                       */
     int32_t L_pos, L_dir;    /* encoding frequencies; this build supports (10, 4)                 */
-    int32_t wdtype;          /* kn_dtype of `weights`.  KN_F32: fp32 arithmetic on the vector     */
-                             /* ALUs.  KN_F16 / KN_BF16: 16-bit weights and activations on the    */
-                             /* matrix cores with fp32 accumulation                               */
+    int32_t wdtype;          /* kn_dtype of `weights`.  KN_F32: fp32 weights, activations and     */
+                             /* accumulation (fp32 matrix-core instructions).  KN_F16 / KN_BF16:  */
+                             /* 16-bit weights and activations on the matrix cores, fp32 sums     */
     const void *weights;     /* dev, N*P elements of wdtype in the canonical layout               */
     int32_t occ_res[3];      /* occupancy grid resolution; all 0 = no grid (whole AABB occupied)  */
     const uint8_t *occupancy;/* dev, occ_res[0]*occ_res[1]*occ_res[2] bytes (0 = empty), x slowest*/
@@ -81,11 +81,10 @@ int64_t kn_params_per_net(int32_t hidden, int32_t L_pos, int32_t L_dir);
 
 /*
  * Create a scene on the current HIP device.  Validates the descriptor, then allocates (hipMalloc)
- * and fills, on `stream`, the library's own device copies: the occupancy grid packed to bits and,
- * for 16-bit types, the weights re-ordered into matrix-core operand order.  For KN_F32 the
- * caller's `weights` buffer itself is used and must stay valid and unchanged for the scene's
- * lifetime; for the other inputs the caller's buffers may be released once `stream` has
- * completed the work enqueued by this call.  This is the only call that allocates device memory.
+ * and fills, on `stream`, the library's own device copies: the occupancy grid packed to bits and
+ * the weights re-ordered into matrix-core operand order.  The caller's buffers may be released
+ * once `stream` has completed the work enqueued by this call.  This is the only call that
+ * allocates device memory.
  */
 int kn_scene_create(const kn_scene_desc *desc, void *stream, kn_scene **out);
 int kn_scene_destroy(kn_scene *scene); /* waits for the device, frees the library's copies */

@@ -16,6 +16,8 @@ int kn_mlp_f32_launch(const kn_scene *sc, hipStream_t st, const KnSampleSrc &src
 int kn_mlp_mfma_launch(const kn_scene *sc, hipStream_t st, const KnSampleSrc &src, const KnBucketOut &b, int64_t max_tiles,
                        float *sigma, float *rgb);
 int kn_mlp_mfma_tile_len(const kn_scene *sc);
+int kn_mlp_f32_tile_len(const kn_scene *sc);
+int kn_mlp_f32_pack_weights(kn_scene *sc, hipStream_t st);
 
 kn_profile g_kn_profile = {};
 bool g_kn_profile_on = false;
@@ -335,7 +337,7 @@ extern "C" int kn_scene_create(const kn_scene_desc *desc, void *stream, kn_scene
         sc->occ_grid = sc->net_grid;
         sc->content_box = sc->net_grid;
     }
-    if (rc == KN_OK && desc->wdtype != KN_F32) rc = kn_mlp_pack_weights(sc, st);
+    if (rc == KN_OK) rc = desc->wdtype == KN_F32 ? kn_mlp_f32_pack_weights(sc, st) : kn_mlp_pack_weights(sc, st);
     if (rc != KN_OK) {
         kn_scene_destroy(sc);
         return rc;
@@ -356,7 +358,7 @@ extern "C" int kn_scene_destroy(kn_scene *sc)
     return KN_OK;
 }
 
-int kn_mlp_tile_len(const kn_scene *sc) { return sc->desc.wdtype == KN_F32 ? 256 : kn_mlp_mfma_tile_len(sc); }
+int kn_mlp_tile_len(const kn_scene *sc) { return sc->desc.wdtype == KN_F32 ? kn_mlp_f32_tile_len(sc) : kn_mlp_mfma_tile_len(sc); }
 
 int kn_mlp_launch(const kn_scene *sc, hipStream_t st, const KnSampleSrc &src, const KnBucketOut &b, int64_t M, float *sigma,
                   float *rgb)

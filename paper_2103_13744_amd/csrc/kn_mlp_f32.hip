@@ -1,99 +1,284 @@
-// Grouped tiny-MLP evaluation in fp32 on the vector ALUs (scenes with KN_F32 weights).
+// Grouped tiny-MLP evaluation in fp32 (scenes with KN_F32 weights) on the matrix cores' fp32 path.
 //
-// One wavefront per tile of the sorted sample list; every lane carries one sample through the
-// encoding and the five layers (Sec. 3.2 "Network Architecture", Eq. 7).  All lanes of a wave use
-// the same network, so weight addresses are wave-uniform and are fetched through the scalar
-// path; activations stay in registers (all loops have compile-time bounds and are unrolled).
-// Accumulation order: bias first, then inputs in index order.
+// Same decomposition as the 16-bit kernel: a wavefront takes a contiguous range of tiles (<= 64 consecutive
+// entries of the grouped sample list, all of one network) and keeps the network's weights in registers until
+// the network changes.  Every layer of Sec. 3.2 / Eq. 7 is computed transposed, out^T = W^T * act^T, with
+// v_mfma_f32_16x16x4_f32: the A operand is a 16(out) x 4(in) block of W^T (lane (m, g) = (lane%16, lane/16)
+// supplies W[in slot g][out m]), the B operand a 4(in) x 16(samples) block of activations (lane (n, g)
+// supplies input slot g of sample n), the accumulator a 16(out) x 16(samples) tile of which lane (n, g)
+// holds outputs 4g + 0..3 of sample n.  An accumulator register is therefore already the B operand of one
+// MFMA of the next layer: MFMA (t, j) of a layer consumes, from lane group g, hidden unit 16t + 4g + j.
+// Which input sits in which slot is free as long as the A operand follows; weights are gathered from the
+// canonical layout into that order once per scene (k_pack_weights_f32), as an image of the register file.
+//
+// Input slots.
+//   gamma(x), 16 MFMAs q: group g < 3: axis g, frequency q/2, sin for even q, cos for odd q;
+//                         group 3:    q < 12: axis q/4, frequency 8 + (q/2)%2, sin / cos; q = 12..14: x, y, z;
+//                                     q = 15: the constant 1 that multiplies b1.
+//   gamma(d), 8 MFMAs q:  group g < 3: axis g, frequency q/2, sin / cos; group 3: dx, dy, dz, 1 (b4), 0 x 4.
+// b2, b3 and b5 initialise accumulators.
+//
+// Density and colour (1 + 3 output rows) share one accumulator among the four 16-sample tiles of a chunk:
+// for tile u the A operand is masked to rows 4u..4u+3 (colour 4u+0..2, density 4u+3), after which lane l holds
+// (r, g, b, sigma) of sample l of the 64.
+//
+// Encoding: accurate sincosf at frequencies 0, 4 (positions), 0 (directions) and 8 (group 3), up to three steps
+// of the double-angle recurrence in between; all in fp32.
 #include "kn_common.h"
 #include "kn_mlp_shared.h"
 
 namespace {
 
-template <int L> __device__ __forceinline__ void posenc_f32(float px, float py, float pz, float *out)
+typedef float f4 __attribute__((ext_vector_type(4)));
+
+constexpr int F32_WAVES = 4;
+constexpr int F32_TILE_LEN = 64;
+
+__device__ __forceinline__ f4 mfma4(float a, float b, f4 c) { return __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, c, 0, 0, 0); }
+
+__device__ __forceinline__ void double_angle(float s, float c, float &s2, float &c2)
 {
-    out[0] = px;
-    out[1] = py;
-    out[2] = pz;
-#pragma unroll
-    for (int k = 0; k < L; ++k) {
-        const float f = (float)(1 << k); // 2^k * p is exact in fp32
-        out[3 + 6 * k + 0] = sinf(f * px);
-        out[3 + 6 * k + 1] = sinf(f * py);
-        out[3 + 6 * k + 2] = sinf(f * pz);
-        out[3 + 6 * k + 3] = cosf(f * px);
-        out[3 + 6 * k + 4] = cosf(f * py);
-        out[3 + 6 * k + 5] = cosf(f * pz);
-    }
+    s2 = 2.0f * (s * c);
+    c2 = fmaf(-2.0f * s, s, 1.0f);
 }
 
-template <int NI, int NO> __device__ __forceinline__ void affine_f32(const float *__restrict__ W, const float *__restrict__ b,
-                                                                     const float *in, float *out)
+// Register file image of one network: register r of lane l sits at packed[(net * N + r) * 64 + l].
+template <int H> struct Regs {
+    static constexpr int HT = H / 16, HQ = H / 4;
+    static constexpr int W1 = 0;                     // (t, q)  -> W1 + 16 t + q
+    static constexpr int W2 = W1 + 16 * HT;          // (t, k)  -> W2 + HQ t + k
+    static constexpr int W3 = W2 + HQ * HT;          // feature rows
+    static constexpr int W4 = W3 + HQ * HT;          // (t, k)  -> W4 + (HQ + 8) t + k; k >= HQ: gamma(d)
+    static constexpr int WO = W4 + (HQ + 8) * HT;    // colour rows (A rows with m%4 < 3) and the density row (m%4 = 3)
+    static constexpr int B2 = WO + HQ;               // (t, j): accumulator initial values of this lane
+    static constexpr int B3 = B2 + 4 * HT;
+    static constexpr int BO = B3 + 4 * HT;
+    static constexpr int N = BO + 4;
+    // canonical offsets (Sec. 3.2: five layers, weights before biases)
+    static constexpr int oW1 = 0, ob1 = 63 * H, oW2 = ob1 + H, ob2 = oW2 + H * H, oW3 = ob2 + H, ob3 = oW3 + H * (H + 1),
+                         oW4 = ob3 + H + 1, ob4 = oW4 + (H + 27) * H, oW5 = ob4 + H, ob5 = oW5 + 3 * H;
+};
+
+// canonical index of the value in register r of lane `lane`; -1 = zero
+template <int H> __device__ int reg_source(int r, int lane)
 {
-#pragma unroll
-    for (int o = 0; o < NO; ++o) out[o] = b[o];
-#pragma unroll
-    for (int i = 0; i < NI; ++i) {
-        const float v = in[i];
-#pragma unroll
-        for (int o = 0; o < NO; ++o) out[o] = fmaf(v, W[i * NO + o], out[o]);
+    using R = Regs<H>;
+    constexpr int HQ = R::HQ;
+    const int m = lane & 15, g = lane >> 4;
+    auto unit = [&](int k) { return 16 * (k >> 2) + 4 * g + (k & 3); }; // hidden unit behind MFMA k for this lane group
+    if (r < R::W2) {
+        const int t = (r - R::W1) >> 4, q = (r - R::W1) & 15, col = 16 * t + m;
+        if (g < 3) return R::oW1 + (3 + 6 * (q >> 1) + 3 * (q & 1) + g) * H + col;
+        if (q < 12) return R::oW1 + (3 + 6 * (8 + ((q >> 1) & 1)) + 3 * (q & 1) + (q >> 2)) * H + col;
+        return q < 15 ? R::oW1 + (q - 12) * H + col : R::ob1 + col;
     }
+    if (r < R::W3) {
+        const int t = (r - R::W2) / HQ, k = (r - R::W2) % HQ;
+        return R::oW2 + unit(k) * H + 16 * t + m;
+    }
+    if (r < R::W4) {
+        const int t = (r - R::W3) / HQ, k = (r - R::W3) % HQ;
+        return R::oW3 + unit(k) * (H + 1) + 1 + 16 * t + m;
+    }
+    if (r < R::WO) {
+        const int t = (r - R::W4) / (HQ + 8), k = (r - R::W4) % (HQ + 8), col = 16 * t + m;
+        if (k < HQ) return R::oW4 + unit(k) * H + col;
+        const int q = k - HQ;
+        if (g < 3) return R::oW4 + (H + 3 + 6 * (q >> 1) + 3 * (q & 1) + g) * H + col;
+        if (q < 3) return R::oW4 + (H + q) * H + col;
+        return q == 3 ? R::ob4 + col : -1;
+    }
+    if (r < R::B2) {
+        const int k = r - R::WO;
+        return (m & 3) < 3 ? R::oW5 + unit(k) * 3 + (m & 3) : R::oW3 + unit(k) * (H + 1);
+    }
+    if (r < R::B3) return R::ob2 + 16 * ((r - R::B2) >> 2) + 4 * g + ((r - R::B2) & 3);
+    if (r < R::BO) return R::ob3 + 1 + 16 * ((r - R::B3) >> 2) + 4 * g + ((r - R::B3) & 3);
+    const int j = r - R::BO;
+    return j < 3 ? R::ob5 + j : R::ob3;
 }
 
 template <int H>
-__global__ void __launch_bounds__(KN_WAVE) k_mlp_f32(const float *__restrict__ weights, int64_t P, KnSampleSrc src,
-                                                     const int32_t *__restrict__ perm, const KnTile *__restrict__ tiles,
-                                                     const int32_t *__restrict__ n_tiles, float *__restrict__ sigma,
-                                                     float *__restrict__ rgb)
+__global__ void k_pack_weights_f32(const float *__restrict__ w, int64_t P, int32_t N, float *__restrict__ packed)
 {
-    constexpr int EX = 63, ED = 27;
-    const int tile = blockIdx.x;
-    if (tile >= *n_tiles) return;
-    const KnTile tl = tiles[tile];
-    const float *__restrict__ w = weights + (int64_t)tl.net * P;
-    const float *W1 = w, *b1 = W1 + EX * H;
-    const float *W2 = b1 + H, *b2 = W2 + H * H;
-    const float *W3 = b2 + H, *b3 = W3 + H * (H + 1);
-    const float *W4 = b3 + (H + 1), *b4 = W4 + (H + ED) * H;
-    const float *W5 = b4 + H, *b5 = W5 + H * 3;
-    const int lane = threadIdx.x;
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    constexpr int64_t per = Regs<H>::N * KN_WAVE;
+    if (i >= per * N) return;
+    const int64_t net = i / per;
+    const int e = (int)(i - net * per);
+    const int s = reg_source<H>(e >> 6, e & 63);
+    packed[i] = s < 0 ? 0.0f : w[net * P + s];
+}
 
-    for (int base = 0; base < tl.len; base += KN_WAVE) {
-        const int j = base + lane;
-        const bool active = j < tl.len;
-        const int32_t idx = perm[tl.start + (active ? j : 0)];
+template <int H>
+__global__ void __launch_bounds__(F32_WAVES *KN_WAVE) __attribute__((amdgpu_waves_per_eu(H == 32 ? 2 : 1, H == 32 ? 2 : 1)))
+    k_mlp_f32(const float *__restrict__ packed, KnSampleSrc src, const int32_t *__restrict__ perm,
+              const KnTile *__restrict__ tiles, const int32_t *__restrict__ n_tiles, float *__restrict__ sigma,
+              float *__restrict__ rgb)
+{
+    constexpr int HT = H / 16, HQ = H / 4; // output tiles per layer, MFMAs per hidden input vector
+    __shared__ float stage[F32_WAVES][KN_WAVE][8]; // x, y, z, dx, dy, dz of the chunk's samples
+
+    const int wave = threadIdx.x / KN_WAVE, lane = threadIdx.x & (KN_WAVE - 1);
+    const int n = lane & 15, g = lane >> 4;
+    const bool g3 = g == 3;
+    const f4 zero4 = {0.0f, 0.0f, 0.0f, 0.0f};
+
+    const int total_tiles = *n_tiles;
+    const int total_waves = gridDim.x * F32_WAVES;
+    const int wid = __builtin_amdgcn_readfirstlane(blockIdx.x * F32_WAVES + wave);
+    const int t_lo = __builtin_amdgcn_readfirstlane((int)((int64_t)wid * total_tiles / total_waves));
+    const int t_hi = __builtin_amdgcn_readfirstlane((int)((int64_t)(wid + 1) * total_tiles / total_waves));
+    if (t_lo >= t_hi) return;
+
+    using R = Regs<H>;
+    float w1[HT][16], w2[HT][HQ], w3[HT][HQ], w4[HT][HQ + 8], wo[HQ];
+    f4 bias2[HT], bias3[HT], bias_out;
+    auto load_network = [&](int32_t net) {
+        const float *__restrict__ wp = packed + (int64_t)net * (R::N * KN_WAVE) + lane;
+        auto reg = [&](int r) { return wp[r * KN_WAVE]; };
+#pragma unroll
+        for (int t = 0; t < HT; ++t) {
+#pragma unroll
+            for (int q = 0; q < 16; ++q) w1[t][q] = reg(R::W1 + 16 * t + q);
+#pragma unroll
+            for (int k = 0; k < HQ; ++k) {
+                w2[t][k] = reg(R::W2 + HQ * t + k);
+                w3[t][k] = reg(R::W3 + HQ * t + k);
+            }
+#pragma unroll
+            for (int k = 0; k < HQ + 8; ++k) w4[t][k] = reg(R::W4 + (HQ + 8) * t + k);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                bias2[t][j] = reg(R::B2 + 4 * t + j);
+                bias3[t][j] = reg(R::B3 + 4 * t + j);
+            }
+        }
+#pragma unroll
+        for (int k = 0; k < HQ; ++k) wo[k] = reg(R::WO + k);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) bias_out[j] = reg(R::BO + j);
+    };
+
+    auto descriptor = [&](int t) -> KnTile { return tiles[min(t, t_hi - 1)]; };
+    auto sample_index = [&](const KnTile &d) { return perm[d.start + min(lane, d.len - 1)]; };
+    KnTile dsc_next = descriptor(t_lo);
+    int32_t idx_next = sample_index(dsc_next);
+    int32_t net_cur = -1;
+
+    for (int t = t_lo; t < t_hi; ++t) {
+        const KnTile tl = dsc_next;
+        const int32_t idx = idx_next;
         float x, y, z, dx, dy, dz;
         kn_load_sample(src, idx, x, y, z, dx, dy, dz);
+        dsc_next = descriptor(t + 1);
+        idx_next = sample_index(dsc_next);
+        if (tl.net != net_cur) { // uniform
+            load_network(tl.net);
+            net_cur = tl.net;
+        }
+        *(f4 *)&stage[wave][lane][0] = (f4){x, y, z, dx};
+        *(f4 *)&stage[wave][lane][4] = (f4){dy, dz, 0.0f, 0.0f};
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 
-        float a[EX > H + ED ? EX : H + ED]; // input of the current layer
-        float h[H + 1];
-        posenc_f32<10>(x, y, z, a);
-        affine_f32<EX, H>(W1, b1, a, h);
+        f4 out = bias_out;
+#pragma unroll 1
+        for (int u = 0; u < 4; ++u) {
+            const f4 s0 = *(const f4 *)&stage[wave][16 * u + n][0];
+            const f4 s1 = *(const f4 *)&stage[wave][16 * u + n][4];
+            const float p[3] = {s0[0], s0[1], s0[2]}, d[3] = {s0[3], s1[0], s1[1]};
+            const float pg = g == 0 ? p[0] : (g == 1 ? p[1] : p[2]);
+            const float dg = g == 0 ? d[0] : (g == 1 ? d[1] : d[2]);
+            // three accurate evaluations per lane; groups 0..2: axis g at frequencies 0 and 4 and the direction at 0,
+            // group 3: the three axes at frequency 8
+            const float ang[3] = {g3 ? 256.0f * p[0] : pg, g3 ? 256.0f * p[1] : 16.0f * pg, g3 ? 256.0f * p[2] : dg};
+            float cs[3][4], cc[3][4];
 #pragma unroll
-        for (int i = 0; i < H; ++i) a[i] = fmaxf(h[i], 0.0f);
-        affine_f32<H, H>(W2, b2, a, h);
+            for (int c = 0; c < 3; ++c) {
+                sincosf(ang[c], &cs[c][0], &cc[c][0]);
 #pragma unroll
-        for (int i = 0; i < H; ++i) a[i] = fmaxf(h[i], 0.0f);
-        affine_f32<H, H + 1>(W3, b3, a, h);
-        const float sg = fmaxf(h[0], 0.0f);
+                for (int k = 1; k < 4; ++k) double_angle(cs[c][k - 1], cc[c][k - 1], cs[c][k], cc[c][k]);
+            }
+            float enc[16], dirv[8];
 #pragma unroll
-        for (int i = 0; i < H; ++i) a[i] = h[1 + i]; // feature vector, no activation
-        posenc_f32<4>(dx, dy, dz, a + H);
-        affine_f32<H + ED, H>(W4, b4, a, h);
+            for (int q = 0; q < 16; ++q) {
+                const int f = q >> 1;
+                const float axis_v = (q & 1) ? cc[f >> 2][f & 3] : cs[f >> 2][f & 3];
+                const float g3_v = q < 12 ? ((q & 1) ? cc[q >> 2][(q >> 1) & 1] : cs[q >> 2][(q >> 1) & 1])
+                                          : (q < 15 ? p[q >= 12 && q < 15 ? q - 12 : 0] : 1.0f);
+                enc[q] = g3 ? g3_v : axis_v;
+            }
 #pragma unroll
-        for (int i = 0; i < H; ++i) a[i] = fmaxf(h[i], 0.0f);
-        float o5[3];
-        affine_f32<H, 3>(W5, b5, a, o5);
-        if (active) {
+            for (int q = 0; q < 8; ++q) {
+                const float axis_v = (q & 1) ? cc[2][q >> 1] : cs[2][q >> 1];
+                const float g3_v = q < 3 ? d[q < 3 ? q : 0] : (q == 3 ? 1.0f : 0.0f);
+                dirv[q] = g3 ? g3_v : axis_v;
+            }
+            const bool my_tile = (n >> 2) == u;
+            const bool sig_row = my_tile && (n & 3) == 3, col_row = my_tile && (n & 3) < 3;
+
+            f4 acc[HT], h[HT];
+            // layer 1: gamma(x) -> H, ReLU
+#pragma unroll
+            for (int t2 = 0; t2 < HT; ++t2) {
+                acc[t2] = zero4;
+#pragma unroll
+                for (int q = 0; q < 16; ++q) acc[t2] = mfma4(w1[t2][q], enc[q], acc[t2]);
+            }
+#pragma unroll
+            for (int t2 = 0; t2 < HT; ++t2)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) h[t2][j] = fmaxf(acc[t2][j], 0.0f);
+            // layer 2: H -> H, ReLU
+#pragma unroll
+            for (int t2 = 0; t2 < HT; ++t2) {
+                acc[t2] = bias2[t2];
+#pragma unroll
+                for (int k = 0; k < HQ; ++k) acc[t2] = mfma4(w2[t2][k], h[k >> 2][k & 3], acc[t2]);
+            }
+#pragma unroll
+            for (int t2 = 0; t2 < HT; ++t2)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) h[t2][j] = fmaxf(acc[t2][j], 0.0f);
+            // layer 3: H -> feature (no activation) and density (row 4u + 3 of the shared tile)
+#pragma unroll
+            for (int t2 = 0; t2 < HT; ++t2) {
+                acc[t2] = bias3[t2];
+#pragma unroll
+                for (int k = 0; k < HQ; ++k) acc[t2] = mfma4(w3[t2][k], h[k >> 2][k & 3], acc[t2]);
+            }
+#pragma unroll
+            for (int k = 0; k < HQ; ++k) out = mfma4(sig_row ? wo[k] : 0.0f, h[k >> 2][k & 3], out);
+#pragma unroll
+            for (int t2 = 0; t2 < HT; ++t2) h[t2] = acc[t2];
+            // layer 4: [feature, gamma(d)] -> H, ReLU
+#pragma unroll
+            for (int t2 = 0; t2 < HT; ++t2) {
+                acc[t2] = zero4;
+#pragma unroll
+                for (int q = 0; q < 8; ++q) acc[t2] = mfma4(w4[t2][HQ + q], dirv[q], acc[t2]);
+#pragma unroll
+                for (int k = 0; k < HQ; ++k) acc[t2] = mfma4(w4[t2][k], h[k >> 2][k & 3], acc[t2]);
+            }
+#pragma unroll
+            for (int t2 = 0; t2 < HT; ++t2)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) h[t2][j] = fmaxf(acc[t2][j], 0.0f);
+            // layer 5: H -> colour rows 4u + 0..2 of the shared tile
+#pragma unroll
+            for (int k = 0; k < HQ; ++k) out = mfma4(col_row ? wo[k] : 0.0f, h[k >> 2][k & 3], out);
+        }
+        __builtin_amdgcn_wave_barrier(); // the staging buffer is rewritten by the next iteration
+
+        if (lane < tl.len) {
+            const float sg = fmaxf(out[3], 0.0f);
             float col[3];
 #pragma unroll
-            for (int c = 0; c < 3; ++c) col[c] = 1.0f / (1.0f + expf(-o5[c]));
+            for (int c = 0; c < 3; ++c) col[c] = 1.0f / (1.0f + expf(-out[c]));
             if (src.out4) {
-                float *o = src.out4 + 4 * (int64_t)idx;
-                o[0] = col[0];
-                o[1] = col[1];
-                o[2] = col[2];
-                o[3] = sg;
+                *(f4 *)(src.out4 + 4 * (int64_t)idx) = (f4){col[0], col[1], col[2], sg};
             } else {
                 sigma[idx] = sg;
 #pragma unroll
@@ -105,18 +290,41 @@ __global__ void __launch_bounds__(KN_WAVE) k_mlp_f32(const float *__restrict__ w
 
 } // namespace
 
+int kn_mlp_f32_tile_len(const kn_scene *) { return F32_TILE_LEN; }
+
+int kn_mlp_f32_pack_weights(kn_scene *sc, hipStream_t st)
+{
+    const int H = sc->desc.hidden;
+    if (H != 32 && H != 64) return KN_E_UNSUPPORTED;
+    const int64_t per = (H == 32 ? Regs<32>::N : Regs<64>::N) * KN_WAVE;
+    KN_HIP(hipMalloc(&sc->packed_w, (size_t)(per * 4 * sc->N)));
+    const int64_t blocks = kn_div_up(per * sc->N, 256);
+    if (blocks > 0x7fffffffLL) return KN_E_UNSUPPORTED;
+    const float *w = (const float *)sc->desc.weights;
+    if (H == 32)
+        hipLaunchKernelGGL(k_pack_weights_f32<32>, dim3((unsigned)blocks), dim3(256), 0, st, w, sc->P, sc->N, (float *)sc->packed_w);
+    else
+        hipLaunchKernelGGL(k_pack_weights_f32<64>, dim3((unsigned)blocks), dim3(256), 0, st, w, sc->P, sc->N, (float *)sc->packed_w);
+    KN_CHECK_LAUNCH();
+    return KN_OK;
+}
+
 int kn_mlp_f32_launch(const kn_scene *sc, hipStream_t st, const KnSampleSrc &src, const KnBucketOut &b, int64_t max_tiles,
                       float *sigma, float *rgb)
 {
     if (max_tiles <= 0) return KN_OK;
-    const float *w = (const float *)sc->desc.weights;
-    dim3 grid((unsigned)max_tiles), block(KN_WAVE);
-    if (sc->desc.hidden == 32)
-        hipLaunchKernelGGL(k_mlp_f32<32>, grid, block, 0, st, w, sc->P, src, b.perm, b.tiles, b.n_tiles, sigma, rgb);
-    else if (sc->desc.hidden == 64)
-        hipLaunchKernelGGL(k_mlp_f32<64>, grid, block, 0, st, w, sc->P, src, b.perm, b.tiles, b.n_tiles, sigma, rgb);
+    const float *w = (const float *)sc->packed_w;
+    const int H = sc->desc.hidden;
+    if (H != 32 && H != 64) return KN_E_UNSUPPORTED;
+    // one workgroup of 4 wavefronts per compute unit and resident wavefront (H = 32: two per SIMD, H = 64: one)
+    int64_t blocks = kn_div_up(max_tiles, F32_WAVES);
+    const int64_t fill = H == 32 ? 512 : 256;
+    if (blocks > fill) blocks = fill;
+    dim3 grid((unsigned)blocks), block(F32_WAVES * KN_WAVE);
+    if (H == 32)
+        hipLaunchKernelGGL(k_mlp_f32<32>, grid, block, 0, st, w, src, b.perm, b.tiles, b.n_tiles, sigma, rgb);
     else
-        return KN_E_UNSUPPORTED;
+        hipLaunchKernelGGL(k_mlp_f32<64>, grid, block, 0, st, w, src, b.perm, b.tiles, b.n_tiles, sigma, rgb);
     KN_CHECK_LAUNCH();
     return KN_OK;
 }
