@@ -63,6 +63,10 @@ def _lib(omp: bool = False):
                                     C.POINTER(C.c_double), C.POINTER(C.c_double)]
         L.kno_render.argtypes = [C.POINTER(Scene), _f32p, _f32p, C.c_int64, C.c_float, C.c_float,
                                  C.c_int32, C.c_float, _f32p, _f64p, C.c_void_p, C.c_void_p, C.c_void_p]
+        _u8p = np.ctypeslib.ndpointer(np.uint8, flags="C_CONTIGUOUS")
+        _i64p = np.ctypeslib.ndpointer(np.int64, flags="C_CONTIGUOUS")
+        L.kno_extract_occupancy_at.argtypes = [C.POINTER(Scene), _i32p, C.c_float, _i64p, C.c_int64, _u8p, _f64p, _f64p]
+        L.kno_extract_occupancy.argtypes = [C.POINTER(Scene), _i32p, C.c_float, _u8p, _f64p, _f64p]
         L.kno_num_threads.restype = C.c_int
         _loaded[omp] = L
     return _loaded[omp]
@@ -144,6 +148,21 @@ class OracleScene:
                                T.ctypes.data, mg.ctypes.data)
         assert rc == 0
         return rgb, n_eval, T, mg
+
+    def extract_occupancy(self, occ_res, tau, voxels=None):
+        """Sec. 3.4 occupancy extraction -> (occupancy bytes, largest probe density, margin to tau), for the
+        whole grid (arrays of shape occ_res) or for the voxels given by linear index."""
+        occ_res = np.asarray(occ_res, np.int32)
+        if voxels is None:
+            n = int(np.prod(occ_res.astype(np.int64)))
+            occ, top, mg = np.empty(n, np.uint8), np.empty(n), np.empty(n)
+            assert self.L.kno_extract_occupancy(C.byref(self.c), occ_res, float(tau), occ, top, mg) == 0
+            shape = tuple(int(r) for r in occ_res)
+            return occ.reshape(shape), top.reshape(shape), mg.reshape(shape)
+        voxels = np.ascontiguousarray(voxels, np.int64)
+        occ, top, mg = np.empty(len(voxels), np.uint8), np.empty(len(voxels)), np.empty(len(voxels))
+        assert self.L.kno_extract_occupancy_at(C.byref(self.c), occ_res, float(tau), voxels, len(voxels), occ, top, mg) == 0
+        return occ, top, mg
 
     def num_threads(self):
         return int(self.L.kno_num_threads())

@@ -22,6 +22,9 @@
  *    ReLU -> 3 sigmoid (Sec. 3.2, "Network Architecture").
  *  - Early termination (Sec. 3.4): after sample i has been blended, stop if T < eps
  *    (strictly); eps = 0 turns it off.  The background colour is added with weight T.
+ *  - Occupancy extraction (Sec. 3.4): the 3x3x3 subgrid of a voxel sits at its sub-cell centres
+ *    (offsets 1/6, 1/2, 5/6 of the voxel per axis); "above" tau is strict; the sampled density
+ *    field is the network grid itself.
  */
 #include "kn_oracle.h"
 
@@ -265,5 +268,74 @@ int kno_render(const kno_scene *s, const float *rays_o, const float *rays_d, int
         if (T_final) T_final[r] = T;
         if (margin) margin[r] = mg_min;
     }
+    return err;
+}
+
+/* Sec. 3.4: one voxel of the occupancy grid, 27 probes. */
+static int extract_voxel(const kno_scene *s, const int32_t occ_res[3], float tau, int64_t voxel,
+                         uint8_t *occ, double *max_sigma, double *margin)
+{
+    static const float sub[3] = {1.0f / 6.0f, 0.5f, 5.0f / 6.0f};
+    const float dir[3] = {0.0f, 0.0f, 1.0f}; /* the density does not depend on the direction */
+    int32_t v[3];
+    v[2] = (int32_t)(voxel % occ_res[2]);
+    v[1] = (int32_t)((voxel / occ_res[2]) % occ_res[1]);
+    v[0] = (int32_t)(voxel / ((int64_t)occ_res[2] * occ_res[1]));
+    float cell[3];
+    for (int a = 0; a < 3; ++a) cell[a] = (s->aabb_max[a] - s->aabb_min[a]) / (float)occ_res[a];
+    int any = 0;
+    double top = 0.0, mg = INFINITY;
+    for (int i = 0; i < 3; ++i)
+        for (int j = 0; j < 3; ++j)
+            for (int k = 0; k < 3; ++k) {
+                const int sel[3] = {i, j, k};
+                float x[3];
+                for (int a = 0; a < 3; ++a) x[a] = fmaf((float)v[a] + sub[sel[a]], cell[a], s->aabb_min[a]);
+                double sg = 0.0, rgb[3];
+                int32_t id = kno_grid_index(s->aabb_min, s->aabb_max, s->res, x);
+                if (id >= 0 && kno_mlp(s, id, x, dir, &sg, rgb) != 0) return -1;
+                if (sg > (double)tau) any = 1;
+                if (sg > top) top = sg;
+                if (fabs(sg - (double)tau) < mg) mg = fabs(sg - (double)tau);
+            }
+    *occ = (uint8_t)any;
+    if (max_sigma) *max_sigma = top;
+    if (margin) *margin = mg;
+    return 0;
+}
+
+int kno_extract_occupancy_at(const kno_scene *s, const int32_t occ_res[3], float tau,
+                             const int64_t *voxels, int64_t n, uint8_t *occ, double *max_sigma,
+                             double *margin)
+{
+    if (!s || !occ_res || occ_res[0] < 1 || occ_res[1] < 1 || occ_res[2] < 1 || n < 0 || (n > 0 && (!voxels || !occ)))
+        return -1;
+    const int64_t total = (int64_t)occ_res[0] * occ_res[1] * occ_res[2];
+    int err = 0;
+#ifdef _OPENMP
+#pragma omp parallel for schedule(dynamic, 64)
+#endif
+    for (int64_t i = 0; i < n; ++i) {
+        if (voxels[i] < 0 || voxels[i] >= total ||
+            extract_voxel(s, occ_res, tau, voxels[i], occ + i, max_sigma ? max_sigma + i : NULL,
+                          margin ? margin + i : NULL) != 0)
+            err = -1;
+    }
+    return err;
+}
+
+int kno_extract_occupancy(const kno_scene *s, const int32_t occ_res[3], float tau, uint8_t *occ,
+                          double *max_sigma, double *margin)
+{
+    if (!s || !occ_res || occ_res[0] < 1 || occ_res[1] < 1 || occ_res[2] < 1 || !occ) return -1;
+    const int64_t total = (int64_t)occ_res[0] * occ_res[1] * occ_res[2];
+    int err = 0;
+#ifdef _OPENMP
+#pragma omp parallel for schedule(dynamic, 64)
+#endif
+    for (int64_t vx = 0; vx < total; ++vx)
+        if (extract_voxel(s, occ_res, tau, vx, occ + vx, max_sigma ? max_sigma + vx : NULL,
+                          margin ? margin + vx : NULL) != 0)
+            err = -1;
     return err;
 }

@@ -11,7 +11,10 @@
  * index, occupancy voxel) is taken in fp32 with one fixed operation sequence,
  * because the index is only well defined for one precision.  Everything else
  * (positional encoding, the affine layers, activations, compositing) runs in
- * fp64 on the fp32 inputs.
+ * fp64 on the fp32 inputs.  Two decisions rest on such fp64 values, early
+ * termination (T < eps) and occupancy extraction (sigma > tau): there the oracle
+ * also reports how close the value came to the threshold, so that a check can
+ * tell a legitimate rounding difference from a mistake.
  *
  * All pointers are host pointers.  No function allocates memory that outlives
  * the call.  Return value 0 = ok, negative = invalid argument.
@@ -86,6 +89,22 @@ int32_t kno_composite(const double *sigma, const double *rgb, int32_t n, double 
 int kno_render(const kno_scene *s, const float *rays_o, const float *rays_d, int64_t R,
                float t_near, float step, int32_t K, float term_eps, const float bg[3],
                double *rgb_out, int32_t *n_eval, double *T_final, double *margin);
+
+/* Occupancy grid extraction (Sec. 3.4, "Empty Space Skipping"; tau: Sec. 4.1): the density is
+ * sampled on a 3x3x3 subgrid of every voxel of a grid of resolution occ_res over the AABB and the
+ * voxel is marked (1) iff any of the 27 densities is above tau (strictly), else 0.  The density
+ * field is the scene's own network grid (the paper samples its teacher model); a probe is
+ * evaluated by the network of the cell it lies in (Eq. 6).  Probe positions (the paper does not
+ * place the subgrid): sub-cell centres, per axis x = bmin + (v + c) * cell with c in {1/6, 1/2, 5/6},
+ * cell = (bmax - bmin) / occ_res, taken in fp32 as fmaf((float)v + c, cell, bmin).
+ * kno_extract_occupancy_at does this for n voxels given by linear index (x slowest);
+ * kno_extract_occupancy for the whole grid.  Optional outputs per voxel (nullable): max_sigma =
+ * the largest of the 27 densities, margin = min over the probes of |sigma - tau|. */
+int kno_extract_occupancy_at(const kno_scene *s, const int32_t occ_res[3], float tau,
+                             const int64_t *voxels, int64_t n, uint8_t *occ, double *max_sigma,
+                             double *margin);
+int kno_extract_occupancy(const kno_scene *s, const int32_t occ_res[3], float tau, uint8_t *occ,
+                          double *max_sigma, double *margin);
 
 /* Number of threads the loops over rays / points use (1 unless built with OpenMP). */
 int kno_num_threads(void);

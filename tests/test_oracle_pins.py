@@ -407,6 +407,112 @@ def test_render_ert_bound_and_straddle_margin():
     assert np.all(mg[n_cut > 0] >= 0)
 
 
+# ------------------------------------------------------------------ occupancy extraction (Sec. 3.4)
+def _probe_coords(lo, hi, res):
+    """(res, 3) positions of the three sub-cell centres of every voxel along one axis, fp64."""
+    v = np.arange(res)[:, None]
+    return lo + (v + np.array([1 / 6, 1 / 2, 5 / 6])[None, :]) * ((hi - lo) / res)
+
+
+def test_extraction_constant_density_and_strict_threshold():
+    w = zero_net(n=8)
+    ks.layer_views(w, 32)[2][1][:, 0] = 10.0                      # b3[0]: sigma = 10 everywhere
+    sc = unit_scene(w, res=(2, 2, 2))
+    occ, top, mg = sc.extract_occupancy((3, 4, 5), 9.999)
+    assert occ.shape == (3, 4, 5) and occ.dtype == np.uint8 and np.all(occ == 1)
+    np.testing.assert_array_equal(top, 10.0)
+    np.testing.assert_allclose(mg, 0.001, atol=1e-6)            # tau is rounded to fp32 first
+    occ, _, mg = sc.extract_occupancy((3, 4, 5), 10.0)            # "above tau" is strict
+    assert np.all(occ == 0) and np.all(mg == 0)
+
+
+@pytest.mark.parametrize("axis", [0, 1, 2])
+@pytest.mark.parametrize("sign", [1.0, -1.0])
+def test_extraction_linear_field_marks_voxels_by_their_extreme_probe(axis, sign):
+    # sigma = relu(sign * k * (x_axis - mid) + 4), k = 8 / extent: rising (or falling) from 0 to 8 along one axis of
+    # the box [-1,1]x[0,2]x[1,5].
+    # A voxel is marked iff the probe with the largest density, the one at offset 5/6 (rising) or 1/6 (falling)
+    # of the voxel along that axis, is above tau.  Which axis of the output array follows the field pins the
+    # x-slowest layout.
+    lo, hi, res = np.array([-1.0, 0.0, 1.0]), np.array([1.0, 2.0, 5.0]), (7, 6, 9)
+    w = zero_net(n=6)
+    lv = ks.layer_views(w, 32)
+    k, mid = 8.0 / (hi[axis] - lo[axis]), 0.5 * (lo[axis] + hi[axis])
+    lv[0][0][:, axis, 0] = sign * k                                # identity input `axis` -> h1[0]
+    lv[0][1][:, 0] = -sign * k * mid + 4.0
+    lv[1][0][:, 0, 0] = 1.0
+    lv[2][0][:, 0, 0] = 1.0
+    sc = unit_scene(w, res=(1, 2, 3), lo=lo, hi=hi)
+    tau = 5.0
+    occ, top, mg = sc.extract_occupancy(res, tau)
+    pc = _probe_coords(lo[axis], hi[axis], res[axis])               # (res, 3)
+    dens = np.maximum(sign * k * (pc - mid) + 4.0, 0.0)
+    want_line = dens.max(axis=1) > tau
+    assert 0 < want_line.sum() < res[axis]
+    assert np.abs(dens - tau).min() > 1e-3                        # no probe sits on the threshold
+    shape = [1, 1, 1]
+    shape[axis] = res[axis]
+    want = np.broadcast_to(want_line.reshape(shape), res)
+    np.testing.assert_array_equal(occ, want.astype(np.uint8))
+    np.testing.assert_allclose(top, np.broadcast_to(dens.max(axis=1).reshape(shape), res), atol=1e-5)
+    np.testing.assert_allclose(mg, np.broadcast_to(np.abs(dens - tau).min(axis=1).reshape(shape), res), atol=1e-5)
+
+
+def test_extraction_sees_the_centre_probe():
+    # A tent of half-width 0.02 around the centre of voxel 3 of 8 along y (unit cube): narrower than the distance to
+    # the neighbouring probes (1/24), so only the probe at offset 1/2 of that voxel is above tau.
+    c = (3 + 0.5) / 8
+    w = zero_net()
+    lv = ks.layer_views(w, 32)
+    lv[0][0][0, 1, 0], lv[0][1][0, 0] = 1.0, -c                  # h1[0] = relu(y - c)
+    lv[0][0][0, 1, 1], lv[0][1][0, 1] = -1.0, c                  # h1[1] = relu(c - y)
+    lv[1][0][0, 0, 0] = lv[1][0][0, 1, 0] = -50.0                # h2[0] = relu(1 - 50 |y - c|)
+    lv[1][1][0, 0] = 1.0
+    lv[2][0][0, 0, 0] = 20.0                                       # sigma = 20 h2[0]
+    occ, top, _ = unit_scene(w).extract_occupancy((2, 8, 2), 10.0)
+    want = np.zeros((2, 8, 2), np.uint8)
+    want[:, 3, :] = 1
+    np.testing.assert_array_equal(occ, want)
+    np.testing.assert_allclose(top[:, 3, :], 20.0, atol=1e-4)
+    # moved to offset 1/6 of the same voxel, then to the voxel boundary where no probe sits
+    for centre, hit in (((3 + 1 / 6) / 8, True), (3 / 8, False)):
+        lv[0][1][0, 0], lv[0][1][0, 1] = -centre, centre
+        occ, _, _ = unit_scene(w).extract_occupancy((2, 8, 2), 10.0)
+        assert bool(occ[:, 3, :].all()) == hit and occ.sum() == (4 if hit else 0)
+
+
+def test_extraction_uses_the_network_of_the_probes_cell_and_the_voxel_list_form():
+    # 2x1x1 networks with different constant densities, 3 voxels along x: the middle voxel straddles the cell
+    # boundary, its probes at offsets 1/6 (x = 0.389) and 1/2 (x = 0.5) fall into different cells.
+    w = zero_net(n=2)
+    ks.layer_views(w, 32)[2][1][0, 0] = 1.0
+    ks.layer_views(w, 32)[2][1][1, 0] = 7.0
+    sc = unit_scene(w, res=(2, 1, 1))
+    occ, top, _ = sc.extract_occupancy((3, 1, 1), 5.0)
+    assert occ.ravel().tolist() == [0, 1, 1] and top.ravel().tolist() == [1.0, 7.0, 7.0]
+    occ, top, _ = sc.extract_occupancy((3, 1, 1), 0.5)
+    assert occ.ravel().tolist() == [1, 1, 1]
+    # the per-voxel form agrees with the whole-grid form on a random scene
+    sc = OracleScene((2, 3, 2), (0, 0, 0), (1, 1, 1), 32, ks.kaiming_weights(12, 32, 77, sigma_scale=20.0))
+    tau = float(np.median(sc.extract_occupancy((5, 4, 6), 0.0)[1]))   # random weights: take tau inside the range
+    full, ftop, fmg = sc.extract_occupancy((5, 4, 6), tau)
+    assert 0 < full.sum() < full.size
+    np.testing.assert_array_equal(full, (ftop > np.float32(tau)).astype(np.uint8))
+    pick = np.array([0, 7, 33, 64, 119], np.int64)
+    o, t, m = sc.extract_occupancy((5, 4, 6), tau, voxels=pick)
+    np.testing.assert_array_equal(o, full.ravel()[pick])
+    np.testing.assert_array_equal(t, ftop.ravel()[pick])
+    np.testing.assert_array_equal(m, fmg.ravel()[pick])
+    # and with 27 explicit evaluations per voxel at independently computed probe positions
+    for vox in pick:
+        ix, iy, iz = np.unravel_index(vox, (5, 4, 6))
+        offs = np.array([1 / 6, 1 / 2, 5 / 6])
+        gx, gy, gz = np.meshgrid((ix + offs) / 5, (iy + offs) / 4, (iz + offs) / 6, indexing="ij")
+        pts = np.stack([gx.ravel(), gy.ravel(), gz.ravel()], 1).astype(np.float32)
+        sg, _, _ = sc.eval_points(pts, np.tile(np.float32([0, 0, 1]), (27, 1)))
+        assert abs(sg.max() - ftop.ravel()[vox]) < 1e-4 * (1 + sg.max())
+
+
 def test_threaded_build_gives_identical_results():
     w = ks.kaiming_weights(8, 32, 1)
     a = OracleScene((2, 2, 2), (0, 0, 0), (1, 1, 1), 32, w)
