@@ -126,6 +126,33 @@ def isolated_mlp(kn, torch, wdtype, iters=10):
             "mlp_hbm_gbps_algorithmic": (24.0 + 4.0 + 16.0 + 3.5) * M / (mlp_ms * 1e-3) / 1e9}
 
 
+def occupancy_extraction(kn, torch, scene, sc, occ_res, iters=5):
+    """Occupancy grid extraction (the step that produces the grid the renderer skips with): 27 density probes per voxel
+    of a grid of the workload's size, from the workload's own networks, tau as in the paper's Sec. 4.1."""
+    import numpy as np
+    out = torch.empty(tuple(occ_res), dtype=torch.uint8, device="cuda")
+    for _ in range(2):
+        scene.extract_occupancy(occ_res, 10.0, out=out)
+    torch.cuda.synchronize()
+    kn.profile_enable(True)
+    kn.profile_read(reset=True)
+    for _ in range(iters):
+        scene.extract_occupancy(occ_res, 10.0, out=out)
+    prof = kn.profile_read(reset=True)
+    kn.profile_enable(False)
+    H = sc["hidden"]
+    probes = 27 * int(np.prod(occ_res))
+    flop = 2 * (63 * H + H * H + H)          # layers 1 and 2 and the density row of layer 3
+    ms = prof["ms_mlp"] / iters
+    tf = flop * probes / (ms * 1e-3) / 1e12
+    return {"workload": "%dx%dx%d voxels x 27 probes, %s networks of width %d, %s, tau = 10" %
+                        (*occ_res, "x".join(str(r) for r in sc["res"]), H, sc["wdtype"]),
+            "probes": probes, "ms_probe_kernel": ms, "ms_setup": prof["ms_setup"] / iters, "probes_per_sec": probes / (ms * 1e-3),
+            "voxels_marked_frac": float(out.float().mean().item()),
+            "roofline": {"kernel": "k_probe_mfma (density of the probe points)", "bound": "mfma", "achieved": tf,
+                         "peak": PEAK_MFMA_16BIT / 1e12, "unit": "TFLOP/s", "frac": tf * 1e12 / PEAK_MFMA_16BIT, "traffic": None}}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -260,6 +287,7 @@ def main():
         torch.cuda.synchronize()
         del src_buf, dst_buf
     if a.wdtype in ("f16", "bf16"):
+        res["occupancy_extraction"] = occupancy_extraction(kn, torch, scene, sc, sc["occupancy"].shape)
         del scene
         torch.cuda.empty_cache()
         res["isolated_mlp"] = isolated_mlp(kn, torch, a.wdtype)

@@ -155,6 +155,25 @@ int kn_render(const kn_scene *scene, void *stream, const float *rays_o /*dev R*3
               const float bg[3] /*host*/, float *rgb_out /*dev R*3*/,
               kn_render_stats *stats /*host, nullable*/, void *workspace, int64_t workspace_bytes);
 
+/* Sec. 3.4 ("Empty Space Skipping"; tau: Sec. 4.1): fill an occupancy grid of resolution occ_res
+ * over the scene's AABB.  The density is sampled on a 3x3x3 subgrid of every voxel and the voxel
+ * is marked (byte 1, else 0) iff any of the 27 densities is above tau (strictly).  The density
+ * field is the scene's own network grid (the paper samples its teacher model); a probe is
+ * evaluated by the network of the cell it lies in (Eq. 6), whether or not occ_res is a multiple
+ * of the network grid.  The paper does not place the subgrid; it sits at the sub-cell centres, per
+ * axis x = b_min + (v + c) * cell, c in {1/6, 1/2, 5/6}, cell = (b_max - b_min) / occ_res, taken
+ * in fp32 as fma((float)v + c, cell, b_min).  Only layers 1-3 of the networks run (the density
+ * does not depend on the direction), with the scene's arithmetic (fp32, or 16-bit operands).
+ * occupancy: dev, occ_res[0]*occ_res[1]*occ_res[2] bytes, x slowest -- the format kn_scene_desc
+ * takes; any occupancy grid the scene itself was created with plays no role.  The workspace
+ * (kn_extract_workspace_bytes, dev, 256-byte aligned) holds small index tables.  Asynchronous on
+ * `stream`.  KN_E_UNSUPPORTED above 2^31-1 voxels, or when one network cell would own more than
+ * about 79 million voxels. */
+int kn_extract_workspace_bytes(const kn_scene *scene, int64_t *out_bytes);
+int kn_extract_occupancy(const kn_scene *scene, void *stream, const int32_t occ_res[3] /*host*/,
+                         float tau, uint8_t *occupancy /*dev, out*/, void *workspace,
+                         int64_t workspace_bytes);
+
 /* Tuning knobs of kn_render (process-wide, for experiments; defaults are used otherwise):
  * samples per ray in the first wave, the slot budget per ray (workspace size; later waves share
  * the budget out among the surviving rays), and the factor by which the samples per ray grow from

@@ -18,6 +18,7 @@ KN_F32, KN_F16, KN_BF16 = 0, 1, 2
 DTYPES = {"f32": KN_F32, "f16": KN_F16, "bf16": KN_BF16}
 
 EXPORTS = ["kn_error_string", "kn_last_hip_error", "kn_params_per_net", "kn_scene_create", "kn_scene_destroy",
+           "kn_extract_workspace_bytes", "kn_extract_occupancy",
            "kn_workspace_bytes", "kn_cell_ids", "kn_bucket", "kn_eval_grouped", "kn_march", "kn_composite",
            "kn_render", "kn_set_render_params", "kn_profile_enable", "kn_profile_read"]
 
@@ -73,6 +74,8 @@ def load_library(build_if_missing: bool = True):
     L.kn_bucket.argtypes = [vp, vp, vp, i64, vp, vp, vp, vp, i64]
     L.kn_eval_grouped.argtypes = [vp, vp, vp, vp, i64, vp, vp, vp, vp, vp, vp, i64]
     L.kn_march.argtypes = [vp, vp, vp, vp, i64, f32, f32, i32, vp, i32, vp, vp, vp]
+    L.kn_extract_workspace_bytes.argtypes = [vp, C.POINTER(i64)]
+    L.kn_extract_occupancy.argtypes = [vp, vp, C.POINTER(i32 * 3), f32, vp, vp, i64]
     L.kn_composite.argtypes = [vp, vp, vp, vp, i64, f32, f32, C.POINTER(f32 * 3), vp, vp, vp]
     L.kn_render.argtypes = [vp, vp, vp, vp, i64, f32, f32, i32, f32, C.POINTER(f32 * 3), vp,
                             C.POINTER(RenderStats), vp, i64]
@@ -222,6 +225,19 @@ class Scene:
         if want_aux:
             return sigma, rgb, ids, counts, perm
         return sigma, rgb
+
+    def extract_occupancy(self, occ_res, tau, out=None):
+        """Occupancy grid of resolution ``occ_res`` from the scene's own density field (27 probes per voxel,
+        marked where any density is above ``tau``): a uint8 device tensor of shape ``occ_res``."""
+        import torch
+        res = tuple(int(r) for r in occ_res)
+        occ = torch.empty(res, dtype=torch.uint8, device=self.device) if out is None else out
+        need = C.c_int64()
+        _check(self.L.kn_extract_workspace_bytes(self.h, C.byref(need)), "kn_extract_workspace_bytes")
+        ws = torch.empty(int(need.value), dtype=torch.uint8, device=self.device)
+        _check(self.L.kn_extract_occupancy(self.h, _stream(), C.byref((C.c_int32 * 3)(*res)), float(tau), _ptr(occ, torch.uint8),
+                                           _ptr(ws), ws.numel()), "kn_extract_occupancy")
+        return occ
 
     def march(self, rays_o, rays_d, t_near, step, K, S=None, k_begin=None):
         import torch

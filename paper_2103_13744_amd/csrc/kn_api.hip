@@ -1,5 +1,6 @@
 // Host side of the C ABI: scene objects, validation, workspace sizing, kn_eval_grouped.
 #include "kn_common.h"
+#include "kn_probe.h"
 
 #include <math.h>
 #include <new>
@@ -18,6 +19,8 @@ int kn_mlp_mfma_launch(const kn_scene *sc, hipStream_t st, const KnSampleSrc &sr
 int kn_mlp_mfma_tile_len(const kn_scene *sc);
 int kn_mlp_f32_tile_len(const kn_scene *sc);
 int kn_mlp_f32_pack_weights(kn_scene *sc, hipStream_t st);
+int kn_probe_mfma_launch(const kn_scene *sc, hipStream_t st, const KnProbeJob &job);
+int kn_probe_f32_launch(const kn_scene *sc, hipStream_t st, const KnProbeJob &job);
 
 kn_profile g_kn_profile = {};
 bool g_kn_profile_on = false;
@@ -419,6 +422,105 @@ extern "C" int kn_eval_grouped(const kn_scene *sc, void *stream, const float *po
         g_kn_profile.mlp_launches += 1;
         g_kn_profile.mlp_samples += M; // includes points outside the AABB (they cost no MLP work)
         g_kn_profile.bucket_keys += M;
+        g_kn_profile.calls += 1;
+    }
+    return KN_OK;
+}
+
+// ---------------------------------------------------------------------------------------------
+// Occupancy grid extraction (Sec. 3.4)
+namespace {
+
+__global__ void k_zero_bytes(uint8_t *p, int64_t n)
+{
+    const int64_t i = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) * 16;
+    if (i + 16 <= n && ((uintptr_t)(p + i) & 15) == 0) {
+        *(uint4 *)(p + i) = make_uint4(0u, 0u, 0u, 0u);
+    } else {
+        for (int64_t j = i; j < n && j < i + 16; ++j) p[j] = 0;
+    }
+}
+
+// first[c] = first voxel along axis blockIdx.x whose centre lies in network cell c or beyond (res + 1 entries):
+// the voxels whose centre lies in cell c are first[c] .. first[c+1]-1.
+__global__ void k_probe_ranges(KnGrid occ, KnGrid net, int32_t *first0, int32_t *first1, int32_t *first2)
+{
+    const int a = blockIdx.x;
+    int32_t *first = a == 0 ? first0 : (a == 1 ? first1 : first2);
+    const int nc = net.res[a], nv = occ.res[a];
+    for (int c = threadIdx.x; c <= nc; c += blockDim.x) first[c] = nv;
+    __syncthreads();
+    auto home = [&](int v) {
+        const float x = fmaf((float)v + 0.5f, occ.cell[a], occ.bmin[a]);
+        const float f = floorf((x - net.bmin[a]) / net.cell[a]);
+        return (int)fminf(fmaxf(f, 0.0f), (float)(nc - 1));
+    };
+    for (int v = threadIdx.x; v < nv; v += blockDim.x) {
+        const int h = home(v), before = v == 0 ? -1 : home(v - 1); // non-decreasing in v
+        for (int c = before + 1; c <= h; ++c) first[c] = v;
+    }
+}
+
+int64_t extract_ws_bytes(const kn_scene *sc)
+{
+    int64_t b = 0;
+    for (int a = 0; a < 3; ++a) b += kn_align_up(((int64_t)sc->desc.res[a] + 1) * 4, 256);
+    return b;
+}
+
+} // namespace
+
+extern "C" int kn_extract_workspace_bytes(const kn_scene *sc, int64_t *out_bytes)
+{
+    if (!sc || !out_bytes) return KN_E_INVALID_ARG;
+    *out_bytes = extract_ws_bytes(sc) + 256;
+    return KN_OK;
+}
+
+extern "C" int kn_extract_occupancy(const kn_scene *sc, void *stream, const int32_t occ_res[3], float tau,
+                                    uint8_t *occupancy, void *workspace, int64_t workspace_bytes)
+{
+    if (!sc || !occ_res || !occupancy || tau != tau) return KN_E_INVALID_ARG;
+    KnProbeJob job{};
+    if (!make_grid(sc->desc.aabb_min, sc->desc.aabb_max, occ_res, job.occ)) return KN_E_INVALID_ARG;
+    const int64_t voxels = (int64_t)occ_res[0] * occ_res[1] * occ_res[2];
+    if (voxels > 0x7fffffffLL) return KN_E_UNSUPPORTED;
+    // upper bound of the voxels one network cell can own, and the nominal number of tiles per cell
+    int64_t box = 1;
+    for (int a = 0; a < 3; ++a) box *= kn_div_up(occ_res[a], sc->desc.res[a]) + 1;
+    if (box > KN_PROBE_MAX_BOX) return KN_E_UNSUPPORTED;
+    if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < extract_ws_bytes(sc)) return KN_E_WORKSPACE;
+    hipStream_t st = (hipStream_t)stream;
+    KnCarver ws(workspace, workspace_bytes);
+    int32_t *first[3];
+    for (int a = 0; a < 3; ++a) first[a] = ws.carve<int32_t>(sc->desc.res[a] + 1);
+    if (!ws.ok()) return KN_E_WORKSPACE;
+    job.net = sc->net_grid;
+    for (int a = 0; a < 3; ++a) job.first[a] = first[a];
+    job.tau = tau;
+    job.occupancy = occupancy;
+    // enough workgroups to fill the chip several times over, but at least some tens of tiles per wavefront
+    const int64_t tiles_per_cell = kn_div_up(KN_PROBES * kn_div_up(voxels, sc->N), KN_WAVE);
+    int64_t parts = kn_div_up(2048, sc->N);
+    if (parts > tiles_per_cell / 32) parts = tiles_per_cell / 32;
+    if (parts < 1) parts = 1;
+    job.parts = (int32_t)parts;
+
+    KnStageTimer tm(st);
+    tm.begin();
+    hipLaunchKernelGGL(k_zero_bytes, dim3((unsigned)kn_div_up(kn_div_up(voxels, 16), 256)), dim3(256), 0, st, occupancy, voxels);
+    KN_CHECK_LAUNCH();
+    hipLaunchKernelGGL(k_probe_ranges, dim3(3), dim3(256), 0, st, job.occ, job.net, first[0], first[1], first[2]);
+    KN_CHECK_LAUNCH();
+    tm.mark(KN_ST_SETUP);
+    if (sc->desc.wdtype == KN_F32)
+        KN_TRY(kn_probe_f32_launch(sc, st, job));
+    else
+        KN_TRY(kn_probe_mfma_launch(sc, st, job));
+    tm.mark(KN_ST_MLP);
+    if (tm.on) {
+        g_kn_profile.mlp_launches += 1;
+        g_kn_profile.mlp_samples += KN_PROBES * voxels;
         g_kn_profile.calls += 1;
     }
     return KN_OK;

@@ -26,6 +26,7 @@
 // of the double-angle recurrence in between; all in fp32.
 #include "kn_common.h"
 #include "kn_mlp_shared.h"
+#include "kn_probe.h"
 
 namespace {
 
@@ -288,6 +289,132 @@ __global__ void __launch_bounds__(F32_WAVES *KN_WAVE) __attribute__((amdgpu_wave
     }
 }
 
+
+// Density only, for occupancy extraction (Sec. 3.4): layers 1 and 2 and the density row of layer 3 at the probe
+// points of one network cell's voxels, which are generated in the kernel.  Same formulation as k_mlp_f32.
+template <int H>
+__global__ void __launch_bounds__(F32_WAVES *KN_WAVE) __attribute__((amdgpu_waves_per_eu(2, 2)))
+    k_probe_f32(const float *__restrict__ packed, KnProbeJob job)
+{
+    using R = Regs<H>;
+    constexpr int HT = H / 16, HQ = H / 4;
+    __shared__ float stage[F32_WAVES][KN_WAVE][4];
+    const int wave = threadIdx.x / KN_WAVE, lane = threadIdx.x & (KN_WAVE - 1);
+    const int n = lane & 15, g = lane >> 4;
+    const bool g3 = g == 3;
+    const f4 zero4 = {0.0f, 0.0f, 0.0f, 0.0f};
+
+    const int32_t cell = blockIdx.x / job.parts, part = blockIdx.x - cell * job.parts;
+    const KnProbeBox box = kn_probe_box(job, cell);
+    if (box.points == 0) return;
+    const int shares = job.parts * F32_WAVES, share = part * F32_WAVES + wave;
+    const int t_lo = __builtin_amdgcn_readfirstlane((int)((int64_t)share * box.tiles / shares));
+    const int t_hi = __builtin_amdgcn_readfirstlane((int)((int64_t)(share + 1) * box.tiles / shares));
+    if (t_lo >= t_hi) return;
+
+    float w1[HT][16], w2[HT][HQ], wo[HQ], bias_sig = 0.0f;
+    f4 bias2[HT];
+    auto load_network = [&](int32_t net) {
+        const float *__restrict__ wp = packed + (int64_t)net * (R::N * KN_WAVE) + lane;
+        auto reg = [&](int r) { return wp[r * KN_WAVE]; };
+#pragma unroll
+        for (int t = 0; t < HT; ++t) {
+#pragma unroll
+            for (int q = 0; q < 16; ++q) w1[t][q] = reg(R::W1 + 16 * t + q);
+#pragma unroll
+            for (int k = 0; k < HQ; ++k) w2[t][k] = reg(R::W2 + HQ * t + k);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) bias2[t][j] = reg(R::B2 + 4 * t + j);
+        }
+#pragma unroll
+        for (int k = 0; k < HQ; ++k) wo[k] = reg(R::WO + k);
+        bias_sig = reg(R::BO + 3);
+    };
+    int32_t net_loaded = -1;
+
+    for (int t = t_lo; t < t_hi; ++t) {
+        const int32_t p = t * KN_WAVE + lane;
+        const bool active = p < box.points;
+        float x, y, z;
+        int64_t voxel;
+        int32_t probe;
+        kn_probe_point(job, box, min(p, box.points - 1), x, y, z, voxel, probe);
+        const int32_t net = kn_grid_index(job.net, x, y, z);
+        bool todo = active && net >= 0;
+        float sg = 0.0f;
+        *(f4 *)&stage[wave][lane][0] = (f4){x, y, z, 0.0f};
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+
+        // one pass per network met in the tile (a single one when the grids nest)
+        for (;;) {
+            const unsigned long long pending = __ballot(todo);
+            if (pending == 0ull) break;
+            const int32_t nsel = __builtin_amdgcn_readlane(net, (int)__builtin_ctzll(pending));
+            if (nsel != net_loaded) {
+                load_network(nsel);
+                net_loaded = nsel;
+            }
+            f4 out = {0.0f, 0.0f, 0.0f, bias_sig};
+#pragma unroll 1
+            for (int u = 0; u < 4; ++u) {
+                const f4 s0 = *(const f4 *)&stage[wave][16 * u + n][0];
+                const float pt[3] = {s0[0], s0[1], s0[2]};
+                const float pg = g == 0 ? pt[0] : (g == 1 ? pt[1] : pt[2]);
+                // groups 0..2: axis g at frequencies 0 and 4; group 3: the three axes at frequency 8
+                const float ang[3] = {g3 ? 256.0f * pt[0] : pg, g3 ? 256.0f * pt[1] : 16.0f * pg, 256.0f * pt[2]};
+                float cs[3][4], cc[3][4];
+#pragma unroll
+                for (int c = 0; c < 3; ++c) {
+                    sincosf(ang[c], &cs[c][0], &cc[c][0]);
+#pragma unroll
+                    for (int k = 1; k < 4; ++k) double_angle(cs[c][k - 1], cc[c][k - 1], cs[c][k], cc[c][k]);
+                }
+                float enc[16];
+#pragma unroll
+                for (int q = 0; q < 16; ++q) {
+                    const int f = q >> 1;
+                    const float axis_v = (q & 1) ? cc[f >> 2][f & 3] : cs[f >> 2][f & 3];
+                    const float g3_v = q < 12 ? ((q & 1) ? cc[q >> 2][(q >> 1) & 1] : cs[q >> 2][(q >> 1) & 1])
+                                              : (q < 15 ? pt[q >= 12 && q < 15 ? q - 12 : 0] : 1.0f);
+                    enc[q] = g3 ? g3_v : axis_v;
+                }
+                const bool sig_row = (n >> 2) == u && (n & 3) == 3;
+                f4 acc[HT], h[HT];
+#pragma unroll
+                for (int t2 = 0; t2 < HT; ++t2) {
+                    acc[t2] = zero4;
+#pragma unroll
+                    for (int q = 0; q < 16; ++q) acc[t2] = mfma4(w1[t2][q], enc[q], acc[t2]);
+                }
+#pragma unroll
+                for (int t2 = 0; t2 < HT; ++t2)
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) h[t2][j] = fmaxf(acc[t2][j], 0.0f);
+#pragma unroll
+                for (int t2 = 0; t2 < HT; ++t2) {
+                    acc[t2] = bias2[t2];
+#pragma unroll
+                    for (int k = 0; k < HQ; ++k) acc[t2] = mfma4(w2[t2][k], h[k >> 2][k & 3], acc[t2]);
+                }
+#pragma unroll
+                for (int t2 = 0; t2 < HT; ++t2)
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) h[t2][j] = fmaxf(acc[t2][j], 0.0f);
+#pragma unroll
+                for (int k = 0; k < HQ; ++k) out = mfma4(sig_row ? wo[k] : 0.0f, h[k >> 2][k & 3], out);
+            }
+            if (todo && net == nsel) {
+                sg = fmaxf(out[3], 0.0f);
+                todo = false;
+            }
+        }
+        __builtin_amdgcn_wave_barrier(); // the staging buffer is rewritten by the next iteration
+        kn_probe_mark(job, active, sg > job.tau, voxel, probe, lane);
+    }
+}
+
 } // namespace
 
 int kn_mlp_f32_tile_len(const kn_scene *) { return F32_TILE_LEN; }
@@ -325,6 +452,20 @@ int kn_mlp_f32_launch(const kn_scene *sc, hipStream_t st, const KnSampleSrc &src
         hipLaunchKernelGGL(k_mlp_f32<32>, grid, block, 0, st, w, src, b.perm, b.tiles, b.n_tiles, sigma, rgb);
     else
         hipLaunchKernelGGL(k_mlp_f32<64>, grid, block, 0, st, w, src, b.perm, b.tiles, b.n_tiles, sigma, rgb);
+    KN_CHECK_LAUNCH();
+    return KN_OK;
+}
+
+int kn_probe_f32_launch(const kn_scene *sc, hipStream_t st, const KnProbeJob &job)
+{
+    const int H = sc->desc.hidden;
+    if (H != 32 && H != 64) return KN_E_UNSUPPORTED;
+    const dim3 grid((unsigned)((int64_t)sc->N * job.parts)), block(F32_WAVES * KN_WAVE);
+    const float *w = (const float *)sc->packed_w;
+    if (H == 32)
+        hipLaunchKernelGGL(k_probe_f32<32>, grid, block, 0, st, w, job);
+    else
+        hipLaunchKernelGGL(k_probe_f32<64>, grid, block, 0, st, w, job);
     KN_CHECK_LAUNCH();
     return KN_OK;
 }

@@ -38,6 +38,7 @@
 // role.
 #include "kn_common.h"
 #include "kn_mlp_shared.h"
+#include "kn_probe.h"
 
 #include <stdlib.h>
 
@@ -494,6 +495,134 @@ __global__ void __launch_bounds__(WAVES *KN_WAVE) __attribute__((amdgpu_waves_pe
 #endif
 }
 
+
+// Density only, for occupancy extraction (Sec. 3.4): layers 1 and 2 and the density row of layer 3 at the probe
+// points of one network cell's voxels, which are generated in the kernel.  Same formulation as k_mlp_mfma.
+template <int H, bool BF, int WAVES, bool WRAP>
+__global__ void __launch_bounds__(WAVES *KN_WAVE) __attribute__((amdgpu_waves_per_eu(H == 32 ? 4 : 3, H == 32 ? 4 : 3)))
+    k_probe_mfma(const uint16_t *__restrict__ packed, KnProbeJob job)
+{
+    using L = Lay<H>;
+    constexpr int HT = L::HT, HK = L::HK;
+    __shared__ f4 stage[WAVES][4][2][KN_WAVE]; // as in k_mlp_mfma, without the direction
+    const int wave = threadIdx.x / KN_WAVE, lane = threadIdx.x & (KN_WAVE - 1);
+    const int n = lane & 15, g = lane >> 4;
+    const unsigned m3 = (g == 3) ? 0xffffffffu : 0u;
+    const int mrow = n >> 2;
+    const f4 zero4 = {0.0f, 0.0f, 0.0f, 0.0f};
+    const u4 zero_u4 = {0u, 0u, 0u, 0u};
+
+    const int32_t cell = blockIdx.x / job.parts, part = blockIdx.x - cell * job.parts;
+    const KnProbeBox box = kn_probe_box(job, cell);
+    if (box.points == 0) return;
+    const int shares = job.parts * WAVES, share = part * WAVES + wave;
+    const int t_lo = __builtin_amdgcn_readfirstlane((int)((int64_t)share * box.tiles / shares));
+    const int t_hi = __builtin_amdgcn_readfirstlane((int)((int64_t)(share + 1) * box.tiles / shares));
+    if (t_lo >= t_hi) return;
+
+    u4 a1[2 * HT], a2[HT * HK], a_sig[HK];
+    f4 bias2[HT];
+    float bias_sig = 0.0f;
+    auto load_network = [&](int32_t net) {
+        const u4 *__restrict__ wp = (const u4 *)(packed + (int64_t)net * L::HALFS);
+#pragma unroll
+        for (int b = 0; b < 2 * HT; ++b) a1[b] = wp[(L::L1 + b) * KN_WAVE + lane];
+#pragma unroll
+        for (int b = 0; b < HT * HK; ++b) a2[b] = wp[(L::L2 + b) * KN_WAVE + lane];
+#pragma unroll
+        for (int kb = 0; kb < HK; ++kb) a_sig[kb] = wp[(L::LS + kb) * KN_WAVE + lane];
+        const float *__restrict__ tail = (const float *)(wp + L::NBLK * KN_WAVE);
+#pragma unroll
+        for (int t = 0; t < HT; ++t) bias2[t] = *(const f4 *)(tail + 16 * t + 4 * g);
+        bias_sig = tail[2 * H + 3];
+    };
+    int32_t net_loaded = -1;
+
+    for (int t = t_lo; t < t_hi; ++t) {
+        const int32_t p = t * KN_WAVE + lane;
+        const bool active = p < box.points;
+        float x, y, z;
+        int64_t voxel;
+        int32_t probe;
+        kn_probe_point(job, box, min(p, box.points - 1), x, y, z, voxel, probe);
+        const int32_t net = kn_grid_index(job.net, x, y, z);
+        bool todo = active && net >= 0;
+        float sg = 0.0f;
+        {
+            const float p3[3] = {x, y, z};
+#pragma unroll
+            for (int a = 0; a < 3; ++a)
+                stage[wave][a][0][lane] = (f4){p3[a] * INV_2PI, p3[a] * (4.0f * INV_2PI), p3[a] * (16.0f * INV_2PI), 0.0f};
+            stage[wave][3][0][lane] = (f4){x * (256.0f * INV_2PI), y * (256.0f * INV_2PI), z * (256.0f * INV_2PI), 0.0f};
+            const u4 ident = {pk<BF>(x, y), pk<BF>(z, 1.0f), 0u, 0u};
+            stage[wave][3][1][lane] = __builtin_bit_cast(f4, ident);
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+
+        // One pass per network met in the tile: a single pass when the grids nest, a second one for the probes
+        // of voxels that reach into a neighbouring cell otherwise.
+        for (;;) {
+            const unsigned long long pending = __ballot(todo);
+            if (pending == 0ull) break;
+            const int32_t nsel = __builtin_amdgcn_readlane(net, (int)__builtin_ctzll(pending));
+            if (nsel != net_loaded) {
+                load_network(nsel);
+                net_loaded = nsel;
+            }
+            f4 out = {0.0f, 0.0f, 0.0f, bias_sig};
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const f4 ang = stage[wave][g][0][16 * u + n];
+                const u4 ident = __builtin_bit_cast(u4, stage[wave][g][1][16 * u + n]);
+                u4 Bx[2];
+                {
+                    float s[8], m[8];
+                    sincos_rev<WRAP>(ang[0], s[0], m[0]);
+                    double_angle(s[0], m[0], s[1], m[1]);
+                    sincos_rev<WRAP>(ang[1], s[2], m[2]);
+                    double_angle(s[2], m[2], s[3], m[3]);
+                    sincos_rev<WRAP>(ang[2], s[4], m[4]);
+                    double_angle(s[4], m[4], s[5], m[5]);
+                    double_angle(s[5], m[5], s[6], m[6]);
+                    double_angle(s[6], m[6], s[7], m[7]);
+                    unsigned q[8];
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) q[i] = pk<BF>(s[i], m[i]);
+                    q[6] = (ident[0] & m3) | (q[6] & ~m3);
+                    q[7] = (ident[1] & m3) | (q[7] & ~m3);
+                    Bx[0] = (u4){q[0], q[1], q[2], q[3]};
+                    Bx[1] = (u4){q[4], q[5], q[6], q[7]};
+                }
+                f4 acc[HT];
+                u4 Bh[HK];
+#pragma unroll
+                for (int t2 = 0; t2 < HT; ++t2) {
+                    acc[t2] = mfma<BF>(a1[2 * t2], Bx[0], zero4);
+                    acc[t2] = mfma<BF>(a1[2 * t2 + 1], Bx[1], acc[t2]);
+                }
+                pack_acts<H, BF, true>(acc, Bh);
+#pragma unroll
+                for (int t2 = 0; t2 < HT; ++t2) {
+                    acc[t2] = bias2[t2];
+#pragma unroll
+                    for (int kb = 0; kb < HK; ++kb) acc[t2] = mfma<BF>(a2[t2 * HK + kb], Bh[kb], acc[t2]);
+                }
+                pack_acts<H, BF, true>(acc, Bh);
+#pragma unroll
+                for (int kb = 0; kb < HK; ++kb) out = mfma<BF>(mrow == u ? a_sig[kb] : zero_u4, Bh[kb], out);
+            }
+            if (todo && net == nsel) {
+                sg = fmaxf(out[3], 0.0f);
+                todo = false;
+            }
+        }
+        __builtin_amdgcn_wave_barrier(); // the staging buffer is rewritten by the next iteration
+        kn_probe_mark(job, active, sg > job.tau, voxel, probe, lane);
+    }
+}
+
 template <int H, bool BF, int WAVES>
 int launch(const kn_scene *sc, hipStream_t st, const KnSampleSrc &src, const KnBucketOut &b, int64_t max_tiles, float *sigma,
            float *rgb)
@@ -547,6 +676,33 @@ int kn_mlp_pack_weights(kn_scene *sc, hipStream_t st)
     else
         hipLaunchKernelGGL(k_pack_weights<64>, dim3((unsigned)blocks), dim3(256), 0, st, w, sc->P, sc->N, bf,
                            (uint16_t *)sc->packed_w);
+    KN_CHECK_LAUNCH();
+    return KN_OK;
+}
+
+int kn_probe_mfma_launch(const kn_scene *sc, hipStream_t st, const KnProbeJob &job)
+{
+    const bool bf = sc->desc.wdtype == KN_BF16;
+    const int H = sc->desc.hidden;
+    float reach = 0.0f;
+    for (int a = 0; a < 3; ++a)
+        reach = fmaxf(reach, fmaxf(fabsf(sc->desc.aabb_min[a]), fabsf(sc->desc.aabb_max[a])));
+    const bool wrap = !(reach * (256.0f * INV_2PI) < 250.0f);
+    const dim3 grid((unsigned)((int64_t)sc->N * job.parts)), block(MLP_WAVES * KN_WAVE);
+    const uint16_t *w = (const uint16_t *)sc->packed_w;
+#define KN_PROBE_CASE(HH, BB, WW)                                                                          \
+    if (H == HH && bf == BB && wrap == WW)                                                                  \
+        hipLaunchKernelGGL((k_probe_mfma<HH, BB, MLP_WAVES, WW>), grid, block, 0, st, w, job);
+    KN_PROBE_CASE(32, false, false)
+    KN_PROBE_CASE(32, false, true)
+    KN_PROBE_CASE(32, true, false)
+    KN_PROBE_CASE(32, true, true)
+    KN_PROBE_CASE(64, false, false)
+    KN_PROBE_CASE(64, false, true)
+    KN_PROBE_CASE(64, true, false)
+    KN_PROBE_CASE(64, true, true)
+#undef KN_PROBE_CASE
+    if (H != 32 && H != 64) return KN_E_UNSUPPORTED;
     KN_CHECK_LAUNCH();
     return KN_OK;
 }

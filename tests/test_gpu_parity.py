@@ -407,6 +407,83 @@ def test_march_and_render_on_grids_that_do_not_nest():
         np.testing.assert_array_equal(out_k[r, :cnt[r]], want)
 
 
+# ------------------------------------------------------------------ occupancy extraction (Sec. 3.4)
+def extraction_check(sc, occ_res, tau, sigma_unit=1.0, voxels=None):
+    """Occupancy bytes against the oracle's.  The decision sigma > tau rests on a floating-point density, so a
+    voxel with a probe whose oracle density lies within the density tolerance of tau may legitimately come out
+    either way; all other voxels must agree exactly, and the undecided ones must be few."""
+    import torch
+    dev, orc = make_pair(sc, threads=True)
+    got = dev.extract_occupancy(occ_res, tau)
+    torch.cuda.synchronize()
+    assert got.dtype == torch.uint8 and tuple(got.shape) == tuple(occ_res)
+    got = got.cpu().numpy()
+    assert set(np.unique(got)) <= {0, 1}
+    if voxels is None:
+        want, top, mg = orc.extract_occupancy(occ_res, tau)
+    else:
+        want, top, mg = orc.extract_occupancy(occ_res, tau, voxels=voxels)
+        got = got.ravel()[voxels]
+    # fp32: the density bar itself.  16-bit: the bar (2e-2) is far wider than the rounding the arithmetic has (every
+    # activation is rounded to 11 / 8 significant bits), and with 27 probes per voxel a margin that wide would leave
+    # a third of the voxels undecided; the margins below are about four roundings.
+    rel = {"f32": 1e-4, "f16": 4e-3, "bf16": 2e-2}[sc["wdtype"]]
+    tol = rel * sigma_unit * (1.0 + (0 if sc["wdtype"] == "f32" else 1) * tau / sigma_unit)
+    close = mg <= tol
+    log("  extraction %s H=%d %s: %d voxels, %.1f %% marked, %d within the density tolerance of tau, %d of those differ"
+        % (sc["wdtype"], sc["hidden"], tuple(occ_res), want.size, 100 * want.mean(), close.sum(), (got != want)[close].sum()))
+    np.testing.assert_array_equal(got[~close], want[~close])
+    assert 0.02 < want.mean() < 0.98
+    assert close.mean() < {"f32": 0.002, "f16": 0.12, "bf16": 0.45}[sc["wdtype"]]
+    assert (got != want)[close].sum() <= 0.05 * close.sum() + 2     # and even those mostly agree
+    return dev, got
+
+
+def median_density(sc, occ_res):
+    """A threshold inside the range of a random scene's densities: the median over voxels of the largest probe."""
+    orc = make_pair(sc, threads=True)[1]
+    n = int(np.prod(occ_res))
+    pick = np.arange(0, n, max(1, n // 2000), dtype=np.int64)
+    return float(np.median(orc.extract_occupancy(occ_res, 0.0, voxels=pick)[1]))
+
+
+@pytest.mark.parametrize("wdtype,H", [("f32", 32), ("f32", 64), ("f16", 32), ("bf16", 32), ("f16", 64), ("bf16", 64)])
+def test_extract_occupancy_nested_grid(wdtype, H):
+    # 16 voxels per network cell and axis do not fill whole 64-probe tiles (27 * 8^3 = 216 tiles, the last ragged)
+    sc = scene_dict((2, 3, 2), (-1, -1, -1), (1, 1, 1), H, wdtype, 31, sigma_scale=20.0)
+    res = (16, 24, 16)
+    extraction_check(sc, res, median_density(sc, res), sigma_unit=20.0)
+
+
+@pytest.mark.parametrize("wdtype", ["f32", "f16"])
+def test_extract_occupancy_grids_that_do_not_nest(wdtype):
+    # voxels straddle network cells: their probes are evaluated by different networks; one axis has fewer voxels
+    # than cells, so some cells own no voxel at all
+    sc = scene_dict((3, 5, 2), (-1, 0, 0.5), (1, 2, 4.5), 32, wdtype, 32, sigma_scale=20.0)
+    res = (20, 3, 9)
+    extraction_check(sc, res, median_density(sc, res), sigma_unit=20.0)
+
+
+def test_extract_occupancy_threshold_cases_and_single_network():
+    import torch
+    sc = scene_dict((1, 1, 1), (0, 0, 0), (1, 1, 1), 32, "f16", 33, sigma_scale=20.0)
+    dev, _ = make_pair(sc)
+    assert int(dev.extract_occupancy((5, 7, 3), 1e30).sum()) == 0          # nothing is above
+    assert int(dev.extract_occupancy((5, 7, 3), -1.0).sum()) == 105        # densities are >= 0: everything is above
+    assert int(dev.extract_occupancy((1, 1, 1), -1.0).sum()) == 1
+    extraction_check(sc, (12, 10, 14), median_density(sc, (12, 10, 14)), sigma_unit=20.0)
+    # the result is what kn_scene_create takes as an occupancy grid
+    occ = dev.extract_occupancy((8, 8, 8), median_density(sc, (8, 8, 8)))
+    sc2 = dict(sc)
+    sc2["occupancy"] = occ.cpu().numpy()
+    cfg = configs.config3(16, 16)
+    dev2, orc2 = make_pair(sc2)
+    o, d = cfg["rays_o"] * 0.25 + 0.5, cfg["rays_d"]
+    k, cnt, _ = dev2.march(cuda(o), cuda(d), 0.0, 0.02, 100)
+    for r in range(0, len(o), 17):
+        np.testing.assert_array_equal(k[r, :cnt[r]].cpu().numpy(), orc2.march(o[r], d[r], 0.0, 0.02, 100))
+
+
 # ------------------------------------------------------------------ full-size workloads (sampled comparison)
 def test_full_config2_sampled():
     cfg = configs.config2()
@@ -435,3 +512,14 @@ def test_full_config5_sampled():
     R = len(cfg["rays_o"])
     sel = np.sort(ks.rng(96).choice(R, size=3000, replace=False))
     render_check(cfg, sel=sel)
+
+
+def test_full_extraction_config3_sampled():
+    """Extraction at the size of the render workload (16^3 networks, 256^3 voxels, 4.5e8 probes), fp16; the oracle
+    checks a sample of the voxels."""
+    sc = configs.config3(8, 8)["scene"]
+    res = (256, 256, 256)
+    pick = np.unique(ks.rng(77).integers(0, 256 ** 3, size=1500)).astype(np.int64)
+    orc = make_pair(sc, threads=True)[1]
+    tau = float(np.median(orc.extract_occupancy(res, 0.0, voxels=pick[:300])[1]))
+    extraction_check(sc, res, tau, sigma_unit=100.0, voxels=pick)
