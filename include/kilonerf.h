@@ -175,9 +175,10 @@ int kn_extract_occupancy(const kn_scene *scene, void *stream, const int32_t occ_
                          int64_t workspace_bytes);
 
 /* Tuning knobs of kn_render (process-wide, for experiments; defaults are used otherwise):
- * samples per ray in the first wave, the slot budget per ray (workspace size; later waves share
- * the budget out among the surviving rays), and the factor by which the samples per ray grow from
- * one wave to the next.  Values <= 0 restore the default. */
+ * samples per ray in the first wave (default max(48, K / 16), at most the slot budget), the slot
+ * budget per ray (default 128; sizes the workspace; later waves share the budget out among the
+ * surviving rays), and the factor by which the samples per ray grow from one wave to the next
+ * (default 32).  Values <= 0 restore the default. */
 int kn_set_render_params(int32_t first_wave_samples, int32_t slots_per_ray, int32_t wave_growth);
 
 /* Per-stage device time of kn_render / kn_eval_grouped, measured with HIP events recorded on the

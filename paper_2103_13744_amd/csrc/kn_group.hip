@@ -9,7 +9,7 @@
 //               itself; otherwise by k_group_pass<0>.
 //   offsets     exclusive prefix sums of the histogram and the tile list.  Small grids: every workgroup of
 //               the fill pass derives the offsets it needs from the histogram, the first few also write the
-//               tiles; otherwise k_group_tiles.
+//               tiles; otherwise k_group_offsets (one workgroup) and k_group_tiles (one thread per group).
 //   fill        a workgroup reserves, per bin it met, a range inside the group with one integer atomic and
 //               writes the slot numbers of its samples there.
 //
@@ -20,8 +20,9 @@
 namespace {
 
 constexpr int GROUP_THREADS = 256;
-constexpr int GROUP_MAX_BINS = 32768;     // bins of one LDS window (larger grids: window by window)
 constexpr int GROUP_FUSED_MAX_BINS = 8192; // largest grid whose histogram the fill pass scans by itself
+constexpr int GROUP_HASH_SLOTS = 2048;     // larger grids: LDS table of the bins a workgroup meets (power of two)
+constexpr int GROUP_HASH_PROBES = 16;      // slots tried before a bin is handled through global memory instead
 constexpr int GROUP_LIST = 512;                     // bins a workgroup can list as touched before it visits all
 
 #ifdef KN_GROUP_TIMING
@@ -50,7 +51,10 @@ __device__ __forceinline__ void write_tiles(KnTile *__restrict__ tiles, int32_t 
 
 // MODE 0: add this workgroup's key counts to `global` (the histogram).
 // MODE 1: `global` holds each group's absolute fill cursor; reserve and fill this workgroup's ranges of `perm`.
-// MODE 2: (small grids, one window) `hist` holds the finished histogram and `global` zeroed fill counters:
+//         Modes 0 and 1 serve large grids: a counter per network would not fit in LDS, and neighbouring rays meet few
+//         networks, so the counters live in an LDS hash table (bins_cap slots, linear probing) keyed by network; a
+//         bin that finds no slot within GROUP_HASH_PROBES is counted / reserved through global memory run by run.
+// MODE 2: (small grids) bins_cap = N direct counters; `hist` holds the finished histogram and `global` zeroed fill counters:
 //         derive the group offsets here (groups are laid out in the order bin % 256, bin / 256), reserve and
 //         fill; the first N / 256 workgroups also write the tile list.
 //
@@ -65,7 +69,7 @@ __global__ void __launch_bounds__(GROUP_THREADS)
                  KnTile *__restrict__ tiles, int32_t *__restrict__ n_tiles, int dbg)
 {
     typedef int32_t i4 __attribute__((ext_vector_type(4)));
-    extern __shared__ int32_t bins[]; // [bins_cap], MODE 2: then the wave's histogram [N]
+    extern __shared__ int32_t bins[]; // MODE 2: counters [N], then the wave's histogram [N]; else hash keys, counts [bins_cap] each
     __shared__ int32_t touched[GROUP_LIST], touched_off[MODE == 2 ? GROUP_LIST : 1], n_touched, scan_lds[GROUP_THREADS / KN_WAVE];
     const int tid = threadIdx.x, lane = tid & (KN_WAVE - 1);
     // the wave's shape comes from device memory (ctl[0] rows of ctl[1] slots): the launch may have been enqueued
@@ -152,7 +156,55 @@ __global__ void __launch_bounds__(GROUP_THREADS)
         }
     }
 
-    for (int32_t w0 = 0; w0 < N; w0 += bins_cap) { // MODE 2: a single window
+    if constexpr (MODE != 2) {
+        int32_t *hkeys = bins, *hcnt = bins + bins_cap;
+        const uint32_t hmask = (uint32_t)bins_cap - 1u;
+        const int hshift = __builtin_clz((uint32_t)bins_cap) + 1; // 32 - log2(bins_cap)
+        for (int32_t b = tid; b < bins_cap; b += GROUP_THREADS) {
+            hkeys[b] = -1;
+            hcnt[b] = 0;
+        }
+        __syncthreads();
+        // slot of bin k, claimed on first use; -1 when the probed slots all belong to other bins (they never become
+        // free again, so the answer for a bin is the same throughout the kernel)
+        auto slot_of = [&](int32_t k) -> int32_t {
+            uint32_t h = ((uint32_t)k * 2654435761u) >> hshift;
+            for (int probe = 0; probe < GROUP_HASH_PROBES; ++probe) {
+                int32_t old = hkeys[h];
+                if (old == -1) old = atomicCAS(&hkeys[h], -1, k);
+                if (old == -1 || old == k) return (int32_t)h;
+                h = (h + 1u) & hmask;
+            }
+            return -1;
+        };
+        if (nr > 0)
+            sweep(0, N, first_rows, [&](int32_t k, int64_t, int32_t len) {
+                const int32_t sl = slot_of(k);
+                if (sl >= 0) atomicAdd(&hcnt[sl], len);
+                else if (MODE == 0) atomicAdd(&global[k], len);
+            });
+        __syncthreads();
+        GT(1);
+        for (int32_t q = tid; q < bins_cap; q += GROUP_THREADS) {
+            const int32_t k = hkeys[q], c = hcnt[q];
+            if (k >= 0 && c > 0) {
+                const int32_t before = atomicAdd(&global[k], c);
+                if (MODE == 1) hcnt[q] = before; // first position of this workgroup's range inside the group
+            }
+        }
+        if constexpr (MODE == 1) {
+            __syncthreads();
+            GT(3);
+            if (nr > 0)
+                sweep(0, N, fetch_rows(0), [&](int32_t k, int64_t slot, int32_t len) {
+                    const int32_t sl = slot_of(k);
+                    const int32_t pos = sl >= 0 ? atomicAdd(&hcnt[sl], len) : atomicAdd(&global[k], len);
+                    for (int32_t t = 0; t < len; ++t) perm[pos + t] = (int32_t)slot + t;
+                });
+        }
+        GT(4);
+    } else {
+    for (int32_t w0 = 0; w0 < N; w0 += bins_cap) { // (a single window: bins_cap = N)
         const int32_t nb = min(bins_cap, N - w0);
         for (int32_t b = tid; b < nb; b += GROUP_THREADS) bins[b] = 0;
         if (tid == 0) n_touched = 0;
@@ -162,25 +214,7 @@ __global__ void __launch_bounds__(GROUP_THREADS)
         __syncthreads();
         GT(1);
         int32_t fused_off0 = 0; // MODE 2: offset of the first group this thread laid out
-        // list the touched bins, so that the global atomics below are issued side by side
-        auto list_bin = [&](int32_t b, bool hit, int32_t off) {
-            const unsigned long long m = __ballot(hit);
-            if (m) {
-                int32_t at = 0;
-                if (lane == 0) at = atomicAdd(&n_touched, __builtin_popcountll(m));
-                at = __shfl(at, 0, KN_WAVE) + __builtin_popcountll(m & ((1ull << lane) - 1ull));
-                if (hit && at < GROUP_LIST) {
-                    touched[at] = b;
-                    if (MODE == 2) touched_off[at] = off;
-                }
-            }
-        };
-        if constexpr (MODE != 2) {
-            for (int32_t b0 = 0; b0 < nb; b0 += GROUP_THREADS) {
-                const int32_t b = b0 + tid;
-                list_bin(b, b < nb && bins[b] > 0, 0);
-            }
-        } else {
+        {
             // exclusive offsets of all groups: thread t owns the bins t, t + 256, ... and lays them out in a row;
             // the touched ones are listed together with their offsets
             int32_t mine = 0;
@@ -247,13 +281,7 @@ __global__ void __launch_bounds__(GROUP_THREADS)
         const bool listed = nt <= GROUP_LIST; // otherwise all bins of the window are visited
         const int32_t n_visit = listed ? nt : nb;
         GT(2);
-        if constexpr (MODE == 0) {
-            for (int32_t q = tid; q < n_visit; q += GROUP_THREADS) {
-                const int32_t b = listed ? touched[q] : q;
-                const int32_t c = bins[b];
-                if (c) atomicAdd(&global[w0 + b], c);
-            }
-        } else {
+        {
             // first position of this workgroup's range inside each group it met
             if (MODE == 2 && !listed) { // more bins than the list holds: every thread walks the bins it laid out
                 int32_t off = fused_off0;
@@ -280,67 +308,99 @@ __global__ void __launch_bounds__(GROUP_THREADS)
         __syncthreads();
         GT(4);
     }
+    }
 }
 
-// histogram -> group offsets (also the fill cursors) and the tile list; leaves the histogram zero for the next
-// use.  One workgroup; thread t owns the bins [t * per, (t + 1) * per).
-constexpr int TILES_CHUNK = 8;
+// histogram -> group offsets (also the fill cursors) and tile positions.  One workgroup, a round of 4,096 bins at a
+// time: global memory is read and written with consecutive threads on consecutive bins, the four contiguous bins
+// that a thread scans come through LDS (index + index / 32 keeps both access patterns free of bank conflicts).
+// The histogram entries are replaced by the groups' first tile positions, totals[0] = tiles, totals[1] = samples;
+// k_group_tiles writes the tiles from that and clears the histogram for the next use.
 __global__ void __launch_bounds__(1024)
-    k_group_tiles(int32_t *__restrict__ hist, int32_t N, int32_t tile_len, int32_t *__restrict__ cursor,
-                  KnTile *__restrict__ tiles, int32_t *__restrict__ n_tiles)
+    k_group_offsets(int32_t *__restrict__ hist, int32_t N, int32_t tile_len, int32_t *__restrict__ cursor,
+                    int32_t *__restrict__ totals)
 {
-    __shared__ int32_t lds[1024 / KN_WAVE];
-    const int lane = threadIdx.x & (KN_WAVE - 1);
-    const int32_t per = (N + 1023) / 1024;
-    const int32_t b0 = min(N, (int32_t)threadIdx.x * per), b1 = min(N, b0 + per);
-    int32_t samples = 0, my_tiles = 0;
-    for (int32_t c0 = b0; c0 < b1; c0 += TILES_CHUNK) {
-        int32_t c[TILES_CHUNK];
+    constexpr int T = 1024, PER = 4, ROUND = T * PER;
+    __shared__ int32_t tr_s[ROUND + ROUND / 32], tr_t[ROUND + ROUND / 32];
+    __shared__ int32_t lds[T / KN_WAVE];
+    const int tid = threadIdx.x;
+    int32_t carry_s = 0, carry_t = 0;
+    for (int32_t b0 = 0; b0 < N; b0 += ROUND) {
+        int32_t c[PER];
 #pragma unroll
-        for (int q = 0; q < TILES_CHUNK; ++q) c[q] = hist[min(c0 + q, N - 1)]; // loads issued together
+        for (int u = 0; u < PER; ++u) c[u] = hist[min(b0 + u * T + tid, N - 1)]; // loads issued together
 #pragma unroll
-        for (int q = 0; q < TILES_CHUNK; ++q)
-            if (c0 + q < b1) {
-                samples += c[q];
-                my_tiles += (c[q] + tile_len - 1) / tile_len;
-            }
-    }
-    int32_t total;
-    int32_t off = kn_block_exclusive_scan(samples, lds, total);
-    int32_t tpos = kn_block_exclusive_scan(my_tiles, lds, total);
-    if (threadIdx.x == 0) *n_tiles = total;
-    // all threads of a wavefront run the same number of chunk steps (bins past b1 count as empty)
-    for (int32_t c0 = b0; c0 < b0 + per; c0 += TILES_CHUNK) {
-        int32_t c[TILES_CHUNK];
-#pragma unroll
-        for (int q = 0; q < TILES_CHUNK; ++q) c[q] = hist[min(c0 + q, N - 1)];
-#pragma unroll
-        for (int q = 0; q < TILES_CHUNK; ++q) {
-            const int32_t b = c0 + q;
-            const int32_t cc = b < b1 ? c[q] : 0;
-            const int32_t nt = (cc + tile_len - 1) / tile_len;
-            if (b < b1) {
-                hist[b] = 0;
-                cursor[b] = off;
-            }
-            write_tiles(tiles, b, off, cc, nt, tpos, tile_len, lane);
-            off += cc;
-            tpos += nt;
+        for (int u = 0; u < PER; ++u) {
+            const int e = u * T + tid;
+            tr_s[e + (e >> 5)] = b0 + e < N ? c[u] : 0;
         }
+        __syncthreads();
+        int32_t sum_s = 0, sum_t = 0;
+#pragma unroll
+        for (int u = 0; u < PER; ++u) {
+            const int e = PER * tid + u;
+            c[u] = tr_s[e + (e >> 5)];
+            sum_s += c[u];
+            sum_t += (c[u] + tile_len - 1) / tile_len;
+        }
+        int32_t tot_s, tot_t;
+        int32_t off = carry_s + kn_block_exclusive_scan(sum_s, lds, tot_s);
+        int32_t tpos = carry_t + kn_block_exclusive_scan(sum_t, lds, tot_t);
+#pragma unroll
+        for (int u = 0; u < PER; ++u) {
+            const int e = PER * tid + u;
+            tr_s[e + (e >> 5)] = off;
+            tr_t[e + (e >> 5)] = tpos;
+            off += c[u];
+            tpos += (c[u] + tile_len - 1) / tile_len;
+        }
+        carry_s += tot_s;
+        carry_t += tot_t;
+        __syncthreads();
+#pragma unroll
+        for (int u = 0; u < PER; ++u) {
+            const int e = u * T + tid;
+            if (b0 + e < N) {
+                cursor[b0 + e] = tr_s[e + (e >> 5)];
+                hist[b0 + e] = tr_t[e + (e >> 5)];
+            }
+        }
+        __syncthreads();
     }
+    if (tid == 0) {
+        totals[0] = carry_t;
+        totals[1] = carry_s;
+    }
+}
+
+// one thread per group; groups of several tiles are finished by the whole wavefront
+__global__ void __launch_bounds__(GROUP_THREADS)
+    k_group_tiles(int32_t *__restrict__ hist, int32_t N, int32_t tile_len, const int32_t *__restrict__ cursor,
+                  const int32_t *__restrict__ totals, KnTile *__restrict__ tiles)
+{
+    const int32_t b = blockIdx.x * GROUP_THREADS + threadIdx.x;
+    const int lane = threadIdx.x & (KN_WAVE - 1);
+    int32_t off = 0, c = 0, tpos = 0;
+    if (b < N) {
+        off = cursor[b];
+        c = (b + 1 < N ? cursor[b + 1] : totals[1]) - off;
+        tpos = hist[b];
+        hist[b] = 0;
+    }
+    write_tiles(tiles, b, off, c, (c + tile_len - 1) / tile_len, tpos, tile_len, lane);
 }
 
 } // namespace
 
-// KN_GROUP_WINDOW / KN_GROUP_FUSED_MAX: test knobs (read once) that shrink the LDS window and the fused-scan
-// limit, so that small scenes reach the code paths of large network grids
-static int32_t group_window()
+// KN_GROUP_HASH_SLOTS / KN_GROUP_FUSED_MAX: test knobs (read once) that shrink the LDS hash table and the
+// fused-scan limit, so that small scenes reach the code paths of large network grids, table overflow included
+static int32_t group_hash_slots()
 {
     static int32_t v = 0;
     if (!v) {
-        const char *e = getenv("KN_GROUP_WINDOW");
+        const char *e = getenv("KN_GROUP_HASH_SLOTS");
         const int x = e ? atoi(e) : 0;
-        v = (x >= 1 && x <= GROUP_MAX_BINS) ? x : GROUP_MAX_BINS;
+        v = (x >= 16 && x <= GROUP_HASH_SLOTS && (x & (x - 1)) == 0) ? x : GROUP_HASH_SLOTS;
     }
     return v;
 }
@@ -352,14 +412,14 @@ bool kn_group_fused(int32_t N)
         const int x = e ? atoi(e) : -1;
         lim = (x >= 0 && x <= GROUP_FUSED_MAX_BINS) ? x : GROUP_FUSED_MAX_BINS;
     }
-    return N <= lim && N <= group_window();
+    return N <= lim;
 }
 
 static void carve_group(KnCarver &c, int64_t slots, int32_t N, KnGroupWs &w)
 {
     w.hist = c.carve<int32_t>(2 * (int64_t)N); // histogram, then the fill cursors
     w.cursor = w.hist ? w.hist + N : nullptr;
-    w.n_tiles = c.carve<int32_t>(1);
+    w.n_tiles = c.carve<int32_t>(2); // [1]: the sample total (large grids)
     w.perm = c.carve<int32_t>(slots);
     w.tiles = c.carve<KnTile>(kn_max_tiles(slots, N, 64));
 }
@@ -381,13 +441,13 @@ int kn_group_run(hipStream_t st, const int32_t *row_keys, const int32_t *cnt, co
     if (!w.hist || !w.cursor || !w.n_tiles || !w.perm || !w.tiles) return KN_E_WORKSPACE;
     const bool fused = kn_group_fused(N);
     if (hist_ready && !fused) return KN_E_INVALID_ARG;
-    const int32_t bins_cap = N < group_window() ? N : group_window();
+    const int32_t bins_cap = fused ? N : group_hash_slots(); // direct counters, or hash slots
     int64_t blocks = kn_div_up(max_rows > 0 ? max_rows : 1, 16);
     if (blocks > 1024) blocks = 1024;
-    const size_t lds_bytes = sizeof(int32_t) * (size_t)bins_cap * (fused ? 2 : 1);
+    const size_t lds_bytes = sizeof(int32_t) * (size_t)bins_cap * 2;
     static bool configured = false; // the kernels may need more dynamic LDS than the default limit
     if (!configured) {
-        const int most = (int)(sizeof(int32_t) * GROUP_MAX_BINS);
+        const int most = (int)(sizeof(int32_t) * 2 * GROUP_FUSED_MAX_BINS);
         KN_HIP(hipFuncSetAttribute((const void *)k_group_pass<0>, hipFuncAttributeMaxDynamicSharedMemorySize, most));
         KN_HIP(hipFuncSetAttribute((const void *)k_group_pass<1>, hipFuncAttributeMaxDynamicSharedMemorySize, most));
         KN_HIP(hipFuncSetAttribute((const void *)k_group_pass<2>, hipFuncAttributeMaxDynamicSharedMemorySize, most));
@@ -410,7 +470,10 @@ int kn_group_run(hipStream_t st, const int32_t *row_keys, const int32_t *cnt, co
                            (const int32_t *)w.hist, tile_len, w.tiles, w.n_tiles, DBG);
         KN_CHECK_LAUNCH();
     } else {
-        hipLaunchKernelGGL(k_group_tiles, dim3(1), dim3(1024), 0, st, w.hist, N, tile_len, w.cursor, w.tiles, w.n_tiles);
+        hipLaunchKernelGGL(k_group_offsets, dim3(1), dim3(1024), 0, st, w.hist, N, tile_len, w.cursor, w.n_tiles);
+        KN_CHECK_LAUNCH();
+        hipLaunchKernelGGL(k_group_tiles, dim3((unsigned)kn_div_up(N, GROUP_THREADS)), dim3(GROUP_THREADS), 0, st, w.hist, N,
+                           tile_len, (const int32_t *)w.cursor, (const int32_t *)w.n_tiles, w.tiles);
         KN_CHECK_LAUNCH();
         hipLaunchKernelGGL(k_group_pass<1>, grid, block, lds_bytes, st, row_keys, cnt, ctl, N, bins_cap, w.cursor, w.perm,
                            (const int32_t *)nullptr, tile_len, (KnTile *)nullptr, (int32_t *)nullptr, DBG);

@@ -309,8 +309,9 @@ def test_render_is_independent_of_wave_cut_and_deterministic():
 
 
 def test_render_large_grid_code_paths(tmp_path):
-    """Grids too large for one LDS window are grouped window by window with separate histogram and
-    offset kernels; a child process forces those paths on a small scene and must produce the same image."""
+    """Grids with too many networks for a counter each in LDS are grouped with separate histogram, offset and fill
+    kernels and an LDS hash table; a child process forces those paths on a small scene and must produce the same
+    image."""
     import subprocess
     import sys
     cfg = configs.config3(64, 64)
@@ -330,9 +331,12 @@ def test_render_large_grid_code_paths(tmp_path):
         "img = dev.render(o, d, cfg['t_near'], cfg['step'], cfg['K'], cfg['term_eps'], cfg['bg'])\n"
         "np.save(%r, img.cpu().numpy())\n"
     ) % (os.path.dirname(os.path.dirname(os.path.abspath(__file__))), str(out))
-    env = dict(os.environ, KN_GROUP_WINDOW="1000", KN_GROUP_FUSED_MAX="0")
-    subprocess.run([sys.executable, "-c", code], env=env, check=True, timeout=300)
-    np.testing.assert_array_equal(np.load(out), here)
+    # the path of large grids (counters in an LDS hash table), then the same with a table so small that most bins
+    # overflow into the global-memory path
+    for knobs in (dict(KN_GROUP_FUSED_MAX="0"), dict(KN_GROUP_FUSED_MAX="0", KN_GROUP_HASH_SLOTS="16")):
+        subprocess.run([sys.executable, "-c", code], env=dict(os.environ, **knobs), check=True, timeout=300)
+        np.testing.assert_array_equal(np.load(out), here)
+        out.unlink()
 
 
 def test_render_calls_in_flight_on_one_scene():
