@@ -30,6 +30,8 @@
 // sample tile u the density row is placed at row 4u+3 and the colour rows at 4u+0..2 (the weight
 // block is masked to those rows), and all eight MFMAs accumulate into the same tile.  Afterwards
 // lane l holds (r, g, b, sigma) pre-activations of sample l of the 64, one sample per lane.
+// (Width 64 keeps one such accumulator per sample tile instead and uses the unmasked blocks, whose rows repeat
+// with period four: the masked copies would cost the registers that the second wavefront per SIMD needs.)
 //
 // Encoding.  sin/cos of 2^f * p come from v_sin_f32 / v_cos_f32 at three "restart" frequencies
 // per lane and the double-angle recurrence in between (fp32), which is far inside the 16-bit
@@ -224,9 +226,9 @@ constexpr float INV_2PI = 0.15915494309189535f;
 __device__ unsigned long long kn_mlp_timing[8 * 4096];
 #endif
 // Weights stay in registers: 14 blocks (56 VGPRs) for H = 32, three wavefronts per SIMD; 40 blocks (160 VGPRs) for
-// H = 64, one wavefront per SIMD (the matrix-core operands are read straight from the register file either way).
+// H = 64, two wavefronts per SIMD (the matrix-core operands are read straight from the register file either way).
 template <int H, bool BF, int WAVES, bool WRAP>
-__global__ void __launch_bounds__(WAVES *KN_WAVE) __attribute__((amdgpu_waves_per_eu(H == 32 ? KN_MLP_WPE : 1, H == 32 ? KN_MLP_WPE : 1)))
+__global__ void __launch_bounds__(WAVES *KN_WAVE) __attribute__((amdgpu_waves_per_eu(H == 32 ? KN_MLP_WPE : 2, H == 32 ? KN_MLP_WPE : 2)))
     k_mlp_mfma(const uint16_t *__restrict__ packed, KnSampleSrc src, const int32_t *__restrict__ perm,
                const KnTile *__restrict__ tiles, const int32_t *__restrict__ n_tiles, float *__restrict__ sigma,
                float *__restrict__ rgb)
@@ -265,26 +267,26 @@ __global__ void __launch_bounds__(WAVES *KN_WAVE) __attribute__((amdgpu_waves_pe
     auto A = [&](int b) -> u4 {
         return areg[b];
     };
-    // density / colour blocks restricted to the four output rows of sample tile u
-    u4 a_sig[4][HK], a_col[4][HK];
-    auto Asig = [&](int u, int kb) -> u4 {
-        return a_sig[u][kb];
-    };
-    auto Acol = [&](int u, int kb) -> u4 {
-        return a_col[u][kb];
-    };
+    // Density / colour rows.  H = 32: one accumulator shared by the four sample tiles, fed through copies of the
+    // density / colour blocks restricted to the four output rows of tile u (made once per network).  H = 64: the
+    // copies would cost 64 registers and the second wavefront per SIMD with them; there every tile has its own
+    // accumulator, fed by the unmasked blocks (whose rows repeat with period four), and lane group g keeps tile g.
+    constexpr bool SHARED_OUT = H == 32;
+    u4 a_sig[SHARED_OUT ? 4 : 1][HK], a_col[SHARED_OUT ? 4 : 1][HK];
     f4 bias2[HT], bias3[HT], bias_out;
     auto load_network = [&](int32_t net) {
         const u4 *__restrict__ wp = (const u4 *)(packed + (int64_t)net * L::HALFS);
 #pragma unroll
         for (int b = 0; b < NBLK; ++b) areg[b] = wp[b * KN_WAVE + lane];
+        if constexpr (SHARED_OUT) {
 #pragma unroll
-        for (int u = 0; u < 4; ++u)
+            for (int u = 0; u < 4; ++u)
 #pragma unroll
-            for (int kb = 0; kb < HK; ++kb) {
-                a_sig[u][kb] = mrow == u ? areg[L::LS + kb] : zero_u4;
-                a_col[u][kb] = mrow == u ? areg[L::L5 + kb] : zero_u4;
-            }
+                for (int kb = 0; kb < HK; ++kb) {
+                    a_sig[u][kb] = mrow == u ? areg[L::LS + kb] : zero_u4;
+                    a_col[u][kb] = mrow == u ? areg[L::L5 + kb] : zero_u4;
+                }
+        }
         const float *__restrict__ tail = (const float *)(wp + NBLK * KN_WAVE);
 #pragma unroll
         for (int t = 0; t < HT; ++t) {
@@ -397,7 +399,9 @@ __global__ void __launch_bounds__(WAVES *KN_WAVE) __attribute__((amdgpu_waves_pe
         __builtin_amdgcn_wave_barrier();
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 
-        f4 out = bias_out;
+        f4 outs[SHARED_OUT ? 1 : 4];
+#pragma unroll
+        for (int u = 0; u < (SHARED_OUT ? 1 : 4); ++u) outs[u] = bias_out;
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
             { // all four sample tiles are always computed: straight-line code lets the scheduler interleave them
@@ -458,7 +462,10 @@ __global__ void __launch_bounds__(WAVES *KN_WAVE) __attribute__((amdgpu_waves_pe
                     for (int kb = 0; kb < HK; ++kb) acc[t] = mfma<BF>(A(L::L3 + t * HK + kb), Bh[kb], acc[t]);
                 }
 #pragma unroll
-                for (int kb = 0; kb < HK; ++kb) out = mfma<BF>(Asig(u, kb), Bh[kb], out);
+                for (int kb = 0; kb < HK; ++kb) {
+                    if constexpr (SHARED_OUT) outs[0] = mfma<BF>(a_sig[u][kb], Bh[kb], outs[0]);
+                    else outs[u] = mfma<BF>(A(L::LS + kb), Bh[kb], outs[u]);
+                }
                 pack_acts<H, BF, false>(acc, Bh);
                 // layer 4: [feature, gamma(d)] -> H, ReLU (bias through the constant-1 slot)
 #pragma unroll
@@ -470,7 +477,10 @@ __global__ void __launch_bounds__(WAVES *KN_WAVE) __attribute__((amdgpu_waves_pe
                 pack_acts<H, BF, true>(acc, Bh);
                 // layer 5: H -> colour rows 4u+0..2 of the shared tile
 #pragma unroll
-                for (int kb = 0; kb < HK; ++kb) out = mfma<BF>(Acol(u, kb), Bh[kb], out);
+                for (int kb = 0; kb < HK; ++kb) {
+                    if constexpr (SHARED_OUT) outs[0] = mfma<BF>(a_col[u][kb], Bh[kb], outs[0]);
+                    else outs[u] = mfma<BF>(A(L::L5 + kb), Bh[kb], outs[u]);
+                }
             }
         }
         __builtin_amdgcn_wave_barrier(); // staging buffer is rewritten by the next iteration
@@ -478,8 +488,11 @@ __global__ void __launch_bounds__(WAVES *KN_WAVE) __attribute__((amdgpu_waves_pe
         // behind the last LDS read of the iteration, its latency is not part of any wait for staged data.
         dsc3 = descriptor(t + 4);
 
-        // output activations; the store itself is issued at the top of the next iteration (see write_out)
+        // output activations; the store itself is issued at the top of the next iteration (see write_out).
+        // Either way lane l ends up with sample l of the 64.
         {
+            f4 out = outs[0];
+            if constexpr (!SHARED_OUT) out = g == 0 ? outs[0] : (g == 1 ? outs[1] : (g == 2 ? outs[2] : outs[3]));
             const float sg = fmaxf(out[3], 0.0f);
             float col[3];
 #pragma unroll
@@ -633,8 +646,8 @@ int launch(const kn_scene *sc, hipStream_t st, const KnSampleSrc &src, const KnB
         const char *e = getenv("KN_MLP_BLOCKS");
         cap = e && atoi(e) > 0 ? atoi(e) : 256 * 3;
     }
-    // one workgroup of 4 wavefronts per compute unit and resident wavefront (H = 32: three per SIMD, H = 64: one)
-    const int fill = H == 32 ? cap : cap / 3;
+    // one workgroup of 4 wavefronts per compute unit and resident wavefront (H = 32: three per SIMD, H = 64: two)
+    const int fill = H == 32 ? cap : cap * 2 / 3;
     if (blocks > fill) blocks = fill;
     // positions are only ever evaluated inside the grid's box: its largest coordinate bounds the encoding's
     // largest argument, 2^8 |p| / (2 pi) revolutions at the highest restart frequency
