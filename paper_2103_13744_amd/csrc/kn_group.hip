@@ -23,14 +23,7 @@ constexpr int GROUP_THREADS = 256;
 constexpr int GROUP_FUSED_MAX_BINS = 8192; // largest grid whose histogram the fill pass scans by itself
 constexpr int GROUP_HASH_SLOTS = 2048;     // larger grids: LDS table of the bins a workgroup meets (power of two)
 constexpr int GROUP_HASH_PROBES = 16;      // slots tried before a bin is handled through global memory instead
-constexpr int GROUP_LIST = 512;                     // bins a workgroup can list as touched before it visits all
-
-#ifdef KN_GROUP_TIMING
-__device__ unsigned long long kn_group_timing[8][4096][8];
-#define GT(k) do { if (threadIdx.x == 0 && blockIdx.x < 4096 && dbg < 8) kn_group_timing[dbg][blockIdx.x][k] = wall_clock64(); } while (0)
-#else
-#define GT(k)
-#endif
+constexpr int GROUP_LIST = 512;            // bins a workgroup can list as touched before it visits all
 
 // tiles of one group: the owner lane has written the first; groups of several tiles are finished by the
 // whole wavefront (every lane of the wavefront must call this, with its own group or nt == 0)
@@ -66,7 +59,7 @@ __global__ void __launch_bounds__(GROUP_THREADS)
     k_group_pass(const int32_t *__restrict__ row_keys, const int32_t *__restrict__ cnt, const int32_t *__restrict__ ctl,
                  int32_t N, int32_t bins_cap, int32_t *__restrict__ global,
                  int32_t *__restrict__ perm, const int32_t *__restrict__ hist, int32_t tile_len,
-                 KnTile *__restrict__ tiles, int32_t *__restrict__ n_tiles, int dbg)
+                 KnTile *__restrict__ tiles, int32_t *__restrict__ n_tiles)
 {
     typedef int32_t i4 __attribute__((ext_vector_type(4)));
     extern __shared__ int32_t bins[]; // MODE 2: counters [N], then the wave's histogram [N]; else hash keys, counts [bins_cap] each
@@ -83,7 +76,6 @@ __global__ void __launch_bounds__(GROUP_THREADS)
     const int32_t nr = min(rows_per_block, n_rows - r0);
     const bool vec = (S & 3) == 0; // rows start on 16-byte boundaries
     const int32_t row_chunks = (S + 3) >> 2;
-    GT(0);
 
     int32_t *hcl = bins + bins_cap; // MODE 2: the wave's histogram [N]
 
@@ -184,7 +176,6 @@ __global__ void __launch_bounds__(GROUP_THREADS)
                 else if (MODE == 0) atomicAdd(&global[k], len);
             });
         __syncthreads();
-        GT(1);
         for (int32_t q = tid; q < bins_cap; q += GROUP_THREADS) {
             const int32_t k = hkeys[q], c = hcnt[q];
             if (k >= 0 && c > 0) {
@@ -194,7 +185,6 @@ __global__ void __launch_bounds__(GROUP_THREADS)
         }
         if constexpr (MODE == 1) {
             __syncthreads();
-            GT(3);
             if (nr > 0)
                 sweep(0, N, fetch_rows(0), [&](int32_t k, int64_t slot, int32_t len) {
                     const int32_t sl = slot_of(k);
@@ -202,17 +192,14 @@ __global__ void __launch_bounds__(GROUP_THREADS)
                     for (int32_t t = 0; t < len; ++t) perm[pos + t] = (int32_t)slot + t;
                 });
         }
-        GT(4);
     } else {
     for (int32_t w0 = 0; w0 < N; w0 += bins_cap) { // (a single window: bins_cap = N)
         const int32_t nb = min(bins_cap, N - w0);
         for (int32_t b = tid; b < nb; b += GROUP_THREADS) bins[b] = 0;
         if (tid == 0) n_touched = 0;
         __syncthreads();
-        GT(5);
         if (nr > 0) sweep(w0, nb, w0 == 0 ? first_rows : fetch_rows(0), [&](int32_t k, int64_t, int32_t len) { atomicAdd(&bins[k], len); });
         __syncthreads();
-        GT(1);
         int32_t fused_off0 = 0; // MODE 2: offset of the first group this thread laid out
         {
             // exclusive offsets of all groups: thread t owns the bins t, t + 256, ... and lays them out in a row;
@@ -222,7 +209,6 @@ __global__ void __launch_bounds__(GROUP_THREADS)
             int32_t total;
             int32_t off = kn_block_exclusive_scan(mine, scan_lds, total);
             fused_off0 = off;
-            GT(6);
             for (int32_t b0 = 0; b0 < N; b0 += 4 * GROUP_THREADS) { // uniform trip count: ballots inside
                 // four bins per thread and step: the LDS reads are issued together, one list reservation per step
                 int32_t cnt_b[4], hist_b[4];
@@ -255,7 +241,6 @@ __global__ void __launch_bounds__(GROUP_THREADS)
                     off += hist_b[u];
                 }
             }
-            GT(7);
             // tile list: slice k = the bins 256 k .. 256 k + 255, one workgroup per slice (tile positions follow
             // the same layout order as the offsets)
             for (int64_t slice = blockIdx.x; slice * GROUP_THREADS < N; slice += gridDim.x) {
@@ -280,7 +265,6 @@ __global__ void __launch_bounds__(GROUP_THREADS)
         const int32_t nt = n_touched;
         const bool listed = nt <= GROUP_LIST; // otherwise all bins of the window are visited
         const int32_t n_visit = listed ? nt : nb;
-        GT(2);
         {
             // first position of this workgroup's range inside each group it met
             if (MODE == 2 && !listed) { // more bins than the list holds: every thread walks the bins it laid out
@@ -298,7 +282,6 @@ __global__ void __launch_bounds__(GROUP_THREADS)
                 }
             }
             __syncthreads();
-            GT(3);
             if (nr > 0)
                 sweep(w0, nb, fetch_rows(0), [&](int32_t k, int64_t slot, int32_t len) {
                     const int32_t pos = atomicAdd(&bins[k], len);
@@ -306,7 +289,6 @@ __global__ void __launch_bounds__(GROUP_THREADS)
                 });
         }
         __syncthreads();
-        GT(4);
     }
     }
 }
@@ -453,21 +435,15 @@ int kn_group_run(hipStream_t st, const int32_t *row_keys, const int32_t *cnt, co
         KN_HIP(hipFuncSetAttribute((const void *)k_group_pass<2>, hipFuncAttributeMaxDynamicSharedMemorySize, most));
         configured = true;
     }
-#ifdef KN_GROUP_TIMING
-    static int dbg_launch = 0;
-#define DBG dbg_launch++
-#else
-#define DBG 0
-#endif
     const dim3 grid((unsigned)blocks), block(GROUP_THREADS);
     if (!hist_ready) { // no rows: the kernels find no samples and leave empty outputs
         hipLaunchKernelGGL(k_group_pass<0>, grid, block, lds_bytes, st, row_keys, cnt, ctl, N, bins_cap, w.hist,
-                           (int32_t *)nullptr, (const int32_t *)nullptr, tile_len, (KnTile *)nullptr, (int32_t *)nullptr, DBG);
+                           (int32_t *)nullptr, (const int32_t *)nullptr, tile_len, (KnTile *)nullptr, (int32_t *)nullptr);
         KN_CHECK_LAUNCH();
     }
     if (fused) {
         hipLaunchKernelGGL(k_group_pass<2>, grid, block, lds_bytes, st, row_keys, cnt, ctl, N, bins_cap, w.cursor, w.perm,
-                           (const int32_t *)w.hist, tile_len, w.tiles, w.n_tiles, DBG);
+                           (const int32_t *)w.hist, tile_len, w.tiles, w.n_tiles);
         KN_CHECK_LAUNCH();
     } else {
         hipLaunchKernelGGL(k_group_offsets, dim3(1), dim3(1024), 0, st, w.hist, N, tile_len, w.cursor, w.n_tiles);
@@ -476,7 +452,7 @@ int kn_group_run(hipStream_t st, const int32_t *row_keys, const int32_t *cnt, co
                            tile_len, (const int32_t *)w.cursor, (const int32_t *)w.n_tiles, w.tiles);
         KN_CHECK_LAUNCH();
         hipLaunchKernelGGL(k_group_pass<1>, grid, block, lds_bytes, st, row_keys, cnt, ctl, N, bins_cap, w.cursor, w.perm,
-                           (const int32_t *)nullptr, tile_len, (KnTile *)nullptr, (int32_t *)nullptr, DBG);
+                           (const int32_t *)nullptr, tile_len, (KnTile *)nullptr, (int32_t *)nullptr);
         KN_CHECK_LAUNCH();
     }
     out->perm = w.perm;
@@ -487,9 +463,3 @@ int kn_group_run(hipStream_t st, const int32_t *row_keys, const int32_t *cnt, co
     return KN_OK;
 }
 
-#ifdef KN_GROUP_TIMING
-extern "C" int kn_debug_group_timing(unsigned long long *out)
-{
-    return (int)hipMemcpyFromSymbol(out, HIP_SYMBOL(kn_group_timing), sizeof(unsigned long long) * 8 * 4096 * 8);
-}
-#endif

@@ -42,8 +42,6 @@
 #include "kn_mlp_shared.h"
 #include "kn_probe.h"
 
-#include <stdlib.h>
-
 namespace {
 
 typedef _Float16 h8 __attribute__((ext_vector_type(8)));
@@ -219,16 +217,10 @@ __device__ __forceinline__ void double_angle(float s, float c, float &s2o, float
 
 constexpr float INV_2PI = 0.15915494309189535f;
 
-#ifndef KN_MLP_WPE
-#define KN_MLP_WPE 3
-#endif
-#ifdef KN_MLP_TIMING
-__device__ unsigned long long kn_mlp_timing[8 * 4096];
-#endif
 // Weights stay in registers: 14 blocks (56 VGPRs) for H = 32, three wavefronts per SIMD; 40 blocks (160 VGPRs) for
 // H = 64, two wavefronts per SIMD (the matrix-core operands are read straight from the register file either way).
 template <int H, bool BF, int WAVES, bool WRAP>
-__global__ void __launch_bounds__(WAVES *KN_WAVE) __attribute__((amdgpu_waves_per_eu(H == 32 ? KN_MLP_WPE : 2, H == 32 ? KN_MLP_WPE : 2)))
+__global__ void __launch_bounds__(WAVES *KN_WAVE) __attribute__((amdgpu_waves_per_eu(H == 32 ? 3 : 2, H == 32 ? 3 : 2)))
     k_mlp_mfma(const uint16_t *__restrict__ packed, KnSampleSrc src, const int32_t *__restrict__ perm,
                const KnTile *__restrict__ tiles, const int32_t *__restrict__ n_tiles, float *__restrict__ sigma,
                float *__restrict__ rgb)
@@ -250,10 +242,6 @@ __global__ void __launch_bounds__(WAVES *KN_WAVE) __attribute__((amdgpu_waves_pe
     // The tile list is cut into one contiguous range per wavefront (tiles are chunks of at most 64 samples, so
     // the ranges differ by one chunk at most).  Neighbouring tiles mostly belong to the same network: weights
     // are fetched only when the network changes.
-#ifdef KN_MLP_TIMING
-    const unsigned long long T0 = wall_clock64();
-    unsigned long long T1 = 0, T2 = 0;
-#endif
     const int total_tiles = *n_tiles;
     const int total_waves = gridDim.x * WAVES;
     const int wid = __builtin_amdgcn_readfirstlane(blockIdx.x * WAVES + wave);
@@ -365,10 +353,6 @@ __global__ void __launch_bounds__(WAVES *KN_WAVE) __attribute__((amdgpu_waves_pe
             net_cur = tl.net;
         }
         const bool active = lane < tl.len;
-#ifdef KN_MLP_TIMING
-        if (t == t_lo) { T1 = wall_clock64(); }
-        if (t == t_lo + 1) { T2 = wall_clock64(); }
-#endif
         const int32_t idx = idx0;
         float nx, ny, nz;
         finish(raw0, rec0, nx, ny, nz);
@@ -503,9 +487,6 @@ __global__ void __launch_bounds__(WAVES *KN_WAVE) __attribute__((amdgpu_waves_pe
         }
     }
     write_out();
-#ifdef KN_MLP_TIMING
-    if (lane == 0 && wid < 4096) { unsigned long long *o = kn_mlp_timing + 8 * wid; o[0] = T0; o[1] = T1; o[2] = T2; o[3] = wall_clock64(); o[4] = t_hi - t_lo; }
-#endif
 }
 
 
@@ -641,13 +622,8 @@ int launch(const kn_scene *sc, hipStream_t st, const KnSampleSrc &src, const KnB
            float *rgb)
 {
     int64_t blocks = kn_div_up(max_tiles, WAVES);
-    static int cap = 0;
-    if (!cap) { // KN_MLP_BLOCKS: experiment knob, read once
-        const char *e = getenv("KN_MLP_BLOCKS");
-        cap = e && atoi(e) > 0 ? atoi(e) : 256 * 3;
-    }
     // one workgroup of 4 wavefronts per compute unit and resident wavefront (H = 32: three per SIMD, H = 64: two)
-    const int fill = H == 32 ? cap : cap * 2 / 3;
+    const int fill = 256 * (H == 32 ? 3 : 2);
     if (blocks > fill) blocks = fill;
     // positions are only ever evaluated inside the grid's box: its largest coordinate bounds the encoding's
     // largest argument, 2^8 |p| / (2 pi) revolutions at the highest restart frequency
@@ -666,9 +642,6 @@ int launch(const kn_scene *sc, hipStream_t st, const KnSampleSrc &src, const KnB
 
 } // namespace
 
-#ifdef KN_MLP_TIMING
-extern "C" int kn_debug_mlp_timing(unsigned long long *out) { return (int)hipMemcpyFromSymbol(out, HIP_SYMBOL(kn_mlp_timing), sizeof(unsigned long long) * 8 * 4096); }
-#endif
 int kn_mlp_mfma_tile_len(const kn_scene *) { return MLP_TILE_LEN; }
 
 int kn_mlp_pack_weights(kn_scene *sc, hipStream_t st)
