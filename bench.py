@@ -132,6 +132,24 @@ def isolated_mlp(kn, torch, wdtype, iters=10):
     kn.profile_enable(False)
     mlp_ms_g = prof_g["ms_mlp"] / iters
     tflops_g = FLOP_PER_SAMPLE[sc["hidden"]] * M / (mlp_ms_g * 1e-3) / 1e12
+    # the comparison point of Sec. 3.5: the same networks one layer at a time (grouped matrix products, activations
+    # through device memory), on the grouped-order input
+    need = scene.L.kn_layered_workspace_bytes  # sized once, outside the timed calls
+    import ctypes
+    nbytes = ctypes.c_int64()
+    need(scene.h, M, ctypes.byref(nbytes))
+    ws_l = torch.empty(int(nbytes.value), dtype=torch.uint8, device="cuda")
+    for _ in range(2):
+        scene.eval_grouped_layered(pts_g, dirs_g, out=out, workspace=ws_l)
+    torch.cuda.synchronize()
+    kn.profile_enable(True)
+    kn.profile_read(reset=True)
+    for _ in range(iters):
+        scene.eval_grouped_layered(pts_g, dirs_g, out=out, workspace=ws_l)
+    prof_l = kn.profile_read(reset=True)
+    kn.profile_enable(False)
+    mlp_ms_l = prof_l["ms_mlp"] / iters
+    del ws_l
     # algorithmic bytes per point of the whole call: x, d read twice (cell ids, MLP) is not credited: 12 + 12 in, 16 out,
     # key/perm traffic of the bucketing 16
     return {"workload": "cfg2: 2^22 points, 16^3 networks, %s" % wdtype, "points": M,
@@ -139,7 +157,8 @@ def isolated_mlp(kn, torch, wdtype, iters=10):
             "ms_bucket": prof["ms_bucket"] / iters, "ms_mlp_kernel": mlp_ms,
             "mlp_evals_per_sec": M / (mlp_ms * 1e-3), "mlp_tflops": tflops, "mlp_frac_of_mfma_peak": tflops * 1e12 / PEAK_MFMA_16BIT,
             "grouped_order_input": {"ms_mlp_kernel": mlp_ms_g, "mlp_evals_per_sec": M / (mlp_ms_g * 1e-3), "mlp_tflops": tflops_g,
-                                    "mlp_frac_of_mfma_peak": tflops_g * 1e12 / PEAK_MFMA_16BIT},
+                                    "mlp_frac_of_mfma_peak": tflops_g * 1e12 / PEAK_MFMA_16BIT,
+                                    "layer_at_a_time_ms": mlp_ms_l, "fused_speedup_over_layer_at_a_time": mlp_ms_l / mlp_ms_g},
             "bucket_gbps_algorithmic": 16.0 * M / (prof["ms_bucket"] / iters * 1e-3) / 1e9,
             "mlp_hbm_gbps_algorithmic": (24.0 + 4.0 + 16.0 + 3.5) * M / (mlp_ms * 1e-3) / 1e9}
 

@@ -155,6 +155,18 @@ int kn_render(const kn_scene *scene, void *stream, const float *rays_o /*dev R*3
               const float bg[3] /*host*/, float *rgb_out /*dev R*3*/,
               kn_render_stats *stats /*host, nullable*/, void *workspace, int64_t workspace_bytes);
 
+/* Sec. 3.5: the same function as kn_eval_grouped, evaluated one layer at a time: per layer one
+ * variable-batch grouped matrix product (a separate product per network, batch sizes that differ
+ * from network to network) over the batch ordered by network, activations written to and read
+ * from device memory between the layers (320 + 4*H bytes per point of workspace on top of
+ * kn_eval_grouped's).  Same operands and order of operations as the fused kernel, so the results
+ * are the same bits; it is the comparison point that shows what the fusion buys, not the fast
+ * path.  16-bit scenes only (KN_E_UNSUPPORTED for KN_F32). */
+int kn_layered_workspace_bytes(const kn_scene *scene, int64_t max_points, int64_t *out_bytes);
+int kn_eval_grouped_layered(const kn_scene *scene, void *stream, const float *points /*dev M*3*/,
+                            const float *dirs /*dev M*3*/, int64_t M, float *sigma /*dev M*/,
+                            float *rgb /*dev M*3*/, void *workspace, int64_t workspace_bytes);
+
 /* Sec. 3.4 ("Empty Space Skipping"; tau: Sec. 4.1): fill an occupancy grid of resolution occ_res
  * over the scene's AABB.  The density is sampled on a 3x3x3 subgrid of every voxel and the voxel
  * is marked (byte 1, else 0) iff any of the 27 densities is above tau (strictly).  The density

@@ -18,7 +18,7 @@ KN_F32, KN_F16, KN_BF16 = 0, 1, 2
 DTYPES = {"f32": KN_F32, "f16": KN_F16, "bf16": KN_BF16}
 
 EXPORTS = ["kn_error_string", "kn_last_hip_error", "kn_params_per_net", "kn_scene_create", "kn_scene_destroy",
-           "kn_extract_workspace_bytes", "kn_extract_occupancy",
+           "kn_extract_workspace_bytes", "kn_extract_occupancy", "kn_layered_workspace_bytes", "kn_eval_grouped_layered",
            "kn_workspace_bytes", "kn_cell_ids", "kn_bucket", "kn_eval_grouped", "kn_march", "kn_composite",
            "kn_render", "kn_set_render_params", "kn_profile_enable", "kn_profile_read"]
 
@@ -75,6 +75,8 @@ def load_library(build_if_missing: bool = True):
     L.kn_eval_grouped.argtypes = [vp, vp, vp, vp, i64, vp, vp, vp, vp, vp, vp, i64]
     L.kn_march.argtypes = [vp, vp, vp, vp, i64, f32, f32, i32, vp, i32, vp, vp, vp]
     L.kn_extract_workspace_bytes.argtypes = [vp, C.POINTER(i64)]
+    L.kn_layered_workspace_bytes.argtypes = [vp, i64, C.POINTER(i64)]
+    L.kn_eval_grouped_layered.argtypes = [vp, vp, vp, vp, i64, vp, vp, vp, i64]
     L.kn_extract_occupancy.argtypes = [vp, vp, C.POINTER(i32 * 3), f32, vp, vp, i64]
     L.kn_composite.argtypes = [vp, vp, vp, vp, i64, f32, f32, C.POINTER(f32 * 3), vp, vp, vp]
     L.kn_render.argtypes = [vp, vp, vp, vp, i64, f32, f32, i32, f32, C.POINTER(f32 * 3), vp,
@@ -155,7 +157,7 @@ class Scene:
         self.N = int(res[0]) * int(res[1]) * int(res[2])
         self.hidden = int(hidden)
         self.device = weights.device
-        self._keep = (weights, occupancy)     # KN_F32 scenes borrow the weight buffer
+        self._keep = (weights, occupancy)     # scene creation reads them asynchronously on the stream
         h = C.c_void_p()
         _check(self.L.kn_scene_create(C.byref(d), _stream(), C.byref(h)), "kn_scene_create")
         self.h = h
@@ -224,6 +226,25 @@ class Scene:
                                       _ptr(counts, allow_none=True), p(perm), _ptr(ws), ws.numel()), "kn_eval_grouped")
         if want_aux:
             return sigma, rgb, ids, counts, perm
+        return sigma, rgb
+
+    def eval_grouped_layered(self, points, dirs, out=None, workspace=None):
+        """eval_grouped one layer at a time (grouped matrix products with activations in device memory): the
+        comparison point for the fused kernel.  16-bit scenes only."""
+        import torch
+        M = points.shape[0]
+        if out is None:
+            sigma = torch.empty(M, dtype=torch.float32, device=self.device)
+            rgb = torch.empty((M, 3), dtype=torch.float32, device=self.device)
+        else:
+            sigma, rgb = out
+        if workspace is None:
+            need = C.c_int64()
+            _check(self.L.kn_layered_workspace_bytes(self.h, max(M, 1), C.byref(need)), "kn_layered_workspace_bytes")
+            workspace = torch.empty(int(need.value), dtype=torch.uint8, device=self.device)
+        p = (lambda t: _ptr(t) if M else None)
+        _check(self.L.kn_eval_grouped_layered(self.h, _stream(), p(points), p(dirs), M, p(sigma), p(rgb), _ptr(workspace),
+                                              workspace.numel()), "kn_eval_grouped_layered")
         return sigma, rgb
 
     def extract_occupancy(self, occ_res, tau, out=None):

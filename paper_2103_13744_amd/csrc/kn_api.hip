@@ -21,6 +21,9 @@ int kn_mlp_f32_tile_len(const kn_scene *sc);
 int kn_mlp_f32_pack_weights(kn_scene *sc, hipStream_t st);
 int kn_probe_mfma_launch(const kn_scene *sc, hipStream_t st, const KnProbeJob &job);
 int kn_probe_f32_launch(const kn_scene *sc, hipStream_t st, const KnProbeJob &job);
+int64_t kn_layered_act_bytes(const kn_scene *sc, int64_t M);
+int kn_mlp_layered_launch(const kn_scene *sc, hipStream_t st, const KnSampleSrc &src, const KnBucketOut &b, int64_t M,
+                          int64_t max_tiles, void *acts, float *sigma, float *rgb);
 
 kn_profile g_kn_profile = {};
 bool g_kn_profile_on = false;
@@ -421,6 +424,58 @@ extern "C" int kn_eval_grouped(const kn_scene *sc, void *stream, const float *po
     if (tm.on) {
         g_kn_profile.mlp_launches += 1;
         g_kn_profile.mlp_samples += M; // includes points outside the AABB (they cost no MLP work)
+        g_kn_profile.bucket_keys += M;
+        g_kn_profile.calls += 1;
+    }
+    return KN_OK;
+}
+
+// ---------------------------------------------------------------------------------------------
+// Layer-at-a-time evaluation (the comparison point for the fused kernel)
+extern "C" int kn_layered_workspace_bytes(const kn_scene *sc, int64_t max_points, int64_t *out_bytes)
+{
+    if (!sc || !out_bytes || max_points < 0) return KN_E_INVALID_ARG;
+    if (max_points > (1ll << 30)) return KN_E_UNSUPPORTED;
+    *out_bytes = eval_ws_bytes(sc, max_points) + kn_layered_act_bytes(sc, max_points) + 512;
+    return KN_OK;
+}
+
+extern "C" int kn_eval_grouped_layered(const kn_scene *sc, void *stream, const float *points, const float *dirs, int64_t M,
+                                       float *sigma, float *rgb, void *workspace, int64_t workspace_bytes)
+{
+    if (!sc || M < 0 || (M > 0 && (!points || !dirs || !sigma || !rgb))) return KN_E_INVALID_ARG;
+    if (M > (1ll << 30) || sc->desc.wdtype == KN_F32) return KN_E_UNSUPPORTED;
+    if (!workspace || ((uintptr_t)workspace & 255) ||
+        workspace_bytes < eval_ws_bytes(sc, M) + kn_layered_act_bytes(sc, M) + 256)
+        return KN_E_WORKSPACE;
+    hipStream_t st = (hipStream_t)stream;
+    KnCarver ws(workspace, workspace_bytes);
+    void *acts = ws.carve<char>(kn_layered_act_bytes(sc, M));
+    int32_t *keys = ws.carve<int32_t>(M);
+    if (!ws.ok()) return KN_E_WORKSPACE;
+    KnStageTimer tm(st);
+    tm.begin();
+    int32_t *scratch = nullptr;
+    int64_t n_scratch = 0;
+    kn_bucket_scratch(ws, M, sc->N, &scratch, &n_scratch);
+    KN_TRY(kn_cell_keys(sc, st, points, M, nullptr, keys, scratch, scratch ? n_scratch : 0));
+    tm.mark(KN_ST_CELL);
+    KnBucketOut bo;
+    const int tile_len = kn_mlp_tile_len(sc);
+    KN_TRY(kn_bucket_run(st, keys, M, nullptr, sc->N, tile_len, nullptr, nullptr, nullptr, ws, &bo, scratch != nullptr));
+    if (M == 0) return KN_OK;
+    tm.mark(KN_ST_BUCKET);
+    KnSampleSrc src{};
+    src.points = points;
+    src.dirs = dirs;
+    KN_TRY(kn_mlp_layered_launch(sc, st, src, bo, M, kn_max_tiles(M, sc->N, tile_len), acts, sigma, rgb));
+    hipLaunchKernelGGL(k_zero_outside, dim3((unsigned)kn_div_up(M, 256)), dim3(256), 0, st, bo.perm, bo.offsets, sc->N, M, sigma,
+                       rgb);
+    KN_CHECK_LAUNCH();
+    tm.mark(KN_ST_MLP);
+    if (tm.on) {
+        g_kn_profile.mlp_launches += 6;
+        g_kn_profile.mlp_samples += M;
         g_kn_profile.bucket_keys += M;
         g_kn_profile.calls += 1;
     }

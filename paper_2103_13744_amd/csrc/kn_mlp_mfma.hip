@@ -217,6 +217,41 @@ __device__ __forceinline__ void double_angle(float s, float c, float &s2o, float
 
 constexpr float INV_2PI = 0.15915494309189535f;
 
+// B operands of layer 1 for one lane: gamma(x) slots of lane group g (see "Slot order").  ang[0..2]: the lane's three
+// restart angles in revolutions; ident[0..1]: the packed pairs (x, y), (z, 1) that sit in group 3's last slots.
+template <bool BF, bool WRAP> __device__ __forceinline__ void encode_position(f4 ang, u4 ident, unsigned m3, u4 (&Bx)[2])
+{
+    // s[q] = sin, m[q] = cos of the q-th angle of this lane
+    float s[8], m[8];
+    sincos_rev<WRAP>(ang[0], s[0], m[0]);
+    double_angle(s[0], m[0], s[1], m[1]);
+    sincos_rev<WRAP>(ang[1], s[2], m[2]);
+    double_angle(s[2], m[2], s[3], m[3]);
+    sincos_rev<WRAP>(ang[2], s[4], m[4]);
+    double_angle(s[4], m[4], s[5], m[5]);
+    double_angle(s[5], m[5], s[6], m[6]);
+    double_angle(s[6], m[6], s[7], m[7]);
+    unsigned p[8];
+#pragma unroll
+    for (int q = 0; q < 8; ++q) p[q] = pk<BF>(s[q], m[q]);
+    p[6] = (ident[0] & m3) | (p[6] & ~m3);
+    p[7] = (ident[1] & m3) | (p[7] & ~m3);
+    Bx[0] = (u4){p[0], p[1], p[2], p[3]};
+    Bx[1] = (u4){p[4], p[5], p[6], p[7]};
+}
+// The gamma(d) block of layer 4.  rev: the lane's direction component in revolutions; ident[2..3]: (dx, dy), (dz, 1).
+template <bool BF> __device__ __forceinline__ u4 encode_direction(float rev, u4 ident, unsigned m3)
+{
+    float s[4], m[4];
+    sincos_rev<false>(rev, s[0], m[0]); // directions: |d| far below 256 revolutions
+    double_angle(s[0], m[0], s[1], m[1]);
+    double_angle(s[1], m[1], s[2], m[2]);
+    double_angle(s[2], m[2], s[3], m[3]);
+    // group 3: slots 0..3 hold dx, dy, dz, 1; its slots 4..7 meet zero weights, any finite value does
+    return (u4){(ident[2] & m3) | (pk<BF>(s[0], m[0]) & ~m3), (ident[3] & m3) | (pk<BF>(s[1], m[1]) & ~m3),
+                pk<BF>(s[2], m[2]), pk<BF>(s[3], m[3])};
+}
+
 // Weights stay in registers: 14 blocks (56 VGPRs) for H = 32, three wavefronts per SIMD; 40 blocks (160 VGPRs) for
 // H = 64, two wavefronts per SIMD (the matrix-core operands are read straight from the register file either way).
 template <int H, bool BF, int WAVES, bool WRAP>
@@ -391,36 +426,9 @@ __global__ void __launch_bounds__(WAVES *KN_WAVE) __attribute__((amdgpu_waves_pe
             { // all four sample tiles are always computed: straight-line code lets the scheduler interleave them
                 const f4 ang = stage[wave][g][0][16 * u + n];
                 const u4 ident = __builtin_bit_cast(u4, stage[wave][g][1][16 * u + n]); // meaningful in group 3 only
-                u4 Bx[2], Bd;
-                {
-                    // s[q] = sin, m[q] = cos of the q-th angle of this lane
-                    float s[8], m[8];
-                    sincos_rev<WRAP>(ang[0], s[0], m[0]);
-                    double_angle(s[0], m[0], s[1], m[1]);
-                    sincos_rev<WRAP>(ang[1], s[2], m[2]);
-                    double_angle(s[2], m[2], s[3], m[3]);
-                    sincos_rev<WRAP>(ang[2], s[4], m[4]);
-                    double_angle(s[4], m[4], s[5], m[5]);
-                    double_angle(s[5], m[5], s[6], m[6]);
-                    double_angle(s[6], m[6], s[7], m[7]);
-                    unsigned p[8];
-#pragma unroll
-                    for (int q = 0; q < 8; ++q) p[q] = pk<BF>(s[q], m[q]);
-                    p[6] = (ident[0] & m3) | (p[6] & ~m3);
-                    p[7] = (ident[1] & m3) | (p[7] & ~m3);
-                    Bx[0] = (u4){p[0], p[1], p[2], p[3]};
-                    Bx[1] = (u4){p[4], p[5], p[6], p[7]};
-                }
-                {
-                    float s[4], m[4];
-                    sincos_rev<false>(ang[3], s[0], m[0]); // directions: |d| far below 256 revolutions
-                    double_angle(s[0], m[0], s[1], m[1]);
-                    double_angle(s[1], m[1], s[2], m[2]);
-                    double_angle(s[2], m[2], s[3], m[3]);
-                    // group 3: slots 0..3 hold dx, dy, dz, 1; its slots 4..7 meet zero weights, any finite value does
-                    Bd = (u4){(ident[2] & m3) | (pk<BF>(s[0], m[0]) & ~m3), (ident[3] & m3) | (pk<BF>(s[1], m[1]) & ~m3),
-                              pk<BF>(s[2], m[2]), pk<BF>(s[3], m[3])};
-                }
+                u4 Bx[2];
+                encode_position<BF, WRAP>(ang, ident, m3, Bx);
+                const u4 Bd = encode_direction<BF>(ang[3], ident, m3);
                 f4 acc[HT];
                 u4 Bh[HK];
                 // layer 1: gamma(x) -> H, ReLU (bias through the constant-1 slot)
@@ -571,24 +579,7 @@ __global__ void __launch_bounds__(WAVES *KN_WAVE) __attribute__((amdgpu_waves_pe
                 const f4 ang = stage[wave][g][0][16 * u + n];
                 const u4 ident = __builtin_bit_cast(u4, stage[wave][g][1][16 * u + n]);
                 u4 Bx[2];
-                {
-                    float s[8], m[8];
-                    sincos_rev<WRAP>(ang[0], s[0], m[0]);
-                    double_angle(s[0], m[0], s[1], m[1]);
-                    sincos_rev<WRAP>(ang[1], s[2], m[2]);
-                    double_angle(s[2], m[2], s[3], m[3]);
-                    sincos_rev<WRAP>(ang[2], s[4], m[4]);
-                    double_angle(s[4], m[4], s[5], m[5]);
-                    double_angle(s[5], m[5], s[6], m[6]);
-                    double_angle(s[6], m[6], s[7], m[7]);
-                    unsigned q[8];
-#pragma unroll
-                    for (int i = 0; i < 8; ++i) q[i] = pk<BF>(s[i], m[i]);
-                    q[6] = (ident[0] & m3) | (q[6] & ~m3);
-                    q[7] = (ident[1] & m3) | (q[7] & ~m3);
-                    Bx[0] = (u4){q[0], q[1], q[2], q[3]};
-                    Bx[1] = (u4){q[4], q[5], q[6], q[7]};
-                }
+                encode_position<BF, WRAP>(ang, ident, m3, Bx);
                 f4 acc[HT];
                 u4 Bh[HK];
 #pragma unroll
@@ -614,6 +605,175 @@ __global__ void __launch_bounds__(WAVES *KN_WAVE) __attribute__((amdgpu_waves_pe
         }
         __builtin_amdgcn_wave_barrier(); // the staging buffer is rewritten by the next iteration
         kn_probe_mark(job, active, sg > job.tau, voxel, probe, lane);
+    }
+}
+
+
+// ---------------------------------------------------------------------------------------------
+// Layer-at-a-time evaluation: the variable-batch grouped matrix products of Sec. 3.5 (one product per network and
+// layer, batch sizes that differ per network), which the paper uses where the fused kernel does not apply.  Here it
+// is the fused kernel cut at the layer boundaries, one launch per layer, with the same operands and the same
+// order of operations, so both give the same bits; it exists as the comparison point for the fusion.
+// Activations travel through HBM: row-major per sorted position, 16-bit, columns in slot order, so that the 16 bytes
+// at column 32 kb + 8 g of a row are the B operand of lane group g for input block kb.
+struct KnLayerBufs {
+    uint16_t *x0; // M x 64: gamma(x)
+    uint16_t *dd; // M x 32: gamma(d)
+    uint16_t *ha; // M x H
+    uint16_t *hb; // M x H
+};
+
+template <bool BF, int WAVES, bool WRAP>
+__global__ void __launch_bounds__(WAVES *KN_WAVE)
+    k_layer_encode(KnSampleSrc src, const int32_t *__restrict__ perm, const KnTile *__restrict__ tiles,
+                   const int32_t *__restrict__ n_tiles, KnLayerBufs buf)
+{
+    __shared__ f4 stage[WAVES][4][2][KN_WAVE];
+    const int wave = threadIdx.x / KN_WAVE, lane = threadIdx.x & (KN_WAVE - 1);
+    const int n = lane & 15, g = lane >> 4;
+    const unsigned m3 = (g == 3) ? 0xffffffffu : 0u;
+    const int total_tiles = *n_tiles;
+    for (int t = blockIdx.x * WAVES + wave; t < total_tiles; t += gridDim.x * WAVES) {
+        const KnTile tl = tiles[t];
+        const int32_t idx = perm[tl.start + min(lane, tl.len - 1)];
+        float x, y, z, dx, dy, dz;
+        kn_load_sample(src, idx, x, y, z, dx, dy, dz);
+        {
+            const float p3[3] = {x, y, z}, d3[3] = {dx, dy, dz};
+#pragma unroll
+            for (int a = 0; a < 3; ++a)
+                stage[wave][a][0][lane] = (f4){p3[a] * INV_2PI, p3[a] * (4.0f * INV_2PI), p3[a] * (16.0f * INV_2PI), d3[a] * INV_2PI};
+            stage[wave][3][0][lane] = (f4){x * (256.0f * INV_2PI), y * (256.0f * INV_2PI), z * (256.0f * INV_2PI), 0.0f};
+            const u4 ident = {pk<BF>(x, y), pk<BF>(z, 1.0f), pk<BF>(dx, dy), pk<BF>(dz, 1.0f)};
+            stage[wave][3][1][lane] = __builtin_bit_cast(f4, ident);
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const f4 ang = stage[wave][g][0][16 * u + n];
+            const u4 ident = __builtin_bit_cast(u4, stage[wave][g][1][16 * u + n]);
+            u4 Bx[2];
+            encode_position<BF, WRAP>(ang, ident, m3, Bx);
+            const u4 Bd = encode_direction<BF>(ang[3], ident, m3);
+            if (16 * u + n < tl.len) {
+                const int64_t row = tl.start + 16 * u + n;
+                *(u4 *)(buf.x0 + row * 64 + 8 * g) = Bx[0];
+                *(u4 *)(buf.x0 + row * 64 + 32 + 8 * g) = Bx[1];
+                *(u4 *)(buf.dd + row * 32 + 8 * g) = Bd;
+            }
+        }
+        __builtin_amdgcn_wave_barrier(); // the staging buffer is rewritten by the next iteration
+    }
+}
+
+// LAYER 1..5 of Sec. 3.2: 1: gamma(x) -> ha; 2: ha -> hb; 3: hb -> ha (feature) and the density; 4: [ha, gamma(d)] -> hb;
+// 5: hb -> colour.  Tiles are dealt out as in k_mlp_mfma (a contiguous range per wavefront, weights re-fetched when
+// the network changes).
+template <int H, bool BF, int WAVES, int LAYER>
+__global__ void __launch_bounds__(WAVES *KN_WAVE)
+    k_layer(const uint16_t *__restrict__ packed, const int32_t *__restrict__ perm, const KnTile *__restrict__ tiles,
+            const int32_t *__restrict__ n_tiles, KnLayerBufs buf, float *__restrict__ sigma, float *__restrict__ rgb)
+{
+    using L = Lay<H>;
+    constexpr int HT = L::HT, HK = L::HK;
+    constexpr int NB = LAYER == 1 ? 2 : (LAYER == 4 ? HK + 1 : HK); // input blocks
+    constexpr int NT = LAYER == 5 ? 0 : HT;                          // output tiles of the layer proper
+    constexpr int W0 = LAYER == 1 ? L::L1 : (LAYER == 2 ? L::L2 : (LAYER == 3 ? L::L3 : (LAYER == 4 ? L::L4 : L::L5)));
+    constexpr bool HEAD = LAYER == 3 || LAYER == 5;                  // has a density / colour head
+    constexpr int WH = LAYER == 3 ? L::LS : L::L5;
+    const uint16_t *__restrict__ in = LAYER == 1 ? buf.x0 : ((LAYER == 2 || LAYER == 4) ? buf.ha : buf.hb);
+    uint16_t *__restrict__ out = (LAYER == 1 || LAYER == 3) ? buf.ha : buf.hb;
+    constexpr int IN_COLS = LAYER == 1 ? 64 : H;
+
+    const int wave = threadIdx.x / KN_WAVE, lane = threadIdx.x & (KN_WAVE - 1);
+    const int n = lane & 15, g = lane >> 4;
+    const f4 zero4 = {0.0f, 0.0f, 0.0f, 0.0f};
+    const int total_tiles = *n_tiles;
+    const int total_waves = gridDim.x * WAVES;
+    const int wid = __builtin_amdgcn_readfirstlane(blockIdx.x * WAVES + wave);
+    const int t_lo = __builtin_amdgcn_readfirstlane((int)((int64_t)wid * total_tiles / total_waves));
+    const int t_hi = __builtin_amdgcn_readfirstlane((int)((int64_t)(wid + 1) * total_tiles / total_waves));
+    if (t_lo >= t_hi) return;
+
+    u4 aw[NT * NB > 0 ? NT * NB : 1], ah[HEAD ? HK : 1];
+    f4 bias[NT > 0 ? NT : 1], bias_head = zero4;
+    auto load_network = [&](int32_t net) {
+        const u4 *__restrict__ wp = (const u4 *)(packed + (int64_t)net * L::HALFS);
+#pragma unroll
+        for (int b = 0; b < NT * NB; ++b) aw[b] = wp[(W0 + b) * KN_WAVE + lane];
+        if constexpr (HEAD) {
+#pragma unroll
+            for (int kb = 0; kb < HK; ++kb) ah[kb] = wp[(WH + kb) * KN_WAVE + lane];
+        }
+        const float *__restrict__ tail = (const float *)(wp + L::NBLK * KN_WAVE);
+#pragma unroll
+        for (int t = 0; t < NT; ++t) {
+            if constexpr (LAYER == 2) bias[t] = *(const f4 *)(tail + 16 * t + 4 * g);
+            else if constexpr (LAYER == 3) bias[t] = *(const f4 *)(tail + H + 16 * t + 4 * g);
+            else bias[t] = zero4; // layers 1 and 4: the bias rides in a constant-1 input slot
+        }
+        if constexpr (HEAD) bias_head = *(const f4 *)(tail + 2 * H); // (b5, density bias)
+    };
+    int32_t net_cur = -1;
+    for (int t = t_lo; t < t_hi; ++t) {
+        const KnTile tl = tiles[t];
+        if (tl.net != net_cur) { // uniform
+            load_network(tl.net);
+            net_cur = tl.net;
+        }
+        f4 heads[4] = {bias_head, bias_head, bias_head, bias_head};
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int64_t row = tl.start + min(16 * u + n, tl.len - 1);
+            u4 B[NB];
+#pragma unroll
+            for (int kb = 0; kb < NB; ++kb) {
+                if (LAYER == 4 && kb == HK) B[kb] = *(const u4 *)(buf.dd + row * 32 + 8 * g);
+                else B[kb] = *(const u4 *)(in + row * IN_COLS + 32 * kb + 8 * g);
+            }
+            if constexpr (NT > 0) {
+                f4 acc[NT];
+#pragma unroll
+                for (int t2 = 0; t2 < NT; ++t2) {
+                    if constexpr (LAYER == 4) { // same order as the fused kernel: gamma(d) block first
+                        acc[t2] = mfma<BF>(aw[t2 * NB + HK], B[HK], zero4);
+#pragma unroll
+                        for (int kb = 0; kb < HK; ++kb) acc[t2] = mfma<BF>(aw[t2 * NB + kb], B[kb], acc[t2]);
+                    } else {
+                        acc[t2] = bias[t2];
+#pragma unroll
+                        for (int kb = 0; kb < NB; ++kb) acc[t2] = mfma<BF>(aw[t2 * NB + kb], B[kb], acc[t2]);
+                    }
+                }
+                u4 Bh[HK];
+                pack_acts<H, BF, LAYER != 3>(acc, Bh);
+                if (16 * u + n < tl.len) {
+                    const int64_t orow = tl.start + 16 * u + n;
+#pragma unroll
+                    for (int kb = 0; kb < HK; ++kb) *(u4 *)(out + orow * H + 32 * kb + 8 * g) = Bh[kb];
+                }
+            }
+            if constexpr (HEAD) {
+#pragma unroll
+                for (int kb = 0; kb < HK; ++kb) heads[u] = mfma<BF>(ah[kb], B[kb], heads[u]);
+            }
+        }
+        if constexpr (HEAD) {
+            // the head blocks repeat their rows with period four: lane group g keeps tile g, lane l sample l
+            const f4 o = g == 0 ? heads[0] : (g == 1 ? heads[1] : (g == 2 ? heads[2] : heads[3]));
+            if (lane < tl.len) {
+                const int32_t idx = perm[tl.start + lane];
+                if constexpr (LAYER == 3) {
+                    sigma[idx] = fmaxf(o[3], 0.0f);
+                } else {
+#pragma unroll
+                    for (int c = 0; c < 3; ++c)
+                        rgb[3 * (int64_t)idx + c] = __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-1.4426950408889634f * o[c]));
+                }
+            }
+        }
     }
 }
 
@@ -691,6 +851,65 @@ int kn_probe_mfma_launch(const kn_scene *sc, hipStream_t st, const KnProbeJob &j
     if (H != 32 && H != 64) return KN_E_UNSUPPORTED;
     KN_CHECK_LAUNCH();
     return KN_OK;
+}
+
+int64_t kn_layered_act_bytes(const kn_scene *sc, int64_t M)
+{
+    const int64_t m = M > 0 ? M : 1;
+    return kn_align_up(m * 64 * 2, 256) + kn_align_up(m * 32 * 2, 256) + 2 * kn_align_up(m * sc->desc.hidden * 2, 256);
+}
+
+template <int H, bool BF>
+static int layered_launch(const kn_scene *sc, hipStream_t st, const KnSampleSrc &src, const KnBucketOut &b, int64_t max_tiles,
+                          bool wrap, const KnLayerBufs &buf, float *sigma, float *rgb)
+{
+    constexpr int W = MLP_WAVES;
+    int64_t blocks = kn_div_up(max_tiles, W);
+    if (blocks > 256 * 4) blocks = 256 * 4;
+    const dim3 grid((unsigned)blocks), block(W * KN_WAVE);
+    const uint16_t *w = (const uint16_t *)sc->packed_w;
+    if (wrap)
+        hipLaunchKernelGGL((k_layer_encode<BF, W, true>), grid, block, 0, st, src, b.perm, b.tiles, b.n_tiles, buf);
+    else
+        hipLaunchKernelGGL((k_layer_encode<BF, W, false>), grid, block, 0, st, src, b.perm, b.tiles, b.n_tiles, buf);
+    KN_CHECK_LAUNCH();
+    hipLaunchKernelGGL((k_layer<H, BF, W, 1>), grid, block, 0, st, w, b.perm, b.tiles, b.n_tiles, buf, sigma, rgb);
+    KN_CHECK_LAUNCH();
+    hipLaunchKernelGGL((k_layer<H, BF, W, 2>), grid, block, 0, st, w, b.perm, b.tiles, b.n_tiles, buf, sigma, rgb);
+    KN_CHECK_LAUNCH();
+    hipLaunchKernelGGL((k_layer<H, BF, W, 3>), grid, block, 0, st, w, b.perm, b.tiles, b.n_tiles, buf, sigma, rgb);
+    KN_CHECK_LAUNCH();
+    hipLaunchKernelGGL((k_layer<H, BF, W, 4>), grid, block, 0, st, w, b.perm, b.tiles, b.n_tiles, buf, sigma, rgb);
+    KN_CHECK_LAUNCH();
+    hipLaunchKernelGGL((k_layer<H, BF, W, 5>), grid, block, 0, st, w, b.perm, b.tiles, b.n_tiles, buf, sigma, rgb);
+    KN_CHECK_LAUNCH();
+    return KN_OK;
+}
+
+// `acts`: kn_layered_act_bytes(sc, M) bytes of device memory, 256-byte aligned
+int kn_mlp_layered_launch(const kn_scene *sc, hipStream_t st, const KnSampleSrc &src, const KnBucketOut &b, int64_t M,
+                          int64_t max_tiles, void *acts, float *sigma, float *rgb)
+{
+    if (max_tiles <= 0 || M <= 0) return KN_OK;
+    const int H = sc->desc.hidden;
+    if (sc->desc.wdtype == KN_F32 || (H != 32 && H != 64)) return KN_E_UNSUPPORTED;
+    KnCarver c(acts, kn_layered_act_bytes(sc, M));
+    KnLayerBufs buf;
+    buf.x0 = c.carve<uint16_t>(M * 64);
+    buf.dd = c.carve<uint16_t>(M * 32);
+    buf.ha = c.carve<uint16_t>(M * H);
+    buf.hb = c.carve<uint16_t>(M * H);
+    if (!c.ok()) return KN_E_WORKSPACE;
+    float reach = 0.0f;
+    for (int a = 0; a < 3; ++a)
+        reach = fmaxf(reach, fmaxf(fabsf(sc->desc.aabb_min[a]), fabsf(sc->desc.aabb_max[a])));
+    const bool wrap = !(reach * (256.0f * INV_2PI) < 250.0f);
+    const bool bf = sc->desc.wdtype == KN_BF16;
+    if (H == 32)
+        return bf ? layered_launch<32, true>(sc, st, src, b, max_tiles, wrap, buf, sigma, rgb)
+                  : layered_launch<32, false>(sc, st, src, b, max_tiles, wrap, buf, sigma, rgb);
+    return bf ? layered_launch<64, true>(sc, st, src, b, max_tiles, wrap, buf, sigma, rgb)
+              : layered_launch<64, false>(sc, st, src, b, max_tiles, wrap, buf, sigma, rgb);
 }
 
 int kn_mlp_mfma_launch(const kn_scene *sc, hipStream_t st, const KnSampleSrc &src, const KnBucketOut &b, int64_t max_tiles,

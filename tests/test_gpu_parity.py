@@ -159,6 +159,36 @@ def test_eval_grouped_empty_and_permutation_invariance():
     np.testing.assert_array_equal(c2, c1[p])
 
 
+@pytest.mark.parametrize("wdtype,H", [("f16", 32), ("bf16", 32), ("f16", 64), ("bf16", 64)])
+def test_layer_at_a_time_equals_fused_and_oracle(wdtype, H):
+    """Sec. 3.5's grouped matrix products, one launch per layer: same operands and order of operations as the fused
+    kernel, so the same bits; and within the 16-bit bar of the oracle."""
+    import torch
+    sc = scene_dict((4, 3, 5), (-1, -1, -1), (1, 1, 1), H, wdtype, 41, sigma_scale=3.0)
+    M = 23_017                                                   # ragged groups, a ragged last tile, points outside
+    pts, dirs = ks.uniform_points(M, 42, lo=(-1.03,) * 3, hi=(1.03,) * 3), ks.sphere_dirs(M, 43)
+    dev, orc = make_pair(sc, threads=True)
+    s_f, c_f = [t.cpu().numpy() for t in dev.eval_grouped(cuda(pts), cuda(dirs))]
+    s_l, c_l = [t.cpu().numpy() for t in dev.eval_grouped_layered(cuda(pts), cuda(dirs))]
+    np.testing.assert_array_equal(s_l, s_f)
+    np.testing.assert_array_equal(c_l, c_f)
+    s_o, c_o, ids = orc.eval_points(pts, dirs)
+    assert np.abs(c_l - c_o).max() <= TOL[wdtype]
+    assert (np.abs(s_l - s_o) / 3.0 / (1 + s_o / 3.0)).max() <= TOL[wdtype]
+    assert np.all(s_l[ids < 0] == 0) and np.all(c_l[ids < 0] == 0) and (ids < 0).sum() > 100
+    e = torch.empty((0, 3), dtype=torch.float32, device="cuda")
+    assert dev.eval_grouped_layered(e, e)[0].numel() == 0
+
+
+def test_layer_at_a_time_is_refused_for_fp32_scenes():
+    import paper_2103_13744_amd as kn
+    sc = scene_dict((2, 2, 2), (0, 0, 0), (1, 1, 1), 32, "f32", 44)
+    dev, _ = make_pair(sc)
+    pts, dirs = ks.uniform_points(100, 45), ks.sphere_dirs(100, 46)
+    with pytest.raises(kn.KnError):
+        dev.eval_grouped_layered(cuda(pts), cuda(dirs))
+
+
 # ------------------------------------------------------------------ a1: marching
 def test_march_bit_exact_and_resumable():
     cfg = configs.config3(40, 40)
