@@ -127,7 +127,10 @@ __global__ void __launch_bounds__(F32_WAVES *KN_WAVE) __attribute__((amdgpu_wave
 
     const int total_tiles = *n_tiles;
     const int total_waves = gridDim.x * F32_WAVES;
-    const int wid = __builtin_amdgcn_readfirstlane(blockIdx.x * F32_WAVES + wave);
+    // workgroup b runs on XCD b % 8: renumbered so that an XCD (one L2) works on a contiguous eighth of the tile list
+    const int xcd_share = gridDim.x >> 3;
+    const int block_no = (gridDim.x & 7) == 0 ? (int)(blockIdx.x & 7) * xcd_share + (int)(blockIdx.x >> 3) : (int)blockIdx.x;
+    const int wid = __builtin_amdgcn_readfirstlane(block_no * F32_WAVES + wave);
     const int t_lo = __builtin_amdgcn_readfirstlane((int)((int64_t)wid * total_tiles / total_waves));
     const int t_hi = __builtin_amdgcn_readfirstlane((int)((int64_t)(wid + 1) * total_tiles / total_waves));
     if (t_lo >= t_hi) return;

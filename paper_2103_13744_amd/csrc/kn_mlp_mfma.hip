@@ -279,7 +279,12 @@ __global__ void __launch_bounds__(WAVES *KN_WAVE) __attribute__((amdgpu_waves_pe
     // are fetched only when the network changes.
     const int total_tiles = *n_tiles;
     const int total_waves = gridDim.x * WAVES;
-    const int wid = __builtin_amdgcn_readfirstlane(blockIdx.x * WAVES + wave);
+    // Workgroups are dealt to the eight XCDs round-robin (workgroup b runs on XCD b % 8, each with an L2 of its
+    // own).  Renumbered so that an XCD works on one contiguous eighth of the tile list, i.e. on neighbouring
+    // networks: a ray's data and a network's weights are then fetched into one L2 instead of several.
+    const int xcd_share = gridDim.x >> 3;
+    const int block_no = (gridDim.x & 7) == 0 ? (int)(blockIdx.x & 7) * xcd_share + (int)(blockIdx.x >> 3) : (int)blockIdx.x;
+    const int wid = __builtin_amdgcn_readfirstlane(block_no * WAVES + wave);
     // (kept in scalar registers: tile descriptors are then fetched through the scalar cache, whose counter is
     // separate from the one of the vector loads and stores in flight)
     const int t_lo = __builtin_amdgcn_readfirstlane((int)((int64_t)wid * total_tiles / total_waves));
