@@ -298,6 +298,22 @@ def main():
                 "frac": nbytes / s_ / PEAK_HBM if s_ > 0 else 0.0, "traffic": traffic.get("k_march_wave"),
                 "avg_launch_ms": p["ms_march"] / max(launches, 1), "launches": launches}
 
+    def roof_hbm(p, key, kernel, nbytes, traffic_key):
+        s_ = p[key] * 1e-3
+        return {"kernel": kernel, "bound": "hbm", "achieved": nbytes / s_ / 1e9 if s_ > 0 else 0.0, "peak": PEAK_HBM / 1e9,
+                "unit": "GB/s", "frac": nbytes / s_ / PEAK_HBM if s_ > 0 else 0.0, "traffic": traffic.get(traffic_key),
+                "avg_launch_ms": p[key] / max(launches, 1), "launches": launches}
+
+    def roof_group(p):
+        # algorithmic bytes: every sample's key is read twice (count, fill) and its slot number written: 12 B
+        return roof_hbm(p, "ms_bucket", "k_group_pass (order-free grouping by network)", 12.0 * evaluated, "k_group_pass")
+
+    def roof_blend(p):
+        # algorithmic bytes: 16 B read per evaluated sample, 12 B written per ray of the frame; the per-ray state of the
+        # live rays (32 B per wave) is not credited here
+        return roof_hbm(p, "ms_blend", "k_composite_wave / k_composite_group + k_sum_partials (blend, early termination)",
+                        16.0 * evaluated + 12.0 * R * a.steps, "k_composite_wave")
+
     roofline = roof_mlp(prof) if dominant == "ms_mlp" else roof_march(prof) if dominant == "ms_march" else roof_mlp(prof_all)
     res = {
         "metric": "MLP sample evals/sec + frames/sec at 800x800",
@@ -314,6 +330,7 @@ def main():
         "dominant_kernel_stage": dominant,
         "roofline": roofline,
         "roofline_mlp_all_events": roof_mlp(prof_all), "roofline_march_all_events": roof_march(prof_all),
+        "roofline_group_all_events": roof_group(prof_all), "roofline_blend_all_events": roof_blend(prof_all),
     }
     if a.in_flight > 1:
         res["frames_in_flight"] = frames_in_flight(torch, scene, rays, args, R, a.steps, a.in_flight, blended / a.steps)
