@@ -189,6 +189,46 @@ def test_layer_at_a_time_is_refused_for_fp32_scenes():
         dev.eval_grouped_layered(cuda(pts), cuda(dirs))
 
 
+def test_eval_grouped_random_configurations_fp32():
+    """Thirty seeded random cases: grid shapes, boxes, batch sizes from 0 to a few thousand, points partly outside."""
+    g = np.random.default_rng(20210314)
+    for it in range(30):
+        H = [32, 64][g.integers(0, 2)]
+        nres = tuple(int(v) for v in g.integers(1, 9, size=3))
+        lo = g.uniform(-3, 1, size=3)
+        hi = lo + g.uniform(0.3, 4, size=3)
+        sc = scene_dict(nres, tuple(lo), tuple(hi), H, "f32", int(g.integers(1, 1 << 30)))
+        M = int(g.choice([0, 1, 2, 63, 64, 65, 1000, 4097]))
+        pad = 0.05 * (hi - lo)
+        pts = ks.uniform_points(M, int(g.integers(1, 1 << 30)), lo=tuple(lo - pad), hi=tuple(hi + pad))
+        dirs = ks.sphere_dirs(M, int(g.integers(1, 1 << 30)))
+        if M == 0:
+            dev, _ = make_pair(sc)
+            assert dev.eval_grouped(cuda(pts.reshape(0, 3)), cuda(dirs.reshape(0, 3)))[0].numel() == 0
+        else:
+            check_eval(sc, pts, dirs)
+
+
+def test_extract_occupancy_random_configurations_fp32():
+    """Fifteen seeded random pairs of network grid and occupancy resolution (mostly not nested), every voxel checked."""
+    g = np.random.default_rng(20210315)
+    for it in range(15):
+        nres = tuple(int(v) for v in g.integers(1, 6, size=3))
+        ores = tuple(int(v) for v in g.integers(1, 14, size=3))
+        lo = g.uniform(-2, 0, size=3)
+        hi = lo + g.uniform(0.5, 3, size=3)
+        sc = scene_dict(nres, tuple(lo), tuple(hi), [32, 64][g.integers(0, 2)], "f32", int(g.integers(1, 1 << 30)), sigma_scale=20.0)
+        orc = make_pair(sc, threads=True)[1]
+        top = orc.extract_occupancy(ores, 0.0)[1]
+        tau = float(np.quantile(top, g.uniform(0.2, 0.8)))
+        dev = make_pair(sc)[0]
+        got = dev.extract_occupancy(ores, tau).cpu().numpy()
+        want, _, mg = orc.extract_occupancy(ores, tau)
+        close = mg <= 1e-4 * 20.0
+        np.testing.assert_array_equal(got[~close], want[~close])
+        assert close.sum() <= 2 + 0.01 * close.size
+
+
 # ------------------------------------------------------------------ a1: marching
 def test_march_bit_exact_and_resumable():
     cfg = configs.config3(40, 40)
@@ -403,6 +443,52 @@ def test_render_calls_in_flight_on_one_scene():
         x.join()
     for t, (_, _, ref) in enumerate(views):
         np.testing.assert_array_equal(results[t], ref)
+
+
+def test_render_random_configurations_fp32():
+    """Forty seeded random scenes: grid shapes (nested and not, with and without occupancy), boxes, cameras, K from 1 to
+    600, termination thresholds and wave schedules (down to one sample per ray and wave, four slots per ray), fp32 so
+    that the pixel bar is tight.  Every pixel against the oracle."""
+    import torch
+    import paper_2103_13744_amd as kn
+    g = np.random.default_rng(20210313)
+    try:
+        for it in range(40):
+            H = [32, 64][g.integers(0, 2)]
+            nres = tuple(int(v) for v in g.integers(1, 7, size=3))
+            if g.random() < 0.5:
+                ores = tuple(int(n * 2 ** g.integers(0, 4)) for n in nres)
+            else:
+                ores = tuple(int(v) for v in g.integers(1, 40, size=3))
+            lo = g.uniform(-2, 0, size=3)
+            hi = lo + g.uniform(0.5, 3, size=3)
+            seed = int(g.integers(1, 1 << 30))
+            occ = ks.blob_occupancy(ores, int(g.integers(1, 6)), float(g.uniform(0.05, 0.6)), seed) if g.random() < 0.8 else None
+            sc = configs._scene(nres, lo, hi, H, "f32", seed, sigma_scale=float(g.choice([1.0, 10.0, 100.0])), occ=occ)
+            W, Hh = int(g.integers(1, 40)), int(g.integers(1, 40))
+            diag = float(np.linalg.norm(hi - lo))
+            rad = diag * g.uniform(0.8, 1.5)
+            o, d = ks.camera_rays(W, Hh, float(g.uniform(20, 70)), rad, float(g.uniform(0, 360)), float(g.uniform(-60, 60)),
+                                  center=tuple(0.5 * (lo + hi)))
+            K = int(g.choice([1, 7, 32, 100, 257, 600]))
+            t_near = max(rad - diag / 2, 0.0) * g.uniform(0.9, 1.0)
+            step = diag / K * g.uniform(0.8, 1.3)
+            eps = float(g.choice([0.0, 0.01, 0.1]))
+            sched = (int(g.choice([0, 1, 3, 16, 48])), int(g.choice([0, 4, 32, 128])), int(g.choice([0, 2, 4, 32])))
+            kn.set_render_params(*sched)
+            dev, orc = make_pair(sc, threads=True)
+            img, st = dev.render(cuda(o), cuda(d), t_near, step, K, eps, (0.3, 0.6, 0.9), want_stats=True)
+            torch.cuda.synchronize()
+            ref, n_eval, _, mg = orc.render(o, d, t_near, step, K, eps, (0.3, 0.6, 0.9))
+            err = np.abs(img.cpu().numpy().astype(np.float64) - ref).max(axis=1)
+            straddle = mg < 1e-3
+            what = "case %d: H %d grid %s occupancy %s K %d eps %g schedule %s" % (it, H, nres, ores if occ is not None else None, K, eps, sched)
+            assert err[~straddle].max(initial=0.0) <= 1e-4, what
+            assert err[straddle].max(initial=0.0) <= 1e-4 + eps, what
+            assert abs(st["samples_blended"] - n_eval.sum()) <= straddle.sum(), what
+            assert st["samples_evaluated"] >= st["samples_blended"], what
+    finally:
+        kn.set_render_params(0, 0, 0)
 
 
 def test_render_edge_cases():
