@@ -118,6 +118,14 @@ def test_eval_grouped_fp32_noncubic_grid():
     check_eval(sc, pts, ks.sphere_dirs(M, 4))
 
 
+def test_eval_grouped_fp32_large_box():
+    # 2^9 p reaches tens of thousands of radians: the encoding's range reduction has to stay accurate there
+    sc = scene_dict((3, 2, 4), (-40, -10, 5), (40, 30, 45), 32, "f32", 18)
+    M = 10_003
+    pts = ks.uniform_points(M, 19, lo=(-41, -11, 4), hi=(41, 31, 46))
+    check_eval(sc, pts, ks.sphere_dirs(M, 20))
+
+
 @pytest.mark.parametrize("wdtype,H", [("f16", 32), ("bf16", 32), ("f16", 64), ("bf16", 64)])
 def test_eval_grouped_matrix_cores(wdtype, H):
     sc = scene_dict((4, 4, 4), (-1, -1, -1), (1, 1, 1), H, wdtype, 7)
