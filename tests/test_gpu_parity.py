@@ -612,6 +612,37 @@ def test_extract_occupancy_threshold_cases_and_single_network():
         np.testing.assert_array_equal(k[r, :cnt[r]].cpu().numpy(), orc2.march(o[r], d[r], 0.0, 0.02, 100))
 
 
+def test_error_statuses_of_extraction_and_layered_evaluation():
+    """Bad arguments are turned into status codes on the host, before any launch."""
+    import ctypes as C
+    import torch
+    import paper_2103_13744_amd as kn
+    sc = scene_dict((2, 2, 2), (0, 0, 0), (1, 1, 1), 32, "f16", 51)
+    dev, _ = make_pair(sc)
+    L, h = dev.L, dev.h
+    occ = torch.empty(64, dtype=torch.uint8, device="cuda")
+    ws = torch.empty(1 << 16, dtype=torch.uint8, device="cuda")
+    res = lambda *v: C.byref((C.c_int32 * 3)(*v))
+    call = lambda r, tau, o, w, nb: L.kn_extract_occupancy(h, None, r, tau, o, w, nb)
+    assert call(res(4, 4, 4), 1.0, occ.data_ptr(), ws.data_ptr(), ws.numel()) == 0
+    assert call(res(4, 0, 4), 1.0, occ.data_ptr(), ws.data_ptr(), ws.numel()) == -1          # empty resolution
+    assert call(res(4, 4, 4), float("nan"), occ.data_ptr(), ws.data_ptr(), ws.numel()) == -1
+    assert call(res(4, 4, 4), 1.0, None, ws.data_ptr(), ws.numel()) == -1                    # no output
+    assert call(res(4, 4, 4), 1.0, occ.data_ptr(), None, 0) == -3                            # no workspace
+    assert call(res(4, 4, 4), 1.0, occ.data_ptr(), ws.data_ptr(), 16) == -3                  # workspace too small
+    assert call(res(4, 4, 4), 1.0, occ.data_ptr(), ws.data_ptr() + 4, ws.numel() - 4) == -3  # misaligned
+    assert call(res(2048, 2048, 2048), 1.0, occ.data_ptr(), ws.data_ptr(), ws.numel()) == -2 # more than 2^31 - 1 voxels
+    assert call(res(1300, 1300, 1200), 1.0, occ.data_ptr(), ws.data_ptr(), ws.numel()) == -2 # too many voxels per network
+    pts = cuda(ks.uniform_points(10, 52))
+    out_s, out_c = torch.empty(10, device="cuda"), torch.empty((10, 3), device="cuda")
+    lay = lambda m, w, nb: L.kn_eval_grouped_layered(h, None, pts.data_ptr(), pts.data_ptr(), m, out_s.data_ptr(),
+                                                      out_c.data_ptr(), w, nb)
+    assert lay(-1, ws.data_ptr(), ws.numel()) == -1
+    assert lay(10, ws.data_ptr(), 64) == -3
+    assert lay(10, None, 0) == -3
+    torch.cuda.synchronize()
+
+
 # ------------------------------------------------------------------ full-size workloads (sampled comparison)
 def test_full_config2_sampled():
     cfg = configs.config2()
