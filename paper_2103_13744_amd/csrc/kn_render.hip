@@ -745,103 +745,107 @@ __global__ void __launch_bounds__(256)
 // ... counters[3] += slots of this wave, counters[4] += 1 if the wave had rows; writes the next wave's control
 // partials: evaluated and blended samples per workgroup of the blend (2 * n_cb); surv16: survivors per group of 16
 // rows (n_blocks groups)
-__global__ void __launch_bounds__(256) k_sum_partials(const int32_t *__restrict__ partials, int32_t n_cb,
-                                                      const int32_t *__restrict__ surv16, int32_t n_blocks,
-                                                      unsigned long long *__restrict__ counters,
-                                                      const int32_t *__restrict__ ctl, int32_t *__restrict__ ctl_next,
-                                                      WaveSchedule sched, int32_t *__restrict__ blk_off,
-                                                      unsigned long long *mailbox, unsigned long long seq)
+__global__ void __launch_bounds__(1024) k_sum_partials(const int32_t *__restrict__ partials, int32_t n_cb,
+                                                        const int32_t *__restrict__ surv16, int32_t n_blocks,
+                                                        unsigned long long *__restrict__ counters,
+                                                        const int32_t *__restrict__ ctl, int32_t *__restrict__ ctl_next,
+                                                        WaveSchedule sched, int32_t *__restrict__ blk_off,
+                                                        unsigned long long *mailbox, unsigned long long seq)
 {
-    __shared__ unsigned long long red[3][256 / KN_WAVE];
-    unsigned long long v[3] = {0ull, 0ull, 0ull};
-    for (int32_t b0 = 0; b0 < max(n_blocks, n_cb); b0 += 256 * 8) { // batches of independent loads
-        int32_t t[3][8];
+    // This kernel sits alone between the blend and the next wave's march: what counts is its latency.  Every value is
+    // requested once, as early as possible, and each thread scans 16 contiguous entries (one 64-byte line) itself.
+    constexpr int T = 1024, PER = 16;
+    typedef int32_t i4 __attribute__((ext_vector_type(4)));
+    __shared__ int32_t lds[T / KN_WAVE];
+    __shared__ unsigned long long red[2][T / KN_WAVE];
+    const int tid = threadIdx.x;
+    int32_t rows = 0, slots_per_row = 0, s_sched = 0;
+    unsigned long long tot_eval = 0ull, tot_blend = 0ull, tot_slots = 0ull, tot_waves = 0ull;
+    if (tid == 0) { // the scalars of the closing thread
+        rows = ctl[0];
+        slots_per_row = ctl[1];
+        s_sched = ctl[2];
+        tot_eval = counters[0];
+        tot_blend = counters[1];
+        tot_slots = counters[3];
+        tot_waves = counters[4];
+    }
+    unsigned long long ev = 0ull, bl = 0ull;
+    for (int32_t b = tid; b < n_cb; b += T) {
+        ev += (unsigned long long)partials[b];
+        bl += (unsigned long long)partials[(int64_t)n_cb + b];
+    }
+    // exclusive prefix sums of the survivors per 16-row group: the next wave's march compacts the list with them
+    int32_t survivors = 0;
+    for (int32_t b0 = 0; b0 < n_blocks; b0 += T * PER) {
+        const int32_t e0 = b0 + PER * tid;
+        const bool full = e0 + PER <= n_blocks;
+        int32_t v[PER];
+        if (full) {
 #pragma unroll
-        for (int u = 0; u < 8; ++u) {
-            const int32_t b = b0 + u * 256 + threadIdx.x;
-            // unconditional (clamped) loads batch up
-            const int32_t qe = partials[min(b, n_cb - 1)], qb = partials[(int64_t)n_cb + min(b, n_cb - 1)];
-            const int32_t qs = surv16[min(b, n_blocks - 1)];
-            t[0][u] = b < n_cb ? qe : 0;
-            t[1][u] = b < n_cb ? qb : 0;
-            t[2][u] = b < n_blocks ? qs : 0;
+            for (int u = 0; u < PER / 4; ++u) {
+                const i4 q = *(const i4 *)(surv16 + e0 + 4 * u);
+                v[4 * u] = q[0]; v[4 * u + 1] = q[1]; v[4 * u + 2] = q[2]; v[4 * u + 3] = q[3];
+            }
+        } else {
+#pragma unroll
+            for (int u = 0; u < PER; ++u) v[u] = e0 + u < n_blocks ? surv16[e0 + u] : 0;
         }
+        int32_t sum = 0;
 #pragma unroll
-        for (int u = 0; u < 8; ++u)
+        for (int u = 0; u < PER; ++u) sum += v[u];
+        int32_t total;
+        int32_t off = survivors + kn_block_exclusive_scan(sum, lds, total);
 #pragma unroll
-            for (int c = 0; c < 3; ++c) v[c] += (unsigned long long)t[c][u];
+        for (int u = 0; u < PER; ++u) {
+            const int32_t c = v[u];
+            v[u] = off;
+            off += c;
+        }
+        if (full) {
+#pragma unroll
+            for (int u = 0; u < PER / 4; ++u) *(i4 *)(blk_off + e0 + 4 * u) = (i4){v[4 * u], v[4 * u + 1], v[4 * u + 2], v[4 * u + 3]};
+        } else {
+#pragma unroll
+            for (int u = 0; u < PER; ++u)
+                if (e0 + u < n_blocks) blk_off[e0 + u] = v[u];
+        }
+        survivors += total;
     }
 #pragma unroll
-    for (int c = 0; c < 3; ++c) {
-#pragma unroll
-        for (int d = KN_WAVE / 2; d > 0; d >>= 1) v[c] += __shfl_down(v[c], d, KN_WAVE);
-        if ((threadIdx.x & (KN_WAVE - 1)) == 0) red[c][threadIdx.x / KN_WAVE] = v[c];
+    for (int d = KN_WAVE / 2; d > 0; d >>= 1) {
+        ev += __shfl_down(ev, d, KN_WAVE);
+        bl += __shfl_down(bl, d, KN_WAVE);
+    }
+    if ((tid & (KN_WAVE - 1)) == 0) {
+        red[0][tid / KN_WAVE] = ev;
+        red[1][tid / KN_WAVE] = bl;
     }
     __syncthreads();
-    if (threadIdx.x < 3) {
-        unsigned long long t = 0ull;
+    if (tid == 0) {
 #pragma unroll
-        for (int w = 0; w < 256 / KN_WAVE; ++w) t += red[threadIdx.x][w];
-        if (threadIdx.x == 2) counters[2] = t; else counters[threadIdx.x] += t;
-    }
-    __syncthreads();
-    // exclusive prefix sums of the survivors per 16-row group: the next wave's march compacts the list with them.
-    // Global memory is read and written with consecutive threads on consecutive entries; the contiguous 32 entries
-    // that a thread scans come through LDS (index + index / 32 keeps both access patterns free of bank conflicts).
-    if (counters[2] != 0) { // (uniform) no survivors: no further wave, nothing to compact
-        constexpr int PER = 32, ROUND = 256 * PER;
-        __shared__ int32_t tr[ROUND + ROUND / 32];
-        __shared__ int32_t scan_lds[256 / KN_WAVE];
-        const int32_t *surv = surv16;
-        const int tid = threadIdx.x;
-        int32_t carry = 0;
-        for (int32_t b0 = 0; b0 < n_blocks; b0 += ROUND) {
-            int32_t v[PER];
-#pragma unroll
-            for (int u = 0; u < PER; ++u) v[u] = surv[min(b0 + u * 256 + tid, n_blocks - 1)]; // loads issued together
-#pragma unroll
-            for (int u = 0; u < PER; ++u) {
-                const int e = u * 256 + tid;
-                tr[e + (e >> 5)] = b0 + e < n_blocks ? v[u] : 0;
-            }
-            __syncthreads();
-            int32_t sum = 0;
-#pragma unroll
-            for (int u = 0; u < PER; ++u) {
-                v[u] = tr[PER * tid + u + tid];
-                sum += v[u];
-            }
-            int32_t total;
-            int32_t off = carry + kn_block_exclusive_scan(sum, scan_lds, total);
-#pragma unroll
-            for (int u = 0; u < PER; ++u) {
-                tr[PER * tid + u + tid] = off;
-                off += v[u];
-            }
-            carry += total;
-            __syncthreads();
-#pragma unroll
-            for (int u = 0; u < PER; ++u) {
-                const int e = u * 256 + tid;
-                if (b0 + e < n_blocks) blk_off[b0 + e] = tr[e + (e >> 5)];
-            }
-            __syncthreads();
+        for (int w = 0; w < T / KN_WAVE; ++w) {
+            tot_eval += red[0][w];
+            tot_blend += red[1][w];
         }
-    }
-    if (threadIdx.x == 0) {
-        counters[3] += (unsigned long long)ctl[0] * (unsigned long long)ctl[1];
-        counters[4] += ctl[0] > 0 ? 1ull : 0ull;
+        tot_slots += (unsigned long long)rows * (unsigned long long)slots_per_row;
+        tot_waves += rows > 0 ? 1ull : 0ull;
+        counters[0] = tot_eval;
+        counters[1] = tot_blend;
+        counters[2] = (unsigned long long)survivors;
+        counters[3] = tot_slots;
+        counters[4] = tot_waves;
         // the next wave: the survivors (the live list is compacted in between), schedule value grown
-        const int64_t grown = (int64_t)ctl[2] * sched.growth;
-        set_wave(ctl_next, (int32_t)counters[2], (int32_t)(grown < sched.K ? grown : sched.K), sched);
+        const int64_t grown = (int64_t)s_sched * sched.growth;
+        set_wave(ctl_next, survivors, (int32_t)(grown < sched.K ? grown : sched.K), sched);
         // running totals ride along so that the host never has to read the counters back
         if (mailbox) {
-            __hip_atomic_store(&mailbox[2], counters[0], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
-            __hip_atomic_store(&mailbox[3], counters[1], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
-            __hip_atomic_store(&mailbox[4], counters[3], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
-            __hip_atomic_store(&mailbox[5], counters[4], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+            __hip_atomic_store(&mailbox[2], tot_eval, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+            __hip_atomic_store(&mailbox[3], tot_blend, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+            __hip_atomic_store(&mailbox[4], tot_slots, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+            __hip_atomic_store(&mailbox[5], tot_waves, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
         }
-        post_mailbox(mailbox, seq, counters[2]);
+        post_mailbox(mailbox, seq, (unsigned long long)survivors);
     }
 }
 
@@ -1160,7 +1164,7 @@ extern "C" int kn_render(const kn_scene *sc, void *stream, const float *rays_o, 
                                fused_hist ? (int32_t)n_hist : 0, wave_no == 0 ? 1 : 0);
         KN_CHECK_LAUNCH();
         seq = next_seq();
-        hipLaunchKernelGGL(k_sum_partials, dim3(1), dim3(256), 0, st, w.partials, cblocks, w.surv16, groups, w.counters, ctl,
+        hipLaunchKernelGGL(k_sum_partials, dim3(1), dim3(1024), 0, st, w.partials, cblocks, w.surv16, groups, w.counters, ctl,
                            ctl_next, sched, w.blk_off, mb_dev, seq);
         KN_CHECK_LAUNCH();
         tm.mark(KN_ST_BLEND);
