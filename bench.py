@@ -205,7 +205,7 @@ def main():
                     help="also run one plain 1 GiB device copy (reference point for FETCH_SIZE / WRITE_SIZE counters)")
     a = ap.parse_args()
     if a.gpus != 1:
-        print("bench.py: this build runs on one GPU only (rays would shard across GPUs; see DESIGN.md); use --gpus 1",
+        print("bench.py: this build runs on one GPU only (the path would shard by rays, every GPU holding the whole scene); use --gpus 1",
               file=sys.stderr)
         sys.exit(2)
 
