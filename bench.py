@@ -87,9 +87,17 @@ def cpu_baseline(cfg_fn, poses, budget_s=12.0):
         t_total += time.perf_counter() - t0
         samples += int(n_eval.sum())
         frames += 1
+    # the one-thread build (the oracle as defined) on every 4th ray of the first pose: a few seconds
+    one = OracleScene(s["res"], s["aabb_min"], s["aabb_max"], s["hidden"], s["weights"], s["occupancy"], threads=False)
+    c = cfg_fn(poses[0])
+    t0 = time.perf_counter()
+    _, n1, _, _ = one.render(c["rays_o"][::4], c["rays_d"][::4], c["t_near"], c["step"], c["K"], c["term_eps"], c["bg"])
+    t_one = time.perf_counter() - t0
     return {"value": samples / t_total, "unit": "samples/s", "cores": orc.num_threads(), "kind": "oracle",
             "sample": "%d whole 800x800 frame(s) of the same scene (%d blended samples, %.1f s)" % (frames, samples, t_total),
-            "frames_per_sec": frames / t_total}
+            "frames_per_sec": frames / t_total,
+            "one_thread": {"value": int(n1.sum()) / t_one, "unit": "samples/s", "cores": 1,
+                           "sample": "every 4th ray of one frame (%d blended samples, %.1f s)" % (int(n1.sum()), t_one)}}
 
 
 def isolated_mlp(kn, torch, wdtype, iters=10):
