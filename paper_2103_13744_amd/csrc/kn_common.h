@@ -183,11 +183,13 @@ int kn_bucket_run(hipStream_t st, int32_t *keys, int64_t M, const int32_t *M_dev
 // out->perm lists slot numbers group by group, in no particular order inside a group or between groups;
 // out->counts / out->offsets are not produced.
 //
-// `hist` (N ints) must be zero before the wave's histogram is accumulated and `cursor` (the N ints behind
-// it) before kn_group_run.  Where kn_group_fused(N) holds (small grids) the caller may accumulate the
-// histogram itself (hist_ready) and has to clear both arrays after the run; otherwise kn_group_run counts
-// the keys itself and leaves the histogram zero.
+// `hist` (N ints) holds the wave's histogram, accumulated by the caller (the marching kernel) on a zeroed array;
+// `cursor` are the N ints behind it.  Where kn_group_fused(N) holds (small grids: the fill pass derives the
+// offsets itself) `cursor` must be zero before the run and the caller clears both arrays afterwards; otherwise
+// kn_group_run leaves the histogram zero and overwrites the cursors.  kn_group_hash_slots(): size of the LDS hash
+// table (a power of two) that kernels use for per-workgroup counters where a counter per network does not fit.
 bool kn_group_fused(int32_t N);
+int32_t kn_group_hash_slots();
 struct KnGroupWs {
     int32_t *hist, *cursor, *n_tiles, *perm;
     KnTile *tiles;
@@ -196,7 +198,7 @@ int64_t kn_group_ws_bytes(int64_t slots, int32_t N);
 void kn_group_carve(KnCarver &ws, int64_t slots, int32_t N, KnGroupWs *w);
 // ctl (device): ctl[0] = number of rows, ctl[1] = S; max_rows: host-side upper bound of ctl[0] (sizes the grid).
 int kn_group_run(hipStream_t st, const int32_t *row_keys, const int32_t *cnt, const int32_t *ctl, int64_t max_rows,
-                 int32_t N, int32_t tile_len, const KnGroupWs &w, bool hist_ready, KnBucketOut *out);
+                 int32_t N, int32_t tile_len, const KnGroupWs &w, KnBucketOut *out);
 
 // The scratch counters (to be zero before the sort) that kn_bucket_run will carve from `ws` when it
 // is called with a carver in this same state, so that a caller's own kernel can clear them.

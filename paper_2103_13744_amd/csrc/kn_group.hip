@@ -5,8 +5,7 @@
 // not depend on where it sits inside its group, nor on the order of the groups.  Samples of neighbouring
 // rays fall into few cells, so instead of sorting the keys every workgroup counts the keys of a contiguous
 // range of rows in LDS and touches global memory only for the bins it met:
-//   histogram   per-network sample counts of the wave.  Small grids: accumulated by the marching kernel
-//               itself; otherwise by k_group_pass<0>.
+//   histogram   per-network sample counts of the wave, accumulated by the marching kernel itself.
 //   offsets     exclusive prefix sums of the histogram and the tile list.  Small grids: every workgroup of
 //               the fill pass derives the offsets it needs from the histogram, the first few also write the
 //               tiles; otherwise k_group_offsets (one workgroup) and k_group_tiles (one thread per group).
@@ -42,11 +41,10 @@ __device__ __forceinline__ void write_tiles(KnTile *__restrict__ tiles, int32_t 
     }
 }
 
-// MODE 0: add this workgroup's key counts to `global` (the histogram).
-// MODE 1: `global` holds each group's absolute fill cursor; reserve and fill this workgroup's ranges of `perm`.
-//         Modes 0 and 1 serve large grids: a counter per network would not fit in LDS, and neighbouring rays meet few
-//         networks, so the counters live in an LDS hash table (bins_cap slots, linear probing) keyed by network; a
-//         bin that finds no slot within GROUP_HASH_PROBES is counted / reserved through global memory run by run.
+// MODE 1: (large grids) `global` holds each group's absolute fill cursor; reserve and fill this workgroup's ranges of
+//         `perm`.  A counter per network would not fit in LDS, and neighbouring rays meet few networks, so the
+//         counters live in an LDS hash table (bins_cap slots, linear probing) keyed by network; a bin that finds no
+//         slot within GROUP_HASH_PROBES is reserved through global memory run by run.
 // MODE 2: (small grids) bins_cap = N direct counters; `hist` holds the finished histogram and `global` zeroed fill counters:
 //         derive the group offsets here (groups are laid out in the order bin % 256, bin / 256), reserve and
 //         fill; the first N / 256 workgroups also write the tile list.
@@ -173,25 +171,21 @@ __global__ void __launch_bounds__(GROUP_THREADS)
             sweep(0, N, first_rows, [&](int32_t k, int64_t, int32_t len) {
                 const int32_t sl = slot_of(k);
                 if (sl >= 0) atomicAdd(&hcnt[sl], len);
-                else if (MODE == 0) atomicAdd(&global[k], len);
             });
         __syncthreads();
         for (int32_t q = tid; q < bins_cap; q += GROUP_THREADS) {
             const int32_t k = hkeys[q], c = hcnt[q];
             if (k >= 0 && c > 0) {
-                const int32_t before = atomicAdd(&global[k], c);
-                if (MODE == 1) hcnt[q] = before; // first position of this workgroup's range inside the group
+                hcnt[q] = atomicAdd(&global[k], c); // first position of this workgroup's range inside the group
             }
         }
-        if constexpr (MODE == 1) {
-            __syncthreads();
-            if (nr > 0)
-                sweep(0, N, fetch_rows(0), [&](int32_t k, int64_t slot, int32_t len) {
-                    const int32_t sl = slot_of(k);
-                    const int32_t pos = sl >= 0 ? atomicAdd(&hcnt[sl], len) : atomicAdd(&global[k], len);
-                    for (int32_t t = 0; t < len; ++t) perm[pos + t] = (int32_t)slot + t;
-                });
-        }
+        __syncthreads();
+        if (nr > 0)
+            sweep(0, N, fetch_rows(0), [&](int32_t k, int64_t slot, int32_t len) {
+                const int32_t sl = slot_of(k);
+                const int32_t pos = sl >= 0 ? atomicAdd(&hcnt[sl], len) : atomicAdd(&global[k], len);
+                for (int32_t t = 0; t < len; ++t) perm[pos + t] = (int32_t)slot + t;
+            });
     } else {
     for (int32_t w0 = 0; w0 < N; w0 += bins_cap) { // (a single window: bins_cap = N)
         const int32_t nb = min(bins_cap, N - w0);
@@ -376,7 +370,7 @@ __global__ void __launch_bounds__(GROUP_THREADS)
 
 // KN_GROUP_HASH_SLOTS / KN_GROUP_FUSED_MAX: test knobs (read once) that shrink the LDS hash table and the
 // fused-scan limit, so that small scenes reach the code paths of large network grids, table overflow included
-static int32_t group_hash_slots()
+int32_t kn_group_hash_slots()
 {
     static int32_t v = 0;
     if (!v) {
@@ -417,30 +411,23 @@ int64_t kn_group_ws_bytes(int64_t slots, int32_t N)
 void kn_group_carve(KnCarver &ws, int64_t slots, int32_t N, KnGroupWs *w) { carve_group(ws, slots, N, *w); }
 
 int kn_group_run(hipStream_t st, const int32_t *row_keys, const int32_t *cnt, const int32_t *ctl, int64_t max_rows,
-                 int32_t N, int32_t tile_len, const KnGroupWs &w, bool hist_ready, KnBucketOut *out)
+                 int32_t N, int32_t tile_len, const KnGroupWs &w, KnBucketOut *out)
 {
     if (!ctl || max_rows < 0 || max_rows > 0x7fffffffLL || N < 1 || tile_len < 64) return KN_E_INVALID_ARG;
     if (!w.hist || !w.cursor || !w.n_tiles || !w.perm || !w.tiles) return KN_E_WORKSPACE;
     const bool fused = kn_group_fused(N);
-    if (hist_ready && !fused) return KN_E_INVALID_ARG;
-    const int32_t bins_cap = fused ? N : group_hash_slots(); // direct counters, or hash slots
+    const int32_t bins_cap = fused ? N : kn_group_hash_slots(); // direct counters, or hash slots
     int64_t blocks = kn_div_up(max_rows > 0 ? max_rows : 1, 16);
     if (blocks > 1024) blocks = 1024;
     const size_t lds_bytes = sizeof(int32_t) * (size_t)bins_cap * 2;
     static bool configured = false; // the kernels may need more dynamic LDS than the default limit
     if (!configured) {
         const int most = (int)(sizeof(int32_t) * 2 * GROUP_FUSED_MAX_BINS);
-        KN_HIP(hipFuncSetAttribute((const void *)k_group_pass<0>, hipFuncAttributeMaxDynamicSharedMemorySize, most));
         KN_HIP(hipFuncSetAttribute((const void *)k_group_pass<1>, hipFuncAttributeMaxDynamicSharedMemorySize, most));
         KN_HIP(hipFuncSetAttribute((const void *)k_group_pass<2>, hipFuncAttributeMaxDynamicSharedMemorySize, most));
         configured = true;
     }
     const dim3 grid((unsigned)blocks), block(GROUP_THREADS);
-    if (!hist_ready) { // no rows: the kernels find no samples and leave empty outputs
-        hipLaunchKernelGGL(k_group_pass<0>, grid, block, lds_bytes, st, row_keys, cnt, ctl, N, bins_cap, w.hist,
-                           (int32_t *)nullptr, (const int32_t *)nullptr, tile_len, (KnTile *)nullptr, (int32_t *)nullptr);
-        KN_CHECK_LAUNCH();
-    }
     if (fused) {
         hipLaunchKernelGGL(k_group_pass<2>, grid, block, lds_bytes, st, row_keys, cnt, ctl, N, bins_cap, w.cursor, w.perm,
                            (const int32_t *)w.hist, tile_len, w.tiles, w.n_tiles);

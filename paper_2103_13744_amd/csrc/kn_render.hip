@@ -435,8 +435,9 @@ __global__ void __launch_bounds__(RAY_BLOCK)
 }
 
 // MARCH_G lanes per live ray: collect up to S kept samples into row i of the wave's row buffers.
-// With `hist` the workgroup also counts its samples per network in LDS (n_bins ints of dynamic LDS) and adds
-// the bins it touched to the global histogram that the grouping of this wave starts from.
+// With `hist` the workgroup also counts its samples per network in LDS (dynamic LDS: n_bins counters, or a hash table
+// of 2 * hash_slots ints where a counter per network does not fit) and adds what it counted to the global histogram
+// that the grouping of this wave starts from.
 //
 // From the second wave on (`blk_off` given) the kernel also compacts the live list while it reads it: it runs over
 // the rows of the previous wave's list (`old_ctl`), the survivors among the 16 rows of a workgroup get the new row
@@ -447,10 +448,14 @@ __global__ void __launch_bounds__(256)
     k_march_wave(MarchParams p, const float *__restrict__ rays_o, const float *__restrict__ rays_d,
                  const int32_t *__restrict__ live, const int32_t *__restrict__ alive, const int32_t *__restrict__ ctl,
                  int32_t kbits, RayState s, int32_t *__restrict__ row_keys, uint32_t *__restrict__ row_rec,
-                 int32_t *__restrict__ cnt, int32_t *__restrict__ hist, int32_t n_bins, const int32_t *__restrict__ old_ctl,
-                 const int32_t *__restrict__ blk_off, int32_t *__restrict__ live_out, int32_t *__restrict__ alive_out)
+                 int32_t *__restrict__ cnt, int32_t *__restrict__ hist, int32_t n_bins, int32_t hash_slots,
+                 const int32_t *__restrict__ old_ctl, const int32_t *__restrict__ blk_off, int32_t *__restrict__ live_out,
+                 int32_t *__restrict__ alive_out)
 {
-    extern __shared__ int32_t bins[]; // [n_bins] when hist is given
+    // per-network sample counters of the workgroup: one per network (hash_slots = 0: small grids), else a hash
+    // table keyed by network (keys [hash_slots], then counts [hash_slots]; a power of two)
+    extern __shared__ int32_t bins[];
+    const int32_t n_lds = hash_slots ? 2 * hash_slots : n_bins;
     __shared__ int32_t flags[256 / MARCH_G];
     const int32_t n_in = blk_off ? old_ctl[0] : ctl[0]; // rows of the list that is read
     const int32_t S = ctl[1];
@@ -473,9 +478,27 @@ __global__ void __launch_bounds__(256)
         i = blk_off[blockIdx.x] + rank;
     }
     if (hist) {
-        for (int32_t b = threadIdx.x; b < n_bins; b += 256) bins[b] = 0;
+        for (int32_t b = threadIdx.x; b < n_lds; b += 256) bins[b] = (hash_slots && b < hash_slots) ? -1 : 0;
         __syncthreads();
     }
+    // one more sample of network `cell`
+    auto count = [&](int32_t cell) {
+        if (!hash_slots) {
+            atomicAdd(&bins[cell], 1);
+            return;
+        }
+        uint32_t h = ((uint32_t)cell * 2654435761u) >> (__builtin_clz((uint32_t)hash_slots) + 1);
+        for (int probe = 0; probe < 8; ++probe) {
+            int32_t old = bins[h];
+            if (old == -1) old = atomicCAS(&bins[h], -1, cell);
+            if (old == -1 || old == cell) {
+                atomicAdd(&bins[hash_slots + h], 1);
+                return;
+            }
+            h = (h + 1u) & (uint32_t)(hash_slots - 1);
+        }
+        atomicAdd(&hist[cell], 1); // no slot nearby: straight to the global histogram
+    };
     if (!lives) {
         // without compaction retired rows stay in the list: they get no samples
         if (!blk_off && i_in < n_in && gl == 0) cnt[i_in] = 0;
@@ -495,7 +518,7 @@ __global__ void __launch_bounds__(256)
         const int32_t n = march_group(p, gn, go, o, d, k, k_hi, S, gl, [&](int j, int32_t kk, int32_t cell) {
             kr[j] = cell;
             rr[j] = ((uint32_t)r << kbits) | (uint32_t)kk;
-            if (hist) atomicAdd(&bins[cell], 1);
+            if (hist) count(cell);
         });
         if (gl == 0) {
             s.k_next[r] = k;
@@ -504,9 +527,10 @@ __global__ void __launch_bounds__(256)
     }
     if (hist) { // the few bins this workgroup met go to the global histogram
         __syncthreads();
-        for (int32_t b = threadIdx.x; b < n_bins; b += 256) {
-            const int32_t c = bins[b];
-            if (c) atomicAdd(&hist[b], c);
+        const int32_t n_slots = hash_slots ? hash_slots : n_bins;
+        for (int32_t b = threadIdx.x; b < n_slots; b += 256) {
+            const int32_t c = bins[hash_slots + b];
+            if (c) atomicAdd(&hist[hash_slots ? bins[b] : b], c);
         }
     }
 }
@@ -1090,6 +1114,9 @@ extern "C" int kn_render(const kn_scene *sc, void *stream, const float *rays_o, 
     const unsigned rblocks = (unsigned)kn_div_up(R, RAY_BLOCK);
     const int64_t n_hist = 2 * (int64_t)sc->N; // histogram and fill cursors of the sample grouping
     const bool fused_hist = kn_group_fused(sc->N);
+    // the marching kernel counts the samples per network: a counter per network in LDS on small grids, a hash table
+    // of the networks a workgroup meets on large ones
+    const int32_t march_hash = fused_hist ? 0 : kn_group_hash_slots();
     KnStageTimer tm(st);
     tm.begin();
     KnMailbox *mb = mailbox_for(const_cast<kn_scene *>(sc), st); // the mailboxes are the only mutable scene state
@@ -1131,8 +1158,8 @@ extern "C" int kn_render(const kn_scene *sc, void *stream, const float *rays_o, 
     auto march = [&](int64_t rows_in, bool compacting) -> int {
         const int32_t *ctl = w.ctl + 4 * (wave_no & 1), *old_ctl = w.ctl + 4 * ((wave_no + 1) & 1);
         hipLaunchKernelGGL(k_march_wave, dim3((unsigned)kn_div_up(rows_in * MARCH_G, 256)), dim3(256),
-                           fused_hist ? sizeof(int32_t) * (size_t)sc->N : 0, st, p, rays_o, rays_d, live, alive, ctl, kbits, rs,
-                           w.row_keys, w.row_rec, w.cnt, fused_hist ? gw.hist : (int32_t *)nullptr, sc->N, old_ctl,
+                           sizeof(int32_t) * (size_t)(march_hash ? 2 * march_hash : sc->N), st, p, rays_o, rays_d, live, alive,
+                           ctl, kbits, rs, w.row_keys, w.row_rec, w.cnt, gw.hist, sc->N, march_hash, old_ctl,
                            compacting ? w.blk_off : (const int32_t *)nullptr, live_next, alive_next);
         KN_CHECK_LAUNCH();
         if (compacting) {
@@ -1146,7 +1173,7 @@ extern "C" int kn_render(const kn_scene *sc, void *stream, const float *rays_o, 
     auto rest_of_wave = [&](int64_t rows_cap) -> int {
         int32_t *ctl = w.ctl + 4 * (wave_no & 1), *ctl_next = w.ctl + 4 * ((wave_no + 1) & 1);
         KnBucketOut bo;
-        KN_TRY(kn_group_run(st, w.row_keys, w.cnt, ctl, rows_cap, sc->N, tile_len, gw, fused_hist, &bo));
+        KN_TRY(kn_group_run(st, w.row_keys, w.cnt, ctl, rows_cap, sc->N, tile_len, gw, &bo));
         tm.mark(KN_ST_BUCKET);
         KN_TRY(kn_mlp_launch(sc, st, src, bo, budget, nullptr, nullptr));
         tm.mark(KN_ST_MLP);
