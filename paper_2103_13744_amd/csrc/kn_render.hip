@@ -444,6 +444,8 @@ __global__ void __launch_bounds__(RAY_BLOCK)
 // numbers blk_off[workgroup] + rank (ascending, so the order of the list is kept), and the new list is written to
 // live_out / alive_out.  blk_off comes from k_sum_partials (prefix sums of the survivor counts that the blend of
 // the same 16-row groups left).
+// HASH: the per-network counters are a hash table (large grids), else one counter per network.
+template <bool HASH>
 __global__ void __launch_bounds__(256)
     k_march_wave(MarchParams p, const float *__restrict__ rays_o, const float *__restrict__ rays_d,
                  const int32_t *__restrict__ live, const int32_t *__restrict__ alive, const int32_t *__restrict__ ctl,
@@ -455,7 +457,7 @@ __global__ void __launch_bounds__(256)
     // per-network sample counters of the workgroup: one per network (hash_slots = 0: small grids), else a hash
     // table keyed by network (keys [hash_slots], then counts [hash_slots]; a power of two)
     extern __shared__ int32_t bins[];
-    const int32_t n_lds = hash_slots ? 2 * hash_slots : n_bins;
+    const int32_t n_lds = HASH ? 2 * hash_slots : n_bins;
     __shared__ int32_t flags[256 / MARCH_G];
     const int32_t n_in = blk_off ? old_ctl[0] : ctl[0]; // rows of the list that is read
     const int32_t S = ctl[1];
@@ -478,12 +480,12 @@ __global__ void __launch_bounds__(256)
         i = blk_off[blockIdx.x] + rank;
     }
     if (hist) {
-        for (int32_t b = threadIdx.x; b < n_lds; b += 256) bins[b] = (hash_slots && b < hash_slots) ? -1 : 0;
+        for (int32_t b = threadIdx.x; b < n_lds; b += 256) bins[b] = (HASH && b < hash_slots) ? -1 : 0;
         __syncthreads();
     }
     // one more sample of network `cell`
     auto count = [&](int32_t cell) {
-        if (!hash_slots) {
+        if constexpr (!HASH) {
             atomicAdd(&bins[cell], 1);
             return;
         }
@@ -527,10 +529,10 @@ __global__ void __launch_bounds__(256)
     }
     if (hist) { // the few bins this workgroup met go to the global histogram
         __syncthreads();
-        const int32_t n_slots = hash_slots ? hash_slots : n_bins;
+        const int32_t n_slots = HASH ? hash_slots : n_bins;
         for (int32_t b = threadIdx.x; b < n_slots; b += 256) {
-            const int32_t c = bins[hash_slots + b];
-            if (c) atomicAdd(&hist[hash_slots ? bins[b] : b], c);
+            const int32_t c = bins[(HASH ? hash_slots : 0) + b];
+            if (c) atomicAdd(&hist[HASH ? bins[b] : b], c);
         }
     }
 }
@@ -1157,7 +1159,7 @@ extern "C" int kn_render(const kn_scene *sc, void *stream, const float *rays_o, 
     // wave's list, which the kernel compacts on the way (see k_march_wave); the new list is then the current one.
     auto march = [&](int64_t rows_in, bool compacting) -> int {
         const int32_t *ctl = w.ctl + 4 * (wave_no & 1), *old_ctl = w.ctl + 4 * ((wave_no + 1) & 1);
-        hipLaunchKernelGGL(k_march_wave, dim3((unsigned)kn_div_up(rows_in * MARCH_G, 256)), dim3(256),
+        hipLaunchKernelGGL(march_hash ? k_march_wave<true> : k_march_wave<false>, dim3((unsigned)kn_div_up(rows_in * MARCH_G, 256)), dim3(256),
                            sizeof(int32_t) * (size_t)(march_hash ? 2 * march_hash : sc->N), st, p, rays_o, rays_d, live, alive,
                            ctl, kbits, rs, w.row_keys, w.row_rec, w.cnt, gw.hist, sc->N, march_hash, old_ctl,
                            compacting ? w.blk_off : (const int32_t *)nullptr, live_next, alive_next);
