@@ -435,9 +435,9 @@ __global__ void __launch_bounds__(RAY_BLOCK)
 }
 
 // MARCH_G lanes per live ray: collect up to S kept samples into row i of the wave's row buffers.
-// With `hist` the workgroup also counts its samples per network in LDS (dynamic LDS: n_bins counters, or a hash table
-// of 2 * hash_slots ints where a counter per network does not fit) and adds what it counted to the global histogram
-// that the grouping of this wave starts from.
+// The workgroup also counts its samples per network in LDS (dynamic LDS: n_bins counters, or a hash table of
+// 2 * hash_slots ints where a counter per network does not fit) and adds what it counted to the global histogram
+// `hist` that the grouping of this wave starts from.
 //
 // From the second wave on (`blk_off` given) the kernel also compacts the live list while it reads it: it runs over
 // the rows of the previous wave's list (`old_ctl`), the survivors among the 16 rows of a workgroup get the new row
@@ -479,10 +479,8 @@ __global__ void __launch_bounds__(256)
         if (any == 0) return; // (uniform) all 16 rays of the workgroup have retired
         i = blk_off[blockIdx.x] + rank;
     }
-    if (hist) {
-        for (int32_t b = threadIdx.x; b < n_lds; b += 256) bins[b] = (HASH && b < hash_slots) ? -1 : 0;
-        __syncthreads();
-    }
+    for (int32_t b = threadIdx.x; b < n_lds; b += 256) bins[b] = (HASH && b < hash_slots) ? -1 : 0;
+    __syncthreads();
     // one more sample of network `cell`
     auto count = [&](int32_t cell) {
         if constexpr (!HASH) {
@@ -520,20 +518,19 @@ __global__ void __launch_bounds__(256)
         const int32_t n = march_group(p, gn, go, o, d, k, k_hi, S, gl, [&](int j, int32_t kk, int32_t cell) {
             kr[j] = cell;
             rr[j] = ((uint32_t)r << kbits) | (uint32_t)kk;
-            if (hist) count(cell);
+            count(cell);
         });
         if (gl == 0) {
             s.k_next[r] = k;
             cnt[i] = n;
         }
     }
-    if (hist) { // the few bins this workgroup met go to the global histogram
-        __syncthreads();
-        const int32_t n_slots = HASH ? hash_slots : n_bins;
-        for (int32_t b = threadIdx.x; b < n_slots; b += 256) {
-            const int32_t c = bins[(HASH ? hash_slots : 0) + b];
-            if (c) atomicAdd(&hist[HASH ? bins[b] : b], c);
-        }
+    // the few bins this workgroup met go to the global histogram
+    __syncthreads();
+    const int32_t n_slots = HASH ? hash_slots : n_bins;
+    for (int32_t b = threadIdx.x; b < n_slots; b += 256) {
+        const int32_t c = bins[(HASH ? hash_slots : 0) + b];
+        if (c) atomicAdd(&hist[HASH ? bins[b] : b], c);
     }
 }
 
