@@ -499,6 +499,25 @@ def test_render_random_configurations_fp32():
         kn.set_render_params(0, 0, 0)
 
 
+def test_render_on_more_streams_than_mailboxes():
+    """A scene has eight host mailboxes, one per stream that renders on it; calls on further streams fall back to
+    waiting for the stream.  Same image on every stream."""
+    import torch
+    cfg = configs.config3(48, 48)
+    dev, _ = make_pair(cfg["scene"])
+    o, d = cuda(cfg["rays_o"]), cuda(cfg["rays_d"])
+    args = (cfg["t_near"], cfg["step"], cfg["K"], cfg["term_eps"], cfg["bg"])
+    ref = dev.render(o, d, *args).cpu().numpy()
+    for _ in range(11):
+        st = torch.cuda.Stream()
+        st.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(st):
+            img, stats = dev.render(o, d, *args, want_stats=True)
+        st.synchronize()
+        np.testing.assert_array_equal(img.cpu().numpy(), ref)
+        assert stats["waves"] >= 1 and stats["samples_blended"] > 0
+
+
 def test_render_edge_cases():
     import torch
     cfg = configs.config3(16, 16)
