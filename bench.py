@@ -73,31 +73,34 @@ def frames_in_flight(torch, scene, rays, args, R, steps, n, blended_per_frame):
             "samples_per_sec": blended_per_frame * frames / best}
 
 
-def cpu_baseline(cfg_fn, poses, budget_s=12.0):
-    """Time the oracle (threaded build, all host cores) on whole frames of the same workload."""
+def cpu_baseline(cfg, rays_fn, poses, budget_s=12.0):
+    """Time the oracle (threaded build, all host cores) on whole frames of the same workload.  cfg: the workload's
+    configuration (scene, step, K, ...); rays_fn(azimuth) -> (rays_o, rays_d) as numpy arrays."""
     from oracle import OracleScene
-    cfg = cfg_fn(poses[0])
     s = cfg["scene"]
+    frame = (cfg["t_near"], cfg["step"], cfg["K"], cfg["term_eps"], cfg["bg"])
     orc = OracleScene(s["res"], s["aabb_min"], s["aabb_max"], s["hidden"], s["weights"], s["occupancy"], threads=True)
     samples, t_total, frames = 0, 0.0, 0
     while t_total < budget_s and frames < 64: # whole frames, cycling through the poses, until the time budget is used
-        c = cfg_fn(poses[frames % len(poses)])
+        o, d = rays_fn(poses[frames % len(poses)])
         t0 = time.perf_counter()
-        _, n_eval, _, _ = orc.render(c["rays_o"], c["rays_d"], c["t_near"], c["step"], c["K"], c["term_eps"], c["bg"])
+        _, n_eval, _, _ = orc.render(o, d, *frame)
         t_total += time.perf_counter() - t0
         samples += int(n_eval.sum())
         frames += 1
-    # the one-thread build (the oracle as defined) on every 4th ray of the first pose: a few seconds
+    # the one-thread build (the oracle as defined) on a sample of the rays of the first pose: a few seconds
     one = OracleScene(s["res"], s["aabb_min"], s["aabb_max"], s["hidden"], s["weights"], s["occupancy"], threads=False)
-    c = cfg_fn(poses[0])
+    o, d = rays_fn(poses[0])
+    every = max(4, len(o) // 80000)
     t0 = time.perf_counter()
-    _, n1, _, _ = one.render(c["rays_o"][::4], c["rays_d"][::4], c["t_near"], c["step"], c["K"], c["term_eps"], c["bg"])
+    _, n1, _, _ = one.render(o[::every], d[::every], *frame)
     t_one = time.perf_counter() - t0
     return {"value": samples / t_total, "unit": "samples/s", "cores": orc.num_threads(), "kind": "oracle",
-            "sample": "%d whole 800x800 frame(s) of the same scene (%d blended samples, %.1f s)" % (frames, samples, t_total),
+            "sample": "%d whole %dx%d frame(s) of the same scene (%d blended samples, %.1f s)" %
+                      (frames, cfg["width"], cfg["height"], samples, t_total),
             "frames_per_sec": frames / t_total,
             "one_thread": {"value": int(n1.sum()) / t_one, "unit": "samples/s", "cores": 1,
-                           "sample": "every 4th ray of one frame (%d blended samples, %.1f s)" % (int(n1.sum()), t_one)}}
+                           "sample": "every %dth ray of one frame (%d blended samples, %.1f s)" % (every, int(n1.sum()), t_one)}}
 
 
 def isolated_mlp(kn, torch, wdtype, iters=10):
@@ -204,8 +207,11 @@ def main():
     ap.add_argument("--steps", type=int, default=40)
     ap.add_argument("--warmup", type=int, default=8)
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--wdtype", default="f16")
-    ap.add_argument("--size", type=int, default=800)
+    ap.add_argument("--workload", default="cfg3", choices=["cfg3", "cfg5"],
+                    help="cfg3: the 800x800 frame the headline metric is quoted on (default); cfg5: 1920x1080, 32^3 networks of "
+                         "width 64, 512^3 occupancy grid, K = 1024 (the largest configuration; bf16 unless --wdtype is given)")
+    ap.add_argument("--wdtype", default=None)
+    ap.add_argument("--size", type=int, default=800, help="cfg3: frame width and height")
     ap.add_argument("--wave", default="", help="first_wave_samples,slots_per_ray,growth (experiment knob)")
     ap.add_argument("--in-flight", type=int, default=3,
                     help="frames in flight (one stream and host thread each) of the supplementary throughput pass; 0 = skip")
@@ -228,17 +234,27 @@ def main():
     if a.wave:
         kn.set_render_params(*[int(v) for v in a.wave.split(",")])
     poses = [45.0 * i for i in range(8)]
-    cfg_fn = lambda az: configs.config3(a.size, a.size, azimuth=az, wdtype=a.wdtype)
-    cfg = cfg_fn(poses[0])
+    if a.wdtype is None:
+        a.wdtype = "f16" if a.workload == "cfg3" else "bf16"
+    if a.workload == "cfg3":
+        cfg = configs.config3(a.size, a.size, azimuth=poses[0], wdtype=a.wdtype)
+        workload = ("cfg3: %dx%d render, 16^3 networks (H=32), 256^3 occupancy grid (8%% occupied), step diag/512, eps 0.01, "
+                    "8 camera poses" % (a.size, a.size))
+    else:
+        cfg = configs.config5(azimuth=poses[0], wdtype=a.wdtype)
+        workload = ("cfg5: 1920x1080 render, 32^3 networks (H=64), 512^3 occupancy grid (5% occupied), step diag/1024, "
+                    "eps 0.01, 8 camera poses")
+    width, height = cfg["width"], cfg["height"]
+    rays_fn = lambda az: configs.camera_rays(width, height, 40.0, 4.0, az, 30.0)
     sc = cfg["scene"]
     dt = {"f32": torch.float32, "f16": torch.float16, "bf16": torch.bfloat16}[a.wdtype]
     scene = kn.Scene(sc["res"], sc["aabb_min"], sc["aabb_max"], sc["hidden"], torch.from_numpy(sc["weights"]).to(dt).cuda(),
                      torch.from_numpy(sc["occupancy"]).cuda())
     rays = []
     for az in poses:
-        o, d = configs.camera_rays(a.size, a.size, 40.0, 4.0, az, 30.0)
+        o, d = rays_fn(az)
         rays.append((torch.from_numpy(o).cuda(), torch.from_numpy(d).cuda()))
-    R = a.size * a.size
+    R = width * height
     out = torch.empty((R, 3), dtype=torch.float32, device="cuda")
     args = (cfg["t_near"], cfg["step"], cfg["K"], cfg["term_eps"], cfg["bg"])
 
@@ -280,7 +296,8 @@ def main():
     waves = sum(stats[i % 8]["waves"] for i in range(a.steps))
     launches = waves  # one launch of each per-wave kernel per wave
     H = sc["hidden"]
-    traffic = read_traffic()
+    # (the committed counter summary is of the default workload)
+    traffic = read_traffic() if (a.workload == "cfg3" and a.wdtype == "f16" and a.size == 800) else {}
 
     def roof_mlp(p):
         s_ = p["ms_mlp"] * 1e-3
@@ -328,8 +345,7 @@ def main():
         "value": blended / dt_s, "unit": "samples/s",
         "n_gpus": 1, "steps": a.steps, "warmup": a.warmup, "ms_per_step": dt_s * 1e3 / a.steps,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": a.wdtype, "data": "synthetic",
-        "config": {"workload": "cfg3: %dx%d render, 16^3 networks (H=32), 256^3 occupancy grid (8%% occupied), "
-                               "step diag/512, eps 0.01, 8 camera poses" % (a.size, a.size)},
+        "config": {"workload": workload},
         "frames_per_sec": a.steps / dt_s,
         "ms_per_step_without_events": dt_plain_s * 1e3 / a.steps,
         "samples_blended_per_frame": blended / a.steps, "samples_evaluated_per_frame": evaluated / a.steps,
@@ -348,13 +364,13 @@ def main():
         dst_buf.copy_(src_buf)
         torch.cuda.synchronize()
         del src_buf, dst_buf
-    if a.wdtype in ("f16", "bf16"):
+    if a.wdtype in ("f16", "bf16") and a.workload == "cfg3":
         res["occupancy_extraction"] = occupancy_extraction(kn, torch, scene, sc, sc["occupancy"].shape)
         del scene
         torch.cuda.empty_cache()
         res["isolated_mlp"] = isolated_mlp(kn, torch, a.wdtype)
     if not a.no_cpu_baseline:
-        res["cpu_baseline"] = cpu_baseline(cfg_fn, poses)
+        res["cpu_baseline"] = cpu_baseline(cfg, rays_fn, poses)
     print(json.dumps(res))
 
 
