@@ -287,61 +287,67 @@ __global__ void __launch_bounds__(GROUP_THREADS)
     }
 }
 
-// histogram -> group offsets (also the fill cursors) and tile positions.  One workgroup, a round of 4,096 bins at a
-// time: global memory is read and written with consecutive threads on consecutive bins, the four contiguous bins
-// that a thread scans come through LDS (index + index / 32 keeps both access patterns free of bank conflicts).
-// The histogram entries are replaced by the groups' first tile positions, totals[0] = tiles, totals[1] = samples;
-// k_group_tiles writes the tiles from that and clears the histogram for the next use.
+// histogram -> group offsets (also the fill cursors) and tile positions.  One workgroup; a thread scans 16 contiguous
+// bins (one 64-byte line, read and written as four 16-byte accesses), 16,384 bins per round.  The histogram entries
+// are replaced by the groups' first tile positions, totals[0] = tiles, totals[1] = samples; k_group_tiles writes the
+// tiles from that and clears the histogram for the next use.
 __global__ void __launch_bounds__(1024)
     k_group_offsets(int32_t *__restrict__ hist, int32_t N, int32_t tile_len, int32_t *__restrict__ cursor,
                     int32_t *__restrict__ totals)
 {
-    constexpr int T = 1024, PER = 4, ROUND = T * PER;
-    __shared__ int32_t tr_s[ROUND + ROUND / 32], tr_t[ROUND + ROUND / 32];
+    constexpr int T = 1024, PER = 16;
+    typedef int32_t i4 __attribute__((ext_vector_type(4)));
     __shared__ int32_t lds[T / KN_WAVE];
     const int tid = threadIdx.x;
     int32_t carry_s = 0, carry_t = 0;
-    for (int32_t b0 = 0; b0 < N; b0 += ROUND) {
+    for (int32_t b0 = 0; b0 < N; b0 += T * PER) {
+        const int32_t e0 = b0 + PER * tid;
+        // (16-byte accesses only where both arrays are 16-byte aligned: the cursors start N ints behind the histogram)
+        const bool full = e0 + PER <= N && (N & 3) == 0;
         int32_t c[PER];
+        if (full) {
 #pragma unroll
-        for (int u = 0; u < PER; ++u) c[u] = hist[min(b0 + u * T + tid, N - 1)]; // loads issued together
+            for (int u = 0; u < PER / 4; ++u) {
+                const i4 q = *(const i4 *)(hist + e0 + 4 * u);
+                c[4 * u] = q[0]; c[4 * u + 1] = q[1]; c[4 * u + 2] = q[2]; c[4 * u + 3] = q[3];
+            }
+        } else {
 #pragma unroll
-        for (int u = 0; u < PER; ++u) {
-            const int e = u * T + tid;
-            tr_s[e + (e >> 5)] = b0 + e < N ? c[u] : 0;
+            for (int u = 0; u < PER; ++u) c[u] = e0 + u < N ? hist[e0 + u] : 0;
         }
-        __syncthreads();
         int32_t sum_s = 0, sum_t = 0;
 #pragma unroll
         for (int u = 0; u < PER; ++u) {
-            const int e = PER * tid + u;
-            c[u] = tr_s[e + (e >> 5)];
             sum_s += c[u];
             sum_t += (c[u] + tile_len - 1) / tile_len;
         }
         int32_t tot_s, tot_t;
         int32_t off = carry_s + kn_block_exclusive_scan(sum_s, lds, tot_s);
         int32_t tpos = carry_t + kn_block_exclusive_scan(sum_t, lds, tot_t);
+        int32_t o[PER], t[PER];
 #pragma unroll
         for (int u = 0; u < PER; ++u) {
-            const int e = PER * tid + u;
-            tr_s[e + (e >> 5)] = off;
-            tr_t[e + (e >> 5)] = tpos;
+            o[u] = off;
+            t[u] = tpos;
             off += c[u];
             tpos += (c[u] + tile_len - 1) / tile_len;
         }
+        if (full) {
+#pragma unroll
+            for (int u = 0; u < PER / 4; ++u) {
+                *(i4 *)(cursor + e0 + 4 * u) = (i4){o[4 * u], o[4 * u + 1], o[4 * u + 2], o[4 * u + 3]};
+                *(i4 *)(hist + e0 + 4 * u) = (i4){t[4 * u], t[4 * u + 1], t[4 * u + 2], t[4 * u + 3]};
+            }
+        } else {
+#pragma unroll
+            for (int u = 0; u < PER; ++u)
+                if (e0 + u < N) {
+                    cursor[e0 + u] = o[u];
+                    hist[e0 + u] = t[u];
+                }
+        }
         carry_s += tot_s;
         carry_t += tot_t;
-        __syncthreads();
-#pragma unroll
-        for (int u = 0; u < PER; ++u) {
-            const int e = u * T + tid;
-            if (b0 + e < N) {
-                cursor[b0 + e] = tr_s[e + (e >> 5)];
-                hist[b0 + e] = tr_t[e + (e >> 5)];
-            }
-        }
-        __syncthreads();
     }
     if (tid == 0) {
         totals[0] = carry_t;

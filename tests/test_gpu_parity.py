@@ -417,6 +417,19 @@ def test_render_large_grid_code_paths(tmp_path):
         out.unlink()
 
 
+def test_render_network_grid_above_the_fused_grouping_limit():
+    """21^3 = 9,261 networks: more than the grouping keeps a counter each for in LDS (hash tables instead), and not a
+    multiple of four (the offset arrays then start at odd alignments)."""
+    occ = ks.blob_occupancy((42, 42, 42), 5, 0.3, 881)
+    sc = configs._scene((21, 21, 21), (-1, -1, -1), (1, 1, 1), 32, "f16", 882, sigma_scale=30.0, occ=occ)
+    o, d = ks.camera_rays(40, 30, 40.0, 4.0, 20.0, 30.0)
+    diag = 2.0 * math.sqrt(3.0)
+    cfg = dict(scene=sc, rays_o=o, rays_d=d, t_near=4.0 - math.sqrt(3.0), step=diag / 128, K=128, term_eps=0.01,
+               bg=(1.0, 1.0, 1.0), name="odd_large_grid_f16")
+    _, _, stats = render_check(cfg)
+    assert stats["samples_blended"] > 5000
+
+
 def test_render_calls_in_flight_on_one_scene():
     """Calls on different streams (own workspace and output each) may overlap on one scene: every stream gets its
     own host mailbox.  Each result must equal the one-at-a-time image of the same rays."""
