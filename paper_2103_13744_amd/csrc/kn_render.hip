@@ -182,6 +182,7 @@ __device__ __forceinline__ int32_t skip_lookup(const MarchParams &p, float x, fl
 __device__ __forceinline__ int32_t skip_to_content(const MarchParams &p, const GridFast &go, const float o[3],
                                                    const float d[3], int32_t k, int32_t k_hi)
 {
+    if (k >= k_hi) return k_hi; // the ray misses the content box: nothing to walk through
     const SkipJump sj(p, o, d);
     if (!sj.use) return k;
     while (k < k_hi) {
