@@ -536,12 +536,13 @@ __global__ void __launch_bounds__(256)
 }
 
 // Eq. 2-4 over this wave's samples, early termination, retiring of finished rays.  A wavefront owns 64 consecutive
-// rows.  Its lanes fetch the rows' next BLEND_CHUNK samples together (16 lanes per row and request, consecutive
-// addresses) and turn densities into alphas; the values go through LDS to the lane that owns the row, which runs
+// rows.  Its lanes fetch the rows' next BLEND_CHUNK samples together (BLEND_CHUNK lanes per row and request,
+// consecutive addresses) and turn densities into alphas; the values go through LDS to the lane that owns the row, which runs
 // the blend as the sequential recurrence of the definition: one lane per ray, the same operation order for every
 // wave cut.  (Blending with 16 lanes per ray, all of them stepping through the recurrence on broadcast values, cost
 // 16 times the instructions.)
-constexpr int BLEND_CHUNK = 16;
+// (16 samples per request: 70 KiB of LDS per workgroup, two wavefronts per SIMD, 3 us slower per frame; 4: too few loads in flight)
+constexpr int BLEND_CHUNK = 8;
 constexpr int BLEND_ROWS = 256; // rows per workgroup
 __global__ void __launch_bounds__(256)
     k_composite_wave(const int32_t *__restrict__ live, const int32_t *__restrict__ ctl, int32_t rows_cap,
@@ -574,7 +575,7 @@ __global__ void __launch_bounds__(256)
     }
     bool dead = false;
     int32_t blended = 0;
-    const int sub = lane / BLEND_CHUNK, jl = lane % BLEND_CHUNK; // loader role: row sub, sub + 4, ...; sample jl of the chunk
+    const int sub = lane / BLEND_CHUNK, jl = lane % BLEND_CHUNK; // loader role: rows sub, sub + 64 / BLEND_CHUNK, ...; sample jl of the chunk
     for (int32_t j0 = 0; __ballot(mine && !dead && j0 < n) != 0ull; j0 += BLEND_CHUNK) {
         // fetch: KN_WAVE / BLEND_CHUNK rows per request, all requests issued before the first use
         f4 v[BLEND_CHUNK];
@@ -1178,7 +1179,7 @@ extern "C" int kn_render(const kn_scene *sc, void *stream, const float *rays_o, 
         KN_TRY(kn_mlp_launch(sc, st, src, bo, budget, nullptr, nullptr));
         tm.mark(KN_ST_MLP);
         // many rays with few samples each: one lane per ray; few rays with many samples: 16 lanes per ray
-        const bool lane_per_ray = s_bound <= 4 * BLEND_CHUNK;
+        const bool lane_per_ray = s_bound <= 64;
         const int32_t groups = (int32_t)kn_div_up(rows_cap, MARCH_G);
         const int32_t cblocks = lane_per_ray ? (int32_t)kn_div_up(rows_cap, BLEND_ROWS) : groups;
         if (lane_per_ray)
