@@ -11,6 +11,9 @@
  *    caller buffers for the duration of a call (scene inputs: see kn_scene_create).
  *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls enqueue
  *    work on it and return without waiting unless stated otherwise.
+ *    Calls that neither wait nor read results back on the host (all but kn_scene_create /
+ *    kn_scene_destroy, kn_render and kn_profile_read) use only kernel launches on `stream` and may be
+ *    captured into a HIP graph, with profiling off.
  *  - Every function returns 0 (KN_OK) or a negative kn_status.  Arguments are validated on
  *    the host before anything is launched; sizes of 0 are valid and do nothing.
  *  - Positions and directions are fp32, row-major (n, 3).  Directions must have unit length:

@@ -237,6 +237,41 @@ def test_extract_occupancy_random_configurations_fp32():
         assert close.sum() <= 2 + 0.01 * close.size
 
 
+def test_eval_grouped_replays_from_a_hip_graph():
+    """kn_eval_grouped neither allocates nor waits on the host, so it can be captured into a graph: three replays on
+    fresh inputs, with eager calls in between, each equal to the eager result of the same inputs."""
+    import torch
+    sc = scene_dict((4, 4, 4), (0, 0, 0), (1, 1, 1), 32, "f16", 61)
+    dev, _ = make_pair(sc)
+    M = 20_000
+    pts, dirs = torch.empty((M, 3), device="cuda"), torch.empty((M, 3), device="cuda")
+    out = (torch.empty(M, device="cuda"), torch.empty((M, 3), device="cuda"))
+    batches = [(cuda(ks.uniform_points(M, 62 + i, lo=(-0.05,) * 3, hi=(1.05,) * 3)), cuda(ks.sphere_dirs(M, 72 + i)))
+               for i in range(3)]
+    pts.copy_(batches[0][0])
+    dirs.copy_(batches[0][1])
+    dev.eval_grouped(pts, dirs, out=out)                       # warm-up: workspace allocated, kernels loaded
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            dev.eval_grouped(pts, dirs, out=out)
+    torch.cuda.current_stream().wait_stream(side)
+    for p, d in batches:
+        want_s, want_c = [t.clone() for t in dev.eval_grouped(p, d)]      # eager, own output buffers
+        torch.cuda.synchronize()
+        pts.copy_(p)
+        dirs.copy_(d)
+        out[0].zero_()
+        out[1].zero_()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out[0], want_s) and torch.equal(out[1], want_c)
+        assert float(want_s.abs().sum()) > 0
+
+
 # ------------------------------------------------------------------ a1: marching
 def test_march_bit_exact_and_resumable():
     cfg = configs.config3(40, 40)
