@@ -68,10 +68,22 @@ __global__ void __launch_bounds__(GROUP_THREADS)
     const int32_t n_rows = ctl[0], S = ctl[1];
     int g_log2 = 0;
     while (g_log2 < 6 && (8 << g_log2) < S) ++g_log2;
-    const int G = 1 << g_log2, g = tid & (G - 1), sub = tid >> g_log2, rows_per_set = GROUP_THREADS >> g_log2;
-    const int32_t rows_per_block = ((n_rows + (int32_t)gridDim.x - 1) / (int32_t)gridDim.x + rows_per_set - 1) / rows_per_set * rows_per_set;
+    const int32_t set_s = GROUP_THREADS >> g_log2; // rows per set if the rows were full
+    const int32_t rows_per_block = ((n_rows + (int32_t)gridDim.x - 1) / (int32_t)gridDim.x + set_s - 1) / set_s * set_s;
     const int32_t r0 = min((int64_t)blockIdx.x * rows_per_block, (int64_t)n_rows);
     const int32_t nr = min(rows_per_block, n_rows - r0);
+    // Rows of later waves are long but mostly far from full: the lanes per row follow the average sample count of
+    // this workgroup's rows instead of the row length (more rows side by side, fewer idle lanes).
+    if (S > 64 && nr > 0) {
+        int32_t mine = 0;
+        for (int32_t t = tid; t < nr; t += GROUP_THREADS) mine += cnt[r0 + t];
+        const int32_t avg = kn_block_sum(mine, scan_lds) / nr;
+        int fit = 0;
+        while (fit < g_log2 && (8 << fit) < avg) ++fit;
+        g_log2 = fit;
+        __syncthreads(); // scan_lds is used again below
+    }
+    const int G = 1 << g_log2, g = tid & (G - 1), sub = tid >> g_log2, rows_per_set = GROUP_THREADS >> g_log2;
     const bool vec = (S & 3) == 0; // rows start on 16-byte boundaries
     const int32_t row_chunks = (S + 3) >> 2;
 
