@@ -33,7 +33,8 @@ def build(force: bool = False) -> None:
 class Scene(C.Structure):
     _fields_ = [("res", C.c_int32 * 3), ("aabb_min", C.c_float * 3), ("aabb_max", C.c_float * 3),
                 ("hidden", C.c_int32), ("L_pos", C.c_int32), ("L_dir", C.c_int32),
-                ("weights", C.c_void_p), ("occ_res", C.c_int32 * 3), ("occupancy", C.c_void_p)]
+                ("weights", C.c_void_p), ("occ_res", C.c_int32 * 3), ("occupancy", C.c_void_p),
+                ("cell_net", C.c_void_p), ("n_nets", C.c_int32)]
 
 
 _f32p = np.ctypeslib.ndpointer(np.float32, flags="C_CONTIGUOUS")
@@ -58,6 +59,14 @@ def _lib(omp: bool = False):
         L.kno_eval_points.argtypes = [C.POINTER(Scene), _f32p, _f32p, C.c_int64, _f64p, _f64p, C.c_void_p]
         L.kno_march.restype = C.c_int32
         L.kno_march.argtypes = [C.POINTER(Scene), _f32p, _f32p, C.c_float, C.c_float, C.c_int32, _i32p]
+        L.kno_stratified_offset.restype = C.c_float
+        L.kno_stratified_offset.argtypes = [C.c_uint32, C.c_uint32, C.c_int32]
+        L.kno_march_stratified.restype = C.c_int32
+        L.kno_march_stratified.argtypes = [C.POINTER(Scene), _f32p, _f32p, C.c_float, C.c_float, C.c_int32,
+                                           C.c_uint32, C.c_uint32, _i32p]
+        L.kno_render_stratified.argtypes = [C.POINTER(Scene), _f32p, _f32p, C.c_int64, C.c_float, C.c_float,
+                                            C.c_int32, C.c_float, _f32p, C.c_uint32, _f64p, C.c_void_p, C.c_void_p,
+                                            C.c_void_p]
         L.kno_composite.restype = C.c_int32
         L.kno_composite.argtypes = [_f64p, _f64p, C.c_int32, C.c_double, C.c_double, _f64p, _f64p,
                                     C.POINTER(C.c_double), C.POINTER(C.c_double)]
@@ -78,14 +87,20 @@ def params_per_net(hidden: int, L_pos: int = 10, L_dir: int = 4) -> int:
 
 class OracleScene:
     """Host-side scene for the oracle.  ``weights``: (N, P) float32 in the canonical layout
-    (values already rounded to the storage type under test); ``occupancy``: uint8 (ox, oy, oz) or None."""
+    (values already rounded to the storage type under test); ``occupancy``: uint8 (ox, oy, oz) or None;
+    ``cell_net``: None, or for a sparse grid an int32 array with one entry per cell (network index, or -1
+    for a cell without a network); N is then the number of rows of ``weights``."""
 
     def __init__(self, res, aabb_min, aabb_max, hidden, weights, occupancy=None, L_pos=10, L_dir=4,
-                 threads: bool = False):
+                 threads: bool = False, cell_net=None):
         self.omp = bool(threads)
         self.L = _lib(self.omp)
         self.res = tuple(int(v) for v in res)
-        self.N = self.res[0] * self.res[1] * self.res[2]
+        self.cells = self.res[0] * self.res[1] * self.res[2]
+        self.cell_net = None if cell_net is None else np.ascontiguousarray(cell_net, dtype=np.int32).reshape(-1)
+        if self.cell_net is not None:
+            assert self.cell_net.size == self.cells
+        self.N = self.cells if self.cell_net is None else int(np.asarray(weights).shape[0])
         self.hidden, self.L_pos, self.L_dir = int(hidden), int(L_pos), int(L_dir)
         self.P = params_per_net(hidden, L_pos, L_dir)
         self.weights = np.ascontiguousarray(weights, dtype=np.float32).reshape(self.N, self.P)
@@ -103,6 +118,8 @@ class OracleScene:
             assert self.occupancy.ndim == 3
             s.occ_res[:] = list(self.occupancy.shape)
             s.occupancy = self.occupancy.ctypes.data
+        s.cell_net = None if self.cell_net is None else self.cell_net.ctypes.data
+        s.n_nets = 0 if self.cell_net is None else self.N
         self.c = s
         self.aabb_min = np.array(aabb_min, np.float32)
         self.aabb_max = np.array(aabb_max, np.float32)
@@ -138,14 +155,26 @@ class OracleScene:
                              float(t_near), float(step), int(K), ks)
         return ks[:n].copy()
 
-    def render(self, rays_o, rays_d, t_near, step, K, term_eps=0.0, bg=(0.0, 0.0, 0.0)):
+    def march_stratified(self, o, d, t_near, step, K, seed, ray):
+        ks = np.empty(max(K, 1), np.int32)
+        n = self.L.kno_march_stratified(C.byref(self.c), np.asarray(o, np.float32), np.asarray(d, np.float32),
+                                        float(t_near), float(step), int(K), int(seed), int(ray), ks)
+        return ks[:n].copy()
+
+    def render(self, rays_o, rays_d, t_near, step, K, term_eps=0.0, bg=(0.0, 0.0, 0.0), seed=None):
+        """``seed`` None: midpoint lattice; else stratified sampling with that seed (ray number = row)."""
         rays_o = np.ascontiguousarray(rays_o, np.float32).reshape(-1, 3)
         rays_d = np.ascontiguousarray(rays_d, np.float32).reshape(-1, 3)
         R = len(rays_o)
         rgb, n_eval, T, mg = np.empty((R, 3)), np.empty(R, np.int32), np.empty(R), np.empty(R)
-        rc = self.L.kno_render(C.byref(self.c), rays_o, rays_d, R, float(t_near), float(step), int(K),
-                               float(term_eps), np.asarray(bg, np.float32), rgb, n_eval.ctypes.data,
-                               T.ctypes.data, mg.ctypes.data)
+        if seed is None:
+            rc = self.L.kno_render(C.byref(self.c), rays_o, rays_d, R, float(t_near), float(step), int(K),
+                                   float(term_eps), np.asarray(bg, np.float32), rgb, n_eval.ctypes.data,
+                                   T.ctypes.data, mg.ctypes.data)
+        else:
+            rc = self.L.kno_render_stratified(C.byref(self.c), rays_o, rays_d, R, float(t_near), float(step), int(K),
+                                              float(term_eps), np.asarray(bg, np.float32), int(seed), rgb,
+                                              n_eval.ctypes.data, T.ctypes.data, mg.ctypes.data)
         assert rc == 0
         return rgb, n_eval, T, mg
 
@@ -172,6 +201,10 @@ def posenc(p, L):
     out = np.empty(3 + 6 * L)
     _lib().kno_posenc(np.asarray(p, np.float32), int(L), out)
     return out
+
+
+def stratified_offset(seed, ray, k):
+    return float(_lib().kno_stratified_offset(int(seed), int(ray), int(k)))
 
 
 def bucket(ids, N):

@@ -25,6 +25,14 @@
  *  - Occupancy extraction (Sec. 3.4): the 3x3x3 subgrid of a voxel sits at its sub-cell centres
  *    (offsets 1/6, 1/2, 5/6 of the voxel per axis); "above" tau is strict; the sampled density
  *    field is the network grid itself.
+ *  - Sparse network grid (Sec. 5 names data structures that instantiate networks only near surfaces):
+ *    a table maps each cell of the regular grid to the index of its network or to "none"; a cell
+ *    without a network has density 0 everywhere, its lattice points are skipped like empty space,
+ *    and a point in it gets the id -1.
+ *  - Stratified sampling (Sec. 3.3, after NeRF): lattice point k of a ray is drawn uniformly from
+ *    its own interval, t_k = t_near + (k + u) * step with u in [0, 1) from a counter-based
+ *    generator keyed by (seed, ray index, k); delta of sample k is the distance to the next
+ *    lattice point, t_(k+1) - t_k, whether or not that point is skipped.
  */
 #include "kn_oracle.h"
 
@@ -83,11 +91,20 @@ int32_t kno_grid_index(const float bmin[3], const float bmax[3], const int32_t r
     return (idx[0] * res[1] + idx[1]) * res[2] + idx[2];
 }
 
+/* Network of a point: Eq. 6 gives the cell; a sparse scene then looks the cell up in its table
+ * (entries outside [0, n_nets) mean "no network here").  -1 = outside the AABB or no network. */
+static int32_t network_of(const kno_scene *s, const float x[3])
+{
+    int32_t cell = kno_grid_index(s->aabb_min, s->aabb_max, s->res, x);
+    if (cell < 0 || !s->cell_net) return cell;
+    int32_t n = s->cell_net[cell];
+    return (n >= 0 && n < s->n_nets) ? n : -1;
+}
+
 int kno_cell_ids(const kno_scene *s, const float *points, int64_t M, int32_t *ids)
 {
     if (!s || (M > 0 && (!points || !ids))) return -1;
-    for (int64_t m = 0; m < M; ++m)
-        ids[m] = kno_grid_index(s->aabb_min, s->aabb_max, s->res, points + 3 * m);
+    for (int64_t m = 0; m < M; ++m) ids[m] = network_of(s, points + 3 * m);
     return 0;
 }
 
@@ -169,7 +186,7 @@ int kno_eval_points(const kno_scene *s, const float *points, const float *dirs, 
 #pragma omp parallel for schedule(dynamic, 256)
 #endif
     for (int64_t m = 0; m < M; ++m) {
-        int32_t id = kno_grid_index(s->aabb_min, s->aabb_max, s->res, points + 3 * m);
+        int32_t id = network_of(s, points + 3 * m);
         if (ids) ids[m] = id;
         if (id < 0) {
             sigma[m] = 0.0;
@@ -181,33 +198,89 @@ int kno_eval_points(const kno_scene *s, const float *points, const float *dirs, 
     return err;
 }
 
-/* Position of lattice point k on a ray: t_k = t_near + (k + 1/2) step, x = o + t_k d,
- * each as one fused multiply-add in fp32 (never accumulated along the ray). */
-static void lattice_point(const float o[3], const float d[3], float t_near, float step, int32_t k,
-                          float x[3])
+/* 32-bit mixing function (the finalizer of MurmurHash3, a published bijection on 32-bit words). */
+static uint32_t mix32(uint32_t v)
 {
-    float t = fmaf((float)k + 0.5f, step, t_near);
+    v ^= v >> 16;
+    v *= 0x85ebca6bu;
+    v ^= v >> 13;
+    v *= 0xc2b2ae35u;
+    v ^= v >> 16;
+    return v;
+}
+
+float kno_stratified_offset(uint32_t seed, uint32_t ray, int32_t k)
+{
+    uint32_t per_ray = mix32(mix32(seed) + ray);
+    uint32_t word = mix32(per_ray ^ (uint32_t)k);
+    return (float)(word >> 8) * (1.0f / 16777216.0f); /* 24 bits -> [0, 1), exact in fp32 */
+}
+
+/* Where inside its interval lattice point k sits: the middle, or the stratified draw. */
+typedef struct {
+    int on;
+    uint32_t seed, ray;
+} strat;
+
+static float lattice_offset(const strat *j, int32_t k)
+{
+    return (j && j->on) ? kno_stratified_offset(j->seed, j->ray, k) : 0.5f;
+}
+
+/* Parameter of lattice point k on a ray: t_k = t_near + (k + offset) step as one fused
+ * multiply-add in fp32 (never accumulated along the ray). */
+static float lattice_t(float t_near, float step, int32_t k, const strat *j)
+{
+    return fmaf((float)k + lattice_offset(j, k), step, t_near);
+}
+
+/* Position of lattice point k: x = o + t_k d, one fused multiply-add per axis. */
+static void lattice_point(const float o[3], const float d[3], float t_near, float step, int32_t k,
+                          const strat *j, float x[3])
+{
+    float t = lattice_t(t_near, step, k, j);
     for (int a = 0; a < 3; ++a) x[a] = fmaf(t, d[a], o[a]);
+}
+
+/* delta of sample k: the constant spacing on the midpoint lattice; with stratified sampling the
+ * distance to the next lattice point (NeRF's delta_i = t_(i+1) - t_i), also for k = K - 1. */
+static double lattice_delta(float t_near, float step, int32_t k, const strat *j)
+{
+    if (!(j && j->on)) return (double)step;
+    return (double)lattice_t(t_near, step, k + 1, j) - (double)lattice_t(t_near, step, k, j);
 }
 
 static int sample_is_kept(const kno_scene *s, const float x[3])
 {
-    if (kno_grid_index(s->aabb_min, s->aabb_max, s->res, x) < 0) return 0; /* outside the AABB */
+    if (network_of(s, x) < 0) return 0; /* outside the AABB, or a cell without a network */
     if (s->occ_res[0] == 0) return 1;                                      /* no occupancy grid */
     int32_t v = kno_grid_index(s->aabb_min, s->aabb_max, s->occ_res, x);
     return v >= 0 && s->occupancy[v] != 0;
 }
 
-int32_t kno_march(const kno_scene *s, const float o[3], const float d[3], float t_near,
-                  float step, int32_t K, int32_t *ks)
+static int32_t march_ray(const kno_scene *s, const float o[3], const float d[3], float t_near,
+                         float step, int32_t K, const strat *j, int32_t *ks)
 {
     int32_t n = 0;
     for (int32_t k = 0; k < K; ++k) {
         float x[3];
-        lattice_point(o, d, t_near, step, k, x);
+        lattice_point(o, d, t_near, step, k, j, x);
         if (sample_is_kept(s, x)) ks[n++] = k;
     }
     return n;
+}
+
+int32_t kno_march(const kno_scene *s, const float o[3], const float d[3], float t_near,
+                  float step, int32_t K, int32_t *ks)
+{
+    return march_ray(s, o, d, t_near, step, K, NULL, ks);
+}
+
+int32_t kno_march_stratified(const kno_scene *s, const float o[3], const float d[3], float t_near,
+                             float step, int32_t K, uint32_t seed, uint32_t ray, int32_t *ks)
+{
+    const strat j = {1, seed, ray};
+    return march_ray(s, o, d, t_near, step, K, &j, ks);
 }
 
 int32_t kno_composite(const double *sigma, const double *rgb, int32_t n, double step, double eps,
@@ -232,9 +305,10 @@ int32_t kno_composite(const double *sigma, const double *rgb, int32_t n, double 
     return used;
 }
 
-int kno_render(const kno_scene *s, const float *rays_o, const float *rays_d, int64_t R,
-               float t_near, float step, int32_t K, float term_eps, const float bg[3],
-               double *rgb_out, int32_t *n_eval, double *T_final, double *margin)
+static int render_rays(const kno_scene *s, const float *rays_o, const float *rays_d, int64_t R,
+                       float t_near, float step, int32_t K, float term_eps, const float bg[3],
+                       const uint32_t *seed, double *rgb_out, int32_t *n_eval, double *T_final,
+                       double *margin)
 {
     if (!s || K < 0 || (R > 0 && (!rays_o || !rays_d || !rgb_out)) || !bg) return -1;
     int err = 0;
@@ -243,17 +317,18 @@ int kno_render(const kno_scene *s, const float *rays_o, const float *rays_d, int
 #endif
     for (int64_t r = 0; r < R; ++r) {
         const float *o = rays_o + 3 * r, *d = rays_d + 3 * r;
-        const double eps = (double)term_eps, dstep = (double)step;
+        const double eps = (double)term_eps;
+        const strat j = {seed != NULL, seed ? *seed : 0u, (uint32_t)r};
         double T = 1.0, C[3] = {0.0, 0.0, 0.0}, mg_min = INFINITY;
         int32_t used = 0;
         for (int32_t k = 0; k < K; ++k) {
             float x[3];
-            lattice_point(o, d, t_near, step, k, x);
+            lattice_point(o, d, t_near, step, k, &j, x);
             if (!sample_is_kept(s, x)) continue;
-            int32_t id = kno_grid_index(s->aabb_min, s->aabb_max, s->res, x);
+            int32_t id = network_of(s, x);
             double sg, col[3];
             if (kno_mlp(s, id, x, d, &sg, col) != 0) { err = -1; break; }
-            double alpha = 1.0 - exp(-sg * dstep);
+            double alpha = 1.0 - exp(-sg * lattice_delta(t_near, step, k, &j));
             for (int c = 0; c < 3; ++c) C[c] += T * alpha * col[c];
             T *= (1.0 - alpha);
             ++used;
@@ -269,6 +344,23 @@ int kno_render(const kno_scene *s, const float *rays_o, const float *rays_d, int
         if (margin) margin[r] = mg_min;
     }
     return err;
+}
+
+int kno_render(const kno_scene *s, const float *rays_o, const float *rays_d, int64_t R,
+               float t_near, float step, int32_t K, float term_eps, const float bg[3],
+               double *rgb_out, int32_t *n_eval, double *T_final, double *margin)
+{
+    return render_rays(s, rays_o, rays_d, R, t_near, step, K, term_eps, bg, NULL, rgb_out, n_eval,
+                       T_final, margin);
+}
+
+int kno_render_stratified(const kno_scene *s, const float *rays_o, const float *rays_d, int64_t R,
+                          float t_near, float step, int32_t K, float term_eps, const float bg[3],
+                          uint32_t seed, double *rgb_out, int32_t *n_eval, double *T_final,
+                          double *margin)
+{
+    return render_rays(s, rays_o, rays_d, R, t_near, step, K, term_eps, bg, &seed, rgb_out, n_eval,
+                       T_final, margin);
 }
 
 /* Sec. 3.4: one voxel of the occupancy grid, 27 probes. */
@@ -292,7 +384,7 @@ static int extract_voxel(const kno_scene *s, const int32_t occ_res[3], float tau
                 float x[3];
                 for (int a = 0; a < 3; ++a) x[a] = fmaf((float)v[a] + sub[sel[a]], cell[a], s->aabb_min[a]);
                 double sg = 0.0, rgb[3];
-                int32_t id = kno_grid_index(s->aabb_min, s->aabb_max, s->res, x);
+                int32_t id = network_of(s, x);
                 if (id >= 0 && kno_mlp(s, id, x, dir, &sg, rgb) != 0) return -1;
                 if (sg > (double)tau) any = 1;
                 if (sg > top) top = sg;

@@ -37,6 +37,10 @@ typedef struct {
     const float *weights;    /* N * kno_params_per_net(H, L_pos, L_dir) values        */
     int32_t occ_res[3];      /* occupancy grid resolution, all 0 = no grid            */
     const uint8_t *occupancy;/* occ_res[0]*occ_res[1]*occ_res[2] bytes, x slowest     */
+    const int32_t *cell_net; /* NULL: one network per cell, network id = cell index.  Else a  */
+                             /* sparse grid (Sec. 5): rx*ry*rz entries, cell -> network index */
+                             /* in [0, n_nets); any other value = no network in that cell     */
+    int32_t n_nets;          /* networks behind `weights` when cell_net is given              */
 } kno_scene;
 
 /* Number of parameters of one tiny MLP.  Layers (Sec. 3.2, "Network Architecture"):
@@ -53,7 +57,8 @@ void kno_posenc(const float p[3], int32_t L, double *out);
 int32_t kno_grid_index(const float bmin[3], const float bmax[3], const int32_t res[3],
                        const float x[3]);
 
-/* Point -> network id for M points (ids[m] = -1 outside). */
+/* Point -> network id for M points (ids[m] = -1 outside the AABB or, on a sparse grid, in a
+ * cell without a network). */
 int kno_cell_ids(const kno_scene *s, const float *points, int64_t M, int32_t *ids);
 
 /* Stable bucketing by network id: counts[N+1] (slot N counts id=-1), offsets[N+2]
@@ -66,15 +71,28 @@ int kno_bucket(const int32_t *ids, int64_t M, int32_t N, int32_t *counts, int32_
 int kno_mlp(const kno_scene *s, int32_t n, const float x[3], const float d[3],
             double *sigma, double *rgb);
 
-/* eval_grouped: per point, cell id then its network.  Outside points: id -1, sigma 0, rgb 0. */
+/* eval_grouped: per point, cell id then its network.  Points outside, or in a cell without a
+ * network: id -1, sigma 0, rgb 0. */
 int kno_eval_points(const kno_scene *s, const float *points, const float *dirs, int64_t M,
                     double *sigma, double *rgb, int32_t *ids);
 
 /* Sample lattice of one ray with empty-space skipping (Sec. 3.4): writes the step indices
- * k in [0,K) whose point lies inside the AABB in an occupied voxel, ascending; returns
- * how many (<= K). */
+ * k in [0,K) whose point lies inside the AABB in an occupied voxel (and, on a sparse grid, in a
+ * cell that has a network), ascending; returns how many (<= K). */
 int32_t kno_march(const kno_scene *s, const float o[3], const float d[3], float t_near,
                   float step, int32_t K, int32_t *ks);
+
+/* Stratified sampling (Sec. 3.3, "similar to NeRF": one uniform draw per lattice interval).
+ * Offset u in [0, 1) of lattice point k of ray number `ray`:
+ *   mix(v): v ^= v >> 16; v *= 0x85ebca6b; v ^= v >> 13; v *= 0xc2b2ae35; v ^= v >> 16   (uint32)
+ *   u = (mix(mix(mix(seed) + ray) ^ k) >> 8) * 2^-24
+ * so that t_k = t_near + (k + u) * step (fp32, one fused multiply-add) lies in interval k.
+ * kno_march_stratified / kno_render_stratified are kno_march / kno_render on these lattice
+ * points; in the render, ray r of the arrays has ray number r, and sample k is blended with
+ * delta_k = t_(k+1) - t_k (the next lattice point, kept or not; k + 1 = K included). */
+float kno_stratified_offset(uint32_t seed, uint32_t ray, int32_t k);
+int32_t kno_march_stratified(const kno_scene *s, const float o[3], const float d[3], float t_near,
+                             float step, int32_t K, uint32_t seed, uint32_t ray, int32_t *ks);
 
 /* Front-to-back alpha blending with early termination (Sec. 3.1 Eq. 2-4, Sec. 3.4):
  * n samples (sigma, rgb) of constant spacing step.  Returns the number of samples
@@ -90,11 +108,17 @@ int kno_render(const kno_scene *s, const float *rays_o, const float *rays_d, int
                float t_near, float step, int32_t K, float term_eps, const float bg[3],
                double *rgb_out, int32_t *n_eval, double *T_final, double *margin);
 
+int kno_render_stratified(const kno_scene *s, const float *rays_o, const float *rays_d, int64_t R,
+                          float t_near, float step, int32_t K, float term_eps, const float bg[3],
+                          uint32_t seed, double *rgb_out, int32_t *n_eval, double *T_final,
+                          double *margin);
+
 /* Occupancy grid extraction (Sec. 3.4, "Empty Space Skipping"; tau: Sec. 4.1): the density is
  * sampled on a 3x3x3 subgrid of every voxel of a grid of resolution occ_res over the AABB and the
  * voxel is marked (1) iff any of the 27 densities is above tau (strictly), else 0.  The density
  * field is the scene's own network grid (the paper samples its teacher model); a probe is
- * evaluated by the network of the cell it lies in (Eq. 6).  Probe positions (the paper does not
+ * evaluated by the network of the cell it lies in (Eq. 6; density 0 where a sparse grid has no
+ * network).  Probe positions (the paper does not
  * place the subgrid): sub-cell centres, per axis x = bmin + (v + c) * cell with c in {1/6, 1/2, 5/6},
  * cell = (bmax - bmin) / occ_res, taken in fp32 as fmaf((float)v + c, cell, bmin).
  * kno_extract_occupancy_at does this for n voxels given by linear index (x slowest);

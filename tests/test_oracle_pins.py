@@ -408,6 +408,184 @@ def test_render_ert_bound_and_straddle_margin():
 
 
 # ------------------------------------------------------------------ occupancy extraction (Sec. 3.4)
+
+
+# ------------------------------------------------------------------ sparse network grids (Sec. 5)
+def _sparse_fixture():
+    from kn_synth import configs
+    cfg = configs.config3(20, 20)
+    s = cfg["scene"]
+    dense = OracleScene(s["res"], s["aabb_min"], s["aabb_max"], s["hidden"], s["weights"], s["occupancy"])
+    return cfg, s, dense
+
+
+def test_sparse_grid_with_every_cell_present_equals_the_dense_grid_whatever_the_order():
+    cfg, s, dense = _sparse_fixture()
+    n = dense.N
+    args = (cfg["rays_o"], cfg["rays_d"], cfg["t_near"], cfg["step"], cfg["K"], cfg["term_eps"], cfg["bg"])
+    want = dense.render(*args)
+    rng = np.random.default_rng(5)
+    pts = rng.uniform(-1.1, 1.1, (4000, 3)).astype(np.float32)
+    dirs = ks.sphere_dirs(4000, 3)
+    want_pts = dense.eval_points(pts, dirs)
+    for table in (np.arange(n, dtype=np.int32), rng.permutation(n).astype(np.int32)):
+        w = np.empty_like(s["weights"])
+        w[table] = s["weights"]                 # network table[c] holds the weights of cell c
+        sp = OracleScene(s["res"], s["aabb_min"], s["aabb_max"], s["hidden"], w, s["occupancy"], cell_net=table)
+        got = sp.render(*args)
+        for a, b in zip(got, want):
+            assert np.array_equal(a, b)
+        sg, rgb, ids = sp.eval_points(pts, dirs)
+        assert np.array_equal(sg, want_pts[0]) and np.array_equal(rgb, want_pts[1])
+        inside = want_pts[2] >= 0
+        assert np.array_equal(ids[inside], table[want_pts[2][inside]]) and np.all(ids[~inside] == -1)
+        assert np.array_equal(sp.cell_ids(pts), ids)
+
+
+def test_a_cell_without_a_network_is_empty_space():
+    cfg, s, dense = _sparse_fixture()
+    n = dense.N
+    rng = np.random.default_rng(6)
+    present = rng.random(n) < 0.6
+    table = np.full(n, -1, np.int32)
+    table[present] = rng.permutation(int(present.sum())).astype(np.int32)
+    w = np.empty((int(present.sum()), s["weights"].shape[1]), np.float32)
+    w[table[present]] = s["weights"][present]
+    sp = OracleScene(s["res"], s["aabb_min"], s["aabb_max"], s["hidden"], w, s["occupancy"], cell_net=table)
+    # the same field on the dense grid: the absent cells' networks put out density 0 (layer 3, output 0)
+    wz = s["weights"].copy()
+    lv = ks.layer_views(wz, s["hidden"])
+    lv[2][0][~present, :, 0] = 0.0
+    lv[2][1][~present, 0] = 0.0
+    dz = OracleScene(s["res"], s["aabb_min"], s["aabb_max"], s["hidden"], wz, s["occupancy"])
+    args = (cfg["rays_o"], cfg["rays_d"], cfg["t_near"], cfg["step"], cfg["K"], cfg["term_eps"], cfg["bg"])
+    rgb_s, n_s, T_s, _ = sp.render(*args)
+    rgb_z, n_z, T_z, _ = dz.render(*args)
+    np.testing.assert_allclose(rgb_s, rgb_z, atol=1e-12)
+    np.testing.assert_allclose(T_s, T_z, atol=1e-12)
+    assert np.all(n_s <= n_z) and n_s.sum() < n_z.sum()          # the absent cells' samples are never evaluated
+    # marching: exactly the dense ray's samples whose cell has a network
+    for r in (0, 111, 210, 399):
+        kk = dense.march(cfg["rays_o"][r], cfg["rays_d"][r], cfg["t_near"], cfg["step"], cfg["K"])
+        t = np.float32(cfg["t_near"]) + (kk.astype(np.float32) + np.float32(0.5)) * np.float32(cfg["step"])
+        x = cfg["rays_o"][r] + t[:, None] * cfg["rays_d"][r]
+        keep = present[dense.cell_ids(x.astype(np.float32))]
+        got = sp.march(cfg["rays_o"][r], cfg["rays_d"][r], cfg["t_near"], cfg["step"], cfg["K"])
+        # (x is recomputed without the fused multiply-add: a point within rounding of a cell face may differ)
+        assert len(set(got.tolist()) ^ set(kk[keep].tolist())) <= 1
+    # points: density and colour 0 and id -1 in absent cells, the dense values elsewhere
+    pts = rng.uniform(-1, 1, (3000, 3)).astype(np.float32)
+    dirs = np.tile(np.float32([0.6, 0.0, 0.8]), (3000, 1))
+    sg, rgb, ids = sp.eval_points(pts, dirs)
+    sg_d, rgb_d, ids_d = dense.eval_points(pts, dirs)
+    gone = ~present[ids_d]
+    assert gone.sum() > 500 and np.all(ids[gone] == -1) and np.all(sg[gone] == 0) and np.all(rgb[gone] == 0)
+    assert np.array_equal(sg[~gone], sg_d[~gone]) and np.array_equal(rgb[~gone], rgb_d[~gone])
+    # table entries outside [0, n_nets) also mean "no network"
+    bad = table.copy()
+    bad[~present] = np.where(rng.random(int((~present).sum())) < 0.5, len(w), -7)
+    sb = OracleScene(s["res"], s["aabb_min"], s["aabb_max"], s["hidden"], w, s["occupancy"], cell_net=bad)
+    assert np.array_equal(sb.eval_points(pts, dirs)[2], ids)
+    # extraction: the occupancy of the zeroed dense field
+    occ_s = sp.extract_occupancy((12, 12, 12), 0.5)[0]
+    occ_z = dz.extract_occupancy((12, 12, 12), 0.5)[0]
+    assert np.array_equal(occ_s, occ_z) and 0 < occ_s.sum() < occ_s.size
+
+
+# ------------------------------------------------------------------ stratified sampling (Sec. 3.3)
+def test_stratified_offsets_are_uniform_draws_per_seed_ray_and_sample():
+    u = np.array([[[oracle.stratified_offset(s_, r, k) for k in range(64)] for r in range(48)] for s_ in (0, 1, 77)])
+    assert u.min() >= 0.0 and u.max() < 1.0
+    assert np.array_equal(u * 2 ** 24, np.floor(u * 2 ** 24))          # 24-bit fractions
+    n = u.size
+    assert abs(u.mean() - 0.5) < 4 * math.sqrt(1 / 12 / n) and abs(u.var() - 1 / 12) < 0.004
+    hist = np.histogram(u, bins=16, range=(0, 1))[0]
+    assert ((hist - n / 16) ** 2 / (n / 16)).sum() < 45                 # chi-square, 15 degrees of freedom
+    c = u - 0.5
+    for a, b in ((c[:, :, 1:], c[:, :, :-1]), (c[:, 1:], c[:, :-1]), (c[1:], c[:-1])):   # along k, ray, seed
+        assert abs((a * b).mean() * 12) < 5 / math.sqrt(a.size)
+    assert len(np.unique(u)) > 0.99 * n
+    # the function is its published definition (32-bit finalizer of MurmurHash3, nested)
+    def mix(v):
+        v ^= v >> 16; v = (v * 0x85EBCA6B) & 0xFFFFFFFF; v ^= v >> 13; v = (v * 0xC2B2AE35) & 0xFFFFFFFF
+        return v ^ (v >> 16)
+    assert mix(0) == 0 and mix(1) == 0x514E28B7
+    for s_, r, k in ((0, 0, 0), (1, 2, 3), (210313744, 639999, 511), (2 ** 32 - 1, 2 ** 32 - 1, 1023)):
+        want = (mix(mix((mix(s_) + r) & 0xFFFFFFFF) ^ k) >> 8) / 2 ** 24
+        assert oracle.stratified_offset(s_, r, k) == want
+
+
+def test_stratified_march_tests_one_point_per_interval():
+    occ = np.zeros((8, 8, 8), np.uint8)
+    occ[2:4, :, :] = 1                       # slab 0.25 <= x < 0.5
+    sc = const_scene(1.0, (0.5, 0.5, 0.5), occ=occ)
+    o, d = np.array([-1.0, 0.3, 0.6], np.float32), np.array([1.0, 0.0, 0.0], np.float32)
+    differs = 0
+    for seed, ray in ((3, 0), (3, 1), (4, 0), (9, 12345)):
+        got = sc.march_stratified(o, d, 1.0, 1 / 64, 64, seed, ray).tolist()
+        # x_k = (k + u_k) / 64 exactly (all quantities are small dyadic fractions): in the slab iff 16 <= k + u_k < 32
+        want = [k for k in range(64) if 16 <= k + oracle.stratified_offset(seed, ray, k) < 32]
+        assert got == want == list(range(16, 32))        # interval k lies inside the slab or outside it
+        # intervals of 1/40 shifted by 1/128: the slab's faces cut intervals 9 and 19 at 0.6875 of their length
+        tn = 1.0 + 1 / 128
+        got = sc.march_stratified(o, d, tn, 1 / 40, 40, seed, ray).tolist()
+        want = [k for k in range(40) if 9.6875 <= k + oracle.stratified_offset(seed, ray, k) < 19.6875]
+        assert got == want and set(range(10, 19)) <= set(got) <= set(range(9, 20))
+        differs += got != sc.march(o, d, tn, 1 / 40, 40).tolist()
+    assert differs >= 1                                    # the boundary intervals do depend on the draw
+
+
+def test_stratified_render_of_a_constant_medium_telescopes():
+    colour, bg, sigma = np.array([0.2, 0.5, 0.9]), np.array([1.0, 0.25, 0.0]), 3.0
+    sc = const_scene(sigma, colour, res=(1, 1, 1), lo=(-4, -4, -4), hi=(4, 4, 4))
+    o = np.tile(np.float32([-1.0, 0.3, 0.6]), (5, 1))
+    d = np.tile(np.float32([1.0, 0.0, 0.0]), (5, 1))
+    step, t_near, K, seed = 1 / 16, 0.5, 24, 11
+    rgb, n_eval, T, _ = sc.render(o, d, t_near, step, K, 0.0, bg, seed=seed)
+    assert np.all(n_eval == K)
+    for r in range(5):
+        # sum of delta_k = t_K - t_0 = (K + u_K - u_0) * step
+        length = (K + oracle.stratified_offset(seed, r, K) - oracle.stratified_offset(seed, r, 0)) * step
+        assert abs(T[r] - math.exp(-sigma * length)) < 1e-6
+        np.testing.assert_allclose(rgb[r], colour * (1 - T[r]) + bg * T[r], atol=1e-7)
+    assert len(np.unique(T)) == 5                           # each ray has its own draws
+    T_mid = sc.render(o, d, t_near, step, K, 0.0, bg)[2]
+    assert np.allclose(T_mid, math.exp(-sigma * K * step), atol=1e-12)
+    # other seed, other draws; same seed, same picture
+    assert not np.array_equal(sc.render(o, d, t_near, step, K, 0.0, bg, seed=12)[2], T)
+    assert np.array_equal(sc.render(o, d, t_near, step, K, 0.0, bg, seed=seed)[2], T)
+
+
+def test_stratified_render_is_march_then_networks_then_blend_with_its_own_deltas():
+    from kn_synth import configs
+    cfg = configs.config3(16, 16)
+    s = cfg["scene"]
+    sc = OracleScene(s["res"], s["aabb_min"], s["aabb_max"], s["hidden"], s["weights"], s["occupancy"])
+    seed = 5
+    rgb, n_eval, T, _ = sc.render(cfg["rays_o"], cfg["rays_d"], cfg["t_near"], cfg["step"], cfg["K"], 0.0, cfg["bg"], seed=seed)
+    mid = sc.render(cfg["rays_o"], cfg["rays_d"], cfg["t_near"], cfg["step"], cfg["K"], 0.0, cfg["bg"])
+    assert n_eval.sum() > 500 and 1e-4 < np.abs(rgb - mid[0]).max() < 0.3
+    step, tn = float(np.float32(cfg["step"])), float(np.float32(cfg["t_near"]))
+    checked = 0
+    for r in np.argsort(-n_eval)[:6]:
+        kk = sc.march_stratified(cfg["rays_o"][r], cfg["rays_d"][r], cfg["t_near"], cfg["step"], cfg["K"], seed, r)
+        assert len(kk) == n_eval[r]
+        u = np.array([oracle.stratified_offset(seed, r, k) for k in range(cfg["K"] + 1)])
+        t = tn + (np.arange(cfg["K"] + 1) + u) * step
+        x = cfg["rays_o"][r].astype(np.float64) + t[kk, None] * cfg["rays_d"][r].astype(np.float64)
+        sg, col, ids = sc.eval_points(x.astype(np.float32), np.tile(cfg["rays_d"][r], (len(kk), 1)))
+        delta = t[kk + 1] - t[kk]
+        Tr, C = 1.0, np.zeros(3)
+        for i in range(len(kk)):                              # Eq. 2-4 with a delta per sample
+            a = 1 - math.exp(-sg[i] * delta[i])
+            C += Tr * a * col[i]
+            Tr *= 1 - a
+        np.testing.assert_allclose(C + Tr * np.asarray(cfg["bg"]), rgb[r], atol=2e-4)   # x in fp64 here, fp32 lattice there
+        assert abs(Tr - T[r]) < 2e-4
+        checked += 1
+    assert checked == 6
+
+
 def _probe_coords(lo, hi, res):
     """(res, 3) positions of the three sub-cell centres of every voxel along one axis, fp64."""
     v = np.arange(res)[:, None]
