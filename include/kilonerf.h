@@ -51,6 +51,7 @@ typedef enum { KN_F32 = 0, KN_F16 = 1, KN_BF16 = 2 } kn_dtype;
 /* Scene = AABB + network grid + per-cell MLP weights + optional occupancy grid (Sec. 3.2, 3.4). */
 typedef struct {
     int32_t res[3];          /* network grid r = (rx, ry, rz), each >= 1, product <= 65535       */
+                             /* (<= 2^24 cells when cell_net is given)                            */
     float aabb_min[3];       /* b_min                                                             */
     float aabb_max[3];       /* b_max, > b_min per axis                                           */
     int32_t hidden;          /* H: 32 or 64                                                       */
@@ -61,6 +62,14 @@ typedef struct {
     const void *weights;     /* dev, N*P elements of wdtype in the canonical layout               */
     int32_t occ_res[3];      /* occupancy grid resolution; all 0 = no grid (whole AABB occupied)  */
     const uint8_t *occupancy;/* dev, occ_res[0]*occ_res[1]*occ_res[2] bytes (0 = empty), x slowest*/
+    /* Sparse network grid (Sec. 5: networks instantiated only in the vicinity of surfaces).  NULL:   */
+    /* one network per cell, network id = cell index.  Else dev, rx*ry*rz entries (x slowest): the     */
+    /* index in [0, n_nets) of the cell's network in `weights`; any other value = the cell has no      */
+    /* network.  Such a cell is empty space: density 0, its lattice points are skipped, points in it   */
+    /* get id -1 and sigma = rgb = 0.  Wherever this header says "network id" / N, a sparse scene has  */
+    /* the table's value / n_nets.  The library keeps its own copy.                                    */
+    const int32_t *cell_net;
+    int32_t n_nets;          /* networks behind `weights` when cell_net is given: 1 .. 65535         */
 } kn_scene_desc;
 
 typedef struct kn_scene kn_scene; /* opaque */
@@ -98,7 +107,8 @@ int kn_scene_destroy(kn_scene *scene); /* waits for the device, frees the librar
 int kn_workspace_bytes(const kn_scene *scene, int64_t max_points, int64_t max_rays, int64_t *out_bytes);
 
 /* Eq. 6: network index of M points.  ids[m] = (ix*ry + iy)*rz + iz, or -1 outside [b_min, b_max).
- * fp32 arithmetic exactly as written in Eq. 6: floor((x - b_min) / ((b_max - b_min) / r)). */
+ * fp32 arithmetic exactly as written in Eq. 6: floor((x - b_min) / ((b_max - b_min) / r)).  On a sparse
+ * grid the cell index is then mapped through the scene's table (-1 where the cell has no network). */
 int kn_cell_ids(const kn_scene *scene, void *stream, const float *points /*dev M*3*/, int64_t M,
                 int32_t *ids /*dev M*/);
 
@@ -123,13 +133,33 @@ int kn_eval_grouped(const kn_scene *scene, void *stream, const float *points /*d
 /* Sec. 3.4 sampling with empty-space skipping, one stage on its own: for each ray, starting at
  * lattice index k_begin[r] (0 if NULL), collect up to S kept samples.  Lattice: t_k = t_near +
  * (k + 1/2)*step, x_k = o + t_k*d (fp32, one fused multiply-add each), k < K; a sample is kept
- * iff x_k is inside the AABB and its occupancy voxel is non-zero.  out_k[r*S + j] = j-th kept
+ * iff x_k is inside the AABB and its occupancy voxel is non-zero (and, on a sparse grid, its cell
+ * has a network).  out_k[r*S + j] = j-th kept
  * index (unused slots -1), out_count[r] = kept, out_k_next[r] (nullable) = where to resume
  * (K when the ray is exhausted). */
 int kn_march(const kn_scene *scene, void *stream, const float *rays_o /*dev R*3*/,
              const float *rays_d /*dev R*3*/, int64_t R, float t_near, float step, int32_t K,
              const int32_t *k_begin /*dev R, nullable*/, int32_t S, int32_t *out_k /*dev R*S*/,
              int32_t *out_count /*dev R*/, int32_t *out_k_next /*dev R, nullable*/);
+
+/* Sec. 3.3 (stratified sampling, as in NeRF): kn_march / kn_render with one uniform draw per lattice
+ * interval instead of its midpoint: t_k = t_near + (k + u) * step, u in [0, 1) from a counter-based
+ * generator keyed by (seed, ray number, k), the ray number being the ray's row in rays_o / rays_d:
+ *     mix(v): v ^= v >> 16; v *= 0x85ebca6b; v ^= v >> 13; v *= 0xc2b2ae35; v ^= v >> 16   (uint32)
+ *     u = (mix(mix(mix(seed) + ray) ^ k) >> 8) * 2^-24
+ * The same seed gives the same picture; a new seed per frame gives independent draws.  In the render
+ * sample k is blended with its own delta_k = t_(k+1) - t_k, the distance to the next lattice point
+ * whether or not that point is kept (k + 1 = K included); everything else is as in kn_render. */
+int kn_march_stratified(const kn_scene *scene, void *stream, const float *rays_o /*dev R*3*/,
+                        const float *rays_d /*dev R*3*/, int64_t R, float t_near, float step, int32_t K,
+                        uint32_t seed, const int32_t *k_begin /*dev R, nullable*/, int32_t S,
+                        int32_t *out_k /*dev R*S*/, int32_t *out_count /*dev R*/,
+                        int32_t *out_k_next /*dev R, nullable*/);
+int kn_render_stratified(const kn_scene *scene, void *stream, const float *rays_o /*dev R*3*/,
+                         const float *rays_d /*dev R*3, unit*/, int64_t R, float t_near, float step,
+                         int32_t K, float term_eps, const float bg[3] /*host*/, uint32_t seed,
+                         float *rgb_out /*dev R*3*/, kn_render_stats *stats /*host, nullable*/,
+                         void *workspace, int64_t workspace_bytes);
 
 /* Eq. 2-4 with early ray termination (Sec. 3.4), one stage on its own: ray r owns samples
  * offsets[r] .. offsets[r+1]-1 of sigma / rgb in front-to-back order; alpha = 1 - exp(-sigma*step),
@@ -174,8 +204,8 @@ int kn_eval_grouped_layered(const kn_scene *scene, void *stream, const float *po
  * over the scene's AABB.  The density is sampled on a 3x3x3 subgrid of every voxel and the voxel
  * is marked (byte 1, else 0) iff any of the 27 densities is above tau (strictly).  The density
  * field is the scene's own network grid (the paper samples its teacher model); a probe is
- * evaluated by the network of the cell it lies in (Eq. 6), whether or not occ_res is a multiple
- * of the network grid.  The paper does not place the subgrid; it sits at the sub-cell centres, per
+ * evaluated by the network of the cell it lies in (Eq. 6; density 0 in a cell without a network),
+ * whether or not occ_res is a multiple of the network grid.  The paper does not place the subgrid; it sits at the sub-cell centres, per
  * axis x = b_min + (v + c) * cell, c in {1/6, 1/2, 5/6}, cell = (b_max - b_min) / occ_res, taken
  * in fp32 as fma((float)v + c, cell, b_min).  Only layers 1-3 of the networks run (the density
  * does not depend on the direction), with the scene's arithmetic (fp32, or 16-bit operands).

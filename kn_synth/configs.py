@@ -68,3 +68,38 @@ def config5(width=1920, height=1080, azimuth=45.0, sigma_scale=100.0, wdtype="bf
     1920x1080 rays, step = diagonal / 1024."""
     return _render_config(net_res, occ_res, 64, wdtype, 64, 0.05, width, height, 1024, BASE_SEED + 5, azimuth,
                           sigma_scale, "cfg5_large_%s" % wdtype)
+
+
+def sparsify(scene, present, seed):
+    """Turn a dense scene dict into a sparse one: the cells flagged in ``present`` keep their network, the networks
+    are stored in shuffled order, ``cell_net`` maps cell -> row of ``weights`` (-1: no network)."""
+    present = np.asarray(present, bool).reshape(-1)
+    n = int(present.sum())
+    table = np.full(present.size, -1, np.int32)
+    table[present] = np.random.default_rng(seed).permutation(n).astype(np.int32)
+    w = np.empty((n, scene["weights"].shape[1]), np.float32)
+    w[table[present]] = scene["weights"][present]
+    out = dict(scene)
+    out["weights"] = w
+    out["cell_net"] = table
+    return out
+
+
+def config_sparse(width=800, height=800, azimuth=45.0, sigma_scale=100.0, wdtype="f16", net_res=48, occ_res=192,
+                  hidden=32, frac=0.04):
+    """A finer network grid than a dense scene could hold (48^3 = 110,592 cells), with networks only in the cells
+    that contain occupied voxels (the sparse instantiation Sec. 5 proposes); camera and lattice as config 3."""
+    occ = blob_occupancy((occ_res,) * 3, 32, frac, BASE_SEED + 67)
+    f = occ_res // net_res
+    assert f * net_res == occ_res
+    present = occ.reshape(net_res, f, net_res, f, net_res, f).any(axis=(1, 3, 5)).reshape(-1)
+    n = int(present.sum())
+    table = np.full(present.size, -1, np.int32)
+    table[present] = np.random.default_rng(BASE_SEED + 68).permutation(n).astype(np.int32)
+    w = round_to_storage(kaiming_weights(n, hidden, BASE_SEED + 6, sigma_scale=sigma_scale), wdtype)
+    sc = dict(res=(net_res,) * 3, aabb_min=(-1.0, -1.0, -1.0), aabb_max=(1.0, 1.0, 1.0), hidden=hidden, wdtype=wdtype,
+              weights=w, occupancy=occ, L_pos=10, L_dir=4, cell_net=table)
+    o, d = camera_rays(width, height, 40.0, 4.0, azimuth, 30.0)
+    diag = 2.0 * math.sqrt(3.0)
+    return dict(scene=sc, rays_o=o, rays_d=d, t_near=4.0 - math.sqrt(3.0), step=diag / 512, K=512, term_eps=0.01,
+                bg=(1.0, 1.0, 1.0), width=width, height=height, name="sparse_render_%s" % wdtype)

@@ -20,7 +20,7 @@ DTYPES = {"f32": KN_F32, "f16": KN_F16, "bf16": KN_BF16}
 EXPORTS = ["kn_error_string", "kn_last_hip_error", "kn_params_per_net", "kn_scene_create", "kn_scene_destroy",
            "kn_extract_workspace_bytes", "kn_extract_occupancy", "kn_layered_workspace_bytes", "kn_eval_grouped_layered",
            "kn_workspace_bytes", "kn_cell_ids", "kn_bucket", "kn_eval_grouped", "kn_march", "kn_composite",
-           "kn_render", "kn_set_render_params", "kn_profile_enable", "kn_profile_read"]
+           "kn_render", "kn_march_stratified", "kn_render_stratified", "kn_set_render_params", "kn_profile_enable", "kn_profile_read"]
 
 
 class KnError(RuntimeError):
@@ -30,7 +30,8 @@ class KnError(RuntimeError):
 class SceneDesc(C.Structure):
     _fields_ = [("res", C.c_int32 * 3), ("aabb_min", C.c_float * 3), ("aabb_max", C.c_float * 3),
                 ("hidden", C.c_int32), ("L_pos", C.c_int32), ("L_dir", C.c_int32), ("wdtype", C.c_int32),
-                ("weights", C.c_void_p), ("occ_res", C.c_int32 * 3), ("occupancy", C.c_void_p)]
+                ("weights", C.c_void_p), ("occ_res", C.c_int32 * 3), ("occupancy", C.c_void_p),
+                ("cell_net", C.c_void_p), ("n_nets", C.c_int32)]
 
 
 class RenderStats(C.Structure):
@@ -81,6 +82,10 @@ def load_library(build_if_missing: bool = True):
     L.kn_composite.argtypes = [vp, vp, vp, vp, i64, f32, f32, C.POINTER(f32 * 3), vp, vp, vp]
     L.kn_render.argtypes = [vp, vp, vp, vp, i64, f32, f32, i32, f32, C.POINTER(f32 * 3), vp,
                             C.POINTER(RenderStats), vp, i64]
+    u32 = C.c_uint32
+    L.kn_march_stratified.argtypes = [vp, vp, vp, vp, i64, f32, f32, i32, u32, vp, i32, vp, vp, vp]
+    L.kn_render_stratified.argtypes = [vp, vp, vp, vp, i64, f32, f32, i32, f32, C.POINTER(f32 * 3), u32, vp,
+                                       C.POINTER(RenderStats), vp, i64]
     L.kn_set_render_params.argtypes = [i32, i32, i32]
     L.kn_profile_enable.argtypes = [C.c_int]
     L.kn_profile_read.argtypes = [C.POINTER(Profile), C.c_int]
@@ -134,9 +139,11 @@ def profile_read(reset: bool = True) -> dict:
 
 class Scene:
     """Device-resident KiloNeRF scene.  ``weights``: device tensor (N, P) of float32 / float16 /
-    bfloat16 in the canonical layout; ``occupancy``: device uint8 tensor (ox, oy, oz) or None."""
+    bfloat16 in the canonical layout; ``occupancy``: device uint8 tensor (ox, oy, oz) or None; ``cell_net``: None, or
+    for a sparse grid a device int32 tensor with one entry per cell (network index, -1 = no network); N is then the
+    number of rows of ``weights``."""
 
-    def __init__(self, res, aabb_min, aabb_max, hidden, weights, occupancy=None, L_pos=10, L_dir=4):
+    def __init__(self, res, aabb_min, aabb_max, hidden, weights, occupancy=None, L_pos=10, L_dir=4, cell_net=None):
         import torch
         self.L = load_library()
         wd = {torch.float32: KN_F32, torch.float16: KN_F16, torch.bfloat16: KN_BF16}.get(weights.dtype)
@@ -155,9 +162,14 @@ class Scene:
             d.occ_res[:] = list(occupancy.shape)
             d.occupancy = _ptr(occupancy, torch.uint8)
         self.N = int(res[0]) * int(res[1]) * int(res[2])
+        if cell_net is not None:
+            if cell_net.numel() != self.N:
+                raise KnError("cell_net must have one entry per cell")
+            d.cell_net = _ptr(cell_net, torch.int32)
+            d.n_nets = self.N = int(weights.shape[0])
         self.hidden = int(hidden)
         self.device = weights.device
-        self._keep = (weights, occupancy)     # scene creation reads them asynchronously on the stream
+        self._keep = (weights, occupancy, cell_net)     # scene creation reads them asynchronously on the stream
         h = C.c_void_p()
         _check(self.L.kn_scene_create(C.byref(d), _stream(), C.byref(h)), "kn_scene_create")
         self.h = h
@@ -260,21 +272,26 @@ class Scene:
                                            _ptr(ws), ws.numel()), "kn_extract_occupancy")
         return occ
 
-    def march(self, rays_o, rays_d, t_near, step, K, S=None, k_begin=None):
+    def march(self, rays_o, rays_d, t_near, step, K, S=None, k_begin=None, seed=None):
+        """``seed`` None: midpoint lattice (kn_march); else stratified sampling (kn_march_stratified)."""
         import torch
         R = rays_o.shape[0]
         S = int(K if S is None else S)
         out_k = torch.empty((R, S), dtype=torch.int32, device=self.device)
         cnt = torch.empty(R, dtype=torch.int32, device=self.device)
         nxt = torch.empty(R, dtype=torch.int32, device=self.device)
-        _check(self.L.kn_march(self.h, _stream(), _ptr(rays_o, torch.float32), _ptr(rays_d, torch.float32), R,
-                               float(t_near), float(step), int(K), _ptr(k_begin, allow_none=True), S, _ptr(out_k),
-                               _ptr(cnt), _ptr(nxt)), "kn_march")
+        head = (self.h, _stream(), _ptr(rays_o, torch.float32), _ptr(rays_d, torch.float32), R, float(t_near), float(step),
+                int(K))
+        tail = (_ptr(k_begin, allow_none=True), S, _ptr(out_k), _ptr(cnt), _ptr(nxt))
+        if seed is None:
+            _check(self.L.kn_march(*head, *tail), "kn_march")
+        else:
+            _check(self.L.kn_march_stratified(*head, int(seed), *tail), "kn_march_stratified")
         return out_k, cnt, nxt
 
     def render(self, rays_o, rays_d, t_near, step, K, term_eps=0.0, bg=(0.0, 0.0, 0.0), want_stats=False, out=None,
-               workspace=None):
-        """``workspace``: a uint8 device tensor of at least ``workspace_bytes(max_rays=R)`` bytes; by default one
+               workspace=None, seed=None):
+        """``seed`` None: midpoint lattice (kn_render); else stratified sampling (kn_render_stratified).  ``workspace``: a uint8 device tensor of at least ``workspace_bytes(max_rays=R)`` bytes; by default one
         cached workspace per scene is used.  Calls that are in flight at the same time (on different streams) need
         a workspace each."""
         import torch
@@ -283,10 +300,13 @@ class Scene:
         ws = self._workspace(max_rays=max(R, 1)) if workspace is None else workspace
         st = RenderStats()
         bgc = (C.c_float * 3)(*[float(v) for v in bg])
-        _check(self.L.kn_render(self.h, _stream(), _ptr(rays_o, torch.float32) if R else None,
-                                _ptr(rays_d, torch.float32) if R else None, R, float(t_near), float(step), int(K),
-                                float(term_eps), C.byref(bgc), _ptr(rgb) if R else None,
-                                C.byref(st) if want_stats else None, _ptr(ws), ws.numel()), "kn_render")
+        head = (self.h, _stream(), _ptr(rays_o, torch.float32) if R else None, _ptr(rays_d, torch.float32) if R else None,
+                R, float(t_near), float(step), int(K), float(term_eps), C.byref(bgc))
+        tail = (_ptr(rgb) if R else None, C.byref(st) if want_stats else None, _ptr(ws), ws.numel())
+        if seed is None:
+            _check(self.L.kn_render(*head, *tail), "kn_render")
+        else:
+            _check(self.L.kn_render_stratified(*head, int(seed), *tail), "kn_render_stratified")
         if want_stats:
             return rgb, {k: getattr(st, k) for k, _ in RenderStats._fields_}
         return rgb

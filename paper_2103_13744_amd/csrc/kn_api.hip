@@ -174,6 +174,15 @@ __global__ void k_zero_outside(const int32_t *__restrict__ perm, const int32_t *
     rgb[3 * idx] = rgb[3 * idx + 1] = rgb[3 * idx + 2] = 0.0f;
 }
 
+// the library's copy of a sparse grid's table: entries outside [0, n_nets) become -1 (no network)
+__global__ void k_copy_cell_net(const int32_t *__restrict__ in, int64_t cells, int32_t n_nets, int32_t *__restrict__ out)
+{
+    const int64_t c = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (c >= cells) return;
+    const int32_t v = in[c];
+    out[c] = (v >= 0 && v < n_nets) ? v : -1;
+}
+
 bool make_grid(const float bmin[3], const float bmax[3], const int32_t res[3], KnGrid &g)
 {
     for (int a = 0; a < 3; ++a) {
@@ -218,7 +227,12 @@ static int validate_desc(const kn_scene_desc *d)
     KnGrid g;
     if (!make_grid(d->aabb_min, d->aabb_max, d->res, g)) return KN_E_INVALID_ARG;
     const int64_t n = (int64_t)d->res[0] * d->res[1] * d->res[2];
-    if (n > 65535) return KN_E_UNSUPPORTED;
+    if (d->cell_net) { // sparse grid: many cells, the networks are what is limited
+        if (d->n_nets < 1) return KN_E_INVALID_ARG;
+        if (n > KN_MAX_CELLS || d->n_nets > 65535) return KN_E_UNSUPPORTED;
+    } else if (n > 65535) {
+        return KN_E_UNSUPPORTED;
+    }
     if (d->wdtype != KN_F32 && d->wdtype != KN_F16 && d->wdtype != KN_BF16) return KN_E_INVALID_ARG;
     if (d->hidden < 1 || d->L_pos < 0 || d->L_dir < 0) return KN_E_INVALID_ARG;
     if ((d->hidden != 32 && d->hidden != 64) || d->L_pos != 10 || d->L_dir != 4) return KN_E_UNSUPPORTED;
@@ -279,7 +293,9 @@ extern "C" int kn_scene_create(const kn_scene_desc *desc, void *stream, kn_scene
     kn_scene *sc = new (std::nothrow) kn_scene();
     if (!sc) return KN_E_INVALID_ARG;
     sc->desc = *desc;
-    sc->N = desc->res[0] * desc->res[1] * desc->res[2];
+    sc->cells = (int64_t)desc->res[0] * desc->res[1] * desc->res[2];
+    sc->N = desc->cell_net ? desc->n_nets : (int32_t)sc->cells;
+    sc->cell_net = nullptr;
     sc->P = kn_params_per_net(desc->hidden, desc->L_pos, desc->L_dir);
     sc->device = dev;
     make_grid(desc->aabb_min, desc->aabb_max, desc->res, sc->net_grid);
@@ -305,7 +321,18 @@ extern "C" int kn_scene_create(const kn_scene_desc *desc, void *stream, kn_scene
     }
     hipStream_t st = (hipStream_t)stream;
     int rc = KN_OK;
-    if (sc->has_occ) {
+    if (desc->cell_net) {
+        if (hipMalloc((void **)&sc->cell_net, (size_t)sc->cells * 4) != hipSuccess) {
+            rc = KN_E_HIP;
+        } else {
+            hipLaunchKernelGGL(k_copy_cell_net, dim3((unsigned)kn_div_up(sc->cells, 256)), dim3(256), 0, st, desc->cell_net,
+                               sc->cells, sc->N, sc->cell_net);
+            if (hipGetLastError() != hipSuccess) rc = KN_E_HIP;
+        }
+    }
+    if (rc != KN_OK) {
+        // (the clean-up below)
+    } else if (sc->has_occ) {
         make_grid(desc->aabb_min, desc->aabb_max, desc->occ_res, sc->occ_grid);
         const int64_t vox = (int64_t)desc->occ_res[0] * desc->occ_res[1] * desc->occ_res[2];
         const int64_t words = kn_div_up(vox, 32);
@@ -359,6 +386,7 @@ extern "C" int kn_scene_destroy(kn_scene *sc)
     if (sc->occ_bits) (void)hipFree(sc->occ_bits);
     if (sc->packed_w) (void)hipFree(sc->packed_w);
     if (sc->skip_dist) (void)hipFree(sc->skip_dist);
+    if (sc->cell_net) (void)hipFree(sc->cell_net);
     if (sc->mailbox[0].host) (void)hipHostFree((void *)sc->mailbox[0].host);
     delete sc;
     return KN_OK;
@@ -551,12 +579,13 @@ extern "C" int kn_extract_occupancy(const kn_scene *sc, void *stream, const int3
     for (int a = 0; a < 3; ++a) first[a] = ws.carve<int32_t>(sc->desc.res[a] + 1);
     if (!ws.ok()) return KN_E_WORKSPACE;
     job.net = sc->net_grid;
+    job.cell_net = sc->cell_net;
     for (int a = 0; a < 3; ++a) job.first[a] = first[a];
     job.tau = tau;
     job.occupancy = occupancy;
     // enough workgroups to fill the chip several times over, but at least some tens of tiles per wavefront
-    const int64_t tiles_per_cell = kn_div_up(KN_PROBES * kn_div_up(voxels, sc->N), KN_WAVE);
-    int64_t parts = kn_div_up(2048, sc->N);
+    const int64_t tiles_per_cell = kn_div_up(KN_PROBES * kn_div_up(voxels, sc->cells), KN_WAVE);
+    int64_t parts = kn_div_up(2048, sc->cells);
     if (parts > tiles_per_cell / 32) parts = tiles_per_cell / 32;
     if (parts < 1) parts = 1;
     job.parts = (int32_t)parts;

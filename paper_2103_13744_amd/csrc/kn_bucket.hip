@@ -35,14 +35,15 @@ __global__ void k_fill_i32(int32_t *p, int64_t n, int32_t v)
     if (i < n) p[i] = v;
 }
 
-__global__ void k_cell_ids(const float *__restrict__ pts, int64_t M, KnGrid g, int32_t *__restrict__ ids,
-                           int32_t *__restrict__ keys, int32_t N, int32_t *__restrict__ zero, int64_t n_zero)
+__global__ void k_cell_ids(const float *__restrict__ pts, int64_t M, KnGrid g, const int32_t *__restrict__ cell_net,
+                           int32_t *__restrict__ ids, int32_t *__restrict__ keys, int32_t N, int32_t *__restrict__ zero,
+                           int64_t n_zero)
 {
     int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i < n_zero) zero[i] = 0; // scratch counters of the sort that follows
     if (i >= M) return;
     float x = pts[3 * i], y = pts[3 * i + 1], z = pts[3 * i + 2];
-    int32_t id = kn_grid_index(g, x, y, z);
+    int32_t id = kn_net_of_cell(cell_net, kn_grid_index(g, x, y, z)); // Eq. 6, then the table of a sparse grid
     if (ids) ids[i] = id;
     if (keys) keys[i] = id < 0 ? N : id;
 }
@@ -525,7 +526,7 @@ extern "C" int kn_cell_ids(const kn_scene *sc, void *stream, const float *points
     if (M == 0) return KN_OK;
     dim3 grid;
     KN_TRY(launch_1d(M, 256, grid));
-    hipLaunchKernelGGL(k_cell_ids, grid, dim3(256), 0, (hipStream_t)stream, points, M, sc->net_grid, ids,
+    hipLaunchKernelGGL(k_cell_ids, grid, dim3(256), 0, (hipStream_t)stream, points, M, sc->net_grid, sc->cell_net, ids,
                        (int32_t *)nullptr, sc->N, (int32_t *)nullptr, (int64_t)0);
     KN_CHECK_LAUNCH();
     return KN_OK;
@@ -538,7 +539,8 @@ int kn_cell_keys(const kn_scene *sc, hipStream_t st, const float *points, int64_
     if (M == 0 && n_zero == 0) return KN_OK;
     dim3 grid;
     KN_TRY(launch_1d(M > n_zero ? M : n_zero, 256, grid));
-    hipLaunchKernelGGL(k_cell_ids, grid, dim3(256), 0, st, points, M, sc->net_grid, ids, keys, sc->N, zero, n_zero);
+    hipLaunchKernelGGL(k_cell_ids, grid, dim3(256), 0, st, points, M, sc->net_grid, sc->cell_net, ids, keys, sc->N, zero,
+                       n_zero);
     KN_CHECK_LAUNCH();
     return KN_OK;
 }

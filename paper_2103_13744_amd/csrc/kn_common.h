@@ -8,6 +8,7 @@
 #include "kilonerf.h"
 
 #define KN_WAVE 64
+#define KN_MAX_CELLS (1 << 24) // cells of a sparse network grid
 
 // Uniform grid over the scene AABB (Sec. 3.2).  `cell` is the fp32 quotient (b_max - b_min) / r
 // computed once on the host, so that Eq. 6 is evaluated as floor((x - b_min) / cell) with the
@@ -39,6 +40,8 @@ struct KnMailbox {
 struct kn_scene {
     kn_scene_desc desc;
     int32_t N;             // number of networks
+    int64_t cells;         // cells of the network grid (= N unless the grid is sparse)
+    int32_t *cell_net;     // device, sparse grids only (else nullptr): cell -> network index in [0, N) or -1
     int64_t P;             // parameters per network
     int device;
     KnGrid net_grid;
@@ -114,12 +117,44 @@ __device__ __forceinline__ int32_t kn_grid_index(const KnGrid &g, float x, float
     return ((int32_t)fx * g.res[1] + (int32_t)fy) * g.res[2] + (int32_t)fz;
 }
 
-// Lattice point k of a ray (Sec. 3.4): t_k = t_near + (k + 1/2) step, x = o + t_k d.
+// Network of a cell: the cell itself on a dense grid, the table's entry (-1 = none) on a sparse one.
+__device__ __forceinline__ int32_t kn_net_of_cell(const int32_t *__restrict__ cell_net, int32_t cell)
+{
+    return (cell_net != nullptr && cell >= 0) ? cell_net[cell] : cell;
+}
+
+// Stratified sampling (Sec. 3.3): lattice point k of a ray sits at offset u in [0, 1) of its interval,
+// u = (mix(mix(mix(seed) + ray) ^ k) >> 8) * 2^-24 with the 32-bit finalizer of MurmurHash3 as mix.  The host
+// passes seed_key = mix(seed); a kernel forms ray_key = mix(seed_key + ray) once per ray.
+__host__ __device__ __forceinline__ uint32_t kn_mix32(uint32_t v)
+{
+    v ^= v >> 16;
+    v *= 0x85ebca6bu;
+    v ^= v >> 13;
+    v *= 0xc2b2ae35u;
+    v ^= v >> 16;
+    return v;
+}
+__device__ __forceinline__ float kn_strat_offset(uint32_t ray_key, int32_t k)
+{
+    return (float)(kn_mix32(ray_key ^ (uint32_t)k) >> 8) * (1.0f / 16777216.0f);
+}
+
+// Lattice point k of a ray (Sec. 3.4): t_k = t_near + (k + offset) step, x = o + t_k d; offset = 1/2, or the
+// stratified draw of (ray, k).
+template <bool STRAT = false>
+__device__ __forceinline__ float kn_lattice_t(float t_near, float step, int32_t k, uint32_t ray_key = 0u)
+{
+    float off = 0.5f;
+    if constexpr (STRAT) off = kn_strat_offset(ray_key, k);
+    return fmaf((float)k + off, step, t_near);
+}
+template <bool STRAT = false>
 __device__ __forceinline__ void kn_lattice_point(float ox, float oy, float oz, float dx, float dy,
                                                  float dz, float t_near, float step, int32_t k,
-                                                 float &x, float &y, float &z)
+                                                 float &x, float &y, float &z, uint32_t ray_key = 0u)
 {
-    float t = fmaf((float)k + 0.5f, step, t_near);
+    float t = kn_lattice_t<STRAT>(t_near, step, k, ray_key);
     x = fmaf(t, dx, ox);
     y = fmaf(t, dy, oy);
     z = fmaf(t, dz, oz);
@@ -215,6 +250,11 @@ struct KnSampleSrc {
     float t_near, step;
     int32_t kbits;
     float *out4;           // render: (r, g, b, sigma) per sample, 16 bytes each; nullptr = separate sigma / rgb arrays
+    // Stratified sampling (render only): lattice points sit at their drawn offsets, and the density that goes to
+    // out4 is scaled by delta_k / step, delta_k = t_(k+1) - t_k, so that the blend's exp(-sigma * step) is Eq. 4
+    // with the sample's own delta.
+    int32_t strat;         // 0 = midpoint lattice
+    uint32_t seed_key;     // kn_mix32(seed)
 };
 
 int kn_mlp_launch(const kn_scene *sc, hipStream_t st, const KnSampleSrc &src, const KnBucketOut &b,

@@ -173,8 +173,8 @@ __global__ void __launch_bounds__(F32_WAVES *KN_WAVE) __attribute__((amdgpu_wave
     for (int t = t_lo; t < t_hi; ++t) {
         const KnTile tl = dsc_next;
         const int32_t idx = idx_next;
-        float x, y, z, dx, dy, dz;
-        kn_load_sample(src, idx, x, y, z, dx, dy, dz);
+        float x, y, z, dx, dy, dz, dscale;
+        kn_load_sample(src, idx, x, y, z, dx, dy, dz, dscale);
         dsc_next = descriptor(t + 1);
         idx_next = sample_index(dsc_next);
         if (tl.net != net_cur) { // uniform
@@ -277,7 +277,7 @@ __global__ void __launch_bounds__(F32_WAVES *KN_WAVE) __attribute__((amdgpu_wave
         __builtin_amdgcn_wave_barrier(); // the staging buffer is rewritten by the next iteration
 
         if (lane < tl.len) {
-            const float sg = fmaxf(out[3], 0.0f);
+            const float sg = fmaxf(out[3], 0.0f) * dscale;
             float col[3];
 #pragma unroll
             for (int c = 0; c < 3; ++c) col[c] = 1.0f / (1.0f + expf(-out[c]));
@@ -342,7 +342,7 @@ __global__ void __launch_bounds__(F32_WAVES *KN_WAVE) __attribute__((amdgpu_wave
         int64_t voxel;
         int32_t probe;
         kn_probe_point(job, box, min(p, box.points - 1), x, y, z, voxel, probe);
-        const int32_t net = kn_grid_index(job.net, x, y, z);
+        const int32_t net = kn_net_of_cell(job.cell_net, kn_grid_index(job.net, x, y, z));
         bool todo = active && net >= 0;
         float sg = 0.0f;
         *(f4 *)&stage[wave][lane][0] = (f4){x, y, z, 0.0f};
@@ -463,7 +463,7 @@ int kn_probe_f32_launch(const kn_scene *sc, hipStream_t st, const KnProbeJob &jo
 {
     const int H = sc->desc.hidden;
     if (H != 32 && H != 64) return KN_E_UNSUPPORTED;
-    const dim3 grid((unsigned)((int64_t)sc->N * job.parts)), block(F32_WAVES * KN_WAVE);
+    const dim3 grid((unsigned)(sc->cells * job.parts)), block(F32_WAVES * KN_WAVE);
     const float *w = (const float *)sc->packed_w;
     if (H == 32)
         hipLaunchKernelGGL(k_probe_f32<32>, grid, block, 0, st, w, job);

@@ -254,7 +254,9 @@ template <bool BF> __device__ __forceinline__ u4 encode_direction(float rev, u4 
 
 // Weights stay in registers: 14 blocks (56 VGPRs) for H = 32, three wavefronts per SIMD; 40 blocks (160 VGPRs) for
 // H = 64, two wavefronts per SIMD (the matrix-core operands are read straight from the register file either way).
-template <int H, bool BF, int WAVES, bool WRAP>
+// STRAT (render with stratified sampling): the lattice points sit at their drawn offsets and the density is
+// scaled by delta_k / step on the way out (see KnSampleSrc).
+template <int H, bool BF, int WAVES, bool WRAP, bool STRAT>
 __global__ void __launch_bounds__(WAVES *KN_WAVE) __attribute__((amdgpu_waves_per_eu(H == 32 ? 3 : 2, H == 32 ? 3 : 2)))
     k_mlp_mfma(const uint16_t *__restrict__ packed, KnSampleSrc src, const int32_t *__restrict__ perm,
                const KnTile *__restrict__ tiles, const int32_t *__restrict__ n_tiles, float *__restrict__ sigma,
@@ -342,8 +344,18 @@ __global__ void __launch_bounds__(WAVES *KN_WAVE) __attribute__((amdgpu_waves_pe
         for (int c = 0; c < 3; ++c) { q.a[c] = pa[c]; q.b[c] = pb[c]; }
         return q;
     };
-    auto finish = [&](const Raw &q, uint32_t r, float &x, float &y, float &z) {
-        if (from_rays)
+    auto finish = [&](const Raw &q, uint32_t r, float &x, float &y, float &z, float &dscale) {
+        dscale = 1.0f;
+        if constexpr (STRAT) {
+            const int32_t k = (int32_t)(r & ((1u << src.kbits) - 1u));
+            const uint32_t ray_key = kn_mix32(src.seed_key + (r >> src.kbits));
+            const float t0 = kn_lattice_t<true>(src.t_near, src.step, k, ray_key);
+            const float t1 = kn_lattice_t<true>(src.t_near, src.step, k + 1, ray_key);
+            x = fmaf(t0, q.b[0], q.a[0]);
+            y = fmaf(t0, q.b[1], q.a[1]);
+            z = fmaf(t0, q.b[2], q.a[2]);
+            dscale = (t1 - t0) / src.step;
+        } else if (from_rays)
             kn_lattice_point(q.a[0], q.a[1], q.a[2], q.b[0], q.b[1], q.b[2], src.t_near, src.step,
                              (int32_t)(r & ((1u << src.kbits) - 1u)), x, y, z);
         else { x = q.a[0]; y = q.a[1]; z = q.a[2]; }
@@ -394,8 +406,8 @@ __global__ void __launch_bounds__(WAVES *KN_WAVE) __attribute__((amdgpu_waves_pe
         }
         const bool active = lane < tl.len;
         const int32_t idx = idx0;
-        float nx, ny, nz;
-        finish(raw0, rec0, nx, ny, nz);
+        float nx, ny, nz, dscale;
+        finish(raw0, rec0, nx, ny, nz, dscale);
         const float ndx = raw0.b[0], ndy = raw0.b[1], ndz = raw0.b[2];
         write_out(); // after the loads of the last iteration have been waited for, before new ones are issued
         // next levels for the following tiles (their operands were loaded one iteration ago)
@@ -490,7 +502,8 @@ __global__ void __launch_bounds__(WAVES *KN_WAVE) __attribute__((amdgpu_waves_pe
         {
             f4 out = outs[0];
             if constexpr (!SHARED_OUT) out = g == 0 ? outs[0] : (g == 1 ? outs[1] : (g == 2 ? outs[2] : outs[3]));
-            const float sg = fmaxf(out[3], 0.0f);
+            float sg = fmaxf(out[3], 0.0f);
+            if constexpr (STRAT) sg *= dscale;
             float col[3];
 #pragma unroll
             for (int c = 0; c < 3; ++c)
@@ -552,7 +565,7 @@ __global__ void __launch_bounds__(WAVES *KN_WAVE) __attribute__((amdgpu_waves_pe
         int64_t voxel;
         int32_t probe;
         kn_probe_point(job, box, min(p, box.points - 1), x, y, z, voxel, probe);
-        const int32_t net = kn_grid_index(job.net, x, y, z);
+        const int32_t net = kn_net_of_cell(job.cell_net, kn_grid_index(job.net, x, y, z));
         bool todo = active && net >= 0;
         float sg = 0.0f;
         {
@@ -642,7 +655,8 @@ __global__ void __launch_bounds__(WAVES *KN_WAVE)
         const KnTile tl = tiles[t];
         const int32_t idx = perm[tl.start + min(lane, tl.len - 1)];
         float x, y, z, dx, dy, dz;
-        kn_load_sample(src, idx, x, y, z, dx, dy, dz);
+        float dscale; // (explicit points: always 1)
+        kn_load_sample(src, idx, x, y, z, dx, dy, dz, dscale);
         {
             const float p3[3] = {x, y, z}, d3[3] = {dx, dy, dz};
 #pragma unroll
@@ -795,12 +809,12 @@ int launch(const kn_scene *sc, hipStream_t st, const KnSampleSrc &src, const KnB
     float reach = 0.0f;
     for (int a = 0; a < 3; ++a)
         reach = fmaxf(reach, fmaxf(fabsf(sc->desc.aabb_min[a]), fabsf(sc->desc.aabb_max[a])));
-    if (reach * (256.0f * INV_2PI) < 250.0f)
-        hipLaunchKernelGGL((k_mlp_mfma<H, BF, WAVES, false>), dim3((unsigned)blocks), dim3(WAVES * KN_WAVE), 0, st,
-                           (const uint16_t *)sc->packed_w, src, b.perm, b.tiles, b.n_tiles, sigma, rgb);
-    else
-        hipLaunchKernelGGL((k_mlp_mfma<H, BF, WAVES, true>), dim3((unsigned)blocks), dim3(WAVES * KN_WAVE), 0, st,
-                           (const uint16_t *)sc->packed_w, src, b.perm, b.tiles, b.n_tiles, sigma, rgb);
+    const bool wrap = !(reach * (256.0f * INV_2PI) < 250.0f);
+    const bool strat = src.strat != 0 && src.points == nullptr;
+    auto kernel = wrap ? (strat ? k_mlp_mfma<H, BF, WAVES, true, true> : k_mlp_mfma<H, BF, WAVES, true, false>)
+                       : (strat ? k_mlp_mfma<H, BF, WAVES, false, true> : k_mlp_mfma<H, BF, WAVES, false, false>);
+    hipLaunchKernelGGL(kernel, dim3((unsigned)blocks), dim3(WAVES * KN_WAVE), 0, st, (const uint16_t *)sc->packed_w, src, b.perm,
+                       b.tiles, b.n_tiles, sigma, rgb);
     KN_CHECK_LAUNCH();
     return KN_OK;
 }
@@ -839,7 +853,7 @@ int kn_probe_mfma_launch(const kn_scene *sc, hipStream_t st, const KnProbeJob &j
     for (int a = 0; a < 3; ++a)
         reach = fmaxf(reach, fmaxf(fabsf(sc->desc.aabb_min[a]), fabsf(sc->desc.aabb_max[a])));
     const bool wrap = !(reach * (256.0f * INV_2PI) < 250.0f);
-    const dim3 grid((unsigned)((int64_t)sc->N * job.parts)), block(MLP_WAVES * KN_WAVE);
+    const dim3 grid((unsigned)(sc->cells * job.parts)), block(MLP_WAVES * KN_WAVE);
     const uint16_t *w = (const uint16_t *)sc->packed_w;
 #define KN_PROBE_CASE(HH, BB, WW)                                                                          \
     if (H == HH && bf == BB && wrap == WW)                                                                  \

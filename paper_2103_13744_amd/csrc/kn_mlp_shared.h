@@ -5,10 +5,12 @@
 
 // Fetch position and direction of sorted-list entry `idx`: either from explicit arrays, or by
 // rebuilding the lattice point of a render sample from its packed (ray, k) record with the same
-// fused multiply-adds the marching kernel used.
+// fused multiply-adds the marching kernel used.  dscale: the factor on the density that leaves the kernel
+// (delta_k / step with stratified sampling, else 1).
 __device__ __forceinline__ void kn_load_sample(const KnSampleSrc &s, int32_t idx, float &x, float &y, float &z,
-                                               float &dx, float &dy, float &dz)
+                                               float &dx, float &dy, float &dz, float &dscale)
 {
+    dscale = 1.0f;
     if (s.points) {
         const float *p = s.points + 3 * (int64_t)idx;
         const float *d = s.dirs + 3 * (int64_t)idx;
@@ -21,6 +23,16 @@ __device__ __forceinline__ void kn_load_sample(const KnSampleSrc &s, int32_t idx
         const float *o = s.rays_o + 3 * (int64_t)ray;
         const float *d = s.rays_d + 3 * (int64_t)ray;
         dx = d[0]; dy = d[1]; dz = d[2];
-        kn_lattice_point(o[0], o[1], o[2], dx, dy, dz, s.t_near, s.step, k, x, y, z);
+        if (s.strat) {
+            const uint32_t ray_key = kn_mix32(s.seed_key + ray);
+            const float t0 = kn_lattice_t<true>(s.t_near, s.step, k, ray_key);
+            const float t1 = kn_lattice_t<true>(s.t_near, s.step, k + 1, ray_key);
+            x = fmaf(t0, dx, o[0]);
+            y = fmaf(t0, dy, o[1]);
+            z = fmaf(t0, dz, o[2]);
+            dscale = (t1 - t0) / s.step;
+        } else {
+            kn_lattice_point(o[0], o[1], o[2], dx, dy, dz, s.t_near, s.step, k, x, y, z);
+        }
     }
 }

@@ -17,6 +17,7 @@
 struct KnProbeJob {
     KnGrid occ;              // the grid being filled
     KnGrid net;              // the network grid
+    const int32_t *cell_net; // device, sparse network grids: cell -> network or -1; nullptr on a dense grid
     const int32_t *first[3]; // device, net.res[a] + 1 entries per axis
     int32_t parts;           // workgroups per network cell
     float tau;

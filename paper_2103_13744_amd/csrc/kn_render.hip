@@ -35,7 +35,14 @@ struct MarchParams {
     int32_t net_shift[3];
     float t_near, step;
     int32_t K;
+    const int32_t *cell_net; // sparse network grid: cell -> network or -1 (kernels built with OPT_SPARSE read it)
+    uint32_t seed_key;       // stratified sampling: kn_mix32(seed) (kernels built with OPT_STRAT use it)
 };
+
+// Variants of the marching kernels, chosen at compile time so that the plain path carries none of their cost:
+// a sparse network grid (a table look-up per kept point; points in cells without a network are dropped) and
+// stratified sampling (lattice points at their drawn offsets instead of the middle of their intervals).
+constexpr int OPT_SPARSE = 1, OPT_STRAT = 2;
 
 // One axis of Eq. 6 without the division when the result cannot depend on it: u' = rel * (1/cell)
 // differs from the correctly rounded quotient by a few ulp; only when u' sits that close to an
@@ -132,21 +139,6 @@ __device__ __forceinline__ void clip_ray(const KnGrid &g, const float o[3], cons
     k_hi = (int32_t)b;
 }
 
-// Exact test of one lattice point (Sec. 3.4): inside the AABB and in an occupied voxel.  The
-// occupancy voxel is looked up first; Eq. 6 for the network grid is only evaluated for points
-// that pass it.  cell = network id of a kept point.
-__device__ __forceinline__ bool sample_kept(const MarchParams &p, const GridFast &gn, const GridFast &go, float x, float y,
-                                            float z, int32_t &cell)
-{
-    if (p.has_occ) {
-        const int32_t v = grid_index_fast(go, x, y, z);
-        if (v < 0) return false;
-        if (!((p.occ_bits[(uint32_t)v >> 5] >> (v & 31)) & 1u)) return false;
-    }
-    cell = grid_index_fast(gn, x, y, z);
-    return cell >= 0;
-}
-
 // Jump length bookkeeping shared by the two users of the skip field.  A point whose block has
 // Chebyshev distance dist >= 2 to the nearest occupied block lies in an empty block, and so does
 // every point within Euclidean distance (dist-1) * (shortest block edge) of it, minus a rounding
@@ -154,12 +146,14 @@ __device__ __forceinline__ bool sample_kept(const MarchParams &p, const GridFast
 struct SkipJump {
     float a, b;
     bool use;
-    __device__ __forceinline__ SkipJump(const MarchParams &p, const float o[3], const float d[3])
+    // strat: with stratified sampling point k + j lies up to j + 1 steps from point k, one more than on the
+    // midpoint lattice
+    __device__ __forceinline__ SkipJump(const MarchParams &p, const float o[3], const float d[3], bool strat)
     {
         const float dlen = sqrtf(d[0] * d[0] + d[1] * d[1] + d[2] * d[2]);
         const float inv_step_len = 1.0f / (p.step * dlen); // 1 / distance covered by one lattice step
         a = p.skip_edge_min * inv_step_len;
-        b = (p.skip_margin + 1e-6f * (fabsf(o[0]) + fabsf(o[1]) + fabsf(o[2]))) * inv_step_len + 1.0f;
+        b = (p.skip_margin + 1e-6f * (fabsf(o[0]) + fabsf(o[1]) + fabsf(o[2]))) * inv_step_len + (strat ? 2.0f : 1.0f);
         use = p.skip_dist != nullptr && isfinite(inv_step_len);
     }
     __device__ __forceinline__ int32_t jump(int32_t dist) const { return (int32_t)fmaxf(floorf((float)(dist - 1) * a - b), 0.0f); }
@@ -179,15 +173,17 @@ __device__ __forceinline__ int32_t skip_lookup(const MarchParams &p, float x, fl
 
 // One thread walks a ray through provably empty space: returns the first index in [k, k_hi) whose
 // point is not known to be empty (or k_hi).  No index it passes over can be a kept sample.
+template <int OPT>
 __device__ __forceinline__ int32_t skip_to_content(const MarchParams &p, const GridFast &go, const float o[3],
-                                                   const float d[3], int32_t k, int32_t k_hi)
+                                                   const float d[3], int32_t k, int32_t k_hi, uint32_t ray_key)
 {
+    constexpr bool STRAT = (OPT & OPT_STRAT) != 0;
     if (k >= k_hi) return k_hi; // the ray misses the content box: nothing to walk through
-    const SkipJump sj(p, o, d);
+    const SkipJump sj(p, o, d, STRAT);
     if (!sj.use) return k;
     while (k < k_hi) {
         float x, y, z;
-        kn_lattice_point(o[0], o[1], o[2], d[0], d[1], d[2], p.t_near, p.step, k, x, y, z);
+        kn_lattice_point<STRAT>(o[0], o[1], o[2], d[0], d[1], d[2], p.t_near, p.step, k, x, y, z, ray_key);
         const int32_t dist = skip_lookup(p, x, y, z);
         if (dist >= 2) {
             k += 1 + sj.jump(dist);
@@ -204,15 +200,16 @@ __device__ __forceinline__ int32_t skip_to_content(const MarchParams &p, const G
 // the same arguments; gl = lane index inside the group).  Collects up to S kept lattice indices in
 // [k, k_hi), in ascending order, through emit(j, kk, cell).  Returns the number collected and
 // leaves in k the index to resume at (>= k_hi: the ray is exhausted).
-template <typename Emit>
+template <int OPT, typename Emit>
 __device__ __forceinline__ int32_t march_group(const MarchParams &p, const GridFast &gn, const GridFast &go,
                                                const float o[3], const float d[3], int32_t &k, int32_t k_hi, int32_t S,
-                                               int gl, Emit emit)
+                                               int gl, uint32_t ray_key, Emit emit)
 {
+    constexpr bool STRAT = (OPT & OPT_STRAT) != 0, SPARSE = (OPT & OPT_SPARSE) != 0;
     const int lane = threadIdx.x & (KN_WAVE - 1);
     const int gshift = lane & ~(MARCH_G - 1);
     const uint32_t gmask = (MARCH_G == 32) ? 0xffffffffu : ((1u << MARCH_G) - 1u);
-    const SkipJump sj(p, o, d);
+    const SkipJump sj(p, o, d, STRAT);
     int32_t n = 0;
     constexpr int SKIP_SHIFT = 2;
     static_assert((1 << SKIP_SHIFT) == KN_SKIP_BLOCK, "skip blocks are 4 voxels wide");
@@ -238,7 +235,7 @@ __device__ __forceinline__ int32_t march_group(const MarchParams &p, const GridF
             word[c] = 0xffffffffu;
             dist[c] = 0;
             if (kk[c] < k_hi) {
-                kn_lattice_point(o[0], o[1], o[2], d[0], d[1], d[2], p.t_near, p.step, kk[c], x[c], y[c], z[c]);
+                kn_lattice_point<STRAT>(o[0], o[1], o[2], d[0], d[1], d[2], p.t_near, p.step, kk[c], x[c], y[c], z[c], ray_key);
                 if (p.has_occ) {
                     const bool in = grid_coords_fast(go, x[c], y[c], z[c], ix[c], iy[c], iz[c]);
                     vox[c] = in ? (ix[c] * go.res1 + iy[c]) * go.res2 + iz[c] : -1;
@@ -262,6 +259,7 @@ __device__ __forceinline__ int32_t march_group(const MarchParams &p, const GridF
                                       (iz[c] >> p.net_shift[2]);
                         else
                             cell[c] = grid_index_fast(gn, x[c], y[c], z[c]);
+                        if constexpr (SPARSE) cell[c] = kn_net_of_cell(p.cell_net, cell[c]); // the network, or none
                         kept[c] = cell[c] >= 0;
                     }
                     reach[c] = kept[c] ? kk[c] : kk[c] + 1;
@@ -301,6 +299,7 @@ __device__ __forceinline__ int32_t march_group(const MarchParams &p, const GridF
 
 // ---------------------------------------------------------------------------------------------
 // stage kernel behind kn_march: MARCH_G lanes per ray, explicit output arrays
+template <int OPT>
 __global__ void __launch_bounds__(256)
     k_march_stage(MarchParams p, const float *__restrict__ rays_o, const float *__restrict__ rays_d, int64_t R,
                   const int32_t *__restrict__ k_begin, int32_t S, int32_t *__restrict__ out_k, int32_t *__restrict__ out_count,
@@ -316,7 +315,8 @@ __global__ void __launch_bounds__(256)
     clip_ray(p.content, o, d, p.t_near, p.step, p.K, k_lo, k_hi);
     int32_t k = max(k_begin ? max(k_begin[r], 0) : 0, k_lo);
     int32_t *row = out_k + r * S;
-    const int32_t n = march_group(p, gn, go, o, d, k, k_hi, S, gl, [&](int j, int32_t kk, int32_t) { row[j] = kk; });
+    const uint32_t ray_key = kn_mix32(p.seed_key + (uint32_t)r);
+    const int32_t n = march_group<OPT>(p, gn, go, o, d, k, k_hi, S, gl, ray_key, [&](int j, int32_t kk, int32_t) { row[j] = kk; });
     for (int32_t j = n + gl; j < S; j += MARCH_G) row[j] = -1;
     if (gl == 0) {
         out_count[r] = n;
@@ -353,6 +353,7 @@ __device__ __forceinline__ int32_t prefix_of_block_sums(const int32_t *__restric
 
 // clip every ray against the AABB and walk it to the first lattice point near content; rays that
 // cannot produce a sample get the background right away.  Writes per-block counts of live rays.
+template <int OPT>
 __global__ void __launch_bounds__(RAY_BLOCK)
     k_render_init(MarchParams p, const float *__restrict__ rays_o, const float *__restrict__ rays_d, int64_t R, RayState s,
                   int32_t *__restrict__ alive, int32_t *__restrict__ blk_sum, float bg0, float bg1, float bg2,
@@ -370,7 +371,7 @@ __global__ void __launch_bounds__(RAY_BLOCK)
         int32_t k_lo, k_hi;
         clip_ray(p.content, o, d, p.t_near, p.step, p.K, k_lo, k_hi);
         // walk through provably empty space up to the first lattice point that is near occupied blocks
-        k_lo = skip_to_content(p, make_fast(p.occ), o, d, k_lo, k_hi);
+        k_lo = skip_to_content<OPT>(p, make_fast(p.occ), o, d, k_lo, k_hi, kn_mix32(p.seed_key + (uint32_t)r));
         s.k_next[r] = k_lo;
         s.k_end[r] = k_hi;
         lives = k_lo < k_hi ? 1 : 0;
@@ -446,7 +447,7 @@ __global__ void __launch_bounds__(RAY_BLOCK)
 // live_out / alive_out.  blk_off comes from k_sum_partials (prefix sums of the survivor counts that the blend of
 // the same 16-row groups left).
 // HASH: the per-network counters are a hash table (large grids), else one counter per network.
-template <bool HASH>
+template <bool HASH, int OPT>
 __global__ void __launch_bounds__(256)
     k_march_wave(MarchParams p, const float *__restrict__ rays_o, const float *__restrict__ rays_d,
                  const int32_t *__restrict__ live, const int32_t *__restrict__ alive, const int32_t *__restrict__ ctl,
@@ -516,7 +517,8 @@ __global__ void __launch_bounds__(256)
         const int32_t k_hi = s.k_end[r];
         int32_t *kr = row_keys + (int64_t)i * S;
         uint32_t *rr = row_rec + (int64_t)i * S;
-        const int32_t n = march_group(p, gn, go, o, d, k, k_hi, S, gl, [&](int j, int32_t kk, int32_t cell) {
+        const uint32_t ray_key = kn_mix32(p.seed_key + (uint32_t)r);
+        const int32_t n = march_group<OPT>(p, gn, go, o, d, k, k_hi, S, gl, ray_key, [&](int j, int32_t kk, int32_t cell) {
             kr[j] = cell;
             rr[j] = ((uint32_t)r << kbits) | (uint32_t)kk;
             count(cell);
@@ -901,9 +903,11 @@ __global__ void k_composite_stage(const float *__restrict__ sigma, const float *
     if (n_used) n_used[r] = used;
 }
 
-MarchParams make_params(const kn_scene *sc, float t_near, float step, int32_t K)
+MarchParams make_params(const kn_scene *sc, float t_near, float step, int32_t K, const uint32_t *seed = nullptr)
 {
     MarchParams p;
+    p.cell_net = sc->cell_net;
+    p.seed_key = seed ? kn_mix32(*seed) : 0u;
     p.net = sc->net_grid;
     p.occ = sc->has_occ ? sc->occ_grid : sc->net_grid;
     p.content = sc->content_box;
@@ -948,6 +952,28 @@ int g_slots_per_ray = DEFAULT_SLOTS;
 int g_wave_growth = DEFAULT_GROWTH;
 
 bool finite_pos(float v) { return isfinite(v) && v > 0.0f; }
+
+// kernel variants for a scene and a sampling mode
+int march_options(const kn_scene *sc, const uint32_t *seed) { return (sc->cell_net ? OPT_SPARSE : 0) | (seed ? OPT_STRAT : 0); }
+using MarchStageFn = decltype(&k_march_stage<0>);
+using RenderInitFn = decltype(&k_render_init<0>);
+using MarchWaveFn = decltype(&k_march_wave<false, 0>);
+MarchStageFn march_stage_kernel(int opt)
+{
+    static const MarchStageFn table[4] = {k_march_stage<0>, k_march_stage<1>, k_march_stage<2>, k_march_stage<3>};
+    return table[opt & 3];
+}
+RenderInitFn render_init_kernel(int opt)
+{
+    return (opt & OPT_STRAT) ? k_render_init<OPT_STRAT> : k_render_init<0>; // the table of a sparse grid plays no role here
+}
+MarchWaveFn march_wave_kernel(bool hash, int opt)
+{
+    static const MarchWaveFn table[2][4] = {
+        {k_march_wave<false, 0>, k_march_wave<false, 1>, k_march_wave<false, 2>, k_march_wave<false, 3>},
+        {k_march_wave<true, 0>, k_march_wave<true, 1>, k_march_wave<true, 2>, k_march_wave<true, 3>}};
+    return table[hash ? 1 : 0][opt & 3];
+}
 
 } // namespace
 
@@ -1054,19 +1080,34 @@ int64_t kn_render_ws_bytes(const kn_scene *sc, int64_t R)
     return c.used + kn_group_ws_bytes(slots, sc->N);
 }
 
-extern "C" int kn_march(const kn_scene *sc, void *stream, const float *rays_o, const float *rays_d, int64_t R, float t_near,
-                        float step, int32_t K, const int32_t *k_begin, int32_t S, int32_t *out_k, int32_t *out_count,
-                        int32_t *out_k_next)
+static int march_impl(const kn_scene *sc, void *stream, const float *rays_o, const float *rays_d, int64_t R, float t_near,
+                      float step, int32_t K, const uint32_t *seed, const int32_t *k_begin, int32_t S, int32_t *out_k,
+                      int32_t *out_count, int32_t *out_k_next)
 {
     if (!sc || R < 0 || K < 0 || S < 1 || !isfinite(t_near) || !finite_pos(step)) return KN_E_INVALID_ARG;
     if (R > 0 && (!rays_o || !rays_d || !out_k || !out_count)) return KN_E_INVALID_ARG;
     if (R == 0) return KN_OK;
     const int64_t blocks = kn_div_up(R * MARCH_G, 256);
     if (blocks > 0x7fffffffLL) return KN_E_UNSUPPORTED;
-    hipLaunchKernelGGL(k_march_stage, dim3((unsigned)blocks), dim3(256), 0, (hipStream_t)stream,
-                       make_params(sc, t_near, step, K), rays_o, rays_d, R, k_begin, S, out_k, out_count, out_k_next);
+    if (seed && R > 0xffffffffLL) return KN_E_UNSUPPORTED; // ray numbers are 32-bit
+    hipLaunchKernelGGL(march_stage_kernel(march_options(sc, seed)), dim3((unsigned)blocks), dim3(256), 0, (hipStream_t)stream,
+                       make_params(sc, t_near, step, K, seed), rays_o, rays_d, R, k_begin, S, out_k, out_count, out_k_next);
     KN_CHECK_LAUNCH();
     return KN_OK;
+}
+
+extern "C" int kn_march(const kn_scene *sc, void *stream, const float *rays_o, const float *rays_d, int64_t R, float t_near,
+                        float step, int32_t K, const int32_t *k_begin, int32_t S, int32_t *out_k, int32_t *out_count,
+                        int32_t *out_k_next)
+{
+    return march_impl(sc, stream, rays_o, rays_d, R, t_near, step, K, nullptr, k_begin, S, out_k, out_count, out_k_next);
+}
+
+extern "C" int kn_march_stratified(const kn_scene *sc, void *stream, const float *rays_o, const float *rays_d, int64_t R,
+                                   float t_near, float step, int32_t K, uint32_t seed, const int32_t *k_begin, int32_t S,
+                                   int32_t *out_k, int32_t *out_count, int32_t *out_k_next)
+{
+    return march_impl(sc, stream, rays_o, rays_d, R, t_near, step, K, &seed, k_begin, S, out_k, out_count, out_k_next);
 }
 
 extern "C" int kn_composite(void *stream, const float *sigma, const float *rgb, const int32_t *offsets, int64_t R,
@@ -1082,9 +1123,9 @@ extern "C" int kn_composite(void *stream, const float *sigma, const float *rgb, 
     return KN_OK;
 }
 
-extern "C" int kn_render(const kn_scene *sc, void *stream, const float *rays_o, const float *rays_d, int64_t R, float t_near,
-                         float step, int32_t K, float term_eps, const float bg[3], float *rgb_out, kn_render_stats *stats,
-                         void *workspace, int64_t workspace_bytes)
+static int render_impl(const kn_scene *sc, void *stream, const float *rays_o, const float *rays_d, int64_t R, float t_near,
+                       float step, int32_t K, float term_eps, const float bg[3], const uint32_t *seed, float *rgb_out,
+                       kn_render_stats *stats, void *workspace, int64_t workspace_bytes)
 {
     if (!sc || R < 0 || K < 0 || !bg || !isfinite(t_near) || !finite_pos(step) || !(term_eps >= 0.0f && term_eps < 1.0f))
         return KN_E_INVALID_ARG;
@@ -1110,7 +1151,8 @@ extern "C" int kn_render(const kn_scene *sc, void *stream, const float *rays_o, 
     kn_group_carve(ws, budget, sc->N, &gw);
     if (!ws.ok()) return KN_E_WORKSPACE;
 
-    const MarchParams p = make_params(sc, t_near, step, K);
+    const MarchParams p = make_params(sc, t_near, step, K, seed);
+    const int opt = march_options(sc, seed);
     RayState rs{w.T, w.C, w.k_next, w.k_end};
     const unsigned rblocks = (unsigned)kn_div_up(R, RAY_BLOCK);
     const int64_t n_hist = 2 * (int64_t)sc->N; // histogram and fill cursors of the sample grouping
@@ -1127,7 +1169,7 @@ extern "C" int kn_render(const kn_scene *sc, void *stream, const float *rays_o, 
     int first_samples = g_first_wave_samples > 0 ? g_first_wave_samples : (K / 16 > DEFAULT_FIRST_WAVE ? K / 16 : DEFAULT_FIRST_WAVE);
     if (first_samples > g_slots_per_ray) first_samples = g_slots_per_ray;
     const WaveSchedule sched{first_samples, g_wave_growth, K > 0 ? K : 1, budget};
-    hipLaunchKernelGGL(k_render_init, dim3(rblocks), dim3(RAY_BLOCK), 0, st, p, rays_o, rays_d, R, rs, w.alive_b, w.blk_sum,
+    hipLaunchKernelGGL(render_init_kernel(opt), dim3(rblocks), dim3(RAY_BLOCK), 0, st, p, rays_o, rays_d, R, rs, w.alive_b, w.blk_sum,
                        bg[0], bg[1], bg[2], rgb_out, (int32_t *)w.counters, 16, gw.hist, R >= n_hist ? (int32_t)n_hist : 0);
     KN_CHECK_LAUNCH();
     if (R < n_hist) KN_TRY(kn_fill_i32(st, gw.hist, n_hist, 0));
@@ -1148,6 +1190,8 @@ extern "C" int kn_render(const kn_scene *sc, void *stream, const float *rays_o, 
     src.step = step;
     src.kbits = kbits;
     src.out4 = w.out4;
+    src.strat = seed ? 1 : 0;
+    src.seed_key = p.seed_key;
 
     const int tile_len = kn_mlp_tile_len(sc);
     int32_t *live = w.live_a, *live_next = w.live_b, *alive = w.alive_a, *alive_next = w.alive_b;
@@ -1158,7 +1202,7 @@ extern "C" int kn_render(const kn_scene *sc, void *stream, const float *rays_o, 
     // wave's list, which the kernel compacts on the way (see k_march_wave); the new list is then the current one.
     auto march = [&](int64_t rows_in, bool compacting) -> int {
         const int32_t *ctl = w.ctl + 4 * (wave_no & 1), *old_ctl = w.ctl + 4 * ((wave_no + 1) & 1);
-        hipLaunchKernelGGL(march_hash ? k_march_wave<true> : k_march_wave<false>, dim3((unsigned)kn_div_up(rows_in * MARCH_G, 256)), dim3(256),
+        hipLaunchKernelGGL(march_wave_kernel(march_hash != 0, opt), dim3((unsigned)kn_div_up(rows_in * MARCH_G, 256)), dim3(256),
                            sizeof(int32_t) * (size_t)(march_hash ? 2 * march_hash : sc->N), st, p, rays_o, rays_d, live, alive,
                            ctl, kbits, rs, w.row_keys, w.row_rec, w.cnt, gw.hist, sc->N, march_hash, old_ctl,
                            compacting ? w.blk_off : (const int32_t *)nullptr, live_next, alive_next);
@@ -1260,4 +1304,20 @@ extern "C" int kn_render(const kn_scene *sc, void *stream, const float *rays_o, 
         }
     }
     return KN_OK;
+}
+
+extern "C" int kn_render(const kn_scene *sc, void *stream, const float *rays_o, const float *rays_d, int64_t R, float t_near,
+                         float step, int32_t K, float term_eps, const float bg[3], float *rgb_out, kn_render_stats *stats,
+                         void *workspace, int64_t workspace_bytes)
+{
+    return render_impl(sc, stream, rays_o, rays_d, R, t_near, step, K, term_eps, bg, nullptr, rgb_out, stats, workspace,
+                       workspace_bytes);
+}
+
+extern "C" int kn_render_stratified(const kn_scene *sc, void *stream, const float *rays_o, const float *rays_d, int64_t R,
+                                    float t_near, float step, int32_t K, float term_eps, const float bg[3], uint32_t seed,
+                                    float *rgb_out, kn_render_stats *stats, void *workspace, int64_t workspace_bytes)
+{
+    return render_impl(sc, stream, rays_o, rays_d, R, t_near, step, K, term_eps, bg, &seed, rgb_out, stats, workspace,
+                       workspace_bytes);
 }

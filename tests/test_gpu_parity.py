@@ -348,11 +348,14 @@ def render_check(cfg, sel=None, margin=None):
     margin = (1e-3 if sc["wdtype"] == "f32" else 0.08) if margin is None else margin
     dev, orc = make_pair(sc, threads=True)
     o, d = cfg["rays_o"], cfg["rays_d"]
-    img, stats = dev.render(cuda(o), cuda(d), cfg["t_near"], cfg["step"], cfg["K"], cfg["term_eps"], cfg["bg"], want_stats=True)
+    seed = cfg.get("seed")          # stratified sampling with this seed; None: the midpoint lattice
+    img, stats = dev.render(cuda(o), cuda(d), cfg["t_near"], cfg["step"], cfg["K"], cfg["term_eps"], cfg["bg"], want_stats=True,
+                            seed=seed)
     torch.cuda.synchronize()
     img = img.cpu().numpy().astype(np.float64)
     sel = np.arange(len(o)) if sel is None else sel
-    ref, n_eval, T, mg = orc.render(o[sel], d[sel], cfg["t_near"], cfg["step"], cfg["K"], cfg["term_eps"], cfg["bg"])
+    assert seed is None or len(sel) == len(o)            # the draws are keyed by the ray's row
+    ref, n_eval, T, mg = orc.render(o[sel], d[sel], cfg["t_near"], cfg["step"], cfg["K"], cfg["term_eps"], cfg["bg"], seed=seed)
     err = np.abs(img[sel] - ref).max(axis=1)
     straddle = mg < margin
     log("  render %s: %d rays, waves %d, evaluated %d, blended %d; oracle blended (subset) %d; max err %.3g "
@@ -749,3 +752,195 @@ def test_full_extraction_config3_sampled():
     orc = make_pair(sc, threads=True)[1]
     tau = float(np.median(orc.extract_occupancy(res, 0.0, voxels=pick[:300])[1]))
     extraction_check(sc, res, tau, sigma_unit=100.0, voxels=pick)
+
+
+# ------------------------------------------------------------------ sparse network grids (Sec. 5)
+def _sparse_cfg3(wdtype, width=64, height=64, keep=0.6, seed=31):
+    cfg = configs.config3(width, height, wdtype=wdtype)
+    n = int(np.prod(cfg["scene"]["res"]))
+    cfg["scene"] = configs.sparsify(cfg["scene"], np.random.default_rng(seed).random(n) < keep, seed + 1)
+    cfg["name"] += "_sparse"
+    return cfg
+
+
+@pytest.mark.parametrize("wdtype", ["f32", "f16"])
+def test_sparse_grid_ids_eval_march_render(wdtype):
+    cfg = _sparse_cfg3(wdtype)
+    sc = cfg["scene"]
+    log("sparse grid", wdtype, "networks", len(sc["weights"]), "of", sc["cell_net"].size, "cells")
+    g = ks.rng(91)
+    M = 150_001
+    pts = (-1.05 + g.random((M, 3)) * 2.1).astype(np.float32)
+    dev = check_eval(sc, pts, ks.sphere_dirs(M, 92), sample=np.arange(0, M, 7), sigma_unit=100.0)
+    _, orc = make_pair(sc)
+    ids = orc.cell_ids(pts)
+    assert (ids < 0).mean() > 0.3 and len(np.unique(ids)) == len(sc["weights"]) + 1
+    np.testing.assert_array_equal(dev.cell_ids(cuda(pts)).cpu().numpy(), ids)
+    # marching: the kept lattice points, bit-exact
+    o, d = cfg["rays_o"], cfg["rays_d"]
+    out_k, cnt, _ = dev.march(cuda(o), cuda(d), cfg["t_near"], cfg["step"], cfg["K"])
+    out_k, cnt = out_k.cpu().numpy(), cnt.cpu().numpy()
+    total = 0
+    for r in range(0, len(o), 3):
+        want = orc.march(o[r], d[r], cfg["t_near"], cfg["step"], cfg["K"])
+        assert cnt[r] == len(want), r
+        np.testing.assert_array_equal(out_k[r, :cnt[r]], want)
+        total += len(want)
+    assert total > 3000
+    render_check(cfg)
+
+
+def test_sparse_grid_entries_out_of_range_mean_no_network():
+    import torch
+    import paper_2103_13744_amd as kn
+    cfg = _sparse_cfg3("f32", 8, 8)
+    sc = cfg["scene"]
+    bad = sc["cell_net"].copy()
+    gone = bad < 0
+    bad[gone] = np.where(np.random.default_rng(3).random(int(gone.sum())) < 0.5, len(sc["weights"]), -9)
+    dev, orc = make_pair(dict(sc, cell_net=bad))
+    pts = (-1 + ks.rng(5).random((20_000, 3)) * 2).astype(np.float32)
+    np.testing.assert_array_equal(dev.cell_ids(cuda(pts)).cpu().numpy(), orc.cell_ids(pts))
+    np.testing.assert_array_equal(orc.cell_ids(pts), make_pair(sc)[1].cell_ids(pts))
+    # descriptor checks
+    w = torch.zeros((4, kn.params_per_net(32)), device="cuda")
+    with pytest.raises(kn.KnError, match="one entry per cell"):
+        kn.Scene((2, 2, 2), (0, 0, 0), (1, 1, 1), 32, w, cell_net=torch.zeros(7, dtype=torch.int32, device="cuda"))
+    with pytest.raises(kn.KnError, match="unsupported"):
+        kn.Scene((300, 300, 300), (0, 0, 0), (1, 1, 1), 32, w, cell_net=torch.zeros(27_000_000, dtype=torch.int32, device="cuda"))
+
+
+@pytest.mark.parametrize("wdtype", ["f32", "bf16"])
+def test_sparse_grid_extraction(wdtype):
+    sc = scene_dict((6, 5, 7), (-1, -1, -1), (1, 1, 1), 32, wdtype, 41, sigma_scale=5.0)
+    sc = configs.sparsify(sc, np.random.default_rng(8).random(6 * 5 * 7) < 0.7, 9)
+    for occ_res in ((24, 20, 28), (25, 23, 30)):          # nested, and not
+        tau = median_density(sc, occ_res)
+        dev, got = extraction_check(sc, occ_res, max(tau, 0.05), sigma_unit=5.0)
+        if occ_res != (24, 20, 28):
+            continue          # (a voxel that straddles cell faces can reach a network cell through a corner)
+        # nested grids: a voxel whose cell has no network is never marked
+        _, orc = make_pair(sc)
+        ctr = (np.stack(np.meshgrid(*[np.arange(r) + 0.5 for r in occ_res], indexing="ij"), -1) / np.array(occ_res) * 2 - 1)
+        ids = orc.cell_ids(ctr.reshape(-1, 3).astype(np.float32)).reshape(occ_res)
+        assert (ids < 0).sum() > 1000 and not got[ids < 0].any()
+
+
+def test_sparse_grid_with_more_cells_than_a_dense_grid_may_have():
+    cfg = configs.config_sparse(96, 96)
+    sc = cfg["scene"]
+    log("sparse 48^3:", len(sc["weights"]), "networks in", sc["cell_net"].size, "cells")
+    assert sc["cell_net"].size > 65535 and 1000 < len(sc["weights"]) < 65535
+    dev, img, stats = render_check(cfg)
+    assert stats["samples_blended"] > 10_000
+    # networks only where something is occupied: the table drops no sample, so the march equals the dense rule
+    _, orc = make_pair(sc)
+    o, d = cfg["rays_o"], cfg["rays_d"]
+    out_k, cnt, _ = dev.march(cuda(o), cuda(d), cfg["t_near"], cfg["step"], cfg["K"])
+    out_k, cnt = out_k.cpu().numpy(), cnt.cpu().numpy()
+    for r in range(0, len(o), 97):
+        np.testing.assert_array_equal(out_k[r, :cnt[r]], orc.march(o[r], d[r], cfg["t_near"], cfg["step"], cfg["K"]))
+    g = ks.rng(93)
+    pts = (-1 + g.random((100_000, 3)) * 2).astype(np.float32)
+    check_eval(sc, pts, ks.sphere_dirs(100_000, 94), sample=np.arange(0, 100_000, 11), sigma_unit=100.0)
+
+
+# ------------------------------------------------------------------ stratified sampling (Sec. 3.3)
+def test_stratified_march_bit_exact_and_resumable():
+    cfg = configs.config3(40, 40)
+    dev, orc = make_pair(cfg["scene"])
+    o, d, K = cfg["rays_o"], cfg["rays_d"], cfg["K"]
+    differ = 0
+    for seed in (0, 7, 2 ** 32 - 1):
+        out_k, cnt, nxt = dev.march(cuda(o), cuda(d), cfg["t_near"], cfg["step"], K, seed=seed)
+        out_k, cnt = out_k.cpu().numpy(), cnt.cpu().numpy()
+        total = 0
+        for r in range(0, len(o), 2):
+            want = orc.march_stratified(o[r], d[r], cfg["t_near"], cfg["step"], K, seed, r)
+            assert cnt[r] == len(want), (seed, r)
+            np.testing.assert_array_equal(out_k[r, :cnt[r]], want)
+            differ += want.tolist() != orc.march(o[r], d[r], cfg["t_near"], cfg["step"], K).tolist()
+            total += len(want)
+        assert total > 2500
+    assert differ > 100           # the draws do move lattice points across voxel faces
+    seed = 7
+    kb = cuda(np.zeros(len(o), np.int32))
+    got = [[] for _ in range(len(o))]
+    for _ in range(K):
+        ck, cc, kb = dev.march(cuda(o), cuda(d), cfg["t_near"], cfg["step"], K, S=6, k_begin=kb, seed=seed)
+        ck, cc = ck.cpu().numpy(), cc.cpu().numpy()
+        for r in np.nonzero(cc)[0]:
+            got[r] += ck[r, :cc[r]].tolist()
+        if cc.sum() == 0:
+            break
+    out_k, cnt, _ = dev.march(cuda(o), cuda(d), cfg["t_near"], cfg["step"], K, seed=seed)
+    out_k, cnt = out_k.cpu().numpy(), cnt.cpu().numpy()
+    for r in range(0, len(o), 5):
+        assert got[r] == out_k[r, :cnt[r]].tolist()
+
+
+def test_stratified_march_without_grid_and_coarse_steps():
+    # no occupancy grid; steps much longer than a skip block would be; rays that graze and miss the box
+    cfg = configs.config1(24, 24)
+    dev, orc = make_pair(cfg["scene"])
+    o, d = cfg["rays_o"], cfg["rays_d"]
+    for K, seed in ((32, 1), (5, 2), (1, 3)):
+        step = cfg["step"] * 32 / K
+        out_k, cnt, _ = dev.march(cuda(o), cuda(d), cfg["t_near"], step, K, seed=seed)
+        out_k, cnt = out_k.cpu().numpy(), cnt.cpu().numpy()
+        for r in range(len(o)):
+            want = orc.march_stratified(o[r], d[r], cfg["t_near"], step, K, seed, r)
+            assert cnt[r] == len(want)
+            np.testing.assert_array_equal(out_k[r, :cnt[r]], want)
+
+
+@pytest.mark.parametrize("wdtype,H", [("f32", 32), ("f16", 32), ("bf16", 64), ("f32", 64)])
+def test_stratified_render(wdtype, H):
+    if H == 32:
+        cfg = configs.config3(72, 72, wdtype=wdtype)
+    else:
+        cfg = configs.config5(64, 40, net_res=8, occ_res=128, wdtype=wdtype)
+    cfg["seed"] = 1234
+    cfg["name"] += "_stratified"
+    dev, img, _ = render_check(cfg)
+    mid = dev.render(cuda(cfg["rays_o"]), cuda(cfg["rays_d"]), cfg["t_near"], cfg["step"], cfg["K"], cfg["term_eps"],
+                     cfg["bg"]).cpu().numpy()
+    assert np.abs(mid - img).max() > 0.01            # not the midpoint picture
+
+
+def test_stratified_render_without_termination_fp32():
+    cfg = configs.config1(48, 48)
+    cfg["seed"] = 99
+    render_check(cfg)
+
+
+def test_stratified_render_is_seeded_and_independent_of_the_wave_cut():
+    import paper_2103_13744_amd as kn
+    cfg = configs.config3(80, 80)
+    dev, _ = make_pair(cfg["scene"])
+    o, d = cuda(cfg["rays_o"]), cuda(cfg["rays_d"])
+    args = (cfg["t_near"], cfg["step"], cfg["K"], cfg["term_eps"], cfg["bg"])
+    try:
+        imgs = []
+        for first, slots, growth in ((0, 0, 0), (4, 32, 2), (1, 8, 3), (512, 512, 2)):
+            kn.set_render_params(first, slots, growth)
+            imgs.append(dev.render(o, d, *args, seed=5).cpu().numpy())
+            again = dev.render(o, d, *args, seed=5).cpu().numpy()
+            np.testing.assert_array_equal(imgs[-1], again)
+        for im in imgs[1:]:
+            np.testing.assert_array_equal(im, imgs[0])
+        other = dev.render(o, d, *args, seed=6).cpu().numpy()
+        assert np.abs(other - imgs[0]).max() > 0.01
+    finally:
+        kn.set_render_params(0, 0, 0)
+
+
+def test_stratified_render_on_a_sparse_grid_and_on_grids_that_do_not_nest():
+    cfg = _sparse_cfg3("f32", 56, 56)
+    cfg["seed"] = 77
+    render_check(cfg)
+    occ = ks.blob_occupancy((50, 45, 61), 12, 0.15, 5)
+    cfg = configs.config3(48, 48, wdtype="f32")
+    cfg["scene"] = scene_dict((5, 8, 5), (-1, -1, -1), (1, 1, 1), 32, "f32", 13, occ=occ, sigma_scale=60.0)
+    cfg["seed"] = 78
+    render_check(cfg)

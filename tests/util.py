@@ -19,9 +19,12 @@ def make_pair(sc, threads=False):
     import torch
     import paper_2103_13744_amd as kn
     occ = sc["occupancy"]
+    table = sc.get("cell_net")          # sparse network grid: cell -> row of weights, or None
     dev = kn.Scene(sc["res"], sc["aabb_min"], sc["aabb_max"], sc["hidden"], device_weights(sc["weights"], sc["wdtype"]),
-                   None if occ is None else torch.from_numpy(occ).cuda())
-    orc = OracleScene(sc["res"], sc["aabb_min"], sc["aabb_max"], sc["hidden"], sc["weights"], occ, threads=threads)
+                   None if occ is None else torch.from_numpy(occ).cuda(),
+                   cell_net=None if table is None else torch.from_numpy(table).cuda())
+    orc = OracleScene(sc["res"], sc["aabb_min"], sc["aabb_max"], sc["hidden"], sc["weights"], occ, threads=threads,
+                      cell_net=table)
     return dev, orc
 
 
