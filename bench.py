@@ -201,6 +201,51 @@ def occupancy_extraction(kn, torch, scene, sc, occ_res, iters=5):
                          "peak": PEAK_MFMA_16BIT / 1e12, "unit": "TFLOP/s", "frac": tf * 1e12 / PEAK_MFMA_16BIT, "traffic": None}}
 
 
+def render_variant(kn, torch, scene, rays, args, out, steps, seeded):
+    """Frames of a variant of the render (stratified sampling: a new seed per frame; or another scene): ms per frame
+    without events, then the stages with events."""
+    def frames(n):
+        for i in range(n):
+            scene.render(*rays[i % len(rays)], *args, out=out, seed=(1000 + i) if seeded else None)
+    frames(4)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    frames(steps)
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / steps
+    kn.profile_enable(1)
+    kn.profile_read(reset=True)
+    frames(steps)
+    prof = kn.profile_read(reset=True)
+    kn.profile_enable(0)
+    return {"ms_per_frame": ms, "frames_per_sec": 1e3 / ms,
+            "stage_ms_per_frame": {k: prof[k] / steps for k in ("ms_setup", "ms_march", "ms_bucket", "ms_mlp", "ms_blend")},
+            "samples_evaluated_per_frame": prof["mlp_samples"] / steps}
+
+
+def sparse_grid(kn, torch, configs, poses, size, wdtype, steps):
+    """A network grid finer than a dense scene may be (48^3 cells) with networks only in the cells that hold occupied
+    voxels, same camera and lattice as the default workload."""
+    cfg = configs.config_sparse(size, size, azimuth=poses[0], wdtype=wdtype)
+    sc = cfg["scene"]
+    dt = {"f16": torch.float16, "bf16": torch.bfloat16}[wdtype]
+    scene = kn.Scene(sc["res"], sc["aabb_min"], sc["aabb_max"], sc["hidden"], torch.from_numpy(sc["weights"]).to(dt).cuda(),
+                     torch.from_numpy(sc["occupancy"]).cuda(), cell_net=torch.from_numpy(sc["cell_net"]).cuda())
+    rays = []
+    for az in poses:
+        o, d = configs.camera_rays(size, size, 40.0, 4.0, az, 30.0)
+        rays.append((torch.from_numpy(o).cuda(), torch.from_numpy(d).cuda()))
+    out = torch.empty((size * size, 3), dtype=torch.float32, device="cuda")
+    res = render_variant(kn, torch, scene, rays, (cfg["t_near"], cfg["step"], cfg["K"], cfg["term_eps"], cfg["bg"]), out, steps,
+                         False)
+    res["workload"] = ("%dx%d render, %d networks (H=%d, %s) in a %s grid, %s occupancy grid (%.1f %% occupied), step diag/512, "
+                       "eps 0.01, %d camera poses" % (size, size, len(sc["weights"]), sc["hidden"], wdtype,
+                                                      "x".join(str(r) for r in sc["res"]),
+                                                      "x".join(str(r) for r in sc["occupancy"].shape),
+                                                      100.0 * sc["occupancy"].mean(), len(poses)))
+    return res
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -365,7 +410,10 @@ def main():
         torch.cuda.synchronize()
         del src_buf, dst_buf
     if a.wdtype in ("f16", "bf16") and a.workload == "cfg3":
+        # the same frames with stratified sampling (Sec. 3.3), a new seed per frame
+        res["stratified_sampling"] = render_variant(kn, torch, scene, rays, args, out, a.steps, True)
         res["occupancy_extraction"] = occupancy_extraction(kn, torch, scene, sc, sc["occupancy"].shape)
+        res["sparse_grid"] = sparse_grid(kn, torch, configs, poses, a.size, a.wdtype, a.steps)
         del scene
         torch.cuda.empty_cache()
         res["isolated_mlp"] = isolated_mlp(kn, torch, a.wdtype)
