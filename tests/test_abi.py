@@ -59,6 +59,14 @@ def test_host_side_argument_validation(lib):
     assert lib.kn_scene_create(C.byref(d), None, C.byref(h)) == -1       # zero grid component
     d.res[:] = [64, 64, 64]
     assert lib.kn_scene_create(C.byref(d), None, C.byref(h)) == -2       # too many networks
+    d.cell_net, d.n_nets = 256, 0                                       # sparse grid (table never dereferenced below)
+    assert lib.kn_scene_create(C.byref(d), None, C.byref(h)) == -1       # no networks behind the table
+    d.n_nets = 70000
+    assert lib.kn_scene_create(C.byref(d), None, C.byref(h)) == -2       # too many networks
+    d.res[:] = [300, 300, 300]
+    d.n_nets = 100
+    assert lib.kn_scene_create(C.byref(d), None, C.byref(h)) == -2       # too many cells
+    d.cell_net, d.n_nets = None, 0
     d.res[:] = [2, 2, 2]
     d.hidden = 48
     assert lib.kn_scene_create(C.byref(d), None, C.byref(h)) == -2       # no kernel for this width
@@ -73,6 +81,8 @@ def test_host_side_argument_validation(lib):
     assert lib.kn_cell_ids(None, None, None, 0, None) == -1
     assert lib.kn_render(None, None, None, None, 0, 0.0, 1.0, 8, 0.0, None, None, None, None, 0) == -1
     bg = (C.c_float * 3)(0, 0, 0)
+    assert lib.kn_render_stratified(None, None, None, None, 0, 0.0, 1.0, 8, 0.0, C.byref(bg), 1, None, None, None, 0) == -1
+    assert lib.kn_march_stratified(None, None, None, None, 0, 0.0, 1.0, 8, 1, None, 4, None, None, None) == -1
     assert lib.kn_composite(None, None, None, None, -1, 0.1, 0.0, C.byref(bg), None, None, None) == -1
     assert lib.kn_composite(None, None, None, None, 0, 0.0, 0.0, C.byref(bg), None, None, None) == -1   # step <= 0
     assert lib.kn_composite(None, None, None, None, 0, 0.1, 1.5, C.byref(bg), None, None, None) == -1   # eps >= 1
