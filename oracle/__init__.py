@@ -65,8 +65,8 @@ def _lib(omp: bool = False):
         L.kno_march_stratified.argtypes = [C.POINTER(Scene), _f32p, _f32p, C.c_float, C.c_float, C.c_int32,
                                            C.c_uint32, C.c_uint32, _i32p]
         L.kno_render_stratified.argtypes = [C.POINTER(Scene), _f32p, _f32p, C.c_int64, C.c_float, C.c_float,
-                                            C.c_int32, C.c_float, _f32p, C.c_uint32, _f64p, C.c_void_p, C.c_void_p,
-                                            C.c_void_p]
+                                            C.c_int32, C.c_float, _f32p, C.c_uint32, C.c_void_p, _f64p, C.c_void_p,
+                                            C.c_void_p, C.c_void_p]
         L.kno_composite.restype = C.c_int32
         L.kno_composite.argtypes = [_f64p, _f64p, C.c_int32, C.c_double, C.c_double, _f64p, _f64p,
                                     C.POINTER(C.c_double), C.POINTER(C.c_double)]
@@ -161,19 +161,23 @@ class OracleScene:
                                         float(t_near), float(step), int(K), int(seed), int(ray), ks)
         return ks[:n].copy()
 
-    def render(self, rays_o, rays_d, t_near, step, K, term_eps=0.0, bg=(0.0, 0.0, 0.0), seed=None):
-        """``seed`` None: midpoint lattice; else stratified sampling with that seed (ray number = row)."""
+    def render(self, rays_o, rays_d, t_near, step, K, term_eps=0.0, bg=(0.0, 0.0, 0.0), seed=None, ray_ids=None):
+        """``seed`` None: midpoint lattice; else stratified sampling with that seed; ray number = row, or
+        ``ray_ids[row]`` when the rays are a subset of a frame."""
         rays_o = np.ascontiguousarray(rays_o, np.float32).reshape(-1, 3)
         rays_d = np.ascontiguousarray(rays_d, np.float32).reshape(-1, 3)
         R = len(rays_o)
         rgb, n_eval, T, mg = np.empty((R, 3)), np.empty(R, np.int32), np.empty(R), np.empty(R)
+        ids = None if ray_ids is None else np.ascontiguousarray(ray_ids, np.uint32)
+        assert ids is None or len(ids) == R
         if seed is None:
             rc = self.L.kno_render(C.byref(self.c), rays_o, rays_d, R, float(t_near), float(step), int(K),
                                    float(term_eps), np.asarray(bg, np.float32), rgb, n_eval.ctypes.data,
                                    T.ctypes.data, mg.ctypes.data)
         else:
             rc = self.L.kno_render_stratified(C.byref(self.c), rays_o, rays_d, R, float(t_near), float(step), int(K),
-                                              float(term_eps), np.asarray(bg, np.float32), int(seed), rgb,
+                                              float(term_eps), np.asarray(bg, np.float32), int(seed),
+                                              None if ids is None else ids.ctypes.data, rgb,
                                               n_eval.ctypes.data, T.ctypes.data, mg.ctypes.data)
         assert rc == 0
         return rgb, n_eval, T, mg

@@ -307,8 +307,8 @@ int32_t kno_composite(const double *sigma, const double *rgb, int32_t n, double 
 
 static int render_rays(const kno_scene *s, const float *rays_o, const float *rays_d, int64_t R,
                        float t_near, float step, int32_t K, float term_eps, const float bg[3],
-                       const uint32_t *seed, double *rgb_out, int32_t *n_eval, double *T_final,
-                       double *margin)
+                       const uint32_t *seed, const uint32_t *ray_ids, double *rgb_out, int32_t *n_eval,
+                       double *T_final, double *margin)
 {
     if (!s || K < 0 || (R > 0 && (!rays_o || !rays_d || !rgb_out)) || !bg) return -1;
     int err = 0;
@@ -318,7 +318,7 @@ static int render_rays(const kno_scene *s, const float *rays_o, const float *ray
     for (int64_t r = 0; r < R; ++r) {
         const float *o = rays_o + 3 * r, *d = rays_d + 3 * r;
         const double eps = (double)term_eps;
-        const strat j = {seed != NULL, seed ? *seed : 0u, (uint32_t)r};
+        const strat j = {seed != NULL, seed ? *seed : 0u, ray_ids ? ray_ids[r] : (uint32_t)r};
         double T = 1.0, C[3] = {0.0, 0.0, 0.0}, mg_min = INFINITY;
         int32_t used = 0;
         for (int32_t k = 0; k < K; ++k) {
@@ -350,17 +350,17 @@ int kno_render(const kno_scene *s, const float *rays_o, const float *rays_d, int
                float t_near, float step, int32_t K, float term_eps, const float bg[3],
                double *rgb_out, int32_t *n_eval, double *T_final, double *margin)
 {
-    return render_rays(s, rays_o, rays_d, R, t_near, step, K, term_eps, bg, NULL, rgb_out, n_eval,
+    return render_rays(s, rays_o, rays_d, R, t_near, step, K, term_eps, bg, NULL, NULL, rgb_out, n_eval,
                        T_final, margin);
 }
 
 int kno_render_stratified(const kno_scene *s, const float *rays_o, const float *rays_d, int64_t R,
                           float t_near, float step, int32_t K, float term_eps, const float bg[3],
-                          uint32_t seed, double *rgb_out, int32_t *n_eval, double *T_final,
-                          double *margin)
+                          uint32_t seed, const uint32_t *ray_ids, double *rgb_out, int32_t *n_eval,
+                          double *T_final, double *margin)
 {
-    return render_rays(s, rays_o, rays_d, R, t_near, step, K, term_eps, bg, &seed, rgb_out, n_eval,
-                       T_final, margin);
+    return render_rays(s, rays_o, rays_d, R, t_near, step, K, term_eps, bg, &seed, ray_ids, rgb_out,
+                       n_eval, T_final, margin);
 }
 
 /* Sec. 3.4: one voxel of the occupancy grid, 27 probes. */

@@ -88,8 +88,9 @@ int32_t kno_march(const kno_scene *s, const float o[3], const float d[3], float 
  *   u = (mix(mix(mix(seed) + ray) ^ k) >> 8) * 2^-24
  * so that t_k = t_near + (k + u) * step (fp32, one fused multiply-add) lies in interval k.
  * kno_march_stratified / kno_render_stratified are kno_march / kno_render on these lattice
- * points; in the render, ray r of the arrays has ray number r, and sample k is blended with
- * delta_k = t_(k+1) - t_k (the next lattice point, kept or not; k + 1 = K included). */
+ * points; in the render, ray r of the arrays has ray number ray_ids[r] (r if ray_ids is NULL: a
+ * caller that renders a subset of a frame's rays passes their numbers in the frame), and sample k
+ * is blended with delta_k = t_(k+1) - t_k (the next lattice point, kept or not; k + 1 = K included). */
 float kno_stratified_offset(uint32_t seed, uint32_t ray, int32_t k);
 int32_t kno_march_stratified(const kno_scene *s, const float o[3], const float d[3], float t_near,
                              float step, int32_t K, uint32_t seed, uint32_t ray, int32_t *ks);
@@ -110,8 +111,8 @@ int kno_render(const kno_scene *s, const float *rays_o, const float *rays_d, int
 
 int kno_render_stratified(const kno_scene *s, const float *rays_o, const float *rays_d, int64_t R,
                           float t_near, float step, int32_t K, float term_eps, const float bg[3],
-                          uint32_t seed, double *rgb_out, int32_t *n_eval, double *T_final,
-                          double *margin);
+                          uint32_t seed, const uint32_t *ray_ids, double *rgb_out, int32_t *n_eval,
+                          double *T_final, double *margin);
 
 /* Occupancy grid extraction (Sec. 3.4, "Empty Space Skipping"; tau: Sec. 4.1): the density is
  * sampled on a 3x3x3 subgrid of every voxel of a grid of resolution occ_res over the AABB and the

@@ -354,8 +354,8 @@ def render_check(cfg, sel=None, margin=None):
     torch.cuda.synchronize()
     img = img.cpu().numpy().astype(np.float64)
     sel = np.arange(len(o)) if sel is None else sel
-    assert seed is None or len(sel) == len(o)            # the draws are keyed by the ray's row
-    ref, n_eval, T, mg = orc.render(o[sel], d[sel], cfg["t_near"], cfg["step"], cfg["K"], cfg["term_eps"], cfg["bg"], seed=seed)
+    ref, n_eval, T, mg = orc.render(o[sel], d[sel], cfg["t_near"], cfg["step"], cfg["K"], cfg["term_eps"], cfg["bg"], seed=seed,
+                                    ray_ids=None if seed is None else sel)       # the draws are keyed by the ray's row
     err = np.abs(img[sel] - ref).max(axis=1)
     straddle = mg < margin
     log("  render %s: %d rays, waves %d, evaluated %d, blended %d; oracle blended (subset) %d; max err %.3g "
@@ -453,6 +453,16 @@ def test_render_large_grid_code_paths(tmp_path):
         subprocess.run([sys.executable, "-c", code], env=dict(os.environ, **knobs), check=True, timeout=300)
         np.testing.assert_array_equal(np.load(out), here)
         out.unlink()
+    # the same paths under the sparse-grid and stratified variants of the marching kernel
+    cfg = _sparse_cfg3("f16", 64, 64)
+    dev, _ = make_pair(cfg["scene"])
+    here = dev.render(o, d, *args, seed=3).cpu().numpy()
+    code = code.replace("cfg = configs.config3(64, 64)\n",
+                        "from tests.test_gpu_parity import _sparse_cfg3\ncfg = _sparse_cfg3('f16', 64, 64)\n")
+    code = code.replace("cfg['bg'])", "cfg['bg'], seed=3)")
+    assert "_sparse_cfg3" in code and "seed=3" in code
+    subprocess.run([sys.executable, "-c", code], env=dict(os.environ, KN_GROUP_FUSED_MAX="0"), check=True, timeout=300)
+    np.testing.assert_array_equal(np.load(out), here)
 
 
 def test_render_network_grid_above_the_fused_grouping_limit():
@@ -741,6 +751,22 @@ def test_full_config5_sampled():
     R = len(cfg["rays_o"])
     sel = np.sort(ks.rng(96).choice(R, size=3000, replace=False))
     render_check(cfg, sel=sel)
+
+
+def test_full_config3_stratified_sampled():
+    cfg = configs.config3()
+    cfg["seed"] = 2024
+    cfg["name"] += "_stratified"
+    sel = np.sort(ks.rng(95).choice(len(cfg["rays_o"]), size=5000, replace=False))
+    _, img, stats = render_check(cfg, sel=sel)
+    assert stats["samples_blended"] > 1_000_000
+
+
+def test_full_sparse_grid_sampled():
+    cfg = configs.config_sparse()
+    sel = np.sort(ks.rng(94).choice(len(cfg["rays_o"]), size=6000, replace=False))
+    _, img, stats = render_check(cfg, sel=sel)
+    assert stats["samples_blended"] > 500_000
 
 
 def test_full_extraction_config3_sampled():

@@ -551,6 +551,9 @@ def test_stratified_render_of_a_constant_medium_telescopes():
     assert len(np.unique(T)) == 5                           # each ray has its own draws
     T_mid = sc.render(o, d, t_near, step, K, 0.0, bg)[2]
     assert np.allclose(T_mid, math.exp(-sigma * K * step), atol=1e-12)
+    # rays rendered as a subset of a frame carry their numbers in the frame
+    T_sub = sc.render(o[:2], d[:2], t_near, step, K, 0.0, bg, seed=seed, ray_ids=[3, 1])[2]
+    assert np.array_equal(T_sub, T[[3, 1]])
     # other seed, other draws; same seed, same picture
     assert not np.array_equal(sc.render(o, d, t_near, step, K, 0.0, bg, seed=12)[2], T)
     assert np.array_equal(sc.render(o, d, t_near, step, K, 0.0, bg, seed=seed)[2], T)
