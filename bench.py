@@ -260,6 +260,8 @@ def main():
     ap.add_argument("--wave", default="", help="first_wave_samples,slots_per_ray,growth (experiment knob)")
     ap.add_argument("--in-flight", type=int, default=3,
                     help="frames in flight (one stream and host thread each) of the supplementary throughput pass; 0 = skip")
+    ap.add_argument("--frames-only", action="store_true",
+                    help="stop after the timed frames of the workload (no supplementary measurements): for counter runs")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (reference point for FETCH_SIZE / WRITE_SIZE counters)")
     a = ap.parse_args()
@@ -401,7 +403,7 @@ def main():
         "roofline_mlp_all_events": roof_mlp(prof_all), "roofline_march_all_events": roof_march(prof_all),
         "roofline_group_all_events": roof_group(prof_all), "roofline_blend_all_events": roof_blend(prof_all),
     }
-    if a.in_flight > 1:
+    if a.in_flight > 1 and not a.frames_only:
         res["frames_in_flight"] = frames_in_flight(torch, scene, rays, args, R, a.steps, a.in_flight, blended / a.steps)
     if a.calibrate_copy:
         src_buf = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
@@ -409,7 +411,7 @@ def main():
         dst_buf.copy_(src_buf)
         torch.cuda.synchronize()
         del src_buf, dst_buf
-    if a.wdtype in ("f16", "bf16") and a.workload == "cfg3":
+    if a.wdtype in ("f16", "bf16") and a.workload == "cfg3" and not a.frames_only:
         # the same frames with stratified sampling (Sec. 3.3), a new seed per frame
         res["stratified_sampling"] = render_variant(kn, torch, scene, rays, args, out, a.steps, True)
         res["occupancy_extraction"] = occupancy_extraction(kn, torch, scene, sc, sc["occupancy"].shape)
