@@ -7,8 +7,9 @@
 // (Chebyshev distance, in blocks of 4^3 voxels, to the nearest occupied block) lets a group jump
 // over lattice points that provably lie in empty blocks; every point that could be kept is still
 // tested with the exact arithmetic of Eq. 6, so the kept set equals the plain per-point definition.
-// Kept samples go to a per-ray row, rows are compacted (scan of the per-ray counts) into a dense
-// ray-major sample list, and only that list is bucketed and evaluated.
+// Kept samples go to the ray's row of the wave's buffers (network id and packed (ray, k) record per slot, a
+// count per row); the grouping and the MLP kernel address samples by slot number, so the rows are never
+// compacted into a list.
 #include "kn_common.h"
 
 #include <math.h>
