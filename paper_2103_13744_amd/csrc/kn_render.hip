@@ -1216,7 +1216,9 @@ static int render_impl(const kn_scene *sc, void *stream, const float *rays_o, co
         return KN_OK;
     };
     int64_t s_bound = first_samples; // host-side upper bound of the samples per ray of the wave being enqueued
-    auto rest_of_wave = [&](int64_t rows_cap) -> int {
+    // post: the wave's survivor count and the running totals go to the mailbox (only where the host is going to look:
+    // the writes to host memory are part of the kernel that closes the wave)
+    auto rest_of_wave = [&](int64_t rows_cap, bool post) -> int {
         int32_t *ctl = w.ctl + 4 * (wave_no & 1), *ctl_next = w.ctl + 4 * ((wave_no + 1) & 1);
         KnBucketOut bo;
         KN_TRY(kn_group_run(st, w.row_keys, w.cnt, ctl, rows_cap, sc->N, tile_len, gw, &bo));
@@ -1236,9 +1238,9 @@ static int render_impl(const kn_scene *sc, void *stream, const float *rays_o, co
                                w.out4, step, term_eps, bg[0], bg[1], bg[2], rs, rgb_out, alive, w.partials, w.surv16, gw.hist,
                                fused_hist ? (int32_t)n_hist : 0, wave_no == 0 ? 1 : 0);
         KN_CHECK_LAUNCH();
-        seq = next_seq();
+        if (post) seq = next_seq();
         hipLaunchKernelGGL(k_sum_partials, dim3(1), dim3(1024), 0, st, w.partials, cblocks, w.surv16, groups, w.counters, ctl,
-                           ctl_next, sched, w.blk_off, mb_dev, seq);
+                           ctl_next, sched, w.blk_off, post ? mb_dev : (unsigned long long *)nullptr, seq);
         KN_CHECK_LAUNCH();
         tm.mark(KN_ST_BLEND);
         if (tm.on) g_kn_profile.mlp_launches += 1;
@@ -1254,8 +1256,6 @@ static int render_impl(const kn_scene *sc, void *stream, const float *rays_o, co
     if (first < 0 || first > R) return KN_E_HIP;
     long long n_alive = first;
     if (first > 0) {
-        KN_TRY(rest_of_wave(first));
-        int64_t list_cap = first; // upper bound of the length of the current live list
         // Further waves.  The second one is enqueued right behind the first (its shape is computed on the device);
         // after that the host looks at the survivor count before it enqueues more.
         bool speculative = (int64_t)first_samples < (int64_t)K;
@@ -1264,6 +1264,17 @@ static int render_impl(const kn_scene *sc, void *stream, const float *rays_o, co
         const bool second_wave_ends_it = speculative && first * (long long)K <= budget &&
                                          (int64_t)first_samples * g_wave_growth >= (int64_t)K;
         const bool want_counts = (g_kn_profile_on && g_only_stage == KN_ST_NONE) || stats != nullptr;
+        // a wave's count is read by the host unless the next wave is enqueued blindly (the first wave's, when a second
+        // follows) or nothing follows for sure (the second wave's, when it ends every ray)
+        const bool blind_second = speculative;
+        auto host_reads = [&](int wave_index) {
+            if (want_counts) return true;
+            if (wave_index == 0) return !blind_second;
+            if (wave_index == 1 && blind_second) return !second_wave_ends_it;
+            return true;
+        };
+        KN_TRY(rest_of_wave(first, host_reads(0)));
+        int64_t list_cap = first; // upper bound of the length of the current live list
         while (true) {
             if (wave_no == 2 && second_wave_ends_it && !want_counts) break;
             int64_t next_cap = list_cap; // survivors <= rows of the list they come from
@@ -1277,7 +1288,7 @@ static int render_impl(const kn_scene *sc, void *stream, const float *rays_o, co
             tm.begin();
             KN_TRY(march(list_cap, true)); // reads (and compacts) the old list
             list_cap = next_cap;
-            KN_TRY(rest_of_wave(list_cap));
+            KN_TRY(rest_of_wave(list_cap, host_reads(wave_no)));
         }
     }
     if ((g_kn_profile_on && g_only_stage == KN_ST_NONE) || stats) {
