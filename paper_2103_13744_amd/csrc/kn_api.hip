@@ -583,6 +583,14 @@ extern "C" int kn_extract_occupancy(const kn_scene *sc, void *stream, const int3
     for (int a = 0; a < 3; ++a) job.first[a] = first[a];
     job.tau = tau;
     job.occupancy = occupancy;
+    // Where the grid being filled refines the network grid, a probe lies at least a sixth of a voxel from the faces of
+    // its voxel's home cell; if that is far more than the rounding of its position and of Eq. 6 can amount to (a few
+    // units in the last place of the largest coordinate), Eq. 6 gives the home cell for every probe and is skipped.
+    job.nested = 1;
+    for (int a = 0; a < 3; ++a) {
+        const float reach = fabsf(sc->desc.aabb_min[a]) + fabsf(sc->desc.aabb_max[a]) + (sc->desc.aabb_max[a] - sc->desc.aabb_min[a]);
+        if (occ_res[a] % sc->desc.res[a] != 0 || !(job.occ.cell[a] > 48.0f * 2.4e-7f * reach)) job.nested = 0;
+    }
     // enough workgroups to fill the chip several times over, but at least some tens of tiles per wavefront
     const int64_t tiles_per_cell = kn_div_up(KN_PROBES * kn_div_up(voxels, sc->cells), KN_WAVE);
     int64_t parts = kn_div_up(2048, sc->cells);

@@ -335,14 +335,18 @@ __global__ void __launch_bounds__(F32_WAVES *KN_WAVE) __attribute__((amdgpu_wave
     };
     int32_t net_loaded = -1;
 
-    for (int t = t_lo; t < t_hi; ++t) {
+    // every probe of a voxel in its home cell: one network for the whole box (none: nothing to mark)
+    const int32_t home_net = kn_net_of_cell(job.cell_net, cell);
+    if (job.nested && home_net < 0) return;
+    KnProbeCursor cur = kn_probe_cursor(box, t_lo * KN_WAVE + lane);
+    for (int t = t_lo; t < t_hi; ++t, kn_probe_cursor_step(box, cur)) {
         const int32_t p = t * KN_WAVE + lane;
-        const bool active = p < box.points;
+        const bool active = p < box.points; // (beyond the box's last probe the cursor points past the box: unused)
         float x, y, z;
         int64_t voxel;
-        int32_t probe;
-        kn_probe_point(job, box, min(p, box.points - 1), x, y, z, voxel, probe);
-        const int32_t net = kn_net_of_cell(job.cell_net, kn_grid_index(job.net, x, y, z));
+        const int32_t probe = cur.probe;
+        kn_probe_point(job, box, cur, x, y, z, voxel);
+        const int32_t net = job.nested ? home_net : kn_net_of_cell(job.cell_net, kn_grid_index(job.net, x, y, z));
         bool todo = active && net >= 0;
         float sg = 0.0f;
         *(f4 *)&stage[wave][lane][0] = (f4){x, y, z, 0.0f};

@@ -9,7 +9,9 @@
 // form a box, and all probes of a box use the same network unless the grids do not nest (then the probes of a
 // voxel that straddles a cell boundary are evaluated in a second pass with the neighbour's weights).
 // A box's probe points are numbered voxel by voxel (z fastest), 27 consecutive numbers per voxel, and cut into
-// tiles of 64; a workgroup takes one of `parts` equal shares of a box's tiles.
+// tiles of 64; a workgroup takes one of `parts` equal shares of a box's tiles.  A lane handles the probe numbers
+// 64 t + lane of consecutive tiles t: it splits the first into (voxel coordinates inside the box, probe of the voxel)
+// once and from then on steps that cursor by 64, without divisions.
 #pragma once
 
 #include "kn_common.h"
@@ -20,6 +22,8 @@ struct KnProbeJob {
     const int32_t *cell_net; // device, sparse network grids: cell -> network or -1; nullptr on a dense grid
     const int32_t *first[3]; // device, net.res[a] + 1 entries per axis
     int32_t parts;           // workgroups per network cell
+    int32_t nested;          // the grid being filled refines the network grid and every probe lies safely inside its
+                             // voxel's home cell (the host has checked the rounding margins): Eq. 6 is not evaluated
     float tau;
     uint8_t *occupancy;      // device, occ.res[0]*[1]*[2] bytes, zero before the launch
 };
@@ -50,16 +54,56 @@ __device__ __forceinline__ KnProbeBox kn_probe_box(const KnProbeJob &j, int32_t 
     return b;
 }
 
-// Probe point number p of a box: its position, the linear index of its voxel and which of the 27 probes it is.
-__device__ __forceinline__ void kn_probe_point(const KnProbeJob &j, const KnProbeBox &b, int32_t p, float &x, float &y,
-                                               float &z, int64_t &voxel, int32_t &probe)
+// A probe of a box: voxel coordinates inside the box (l[0] may run past the box: such a probe does not exist) and
+// which of the voxel's 27 probes it is.
+struct KnProbeCursor {
+    int32_t l[3];
+    int32_t probe;
+};
+
+__device__ __forceinline__ KnProbeCursor kn_probe_cursor(const KnProbeBox &b, int32_t p)
 {
+    KnProbeCursor c;
     const uint32_t vl = (uint32_t)p / KN_PROBES;
-    probe = p - (int32_t)vl * KN_PROBES;
-    const uint32_t lz = vl % (uint32_t)b.n[2], q = vl / (uint32_t)b.n[2];
-    const uint32_t ly = q % (uint32_t)b.n[1], lx = q / (uint32_t)b.n[1];
-    const int32_t vx = b.v0[0] + (int32_t)lx, vy = b.v0[1] + (int32_t)ly, vz = b.v0[2] + (int32_t)lz;
-    const int32_t pi = probe / 9, pj = (probe / 3) % 3, pk = probe % 3;
+    c.probe = p - (int32_t)vl * KN_PROBES;
+    const uint32_t q = vl / (uint32_t)b.n[2];
+    c.l[2] = (int32_t)(vl - q * (uint32_t)b.n[2]);
+    c.l[0] = (int32_t)(q / (uint32_t)b.n[1]);
+    c.l[1] = (int32_t)(q - (uint32_t)c.l[0] * (uint32_t)b.n[1]);
+    return c;
+}
+
+// 64 probe numbers further: 64 = 2 * 27 + 10, so two or three voxels on, and at most three carries per axis
+__device__ __forceinline__ void kn_probe_cursor_step(const KnProbeBox &b, KnProbeCursor &c)
+{
+    static_assert(KN_WAVE == 2 * KN_PROBES + 10, "step of one tile");
+    c.probe += 10;
+    int32_t dv = 2;
+    if (c.probe >= KN_PROBES) {
+        c.probe -= KN_PROBES;
+        dv = 3;
+    }
+    c.l[2] += dv;
+#pragma unroll
+    for (int i = 0; i < 3; ++i)
+        if (c.l[2] >= b.n[2]) {
+            c.l[2] -= b.n[2];
+            c.l[1] += 1;
+        }
+#pragma unroll
+    for (int i = 0; i < 3; ++i)
+        if (c.l[1] >= b.n[1]) {
+            c.l[1] -= b.n[1];
+            c.l[0] += 1;
+        }
+}
+
+// Position of the cursor's probe and the linear index of its voxel.
+__device__ __forceinline__ void kn_probe_point(const KnProbeJob &j, const KnProbeBox &b, const KnProbeCursor &c, float &x,
+                                               float &y, float &z, int64_t &voxel)
+{
+    const int32_t vx = b.v0[0] + c.l[0], vy = b.v0[1] + c.l[1], vz = b.v0[2] + c.l[2];
+    const int32_t pi = c.probe / 9, pj = (c.probe / 3) % 3, pk = c.probe % 3;
     auto sub = [](int32_t i) { return i == 0 ? 1.0f / 6.0f : (i == 1 ? 0.5f : 5.0f / 6.0f); };
     x = fmaf((float)vx + sub(pi), j.occ.cell[0], j.occ.bmin[0]);
     y = fmaf((float)vy + sub(pj), j.occ.cell[1], j.occ.bmin[1]);
