@@ -45,8 +45,12 @@ _loaded = {}
 
 def _lib(omp: bool = False):
     if omp not in _loaded:
-        build()
-        L = C.CDLL(_LIBS[omp])
+        # KN_ORACLE_LIB: load this shared object instead (the mutation test points the pins at deliberately broken
+        # builds of the oracle to show that they notice)
+        override = os.environ.get("KN_ORACLE_LIB")
+        if not override:
+            build()
+        L = C.CDLL(override or _LIBS[omp])
         L.kno_params_per_net.restype = C.c_int64
         L.kno_params_per_net.argtypes = [C.c_int32] * 3
         L.kno_posenc.restype = None

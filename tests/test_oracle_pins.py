@@ -303,8 +303,11 @@ def test_ert_error_is_bounded_by_eps_and_eps_zero_is_off():
         full, Tf, used_f, _ = oracle.composite(sg, col, 0.05)
         cut, Tc, used_c, mg = oracle.composite(sg, col, 0.05, eps=0.01)
         assert used_f == n and used_c <= n and np.abs(full - cut).max() <= 0.01
-        if used_c < n:
-            assert Tc < 0.01 and mg >= 0
+        # it stops right after the first sample that leaves T = exp(-0.05 * sum of the densities so far) below eps
+        T_after = np.exp(-0.05 * np.cumsum(sg))
+        first_below = int(np.argmax(T_after < 0.01))
+        assert T_after[first_below] < 0.01 and used_c == first_below + 1 < n
+        assert Tc < 0.01 and abs(Tc - T_after[first_below]) < 1e-12 and mg >= 0
         again, _, u2, m2 = oracle.composite(sg, col, 0.05, eps=0.0)
         np.testing.assert_array_equal(again, full)
         assert u2 == n and math.isinf(m2)
@@ -329,6 +332,9 @@ def test_march_counts_lattice_points_inside_the_box():
     ks_ = sc.march(o, d, 0.5, 1 / 16, 40)
     expect = [k for k in range(40) if 0 <= Fraction(-1) + Fraction(1, 2) + Fraction(2 * k + 1, 32) < 1]
     assert ks_.tolist() == expect and len(expect) == 16
+    # lattice points sit in the middle of their steps: shifted by 3/64 the box holds the midpoints 7..22
+    # (x_k = (4k - 27)/64), whereas the starts of the steps inside it would be 8..23
+    assert sc.march(o, d, 0.5 + 3 / 64, 1 / 16, 40).tolist() == list(range(7, 23))
     # a ray that misses the box keeps nothing
     assert len(sc.march(np.array([-1, 2.0, 0.5], np.float32), d, 0.5, 1 / 16, 40)) == 0
 
