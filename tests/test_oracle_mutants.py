@@ -66,6 +66,15 @@ MUTANTS = [
     ("threshold_not_strict", "if (sg > (double)tau) any = 1;", "if (sg >= (double)tau) any = 1;", "extraction_constant_density"),
     ("only_the_centre_probe", "for (int i = 0; i < 3; ++i)\n        for (int j = 0; j < 3; ++j)\n            for (int k = 0; k < 3; ++k) {",
      "for (int i = 1; i < 2; ++i)\n        for (int j = 1; j < 2; ++j)\n            for (int k = 1; k < 2; ++k) {", "extraction"),
+    ("occupancy_at_network_resolution", "int32_t v = kno_grid_index(s->aabb_min, s->aabb_max, s->occ_res, x);",
+     "int32_t v = kno_grid_index(s->aabb_min, s->aabb_max, s->res, x);", "march_skips or render_constant_density"),
+    ("sigmoid_sign", "rgb[c] = 1.0 / (1.0 + exp(-o5[c]));", "rgb[c] = 1.0 / (1.0 + exp(o5[c]));", "mlp_wiring or single_cell"),
+    ("density_without_relu", "*sigma = relu(o3[0]);", "*sigma = o3[0];", "render_constant_density or mlp_wiring"),
+    ("second_layer_without_relu", "for (int i = 0; i < H; ++i) h2[i] = relu(h2[i]);", ";", "single_cell or mlp_wiring"),
+    ("probes_use_the_voxels_home_network", "int32_t id = network_of(s, x);\n                if (id >= 0 && kno_mlp(s, id, x, dir, &sg, rgb) != 0) return -1;",
+     "float ctr[3]; for (int a = 0; a < 3; ++a) ctr[a] = fmaf((float)v[a] + 0.5f, cell[a], s->aabb_min[a]);\n"
+     "                int32_t id = network_of(s, ctr);\n                if (id >= 0 && kno_mlp(s, id, x, dir, &sg, rgb) != 0) return -1;",
+     "extraction_uses_the_network"),
     ("one_parameter_short", "((int64_t)H * (H + 1) + (H + 1))", "((int64_t)H * (H + 1) + H)", "parameter_count"),
 ]
 
