@@ -169,6 +169,11 @@ int kn_composite(void *stream, const float *sigma /*dev*/, const float *rgb /*de
                  const int32_t *offsets /*dev R+1*/, int64_t R, float step, float term_eps,
                  const float bg[3] /*host*/, float *rgb_out /*dev R*3*/, float *T_out /*dev R, nullable*/,
                  int32_t *n_used /*dev R, nullable*/);
+/* The same with a delta per sample (Eq. 4's delta_i; what stratified samples carry): alpha_i = 1 - exp(-sigma_i*delta_i). */
+int kn_composite_deltas(void *stream, const float *sigma /*dev*/, const float *rgb /*dev n*3*/,
+                        const float *delta /*dev n*/, const int32_t *offsets /*dev R+1*/, int64_t R, float term_eps,
+                        const float bg[3] /*host*/, float *rgb_out /*dev R*3*/, float *T_out /*dev R, nullable*/,
+                        int32_t *n_used /*dev R, nullable*/);
 
 /* The whole path (Sec. 3.1 Eq. 1-4, Sec. 3.2, Sec. 3.4): render R rays.  Samples are taken in
  * waves from near to far; rays whose transmittance fell below term_eps, or that ran out of

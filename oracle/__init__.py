@@ -74,6 +74,9 @@ def _lib(omp: bool = False):
         L.kno_composite.restype = C.c_int32
         L.kno_composite.argtypes = [_f64p, _f64p, C.c_int32, C.c_double, C.c_double, _f64p, _f64p,
                                     C.POINTER(C.c_double), C.POINTER(C.c_double)]
+        L.kno_composite_deltas.restype = C.c_int32
+        L.kno_composite_deltas.argtypes = [_f64p, _f64p, _f64p, C.c_int32, C.c_double, _f64p, _f64p,
+                                           C.POINTER(C.c_double), C.POINTER(C.c_double)]
         L.kno_render.argtypes = [C.POINTER(Scene), _f32p, _f32p, C.c_int64, C.c_float, C.c_float,
                                  C.c_int32, C.c_float, _f32p, _f64p, C.c_void_p, C.c_void_p, C.c_void_p]
         _u8p = np.ctypeslib.ndpointer(np.uint8, flags="C_CONTIGUOUS")
@@ -223,10 +226,17 @@ def bucket(ids, N):
 
 
 def composite(sigma, rgb, step, eps=0.0, bg=(0.0, 0.0, 0.0)):
+    """``step``: the constant delta, or an array with a delta per sample."""
     sigma = np.ascontiguousarray(sigma, np.float64)
     rgb = np.ascontiguousarray(rgb, np.float64).reshape(-1, 3)
     out = np.empty(3)
     T, mg = C.c_double(), C.c_double()
-    used = _lib().kno_composite(sigma, rgb, len(sigma), float(step), float(eps),
-                                np.asarray(bg, np.float64), out, C.byref(T), C.byref(mg))
+    if np.ndim(step) == 0:
+        used = _lib().kno_composite(sigma, rgb, len(sigma), float(step), float(eps),
+                                    np.asarray(bg, np.float64), out, C.byref(T), C.byref(mg))
+    else:
+        delta = np.ascontiguousarray(step, np.float64)
+        assert len(delta) == len(sigma)
+        used = _lib().kno_composite_deltas(sigma, rgb, delta, len(sigma), float(eps), np.asarray(bg, np.float64), out,
+                                           C.byref(T), C.byref(mg))
     return out, T.value, int(used), mg.value

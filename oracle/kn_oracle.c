@@ -283,13 +283,15 @@ int32_t kno_march_stratified(const kno_scene *s, const float o[3], const float d
     return march_ray(s, o, d, t_near, step, K, &j, ks);
 }
 
-int32_t kno_composite(const double *sigma, const double *rgb, int32_t n, double step, double eps,
-                      const double bg[3], double out[3], double *T_out, double *margin_out)
+/* Eq. 2-4 with a delta per sample (delta == NULL: the constant `step`). */
+static int32_t composite(const double *sigma, const double *rgb, const double *delta, int32_t n,
+                         double step, double eps, const double bg[3], double out[3], double *T_out,
+                         double *margin_out)
 {
     double T = 1.0, C[3] = {0.0, 0.0, 0.0}, margin = INFINITY;
     int32_t used = 0;
     for (int32_t i = 0; i < n; ++i) {
-        double alpha = 1.0 - exp(-sigma[i] * step);          /* Eq. 4 (sign restored) */
+        double alpha = 1.0 - exp(-sigma[i] * (delta ? delta[i] : step)); /* Eq. 4 (sign restored) */
         for (int c = 0; c < 3; ++c) C[c] += T * alpha * rgb[3 * i + c]; /* Eq. 2 */
         T *= (1.0 - alpha);                                   /* Eq. 3 */
         ++used;
@@ -303,6 +305,20 @@ int32_t kno_composite(const double *sigma, const double *rgb, int32_t n, double 
     if (T_out) *T_out = T;
     if (margin_out) *margin_out = margin;
     return used;
+}
+
+int32_t kno_composite(const double *sigma, const double *rgb, int32_t n, double step, double eps,
+                      const double bg[3], double out[3], double *T_out, double *margin_out)
+{
+    return composite(sigma, rgb, NULL, n, step, eps, bg, out, T_out, margin_out);
+}
+
+int32_t kno_composite_deltas(const double *sigma, const double *rgb, const double *delta, int32_t n,
+                             double eps, const double bg[3], double out[3], double *T_out,
+                             double *margin_out)
+{
+    if (n > 0 && !delta) return -1;
+    return composite(sigma, rgb, delta, n, 0.0, eps, bg, out, T_out, margin_out);
 }
 
 static int render_rays(const kno_scene *s, const float *rays_o, const float *rays_d, int64_t R,

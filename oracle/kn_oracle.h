@@ -101,6 +101,10 @@ int32_t kno_march_stratified(const kno_scene *s, const float o[3], const float d
  * *margin_out = min over composited samples of |T_i - eps| / eps (inf if eps == 0). */
 int32_t kno_composite(const double *sigma, const double *rgb, int32_t n, double step, double eps,
                       const double bg[3], double out[3], double *T_out, double *margin_out);
+/* The same with a delta per sample (Eq. 4 as printed carries delta_i; stratified samples have their own). */
+int32_t kno_composite_deltas(const double *sigma, const double *rgb, const double *delta, int32_t n,
+                             double eps, const double bg[3], double out[3], double *T_out,
+                             double *margin_out);
 
 /* Render R rays.  rgb_out R*3.  Optional per-ray outputs (nullable): n_eval (samples
  * evaluated = composited), T_final, margin (see kno_composite).  Samples behind the

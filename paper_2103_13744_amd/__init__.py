@@ -20,7 +20,7 @@ DTYPES = {"f32": KN_F32, "f16": KN_F16, "bf16": KN_BF16}
 EXPORTS = ["kn_error_string", "kn_last_hip_error", "kn_params_per_net", "kn_scene_create", "kn_scene_destroy",
            "kn_extract_workspace_bytes", "kn_extract_occupancy", "kn_layered_workspace_bytes", "kn_eval_grouped_layered",
            "kn_workspace_bytes", "kn_cell_ids", "kn_bucket", "kn_eval_grouped", "kn_march", "kn_composite",
-           "kn_render", "kn_march_stratified", "kn_render_stratified", "kn_set_render_params", "kn_profile_enable", "kn_profile_read"]
+           "kn_render", "kn_composite_deltas", "kn_march_stratified", "kn_render_stratified", "kn_set_render_params", "kn_profile_enable", "kn_profile_read"]
 
 
 class KnError(RuntimeError):
@@ -80,6 +80,7 @@ def load_library(build_if_missing: bool = True):
     L.kn_eval_grouped_layered.argtypes = [vp, vp, vp, vp, i64, vp, vp, vp, i64]
     L.kn_extract_occupancy.argtypes = [vp, vp, C.POINTER(i32 * 3), f32, vp, vp, i64]
     L.kn_composite.argtypes = [vp, vp, vp, vp, i64, f32, f32, C.POINTER(f32 * 3), vp, vp, vp]
+    L.kn_composite_deltas.argtypes = [vp, vp, vp, vp, vp, i64, f32, C.POINTER(f32 * 3), vp, vp, vp]
     L.kn_render.argtypes = [vp, vp, vp, vp, i64, f32, f32, i32, f32, C.POINTER(f32 * 3), vp,
                             C.POINTER(RenderStats), vp, i64]
     u32 = C.c_uint32
@@ -313,6 +314,8 @@ class Scene:
 
 
 def composite(sigma, rgb, offsets, step, term_eps=0.0, bg=(0.0, 0.0, 0.0)):
+    """``step``: the constant sample spacing (kn_composite), or a float32 device tensor with a spacing per sample
+    (kn_composite_deltas)."""
     import torch
     L = load_library()
     R = offsets.shape[0] - 1
@@ -321,6 +324,14 @@ def composite(sigma, rgb, offsets, step, term_eps=0.0, bg=(0.0, 0.0, 0.0)):
     used = torch.empty(R, dtype=torch.int32, device=offsets.device)
     bgc = (C.c_float * 3)(*[float(v) for v in bg])
     n = sigma.shape[0]
+    if torch.is_tensor(step):
+        if step.shape[0] != n:
+            raise KnError("one delta per sample expected")
+        _check(L.kn_composite_deltas(_stream(), _ptr(sigma, torch.float32) if n else None,
+                                     _ptr(rgb, torch.float32) if n else None, _ptr(step, torch.float32) if n else None,
+                                     _ptr(offsets, torch.int32), R, float(term_eps), C.byref(bgc), _ptr(out), _ptr(T),
+                                     _ptr(used)), "kn_composite_deltas")
+        return out, T, used
     _check(L.kn_composite(_stream(), _ptr(sigma, torch.float32) if n else None, _ptr(rgb, torch.float32) if n else None,
                           _ptr(offsets, torch.int32), R, float(step), float(term_eps), C.byref(bgc), _ptr(out), _ptr(T),
                           _ptr(used)), "kn_composite")

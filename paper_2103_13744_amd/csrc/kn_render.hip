@@ -878,7 +878,9 @@ __global__ void __launch_bounds__(1024) k_sum_partials(const int32_t *__restrict
 }
 
 // stage kernel behind kn_composite: explicit per-ray sample ranges
+// (delta: a spacing per sample, or nullptr for the constant `step`)
 __global__ void k_composite_stage(const float *__restrict__ sigma, const float *__restrict__ rgb,
+                                  const float *__restrict__ delta,
                                   const int32_t *__restrict__ offsets, int64_t R, float step, float eps, float bg0,
                                   float bg1, float bg2, float *__restrict__ rgb_out, float *__restrict__ T_out,
                                   int32_t *__restrict__ n_used)
@@ -888,7 +890,7 @@ __global__ void k_composite_stage(const float *__restrict__ sigma, const float *
     float T = 1.0f, c0 = 0.0f, c1 = 0.0f, c2 = 0.0f;
     int32_t used = 0;
     for (int32_t j = offsets[r]; j < offsets[r + 1]; ++j) {
-        const float alpha = 1.0f - expf(-sigma[j] * step);
+        const float alpha = 1.0f - expf(-sigma[j] * (delta ? delta[j] : step));
         const float wgt = T * alpha;
         c0 = fmaf(wgt, rgb[3 * (int64_t)j], c0);
         c1 = fmaf(wgt, rgb[3 * (int64_t)j + 1], c1);
@@ -1111,17 +1113,32 @@ extern "C" int kn_march_stratified(const kn_scene *sc, void *stream, const float
     return march_impl(sc, stream, rays_o, rays_d, R, t_near, step, K, &seed, k_begin, S, out_k, out_count, out_k_next);
 }
 
-extern "C" int kn_composite(void *stream, const float *sigma, const float *rgb, const int32_t *offsets, int64_t R,
-                            float step, float term_eps, const float bg[3], float *rgb_out, float *T_out, int32_t *n_used)
+static int composite_impl(void *stream, const float *sigma, const float *rgb, const float *delta, const int32_t *offsets,
+                          int64_t R, float step, float term_eps, const float bg[3], float *rgb_out, float *T_out,
+                          int32_t *n_used)
 {
     if (R < 0 || !bg || !finite_pos(step) || !(term_eps >= 0.0f && term_eps < 1.0f)) return KN_E_INVALID_ARG;
     if (R > 0 && (!offsets || !rgb_out)) return KN_E_INVALID_ARG; // sigma / rgb may be NULL when no ray has samples
     if (R == 0) return KN_OK;
     if (kn_div_up(R, 256) > 0x7fffffffLL) return KN_E_UNSUPPORTED;
     hipLaunchKernelGGL(k_composite_stage, dim3((unsigned)kn_div_up(R, 256)), dim3(256), 0, (hipStream_t)stream, sigma, rgb,
-                       offsets, R, step, term_eps, bg[0], bg[1], bg[2], rgb_out, T_out, n_used);
+                       delta, offsets, R, step, term_eps, bg[0], bg[1], bg[2], rgb_out, T_out, n_used);
     KN_CHECK_LAUNCH();
     return KN_OK;
+}
+
+extern "C" int kn_composite(void *stream, const float *sigma, const float *rgb, const int32_t *offsets, int64_t R,
+                            float step, float term_eps, const float bg[3], float *rgb_out, float *T_out, int32_t *n_used)
+{
+    return composite_impl(stream, sigma, rgb, nullptr, offsets, R, step, term_eps, bg, rgb_out, T_out, n_used);
+}
+
+extern "C" int kn_composite_deltas(void *stream, const float *sigma, const float *rgb, const float *delta,
+                                   const int32_t *offsets, int64_t R, float term_eps, const float bg[3], float *rgb_out,
+                                   float *T_out, int32_t *n_used)
+{
+    // (delta may be NULL only when no ray has samples, like sigma and rgb; the kernel then never reads it)
+    return composite_impl(stream, sigma, rgb, delta, offsets, R, 1.0f, term_eps, bg, rgb_out, T_out, n_used);
 }
 
 static int render_impl(const kn_scene *sc, void *stream, const float *rays_o, const float *rays_d, int64_t R, float t_near,

@@ -87,6 +87,9 @@ def test_host_side_argument_validation(lib):
     assert lib.kn_composite(None, None, None, None, 0, 0.0, 0.0, C.byref(bg), None, None, None) == -1   # step <= 0
     assert lib.kn_composite(None, None, None, None, 0, 0.1, 1.5, C.byref(bg), None, None, None) == -1   # eps >= 1
     assert lib.kn_composite(None, None, None, None, 0, 0.1, 0.01, C.byref(bg), None, None, None) == 0   # R = 0: no-op
+    assert lib.kn_composite_deltas(None, None, None, None, None, -1, 0.0, C.byref(bg), None, None, None) == -1
+    assert lib.kn_composite_deltas(None, None, None, None, None, 0, 1.5, C.byref(bg), None, None, None) == -1   # eps >= 1
+    assert lib.kn_composite_deltas(None, None, None, None, None, 0, 0.0, C.byref(bg), None, None, None) == 0    # R = 0
     assert lib.kn_set_render_params(0, 0, 0) == 0
     res = (C.c_int32 * 3)(4, 4, 4)
     assert lib.kn_extract_occupancy(None, None, C.byref(res), 1.0, None, None, 0) == -1

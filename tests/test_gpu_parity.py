@@ -339,6 +339,34 @@ def test_composite_stage():
                 assert abs(used[r] - u_) <= 1 and np.abs(out[r] - o_).max() < 1e-5 + eps
 
 
+def test_composite_stage_with_a_delta_per_sample():
+    import paper_2103_13744_amd as kn
+    g = ks.rng(32)
+    R = 2000
+    n = g.integers(0, 40, size=R)
+    n[:2] = 0
+    off = np.concatenate([[0], np.cumsum(n)]).astype(np.int32)
+    sg = g.uniform(0, 60, size=off[-1]).astype(np.float32)
+    col = g.random((off[-1], 3)).astype(np.float32)
+    delta = g.uniform(0.01, 0.1, size=off[-1]).astype(np.float32)
+    for eps in (0.0, 0.01):
+        out, T, used = kn.composite(cuda(sg), cuda(col), cuda(off), cuda(delta), eps, (1.0, 0.5, 0.25))
+        out, T, used = out.cpu().numpy(), T.cpu().numpy(), used.cpu().numpy()
+        for r in range(R):
+            s_ = slice(off[r], off[r + 1])
+            o_, T_, u_, mg = oracle.composite(sg[s_], col[s_], delta[s_], eps, (1.0, 0.5, 0.25))
+            if mg > 1e-3:
+                assert used[r] == u_
+                assert np.abs(out[r] - o_).max() < 1e-5 and abs(T[r] - T_) < 1e-6
+            else:
+                assert abs(used[r] - u_) <= 1 and np.abs(out[r] - o_).max() < 1e-5 + eps
+    # equal deltas: the bits of the constant-step call
+    a = kn.composite(cuda(sg), cuda(col), cuda(off), cuda(np.full(off[-1], 0.05, np.float32)), 0.01, (1.0, 0.5, 0.25))
+    b = kn.composite(cuda(sg), cuda(col), cuda(off), 0.05, 0.01, (1.0, 0.5, 0.25))
+    for x, y in zip(a, b):
+        np.testing.assert_array_equal(x.cpu().numpy(), y.cpu().numpy())
+
+
 # ------------------------------------------------------------------ a1-a6: render
 def render_check(cfg, sel=None, margin=None):
     """Render on the device, compare (a subset of) pixels with the oracle."""

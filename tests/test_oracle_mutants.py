@@ -15,7 +15,8 @@ SRC = os.path.join(ROOT, "oracle", "kn_oracle.c")
 
 # (name, text in the source, what a mistaken author might have written, pins that must catch it)
 MUTANTS = [
-    ("alpha_sign_as_printed", "double alpha = 1.0 - exp(-sigma[i] * step);", "double alpha = 1.0 - exp(sigma[i] * step);",
+    ("alpha_sign_as_printed", "double alpha = 1.0 - exp(-sigma[i] * (delta ? delta[i] : step));",
+     "double alpha = 1.0 - exp(sigma[i] * (delta ? delta[i] : step));",
      "alpha_blend or constant_density"),
     ("render_alpha_sign", "double alpha = 1.0 - exp(-sg * lattice_delta(t_near, step, k, &j));",
      "double alpha = 1.0 - exp(sg * lattice_delta(t_near, step, k, &j));", "render_constant_density"),
@@ -75,6 +76,8 @@ MUTANTS = [
      "float ctr[3]; for (int a = 0; a < 3; ++a) ctr[a] = fmaf((float)v[a] + 0.5f, cell[a], s->aabb_min[a]);\n"
      "                int32_t id = network_of(s, ctr);\n                if (id >= 0 && kno_mlp(s, id, x, dir, &sg, rgb) != 0) return -1;",
      "extraction_uses_the_network"),
+    ("delta_of_the_previous_sample", "double alpha = 1.0 - exp(-sigma[i] * (delta ? delta[i] : step));",
+     "double alpha = 1.0 - exp(-sigma[i] * (delta ? delta[i > 0 ? i - 1 : 0] : step));", "delta_per_sample"),
     ("one_parameter_short", "((int64_t)H * (H + 1) + (H + 1))", "((int64_t)H * (H + 1) + H)", "parameter_count"),
 ]
 

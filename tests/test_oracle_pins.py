@@ -295,6 +295,35 @@ def test_constant_density_gives_exponential_transmittance():
         np.testing.assert_allclose(out, col * (1 - Texp) + bg * Texp, atol=1e-12)
 
 
+def test_composite_with_a_delta_per_sample():
+    g = ks.rng(61)
+    n = 50
+    sg, col, delta = g.uniform(0, 8, n), g.random((n, 3)), g.uniform(0.01, 0.2, n)
+    bg = (0.2, 0.4, 0.6)
+    out, T, used, _ = oracle.composite(sg, col, delta, 0.0, bg)
+    # transmittance: exp(-sum sigma_i delta_i); a uniform colour c gives c (1 - T) + T bg whatever the deltas
+    assert used == n and abs(T - math.exp(-float(np.dot(sg, delta)))) < 1e-12
+    flat, Tf, _, _ = oracle.composite(sg, np.tile([0.3, 0.5, 0.7], (n, 1)), delta, 0.0, bg)
+    np.testing.assert_allclose(flat, np.array([0.3, 0.5, 0.7]) * (1 - Tf) + np.array(bg) * Tf, atol=1e-12)
+    # equal deltas: the constant-step form; a delta is tied to its own sample (reversing only the deltas changes T's path)
+    same = oracle.composite(sg, col, np.full(n, 0.05), 0.01, bg)
+    ref = oracle.composite(sg, col, 0.05, 0.01, bg)
+    assert np.array_equal(same[0], ref[0]) and same[1:] == ref[1:]
+    # sample i is weighted by T_(i-1) (1 - exp(-sigma_i delta_i)), written out
+    Tr, C = 1.0, np.zeros(3)
+    for i in range(n):
+        a = 1 - math.exp(-sg[i] * delta[i])
+        C += Tr * a * col[i]
+        Tr *= 1 - a
+    np.testing.assert_allclose(out, C + Tr * np.array(bg), atol=1e-12)
+    assert np.abs(oracle.composite(sg, col, delta[::-1].copy(), 0.0, bg)[0] - out).max() > 1e-3
+    # early termination looks at the same T
+    cut, Tc, used_c, _ = oracle.composite(sg, col, delta, 0.05, bg)
+    T_after = np.exp(-np.cumsum(sg * delta))
+    first_below = int(np.argmax(T_after < 0.05))
+    assert used_c == first_below + 1 < n and abs(Tc - T_after[first_below]) < 1e-12 and np.abs(cut - out).max() <= 0.05
+
+
 def test_ert_error_is_bounded_by_eps_and_eps_zero_is_off():
     g = ks.rng(6)
     for _ in range(20):
