@@ -112,8 +112,8 @@ int kn_workspace_bytes(const kn_scene *scene, int64_t max_points, int64_t max_ra
 int kn_cell_ids(const kn_scene *scene, void *stream, const float *points /*dev M*3*/, int64_t M,
                 int32_t *ids /*dev M*/);
 
-/* Sec. 3.5 ("order the input batch such that subsequent inputs are processed by the same
- * network"): stable bucketing of M ids in [-1, N).  counts[N+1] (slot N = outside), offsets[N+2]
+/* Sec. 3.5 (the batch is reordered so that the inputs of one network follow one another): stable
+ * bucketing of M ids in [-1, N).  counts[N+1] (slot N = outside), offsets[N+2]
  * (exclusive scan of counts), perm[M] = sample indices sorted by id, -1 last, ties by index.
  * counts / offsets may be NULL.  M <= 2^30. */
 int kn_bucket(const kn_scene *scene, void *stream, const int32_t *ids /*dev M*/, int64_t M,
