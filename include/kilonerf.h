@@ -43,7 +43,8 @@ typedef enum {
     KN_E_UNSUPPORTED = -2, /* valid request this build has no kernel for (H, dtype, limits) */
     KN_E_WORKSPACE = -3,   /* workspace missing, misaligned or smaller than required        */
     KN_E_HIP = -4,         /* a HIP runtime call failed (see kn_last_hip_error)             */
-    KN_E_NO_DEVICE = -5    /* no usable gfx950 device                                        */
+    KN_E_NO_DEVICE = -5,   /* no usable gfx950 device                                        */
+    KN_E_STATIC_LIMIT = -6 /* kn_eval_grouped_static: M needs more than KN_STATIC_SCRATCH_BYTES */
 } kn_status;
 
 typedef enum { KN_F32 = 0, KN_F16 = 1, KN_BF16 = 2 } kn_dtype;
@@ -129,6 +130,23 @@ int kn_eval_grouped(const kn_scene *scene, void *stream, const float *points /*d
                     float *rgb /*dev M*3*/, int32_t *cell_id /*dev M, nullable*/,
                     int32_t *counts /*dev N+1, nullable*/, int32_t *perm /*dev M, nullable*/,
                     void *workspace, int64_t workspace_bytes);
+
+/* For callers that cannot allocate device memory or pass a workspace (code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc): kn_eval_grouped with the library's own scratch memory in place of the
+ * workspace argument.  The scratch is a static device array of KN_STATIC_SCRATCH_BYTES that every GPU the library
+ * runs on holds until the process ends; its address on the scene's device is looked up when the scene is created.
+ * The call allocates nothing (no hipMalloc / hipFree, no events, no library routine that allocates) and records no
+ * stage timings; inputs and outputs are the caller's, as in kn_eval_grouped, and the results are the same bits.
+ * The device the scene was created on must be current (KN_E_INVALID_ARG otherwise).  M is limited to what the array
+ * holds: KN_E_STATIC_LIMIT when kn_eval_grouped's workspace for M points would exceed KN_STATIC_SCRATCH_BYTES
+ * (the need is about 21 bytes per point + 24 per network: roughly 800,000 points on 4,096 networks).
+ * All calls on one GPU share the one array, whose contents do not outlive a call: calls that overlap on a GPU
+ * (different streams or threads) race; calls on one stream are ordered as usual. */
+#define KN_STATIC_SCRATCH_BYTES (16u << 20)
+int kn_eval_grouped_static(const kn_scene *scene, void *stream, const float *points /*dev M*3*/,
+                           const float *dirs /*dev M*3*/, int64_t M, float *sigma /*dev M*/,
+                           float *rgb /*dev M*3*/, int32_t *cell_id /*dev M, nullable*/,
+                           int32_t *counts /*dev N+1, nullable*/, int32_t *perm /*dev M, nullable*/);
 
 /* Sec. 3.4 sampling with empty-space skipping, one stage on its own: for each ray, starting at
  * lattice index k_begin[r] (0 if NULL), collect up to S kept samples.  Lattice: t_k = t_near +

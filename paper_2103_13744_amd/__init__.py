@@ -19,7 +19,7 @@ DTYPES = {"f32": KN_F32, "f16": KN_F16, "bf16": KN_BF16}
 
 EXPORTS = ["kn_error_string", "kn_last_hip_error", "kn_params_per_net", "kn_scene_create", "kn_scene_destroy",
            "kn_extract_workspace_bytes", "kn_extract_occupancy", "kn_layered_workspace_bytes", "kn_eval_grouped_layered",
-           "kn_workspace_bytes", "kn_cell_ids", "kn_bucket", "kn_eval_grouped", "kn_march", "kn_composite",
+           "kn_workspace_bytes", "kn_cell_ids", "kn_bucket", "kn_eval_grouped", "kn_eval_grouped_static", "kn_march", "kn_composite",
            "kn_render", "kn_composite_deltas", "kn_march_stratified", "kn_render_stratified", "kn_set_render_params", "kn_profile_enable", "kn_profile_read"]
 
 
@@ -74,6 +74,7 @@ def load_library(build_if_missing: bool = True):
     L.kn_cell_ids.argtypes = [vp, vp, vp, i64, vp]
     L.kn_bucket.argtypes = [vp, vp, vp, i64, vp, vp, vp, vp, i64]
     L.kn_eval_grouped.argtypes = [vp, vp, vp, vp, i64, vp, vp, vp, vp, vp, vp, i64]
+    L.kn_eval_grouped_static.argtypes = [vp, vp, vp, vp, i64, vp, vp, vp, vp, vp]
     L.kn_march.argtypes = [vp, vp, vp, vp, i64, f32, f32, i32, vp, i32, vp, vp, vp]
     L.kn_extract_workspace_bytes.argtypes = [vp, C.POINTER(i64)]
     L.kn_layered_workspace_bytes.argtypes = [vp, i64, C.POINTER(i64)]
@@ -239,6 +240,17 @@ class Scene:
                                       _ptr(counts, allow_none=True), p(perm), _ptr(ws), ws.numel()), "kn_eval_grouped")
         if want_aux:
             return sigma, rgb, ids, counts, perm
+        return sigma, rgb
+
+    def eval_grouped_static(self, points, dirs, out, aux=None):
+        """kn_eval_grouped_static: eval_grouped on the library's static scratch array (nothing is allocated, so
+        ``out`` = (sigma, rgb) is required; ``aux`` = (ids, counts, perm) optional outputs)."""
+        M = points.shape[0]
+        sigma, rgb = out
+        ids, counts, perm = aux if aux is not None else (None, None, None)
+        p = (lambda t: _ptr(t) if (t is not None and M) else None)
+        _check(self.L.kn_eval_grouped_static(self.h, _stream(), p(points), p(dirs), M, p(sigma), p(rgb), p(ids),
+                                             _ptr(counts, allow_none=True), p(perm)), "kn_eval_grouped_static")
         return sigma, rgb
 
     def eval_grouped_layered(self, points, dirs, out=None, workspace=None):

@@ -38,6 +38,28 @@ static int g_n_events = 0;
 static hipStream_t g_event_stream = nullptr;
 static bool g_events_ready = false;
 
+// Scratch memory of kn_eval_grouped_static, the entry point for callers that cannot allocate: a file-scope device
+// array that every GPU the library runs on holds until the process ends.  In host code the array's name is only a
+// stand-in for the symbol, not a device address; the address on a device comes from hipGetSymbolAddress with that
+// device current (static_scratch_init, called by kn_scene_create), and only that pointer is handed to kernels.
+static __device__ __align__(256) unsigned char scratch[KN_STATIC_SCRATCH_BYTES];
+constexpr int KN_MAX_DEVICES = 64;
+static void *g_scratch_ptr[KN_MAX_DEVICES] = {};
+static std::mutex g_scratch_mutex;
+
+// once per device, with that device current
+static int static_scratch_init(int dev)
+{
+    if (dev < 0 || dev >= KN_MAX_DEVICES) return KN_E_UNSUPPORTED;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (g_scratch_ptr[dev]) return KN_OK;
+    void *ptr = nullptr;
+    KN_HIP(hipGetSymbolAddress((void **)&ptr, HIP_SYMBOL(scratch)));
+    if (!ptr || ((uintptr_t)ptr & 255)) return KN_E_HIP;
+    g_scratch_ptr[dev] = ptr;
+    return KN_OK;
+}
+
 static int settle_events()
 {
     if (g_n_events >= 2) {
@@ -61,7 +83,7 @@ static int settle_events()
     return KN_OK;
 }
 
-KnStageTimer::KnStageTimer(hipStream_t s) : st(s), on(g_kn_profile_on)
+KnStageTimer::KnStageTimer(hipStream_t s, bool allowed) : st(s), on(allowed && g_kn_profile_on)
 {
     if (on && !g_events_ready) {
         for (auto &e : g_events)
@@ -208,6 +230,7 @@ extern "C" const char *kn_error_string(int status)
     case KN_E_WORKSPACE: return "workspace missing, misaligned or too small";
     case KN_E_HIP: return "HIP runtime error";
     case KN_E_NO_DEVICE: return "no usable gfx950 device";
+    case KN_E_STATIC_LIMIT: return "input needs more scratch memory than the static buffer of kn_eval_grouped_static holds";
     default: return "unknown status";
     }
 }
@@ -289,6 +312,7 @@ extern "C" int kn_scene_create(const kn_scene_desc *desc, void *stream, kn_scene
     hipDeviceProp_t prop;
     KN_HIP(hipGetDeviceProperties(&prop, dev));
     if (strncmp(prop.gcnArchName, "gfx950", 6) != 0) return KN_E_NO_DEVICE;
+    KN_TRY(static_scratch_init(dev));
 
     kn_scene *sc = new (std::nothrow) kn_scene();
     if (!sc) return KN_E_INVALID_ARG;
@@ -418,18 +442,15 @@ extern "C" int kn_workspace_bytes(const kn_scene *sc, int64_t max_points, int64_
     return KN_OK;
 }
 
-extern "C" int kn_eval_grouped(const kn_scene *sc, void *stream, const float *points, const float *dirs, int64_t M,
-                               float *sigma, float *rgb, int32_t *cell_id, int32_t *counts, int32_t *perm, void *workspace,
-                               int64_t workspace_bytes)
+// `timed`: stage events may be recorded (creating the events allocates; the static entry point never does)
+static int eval_grouped_impl(const kn_scene *sc, hipStream_t st, const float *points, const float *dirs, int64_t M,
+                             float *sigma, float *rgb, int32_t *cell_id, int32_t *counts, int32_t *perm, void *workspace,
+                             int64_t workspace_bytes, bool timed)
 {
-    if (!sc || M < 0 || (M > 0 && (!points || !dirs || !sigma || !rgb))) return KN_E_INVALID_ARG;
-    if (M > (1ll << 30)) return KN_E_UNSUPPORTED;
-    if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < eval_ws_bytes(sc, M)) return KN_E_WORKSPACE;
-    hipStream_t st = (hipStream_t)stream;
     KnCarver ws(workspace, workspace_bytes);
     int32_t *keys = ws.carve<int32_t>(M);
     if (!ws.ok()) return KN_E_WORKSPACE;
-    KnStageTimer tm(st);
+    KnStageTimer tm(st, timed);
     tm.begin();
     int32_t *scratch = nullptr;
     int64_t n_scratch = 0;
@@ -456,6 +477,37 @@ extern "C" int kn_eval_grouped(const kn_scene *sc, void *stream, const float *po
         g_kn_profile.calls += 1;
     }
     return KN_OK;
+}
+
+extern "C" int kn_eval_grouped(const kn_scene *sc, void *stream, const float *points, const float *dirs, int64_t M,
+                               float *sigma, float *rgb, int32_t *cell_id, int32_t *counts, int32_t *perm, void *workspace,
+                               int64_t workspace_bytes)
+{
+    if (!sc || M < 0 || (M > 0 && (!points || !dirs || !sigma || !rgb))) return KN_E_INVALID_ARG;
+    if (M > (1ll << 30)) return KN_E_UNSUPPORTED;
+    if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < eval_ws_bytes(sc, M)) return KN_E_WORKSPACE;
+    return eval_grouped_impl(sc, (hipStream_t)stream, points, dirs, M, sigma, rgb, cell_id, counts, perm, workspace,
+                             workspace_bytes, true);
+}
+
+// kn_eval_grouped on the library's static scratch array instead of a caller workspace: nothing is allocated, here
+// or in anything this calls (no stage events either).  All calls on one GPU share the array.
+extern "C" int kn_eval_grouped_static(const kn_scene *sc, void *stream, const float *points, const float *dirs, int64_t M,
+                                      float *sigma, float *rgb, int32_t *cell_id, int32_t *counts, int32_t *perm)
+{
+    if (!sc || M < 0 || (M > 0 && (!points || !dirs || !sigma || !rgb))) return KN_E_INVALID_ARG;
+    if (M > (1ll << 30) || eval_ws_bytes(sc, M) > (int64_t)KN_STATIC_SCRATCH_BYTES) return KN_E_STATIC_LIMIT;
+    int dev = -1;
+    KN_HIP(hipGetDevice(&dev));
+    if (dev != sc->device || dev < 0 || dev >= KN_MAX_DEVICES) return KN_E_INVALID_ARG; // the scene's device must be current
+    void *ptr;
+    {
+        std::lock_guard<std::mutex> lock(g_scratch_mutex);
+        ptr = g_scratch_ptr[dev]; // set when the scene was created on this device
+    }
+    if (!ptr) return KN_E_HIP;
+    return eval_grouped_impl(sc, (hipStream_t)stream, points, dirs, M, sigma, rgb, cell_id, counts, perm, ptr,
+                             (int64_t)KN_STATIC_SCRATCH_BYTES, false);
 }
 
 // ---------------------------------------------------------------------------------------------

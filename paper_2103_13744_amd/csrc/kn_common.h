@@ -275,7 +275,7 @@ enum KnStage { KN_ST_CELL = 0, KN_ST_MARCH, KN_ST_BUCKET, KN_ST_MLP, KN_ST_BLEND
 struct KnStageTimer {
     hipStream_t st;
     bool on;
-    KnStageTimer(hipStream_t s);
+    KnStageTimer(hipStream_t s, bool allowed = true);
     void begin() { mark(KN_ST_NONE); }
     void mark(int stage_id);
 };

@@ -1,0 +1,92 @@
+"""kn_eval_grouped_static, the entry point that allocates nothing (its scratch is a static device array), against
+kn_eval_grouped through the C ABI: same kernels, so the same bits.  Two calls in a row, the second smaller, so that
+what the first call left in the shared array must not matter; then the size limit."""
+import ctypes as C
+
+import numpy as np
+import pytest
+
+import kn_synth as ks
+from tests.util import cuda, make_pair, scene_dict
+
+pytestmark = pytest.mark.gpu
+
+
+def test_eval_grouped_static_equals_eval_grouped_on_two_calls_in_a_row():
+    import torch
+    import paper_2103_13744_amd as kn
+    sc = scene_dict((5, 4, 6), (-1, -1, -1), (1, 1, 1), 32, "f16", 71, sigma_scale=4.0)
+    dev, orc = make_pair(sc, threads=True)
+    L, h = dev.L, dev.h
+    N = dev.N
+    for M, seed in ((300_007, 72), (70_001, 73), (0, 74), (1, 75)):          # the second call is smaller than the first
+        print("static scratch, M =", M, flush=True)
+        pts = cuda(ks.uniform_points(M, seed, lo=(-1.04,) * 3, hi=(1.04,) * 3).reshape(M, 3))
+        dirs = cuda(ks.sphere_dirs(M, seed + 100).reshape(M, 3))
+        want_s, want_c, want_ids, want_counts, want_perm = dev.eval_grouped(pts, dirs, want_aux=True)
+        torch.cuda.synchronize()
+        sg = torch.full((M,), -7.0, device="cuda")
+        rgb = torch.full((M, 3), -7.0, device="cuda")
+        ids = torch.full((M,), -9, dtype=torch.int32, device="cuda")
+        counts = torch.full((N + 1,), -9, dtype=torch.int32, device="cuda")
+        perm = torch.full((M,), -9, dtype=torch.int32, device="cuda")
+        p = lambda t: t.data_ptr() if M else None
+        before = torch.cuda.memory_allocated()
+        rc = L.kn_eval_grouped_static(h, torch.cuda.current_stream().cuda_stream, p(pts), p(dirs), M, p(sg), p(rgb), p(ids),
+                                      counts.data_ptr(), p(perm))
+        assert rc == 0, L.kn_error_string(rc)
+        torch.cuda.synchronize()
+        assert torch.cuda.memory_allocated() == before
+        if M == 0:
+            continue
+        assert torch.equal(ids, want_ids) and torch.equal(counts, want_counts) and torch.equal(perm, want_perm)
+        assert torch.equal(sg, want_s) and torch.equal(rgb, want_c)
+        # and against the oracle, at the 16-bit bar
+        sel = np.arange(0, M, max(1, M // 5000))
+        s_o, c_o, ids_o = orc.eval_points(pts.cpu().numpy()[sel], dirs.cpu().numpy()[sel])
+        np.testing.assert_array_equal(ids.cpu().numpy()[sel], ids_o)
+        assert np.abs(rgb.cpu().numpy()[sel] - c_o).max() <= 2e-2
+        assert (np.abs(sg.cpu().numpy()[sel] - s_o) / 4.0 / (1 + s_o / 4.0)).max() <= 2e-2
+    # the binding's wrapper takes the same route
+    M = 10_000
+    pts, dirs = cuda(ks.uniform_points(M, 80)), cuda(ks.sphere_dirs(M, 81))
+    out = (torch.empty(M, device="cuda"), torch.empty((M, 3), device="cuda"))
+    dev.eval_grouped_static(pts, dirs, out)
+    want = dev.eval_grouped(pts, dirs)
+    assert torch.equal(out[0], want[0]) and torch.equal(out[1], want[1])
+
+
+def test_eval_grouped_static_rejects_what_its_array_cannot_hold():
+    import torch
+    import paper_2103_13744_amd as kn
+    sc = scene_dict((4, 4, 4), (0, 0, 0), (1, 1, 1), 32, "f16", 76)
+    dev, _ = make_pair(sc)
+    L, h = dev.L, dev.h
+    one = torch.zeros((4, 3), device="cuda")
+    # sizes are checked on the host before any pointer is used
+    big = 1 << 22
+    assert L.kn_eval_grouped_static(h, None, one.data_ptr(), one.data_ptr(), big, one.data_ptr(), one.data_ptr(), None, None,
+                                    None) == -6
+    assert b"static" in L.kn_error_string(-6)
+    assert L.kn_eval_grouped_static(h, None, one.data_ptr(), one.data_ptr(), -1, one.data_ptr(), one.data_ptr(), None, None,
+                                    None) == -1
+    assert L.kn_eval_grouped_static(None, None, None, None, 0, None, None, None, None, None) == -1
+    # the largest size that fits is accepted: find it through kn_workspace_bytes (same sizing)
+    lo, hi = 1, big
+    while lo < hi:
+        mid = (lo + hi + 1) // 2
+        if dev.workspace_bytes(max_points=mid) - 256 <= (16 << 20):
+            lo = mid
+        else:
+            hi = mid - 1
+    assert 700_000 < lo < 900_000
+    M = lo
+    pts, dirs = cuda(ks.uniform_points(M, 77)), cuda(ks.sphere_dirs(M, 78))
+    out = (torch.empty(M, device="cuda"), torch.empty((M, 3), device="cuda"))
+    dev.eval_grouped_static(pts, dirs, out)
+    want = dev.eval_grouped(pts, dirs)
+    assert torch.equal(out[0], want[0]) and torch.equal(out[1], want[1])
+    with pytest.raises(kn.KnError, match="static"):
+        M = lo + 1
+        dev.eval_grouped_static(torch.empty((M, 3), device="cuda"), torch.empty((M, 3), device="cuda"),
+                                (torch.empty(M, device="cuda"), torch.empty((M, 3), device="cuda")))
