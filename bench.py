@@ -412,7 +412,7 @@ def main():
         torch.cuda.synchronize()
         del src_buf, dst_buf
     if a.wdtype in ("f16", "bf16") and a.workload == "cfg3" and not a.frames_only:
-        # the same frames with stratified sampling (Sec. 3.3), a new seed per frame
+        # the same frames with stratified sampling (Sec. 3.4), a new seed per frame
         res["stratified_sampling"] = render_variant(kn, torch, scene, rays, args, out, a.steps, True)
         res["occupancy_extraction"] = occupancy_extraction(kn, torch, scene, sc, sc["occupancy"].shape)
         res["sparse_grid"] = sparse_grid(kn, torch, configs, poses, a.size, a.wdtype, a.steps)

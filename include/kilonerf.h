@@ -59,7 +59,15 @@ typedef struct {
     int32_t L_pos, L_dir;    /* encoding frequencies; this build supports (10, 4)                 */
     int32_t wdtype;          /* kn_dtype of `weights`.  KN_F32: fp32 weights, activations and     */
                              /* accumulation (fp32 matrix-core instructions).  KN_F16 / KN_BF16:  */
-                             /* 16-bit weights and activations on the matrix cores, fp32 sums     */
+                             /* 16-bit weights and activations on the matrix cores, fp32 sums.    */
+                             /* Accuracy of the 16-bit types: every operand of a layer is rounded */
+                             /* to 11 (fp16) / 8 (bf16) significant bits, which leaves the        */
+                             /* colour within 1e-3 / 7e-3 and the density within 2.5e-3 / 2e-2 of */
+                             /* the magnitude u of the density head's output (the unit the        */
+                             /* densities of the scene come in).  Eq. 4 multiplies a density      */
+                             /* error by the sample spacing: rendered pixels stay within 2e-2 of  */
+                             /* an exact evaluation where u * step <= 8 (fp16) / <= 1 (bf16); a   */
+                             /* coarser lattice or a steeper density head needs KN_F32.           */
     const void *weights;     /* dev, N*P elements of wdtype in the canonical layout               */
     int32_t occ_res[3];      /* occupancy grid resolution; all 0 = no grid (whole AABB occupied)  */
     const uint8_t *occupancy;/* dev, occ_res[0]*occ_res[1]*occ_res[2] bytes (0 = empty), x slowest*/
@@ -160,7 +168,7 @@ int kn_march(const kn_scene *scene, void *stream, const float *rays_o /*dev R*3*
              const int32_t *k_begin /*dev R, nullable*/, int32_t S, int32_t *out_k /*dev R*S*/,
              int32_t *out_count /*dev R*/, int32_t *out_k_next /*dev R, nullable*/);
 
-/* Sec. 3.3 (stratified sampling, as in NeRF): kn_march / kn_render with one uniform draw per lattice
+/* Sec. 3.4 "Sampling" (stratified sampling, as in NeRF): kn_march / kn_render with one uniform draw per lattice
  * interval instead of its midpoint: t_k = t_near + (k + u) * step, u in [0, 1) from a counter-based
  * generator keyed by (seed, ray number, k), the ray number being the ray's row in rays_o / rays_d:
  *     mix(v): v ^= v >> 16; v *= 0x85ebca6b; v ^= v >> 13; v *= 0xc2b2ae35; v ^= v >> 16   (uint32)

@@ -29,7 +29,7 @@
  *    a table maps each cell of the regular grid to the index of its network or to "none"; a cell
  *    without a network has density 0 everywhere, its lattice points are skipped like empty space,
  *    and a point in it gets the id -1.
- *  - Stratified sampling (Sec. 3.3, after NeRF): lattice point k of a ray is drawn uniformly from
+ *  - Stratified sampling (Sec. 3.4 "Sampling", after NeRF): lattice point k of a ray is drawn uniformly from
  *    its own interval, t_k = t_near + (k + u) * step with u in [0, 1) from a counter-based
  *    generator keyed by (seed, ray index, k); delta of sample k is the distance to the next
  *    lattice point, t_(k+1) - t_k, whether or not that point is skipped.

@@ -82,7 +82,7 @@ int kno_eval_points(const kno_scene *s, const float *points, const float *dirs, 
 int32_t kno_march(const kno_scene *s, const float o[3], const float d[3], float t_near,
                   float step, int32_t K, int32_t *ks);
 
-/* Stratified sampling (Sec. 3.3 refers to NeRF's: one uniform draw per lattice interval).
+/* Stratified sampling (Sec. 3.4 "Sampling" refers to NeRF's: one uniform draw per lattice interval).
  * Offset u in [0, 1) of lattice point k of ray number `ray`:
  *   mix(v): v ^= v >> 16; v *= 0x85ebca6b; v ^= v >> 13; v *= 0xc2b2ae35; v ^= v >> 16   (uint32)
  *   u = (mix(mix(mix(seed) + ray) ^ k) >> 8) * 2^-24

@@ -123,7 +123,7 @@ __device__ __forceinline__ int32_t kn_net_of_cell(const int32_t *__restrict__ ce
     return (cell_net != nullptr && cell >= 0) ? cell_net[cell] : cell;
 }
 
-// Stratified sampling (Sec. 3.3): lattice point k of a ray sits at offset u in [0, 1) of its interval,
+// Stratified sampling (Sec. 3.4 "Sampling"): lattice point k of a ray sits at offset u in [0, 1) of its interval,
 // u = (mix(mix(mix(seed) + ray) ^ k) >> 8) * 2^-24 with the 32-bit finalizer of MurmurHash3 as mix.  The host
 // passes seed_key = mix(seed); a kernel forms ray_key = mix(seed_key + ray) once per ray.
 __host__ __device__ __forceinline__ uint32_t kn_mix32(uint32_t v)

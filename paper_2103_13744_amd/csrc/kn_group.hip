@@ -1,4 +1,4 @@
-// Grouping of a render wave's samples by network (Sec. 3.2 "Implementation": points are ordered so
+// Grouping of a render wave's samples by network (Sec. 3.5 "Implementation": points are ordered so
 // that the inputs of one network are contiguous before the networks are evaluated).
 //
 // The renderer does not need the stable order that kn_bucket guarantees: a sample's network output does

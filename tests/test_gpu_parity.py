@@ -2,9 +2,15 @@
 
 Bars: cell ids, bucket counts and the sample permutation bit-exact; fp32 outputs within 1e-4
 absolute; 16-bit matrix-core outputs within 2e-2 absolute (density: 2e-2 absolute + 2e-2 relative,
-because its scale is free).  Rays whose transmittance comes within a few percent of the
+because its scale is free).  Rays whose transmittance comes within MARGIN (relative) of the
 termination threshold may legitimately stop one sample earlier or later than the oracle; the
 skipped / extra sample contributes at most eps, so those rays are compared at tolerance + eps.
+
+A 16-bit pixel bar needs a regime: Eq. 4 multiplies a density error by the sample spacing, and the density of a
+16-bit evaluation is off by up to RHO density units by rounding alone (tests/test_lowprec_model.py), so one
+sample can move a pixel by 1 - exp(-RHO * unit * step).  The 2e-2 bar is asserted where RHO * unit * step <= 2e-2
+(unit * step <= 1 for bf16, <= 8 for fp16: every benchmark workload, 0.34 to 0.68); beyond that regime the bar is
+widened by exactly that term.
 """
 import math
 import os
@@ -20,6 +26,22 @@ from tests.util import cuda, make_pair, scene_dict
 pytestmark = pytest.mark.gpu
 
 TOL = {"f32": 1e-4, "f16": 2e-2, "bf16": 2e-2}
+# relative distance of a ray's transmittance to eps below which the ray may stop one sample apart from the oracle: a few
+# times the relative error of T, which is the summed density error times the step (16-bit: about 3e-3 / 4e-4 density
+# units per sample, tens of samples, unit * step below 1)
+MARGIN = {"f32": 1e-3, "f16": 0.01, "bf16": 0.03}
+# largest density error of a 16-bit evaluation by rounding alone, in density units (the bar on sigma, and an eighth
+# of it: fp16 keeps three more bits)
+RHO = {"f16": 2.5e-3, "bf16": 2e-2}
+
+
+def pixel_bar(wdtype, unit_times_step):
+    """The pixel bar of a 16-bit scene: 2e-2 inside the supported regime, widened beyond it by what the rounding of
+    one sample's density can move a pixel (module docstring)."""
+    if wdtype == "f32":
+        return TOL["f32"]
+    worst = RHO[wdtype] * unit_times_step
+    return TOL[wdtype] + (0.0 if worst <= TOL[wdtype] else 1.0 - math.exp(-worst))
 
 
 def log(*a):
@@ -132,6 +154,35 @@ def test_eval_grouped_matrix_cores(wdtype, H):
     M = 50_021
     pts = ks.uniform_points(M, 5, lo=(-1.02,) * 3, hi=(1.02,) * 3)
     check_eval(sc, pts, ks.sphere_dirs(M, 6))
+
+
+@pytest.mark.parametrize("wdtype,H,unit", [("bf16", 32, 1.0), ("bf16", 64, 100.0), ("f16", 32, 100.0), ("f16", 64, 1.0)])
+def test_matrix_core_kernel_follows_the_rounding_model(wdtype, H, unit):
+    """Rounding or defect?  The kernel against Eq. 7 with every matrix operand rounded to the storage type and
+    nothing else changed (oracle/lowprec.py).  The two can differ only where a sum or a sine lands within the kernel's
+    own fp32 / hardware-sine error of a rounding boundary and one operand comes out one unit in the last place apart,
+    so they agree far more closely than the kernel and the fp64 oracle do: what separates kernel and oracle is the
+    rounding of the operands, which any 16-bit evaluation has."""
+    from oracle import lowprec
+    sc = scene_dict((4, 3, 5), (-1, -1, -1), (1, 1, 1), H, wdtype, 141, sigma_scale=unit)
+    M = 40_009
+    pts, dirs = ks.uniform_points(M, 142, lo=(-1,) * 3, hi=(1,) * 3), ks.sphere_dirs(M, 143)
+    dev, orc = make_pair(sc, threads=True)
+    s_g, c_g = [t.cpu().numpy().astype(np.float64) for t in dev.eval_grouped(cuda(pts), cuda(dirs))]
+    s_o, c_o, ids = orc.eval_points(pts, dirs)
+    s_m, c_m = lowprec.eval_points(sc["weights"], H, ids, pts, dirs, wdtype)
+    to_oracle, to_model = np.abs(s_g - s_o) / unit, np.abs(s_g - s_m) / unit
+    q = lambda a: float(np.quantile(a, 0.99))
+    log("  %s H=%d unit %g: density error / unit, kernel - oracle max %.2e p99 %.2e; kernel - model max %.2e p99 %.2e; "
+        "model - oracle max %.2e; colour: kernel - oracle %.2e, kernel - model p99 %.2e" %
+        (wdtype, H, unit, to_oracle.max(), q(to_oracle), to_model.max(), q(to_model), (np.abs(s_m - s_o) / unit).max(),
+         np.abs(c_g - c_o).max(), q(np.abs(c_g - c_m))))
+    assert to_oracle.max() <= RHO[wdtype] and (np.abs(s_m - s_o) / unit).max() <= RHO[wdtype]     # both within the rounding bound
+    assert q(to_model) <= {"bf16": 3e-3, "f16": 1e-3}[wdtype]
+    assert np.mean(to_model <= 1e-5) > 0.5          # most samples: the model's value up to fp32 summation
+    if wdtype == "bf16":
+        assert q(to_model) < 0.5 * q(to_oracle)
+    assert q(np.abs(c_g - c_m)) <= {"bf16": 2e-3, "f16": 5e-4}[wdtype]
 
 
 def test_eval_grouped_matrix_cores_large_box():
@@ -373,7 +424,7 @@ def render_check(cfg, sel=None, margin=None):
     import torch
     sc = cfg["scene"]
     tol = TOL[sc["wdtype"]]
-    margin = (1e-3 if sc["wdtype"] == "f32" else 0.08) if margin is None else margin
+    margin = MARGIN[sc["wdtype"]] if margin is None else margin
     dev, orc = make_pair(sc, threads=True)
     o, d = cfg["rays_o"], cfg["rays_d"]
     seed = cfg.get("seed")          # stratified sampling with this seed; None: the midpoint lattice
@@ -393,7 +444,7 @@ def render_check(cfg, sel=None, margin=None):
     assert err[~straddle].max() <= tol
     if straddle.any():
         assert err[straddle].max() <= tol + cfg["term_eps"]
-    assert straddle.mean() < (0.002 if sc["wdtype"] == "f32" else 0.2)
+    assert straddle.mean() < {"f32": 0.002, "f16": 0.02, "bf16": 0.06}[sc["wdtype"]]     # observed: 0.001, 0.005, 0.04
     assert stats["rays"] == len(o) and stats["samples_evaluated"] >= stats["samples_blended"]
     if sel is None or len(sel) == len(o):
         if not straddle.any():
@@ -588,6 +639,76 @@ def test_render_random_configurations_fp32():
         kn.set_render_params(0, 0, 0)
 
 
+def test_render_random_configurations_16bit():
+    """Sixty seeded random scenes in fp16 and bf16: widths 32 and 64, grid shapes (nested and not, with and without
+    occupancy, dense and sparse), midpoint and stratified lattices, K from 1 to 600, density units 1 to 100, termination
+    thresholds, wave schedules.  Every pixel against the oracle at `pixel_bar`: 2e-2 wherever density unit x step is in
+    the supported regime, the derived wider bar beyond it (K = 1 and K = 7 with steep density heads); straddling rays
+    (MARGIN, times unit x step beyond 1) at + eps; the blended-sample count equal to the oracle's up to the straddlers."""
+    import torch
+    import paper_2103_13744_amd as kn
+    g = np.random.default_rng(20210316)
+    inside = outside = 0
+    worst_inside = 0.0
+    try:
+        for it in range(60):
+            wd = ["f16", "bf16"][it % 2]
+            H = [32, 64][g.integers(0, 2)]
+            nres = tuple(int(v) for v in g.integers(1, 7, size=3))
+            if g.random() < 0.5:
+                ores = tuple(int(n * 2 ** g.integers(0, 4)) for n in nres)
+            else:
+                ores = tuple(int(v) for v in g.integers(1, 40, size=3))
+            lo = g.uniform(-2, 0, size=3)
+            hi = lo + g.uniform(0.5, 3, size=3)
+            seed = int(g.integers(1, 1 << 30))
+            occ = ks.blob_occupancy(ores, int(g.integers(1, 6)), float(g.uniform(0.05, 0.6)), seed) if g.random() < 0.8 else None
+            unit = float(g.choice([1.0, 10.0, 100.0]))
+            sc = configs._scene(nres, lo, hi, H, wd, seed, sigma_scale=unit, occ=occ)
+            if g.random() < 0.4:
+                present = g.random(int(np.prod(nres))) < g.uniform(0.3, 1.0)
+                present[0] = True
+                sc = configs.sparsify(sc, present, seed + 5)
+            W, Hh = int(g.integers(1, 40)), int(g.integers(1, 40))
+            diag = float(np.linalg.norm(hi - lo))
+            rad = diag * g.uniform(0.8, 1.5)
+            o, d = ks.camera_rays(W, Hh, float(g.uniform(20, 70)), rad, float(g.uniform(0, 360)), float(g.uniform(-60, 60)),
+                                  center=tuple(0.5 * (lo + hi)))
+            K = int([1, 7, 32, 100, 257, 600][it % 6 if it < 12 else g.integers(0, 6)])      # K = 1 and K = 7 for both types at least
+            t_near = max(rad - diag / 2, 0.0) * g.uniform(0.9, 1.0)
+            step = diag / K * g.uniform(0.8, 1.3)
+            eps = float(g.choice([0.0, 0.01, 0.1]))
+            rseed = int(g.integers(0, 1 << 32)) if g.random() < 0.5 else None
+            sched = (int(g.choice([0, 1, 3, 16, 48])), int(g.choice([0, 4, 32, 128])), int(g.choice([0, 2, 4, 32])))
+            kn.set_render_params(*sched)
+            dev, orc = make_pair(sc, threads=True)
+            img, st = dev.render(cuda(o), cuda(d), t_near, step, K, eps, (0.3, 0.6, 0.9), want_stats=True, seed=rseed)
+            torch.cuda.synchronize()
+            ref, n_eval, _, mg = orc.render(o, d, t_near, step, K, eps, (0.3, 0.6, 0.9), seed=rseed)
+            err = np.abs(img.cpu().numpy().astype(np.float64) - ref).max(axis=1)
+            a = unit * float(np.float32(step))
+            straddle = mg < MARGIN[wd] * max(1.0, a)      # the relative error of T is the summed density error x step
+            bar = pixel_bar(wd, a)
+            what = "case %d: %s H %d grid %s occupancy %s sparse %s K %d unit x step %.3g eps %g stratified %s schedule %s" % (
+                it, wd, H, nres, ores if occ is not None else None, "cell_net" in sc, K, a, eps, rseed is not None, sched)
+            log("  %s: bar %.3g, max err %.3g (straddlers: %d, there %.3g)" % (what, bar, err[~straddle].max(initial=0.0),
+                                                                             straddle.sum(), err[straddle].max(initial=0.0)))
+            assert err[~straddle].max(initial=0.0) <= bar, what
+            assert err[straddle].max(initial=0.0) <= bar + eps, what
+            assert abs(st["samples_blended"] - n_eval.sum()) <= straddle.sum(), what
+            assert st["samples_evaluated"] >= st["samples_blended"], what
+            if bar == TOL[wd]:
+                inside += 1
+                worst_inside = max(worst_inside, err[~straddle].max(initial=0.0))
+            else:
+                outside += 1
+                assert np.mean(err > TOL[wd] + eps) <= 0.02, what       # rounding throws few pixels that far
+    finally:
+        kn.set_render_params(0, 0, 0)
+    log("  inside the regime: %d cases, worst pixel %.3g; outside: %d cases" % (inside, worst_inside, outside))
+    assert inside >= 30 and outside >= 5
+
+
 def test_render_on_more_streams_than_mailboxes():
     """A scene has eight host mailboxes, one per stream that renders on it; calls on further streams fall back to
     waiting for the stream.  Same image on every stream."""
@@ -660,19 +781,34 @@ def extraction_check(sc, occ_res, tau, sigma_unit=1.0, voxels=None):
     else:
         want, top, mg = orc.extract_occupancy(occ_res, tau, voxels=voxels)
         got = got.ravel()[voxels]
-    # fp32: the density bar itself.  16-bit: the bar (2e-2) is far wider than the rounding the arithmetic has (every
-    # activation is rounded to 11 / 8 significant bits), and with 27 probes per voxel a margin that wide would leave
-    # a third of the voxels undecided; the margins below are about four roundings.
-    rel = {"f32": 1e-4, "f16": 4e-3, "bf16": 2e-2}[sc["wdtype"]]
-    tol = rel * sigma_unit * (1.0 + (0 if sc["wdtype"] == "f32" else 1) * tau / sigma_unit)
-    close = mg <= tol
-    log("  extraction %s H=%d %s: %d voxels, %.1f %% marked, %d within the density tolerance of tau, %d of those differ"
-        % (sc["wdtype"], sc["hidden"], tuple(occ_res), want.size, 100 * want.mean(), close.sum(), (got != want)[close].sum()))
+    # fp32: the density bar itself.  16-bit: a voxel with a probe within the rounding bound RHO of tau may differ from
+    # the fp64 oracle; with 27 probes per voxel that is a third of the voxels in bf16, so those are checked against the
+    # rounding model instead (Eq. 7 with 16-bit operands, oracle/lowprec.py), which the kernel follows eight times more
+    # closely (test_matrix_core_kernel_follows_the_rounding_model): only voxels that are close to tau there as well
+    # are left undecided.
+    wd = sc["wdtype"]
+    rel = 1e-4 if wd == "f32" else RHO[wd]
+    tol = rel * sigma_unit * (1.0 + (0 if wd == "f32" else 1) * tau / sigma_unit)
+    close = (mg <= tol).ravel()
+    got, want = got.ravel(), want.ravel()
     np.testing.assert_array_equal(got[~close], want[~close])
+    undecided = close
+    if wd != "f32" and close.any():
+        from oracle import lowprec
+        idx = np.flatnonzero(close) if voxels is None else np.asarray(voxels)[close]
+        m_occ, m_mg = lowprec.extract_occupancy(orc, sc["weights"], sc["hidden"], wd, occ_res, tau, voxels=idx)
+        near = m_mg <= tol / 8
+        np.testing.assert_array_equal(got[close][~near], m_occ[~near])
+        undecided = np.zeros_like(close)
+        undecided[np.flatnonzero(close)[near]] = True
+    log("  extraction %s H=%d %s: %d voxels, %.1f %% marked, %d within the rounding bound of tau for the oracle, %d left "
+        "undecided by the rounding model, %d of those differ from the oracle"
+        % (wd, sc["hidden"], tuple(occ_res), want.size, 100 * want.mean(), close.sum(), undecided.sum(),
+           (got != want)[undecided].sum()))
     assert 0.02 < want.mean() < 0.98
-    assert close.mean() < {"f32": 0.002, "f16": 0.12, "bf16": 0.45}[sc["wdtype"]]
-    assert (got != want)[close].sum() <= 0.05 * close.sum() + 2     # and even those mostly agree
-    return dev, got
+    assert undecided.mean() < {"f32": 0.003, "f16": 0.02, "bf16": 0.09}[wd]               # observed: 0.002, 0.01, 0.063
+    assert (got != want)[undecided].sum() <= 0.25 * undecided.sum() + 2     # and even those mostly agree
+    return dev, got.reshape(occ_res) if voxels is None else got
 
 
 def median_density(sc, occ_res):
@@ -899,7 +1035,7 @@ def test_sparse_grid_with_more_cells_than_a_dense_grid_may_have():
     check_eval(sc, pts, ks.sphere_dirs(100_000, 94), sample=np.arange(0, 100_000, 11), sigma_unit=100.0)
 
 
-# ------------------------------------------------------------------ stratified sampling (Sec. 3.3)
+# ------------------------------------------------------------------ stratified sampling (Sec. 3.4)
 def test_stratified_march_bit_exact_and_resumable():
     cfg = configs.config3(40, 40)
     dev, orc = make_pair(cfg["scene"])

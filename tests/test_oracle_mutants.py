@@ -51,6 +51,8 @@ MUTANTS = [
     ("unstable_bucket", "for (int64_t m = 0; m < M; ++m) { /* ascending m => stable */\n        int32_t b = ids[m] < 0 ? N : ids[m];\n        perm[cursor[b]++] = (int32_t)m;",
      "for (int64_t m = M - 1; m >= 0; --m) {\n        int32_t b = ids[m] < 0 ? N : ids[m];\n        perm[cursor[b]++] = (int32_t)m;", "bucket_equals"),
     ("termination_never", "if (T < eps) break;                               /* Sec. 3.4, ERT */", ";", "ert_error"),
+    ("render_never_terminates", "                if (T < eps) break;\n            }\n        }\n        for (int c = 0; c < 3; ++c) rgb_out[3 * r + c]",
+     "                ;\n            }\n        }\n        for (int c = 0; c < 3; ++c) rgb_out[3 * r + c]", "render_stops_where"),
     ("delta_looks_backwards", "return (double)lattice_t(t_near, step, k + 1, j) - (double)lattice_t(t_near, step, k, j);",
      "return (double)lattice_t(t_near, step, k, j) - (double)lattice_t(t_near, step, k - 1, j);", "stratified_render"),
     ("delta_constant_under_stratification", "if (!(j && j->on)) return (double)step;", "if (1) return (double)step;", "stratified_render"),

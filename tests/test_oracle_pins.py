@@ -428,6 +428,31 @@ def test_render_is_march_then_networks_then_blend():
         assert abs(Tr - T[r]) < 1e-5
 
 
+def test_render_stops_where_the_blend_of_its_samples_stops():
+    """Early termination inside the render (Sec. 3.4): a ray's image, final transmittance and number of evaluated
+    samples equal those of blending all its marched samples with the same threshold (the blend stops by itself)."""
+    from kn_synth import configs
+    cfg = configs.config3(16, 16)
+    s = cfg["scene"]
+    sc = OracleScene(s["res"], s["aabb_min"], s["aabb_max"], s["hidden"], s["weights"], s["occupancy"])
+    o, d, eps = cfg["rays_o"], cfg["rays_d"], 0.05
+    rgb, n_eval, T, mg = sc.render(o, d, cfg["t_near"], cfg["step"], cfg["K"], eps, cfg["bg"])
+    step32, tn32 = np.float32(cfg["step"]), np.float32(cfg["t_near"])
+    stopped = 0
+    for r in np.flatnonzero(n_eval > 0)[::3]:
+        kk = sc.march(o[r], d[r], cfg["t_near"], cfg["step"], cfg["K"])
+        t = ((kk.astype(np.float64) + 0.5) * float(step32) + float(tn32)).astype(np.float32)
+        x = (o[r].astype(np.float64) + t[:, None].astype(np.float64) * d[r].astype(np.float64)).astype(np.float32)
+        sg, col, _ = sc.eval_points(x, np.tile(d[r], (len(kk), 1)))
+        out, Tr, used, m = oracle.composite(sg, col, float(step32), eps, cfg["bg"])
+        if m < 1e-3:
+            continue                                      # (positions recomputed here: a ray on the threshold may differ)
+        assert used == n_eval[r] and abs(Tr - T[r]) < 1e-4
+        np.testing.assert_allclose(out, rgb[r], atol=1e-4)
+        stopped += used < len(kk)
+    assert stopped >= 10                                  # rays that ended early, with samples left behind
+
+
 def test_render_ert_bound_and_straddle_margin():
     from kn_synth import configs
     cfg = configs.config3(24, 24)
@@ -527,7 +552,7 @@ def test_a_cell_without_a_network_is_empty_space():
     assert np.array_equal(occ_s, occ_z) and 0 < occ_s.sum() < occ_s.size
 
 
-# ------------------------------------------------------------------ stratified sampling (Sec. 3.3)
+# ------------------------------------------------------------------ stratified sampling (Sec. 3.4)
 def test_stratified_offsets_are_uniform_draws_per_seed_ray_and_sample():
     u = np.array([[[oracle.stratified_offset(s_, r, k) for k in range(64)] for r in range(48)] for s_ in (0, 1, 77)])
     assert u.min() >= 0.0 and u.max() < 1.0
