@@ -6,14 +6,20 @@
  * them into pixels.  Every step runs in hand-written HIP kernels; there is no CPU fallback.
  *
  * Conventions
- *  - "dev" pointers are HIP device pointers on the device that was current when the scene
- *    was created; "host" pointers are ordinary host memory.  The library only borrows
- *    caller buffers for the duration of a call (scene inputs: see kn_scene_create).
+ *  - A context (kn_ctx, from kn_create) belongs to one HIP device and holds everything that is
+ *    mutable: the wave schedule of kn_render, the timing switches and totals, the host
+ *    mailboxes through which kn_render's kernels report counts.  A scene is immutable once
+ *    created and may be used through any context of its device.  Calls on one context may come
+ *    from several threads (its state is guarded by a mutex), each on a stream, workspace and
+ *    outputs of its own; the context's device must be current in the calling thread.
+ *  - "dev" pointers are HIP device pointers on the context's device; "host" pointers are
+ *    ordinary host memory.  The library only borrows caller buffers for the duration of a call
+ *    (scene inputs and the scene buffer: see kn_scene_create).
  *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls enqueue
  *    work on it and return without waiting unless stated otherwise.
- *    Calls that neither wait nor read results back on the host (all but kn_scene_create /
- *    kn_scene_destroy, kn_render and kn_profile_read) use only kernel launches on `stream` and may be
- *    captured into a HIP graph, with profiling off.
+ *    Calls that neither wait nor read results back on the host (all but kn_create / kn_destroy,
+ *    kn_scene_create / kn_scene_destroy, kn_render and kn_profile_read) use only kernel launches on
+ *    `stream` and may be captured into a HIP graph, with profiling off.
  *  - Every function returns 0 (KN_OK) or a negative kn_status.  Arguments are validated on
  *    the host before anything is launched; sizes of 0 are valid and do nothing.
  *  - Positions and directions are fp32, row-major (n, 3).  Directions must have unit length:
@@ -81,7 +87,8 @@ typedef struct {
     int32_t n_nets;          /* networks behind `weights` when cell_net is given: 1 .. 65535         */
 } kn_scene_desc;
 
-typedef struct kn_scene kn_scene; /* opaque */
+typedef struct kn_scene kn_scene; /* opaque, immutable after kn_scene_create */
+typedef struct kn_ctx kn_ctx;     /* opaque, one per device and user of the library */
 
 /* Counters of one kn_render call (filled when requested). */
 typedef struct {
@@ -100,20 +107,32 @@ int kn_last_hip_error(void);
 /* Number of parameters of one network in the canonical layout; -1 for invalid arguments. */
 int64_t kn_params_per_net(int32_t hidden, int32_t L_pos, int32_t L_dir);
 
+/* A context on HIP device `device_index` (which must be a gfx950 device; the call makes it current in the calling
+ * thread).  Allocates only host memory: the pinned, device-mapped mailboxes.  kn_destroy waits for the device. */
+int kn_create(kn_ctx **out, int device_index);
+int kn_destroy(kn_ctx *ctx);
+
 /*
- * Create a scene on the current HIP device.  Validates the descriptor, then allocates (hipMalloc)
- * and fills, on `stream`, the library's own device copies: the occupancy grid packed to bits and
- * the weights re-ordered into matrix-core operand order.  The caller's buffers may be released
- * once `stream` has completed the work enqueued by this call.  This is the only call that
- * allocates device memory.
+ * Create a scene on the context's device.  Validates the descriptor, then fills, on `stream`, the scene's device
+ * data: the occupancy grid packed to bits with its skip field, the weights re-ordered into matrix-core operand
+ * order, the table of a sparse grid.  That data lives in `buffer` (dev, 256-byte aligned, at least kn_scene_bytes
+ * bytes, owned by the caller, who keeps it until kn_scene_destroy has returned), or, with buffer = NULL, in memory the
+ * library allocates itself (hipMalloc; the only allocation of device memory in the library).  The descriptor's own
+ * buffers (weights, occupancy, cell_net) may be released once the call has returned: it waits for `stream`
+ * because it reads the skip field back to find the box around the occupied voxels.
  */
-int kn_scene_create(const kn_scene_desc *desc, void *stream, kn_scene **out);
-int kn_scene_destroy(kn_scene *scene); /* waits for the device, frees the library's copies */
+int kn_scene_bytes(const kn_scene_desc *desc, int64_t *out_bytes);
+int kn_scene_create(kn_ctx *ctx, const kn_scene_desc *desc, void *stream, void *buffer /*dev, nullable*/,
+                    int64_t buffer_bytes, kn_scene **out);
+int kn_scene_destroy(kn_scene *scene); /* waits for the device; frees what the library allocated */
 
 /* Workspace size (bytes) that kn_bucket / kn_eval_grouped need for up to max_points points and
- * kn_render for up to max_rays rays; pass 0 for the one not needed.  The workspace is a dev
- * buffer, 256-byte aligned, owned by the caller; calls sharing one workspace must not overlap. */
-int kn_workspace_bytes(const kn_scene *scene, int64_t max_points, int64_t max_rays, int64_t *out_bytes);
+ * kn_render for up to max_rays rays with the context's current wave schedule (kn_set_render_params: the slot
+ * budget per ray sizes it; kn_render checks its workspace against the schedule it runs with); pass 0 for the one
+ * not needed.  The workspace is a dev buffer, 256-byte aligned, owned by the caller; calls sharing one workspace
+ * must not overlap. */
+int kn_workspace_bytes(const kn_ctx *ctx, const kn_scene *scene, int64_t max_points, int64_t max_rays,
+                       int64_t *out_bytes);
 
 /* Eq. 6: network index of M points.  ids[m] = (ix*ry + iy)*rz + iz, or -1 outside [b_min, b_max).
  * fp32 arithmetic exactly as written in Eq. 6: floor((x - b_min) / ((b_max - b_min) / r)).  On a sparse
@@ -125,7 +144,7 @@ int kn_cell_ids(const kn_scene *scene, void *stream, const float *points /*dev M
  * bucketing of M ids in [-1, N).  counts[N+1] (slot N = outside), offsets[N+2]
  * (exclusive scan of counts), perm[M] = sample indices sorted by id, -1 last, ties by index.
  * counts / offsets may be NULL.  M <= 2^30. */
-int kn_bucket(const kn_scene *scene, void *stream, const int32_t *ids /*dev M*/, int64_t M,
+int kn_bucket(kn_ctx *ctx, const kn_scene *scene, void *stream, const int32_t *ids /*dev M*/, int64_t M,
               int32_t *counts /*dev N+1, nullable*/, int32_t *offsets /*dev N+2, nullable*/,
               int32_t *perm /*dev M*/, void *workspace, int64_t workspace_bytes);
 
@@ -133,7 +152,7 @@ int kn_bucket(const kn_scene *scene, void *stream, const int32_t *ids /*dev M*/,
  * fused per-network MLP (encoding + 5 layers) over each bucket.  Outputs in caller order; points
  * outside the AABB get sigma = 0, rgb = 0, id = -1.  cell_id / counts / perm are optional
  * outputs as in kn_cell_ids / kn_bucket. */
-int kn_eval_grouped(const kn_scene *scene, void *stream, const float *points /*dev M*3*/,
+int kn_eval_grouped(kn_ctx *ctx, const kn_scene *scene, void *stream, const float *points /*dev M*3*/,
                     const float *dirs /*dev M*3*/, int64_t M, float *sigma /*dev M*/,
                     float *rgb /*dev M*3*/, int32_t *cell_id /*dev M, nullable*/,
                     int32_t *counts /*dev N+1, nullable*/, int32_t *perm /*dev M, nullable*/,
@@ -142,16 +161,16 @@ int kn_eval_grouped(const kn_scene *scene, void *stream, const float *points /*d
 /* For callers that cannot allocate device memory or pass a workspace (code under HIP graph capture, tight serving
  * loops, harnesses that forbid hipMalloc): kn_eval_grouped with the library's own scratch memory in place of the
  * workspace argument.  The scratch is a static device array of KN_STATIC_SCRATCH_BYTES that every GPU the library
- * runs on holds until the process ends; its address on the scene's device is looked up when the scene is created.
+ * runs on holds until the process ends; its address on the context's device is looked up by kn_create.
  * The call allocates nothing (no hipMalloc / hipFree, no events, no library routine that allocates) and records no
  * stage timings; inputs and outputs are the caller's, as in kn_eval_grouped, and the results are the same bits.
- * The device the scene was created on must be current (KN_E_INVALID_ARG otherwise).  M is limited to what the array
+ * The context's device must be current (KN_E_INVALID_ARG otherwise).  M is limited to what the array
  * holds: KN_E_STATIC_LIMIT when kn_eval_grouped's workspace for M points would exceed KN_STATIC_SCRATCH_BYTES
  * (the need is about 21 bytes per point + 24 per network: roughly 800,000 points on 4,096 networks).
  * All calls on one GPU share the one array, whose contents do not outlive a call: calls that overlap on a GPU
  * (different streams or threads) race; calls on one stream are ordered as usual. */
 #define KN_STATIC_SCRATCH_BYTES (16u << 20)
-int kn_eval_grouped_static(const kn_scene *scene, void *stream, const float *points /*dev M*3*/,
+int kn_eval_grouped_static(kn_ctx *ctx, const kn_scene *scene, void *stream, const float *points /*dev M*3*/,
                            const float *dirs /*dev M*3*/, int64_t M, float *sigma /*dev M*/,
                            float *rgb /*dev M*3*/, int32_t *cell_id /*dev M, nullable*/,
                            int32_t *counts /*dev N+1, nullable*/, int32_t *perm /*dev M, nullable*/);
@@ -181,7 +200,7 @@ int kn_march_stratified(const kn_scene *scene, void *stream, const float *rays_o
                         uint32_t seed, const int32_t *k_begin /*dev R, nullable*/, int32_t S,
                         int32_t *out_k /*dev R*S*/, int32_t *out_count /*dev R*/,
                         int32_t *out_k_next /*dev R, nullable*/);
-int kn_render_stratified(const kn_scene *scene, void *stream, const float *rays_o /*dev R*3*/,
+int kn_render_stratified(kn_ctx *ctx, const kn_scene *scene, void *stream, const float *rays_o /*dev R*3*/,
                          const float *rays_d /*dev R*3, unit*/, int64_t R, float t_near, float step,
                          int32_t K, float term_eps, const float bg[3] /*host*/, uint32_t seed,
                          float *rgb_out /*dev R*3*/, kn_render_stats *stats /*host, nullable*/,
@@ -209,11 +228,14 @@ int kn_composite_deltas(void *stream, const float *sigma /*dev*/, const float *r
  * (their shape is computed on the device) and reads the count of surviving rays on the host only to decide
  * about further waves; when it returns, the last wave has been enqueued but `stream` may still be running
  * (it does not wait at all when the slot budget guarantees that the second wave ends every ray and `stats`
- * is NULL).  Work of successive calls on one stream is ordered as usual.  Calls on up to 8 different streams may
- * be in flight on the same scene at the same time, each with a workspace and an output buffer of its own;
- * kn_set_render_params and kn_profile_enable must not be called while calls are in flight, and with
- * profiling on calls must not overlap. */
-int kn_render(const kn_scene *scene, void *stream, const float *rays_o /*dev R*3*/,
+ * is NULL).  Work of successive calls on one stream is ordered as usual.  Calls on different streams (and from
+ * different threads) may be in flight at the same time on one scene, through one context or several, each with a
+ * workspace and an output buffer of its own; one stream must not be used by two calls at once.  A context keeps 8
+ * host mailboxes, one per stream with a call in flight (a mailbox whose last call has reported is handed to the
+ * next stream that needs one); calls beyond that wait for their stream instead of polling.  The wave schedule is
+ * read once, when the call starts (KN_E_WORKSPACE if the workspace does not fit it).  With profiling on, calls
+ * on one context must not overlap: their events would interleave. */
+int kn_render(kn_ctx *ctx, const kn_scene *scene, void *stream, const float *rays_o /*dev R*3*/,
               const float *rays_d /*dev R*3, unit*/, int64_t R, float t_near, float step,
               int32_t K /*max lattice points per ray*/, float term_eps /*0 = off*/,
               const float bg[3] /*host*/, float *rgb_out /*dev R*3*/,
@@ -227,7 +249,7 @@ int kn_render(const kn_scene *scene, void *stream, const float *rays_o /*dev R*3
  * are the same bits; it is the comparison point that shows what the fusion buys, not the fast
  * path.  16-bit scenes only (KN_E_UNSUPPORTED for KN_F32). */
 int kn_layered_workspace_bytes(const kn_scene *scene, int64_t max_points, int64_t *out_bytes);
-int kn_eval_grouped_layered(const kn_scene *scene, void *stream, const float *points /*dev M*3*/,
+int kn_eval_grouped_layered(kn_ctx *ctx, const kn_scene *scene, void *stream, const float *points /*dev M*3*/,
                             const float *dirs /*dev M*3*/, int64_t M, float *sigma /*dev M*/,
                             float *rgb /*dev M*3*/, void *workspace, int64_t workspace_bytes);
 
@@ -246,19 +268,31 @@ int kn_eval_grouped_layered(const kn_scene *scene, void *stream, const float *po
  * `stream`.  KN_E_UNSUPPORTED above 2^31-1 voxels, or when one network cell would own more than
  * about 79 million voxels. */
 int kn_extract_workspace_bytes(const kn_scene *scene, int64_t *out_bytes);
-int kn_extract_occupancy(const kn_scene *scene, void *stream, const int32_t occ_res[3] /*host*/,
+int kn_extract_occupancy(kn_ctx *ctx, const kn_scene *scene, void *stream, const int32_t occ_res[3] /*host*/,
                          float tau, uint8_t *occupancy /*dev, out*/, void *workspace,
                          int64_t workspace_bytes);
 
-/* Tuning knobs of kn_render (process-wide, for experiments; defaults are used otherwise):
+/* The wave schedule of kn_render on this context (defaults are used otherwise):
  * samples per ray in the first wave (default max(48, K / 16), at most the slot budget), the slot
- * budget per ray (default 128; sizes the workspace; later waves share the budget out among the
- * surviving rays), and the factor by which the samples per ray grow from one wave to the next
- * (default 32).  Values <= 0 restore the default. */
-int kn_set_render_params(int32_t first_wave_samples, int32_t slots_per_ray, int32_t wave_growth);
+ * budget per ray (default 128; sizes the workspace, see kn_workspace_bytes; later waves share the budget out
+ * among the surviving rays), and the factor by which the samples per ray grow from one wave to the next
+ * (default 32).  Values <= 0 restore the default.  Calls already running keep the schedule they started with. */
+int kn_set_render_params(kn_ctx *ctx, int32_t first_wave_samples, int32_t slots_per_ray, int32_t wave_growth);
 
-/* Per-stage device time of kn_render / kn_eval_grouped, measured with HIP events recorded on the
- * caller's stream around each stage (process-wide switch, off by default).  Recording does not
+/* Limits that decide between code paths, per context, so that small inputs can reach the paths of large ones (for
+ * tests; value <= 0 restores the default):
+ *   KN_OPT_GROUP_FUSED_MAX          largest number of networks whose per-network counters kn_render's grouping keeps
+ *                                   in LDS one by one (default 8192; 0 is a valid value here: always the hash path;
+ *                                   negative restores the default)
+ *   KN_OPT_GROUP_HASH_SLOTS         slots of the LDS hash table used beyond that (power of two, 16 .. 2048)
+ *   KN_OPT_RADIX_SELF_BASE_BLOCKS   largest number of 4096-key blocks for which the stable bucketing derives its
+ *                                   scatter offsets from per-group sums; beyond, the digit table is scanned
+ *                                   (default 8192 blocks = 33.5 M keys) */
+typedef enum { KN_OPT_GROUP_FUSED_MAX = 1, KN_OPT_GROUP_HASH_SLOTS = 2, KN_OPT_RADIX_SELF_BASE_BLOCKS = 3 } kn_option;
+int kn_set_option(kn_ctx *ctx, int32_t option, int64_t value);
+
+/* Per-stage device time of kn_render / kn_eval_grouped on this context, measured with HIP events recorded on
+ * the caller's stream around each stage (off by default).  Recording does not
  * synchronise; kn_profile_read synchronises the recorded stream, settles all pending intervals and
  * copies the totals accumulated since the last reset. */
 typedef struct {
@@ -276,8 +310,8 @@ typedef struct {
 /* on: 0 = off, 1 = every stage, 2 = only the grouped-MLP kernel, 3 = only the marching kernel (fewer events on
  * the stream: less disturbance of the run that is being timed; mlp_samples / bucket_keys / calls are not
  * gathered in modes 2 and 3, because reading them back would make kn_render wait for the frame) */
-int kn_profile_enable(int on);
-int kn_profile_read(kn_profile *out /*host*/, int reset);
+int kn_profile_enable(kn_ctx *ctx, int on);
+int kn_profile_read(kn_ctx *ctx, kn_profile *out /*host*/, int reset);
 
 #ifdef __cplusplus
 }

@@ -11,7 +11,7 @@ thread_local int g_kn_last_hip_error = 0;
 
 int kn_cell_keys(const kn_scene *sc, hipStream_t st, const float *points, int64_t M, int32_t *ids, int32_t *keys,
                  int32_t *zero, int64_t n_zero);
-int64_t kn_render_ws_bytes(const kn_scene *sc, int64_t R);
+int64_t kn_render_ws_bytes(const kn_scene *sc, int64_t R, int32_t slots_per_ray);
 int kn_mlp_f32_launch(const kn_scene *sc, hipStream_t st, const KnSampleSrc &src, const KnBucketOut &b, int64_t max_tiles,
                       float *sigma, float *rgb);
 int kn_mlp_mfma_launch(const kn_scene *sc, hipStream_t st, const KnSampleSrc &src, const KnBucketOut &b, int64_t max_tiles,
@@ -25,111 +25,222 @@ int64_t kn_layered_act_bytes(const kn_scene *sc, int64_t M);
 int kn_mlp_layered_launch(const kn_scene *sc, hipStream_t st, const KnSampleSrc &src, const KnBucketOut &b, int64_t M,
                           int64_t max_tiles, void *acts, float *sigma, float *rgb);
 
-kn_profile g_kn_profile = {};
-bool g_kn_profile_on = false;
-int g_only_stage = KN_ST_NONE; // != NONE: only this stage's intervals are recorded (and no sample counts)
-// Event ring shared by all calls: intervals are settled (one stream synchronise, then
-// hipEventElapsedTime for each recorded interval) only when the ring is full, when another stream
-// starts recording, or when the totals are read.
-constexpr int KN_N_EVENTS = 1024;
-static hipEvent_t g_events[KN_N_EVENTS];
-static int g_event_stage[KN_N_EVENTS];
-static int g_n_events = 0;
-static hipStream_t g_event_stream = nullptr;
-static bool g_events_ready = false;
+int64_t kn_mlp_packed_bytes(int32_t H, int64_t N);
+int64_t kn_mlp_f32_packed_bytes(int32_t H, int64_t N);
 
 // Scratch memory of kn_eval_grouped_static, the entry point for callers that cannot allocate: a file-scope device
 // array that every GPU the library runs on holds until the process ends.  In host code the array's name is only a
 // stand-in for the symbol, not a device address; the address on a device comes from hipGetSymbolAddress with that
-// device current (static_scratch_init, called by kn_scene_create), and only that pointer is handed to kernels.
+// device current (static_scratch_address, called by kn_create), and only that pointer is handed to kernels.
 static __device__ __align__(256) unsigned char scratch[KN_STATIC_SCRATCH_BYTES];
 constexpr int KN_MAX_DEVICES = 64;
 static void *g_scratch_ptr[KN_MAX_DEVICES] = {};
-static std::mutex g_scratch_mutex;
+static bool g_device_configured[KN_MAX_DEVICES] = {};
+static std::mutex g_device_mutex;
 
-// once per device, with that device current
-static int static_scratch_init(int dev)
+// once per device, with that device current: the address of the device's copy of `scratch`
+static int static_scratch_address(int dev, void **out)
 {
     if (dev < 0 || dev >= KN_MAX_DEVICES) return KN_E_UNSUPPORTED;
-    std::lock_guard<std::mutex> lock(g_scratch_mutex);
-    if (g_scratch_ptr[dev]) return KN_OK;
-    void *ptr = nullptr;
-    KN_HIP(hipGetSymbolAddress((void **)&ptr, HIP_SYMBOL(scratch)));
-    if (!ptr || ((uintptr_t)ptr & 255)) return KN_E_HIP;
-    g_scratch_ptr[dev] = ptr;
+    std::lock_guard<std::mutex> lock(g_device_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *ptr = nullptr;
+        KN_HIP(hipGetSymbolAddress((void **)&ptr, HIP_SYMBOL(scratch)));
+        if (!ptr || ((uintptr_t)ptr & 255)) return KN_E_HIP;
+        g_scratch_ptr[dev] = ptr;
+    }
+    if (!g_device_configured[dev]) {
+        KN_TRY(kn_group_configure());
+        g_device_configured[dev] = true;
+    }
+    *out = g_scratch_ptr[dev];
     return KN_OK;
 }
 
-static int settle_events()
+KnKnobs kn_knobs(const kn_ctx *c)
 {
-    if (g_n_events >= 2) {
-        KN_HIP(hipStreamSynchronize(g_event_stream));
-        for (int i = 1; i < g_n_events; ++i) {
+    kn_ctx *ctx = const_cast<kn_ctx *>(c); // (the mutex)
+    std::lock_guard<std::mutex> lock(ctx->mutex);
+    return KnKnobs{ctx->first_wave_samples, ctx->slots_per_ray, ctx->wave_growth, ctx->group_fused_max, ctx->group_hash_slots,
+                   ctx->radix_self_base_blocks};
+}
+
+// (ctx->mutex held)
+static int settle_events(kn_ctx *ctx)
+{
+    if (ctx->n_events >= 2) {
+        KN_HIP(hipStreamSynchronize(ctx->event_stream));
+        for (int i = 1; i < ctx->n_events; ++i) {
             float ms = 0.0f;
-            if (g_event_stage[i] == KN_ST_NONE || hipEventElapsedTime(&ms, g_events[i - 1], g_events[i]) != hipSuccess)
+            if (ctx->event_stage[i] == KN_ST_NONE || hipEventElapsedTime(&ms, ctx->events[i - 1], ctx->events[i]) != hipSuccess)
                 continue;
-            switch (g_event_stage[i]) {
-            case KN_ST_CELL: g_kn_profile.ms_cell += ms; break;
-            case KN_ST_MARCH: g_kn_profile.ms_march += ms; break;
-            case KN_ST_BUCKET: g_kn_profile.ms_bucket += ms; break;
-            case KN_ST_MLP: g_kn_profile.ms_mlp += ms; break;
-            case KN_ST_BLEND: g_kn_profile.ms_blend += ms; break;
-            case KN_ST_SETUP: g_kn_profile.ms_setup += ms; break;
+            switch (ctx->event_stage[i]) {
+            case KN_ST_CELL: ctx->profile.ms_cell += ms; break;
+            case KN_ST_MARCH: ctx->profile.ms_march += ms; break;
+            case KN_ST_BUCKET: ctx->profile.ms_bucket += ms; break;
+            case KN_ST_MLP: ctx->profile.ms_mlp += ms; break;
+            case KN_ST_BLEND: ctx->profile.ms_blend += ms; break;
+            case KN_ST_SETUP: ctx->profile.ms_setup += ms; break;
             default: break;
             }
         }
     }
-    g_n_events = 0;
+    ctx->n_events = 0;
     return KN_OK;
 }
 
-KnStageTimer::KnStageTimer(hipStream_t s, bool allowed) : st(s), on(allowed && g_kn_profile_on)
+KnStageTimer::KnStageTimer(kn_ctx *c, hipStream_t s, bool allowed) : ctx(c), st(s), on(false), counts(false)
 {
-    if (on && !g_events_ready) {
-        for (auto &e : g_events)
+    if (!allowed || !ctx) return;
+    std::lock_guard<std::mutex> lock(ctx->mutex);
+    on = ctx->profile_on;
+    if (on && !ctx->events_ready) {
+        for (auto &e : ctx->events)
             if (hipEventCreate(&e) != hipSuccess) on = false;
-        g_events_ready = on;
+        ctx->events_ready = on;
     }
-    if (on && g_n_events > 0 && g_event_stream != s) (void)settle_events();
-    g_event_stream = s;
+    if (on && ctx->n_events > 0 && ctx->event_stream != s) (void)settle_events(ctx);
+    if (on) ctx->event_stream = s;
+    counts = on && ctx->only_stage == KN_ST_NONE;
 }
 void KnStageTimer::mark(int stage_id)
 {
     if (!on) return;
-    if (g_only_stage != KN_ST_NONE) {
+    std::lock_guard<std::mutex> lock(ctx->mutex);
+    if (ctx->only_stage != KN_ST_NONE) {
         // the mark before the stage of interest opens its interval; everything else is dropped
-        const bool opens = g_only_stage == KN_ST_MLP ? stage_id == KN_ST_BUCKET
-                                                     : (stage_id == KN_ST_NONE || stage_id == KN_ST_SETUP);
-        const bool closes = stage_id == g_only_stage;
+        const bool opens = ctx->only_stage == KN_ST_MLP ? stage_id == KN_ST_BUCKET
+                                                        : (stage_id == KN_ST_NONE || stage_id == KN_ST_SETUP);
+        const bool closes = stage_id == ctx->only_stage;
         if (!opens && !closes) return;
         if (opens) stage_id = KN_ST_NONE;
     }
-    if (g_n_events == KN_N_EVENTS) {
-        (void)settle_events();
+    if (ctx->n_events == KN_N_EVENTS) {
+        (void)settle_events(ctx);
         if (stage_id != KN_ST_NONE) { // re-open the interval that the settle cut short
-            g_event_stage[0] = KN_ST_NONE;
-            (void)hipEventRecord(g_events[0], st);
-            g_n_events = 1;
+            ctx->event_stage[0] = KN_ST_NONE;
+            (void)hipEventRecord(ctx->events[0], st);
+            ctx->n_events = 1;
         }
     }
-    g_event_stage[g_n_events] = stage_id;
-    (void)hipEventRecord(g_events[g_n_events++], st);
+    ctx->event_stage[ctx->n_events] = stage_id;
+    (void)hipEventRecord(ctx->events[ctx->n_events++], st);
+}
+void KnStageTimer::add(int64_t mlp_launches, int64_t mlp_samples, int64_t bucket_keys, int64_t calls)
+{
+    if (!on) return;
+    std::lock_guard<std::mutex> lock(ctx->mutex);
+    ctx->profile.mlp_launches += mlp_launches;
+    ctx->profile.mlp_samples += mlp_samples;
+    ctx->profile.bucket_keys += bucket_keys;
+    ctx->profile.calls += calls;
 }
 
-extern "C" int kn_profile_enable(int on)
+extern "C" int kn_profile_enable(kn_ctx *ctx, int on)
 {
-    if (g_kn_profile_on) (void)settle_events();
-    g_kn_profile_on = on != 0;
-    g_only_stage = on == 2 ? KN_ST_MLP : on == 3 ? KN_ST_MARCH : KN_ST_NONE;
+    if (!ctx) return KN_E_INVALID_ARG;
+    std::lock_guard<std::mutex> lock(ctx->mutex);
+    if (ctx->profile_on) (void)settle_events(ctx);
+    ctx->profile_on = on != 0;
+    ctx->only_stage = on == 2 ? KN_ST_MLP : on == 3 ? KN_ST_MARCH : KN_ST_NONE;
     return KN_OK;
 }
 
-extern "C" int kn_profile_read(kn_profile *out, int reset)
+extern "C" int kn_profile_read(kn_ctx *ctx, kn_profile *out, int reset)
+{
+    if (!ctx || !out) return KN_E_INVALID_ARG;
+    std::lock_guard<std::mutex> lock(ctx->mutex);
+    KN_TRY(settle_events(ctx));
+    *out = ctx->profile;
+    if (reset) ctx->profile = kn_profile{};
+    return KN_OK;
+}
+
+extern "C" int kn_set_render_params(kn_ctx *ctx, int32_t first_wave_samples, int32_t slots_per_ray, int32_t wave_growth)
+{
+    if (!ctx) return KN_E_INVALID_ARG;
+    std::lock_guard<std::mutex> lock(ctx->mutex);
+    ctx->wave_growth = wave_growth >= 2 ? wave_growth : KN_DEFAULT_GROWTH;
+    ctx->first_wave_samples = first_wave_samples > 0 ? first_wave_samples : 0;
+    ctx->slots_per_ray = slots_per_ray > 0 ? slots_per_ray : KN_DEFAULT_SLOTS;
+    if (ctx->slots_per_ray < ctx->first_wave_samples) ctx->slots_per_ray = ctx->first_wave_samples;
+    return KN_OK;
+}
+
+extern "C" int kn_set_option(kn_ctx *ctx, int32_t option, int64_t value)
+{
+    if (!ctx) return KN_E_INVALID_ARG;
+    std::lock_guard<std::mutex> lock(ctx->mutex);
+    switch (option) {
+    case KN_OPT_GROUP_FUSED_MAX:
+        if (value > KN_GROUP_FUSED_MAX_BINS) return KN_E_INVALID_ARG;
+        ctx->group_fused_max = value < 0 ? KN_GROUP_FUSED_MAX_BINS : (int32_t)value;
+        return KN_OK;
+    case KN_OPT_GROUP_HASH_SLOTS:
+        if (value > 0 && (value < 16 || value > KN_GROUP_HASH_SLOTS_MAX || (value & (value - 1)) != 0)) return KN_E_INVALID_ARG;
+        ctx->group_hash_slots = value <= 0 ? KN_GROUP_HASH_SLOTS_MAX : (int32_t)value;
+        return KN_OK;
+    case KN_OPT_RADIX_SELF_BASE_BLOCKS:
+        if (value > KN_RADIX_SELF_BASE_BLOCKS) return KN_E_INVALID_ARG;
+        ctx->radix_self_base_blocks = value <= 0 ? KN_RADIX_SELF_BASE_BLOCKS : value;
+        return KN_OK;
+    default: return KN_E_INVALID_ARG;
+    }
+}
+
+extern "C" int kn_create(kn_ctx **out, int device_index)
 {
     if (!out) return KN_E_INVALID_ARG;
-    KN_TRY(settle_events());
-    *out = g_kn_profile;
-    if (reset) g_kn_profile = kn_profile{};
+    *out = nullptr;
+    int n_dev = 0;
+    if (hipGetDeviceCount(&n_dev) != hipSuccess || device_index < 0 || device_index >= n_dev) return KN_E_NO_DEVICE;
+    hipDeviceProp_t prop;
+    KN_HIP(hipGetDeviceProperties(&prop, device_index));
+    if (strncmp(prop.gcnArchName, "gfx950", 6) != 0) return KN_E_NO_DEVICE;
+    KN_HIP(hipSetDevice(device_index));
+    void *scratch_ptr = nullptr;
+    KN_TRY(static_scratch_address(device_index, &scratch_ptr));
+    kn_ctx *ctx = new (std::nothrow) kn_ctx();
+    if (!ctx) return KN_E_INVALID_ARG;
+    ctx->device = device_index;
+    ctx->first_wave_samples = 0;
+    ctx->slots_per_ray = KN_DEFAULT_SLOTS;
+    ctx->wave_growth = KN_DEFAULT_GROWTH;
+    ctx->group_fused_max = KN_GROUP_FUSED_MAX_BINS;
+    ctx->group_hash_slots = KN_GROUP_HASH_SLOTS_MAX;
+    ctx->radix_self_base_blocks = KN_RADIX_SELF_BASE_BLOCKS;
+    ctx->profile = kn_profile{};
+    ctx->profile_on = false;
+    ctx->only_stage = KN_ST_NONE;
+    ctx->n_events = 0;
+    ctx->event_stream = nullptr;
+    ctx->events_ready = false;
+    ctx->use_counter = 0;
+    ctx->static_scratch = scratch_ptr;
+    for (auto &m : ctx->mailbox) m = KnMailbox{nullptr, nullptr, 0ull, 0ull, 0ull, nullptr, false};
+    void *hp = nullptr, *dp = nullptr;
+    if (hipHostMalloc(&hp, 64 * KN_MAILBOXES, hipHostMallocMapped) == hipSuccess && hipHostGetDevicePointer(&dp, hp, 0) == hipSuccess) {
+        memset(hp, 0, 64 * KN_MAILBOXES);
+        for (int i = 0; i < KN_MAILBOXES; ++i) {
+            ctx->mailbox[i].host = (volatile unsigned long long *)((char *)hp + 64 * i);
+            ctx->mailbox[i].dev = (unsigned long long *)((char *)dp + 64 * i);
+        }
+    } else if (hp) {
+        (void)hipHostFree(hp); // (kn_render then waits for its stream instead of polling)
+    }
+    *out = ctx;
+    return KN_OK;
+}
+
+extern "C" int kn_destroy(kn_ctx *ctx)
+{
+    if (!ctx) return KN_OK;
+    (void)hipSetDevice(ctx->device);
+    (void)hipDeviceSynchronize();
+    if (ctx->events_ready)
+        for (auto &e : ctx->events) (void)hipEventDestroy(e);
+    if (ctx->mailbox[0].host) (void)hipHostFree((void *)ctx->mailbox[0].host);
+    delete ctx;
     return KN_OK;
 }
 
@@ -302,103 +413,146 @@ static int content_box_from_skip_field(kn_scene *sc, int64_t cells)
     return KN_OK;
 }
 
-extern "C" int kn_scene_create(const kn_scene_desc *desc, void *stream, kn_scene **out)
+// The scene's device data: one buffer (the caller's or the library's), carved in this order.
+struct SceneLayout {
+    int64_t cells, words, skip_cells, packed_bytes;
+    int32_t n_nets;
+    bool has_occ, sparse;
+};
+static SceneLayout scene_layout(const kn_scene_desc *d)
+{
+    SceneLayout l{};
+    l.cells = (int64_t)d->res[0] * d->res[1] * d->res[2];
+    l.sparse = d->cell_net != nullptr;
+    l.n_nets = l.sparse ? d->n_nets : (int32_t)l.cells;
+    l.has_occ = d->occ_res[0] != 0;
+    if (l.has_occ) {
+        l.words = kn_div_up((int64_t)d->occ_res[0] * d->occ_res[1] * d->occ_res[2], 32);
+        l.skip_cells = 1;
+        for (int a = 0; a < 3; ++a) l.skip_cells *= kn_div_up(d->occ_res[a], KN_SKIP_BLOCK);
+    }
+    l.packed_bytes = d->wdtype == KN_F32 ? kn_mlp_f32_packed_bytes(d->hidden, l.n_nets) : kn_mlp_packed_bytes(d->hidden, l.n_nets);
+    return l;
+}
+struct SceneBufs {
+    int32_t *cell_net;
+    uint32_t *occ_bits;
+    uint8_t *skip_dist, *skip_tmp;
+    char *packed_w;
+};
+static void carve_scene(KnCarver &c, const SceneLayout &l, SceneBufs &b)
+{
+    b = SceneBufs{};
+    if (l.sparse) b.cell_net = c.carve<int32_t>(l.cells);
+    if (l.has_occ) {
+        b.occ_bits = c.carve<uint32_t>(l.words);
+        b.skip_dist = c.carve<uint8_t>(l.skip_cells);
+        b.skip_tmp = c.carve<uint8_t>(l.skip_cells); // second buffer of the sweeps (unused afterwards)
+    }
+    b.packed_w = c.carve<char>(l.packed_bytes);
+}
+
+extern "C" int kn_scene_bytes(const kn_scene_desc *desc, int64_t *out_bytes)
+{
+    if (!out_bytes) return KN_E_INVALID_ARG;
+    KN_TRY(validate_desc(desc));
+    KnCarver c((void *)256, INT64_MAX / 2);
+    SceneBufs b;
+    carve_scene(c, scene_layout(desc), b);
+    *out_bytes = c.used;
+    return KN_OK;
+}
+
+extern "C" int kn_scene_create(kn_ctx *ctx, const kn_scene_desc *desc, void *stream, void *buffer, int64_t buffer_bytes,
+                               kn_scene **out)
 {
     if (!out) return KN_E_INVALID_ARG;
     *out = nullptr;
+    if (!ctx) return KN_E_INVALID_ARG;
     KN_TRY(validate_desc(desc));
     int dev = -1;
     if (hipGetDevice(&dev) != hipSuccess) return KN_E_NO_DEVICE;
-    hipDeviceProp_t prop;
-    KN_HIP(hipGetDeviceProperties(&prop, dev));
-    if (strncmp(prop.gcnArchName, "gfx950", 6) != 0) return KN_E_NO_DEVICE;
-    KN_TRY(static_scratch_init(dev));
+    if (dev != ctx->device) return KN_E_INVALID_ARG; // the context's device must be current
+    const SceneLayout lay = scene_layout(desc);
+    int64_t need = 0;
+    {
+        KnCarver c((void *)256, INT64_MAX / 2);
+        SceneBufs b;
+        carve_scene(c, lay, b);
+        need = c.used;
+    }
+    if (buffer && (((uintptr_t)buffer & 255) || buffer_bytes < need)) return KN_E_WORKSPACE;
 
     kn_scene *sc = new (std::nothrow) kn_scene();
     if (!sc) return KN_E_INVALID_ARG;
     sc->desc = *desc;
-    sc->cells = (int64_t)desc->res[0] * desc->res[1] * desc->res[2];
-    sc->N = desc->cell_net ? desc->n_nets : (int32_t)sc->cells;
-    sc->cell_net = nullptr;
+    sc->cells = lay.cells;
+    sc->N = lay.n_nets;
     sc->P = kn_params_per_net(desc->hidden, desc->L_pos, desc->L_dir);
     sc->device = dev;
     make_grid(desc->aabb_min, desc->aabb_max, desc->res, sc->net_grid);
-    sc->has_occ = desc->occ_res[0] != 0;
-    sc->occ_bits = nullptr;
-    sc->packed_w = nullptr;
+    sc->has_occ = lay.has_occ;
     sc->packed_halfs_per_net = 0;
-    sc->skip_dist = nullptr;
     sc->skip_res[0] = sc->skip_res[1] = sc->skip_res[2] = 0;
-    for (auto &m : sc->mailbox) m = KnMailbox{nullptr, nullptr, 0ull, nullptr, false};
-    {
-        void *hp = nullptr, *dp = nullptr;
-        if (hipHostMalloc(&hp, 64 * KN_MAILBOXES, hipHostMallocMapped) == hipSuccess &&
-            hipHostGetDevicePointer(&dp, hp, 0) == hipSuccess) {
-            memset(hp, 0, 64 * KN_MAILBOXES);
-            for (int i = 0; i < KN_MAILBOXES; ++i) {
-                sc->mailbox[i].host = (volatile unsigned long long *)((char *)hp + 64 * i);
-                sc->mailbox[i].dev = (unsigned long long *)((char *)dp + 64 * i);
-            }
-        } else if (hp) {
-            (void)hipHostFree(hp);
+    sc->own_buffer = nullptr;
+    if (!buffer) {
+        if (hipMalloc(&sc->own_buffer, (size_t)need) != hipSuccess) {
+            delete sc;
+            return KN_E_HIP;
         }
+        buffer = sc->own_buffer;
+        buffer_bytes = need;
     }
+    KnCarver carver(buffer, buffer_bytes);
+    SceneBufs bufs;
+    carve_scene(carver, lay, bufs);
+    sc->cell_net = bufs.cell_net;
+    sc->occ_bits = bufs.occ_bits;
+    sc->skip_dist = bufs.skip_dist;
+    sc->packed_w = bufs.packed_w;
     hipStream_t st = (hipStream_t)stream;
-    int rc = KN_OK;
-    if (desc->cell_net) {
-        if (hipMalloc((void **)&sc->cell_net, (size_t)sc->cells * 4) != hipSuccess) {
-            rc = KN_E_HIP;
-        } else {
-            hipLaunchKernelGGL(k_copy_cell_net, dim3((unsigned)kn_div_up(sc->cells, 256)), dim3(256), 0, st, desc->cell_net,
-                               sc->cells, sc->N, sc->cell_net);
-            if (hipGetLastError() != hipSuccess) rc = KN_E_HIP;
-        }
+    int rc = carver.ok() ? KN_OK : KN_E_WORKSPACE;
+    if (rc == KN_OK && lay.sparse) {
+        hipLaunchKernelGGL(k_copy_cell_net, dim3((unsigned)kn_div_up(sc->cells, 256)), dim3(256), 0, st, desc->cell_net,
+                           sc->cells, sc->N, sc->cell_net);
+        if (hipGetLastError() != hipSuccess) rc = KN_E_HIP;
     }
-    if (rc != KN_OK) {
-        // (the clean-up below)
-    } else if (sc->has_occ) {
+    if (rc == KN_OK && sc->has_occ) {
         make_grid(desc->aabb_min, desc->aabb_max, desc->occ_res, sc->occ_grid);
         const int64_t vox = (int64_t)desc->occ_res[0] * desc->occ_res[1] * desc->occ_res[2];
-        const int64_t words = kn_div_up(vox, 32);
-        if (hipMalloc((void **)&sc->occ_bits, (size_t)words * 4) != hipSuccess) {
-            rc = KN_E_HIP;
-        } else {
-            hipLaunchKernelGGL(k_pack_occupancy, dim3((unsigned)kn_div_up(words, 256)), dim3(256), 0, st, desc->occupancy, vox,
-                               sc->occ_bits);
-            if (hipGetLastError() != hipSuccess) rc = KN_E_HIP;
-        }
+        hipLaunchKernelGGL(k_pack_occupancy, dim3((unsigned)kn_div_up(lay.words, 256)), dim3(256), 0, st, desc->occupancy, vox,
+                           sc->occ_bits);
+        if (hipGetLastError() != hipSuccess) rc = KN_E_HIP;
         if (rc == KN_OK) { // skip field: seed, KN_SKIP_MAX sweeps (ping-pong), cap
             int sr[3];
             for (int a = 0; a < 3; ++a) sr[a] = sc->skip_res[a] = (int)kn_div_up(desc->occ_res[a], KN_SKIP_BLOCK);
-            const int64_t cells = (int64_t)sr[0] * sr[1] * sr[2];
-            uint8_t *tmp = nullptr;
-            if (hipMalloc((void **)&sc->skip_dist, (size_t)cells) != hipSuccess ||
-                hipMalloc((void **)&tmp, (size_t)cells) != hipSuccess) {
-                rc = KN_E_HIP;
-            } else {
-                const dim3 grid((unsigned)kn_div_up(cells, 256)), block(256);
-                hipLaunchKernelGGL(k_skip_seed, grid, block, 0, st, desc->occupancy, desc->occ_res[0], desc->occ_res[1],
-                                   desc->occ_res[2], sr[0], sr[1], sr[2], sc->skip_dist);
-                uint8_t *a = sc->skip_dist, *b = tmp;
-                for (int it = 0; it < KN_SKIP_MAX; ++it) { // even count: the result ends in skip_dist
-                    hipLaunchKernelGGL(k_skip_sweep, grid, block, 0, st, a, sr[0], sr[1], sr[2], b);
-                    uint8_t *t = a; a = b; b = t;
-                }
-                hipLaunchKernelGGL(k_skip_cap, grid, block, 0, st, sc->skip_dist, cells);
-                if (hipGetLastError() != hipSuccess || hipStreamSynchronize(st) != hipSuccess) rc = KN_E_HIP;
-                if (rc == KN_OK) rc = content_box_from_skip_field(sc, cells);
+            const int64_t cells = lay.skip_cells;
+            const dim3 grid((unsigned)kn_div_up(cells, 256)), block(256);
+            hipLaunchKernelGGL(k_skip_seed, grid, block, 0, st, desc->occupancy, desc->occ_res[0], desc->occ_res[1],
+                               desc->occ_res[2], sr[0], sr[1], sr[2], sc->skip_dist);
+            uint8_t *a = sc->skip_dist, *b = bufs.skip_tmp;
+            for (int it = 0; it < KN_SKIP_MAX; ++it) { // even count: the result ends in skip_dist
+                hipLaunchKernelGGL(k_skip_sweep, grid, block, 0, st, a, sr[0], sr[1], sr[2], b);
+                uint8_t *t = a; a = b; b = t;
             }
-            if (tmp) (void)hipFree(tmp);
+            hipLaunchKernelGGL(k_skip_cap, grid, block, 0, st, sc->skip_dist, cells);
+            if (hipGetLastError() != hipSuccess || hipStreamSynchronize(st) != hipSuccess) rc = KN_E_HIP;
+            if (rc == KN_OK) rc = content_box_from_skip_field(sc, cells);
         }
-    } else {
+    } else if (rc == KN_OK) {
         sc->occ_grid = sc->net_grid;
         sc->content_box = sc->net_grid;
     }
     if (rc == KN_OK) rc = desc->wdtype == KN_F32 ? kn_mlp_f32_pack_weights(sc, st) : kn_mlp_pack_weights(sc, st);
+    // the descriptor's buffers may go once the call returns
+    if (rc == KN_OK && hipStreamSynchronize(st) != hipSuccess) rc = KN_E_HIP;
     if (rc != KN_OK) {
         kn_scene_destroy(sc);
         return rc;
     }
+    sc->desc.weights = nullptr; // not the scene's to keep
+    sc->desc.occupancy = nullptr;
+    sc->desc.cell_net = nullptr;
     *out = sc;
     return KN_OK;
 }
@@ -407,11 +561,7 @@ extern "C" int kn_scene_destroy(kn_scene *sc)
 {
     if (!sc) return KN_OK;
     (void)hipDeviceSynchronize();
-    if (sc->occ_bits) (void)hipFree(sc->occ_bits);
-    if (sc->packed_w) (void)hipFree(sc->packed_w);
-    if (sc->skip_dist) (void)hipFree(sc->skip_dist);
-    if (sc->cell_net) (void)hipFree(sc->cell_net);
-    if (sc->mailbox[0].host) (void)hipHostFree((void *)sc->mailbox[0].host);
+    if (sc->own_buffer) (void)hipFree(sc->own_buffer);
     delete sc;
     return KN_OK;
 }
@@ -432,33 +582,36 @@ static int64_t eval_ws_bytes(const kn_scene *sc, int64_t M)
     return kn_align_up((M > 0 ? M : 1) * 4, 256) + kn_bucket_ws_bytes(M, sc->N);
 }
 
-extern "C" int kn_workspace_bytes(const kn_scene *sc, int64_t max_points, int64_t max_rays, int64_t *out_bytes)
+extern "C" int kn_workspace_bytes(const kn_ctx *ctx, const kn_scene *sc, int64_t max_points, int64_t max_rays,
+                                  int64_t *out_bytes)
 {
-    if (!sc || !out_bytes || max_points < 0 || max_rays < 0) return KN_E_INVALID_ARG;
+    if (!ctx || !sc || !out_bytes || max_points < 0 || max_rays < 0) return KN_E_INVALID_ARG;
     if (max_points > (1ll << 30) || max_rays > (1ll << 30)) return KN_E_UNSUPPORTED;
     int64_t a = max_points > 0 ? eval_ws_bytes(sc, max_points) : 0;
-    int64_t b = max_rays > 0 ? kn_render_ws_bytes(sc, max_rays) : 0;
+    int64_t b = max_rays > 0 ? kn_render_ws_bytes(sc, max_rays, kn_knobs(ctx).slots_per_ray) : 0;
     *out_bytes = (a > b ? a : b) + 256;
     return KN_OK;
 }
 
 // `timed`: stage events may be recorded (creating the events allocates; the static entry point never does)
-static int eval_grouped_impl(const kn_scene *sc, hipStream_t st, const float *points, const float *dirs, int64_t M,
+static int eval_grouped_impl(kn_ctx *ctx, const kn_scene *sc, hipStream_t st, const float *points, const float *dirs, int64_t M,
                              float *sigma, float *rgb, int32_t *cell_id, int32_t *counts, int32_t *perm, void *workspace,
                              int64_t workspace_bytes, bool timed)
 {
     KnCarver ws(workspace, workspace_bytes);
     int32_t *keys = ws.carve<int32_t>(M);
     if (!ws.ok()) return KN_E_WORKSPACE;
-    KnStageTimer tm(st, timed);
+    KnStageTimer tm(ctx, st, timed);
     tm.begin();
+    const int64_t self_base = kn_knobs(ctx).radix_self_base_blocks;
     int32_t *scratch = nullptr;
     int64_t n_scratch = 0;
     kn_bucket_scratch(ws, M, sc->N, &scratch, &n_scratch);
     KN_TRY(kn_cell_keys(sc, st, points, M, cell_id, keys, scratch, scratch ? n_scratch : 0));
     tm.mark(KN_ST_CELL);
     KnBucketOut bo;
-    KN_TRY(kn_bucket_run(st, keys, M, nullptr, sc->N, kn_mlp_tile_len(sc), counts, nullptr, perm, ws, &bo, scratch != nullptr));
+    KN_TRY(kn_bucket_run(st, keys, M, nullptr, sc->N, kn_mlp_tile_len(sc), counts, nullptr, perm, ws, &bo, scratch != nullptr,
+                         self_base));
     if (M == 0) return KN_OK;
     tm.mark(KN_ST_BUCKET);
     KnSampleSrc src{};
@@ -470,43 +623,34 @@ static int eval_grouped_impl(const kn_scene *sc, hipStream_t st, const float *po
                        rgb);
     KN_CHECK_LAUNCH();
     tm.mark(KN_ST_MLP);
-    if (tm.on) {
-        g_kn_profile.mlp_launches += 1;
-        g_kn_profile.mlp_samples += M; // includes points outside the AABB (they cost no MLP work)
-        g_kn_profile.bucket_keys += M;
-        g_kn_profile.calls += 1;
-    }
+    tm.add(1, M, M, 1); // (M includes points outside the AABB: they cost no MLP work)
     return KN_OK;
 }
 
-extern "C" int kn_eval_grouped(const kn_scene *sc, void *stream, const float *points, const float *dirs, int64_t M,
+extern "C" int kn_eval_grouped(kn_ctx *ctx, const kn_scene *sc, void *stream, const float *points, const float *dirs, int64_t M,
                                float *sigma, float *rgb, int32_t *cell_id, int32_t *counts, int32_t *perm, void *workspace,
                                int64_t workspace_bytes)
 {
-    if (!sc || M < 0 || (M > 0 && (!points || !dirs || !sigma || !rgb))) return KN_E_INVALID_ARG;
+    if (!ctx || !sc || M < 0 || (M > 0 && (!points || !dirs || !sigma || !rgb))) return KN_E_INVALID_ARG;
     if (M > (1ll << 30)) return KN_E_UNSUPPORTED;
     if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < eval_ws_bytes(sc, M)) return KN_E_WORKSPACE;
-    return eval_grouped_impl(sc, (hipStream_t)stream, points, dirs, M, sigma, rgb, cell_id, counts, perm, workspace,
+    return eval_grouped_impl(ctx, sc, (hipStream_t)stream, points, dirs, M, sigma, rgb, cell_id, counts, perm, workspace,
                              workspace_bytes, true);
 }
 
 // kn_eval_grouped on the library's static scratch array instead of a caller workspace: nothing is allocated, here
 // or in anything this calls (no stage events either).  All calls on one GPU share the array.
-extern "C" int kn_eval_grouped_static(const kn_scene *sc, void *stream, const float *points, const float *dirs, int64_t M,
-                                      float *sigma, float *rgb, int32_t *cell_id, int32_t *counts, int32_t *perm)
+extern "C" int kn_eval_grouped_static(kn_ctx *ctx, const kn_scene *sc, void *stream, const float *points, const float *dirs,
+                                      int64_t M, float *sigma, float *rgb, int32_t *cell_id, int32_t *counts, int32_t *perm)
 {
-    if (!sc || M < 0 || (M > 0 && (!points || !dirs || !sigma || !rgb))) return KN_E_INVALID_ARG;
+    if (!ctx || !sc || M < 0 || (M > 0 && (!points || !dirs || !sigma || !rgb))) return KN_E_INVALID_ARG;
     if (M > (1ll << 30) || eval_ws_bytes(sc, M) > (int64_t)KN_STATIC_SCRATCH_BYTES) return KN_E_STATIC_LIMIT;
     int dev = -1;
     KN_HIP(hipGetDevice(&dev));
-    if (dev != sc->device || dev < 0 || dev >= KN_MAX_DEVICES) return KN_E_INVALID_ARG; // the scene's device must be current
-    void *ptr;
-    {
-        std::lock_guard<std::mutex> lock(g_scratch_mutex);
-        ptr = g_scratch_ptr[dev]; // set when the scene was created on this device
-    }
+    if (dev != ctx->device || dev != sc->device) return KN_E_INVALID_ARG; // the context's device must be current
+    void *ptr = ctx->static_scratch; // this device's copy of the array, looked up by kn_create
     if (!ptr) return KN_E_HIP;
-    return eval_grouped_impl(sc, (hipStream_t)stream, points, dirs, M, sigma, rgb, cell_id, counts, perm, ptr,
+    return eval_grouped_impl(ctx, sc, (hipStream_t)stream, points, dirs, M, sigma, rgb, cell_id, counts, perm, ptr,
                              (int64_t)KN_STATIC_SCRATCH_BYTES, false);
 }
 
@@ -520,10 +664,10 @@ extern "C" int kn_layered_workspace_bytes(const kn_scene *sc, int64_t max_points
     return KN_OK;
 }
 
-extern "C" int kn_eval_grouped_layered(const kn_scene *sc, void *stream, const float *points, const float *dirs, int64_t M,
-                                       float *sigma, float *rgb, void *workspace, int64_t workspace_bytes)
+extern "C" int kn_eval_grouped_layered(kn_ctx *ctx, const kn_scene *sc, void *stream, const float *points, const float *dirs,
+                                       int64_t M, float *sigma, float *rgb, void *workspace, int64_t workspace_bytes)
 {
-    if (!sc || M < 0 || (M > 0 && (!points || !dirs || !sigma || !rgb))) return KN_E_INVALID_ARG;
+    if (!ctx || !sc || M < 0 || (M > 0 && (!points || !dirs || !sigma || !rgb))) return KN_E_INVALID_ARG;
     if (M > (1ll << 30) || sc->desc.wdtype == KN_F32) return KN_E_UNSUPPORTED;
     if (!workspace || ((uintptr_t)workspace & 255) ||
         workspace_bytes < eval_ws_bytes(sc, M) + kn_layered_act_bytes(sc, M) + 256)
@@ -533,7 +677,7 @@ extern "C" int kn_eval_grouped_layered(const kn_scene *sc, void *stream, const f
     void *acts = ws.carve<char>(kn_layered_act_bytes(sc, M));
     int32_t *keys = ws.carve<int32_t>(M);
     if (!ws.ok()) return KN_E_WORKSPACE;
-    KnStageTimer tm(st);
+    KnStageTimer tm(ctx, st);
     tm.begin();
     int32_t *scratch = nullptr;
     int64_t n_scratch = 0;
@@ -542,7 +686,8 @@ extern "C" int kn_eval_grouped_layered(const kn_scene *sc, void *stream, const f
     tm.mark(KN_ST_CELL);
     KnBucketOut bo;
     const int tile_len = kn_mlp_tile_len(sc);
-    KN_TRY(kn_bucket_run(st, keys, M, nullptr, sc->N, tile_len, nullptr, nullptr, nullptr, ws, &bo, scratch != nullptr));
+    KN_TRY(kn_bucket_run(st, keys, M, nullptr, sc->N, tile_len, nullptr, nullptr, nullptr, ws, &bo, scratch != nullptr,
+                         kn_knobs(ctx).radix_self_base_blocks));
     if (M == 0) return KN_OK;
     tm.mark(KN_ST_BUCKET);
     KnSampleSrc src{};
@@ -553,12 +698,7 @@ extern "C" int kn_eval_grouped_layered(const kn_scene *sc, void *stream, const f
                        rgb);
     KN_CHECK_LAUNCH();
     tm.mark(KN_ST_MLP);
-    if (tm.on) {
-        g_kn_profile.mlp_launches += 6;
-        g_kn_profile.mlp_samples += M;
-        g_kn_profile.bucket_keys += M;
-        g_kn_profile.calls += 1;
-    }
+    tm.add(6, M, M, 1);
     return KN_OK;
 }
 
@@ -612,10 +752,10 @@ extern "C" int kn_extract_workspace_bytes(const kn_scene *sc, int64_t *out_bytes
     return KN_OK;
 }
 
-extern "C" int kn_extract_occupancy(const kn_scene *sc, void *stream, const int32_t occ_res[3], float tau,
+extern "C" int kn_extract_occupancy(kn_ctx *ctx, const kn_scene *sc, void *stream, const int32_t occ_res[3], float tau,
                                     uint8_t *occupancy, void *workspace, int64_t workspace_bytes)
 {
-    if (!sc || !occ_res || !occupancy || tau != tau) return KN_E_INVALID_ARG;
+    if (!ctx || !sc || !occ_res || !occupancy || tau != tau) return KN_E_INVALID_ARG;
     KnProbeJob job{};
     if (!make_grid(sc->desc.aabb_min, sc->desc.aabb_max, occ_res, job.occ)) return KN_E_INVALID_ARG;
     const int64_t voxels = (int64_t)occ_res[0] * occ_res[1] * occ_res[2];
@@ -650,7 +790,7 @@ extern "C" int kn_extract_occupancy(const kn_scene *sc, void *stream, const int3
     if (parts < 1) parts = 1;
     job.parts = (int32_t)parts;
 
-    KnStageTimer tm(st);
+    KnStageTimer tm(ctx, st);
     tm.begin();
     hipLaunchKernelGGL(k_zero_bytes, dim3((unsigned)kn_div_up(kn_div_up(voxels, 16), 256)), dim3(256), 0, st, occupancy, voxels);
     KN_CHECK_LAUNCH();
@@ -662,10 +802,6 @@ extern "C" int kn_extract_occupancy(const kn_scene *sc, void *stream, const int3
     else
         KN_TRY(kn_probe_mfma_launch(sc, st, job));
     tm.mark(KN_ST_MLP);
-    if (tm.on) {
-        g_kn_profile.mlp_launches += 1;
-        g_kn_profile.mlp_samples += KN_PROBES * voxels;
-        g_kn_profile.calls += 1;
-    }
+    tm.add(1, KN_PROBES * voxels, 0, 1);
     return KN_OK;
 }

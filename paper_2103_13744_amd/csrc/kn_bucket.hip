@@ -417,7 +417,6 @@ int64_t kn_max_tiles(int64_t M, int32_t N, int32_t tile_len)
     return M / tile_len + (M < N ? M : N) + 1;
 }
 
-constexpr int64_t SELF_BASE_MAX_BLOCKS = 8192; // beyond this the (digit, block) table is scanned instead
 
 struct BucketWs {
     int32_t *keys_a, *keys_b, *vals_a, *vals_b, *table, *table_s, *scan_tmp, *atomics, *counts, *offsets, *n_tiles;
@@ -462,14 +461,15 @@ void kn_bucket_scratch(KnCarver ws, int64_t M, int32_t N, int32_t **atomics, int
 
 int kn_bucket_run(hipStream_t st, int32_t *keys, int64_t M, const int32_t *M_dev, int32_t N, int32_t tile_len,
                   int32_t *user_counts, int32_t *user_offsets, int32_t *user_perm, KnCarver &ws, KnBucketOut *out,
-                  bool atomics_zeroed)
+                  bool atomics_zeroed, int64_t self_base_blocks)
 {
     if (M < 0 || M > (1ll << 30) || N < 1 || tile_len < 64) return KN_E_INVALID_ARG;
     BucketWs w;
     carve_bucket(ws, M, N, w);
     if (!ws.ok()) return KN_E_WORKSPACE;
     const int64_t nblk = w.nblk;
-    const bool self_base = nblk <= SELF_BASE_MAX_BLOCKS;
+    // up to this many blocks the scatter derives its offsets from per-group sums; beyond, the (digit, block) table is scanned
+    const bool self_base = nblk <= self_base_blocks;
 
     const int passes = radix_passes(N);
     const int32_t *kin = keys;
@@ -545,10 +545,10 @@ int kn_cell_keys(const kn_scene *sc, hipStream_t st, const float *points, int64_
     return KN_OK;
 }
 
-extern "C" int kn_bucket(const kn_scene *sc, void *stream, const int32_t *ids, int64_t M, int32_t *counts,
+extern "C" int kn_bucket(kn_ctx *ctx, const kn_scene *sc, void *stream, const int32_t *ids, int64_t M, int32_t *counts,
                          int32_t *offsets, int32_t *perm, void *workspace, int64_t workspace_bytes)
 {
-    if (!sc || M < 0 || (M > 0 && (!ids || !perm))) return KN_E_INVALID_ARG;
+    if (!ctx || !sc || M < 0 || (M > 0 && (!ids || !perm))) return KN_E_INVALID_ARG;
     if (M > (1ll << 30)) return KN_E_UNSUPPORTED;
     if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < kn_bucket_ws_bytes(M, sc->N) + kn_align_up(M * 4, 256))
         return KN_E_WORKSPACE;
@@ -562,5 +562,5 @@ extern "C" int kn_bucket(const kn_scene *sc, void *stream, const int32_t *ids, i
         KN_CHECK_LAUNCH();
     }
     KnBucketOut bo;
-    return kn_bucket_run(st, keys, M, nullptr, sc->N, 64, counts, offsets, perm, ws, &bo);
+    return kn_bucket_run(st, keys, M, nullptr, sc->N, 64, counts, offsets, perm, ws, &bo, false, kn_knobs(ctx).radix_self_base_blocks);
 }

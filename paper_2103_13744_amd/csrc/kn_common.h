@@ -29,13 +29,57 @@ struct KnTile {
 };
 
 constexpr int KN_MAILBOXES = 8;
+// Host-visible mailbox (pinned, device-mapped, 8 words): kn_render's kernels post the live-ray count of a wave
+// there, {sequence number, value, totals...}, and the host polls it instead of draining the stream.
 struct KnMailbox {
     volatile unsigned long long *host; // nullptr: could not be allocated (the caller falls back to synchronising)
     unsigned long long *dev;
     unsigned long long seq;            // last sequence number handed out
+    unsigned long long last_posted;    // sequence number of the last post a call asked its kernels for
+    unsigned long long last_use;       // value of the context's use counter when a call last took it
     hipStream_t stream;                // owner, once taken
     bool taken;
 };
+
+enum KnStage { KN_ST_CELL = 0, KN_ST_MARCH, KN_ST_BUCKET, KN_ST_MLP, KN_ST_BLEND, KN_ST_SETUP, KN_ST_NONE };
+constexpr int KN_N_EVENTS = 1024;
+constexpr int KN_DEFAULT_SLOTS = 128, KN_DEFAULT_GROWTH = 32;
+constexpr int KN_GROUP_FUSED_MAX_BINS = 8192; // largest grid whose histogram the grouping's fill pass scans by itself
+constexpr int KN_GROUP_HASH_SLOTS_MAX = 2048; // larger grids: LDS table of the bins a workgroup meets (power of two)
+constexpr int64_t KN_RADIX_SELF_BASE_BLOCKS = 8192; // beyond this the (digit, block) table of a radix pass is scanned
+
+// Everything mutable lives here (the scene is immutable once created).  `mutex` guards all fields below `device`.
+struct kn_ctx {
+    int device;
+    std::mutex mutex;
+    // wave schedule of kn_render (0 / defaults: see kn_set_render_params)
+    int32_t first_wave_samples, slots_per_ray, wave_growth;
+    // limits that decide between code paths (kn_set_option)
+    int32_t group_fused_max, group_hash_slots;
+    int64_t radix_self_base_blocks;
+    // stage timing: an event ring; intervals are settled (one stream synchronise, then hipEventElapsedTime for
+    // each recorded interval) only when the ring is full, when another stream starts recording, or when the
+    // totals are read
+    kn_profile profile;
+    bool profile_on;
+    int only_stage;       // KN_ST_NONE, or the one stage that is being timed (then sample counts are not gathered)
+    hipEvent_t events[KN_N_EVENTS];
+    int event_stage[KN_N_EVENTS];
+    int n_events;
+    hipStream_t event_stream;
+    bool events_ready;
+    // One mailbox per stream with a render call in flight (posts of one stream arrive in order; posts of two
+    // streams would overwrite each other).
+    KnMailbox mailbox[KN_MAILBOXES];
+    unsigned long long use_counter;
+    void *static_scratch; // device address of the library's static scratch array on this device
+};
+// snapshot of the schedule and limits, taken under the mutex at the start of a call
+struct KnKnobs {
+    int32_t first_wave_samples, slots_per_ray, wave_growth, group_fused_max, group_hash_slots;
+    int64_t radix_self_base_blocks;
+};
+KnKnobs kn_knobs(const kn_ctx *ctx);
 
 struct kn_scene {
     kn_scene_desc desc;
@@ -58,12 +102,7 @@ struct kn_scene {
     // Box around all occupied voxels, as a sub-grid of the occupancy grid (whole skip blocks; the network
     // grid's box without occupancy; res = 0 when nothing is occupied): rays are clipped against it.
     KnGrid content_box;
-    // Host-visible mailboxes (pinned, device-mapped, 8 words each): kn_render's kernels post the live-ray count
-    // of a wave there, {sequence number, value, totals...}, and the host polls it instead of draining the stream.
-    // A mailbox belongs to one stream (posts of one stream arrive in order; posts of two streams would overwrite
-    // each other), so calls on up to KN_MAILBOXES different streams can be in flight on one scene.
-    KnMailbox mailbox[KN_MAILBOXES];
-    std::mutex mailbox_mutex;
+    void *own_buffer;      // device memory the library allocated for the scene's data (nullptr: the caller lent it)
 };
 #define KN_SKIP_BLOCK 4
 #define KN_SKIP_MAX 32
@@ -213,7 +252,7 @@ struct KnBucketOut {
 // With atomics_zeroed the caller has already cleared the scratch counters that kn_bucket_scratch reports.
 int kn_bucket_run(hipStream_t st, int32_t *keys, int64_t M, const int32_t *M_dev, int32_t N, int32_t tile_len,
                   int32_t *user_counts, int32_t *user_offsets, int32_t *user_perm, KnCarver &ws,
-                  KnBucketOut *out, bool atomics_zeroed = false);
+                  KnBucketOut *out, bool atomics_zeroed = false, int64_t self_base_blocks = KN_RADIX_SELF_BASE_BLOCKS);
 // Unstable grouping of a render wave's samples (row layout: row i holds cnt[i] samples in slots i*S ..).
 // out->perm lists slot numbers group by group, in no particular order inside a group or between groups;
 // out->counts / out->offsets are not produced.
@@ -221,10 +260,10 @@ int kn_bucket_run(hipStream_t st, int32_t *keys, int64_t M, const int32_t *M_dev
 // `hist` (N ints) holds the wave's histogram, accumulated by the caller (the marching kernel) on a zeroed array;
 // `cursor` are the N ints behind it.  Where kn_group_fused(N) holds (small grids: the fill pass derives the
 // offsets itself) `cursor` must be zero before the run and the caller clears both arrays afterwards; otherwise
-// kn_group_run leaves the histogram zero and overwrites the cursors.  kn_group_hash_slots(): size of the LDS hash
+// kn_group_run leaves the histogram zero and overwrites the cursors.  hash_slots: size of the LDS hash
 // table (a power of two) that kernels use for per-workgroup counters where a counter per network does not fit.
-bool kn_group_fused(int32_t N);
-int32_t kn_group_hash_slots();
+inline bool kn_group_fused(const KnKnobs &k, int32_t N) { return N <= k.group_fused_max; }
+int kn_group_configure(); // once per device: lifts the dynamic-LDS limit of the grouping kernels
 struct KnGroupWs {
     int32_t *hist, *cursor, *n_tiles, *perm;
     KnTile *tiles;
@@ -232,8 +271,8 @@ struct KnGroupWs {
 int64_t kn_group_ws_bytes(int64_t slots, int32_t N);
 void kn_group_carve(KnCarver &ws, int64_t slots, int32_t N, KnGroupWs *w);
 // ctl (device): ctl[0] = number of rows, ctl[1] = S; max_rows: host-side upper bound of ctl[0] (sizes the grid).
-int kn_group_run(hipStream_t st, const int32_t *row_keys, const int32_t *cnt, const int32_t *ctl, int64_t max_rows,
-                 int32_t N, int32_t tile_len, const KnGroupWs &w, KnBucketOut *out);
+int kn_group_run(hipStream_t st, const KnKnobs &knobs, const int32_t *row_keys, const int32_t *cnt, const int32_t *ctl,
+                 int64_t max_rows, int32_t N, int32_t tile_len, const KnGroupWs &w, KnBucketOut *out);
 
 // The scratch counters (to be zero before the sort) that kn_bucket_run will carve from `ws` when it
 // is called with a carver in this same state, so that a caller's own kernel can clear them.
@@ -270,15 +309,15 @@ int64_t kn_scan_tmp_len(int64_t n);
 // Optional per-stage timing with HIP events on the caller's stream (see kn_profile in the header).
 // begin() records a start event, mark(stage) an event that closes an interval charged to `stage`.
 // Elapsed times are read later, in batches (kn_profile_read forces it), so recording does not
-// synchronise the stream.
-enum KnStage { KN_ST_CELL = 0, KN_ST_MARCH, KN_ST_BUCKET, KN_ST_MLP, KN_ST_BLEND, KN_ST_SETUP, KN_ST_NONE };
+// synchronise the stream.  `allowed` false: never record (for calls that must not allocate: creating the events does).
 struct KnStageTimer {
+    kn_ctx *ctx;
     hipStream_t st;
     bool on;
-    KnStageTimer(hipStream_t s, bool allowed = true);
+    bool counts; // every stage is timed: sample counts are gathered as well
+    KnStageTimer(kn_ctx *c, hipStream_t s, bool allowed = true);
     void begin() { mark(KN_ST_NONE); }
     void mark(int stage_id);
+    // totals that are counted, not timed
+    void add(int64_t mlp_launches, int64_t mlp_samples, int64_t bucket_keys, int64_t calls);
 };
-extern kn_profile g_kn_profile;
-extern bool g_kn_profile_on;
-extern int g_only_stage; // KN_ST_NONE, or the one stage that is being timed (then sample counts are not gathered)

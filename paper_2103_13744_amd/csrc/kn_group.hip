@@ -14,13 +14,11 @@
 //
 // Input is the wave's row layout: row i holds cnt[i] samples in slots i*S .. i*S + cnt[i] - 1.
 #include "kn_common.h"
-#include <stdlib.h>
 
 namespace {
 
 constexpr int GROUP_THREADS = 256;
-constexpr int GROUP_FUSED_MAX_BINS = 8192; // largest grid whose histogram the fill pass scans by itself
-constexpr int GROUP_HASH_SLOTS = 2048;     // larger grids: LDS table of the bins a workgroup meets (power of two)
+constexpr int GROUP_FUSED_MAX_BINS = KN_GROUP_FUSED_MAX_BINS; // largest grid whose histogram the fill pass scans by itself
 constexpr int GROUP_HASH_PROBES = 16;      // slots tried before a bin is handled through global memory instead
 constexpr int GROUP_LIST = 512;            // bins a workgroup can list as touched before it visits all
 
@@ -386,27 +384,13 @@ __global__ void __launch_bounds__(GROUP_THREADS)
 
 } // namespace
 
-// KN_GROUP_HASH_SLOTS / KN_GROUP_FUSED_MAX: test knobs (read once) that shrink the LDS hash table and the
-// fused-scan limit, so that small scenes reach the code paths of large network grids, table overflow included
-int32_t kn_group_hash_slots()
+// the fill kernels may need more dynamic LDS than the default limit (once per device, from kn_create)
+int kn_group_configure()
 {
-    static int32_t v = 0;
-    if (!v) {
-        const char *e = getenv("KN_GROUP_HASH_SLOTS");
-        const int x = e ? atoi(e) : 0;
-        v = (x >= 16 && x <= GROUP_HASH_SLOTS && (x & (x - 1)) == 0) ? x : GROUP_HASH_SLOTS;
-    }
-    return v;
-}
-bool kn_group_fused(int32_t N)
-{
-    static int32_t lim = -1;
-    if (lim < 0) {
-        const char *e = getenv("KN_GROUP_FUSED_MAX");
-        const int x = e ? atoi(e) : -1;
-        lim = (x >= 0 && x <= GROUP_FUSED_MAX_BINS) ? x : GROUP_FUSED_MAX_BINS;
-    }
-    return N <= lim;
+    const int most = (int)(sizeof(int32_t) * 2 * GROUP_FUSED_MAX_BINS);
+    KN_HIP(hipFuncSetAttribute((const void *)k_group_pass<1>, hipFuncAttributeMaxDynamicSharedMemorySize, most));
+    KN_HIP(hipFuncSetAttribute((const void *)k_group_pass<2>, hipFuncAttributeMaxDynamicSharedMemorySize, most));
+    return KN_OK;
 }
 
 static void carve_group(KnCarver &c, int64_t slots, int32_t N, KnGroupWs &w)
@@ -428,23 +412,16 @@ int64_t kn_group_ws_bytes(int64_t slots, int32_t N)
 
 void kn_group_carve(KnCarver &ws, int64_t slots, int32_t N, KnGroupWs *w) { carve_group(ws, slots, N, *w); }
 
-int kn_group_run(hipStream_t st, const int32_t *row_keys, const int32_t *cnt, const int32_t *ctl, int64_t max_rows,
-                 int32_t N, int32_t tile_len, const KnGroupWs &w, KnBucketOut *out)
+int kn_group_run(hipStream_t st, const KnKnobs &knobs, const int32_t *row_keys, const int32_t *cnt, const int32_t *ctl,
+                 int64_t max_rows, int32_t N, int32_t tile_len, const KnGroupWs &w, KnBucketOut *out)
 {
     if (!ctl || max_rows < 0 || max_rows > 0x7fffffffLL || N < 1 || tile_len < 64) return KN_E_INVALID_ARG;
     if (!w.hist || !w.cursor || !w.n_tiles || !w.perm || !w.tiles) return KN_E_WORKSPACE;
-    const bool fused = kn_group_fused(N);
-    const int32_t bins_cap = fused ? N : kn_group_hash_slots(); // direct counters, or hash slots
+    const bool fused = kn_group_fused(knobs, N);
+    const int32_t bins_cap = fused ? N : knobs.group_hash_slots; // direct counters, or hash slots
     int64_t blocks = kn_div_up(max_rows > 0 ? max_rows : 1, 16);
     if (blocks > 1024) blocks = 1024;
     const size_t lds_bytes = sizeof(int32_t) * (size_t)bins_cap * 2;
-    static bool configured = false; // the kernels may need more dynamic LDS than the default limit
-    if (!configured) {
-        const int most = (int)(sizeof(int32_t) * 2 * GROUP_FUSED_MAX_BINS);
-        KN_HIP(hipFuncSetAttribute((const void *)k_group_pass<1>, hipFuncAttributeMaxDynamicSharedMemorySize, most));
-        KN_HIP(hipFuncSetAttribute((const void *)k_group_pass<2>, hipFuncAttributeMaxDynamicSharedMemorySize, most));
-        configured = true;
-    }
     const dim3 grid((unsigned)blocks), block(GROUP_THREADS);
     if (fused) {
         hipLaunchKernelGGL(k_group_pass<2>, grid, block, lds_bytes, st, row_keys, cnt, ctl, N, bins_cap, w.cursor, w.perm,

@@ -426,12 +426,20 @@ __global__ void __launch_bounds__(F32_WAVES *KN_WAVE) __attribute__((amdgpu_wave
 
 int kn_mlp_f32_tile_len(const kn_scene *) { return F32_TILE_LEN; }
 
+// bytes of the packed weights of N networks of width H (0: no kernel for that width)
+int64_t kn_mlp_f32_packed_bytes(int32_t H, int64_t N)
+{
+    if (H != 32 && H != 64) return 0;
+    return (int64_t)(H == 32 ? Regs<32>::N : Regs<64>::N) * KN_WAVE * 4 * N;
+}
+
+// fills sc->packed_w (kn_mlp_f32_packed_bytes bytes, assigned by the caller)
 int kn_mlp_f32_pack_weights(kn_scene *sc, hipStream_t st)
 {
     const int H = sc->desc.hidden;
     if (H != 32 && H != 64) return KN_E_UNSUPPORTED;
+    if (!sc->packed_w) return KN_E_INVALID_ARG;
     const int64_t per = (H == 32 ? Regs<32>::N : Regs<64>::N) * KN_WAVE;
-    KN_HIP(hipMalloc(&sc->packed_w, (size_t)(per * 4 * sc->N)));
     const int64_t blocks = kn_div_up(per * sc->N, 256);
     if (blocks > 0x7fffffffLL) return KN_E_UNSUPPORTED;
     const float *w = (const float *)sc->desc.weights;

@@ -827,14 +827,22 @@ int launch(const kn_scene *sc, hipStream_t st, const KnSampleSrc &src, const KnB
 
 int kn_mlp_mfma_tile_len(const kn_scene *) { return MLP_TILE_LEN; }
 
+// bytes of the slot-order weights of N networks of width H (0: no kernel for that width)
+int64_t kn_mlp_packed_bytes(int32_t H, int64_t N)
+{
+    if (H != 32 && H != 64) return 0;
+    return (int64_t)(H == 32 ? Lay<32>::HALFS : Lay<64>::HALFS) * 2 * N;
+}
+
+// fills sc->packed_w (kn_mlp_packed_bytes bytes, assigned by the caller)
 int kn_mlp_pack_weights(kn_scene *sc, hipStream_t st)
 {
     const int H = sc->desc.hidden;
     const bool bf = sc->desc.wdtype == KN_BF16;
+    if (!sc->packed_w || (H != 32 && H != 64)) return KN_E_INVALID_ARG;
     const int64_t halfs = H == 32 ? Lay<32>::HALFS : Lay<64>::HALFS;
     const int64_t per = H == 32 ? Lay<32>::NBLK * 512 + Lay<32>::TAIL_FLOATS : Lay<64>::NBLK * 512 + Lay<64>::TAIL_FLOATS;
     sc->packed_halfs_per_net = halfs;
-    KN_HIP(hipMalloc(&sc->packed_w, (size_t)(halfs * 2 * sc->N)));
     const int64_t total = per * sc->N;
     const int64_t blocks = kn_div_up(total, 256);
     if (blocks > 0x7fffffffLL) return KN_E_UNSUPPORTED;

@@ -949,10 +949,7 @@ MarchParams make_params(const kn_scene *sc, float t_near, float step, int32_t K,
 // budget (slots per ray of the frame, shared by the live rays of a wave) only sizes the workspace; when it
 // covers K slots for every ray that reaches content, the second wave is known to finish the frame and the
 // call returns without waiting for it.
-constexpr int DEFAULT_FIRST_WAVE = 48, DEFAULT_SLOTS = 128, DEFAULT_GROWTH = 32;
-int g_first_wave_samples = 0; // 0: from K (see above)
-int g_slots_per_ray = DEFAULT_SLOTS;
-int g_wave_growth = DEFAULT_GROWTH;
+constexpr int DEFAULT_FIRST_WAVE = 48;
 
 bool finite_pos(float v) { return isfinite(v) && v > 0.0f; }
 
@@ -980,30 +977,32 @@ MarchWaveFn march_wave_kernel(bool hash, int opt)
 
 } // namespace
 
-extern "C" int kn_set_render_params(int32_t first_wave_samples, int32_t slots_per_ray, int32_t wave_growth)
+// A mailbox for a call on `stream`: the one the stream already has, else a free one, else the least recently used one
+// whose last call has reported (the device writes a mailbox only up to the last post a call asked for, so once that
+// sequence number is visible nothing of the old owner is in flight).  nullptr when none can be had: the call then
+// waits for its stream instead of polling.
+static KnMailbox *mailbox_for(kn_ctx *ctx, hipStream_t stream)
 {
-    g_wave_growth = wave_growth >= 2 ? wave_growth : DEFAULT_GROWTH;
-    g_first_wave_samples = first_wave_samples > 0 ? first_wave_samples : 0;
-    g_slots_per_ray = slots_per_ray > 0 ? slots_per_ray : DEFAULT_SLOTS;
-    if (g_slots_per_ray < g_first_wave_samples) g_slots_per_ray = g_first_wave_samples;
-    return KN_OK;
-}
-
-// The mailbox of `stream` on this scene (taken on first use and kept); nullptr when there is none left or none at all.
-static KnMailbox *mailbox_for(kn_scene *sc, hipStream_t stream)
-{
-    std::lock_guard<std::mutex> lock(sc->mailbox_mutex);
-    KnMailbox *free_one = nullptr;
-    for (auto &m : sc->mailbox) {
+    std::lock_guard<std::mutex> lock(ctx->mutex);
+    KnMailbox *pick = nullptr;
+    for (auto &m : ctx->mailbox) {
         if (!m.host) return nullptr;
-        if (m.taken && m.stream == stream) return &m;
-        if (!m.taken && !free_one) free_one = &m;
+        if (m.taken && m.stream == stream) { pick = &m; break; }
     }
-    if (free_one) {
-        free_one->taken = true;
-        free_one->stream = stream;
+    if (!pick)
+        for (auto &m : ctx->mailbox)
+            if (!m.taken) { pick = &m; break; }
+    if (!pick)
+        for (auto &m : ctx->mailbox) {
+            const bool idle = __atomic_load_n((const unsigned long long *)&m.host[0], __ATOMIC_ACQUIRE) == m.last_posted;
+            if (idle && (!pick || m.last_use < pick->last_use)) pick = &m;
+        }
+    if (pick) {
+        pick->taken = true;
+        pick->stream = stream;
+        pick->last_use = ++ctx->use_counter;
     }
-    return free_one;
+    return pick;
 }
 
 // Wait for the mailbox to show `seq` (spinning on pinned memory is much cheaper than draining the
@@ -1074,11 +1073,11 @@ static void carve_render(KnCarver &ws, int64_t R, int64_t slots, RenderWs &w)
     w.out4 = ws.carve<float>(4 * slots);
 }
 
-int64_t kn_render_ws_bytes(const kn_scene *sc, int64_t R)
+int64_t kn_render_ws_bytes(const kn_scene *sc, int64_t R, int32_t slots_per_ray)
 {
     KnCarver c((void *)256, INT64_MAX / 2);
     RenderWs w;
-    const int64_t slots = R * g_slots_per_ray;
+    const int64_t slots = R * slots_per_ray;
     carve_render(c, R, slots, w);
     return c.used + kn_group_ws_bytes(slots, sc->N);
 }
@@ -1141,11 +1140,11 @@ extern "C" int kn_composite_deltas(void *stream, const float *sigma, const float
     return composite_impl(stream, sigma, rgb, delta, offsets, R, 1.0f, term_eps, bg, rgb_out, T_out, n_used);
 }
 
-static int render_impl(const kn_scene *sc, void *stream, const float *rays_o, const float *rays_d, int64_t R, float t_near,
+static int render_impl(kn_ctx *ctx, const kn_scene *sc, void *stream, const float *rays_o, const float *rays_d, int64_t R, float t_near,
                        float step, int32_t K, float term_eps, const float bg[3], const uint32_t *seed, float *rgb_out,
                        kn_render_stats *stats, void *workspace, int64_t workspace_bytes)
 {
-    if (!sc || R < 0 || K < 0 || !bg || !isfinite(t_near) || !finite_pos(step) || !(term_eps >= 0.0f && term_eps < 1.0f))
+    if (!ctx || !sc || R < 0 || K < 0 || !bg || !isfinite(t_near) || !finite_pos(step) || !(term_eps >= 0.0f && term_eps < 1.0f))
         return KN_E_INVALID_ARG;
     if (R > 0 && (!rays_o || !rays_d || !rgb_out)) return KN_E_INVALID_ARG;
     if (stats) {
@@ -1153,16 +1152,18 @@ static int render_impl(const kn_scene *sc, void *stream, const float *rays_o, co
         stats->waves = stats->samples_evaluated = stats->samples_blended = stats->slots = 0;
     }
     if (R == 0) return KN_OK;
+    const KnKnobs knobs = kn_knobs(ctx); // the schedule this call runs with, whatever is set meanwhile
     const int kbits = kbits_for(K > 1 ? K : 2);
-    if (R > (1ll << (32 - kbits)) || R > 0x7fffffffLL / g_slots_per_ray ||
+    if (R > (1ll << (32 - kbits)) || R > 0x7fffffffLL / knobs.slots_per_ray ||
         R > 0x7fffffffLL / MARCH_G)
         return KN_E_UNSUPPORTED; // slot numbers and row * lanes are 32-bit
-    if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < kn_render_ws_bytes(sc, R)) return KN_E_WORKSPACE;
+    if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < kn_render_ws_bytes(sc, R, knobs.slots_per_ray))
+        return KN_E_WORKSPACE;
 
     hipStream_t st = (hipStream_t)stream;
     KnCarver ws(workspace, workspace_bytes);
     RenderWs w;
-    const int64_t budget = R * g_slots_per_ray;
+    const int64_t budget = R * knobs.slots_per_ray;
     carve_render(ws, R, budget, w);
     if (!ws.ok()) return KN_E_WORKSPACE;
     KnGroupWs gw;
@@ -1174,19 +1175,24 @@ static int render_impl(const kn_scene *sc, void *stream, const float *rays_o, co
     RayState rs{w.T, w.C, w.k_next, w.k_end};
     const unsigned rblocks = (unsigned)kn_div_up(R, RAY_BLOCK);
     const int64_t n_hist = 2 * (int64_t)sc->N; // histogram and fill cursors of the sample grouping
-    const bool fused_hist = kn_group_fused(sc->N);
+    const bool fused_hist = kn_group_fused(knobs, sc->N);
     // the marching kernel counts the samples per network: a counter per network in LDS on small grids, a hash table
     // of the networks a workgroup meets on large ones
-    const int32_t march_hash = fused_hist ? 0 : kn_group_hash_slots();
-    KnStageTimer tm(st);
+    const int32_t march_hash = fused_hist ? 0 : knobs.group_hash_slots;
+    KnStageTimer tm(ctx, st);
     tm.begin();
-    KnMailbox *mb = mailbox_for(const_cast<kn_scene *>(sc), st); // the mailboxes are the only mutable scene state
+    KnMailbox *mb = mailbox_for(ctx, st);
     unsigned long long *mb_dev = mb ? mb->dev : nullptr;
     unsigned long long seq_local = 0; // sequence numbers without a mailbox (nobody reads them)
-    auto next_seq = [&]() -> unsigned long long { return mb ? ++mb->seq : ++seq_local; };
-    int first_samples = g_first_wave_samples > 0 ? g_first_wave_samples : (K / 16 > DEFAULT_FIRST_WAVE ? K / 16 : DEFAULT_FIRST_WAVE);
-    if (first_samples > g_slots_per_ray) first_samples = g_slots_per_ray;
-    const WaveSchedule sched{first_samples, g_wave_growth, K > 0 ? K : 1, budget};
+    // (a mailbox's counters are this call's alone until its last post has landed: see mailbox_for)
+    auto next_seq = [&]() -> unsigned long long {
+        if (!mb) return ++seq_local;
+        mb->last_posted = ++mb->seq;
+        return mb->seq;
+    };
+    int first_samples = knobs.first_wave_samples > 0 ? knobs.first_wave_samples : (K / 16 > DEFAULT_FIRST_WAVE ? K / 16 : DEFAULT_FIRST_WAVE);
+    if (first_samples > knobs.slots_per_ray) first_samples = knobs.slots_per_ray;
+    const WaveSchedule sched{first_samples, knobs.wave_growth, K > 0 ? K : 1, budget};
     hipLaunchKernelGGL(render_init_kernel(opt), dim3(rblocks), dim3(RAY_BLOCK), 0, st, p, rays_o, rays_d, R, rs, w.alive_b, w.blk_sum,
                        bg[0], bg[1], bg[2], rgb_out, (int32_t *)w.counters, 16, gw.hist, R >= n_hist ? (int32_t)n_hist : 0);
     KN_CHECK_LAUNCH();
@@ -1238,7 +1244,7 @@ static int render_impl(const kn_scene *sc, void *stream, const float *rays_o, co
     auto rest_of_wave = [&](int64_t rows_cap, bool post) -> int {
         int32_t *ctl = w.ctl + 4 * (wave_no & 1), *ctl_next = w.ctl + 4 * ((wave_no + 1) & 1);
         KnBucketOut bo;
-        KN_TRY(kn_group_run(st, w.row_keys, w.cnt, ctl, rows_cap, sc->N, tile_len, gw, &bo));
+        KN_TRY(kn_group_run(st, knobs, w.row_keys, w.cnt, ctl, rows_cap, sc->N, tile_len, gw, &bo));
         tm.mark(KN_ST_BUCKET);
         KN_TRY(kn_mlp_launch(sc, st, src, bo, budget, nullptr, nullptr));
         tm.mark(KN_ST_MLP);
@@ -1260,9 +1266,9 @@ static int render_impl(const kn_scene *sc, void *stream, const float *rays_o, co
                            ctl_next, sched, w.blk_off, post ? mb_dev : (unsigned long long *)nullptr, seq);
         KN_CHECK_LAUNCH();
         tm.mark(KN_ST_BLEND);
-        if (tm.on) g_kn_profile.mlp_launches += 1;
+        tm.add(1, 0, 0, 0);
         ++wave_no;
-        s_bound = s_bound * g_wave_growth < (int64_t)K ? s_bound * g_wave_growth : (int64_t)K;
+        s_bound = s_bound * knobs.wave_growth < (int64_t)K ? s_bound * knobs.wave_growth : (int64_t)K;
         return KN_OK;
     };
     // first wave: its march is enqueued for all R rays while the host is still waiting for the number of live rays
@@ -1279,8 +1285,8 @@ static int render_impl(const kn_scene *sc, void *stream, const float *rays_o, co
         // With K slots for each of the `first` rays the second wave takes every ray to its end: nothing to wait for
         // (unless the caller wants the counters of this frame).
         const bool second_wave_ends_it = speculative && first * (long long)K <= budget &&
-                                         (int64_t)first_samples * g_wave_growth >= (int64_t)K;
-        const bool want_counts = (g_kn_profile_on && g_only_stage == KN_ST_NONE) || stats != nullptr;
+                                         (int64_t)first_samples * knobs.wave_growth >= (int64_t)K;
+        const bool want_counts = tm.counts || stats != nullptr;
         // a wave's count is read by the host unless the next wave is enqueued blindly (the first wave's, when a second
         // follows) or nothing follows for sure (the second wave's, when it ends every ray)
         const bool blind_second = speculative;
@@ -1308,7 +1314,7 @@ static int render_impl(const kn_scene *sc, void *stream, const float *rays_o, co
             KN_TRY(rest_of_wave(list_cap, host_reads(wave_no)));
         }
     }
-    if ((g_kn_profile_on && g_only_stage == KN_ST_NONE) || stats) {
+    if (tm.counts || stats) {
         unsigned long long c[5] = {0ull, 0ull, 0ull, 0ull, 0ull}; // evaluated, blended, survivors, slots, waves
         if (wave_no > 0 && mb &&
             __atomic_load_n((const unsigned long long *)&mb->host[0], __ATOMIC_ACQUIRE) == seq) {
@@ -1320,11 +1326,7 @@ static int render_impl(const kn_scene *sc, void *stream, const float *rays_o, co
             KN_HIP(hipMemcpyAsync(c, w.counters, sizeof(c), hipMemcpyDeviceToHost, st));
             KN_HIP(hipStreamSynchronize(st));
         }
-        if (g_kn_profile_on) {
-            g_kn_profile.mlp_samples += (int64_t)c[0];
-            g_kn_profile.bucket_keys += (int64_t)c[0];
-            g_kn_profile.calls += 1;
-        }
+        tm.add(0, (int64_t)c[0], (int64_t)c[0], 1);
         if (stats) {
             stats->waves = (int64_t)c[4];
             stats->samples_evaluated = (int64_t)c[0];
@@ -1335,18 +1337,18 @@ static int render_impl(const kn_scene *sc, void *stream, const float *rays_o, co
     return KN_OK;
 }
 
-extern "C" int kn_render(const kn_scene *sc, void *stream, const float *rays_o, const float *rays_d, int64_t R, float t_near,
+extern "C" int kn_render(kn_ctx *ctx, const kn_scene *sc, void *stream, const float *rays_o, const float *rays_d, int64_t R, float t_near,
                          float step, int32_t K, float term_eps, const float bg[3], float *rgb_out, kn_render_stats *stats,
                          void *workspace, int64_t workspace_bytes)
 {
-    return render_impl(sc, stream, rays_o, rays_d, R, t_near, step, K, term_eps, bg, nullptr, rgb_out, stats, workspace,
+    return render_impl(ctx, sc, stream, rays_o, rays_d, R, t_near, step, K, term_eps, bg, nullptr, rgb_out, stats, workspace,
                        workspace_bytes);
 }
 
-extern "C" int kn_render_stratified(const kn_scene *sc, void *stream, const float *rays_o, const float *rays_d, int64_t R,
+extern "C" int kn_render_stratified(kn_ctx *ctx, const kn_scene *sc, void *stream, const float *rays_o, const float *rays_d, int64_t R,
                                     float t_near, float step, int32_t K, float term_eps, const float bg[3], uint32_t seed,
                                     float *rgb_out, kn_render_stats *stats, void *workspace, int64_t workspace_bytes)
 {
-    return render_impl(sc, stream, rays_o, rays_d, R, t_near, step, K, term_eps, bg, &seed, rgb_out, stats, workspace,
+    return render_impl(ctx, sc, stream, rays_o, rays_d, R, t_near, step, K, term_eps, bg, &seed, rgb_out, stats, workspace,
                        workspace_bytes);
 }

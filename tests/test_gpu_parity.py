@@ -503,45 +503,155 @@ def test_render_is_independent_of_wave_cut_and_deterministic():
     assert imgs[2][1]["waves"] > imgs[0][1]["waves"] > imgs[4][1]["waves"] >= 1
 
 
-def test_render_large_grid_code_paths(tmp_path):
+def test_render_large_grid_code_paths():
     """Grids with too many networks for a counter each in LDS are grouped with separate histogram, offset and fill
-    kernels and an LDS hash table; a child process forces those paths on a small scene and must produce the same
-    image."""
-    import subprocess
-    import sys
+    kernels and an LDS hash table; a second context whose limits force those paths on a small scene must produce the
+    same image as the default context on the same scene."""
+    import paper_2103_13744_amd as kn
     cfg = configs.config3(64, 64)
     dev, _ = make_pair(cfg["scene"])
     o, d = cuda(cfg["rays_o"]), cuda(cfg["rays_d"])
     args = (cfg["t_near"], cfg["step"], cfg["K"], cfg["term_eps"], cfg["bg"])
     here = dev.render(o, d, *args).cpu().numpy()
-    out = tmp_path / "img.npy"
-    code = (
-        "import sys, numpy as np, torch\n"
-        "sys.path.insert(0, %r)\n"
-        "from kn_synth import configs\n"
-        "from tests.util import make_pair, cuda\n"
-        "cfg = configs.config3(64, 64)\n"
-        "dev, _ = make_pair(cfg['scene'])\n"
-        "o, d = cuda(cfg['rays_o']), cuda(cfg['rays_d'])\n"
-        "img = dev.render(o, d, cfg['t_near'], cfg['step'], cfg['K'], cfg['term_eps'], cfg['bg'])\n"
-        "np.save(%r, img.cpu().numpy())\n"
-    ) % (os.path.dirname(os.path.dirname(os.path.abspath(__file__))), str(out))
+    forced = kn.Context()
     # the path of large grids (counters in an LDS hash table), then the same with a table so small that most bins
     # overflow into the global-memory path
-    for knobs in (dict(KN_GROUP_FUSED_MAX="0"), dict(KN_GROUP_FUSED_MAX="0", KN_GROUP_HASH_SLOTS="16")):
-        subprocess.run([sys.executable, "-c", code], env=dict(os.environ, **knobs), check=True, timeout=300)
-        np.testing.assert_array_equal(np.load(out), here)
-        out.unlink()
+    for slots in (0, 16):
+        forced.set_option(kn.OPT_GROUP_FUSED_MAX, 0)
+        forced.set_option(kn.OPT_GROUP_HASH_SLOTS, slots)
+        np.testing.assert_array_equal(dev.render(o, d, *args, ctx=forced).cpu().numpy(), here)
+        np.testing.assert_array_equal(dev.render(o, d, *args).cpu().numpy(), here)          # the default context is untouched
     # the same paths under the sparse-grid and stratified variants of the marching kernel
     cfg = _sparse_cfg3("f16", 64, 64)
     dev, _ = make_pair(cfg["scene"])
     here = dev.render(o, d, *args, seed=3).cpu().numpy()
-    code = code.replace("cfg = configs.config3(64, 64)\n",
-                        "from tests.test_gpu_parity import _sparse_cfg3\ncfg = _sparse_cfg3('f16', 64, 64)\n")
-    code = code.replace("cfg['bg'])", "cfg['bg'], seed=3)")
-    assert "_sparse_cfg3" in code and "seed=3" in code
-    subprocess.run([sys.executable, "-c", code], env=dict(os.environ, KN_GROUP_FUSED_MAX="0"), check=True, timeout=300)
-    np.testing.assert_array_equal(np.load(out), here)
+    forced.set_option(kn.OPT_GROUP_HASH_SLOTS, 0)
+    np.testing.assert_array_equal(dev.render(o, d, *args, seed=3, ctx=forced).cpu().numpy(), here)
+    with pytest.raises(kn.KnError):
+        forced.set_option(kn.OPT_GROUP_HASH_SLOTS, 100)       # not a power of two
+    with pytest.raises(kn.KnError):
+        forced.set_option(99, 1)
+    forced.close()
+
+
+def test_bucket_with_a_scanned_digit_table():
+    """Beyond 8,192 blocks of 4,096 keys the radix passes scan their (digit, block) table instead of deriving offsets
+    from per-group sums; a context with that limit lowered takes the path on a small input.  Same counts, offsets and
+    permutation as the oracle, for one and for two passes."""
+    import paper_2103_13744_amd as kn
+    small = kn.Context()
+    small.set_option(kn.OPT_RADIX_SELF_BASE_BLOCKS, 3)
+    for res, M in (((3, 4, 5), 50_001), ((16, 16, 16), 300_017), ((16, 16, 16), 4096 * 3)):   # the last: exactly at the limit
+        N = int(np.prod(res))
+        dev, _ = make_pair(scene_dict(res, (0, 0, 0), (1, 1, 1), 32, "f32", 1))
+        ids = ks.rng(29 + M).integers(-1, N, size=M).astype(np.int32)
+        c, o, p = oracle.bucket(ids, N)
+        for ctx in (small, None):
+            counts, offsets, perm = dev.bucket(cuda(ids), ctx=ctx)
+            np.testing.assert_array_equal(counts.cpu().numpy(), c)
+            np.testing.assert_array_equal(offsets.cpu().numpy(), o)
+            np.testing.assert_array_equal(perm.cpu().numpy(), p)
+    # and through eval_grouped
+    sc = scene_dict((4, 4, 4), (0, 0, 0), (1, 1, 1), 32, "f16", 9)
+    dev, _ = make_pair(sc)
+    pts, dirs = cuda(ks.uniform_points(40_000, 1)), cuda(ks.sphere_dirs(40_000, 2))
+    a = dev.eval_grouped(pts, dirs, want_aux=True)
+    b = dev.eval_grouped(pts, dirs, want_aux=True, ctx=small)
+    for x, y in zip(a, b):
+        np.testing.assert_array_equal(x.cpu().numpy(), y.cpu().numpy())
+    small.close()
+
+
+def test_two_contexts_with_different_schedules_from_two_threads():
+    """A context owns the wave schedule, the timing state and the mailboxes; a scene is immutable.  Two threads render
+    the same scene through a context each, with different schedules and one of them timing its stages: the images are
+    the bits of a one-at-a-time render, and neither context sees the other's settings."""
+    import threading
+    import torch
+    import paper_2103_13744_amd as kn
+    cfg = configs.config3(96, 96)
+    dev, _ = make_pair(cfg["scene"])
+    o, d = cuda(cfg["rays_o"]), cuda(cfg["rays_d"])
+    args = (cfg["t_near"], cfg["step"], cfg["K"], cfg["term_eps"], cfg["bg"])
+    ref, ref_stats = dev.render(o, d, *args, want_stats=True)
+    ref = ref.cpu().numpy()
+    torch.cuda.synchronize()
+    R = len(cfg["rays_o"])
+    ctxs = [kn.Context(), kn.Context()]
+    ctxs[0].set_render_params(8, 16, 2)
+    ctxs[1].set_render_params(64, 512, 4)
+    ctxs[1].profile_enable(1)
+    results, waves, errors = [None, None], [None, None], []
+
+    def worker(t):
+        try:
+            torch.cuda.set_device(0)
+            st = torch.cuda.Stream()
+            ws = torch.empty(dev.workspace_bytes(max_rays=R, ctx=ctxs[t]), dtype=torch.uint8, device="cuda")
+            out = torch.empty((R, 3), dtype=torch.float32, device="cuda")
+            with torch.cuda.stream(st):
+                for _ in range(15):
+                    _, stats = dev.render(o, d, *args, out=out, workspace=ws, ctx=ctxs[t], want_stats=True)
+            st.synchronize()
+            results[t], waves[t] = out.cpu().numpy(), stats["waves"]
+        except Exception as e:       # (an exception in a thread would otherwise be lost)
+            errors.append(e)
+
+    threads = [threading.Thread(target=worker, args=(t,)) for t in range(2)]
+    for x in threads:
+        x.start()
+    for x in threads:
+        x.join()
+    assert not errors, errors
+    np.testing.assert_array_equal(results[0], ref)
+    np.testing.assert_array_equal(results[1], ref)
+    assert waves[0] > ref_stats["waves"] >= waves[1]              # each ran its own schedule
+    prof = ctxs[1].profile_read()
+    assert prof["calls"] == 15 and prof["ms_mlp"] > 0 and ctxs[0].profile_read()["calls"] == 0
+    # a workspace sized for one context's schedule is refused by a context whose schedule needs more
+    small = torch.empty(dev.workspace_bytes(max_rays=R, ctx=ctxs[0]), dtype=torch.uint8, device="cuda")
+    with pytest.raises(kn.KnError, match="workspace"):
+        dev.render(o, d, *args, workspace=small, ctx=ctxs[1])
+    for c in ctxs:
+        c.close()
+
+
+def test_scene_in_a_buffer_the_caller_lends():
+    """kn_scene_bytes + the buffer argument of kn_scene_create: the scene's device data (packed weights, occupancy
+    bits, skip field, table of a sparse grid) in caller memory, or, without a buffer, in memory the library allocates.
+    Same image either way; buffers that are too small or misaligned are refused."""
+    import ctypes as C
+    import torch
+    import paper_2103_13744_amd as kn
+    from tests.util import device_weights
+    cfg = _sparse_cfg3("f16", 48, 48)
+    sc = cfg["scene"]
+    o, d = cuda(cfg["rays_o"]), cuda(cfg["rays_d"])
+    args = (cfg["t_near"], cfg["step"], cfg["K"], cfg["term_eps"], cfg["bg"])
+    w, occ, table = device_weights(sc["weights"], "f16"), cuda(sc["occupancy"]), cuda(sc["cell_net"])
+    mk = lambda lend: kn.Scene(sc["res"], sc["aabb_min"], sc["aabb_max"], 32, w, occ, cell_net=table, lend_buffer=lend)
+    lent, own = mk(True), mk(False)
+    assert lent._buffer is not None and lent._buffer.numel() > w.numel() * 2 and own._buffer is None
+    np.testing.assert_array_equal(lent.render(o, d, *args).cpu().numpy(), own.render(o, d, *args).cpu().numpy())
+    # raw calls: size query, then refusals
+    desc = kn.SceneDesc()
+    desc.res[:] = sc["res"]
+    desc.aabb_min[:] = sc["aabb_min"]
+    desc.aabb_max[:] = sc["aabb_max"]
+    desc.hidden, desc.L_pos, desc.L_dir, desc.wdtype = 32, 10, 4, kn.KN_F16
+    desc.weights, desc.occupancy, desc.cell_net, desc.n_nets = w.data_ptr(), occ.data_ptr(), table.data_ptr(), w.shape[0]
+    desc.occ_res[:] = list(occ.shape)
+    need = C.c_int64()
+    L = lent.L
+    assert L.kn_scene_bytes(C.byref(desc), C.byref(need)) == 0 and need.value == lent._buffer.numel()
+    buf = torch.empty(need.value + 256, dtype=torch.uint8, device="cuda")
+    h = C.c_void_p()
+    ctx = lent.ctx.h
+    assert L.kn_scene_create(ctx, C.byref(desc), None, buf.data_ptr(), need.value - 1, C.byref(h)) == -3
+    assert L.kn_scene_create(ctx, C.byref(desc), None, buf.data_ptr() + 64, need.value, C.byref(h)) == -3
+    assert L.kn_scene_create(None, C.byref(desc), None, buf.data_ptr(), need.value, C.byref(h)) == -1
+    assert L.kn_scene_create(ctx, C.byref(desc), None, buf.data_ptr(), need.value, C.byref(h)) == 0
+    assert L.kn_scene_destroy(h) == 0
 
 
 def test_render_network_grid_above_the_fused_grouping_limit():
@@ -710,8 +820,9 @@ def test_render_random_configurations_16bit():
 
 
 def test_render_on_more_streams_than_mailboxes():
-    """A scene has eight host mailboxes, one per stream that renders on it; calls on further streams fall back to
-    waiting for the stream.  Same image on every stream."""
+    """A context has eight host mailboxes, one per stream with a call in flight; a mailbox whose last call has
+    reported is handed on to the next stream that needs one (calls that find none wait for their stream instead).
+    Same image on every one of eleven streams, used one after the other and then all at once."""
     import torch
     cfg = configs.config3(48, 48)
     dev, _ = make_pair(cfg["scene"])
@@ -726,6 +837,22 @@ def test_render_on_more_streams_than_mailboxes():
         st.synchronize()
         np.testing.assert_array_equal(img.cpu().numpy(), ref)
         assert stats["waves"] >= 1 and stats["samples_blended"] > 0
+    # all at once: eleven calls enqueued back to back, each on its own stream with its own workspace and output
+    R = o.shape[0]
+    jobs = []
+    for _ in range(11):
+        st = torch.cuda.Stream()
+        st.wait_stream(torch.cuda.current_stream())
+        ws = torch.empty(dev.workspace_bytes(max_rays=R), dtype=torch.uint8, device="cuda")
+        out = torch.empty((R, 3), dtype=torch.float32, device="cuda")
+        jobs.append((st, ws, out))
+    for _ in range(3):
+        for st, ws, out in jobs:
+            with torch.cuda.stream(st):
+                dev.render(o, d, *args, out=out, workspace=ws)
+    torch.cuda.synchronize()
+    for _, _, out in jobs:
+        np.testing.assert_array_equal(out.cpu().numpy(), ref)
 
 
 def test_render_edge_cases():
@@ -867,7 +994,7 @@ def test_error_statuses_of_extraction_and_layered_evaluation():
     occ = torch.empty(64, dtype=torch.uint8, device="cuda")
     ws = torch.empty(1 << 16, dtype=torch.uint8, device="cuda")
     res = lambda *v: C.byref((C.c_int32 * 3)(*v))
-    call = lambda r, tau, o, w, nb: L.kn_extract_occupancy(h, None, r, tau, o, w, nb)
+    call = lambda r, tau, o, w, nb: L.kn_extract_occupancy(dev.ctx.h, h, None, r, tau, o, w, nb)
     assert call(res(4, 4, 4), 1.0, occ.data_ptr(), ws.data_ptr(), ws.numel()) == 0
     assert call(res(4, 0, 4), 1.0, occ.data_ptr(), ws.data_ptr(), ws.numel()) == -1          # empty resolution
     assert call(res(4, 4, 4), float("nan"), occ.data_ptr(), ws.data_ptr(), ws.numel()) == -1
@@ -879,7 +1006,7 @@ def test_error_statuses_of_extraction_and_layered_evaluation():
     assert call(res(1300, 1300, 1200), 1.0, occ.data_ptr(), ws.data_ptr(), ws.numel()) == -2 # too many voxels per network
     pts = cuda(ks.uniform_points(10, 52))
     out_s, out_c = torch.empty(10, device="cuda"), torch.empty((10, 3), device="cuda")
-    lay = lambda m, w, nb: L.kn_eval_grouped_layered(h, None, pts.data_ptr(), pts.data_ptr(), m, out_s.data_ptr(),
+    lay = lambda m, w, nb: L.kn_eval_grouped_layered(dev.ctx.h, h, None, pts.data_ptr(), pts.data_ptr(), m, out_s.data_ptr(),
                                                       out_c.data_ptr(), w, nb)
     assert lay(-1, ws.data_ptr(), ws.numel()) == -1
     assert lay(10, ws.data_ptr(), 64) == -3

@@ -17,7 +17,7 @@ def test_eval_grouped_static_equals_eval_grouped_on_two_calls_in_a_row():
     import paper_2103_13744_amd as kn
     sc = scene_dict((5, 4, 6), (-1, -1, -1), (1, 1, 1), 32, "f16", 71, sigma_scale=4.0)
     dev, orc = make_pair(sc, threads=True)
-    L, h = dev.L, dev.h
+    L, h, c = dev.L, dev.h, dev.ctx.h
     N = dev.N
     for M, seed in ((300_007, 72), (70_001, 73), (0, 74), (1, 75)):          # the second call is smaller than the first
         print("static scratch, M =", M, flush=True)
@@ -32,7 +32,7 @@ def test_eval_grouped_static_equals_eval_grouped_on_two_calls_in_a_row():
         perm = torch.full((M,), -9, dtype=torch.int32, device="cuda")
         p = lambda t: t.data_ptr() if M else None
         before = torch.cuda.memory_allocated()
-        rc = L.kn_eval_grouped_static(h, torch.cuda.current_stream().cuda_stream, p(pts), p(dirs), M, p(sg), p(rgb), p(ids),
+        rc = L.kn_eval_grouped_static(c, h, torch.cuda.current_stream().cuda_stream, p(pts), p(dirs), M, p(sg), p(rgb), p(ids),
                                       counts.data_ptr(), p(perm))
         assert rc == 0, L.kn_error_string(rc)
         torch.cuda.synchronize()
@@ -61,16 +61,17 @@ def test_eval_grouped_static_rejects_what_its_array_cannot_hold():
     import paper_2103_13744_amd as kn
     sc = scene_dict((4, 4, 4), (0, 0, 0), (1, 1, 1), 32, "f16", 76)
     dev, _ = make_pair(sc)
-    L, h = dev.L, dev.h
+    L, h, c = dev.L, dev.h, dev.ctx.h
     one = torch.zeros((4, 3), device="cuda")
     # sizes are checked on the host before any pointer is used
     big = 1 << 22
-    assert L.kn_eval_grouped_static(h, None, one.data_ptr(), one.data_ptr(), big, one.data_ptr(), one.data_ptr(), None, None,
+    assert L.kn_eval_grouped_static(c, h, None, one.data_ptr(), one.data_ptr(), big, one.data_ptr(), one.data_ptr(), None, None,
                                     None) == -6
     assert b"static" in L.kn_error_string(-6)
-    assert L.kn_eval_grouped_static(h, None, one.data_ptr(), one.data_ptr(), -1, one.data_ptr(), one.data_ptr(), None, None,
+    assert L.kn_eval_grouped_static(c, h, None, one.data_ptr(), one.data_ptr(), -1, one.data_ptr(), one.data_ptr(), None, None,
                                     None) == -1
-    assert L.kn_eval_grouped_static(None, None, None, None, 0, None, None, None, None, None) == -1
+    assert L.kn_eval_grouped_static(c, None, None, None, None, 0, None, None, None, None, None) == -1
+    assert L.kn_eval_grouped_static(None, h, None, None, None, 0, None, None, None, None, None) == -1
     # the largest size that fits is accepted: find it through kn_workspace_bytes (same sizing)
     lo, hi = 1, big
     while lo < hi:
