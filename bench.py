@@ -17,25 +17,54 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 PEAK_MFMA_16BIT = 2.5e15   # FLOP/s, dense fp16 / bf16 MFMA, MI355X
+PEAK_MFMA_F32 = 157.3e12   # FLOP/s, fp32 MFMA
 PEAK_HBM = 8.0e12          # B/s
+MEASURED = {}              # this machine's own limits (paper_2103_13744_amd.peaks), filled by main()
+
+
+def with_measured(roof, key):
+    """Adds the micro-benchmarked peak of the same kind, and the fraction of it, to a roofline block.  key: an entry
+    of MEASURED in the block's unit (GB/s or TFLOP/s)."""
+    peak = MEASURED.get(key)
+    if peak:
+        roof["measured_peak"] = peak
+        roof["measured_peak_kind"] = key
+        roof["frac_of_measured"] = roof["achieved"] / peak
+    return roof
+
+
+def cpu_model():
+    try:
+        with open("/proc/cpuinfo") as f:
+            for line in f:
+                if line.startswith("model name"):
+                    return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
 FLOP_PER_SAMPLE = {32: 12160, 64: 36608}
 VALU_SLOTS_PER_16_SAMPLES = {32: 125, 64: 190}
 
 
+TRAFFIC_FILE = "profiles/hbm_traffic_cfg3_f16.txt"
+
+
 def read_traffic():
     """HBM bytes per launch from the committed rocprofv3 counter summary (FETCH_SIZE / WRITE_SIZE runs of this
-    benchmark, scaled by the copy-kernel calibration stated in the file); {} if the file is absent."""
-    path = os.path.join(ROOT, "profiles", "hbm_traffic_cfg3_f16.txt")
-    out = {}
+    benchmark, scaled by the copy-kernel calibration stated in the file), and the commit the counters were read at
+    (stated in the file): not measured in this run.  ({}, None) if the file is absent."""
+    out, commit = {}, None
     try:
-        with open(path) as f:
+        with open(os.path.join(ROOT, TRAFFIC_FILE)) as f:
             for line in f:
                 parts = line.split()
-                if len(parts) >= 2 and parts[0] == "traffic_bytes_per_launch":
+                if len(parts) >= 3 and parts[0] == "traffic_bytes_per_launch":
                     out[parts[1]] = float(parts[2])
+                if len(parts) >= 2 and parts[0] == "measured_at_commit":
+                    commit = parts[1]
     except OSError:
         pass
-    return out
+    return out, commit
 
 
 def frames_in_flight(torch, scene, rays, args, R, steps, n, blended_per_frame):
@@ -95,7 +124,7 @@ def cpu_baseline(cfg, rays_fn, poses, budget_s=12.0):
     t0 = time.perf_counter()
     _, n1, _, _ = one.render(o[::every], d[::every], *frame)
     t_one = time.perf_counter() - t0
-    return {"value": samples / t_total, "unit": "samples/s", "cores": orc.num_threads(), "kind": "oracle",
+    return {"value": samples / t_total, "unit": "samples/s", "cores": orc.num_threads(), "cpu_model": cpu_model(), "kind": "oracle",
             "sample": "%d whole %dx%d frame(s) of the same scene (%d blended samples, %.1f s)" %
                       (frames, cfg["width"], cfg["height"], samples, t_total),
             "frames_per_sec": frames / t_total,
@@ -103,10 +132,11 @@ def cpu_baseline(cfg, rays_fn, poses, budget_s=12.0):
                            "sample": "every %dth ray of one frame (%d blended samples, %.1f s)" % (every, int(n1.sum()), t_one)}}
 
 
-def isolated_mlp(kn, torch, wdtype, iters=10):
-    """cfg2: the grouped-MLP kernel on its own (2^22 uniform points, 16^3 networks), through kn_eval_grouped."""
+def isolated_mlp(kn, torch, wdtype, iters=10, skewed=False, layered=True):
+    """cfg2: the grouped-MLP kernel on its own (2^22 uniform points, 16^3 networks), through kn_eval_grouped; or
+    cfg4 (skewed): 2^23 points, 90 % of them in 5 % of the cells."""
     from kn_synth import configs
-    cfg = configs.config2(wdtype=wdtype)
+    cfg = configs.config4(wdtype=wdtype) if skewed else configs.config2(wdtype=wdtype)
     sc = cfg["scene"]
     dt = {"f16": torch.float16, "bf16": torch.bfloat16}[wdtype]
     scene = kn.Scene(sc["res"], sc["aabb_min"], sc["aabb_max"], sc["hidden"], torch.from_numpy(sc["weights"]).to(dt).cuda())
@@ -143,33 +173,45 @@ def isolated_mlp(kn, torch, wdtype, iters=10):
     kn.profile_enable(False)
     mlp_ms_g = prof_g["ms_mlp"] / iters
     tflops_g = FLOP_PER_SAMPLE[sc["hidden"]] * M / (mlp_ms_g * 1e-3) / 1e12
-    # the comparison point of Sec. 3.5: the same networks one layer at a time (grouped matrix products, activations
-    # through device memory), on the grouped-order input
-    need = scene.L.kn_layered_workspace_bytes  # sized once, outside the timed calls
-    import ctypes
-    nbytes = ctypes.c_int64()
-    need(scene.h, M, ctypes.byref(nbytes))
-    ws_l = torch.empty(int(nbytes.value), dtype=torch.uint8, device="cuda")
-    for _ in range(2):
-        scene.eval_grouped_layered(pts_g, dirs_g, out=out, workspace=ws_l)
-    torch.cuda.synchronize()
-    kn.profile_enable(True)
-    kn.profile_read(reset=True)
-    for _ in range(iters):
-        scene.eval_grouped_layered(pts_g, dirs_g, out=out, workspace=ws_l)
-    prof_l = kn.profile_read(reset=True)
-    kn.profile_enable(False)
-    mlp_ms_l = prof_l["ms_mlp"] / iters
-    del ws_l
+    mlp_ms_l = None
+    if layered:
+        # the comparison point of Sec. 3.5: the same networks one layer at a time (grouped matrix products,
+        # activations through device memory), on the grouped-order input
+        import ctypes
+        nbytes = ctypes.c_int64()
+        scene.L.kn_layered_workspace_bytes(scene.h, M, ctypes.byref(nbytes))  # sized once, outside the timed calls
+        ws_l = torch.empty(int(nbytes.value), dtype=torch.uint8, device="cuda")
+        for _ in range(2):
+            scene.eval_grouped_layered(pts_g, dirs_g, out=out, workspace=ws_l)
+        torch.cuda.synchronize()
+        kn.profile_enable(True)
+        kn.profile_read(reset=True)
+        for _ in range(iters):
+            scene.eval_grouped_layered(pts_g, dirs_g, out=out, workspace=ws_l)
+        prof_l = kn.profile_read(reset=True)
+        kn.profile_enable(False)
+        mlp_ms_l = prof_l["ms_mlp"] / iters
+        del ws_l
     # algorithmic bytes per point of the whole call: x, d read twice (cell ids, MLP) is not credited: 12 + 12 in, 16 out,
     # key/perm traffic of the bucketing 16
-    return {"workload": "cfg2: 2^22 points, 16^3 networks, %s" % wdtype, "points": M,
+    return {"workload": ("cfg4: 2^23 points, 90 %% in 5 %% of the cells, 16^3 networks, %s" if skewed else
+                         "cfg2: 2^22 points, 16^3 networks, %s") % wdtype, "points": M, "points_per_sec": M / (dt_s / iters),
             "ms_eval_grouped": dt_s * 1e3 / iters, "ms_cell_ids": prof["ms_cell"] / iters,
             "ms_bucket": prof["ms_bucket"] / iters, "ms_mlp_kernel": mlp_ms,
             "mlp_evals_per_sec": M / (mlp_ms * 1e-3), "mlp_tflops": tflops, "mlp_frac_of_mfma_peak": tflops * 1e12 / PEAK_MFMA_16BIT,
             "grouped_order_input": {"ms_mlp_kernel": mlp_ms_g, "mlp_evals_per_sec": M / (mlp_ms_g * 1e-3), "mlp_tflops": tflops_g,
                                     "mlp_frac_of_mfma_peak": tflops_g * 1e12 / PEAK_MFMA_16BIT,
-                                    "layer_at_a_time_ms": mlp_ms_l, "fused_speedup_over_layer_at_a_time": mlp_ms_l / mlp_ms_g},
+                                    "layer_at_a_time_ms": mlp_ms_l,
+                                    "fused_speedup_over_layer_at_a_time": mlp_ms_l / mlp_ms_g if mlp_ms_l else None},
+            "roofline_mlp": with_measured({"kernel": "k_mlp_mfma (fused grouped MLP), points in caller order", "bound": "mfma",
+                                           "achieved": tflops, "peak": PEAK_MFMA_16BIT / 1e12, "unit": "TFLOP/s",
+                                           "frac": tflops * 1e12 / PEAK_MFMA_16BIT, "traffic": None},
+                                          "mfma_bf16_tflops" if wdtype == "bf16" else "mfma_f16_tflops"),
+            "roofline_bucket": with_measured({"kernel": "k_radix_hist + k_radix_scatter + k_bucket_offsets + k_bucket_tiles (stable bucketing)",
+                                              "bound": "hbm", "achieved": 16.0 * M / (prof["ms_bucket"] / iters * 1e-3) / 1e9,
+                                              "peak": PEAK_HBM / 1e9, "unit": "GB/s",
+                                              "frac": 16.0 * M / (prof["ms_bucket"] / iters * 1e-3) / PEAK_HBM, "traffic": None},
+                                             "hbm_copy_gbps"),
             "bucket_gbps_algorithmic": 16.0 * M / (prof["ms_bucket"] / iters * 1e-3) / 1e9,
             "mlp_hbm_gbps_algorithmic": (24.0 + 4.0 + 16.0 + 3.5) * M / (mlp_ms * 1e-3) / 1e9}
 
@@ -198,7 +240,11 @@ def occupancy_extraction(kn, torch, scene, sc, occ_res, iters=5):
             "probes": probes, "ms_probe_kernel": ms, "ms_setup": prof["ms_setup"] / iters, "probes_per_sec": probes / (ms * 1e-3),
             "voxels_marked_frac": float(out.float().mean().item()),
             "roofline": {"kernel": "k_probe_mfma (density of the probe points)", "bound": "mfma", "achieved": tf,
-                         "peak": PEAK_MFMA_16BIT / 1e12, "unit": "TFLOP/s", "frac": tf * 1e12 / PEAK_MFMA_16BIT, "traffic": None}}
+                         "peak": PEAK_MFMA_16BIT / 1e12, "unit": "TFLOP/s", "frac": tf * 1e12 / PEAK_MFMA_16BIT, "traffic": None}
+                        if not MEASURED else with_measured(
+                            {"kernel": "k_probe_mfma (density of the probe points)", "bound": "mfma", "achieved": tf,
+                             "peak": PEAK_MFMA_16BIT / 1e12, "unit": "TFLOP/s", "frac": tf * 1e12 / PEAK_MFMA_16BIT, "traffic": None},
+                            "mfma_bf16_tflops" if sc["wdtype"] == "bf16" else "mfma_f16_tflops")}
 
 
 def render_variant(kn, torch, scene, rays, args, out, steps, seeded):
@@ -246,6 +292,124 @@ def sparse_grid(kn, torch, configs, poses, size, wdtype, steps):
     return res
 
 
+def measure_render(kn, torch, np, configs, cfg, wdtype, steps, warmup, poses, traffic):
+    """The whole path on one render workload: per-pose sample counts, then three passes of `steps` frames (all stage
+    events / events around the dominant kernel only = the timed region / no events) -> dict of figures, and the
+    objects the supplementary measurements go on with."""
+    width, height = cfg["width"], cfg["height"]
+    rays_fn = lambda az: configs.camera_rays(width, height, cfg.get("fov", 40.0), cfg.get("radius", 4.0), az, cfg.get("elevation", 30.0),
+                                             **({"center": cfg["center"]} if "center" in cfg else {}))
+    sc = cfg["scene"]
+    dt = {"f32": torch.float32, "f16": torch.float16, "bf16": torch.bfloat16}[wdtype]
+    occ = sc["occupancy"]
+    scene = kn.Scene(sc["res"], sc["aabb_min"], sc["aabb_max"], sc["hidden"], torch.from_numpy(sc["weights"]).to(dt).cuda(),
+                     None if occ is None else torch.from_numpy(occ).cuda())
+    rays = []
+    for az in poses:
+        o, d = rays_fn(az)
+        rays.append((torch.from_numpy(o).cuda(), torch.from_numpy(d).cuda()))
+    R = width * height
+    out = torch.empty((R, 3), dtype=torch.float32, device="cuda")
+    args = (cfg["t_near"], cfg["step"], cfg["K"], cfg["term_eps"], cfg["bg"])
+    n_p = len(poses)
+
+    stats = []  # per-pose sample counts (untimed)
+    for o, d in rays:
+        _, st = scene.render(o, d, *args, want_stats=True, out=out)
+        stats.append(st)
+    for i in range(warmup):
+        scene.render(*rays[i % n_p], *args, out=out)
+    torch.cuda.synchronize()
+
+    def run_frames(profile_mode):
+        kn.profile_enable(profile_mode)
+        kn.profile_read(reset=True)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(steps):
+            scene.render(*rays[i % n_p], *args, out=out)
+        torch.cuda.synchronize()
+        dt_ = time.perf_counter() - t0
+        prof = kn.profile_read(reset=True)
+        kn.profile_enable(0)
+        return dt_, prof
+
+    # untimed: frames with HIP events around every stage, to find the kernel that takes the most time
+    _, prof_all = run_frames(1)
+    stage_ms = {k: prof_all[k] for k in ("ms_setup", "ms_march", "ms_bucket", "ms_mlp", "ms_blend")}
+    dominant = max(("ms_march", "ms_bucket", "ms_mlp", "ms_blend"), key=lambda k: stage_ms[k])
+    # timed region: HIP events (recorded by the library on the stream it launches on) only around the dominant
+    # kernel, so that the measurement disturbs the frame as little as possible
+    mode = {"ms_mlp": 2, "ms_march": 3}.get(dominant, 1)
+    dt_s, prof = run_frames(mode)
+    dt_plain_s, _ = run_frames(0)  # the same frames without any events, for reference
+
+    blended = sum(stats[i % n_p]["samples_blended"] for i in range(steps))
+    evaluated = sum(stats[i % n_p]["samples_evaluated"] for i in range(steps))
+    waves = sum(stats[i % n_p]["waves"] for i in range(steps))
+    launches = waves  # one launch of each per-wave kernel per wave
+    H = sc["hidden"]
+    f32 = wdtype == "f32"
+    mfma_peak = PEAK_MFMA_F32 if f32 else PEAK_MFMA_16BIT
+    mfma_key = {"f32": "mfma_f32_tflops", "f16": "mfma_f16_tflops", "bf16": "mfma_bf16_tflops"}[wdtype]
+
+    def roof_mlp(p):
+        s_ = p["ms_mlp"] * 1e-3
+        tf = FLOP_PER_SAMPLE[H] * evaluated / s_ / 1e12 if s_ > 0 else 0.0
+        r = {"kernel": "k_mlp_f32 (fused grouped MLP, fp32 MFMA)" if f32 else "k_mlp_mfma (fused grouped MLP)", "bound": "mfma",
+             "achieved": tf, "peak": mfma_peak / 1e12, "unit": "TFLOP/s", "frac": tf * 1e12 / mfma_peak,
+             "traffic": traffic.get("k_mlp_mfma"), "avg_launch_ms": p["ms_mlp"] / max(launches, 1), "launches": launches,
+             "samples_per_launch": evaluated / max(launches, 1),
+             # the same kernel on the samples the method itself evaluates (those in front of the termination point)
+             "achieved_on_blended_samples": tf * blended / max(evaluated, 1)}
+        if not f32:
+            # second view: its vector-ALU issue slots (counted in the generated code, transcendental instructions
+            # twice) against what 1024 SIMDs can issue at 2.4 GHz, one slot per 4 cycles
+            slots = VALU_SLOTS_PER_16_SAMPLES[H] / 16.0 * evaluated
+            r["valu_issue_frac"] = slots / (s_ * 1024 * 2.4e9 / 4.0) if s_ > 0 else 0.0
+        return with_measured(r, mfma_key)
+
+    def roof_hbm(p, key, kernel, nbytes, traffic_key):
+        s_ = p[key] * 1e-3
+        return with_measured({"kernel": kernel, "bound": "hbm", "achieved": nbytes / s_ / 1e9 if s_ > 0 else 0.0,
+                              "peak": PEAK_HBM / 1e9, "unit": "GB/s", "frac": nbytes / s_ / PEAK_HBM if s_ > 0 else 0.0,
+                              "traffic": traffic.get(traffic_key), "avg_launch_ms": p[key] / max(launches, 1),
+                              "launches": launches}, "hbm_copy_gbps")
+
+    def roof_march(p):
+        # algorithmic bytes: 24 B per ray read + the packed occupancy grid read, once per frame, and 8 B (key,
+        # record) written per kept sample
+        occ_bytes = 0 if occ is None else int(np.prod(occ.shape)) / 8
+        return roof_hbm(p, "ms_march", "k_march_wave (march + empty-space skipping)", steps * (occ_bytes + 24.0 * R) + 8.0 * evaluated,
+                        "k_march_wave")
+
+    def roof_group(p):
+        # algorithmic bytes: every sample's key is read twice (count, fill) and its slot number written: 12 B
+        return roof_hbm(p, "ms_bucket", "k_group_pass (order-free grouping by network)", 12.0 * evaluated, "k_group_pass")
+
+    def roof_blend(p):
+        # algorithmic bytes: 16 B read per evaluated sample, 12 B written per ray of the frame; the per-ray state of the
+        # live rays (32 B per wave) is not credited here
+        return roof_hbm(p, "ms_blend", "k_composite_wave / k_composite_group (blend, early termination)",
+                        16.0 * evaluated + 12.0 * R * steps, "k_composite_wave")
+
+    roofline = roof_mlp(prof) if dominant == "ms_mlp" else roof_march(prof) if dominant == "ms_march" else roof_mlp(prof_all)
+    res = {
+        "value": blended / dt_s, "unit": "samples/s", "steps": steps, "warmup": warmup, "ms_per_step": dt_s * 1e3 / steps,
+        "dtype": wdtype, "frames_per_sec": steps / dt_s,
+        "ms_per_step_without_events": dt_plain_s * 1e3 / steps,
+        "samples_blended_per_frame": blended / steps, "samples_evaluated_per_frame": evaluated / steps,
+        "evaluated_over_blended": evaluated / max(blended, 1),
+        "waves_per_frame": waves / steps,
+        "stage_ms_per_frame": {k: v / steps for k, v in stage_ms.items()},
+        "dominant_kernel_stage": dominant,
+        "roofline": roofline,
+        "roofline_mlp_all_events": roof_mlp(prof_all), "roofline_march_all_events": roof_march(prof_all),
+        "roofline_group_all_events": roof_group(prof_all), "roofline_blend_all_events": roof_blend(prof_all),
+    }
+    return res, dict(scene=scene, rays=rays, args=args, out=out, R=R, rays_fn=rays_fn, blended_per_frame=blended / steps)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -264,6 +428,8 @@ def main():
                     help="stop after the timed frames of the workload (no supplementary measurements): for counter runs")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (reference point for FETCH_SIZE / WRITE_SIZE counters)")
+    ap.add_argument("--bucket-only", action="store_true",
+                    help="only the cfg2 eval_grouped calls (for counter runs on the radix bucketing kernels)")
     a = ap.parse_args()
     if a.gpus != 1:
         print("bench.py: this build runs on one GPU only (the path would shard by rays, every GPU holding the whole scene); use --gpus 1",
@@ -275,11 +441,24 @@ def main():
 
     import paper_2103_13744_amd as kn
     from kn_synth import configs
+    from paper_2103_13744_amd import peaks
 
     torch.cuda.set_device(0)
     kn.load_library(build_if_missing=True)
+    if a.calibrate_copy:  # first, so that the counter runs find it as the largest copy dispatch whatever follows
+        src_buf = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
+        dst_buf = torch.empty_like(src_buf)
+        dst_buf.copy_(src_buf)
+        torch.cuda.synchronize()
+        del src_buf, dst_buf
+    if a.bucket_only:
+        r = isolated_mlp(kn, torch, a.wdtype or "f16", iters=4, layered=False)
+        print(json.dumps({"isolated_mlp": r}))
+        return
     if a.wave:
         kn.set_render_params(*[int(v) for v in a.wave.split(",")])
+    if not a.frames_only:
+        MEASURED.update(peaks.measure_peaks())
     poses = [45.0 * i for i in range(8)]
     if a.wdtype is None:
         a.wdtype = "f16" if a.workload == "cfg3" else "bf16"
@@ -291,137 +470,56 @@ def main():
         cfg = configs.config5(azimuth=poses[0], wdtype=a.wdtype)
         workload = ("cfg5: 1920x1080 render, 32^3 networks (H=64), 512^3 occupancy grid (5% occupied), step diag/1024, "
                     "eps 0.01, 8 camera poses")
-    width, height = cfg["width"], cfg["height"]
-    rays_fn = lambda az: configs.camera_rays(width, height, 40.0, 4.0, az, 30.0)
-    sc = cfg["scene"]
-    dt = {"f32": torch.float32, "f16": torch.float16, "bf16": torch.bfloat16}[a.wdtype]
-    scene = kn.Scene(sc["res"], sc["aabb_min"], sc["aabb_max"], sc["hidden"], torch.from_numpy(sc["weights"]).to(dt).cuda(),
-                     torch.from_numpy(sc["occupancy"]).cuda())
-    rays = []
-    for az in poses:
-        o, d = rays_fn(az)
-        rays.append((torch.from_numpy(o).cuda(), torch.from_numpy(d).cuda()))
-    R = width * height
-    out = torch.empty((R, 3), dtype=torch.float32, device="cuda")
-    args = (cfg["t_near"], cfg["step"], cfg["K"], cfg["term_eps"], cfg["bg"])
-
-    # per-pose sample counts (untimed)
-    stats = []
-    for o, d in rays:
-        _, st = scene.render(o, d, *args, want_stats=True, out=out)
-        stats.append(st)
-    for i in range(a.warmup):
-        scene.render(*rays[i % 8], *args, out=out)
-    torch.cuda.synchronize()
-
-    def run_frames(profile_mode):
-        kn.profile_enable(profile_mode)
-        kn.profile_read(reset=True)
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for i in range(a.steps):
-            scene.render(*rays[i % 8], *args, out=out)
-        torch.cuda.synchronize()
-        dt = time.perf_counter() - t0
-        prof = kn.profile_read(reset=True)
-        kn.profile_enable(0)
-        return dt, prof
-
-    # untimed: K frames with HIP events around every stage, to find the kernel that takes the most time
-    _, prof_all = run_frames(1)
-    stage_ms = {k: prof_all[k] for k in ("ms_setup", "ms_march", "ms_bucket", "ms_mlp", "ms_blend")}
-    dominant = max(("ms_march", "ms_bucket", "ms_mlp", "ms_blend"), key=lambda k: stage_ms[k])
-    # timed region: K frames, HIP events (recorded by the library on the stream it launches on) only around the
-    # dominant kernel, so that the measurement disturbs the frame as little as possible
-    mode = {"ms_mlp": 2, "ms_march": 3}.get(dominant, 1)
-    dt_s, prof = run_frames(mode)
-    # the same K frames without any events, for reference
-    dt_plain_s, _ = run_frames(0)
-
-    blended = sum(stats[i % 8]["samples_blended"] for i in range(a.steps))
-    evaluated = sum(stats[i % 8]["samples_evaluated"] for i in range(a.steps))
-    waves = sum(stats[i % 8]["waves"] for i in range(a.steps))
-    launches = waves  # one launch of each per-wave kernel per wave
-    H = sc["hidden"]
+    default_workload = a.workload == "cfg3" and a.wdtype == "f16" and a.size == 800
     # (the committed counter summary is of the default workload)
-    traffic = read_traffic() if (a.workload == "cfg3" and a.wdtype == "f16" and a.size == 800) else {}
-
-    def roof_mlp(p):
-        s_ = p["ms_mlp"] * 1e-3
-        tf = FLOP_PER_SAMPLE[H] * evaluated / s_ / 1e12 if s_ > 0 else 0.0
-        # second view of the same kernel: its vector-ALU issue slots (counted in the generated code: 125 per 16 samples at
-        # H = 32, transcendental instructions counted twice) against what 1024 SIMDs can issue at 2.4 GHz, one slot per
-        # 4 cycles; the encoding and the 16-bit packing between layers, not the MFMAs, are what the kernel waits for
-        slots = VALU_SLOTS_PER_16_SAMPLES[H] / 16.0 * evaluated
-        valu_frac = slots / (s_ * 1024 * 2.4e9 / 4.0) if s_ > 0 else 0.0
-        return {"kernel": "k_mlp_mfma (fused grouped MLP)", "bound": "mfma", "achieved": tf, "peak": PEAK_MFMA_16BIT / 1e12,
-                "unit": "TFLOP/s", "frac": tf * 1e12 / PEAK_MFMA_16BIT, "traffic": traffic.get("k_mlp_mfma"),
-                "avg_launch_ms": p["ms_mlp"] / max(launches, 1), "launches": launches,
-                "samples_per_launch": evaluated / max(launches, 1), "valu_issue_frac": valu_frac}
-
-    def roof_march(p):
-        # algorithmic bytes: 24 B per ray read + the packed occupancy grid read, once per frame, and 8 B (key,
-        # record) written per kept sample
-        occ_bytes = int(np.prod(sc["occupancy"].shape)) / 8
-        nbytes = a.steps * (occ_bytes + 24.0 * R) + 8.0 * evaluated
-        s_ = p["ms_march"] * 1e-3
-        return {"kernel": "k_march_wave (march + empty-space skipping)", "bound": "hbm",
-                "achieved": nbytes / s_ / 1e9 if s_ > 0 else 0.0, "peak": PEAK_HBM / 1e9, "unit": "GB/s",
-                "frac": nbytes / s_ / PEAK_HBM if s_ > 0 else 0.0, "traffic": traffic.get("k_march_wave"),
-                "avg_launch_ms": p["ms_march"] / max(launches, 1), "launches": launches}
-
-    def roof_hbm(p, key, kernel, nbytes, traffic_key):
-        s_ = p[key] * 1e-3
-        return {"kernel": kernel, "bound": "hbm", "achieved": nbytes / s_ / 1e9 if s_ > 0 else 0.0, "peak": PEAK_HBM / 1e9,
-                "unit": "GB/s", "frac": nbytes / s_ / PEAK_HBM if s_ > 0 else 0.0, "traffic": traffic.get(traffic_key),
-                "avg_launch_ms": p[key] / max(launches, 1), "launches": launches}
-
-    def roof_group(p):
-        # algorithmic bytes: every sample's key is read twice (count, fill) and its slot number written: 12 B
-        return roof_hbm(p, "ms_bucket", "k_group_pass (order-free grouping by network)", 12.0 * evaluated, "k_group_pass")
-
-    def roof_blend(p):
-        # algorithmic bytes: 16 B read per evaluated sample, 12 B written per ray of the frame; the per-ray state of the
-        # live rays (32 B per wave) is not credited here
-        return roof_hbm(p, "ms_blend", "k_composite_wave / k_composite_group + k_sum_partials (blend, early termination)",
-                        16.0 * evaluated + 12.0 * R * a.steps, "k_composite_wave")
-
-    roofline = roof_mlp(prof) if dominant == "ms_mlp" else roof_march(prof) if dominant == "ms_march" else roof_mlp(prof_all)
-    res = {
-        "metric": "MLP sample evals/sec + frames/sec at 800x800",
-        "value": blended / dt_s, "unit": "samples/s",
-        "n_gpus": 1, "steps": a.steps, "warmup": a.warmup, "ms_per_step": dt_s * 1e3 / a.steps,
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": a.wdtype, "data": "synthetic",
-        "config": {"workload": workload},
-        "frames_per_sec": a.steps / dt_s,
-        "ms_per_step_without_events": dt_plain_s * 1e3 / a.steps,
-        "samples_blended_per_frame": blended / a.steps, "samples_evaluated_per_frame": evaluated / a.steps,
-        "waves_per_frame": waves / a.steps,
-        "stage_ms_per_frame": {k: v / a.steps for k, v in stage_ms.items()},
-        "dominant_kernel_stage": dominant,
-        "roofline": roofline,
-        "roofline_mlp_all_events": roof_mlp(prof_all), "roofline_march_all_events": roof_march(prof_all),
-        "roofline_group_all_events": roof_group(prof_all), "roofline_blend_all_events": roof_blend(prof_all),
-    }
+    traffic, traffic_commit = read_traffic() if default_workload else ({}, None)
+    m, ctx = measure_render(kn, torch, np, configs, cfg, a.wdtype, a.steps, a.warmup, poses, traffic)
+    res = {"metric": "MLP sample evals/sec + frames/sec at 800x800", "value": m["value"], "unit": m["unit"], "n_gpus": 1,
+           "steps": a.steps, "warmup": a.warmup, "ms_per_step": m["ms_per_step"], "higher_is_better": True, "scaling": "weak",
+           "vs_baseline": None, "dtype": a.wdtype, "data": "synthetic", "config": {"workload": workload}}
+    res.update({k: v for k, v in m.items() if k not in res})
+    if traffic:
+        res["roofline"]["traffic_source"] = {"file": TRAFFIC_FILE, "measured_at_commit": traffic_commit,
+                                             "note": "rocprofv3 FETCH_SIZE / WRITE_SIZE runs of this command, not re-measured in this run"}
+    if MEASURED:
+        res["measured_peaks"] = dict(MEASURED, note="micro-benchmarks of this GPU (csrc/kn_peaks.hip): plain 1 GiB copy (read + written), "
+                                                    "read-only sweep, register-only MFMA / FMA / sine loops")
+    scene, rays, args, out, R = ctx["scene"], ctx["rays"], ctx["args"], ctx["out"], ctx["R"]
+    sc = cfg["scene"]
     if a.in_flight > 1 and not a.frames_only:
-        res["frames_in_flight"] = frames_in_flight(torch, scene, rays, args, R, a.steps, a.in_flight, blended / a.steps)
-    if a.calibrate_copy:
-        src_buf = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
-        dst_buf = torch.empty_like(src_buf)
-        dst_buf.copy_(src_buf)
-        torch.cuda.synchronize()
-        del src_buf, dst_buf
+        res["frames_in_flight"] = frames_in_flight(torch, scene, rays, args, R, a.steps, a.in_flight, ctx["blended_per_frame"])
     if a.wdtype in ("f16", "bf16") and a.workload == "cfg3" and not a.frames_only:
         # the same frames with stratified sampling (Sec. 3.4), a new seed per frame
         res["stratified_sampling"] = render_variant(kn, torch, scene, rays, args, out, a.steps, True)
         res["occupancy_extraction"] = occupancy_extraction(kn, torch, scene, sc, sc["occupancy"].shape)
         res["sparse_grid"] = sparse_grid(kn, torch, configs, poses, a.size, a.wdtype, a.steps)
-        del scene
+    del scene, ctx
+    torch.cuda.empty_cache()
+    if default_workload and not a.frames_only:
+        # the other workloads of the benchmark's configuration list, shorter: cfg1 (tiny fp32 render), cfg2 (isolated
+        # grouped MLP), cfg4 (load skew), cfg5 (large render, 8 frames, no CPU leg)
+        others = {}
+        c1 = dict(configs.config1(), radius=2.5, elevation=20.0, center=(0.5, 0.5, 0.5))
+        others["cfg1"], _ = measure_render(kn, torch, np, configs, c1, "f32", a.steps, 4, [30.0], {})
+        others["cfg1"]["workload"] = "cfg1: 64x64 render, 2^3 networks (H=32), fp32, 32 samples per ray, no occupancy grid, no termination"
+        others["cfg2"] = isolated_mlp(kn, torch, "f16")
+        others["cfg4"] = isolated_mlp(kn, torch, "bf16", iters=5, skewed=True, layered=False)
         torch.cuda.empty_cache()
-        res["isolated_mlp"] = isolated_mlp(kn, torch, a.wdtype)
-    if not a.no_cpu_baseline:
-        res["cpu_baseline"] = cpu_baseline(cfg, rays_fn, poses)
+        c5 = configs.config5(azimuth=poses[0], wdtype="bf16")
+        others["cfg5"], c5ctx = measure_render(kn, torch, np, configs, c5, "bf16", 8, 2, poses, {})
+        others["cfg5"]["workload"] = ("cfg5: 1920x1080 render, 32^3 networks (H=64), 512^3 occupancy grid (5% occupied), step diag/1024, "
+                                      "eps 0.01, bf16, 8 camera poses, 8 frames")
+        del c5ctx
+        torch.cuda.empty_cache()
+        res["other_workloads"] = others
+        res["isolated_mlp"] = others["cfg2"]
+    if not a.no_cpu_baseline and not a.frames_only:
+        res["cpu_baseline"] = cpu_baseline(cfg, ctx_rays_fn(configs, cfg), poses)
     print(json.dumps(res))
+
+
+def ctx_rays_fn(configs, cfg):
+    return lambda az: configs.camera_rays(cfg["width"], cfg["height"], 40.0, 4.0, az, 30.0)
 
 
 if __name__ == "__main__":
