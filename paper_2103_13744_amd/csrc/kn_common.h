@@ -294,6 +294,9 @@ struct KnSampleSrc {
     // with the sample's own delta.
     int32_t strat;         // 0 = midpoint lattice
     uint32_t seed_key;     // kn_mix32(seed)
+    // render, 16-bit scenes: gamma(d) per ray, already rounded and in the operand order of the direction block of the
+    // last hidden layer: 4 lane groups x 16 bytes per ray (written by the render's set-up kernel for the rays that live)
+    const uint16_t *dir_table;
 };
 
 int kn_mlp_launch(const kn_scene *sc, hipStream_t st, const KnSampleSrc &src, const KnBucketOut &b,

@@ -39,10 +39,16 @@
 // to revolutions per restart frequency, so that each lane group reads exactly the operands of its
 // role.
 #include "kn_common.h"
+#include "kn_dir_encode.h"
 #include "kn_mlp_shared.h"
 #include "kn_probe.h"
 
 namespace {
+
+using kn_enc::double_angle;
+using kn_enc::INV_2PI;
+using kn_enc::pk;
+using kn_enc::sincos_rev;
 
 typedef _Float16 h8 __attribute__((ext_vector_type(8)));
 typedef _Float16 h2 __attribute__((ext_vector_type(2)));
@@ -169,15 +175,6 @@ template <bool BF> __device__ __forceinline__ f4 mfma(u4 a, u4 b, f4 c)
         return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(h8, a), __builtin_bit_cast(h8, b), c, 0, 0, 0);
 }
 
-template <bool BF> __device__ __forceinline__ unsigned pk(float a, float b)
-{
-    f2 v = {a, b};
-    if constexpr (BF)
-        return __builtin_bit_cast(unsigned, __builtin_convertvector(v, b2));
-    else
-        return __builtin_bit_cast(unsigned, __builtin_convertvector(v, h2));
-}
-
 // ReLU on two packed 16-bit floats: as signed 16-bit integers every negative float is negative
 __device__ __forceinline__ unsigned relu2(unsigned v)
 {
@@ -197,25 +194,6 @@ template <int H, bool BF, bool RELU> __device__ __forceinline__ void pack_acts(c
         B[kb] = (u4){r0, r1, r2, r3};
     }
 }
-
-// s = sin, c = cos of 2*pi*rev.  The hardware takes revolutions and reduces the range itself for |rev| <= 256;
-// WRAP adds an explicit reduction for arguments that may exceed that.
-template <bool WRAP> __device__ __forceinline__ void sincos_rev(float rev, float &s, float &c)
-{
-    const float f = WRAP ? __builtin_amdgcn_fractf(rev) : rev;
-    s = __builtin_amdgcn_sinf(f);
-    c = __builtin_amdgcn_cosf(f);
-}
-// (sin a, cos a) -> (sin 2a, cos 2a) = (2 sin a cos a, 2 (1/2 - sin^2 a)).  Written so that each line is one
-// VALU instruction with the "times two" output modifier (this file is compiled with flushed fp32 denormals
-// and without IEEE mode).
-__device__ __forceinline__ void double_angle(float s, float c, float &s2o, float &c2o)
-{
-    s2o = (s * c) * 2.0f;
-    c2o = fmaf(-s, s, 0.5f) * 2.0f;
-}
-
-constexpr float INV_2PI = 0.15915494309189535f;
 
 // B operands of layer 1 for one lane: gamma(x) slots of lane group g (see "Slot order").  ang[0..2]: the lane's three
 // restart angles in revolutions; ident[0..1]: the packed pairs (x, y), (z, 1) that sit in group 3's last slots.
@@ -256,7 +234,10 @@ template <bool BF> __device__ __forceinline__ u4 encode_direction(float rev, u4 
 // H = 64, two wavefronts per SIMD (the matrix-core operands are read straight from the register file either way).
 // STRAT (render with stratified sampling): the lattice points sit at their drawn offsets and the density is
 // scaled by delta_k / step on the way out (see KnSampleSrc).
-template <int H, bool BF, int WAVES, bool WRAP, bool STRAT>
+// DIRTAB (render): gamma(d) is the same for every sample of a ray, so the render's set-up kernel encodes it once
+// per ray, already in operand order (KnSampleSrc::dir_table), and a lane fetches its 16 bytes instead of computing
+// them (a sixth of the kernel's vector instructions).
+template <int H, bool BF, int WAVES, bool WRAP, bool STRAT, bool DIRTAB>
 __global__ void __launch_bounds__(WAVES *KN_WAVE) __attribute__((amdgpu_waves_per_eu(H == 32 ? 3 : 2, H == 32 ? 3 : 2)))
     k_mlp_mfma(const uint16_t *__restrict__ packed, KnSampleSrc src, const int32_t *__restrict__ perm,
                const KnTile *__restrict__ tiles, const int32_t *__restrict__ n_tiles, float *__restrict__ sigma,
@@ -409,6 +390,7 @@ __global__ void __launch_bounds__(WAVES *KN_WAVE) __attribute__((amdgpu_waves_pe
         float nx, ny, nz, dscale;
         finish(raw0, rec0, nx, ny, nz, dscale);
         const float ndx = raw0.b[0], ndy = raw0.b[1], ndz = raw0.b[2];
+        const uint32_t ray_no = rec0 >> src.kbits; // (render)
         write_out(); // after the loads of the last iteration have been waited for, before new ones are issued
         // next levels for the following tiles (their operands were loaded one iteration ago)
         raw0 = load_raw(idx1, rec1);
@@ -424,11 +406,15 @@ __global__ void __launch_bounds__(WAVES *KN_WAVE) __attribute__((amdgpu_waves_pe
             // lane groups 0..2 encode one axis each at frequencies 0..7 (restarts at 2^0, 2^2, 2^4) and the
             // direction at 0..3; group 3 encodes frequencies 8, 9 of all three axes (restarts at 2^8)
             const float p3[3] = {nx, ny, nz}, d3[3] = {ndx, ndy, ndz};
+            // fourth word: the direction component in revolutions, or (DIRTAB) the ray's number for every lane group
+            const float ray_bits = __builtin_bit_cast(float, ray_no);
 #pragma unroll
             for (int a = 0; a < 3; ++a)
-                stage[wave][a][0][lane] = (f4){p3[a] * INV_2PI, p3[a] * (4.0f * INV_2PI), p3[a] * (16.0f * INV_2PI), d3[a] * INV_2PI};
-            stage[wave][3][0][lane] = (f4){nx * (256.0f * INV_2PI), ny * (256.0f * INV_2PI), nz * (256.0f * INV_2PI), 0.0f};
-            const u4 ident = {pk<BF>(nx, ny), pk<BF>(nz, 1.0f), pk<BF>(ndx, ndy), pk<BF>(ndz, 1.0f)};
+                stage[wave][a][0][lane] = (f4){p3[a] * INV_2PI, p3[a] * (4.0f * INV_2PI), p3[a] * (16.0f * INV_2PI),
+                                               DIRTAB ? ray_bits : d3[a] * INV_2PI};
+            stage[wave][3][0][lane] = (f4){nx * (256.0f * INV_2PI), ny * (256.0f * INV_2PI), nz * (256.0f * INV_2PI),
+                                           DIRTAB ? ray_bits : 0.0f};
+            const u4 ident = {pk<BF>(nx, ny), pk<BF>(nz, 1.0f), DIRTAB ? 0u : pk<BF>(ndx, ndy), DIRTAB ? 0u : pk<BF>(ndz, 1.0f)};
             stage[wave][3][1][lane] = __builtin_bit_cast(f4, ident);
         }
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
@@ -445,7 +431,16 @@ __global__ void __launch_bounds__(WAVES *KN_WAVE) __attribute__((amdgpu_waves_pe
                 const u4 ident = __builtin_bit_cast(u4, stage[wave][g][1][16 * u + n]); // meaningful in group 3 only
                 u4 Bx[2];
                 encode_position<BF, WRAP>(ang, ident, m3, Bx);
-                const u4 Bd = encode_direction<BF>(ang[3], ident, m3);
+                u4 Bd;
+                if constexpr (DIRTAB) {
+                    // (the element is copied to a scalar first: a bit cast applied to the vector element itself read
+                    // the vector's first element in the generated code)
+                    const float ray_word = ang[3];
+                    const uint32_t ray_of_sample = __float_as_uint(ray_word);
+                    Bd = *(const u4 *)(src.dir_table + ((int64_t)ray_of_sample * 4 + g) * 8);
+                } else {
+                    Bd = encode_direction<BF>(ang[3], ident, m3);
+                }
                 f4 acc[HT];
                 u4 Bh[HK];
                 // layer 1: gamma(x) -> H, ReLU (bias through the constant-1 slot)
@@ -814,9 +809,13 @@ int launch(const kn_scene *sc, hipStream_t st, const KnSampleSrc &src, const KnB
     for (int a = 0; a < 3; ++a)
         reach = fmaxf(reach, fmaxf(fabsf(sc->desc.aabb_min[a]), fabsf(sc->desc.aabb_max[a])));
     const bool wrap = !(reach * (256.0f * INV_2PI) < 250.0f);
-    const bool strat = src.strat != 0 && src.points == nullptr;
-    auto kernel = wrap ? (strat ? k_mlp_mfma<H, BF, WAVES, true, true> : k_mlp_mfma<H, BF, WAVES, true, false>)
-                       : (strat ? k_mlp_mfma<H, BF, WAVES, false, true> : k_mlp_mfma<H, BF, WAVES, false, false>);
+    const bool rays = src.points == nullptr;
+    const bool strat = src.strat != 0 && rays;
+    if (rays && !src.dir_table) return KN_E_INVALID_ARG;
+    // explicit points: the plain kernel; render: the ray's encoded direction comes from the table, midpoint or stratified lattice
+    auto kernel = !rays ? (wrap ? k_mlp_mfma<H, BF, WAVES, true, false, false> : k_mlp_mfma<H, BF, WAVES, false, false, false>)
+                  : wrap ? (strat ? k_mlp_mfma<H, BF, WAVES, true, true, true> : k_mlp_mfma<H, BF, WAVES, true, false, true>)
+                         : (strat ? k_mlp_mfma<H, BF, WAVES, false, true, true> : k_mlp_mfma<H, BF, WAVES, false, false, true>);
     hipLaunchKernelGGL(kernel, dim3((unsigned)blocks), dim3(WAVES * KN_WAVE), 0, st, (const uint16_t *)sc->packed_w, src, b.perm,
                        b.tiles, b.n_tiles, sigma, rgb);
     KN_CHECK_LAUNCH();

@@ -11,6 +11,7 @@
 // count per row); the grouping and the MLP kernel address samples by slot number, so the rows are never
 // compacted into a list.
 #include "kn_common.h"
+#include "kn_dir_encode.h"
 
 #include <math.h>
 
@@ -359,7 +360,7 @@ __global__ void __launch_bounds__(RAY_BLOCK)
     k_render_init(MarchParams p, const float *__restrict__ rays_o, const float *__restrict__ rays_d, int64_t R, RayState s,
                   int32_t *__restrict__ alive, int32_t *__restrict__ blk_sum, float bg0, float bg1, float bg2,
                   float *__restrict__ rgb_out, int32_t *__restrict__ zero, int32_t n_zero, int32_t *__restrict__ hist,
-                  int32_t n_hist)
+                  int32_t n_hist, uint16_t *__restrict__ dir_table, int32_t dir_bf16)
 {
     __shared__ int32_t lds[RAY_BLOCK / KN_WAVE];
     const int64_t r = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -381,6 +382,14 @@ __global__ void __launch_bounds__(RAY_BLOCK)
             rgb_out[3 * r] = bg0;
             rgb_out[3 * r + 1] = bg1;
             rgb_out[3 * r + 2] = bg2;
+        } else if (dir_table) {
+            // gamma(d) is the same for every sample of the ray: encoded once, in the grouped-MLP kernel's operand order
+            kn_enc::u4 slots[4];
+            if (dir_bf16) kn_enc::dir_slots<true>(d[0], d[1], d[2], slots);
+            else kn_enc::dir_slots<false>(d[0], d[1], d[2], slots);
+            kn_enc::u4 *dst = (kn_enc::u4 *)(dir_table + 32 * r);
+#pragma unroll
+            for (int g = 0; g < 4; ++g) dst[g] = slots[g];
         }
     }
     const int32_t total = kn_block_sum(lives, lds);
@@ -1048,6 +1057,7 @@ struct RenderWs {
     float *T, *C, *out4;
     int32_t *k_next, *k_end;
     unsigned long long *counters;
+    uint16_t *dir_table; // 32 halfs per ray (16-bit scenes)
 };
 
 static void carve_render(KnCarver &ws, int64_t R, int64_t slots, RenderWs &w)
@@ -1071,6 +1081,7 @@ static void carve_render(KnCarver &ws, int64_t R, int64_t slots, RenderWs &w)
     w.row_keys = ws.carve<int32_t>(slots);
     w.row_rec = ws.carve<uint32_t>(slots);
     w.out4 = ws.carve<float>(4 * slots);
+    w.dir_table = ws.carve<uint16_t>(32 * R);
 }
 
 int64_t kn_render_ws_bytes(const kn_scene *sc, int64_t R, int32_t slots_per_ray)
@@ -1194,7 +1205,8 @@ static int render_impl(kn_ctx *ctx, const kn_scene *sc, void *stream, const floa
     if (first_samples > knobs.slots_per_ray) first_samples = knobs.slots_per_ray;
     const WaveSchedule sched{first_samples, knobs.wave_growth, K > 0 ? K : 1, budget};
     hipLaunchKernelGGL(render_init_kernel(opt), dim3(rblocks), dim3(RAY_BLOCK), 0, st, p, rays_o, rays_d, R, rs, w.alive_b, w.blk_sum,
-                       bg[0], bg[1], bg[2], rgb_out, (int32_t *)w.counters, 16, gw.hist, R >= n_hist ? (int32_t)n_hist : 0);
+                       bg[0], bg[1], bg[2], rgb_out, (int32_t *)w.counters, 16, gw.hist, R >= n_hist ? (int32_t)n_hist : 0,
+                       sc->desc.wdtype == KN_F32 ? (uint16_t *)nullptr : w.dir_table, sc->desc.wdtype == KN_BF16 ? 1 : 0);
     KN_CHECK_LAUNCH();
     if (R < n_hist) KN_TRY(kn_fill_i32(st, gw.hist, n_hist, 0));
     if (R < 16) KN_TRY(kn_fill_i32(st, (int32_t *)w.counters, 16, 0));
@@ -1216,6 +1228,7 @@ static int render_impl(kn_ctx *ctx, const kn_scene *sc, void *stream, const floa
     src.out4 = w.out4;
     src.strat = seed ? 1 : 0;
     src.seed_key = p.seed_key;
+    src.dir_table = w.dir_table;
 
     const int tile_len = kn_mlp_tile_len(sc);
     int32_t *live = w.live_a, *live_next = w.live_b, *alive = w.alive_a, *alive_next = w.alive_b;
