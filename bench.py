@@ -146,14 +146,17 @@ def isolated_mlp(kn, torch, wdtype, iters=10, skewed=False, layered=True):
     for _ in range(3):
         scene.eval_grouped(pts, dirs, out=out)
     torch.cuda.synchronize()
-    kn.profile_enable(True)
-    kn.profile_read(reset=True)
     t0 = time.perf_counter()
     for _ in range(iters):
         scene.eval_grouped(pts, dirs, out=out)
     torch.cuda.synchronize()
-    dt_s = time.perf_counter() - t0
-    prof = kn.profile_read(reset=True)
+    dt_s = time.perf_counter() - t0            # the whole call, no stage events on the stream
+    kn.profile_enable(True)
+    kn.profile_read(reset=True)
+    for _ in range(iters):
+        scene.eval_grouped(pts, dirs, out=out)
+    torch.cuda.synchronize()
+    prof = kn.profile_read(reset=True)         # the stages (the events add a few microseconds between them)
     kn.profile_enable(False)
     mlp_ms = prof["ms_mlp"] / iters
     tflops = FLOP_PER_SAMPLE[sc["hidden"]] * M / (mlp_ms * 1e-3) / 1e12
@@ -192,8 +195,14 @@ def isolated_mlp(kn, torch, wdtype, iters=10, skewed=False, layered=True):
         kn.profile_enable(False)
         mlp_ms_l = prof_l["ms_mlp"] / iters
         del ws_l
-    # algorithmic bytes per point of the whole call: x, d read twice (cell ids, MLP) is not credited: 12 + 12 in, 16 out,
-    # key/perm traffic of the bucketing 16
+    # Re-ordering stage (everything between the cell ids and the MLP kernel: two radix passes that move the samples,
+    # their count tables and scans, offsets and tile list; and, after the MLP kernel, the copy of the staged results
+    # into the caller's arrays).  Algorithmic bytes per point = what a physical re-ordering of the batch has to move
+    # once: key 4 + position and direction 24 read, one 32-byte record written, results 16 read and 16 written = 92.
+    # What the kernels really move is 164 (first pass 28 in, 36 out; second 36 in, 32 out; results 16 in, 16 out); the
+    # figure a sort of indices alone would be charged with, 16 per key (the definition this line used while the stage
+    # sorted indices), is kept beside it.  The scattered 16-byte store of each result is inside the MLP kernel's time.
+    t_bucket = prof["ms_bucket"] / iters * 1e-3
     return {"workload": ("cfg4: 2^23 points, 90 %% in 5 %% of the cells, 16^3 networks, %s" if skewed else
                          "cfg2: 2^22 points, 16^3 networks, %s") % wdtype, "points": M, "points_per_sec": M / (dt_s / iters),
             "ms_eval_grouped": dt_s * 1e3 / iters, "ms_cell_ids": prof["ms_cell"] / iters,
@@ -207,13 +216,17 @@ def isolated_mlp(kn, torch, wdtype, iters=10, skewed=False, layered=True):
                                            "achieved": tflops, "peak": PEAK_MFMA_16BIT / 1e12, "unit": "TFLOP/s",
                                            "frac": tflops * 1e12 / PEAK_MFMA_16BIT, "traffic": None},
                                           "mfma_bf16_tflops" if wdtype == "bf16" else "mfma_f16_tflops"),
-            "roofline_bucket": with_measured({"kernel": "k_radix_hist + k_radix_scatter + k_bucket_offsets + k_bucket_tiles (stable bucketing)",
-                                              "bound": "hbm", "achieved": 16.0 * M / (prof["ms_bucket"] / iters * 1e-3) / 1e9,
+            "roofline_bucket": with_measured({"kernel": "k_reorder_scatter x2 + k_key_hist + k_digit_scan x2 + k_offsets_tiles "
+                                                        "+ k_split_results (stable re-ordering of the samples by network, results back in caller order)",
+                                              "bound": "hbm", "achieved": 92.0 * M / t_bucket / 1e9,
                                               "peak": PEAK_HBM / 1e9, "unit": "GB/s",
-                                              "frac": 16.0 * M / (prof["ms_bucket"] / iters * 1e-3) / PEAK_HBM, "traffic": None},
+                                              "frac": 92.0 * M / t_bucket / PEAK_HBM, "traffic": None,
+                                              "bytes_per_point_algorithmic": 92, "bytes_per_point_moved": 164,
+                                              "moved_gbps": 164.0 * M / t_bucket / 1e9},
                                              "hbm_copy_gbps"),
-            "bucket_gbps_algorithmic": 16.0 * M / (prof["ms_bucket"] / iters * 1e-3) / 1e9,
-            "mlp_hbm_gbps_algorithmic": (24.0 + 4.0 + 16.0 + 3.5) * M / (mlp_ms * 1e-3) / 1e9}
+            "bucket_gbps_algorithmic": 92.0 * M / t_bucket / 1e9,
+            "bucket_gbps_at_16_bytes_per_key": 16.0 * M / t_bucket / 1e9,
+            "mlp_hbm_gbps_algorithmic": (32.0 + 16.0 + 16.0 + 16.0 + 3.5) * M / (mlp_ms * 1e-3) / 1e9}
 
 
 def occupancy_extraction(kn, torch, scene, sc, occ_res, iters=5):
@@ -429,7 +442,8 @@ def main():
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (reference point for FETCH_SIZE / WRITE_SIZE counters)")
     ap.add_argument("--bucket-only", action="store_true",
-                    help="only the cfg2 eval_grouped calls (for counter runs on the radix bucketing kernels)")
+                    help="only the cfg2 eval_grouped calls (for counter runs on the re-ordering kernels)")
+    ap.add_argument("--skewed", action="store_true", help="with --bucket-only: cfg4 (load skew) instead of cfg2")
     a = ap.parse_args()
     if a.gpus != 1:
         print("bench.py: this build runs on one GPU only (the path would shard by rays, every GPU holding the whole scene); use --gpus 1",
@@ -452,7 +466,7 @@ def main():
         torch.cuda.synchronize()
         del src_buf, dst_buf
     if a.bucket_only:
-        r = isolated_mlp(kn, torch, a.wdtype or "f16", iters=4, layered=False)
+        r = isolated_mlp(kn, torch, a.wdtype or "f16", iters=4, skewed=a.skewed, layered=False)
         print(json.dumps({"isolated_mlp": r}))
         return
     if a.wave:

@@ -14,7 +14,7 @@ OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libkilonerf_hip.so")
 PEAKS_LIB = os.path.join(HERE, "libkn_peaks.so")
 PEAKS_SOURCE = "kn_peaks.hip"
-SOURCES = ["kn_api.hip", "kn_bucket.hip", "kn_group.hip", "kn_mlp_f32.hip", "kn_mlp_mfma.hip", "kn_render.hip"]
+SOURCES = ["kn_api.hip", "kn_bucket.hip", "kn_group.hip", "kn_mlp_f32.hip", "kn_mlp_mfma.hip", "kn_render.hip", "kn_reorder.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-fPIC", "-std=c++17", "-ffp-contract=off", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-mllvm", "-amdgpu-mfma-vgpr-form=1",
          "-I", INCLUDE, "-I", CSRC]

@@ -51,6 +51,7 @@ static int static_scratch_address(int dev, void **out)
     }
     if (!g_device_configured[dev]) {
         KN_TRY(kn_group_configure());
+        KN_TRY(kn_reorder_configure());
         g_device_configured[dev] = true;
     }
     *out = g_scratch_ptr[dev];
@@ -577,9 +578,16 @@ int kn_mlp_launch(const kn_scene *sc, hipStream_t st, const KnSampleSrc &src, co
     return kn_mlp_mfma_launch(sc, st, src, b, max_tiles, sigma, rgb);
 }
 
-static int64_t eval_ws_bytes(const kn_scene *sc, int64_t M)
+// workspace of an evaluation that sorts indices (layer-at-a-time path, static scratch entry point) ...
+static int64_t index_ws_bytes(const kn_scene *sc, int64_t M)
 {
     return kn_align_up((M > 0 ? M : 1) * 4, 256) + kn_bucket_ws_bytes(M, sc->N);
+}
+// ... and of kn_eval_grouped, which moves the samples themselves
+static int64_t eval_ws_bytes(const kn_scene *sc, int64_t M)
+{
+    const int64_t a = index_ws_bytes(sc, M), b = kn_reorder_ws_bytes(M, sc->N);
+    return a > b ? a : b;
 }
 
 extern "C" int kn_workspace_bytes(const kn_ctx *ctx, const kn_scene *sc, int64_t max_points, int64_t max_rays,
@@ -596,12 +604,31 @@ extern "C" int kn_workspace_bytes(const kn_ctx *ctx, const kn_scene *sc, int64_t
 // `timed`: stage events may be recorded (creating the events allocates; the static entry point never does)
 static int eval_grouped_impl(kn_ctx *ctx, const kn_scene *sc, hipStream_t st, const float *points, const float *dirs, int64_t M,
                              float *sigma, float *rgb, int32_t *cell_id, int32_t *counts, int32_t *perm, void *workspace,
-                             int64_t workspace_bytes, bool timed)
+                             int64_t workspace_bytes, bool timed, bool reorder)
 {
     KnCarver ws(workspace, workspace_bytes);
+    KnStageTimer tm(ctx, st, timed);
+    if (reorder && M > 0) {
+        // the samples themselves are brought into grouped order (Sec. 3.5); the kernel reads them contiguously
+        tm.begin();
+        KnBucketOut bo;
+        const uint32_t *records[2] = {nullptr, nullptr};
+        float *out4 = nullptr;
+        KN_TRY(kn_reorder_run(sc, st, points, dirs, M, kn_mlp_tile_len(sc), cell_id, counts, perm, ws, &bo, records, &out4, &tm));
+        tm.mark(KN_ST_BUCKET);
+        KnSampleSrc src{};
+        src.records = records[0];
+        src.records_dir = records[1];
+        src.out4 = out4;
+        KN_TRY(kn_mlp_launch(sc, st, src, bo, M, sigma, rgb));
+        tm.mark(KN_ST_MLP);
+        KN_TRY(kn_reorder_split_results(st, out4, M, sigma, rgb));
+        tm.mark(KN_ST_BUCKET); // the way back to the caller's order is charged to the re-ordering
+        tm.add(1, M, M, 1);
+        return KN_OK;
+    }
     int32_t *keys = ws.carve<int32_t>(M);
     if (!ws.ok()) return KN_E_WORKSPACE;
-    KnStageTimer tm(ctx, st, timed);
     tm.begin();
     const int64_t self_base = kn_knobs(ctx).radix_self_base_blocks;
     int32_t *scratch = nullptr;
@@ -635,7 +662,7 @@ extern "C" int kn_eval_grouped(kn_ctx *ctx, const kn_scene *sc, void *stream, co
     if (M > (1ll << 30)) return KN_E_UNSUPPORTED;
     if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < eval_ws_bytes(sc, M)) return KN_E_WORKSPACE;
     return eval_grouped_impl(ctx, sc, (hipStream_t)stream, points, dirs, M, sigma, rgb, cell_id, counts, perm, workspace,
-                             workspace_bytes, true);
+                             workspace_bytes, true, true);
 }
 
 // kn_eval_grouped on the library's static scratch array instead of a caller workspace: nothing is allocated, here
@@ -644,14 +671,15 @@ extern "C" int kn_eval_grouped_static(kn_ctx *ctx, const kn_scene *sc, void *str
                                       int64_t M, float *sigma, float *rgb, int32_t *cell_id, int32_t *counts, int32_t *perm)
 {
     if (!ctx || !sc || M < 0 || (M > 0 && (!points || !dirs || !sigma || !rgb))) return KN_E_INVALID_ARG;
-    if (M > (1ll << 30) || eval_ws_bytes(sc, M) > (int64_t)KN_STATIC_SCRATCH_BYTES) return KN_E_STATIC_LIMIT;
+    if (M > (1ll << 30) || index_ws_bytes(sc, M) > (int64_t)KN_STATIC_SCRATCH_BYTES) return KN_E_STATIC_LIMIT;
     int dev = -1;
     KN_HIP(hipGetDevice(&dev));
     if (dev != ctx->device || dev != sc->device) return KN_E_INVALID_ARG; // the context's device must be current
     void *ptr = ctx->static_scratch; // this device's copy of the array, looked up by kn_create
     if (!ptr) return KN_E_HIP;
+    // (indices are sorted, not the samples: the batches that fit the array are small, and so is the workspace then)
     return eval_grouped_impl(ctx, sc, (hipStream_t)stream, points, dirs, M, sigma, rgb, cell_id, counts, perm, ptr,
-                             (int64_t)KN_STATIC_SCRATCH_BYTES, false);
+                             (int64_t)KN_STATIC_SCRATCH_BYTES, false, false);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -660,7 +688,7 @@ extern "C" int kn_layered_workspace_bytes(const kn_scene *sc, int64_t max_points
 {
     if (!sc || !out_bytes || max_points < 0) return KN_E_INVALID_ARG;
     if (max_points > (1ll << 30)) return KN_E_UNSUPPORTED;
-    *out_bytes = eval_ws_bytes(sc, max_points) + kn_layered_act_bytes(sc, max_points) + 512;
+    *out_bytes = index_ws_bytes(sc, max_points) + kn_layered_act_bytes(sc, max_points) + 512;
     return KN_OK;
 }
 
@@ -670,7 +698,7 @@ extern "C" int kn_eval_grouped_layered(kn_ctx *ctx, const kn_scene *sc, void *st
     if (!ctx || !sc || M < 0 || (M > 0 && (!points || !dirs || !sigma || !rgb))) return KN_E_INVALID_ARG;
     if (M > (1ll << 30) || sc->desc.wdtype == KN_F32) return KN_E_UNSUPPORTED;
     if (!workspace || ((uintptr_t)workspace & 255) ||
-        workspace_bytes < eval_ws_bytes(sc, M) + kn_layered_act_bytes(sc, M) + 256)
+        workspace_bytes < index_ws_bytes(sc, M) + kn_layered_act_bytes(sc, M) + 256)
         return KN_E_WORKSPACE;
     hipStream_t st = (hipStream_t)stream;
     KnCarver ws(workspace, workspace_bytes);

@@ -253,6 +253,18 @@ struct KnBucketOut {
 int kn_bucket_run(hipStream_t st, int32_t *keys, int64_t M, const int32_t *M_dev, int32_t N, int32_t tile_len,
                   int32_t *user_counts, int32_t *user_offsets, int32_t *user_perm, KnCarver &ws,
                   KnBucketOut *out, bool atomics_zeroed = false, int64_t self_base_blocks = KN_RADIX_SELF_BASE_BLOCKS);
+// Physical re-ordering of a batch of points by network, for kn_eval_grouped: cell ids and keys (Eq. 6), then a stable
+// radix sort that moves the samples themselves (records[0], records[1]: see KnSampleSrc::records).  out->perm is nullptr;
+// user_ids / user_counts / user_perm (nullable) receive what kn_eval_grouped reports.  M >= 1.
+// *out4: staging array of the results, (r, g, b, sigma) per point in caller order, already zero for the points without
+// a network; the MLP kernel fills the rest (KnSampleSrc::out4), kn_reorder_split_results copies it to sigma / rgb.
+int64_t kn_reorder_ws_bytes(int64_t M, int32_t N);
+struct KnStageTimer;
+int kn_reorder_run(const kn_scene *sc, hipStream_t st, const float *points, const float *dirs, int64_t M, int32_t tile_len,
+                   int32_t *user_ids, int32_t *user_counts, int32_t *user_perm, KnCarver &ws, KnBucketOut *out,
+                   const uint32_t *records[2], float **out4, KnStageTimer *tm /* nullable: marks the end of the cell-id stage */);
+int kn_reorder_configure(); // once per device: lifts the dynamic-LDS limit of the scatter kernels
+int kn_reorder_split_results(hipStream_t st, const float *out4, int64_t M, float *sigma, float *rgb);
 // Unstable grouping of a render wave's samples (row layout: row i holds cnt[i] samples in slots i*S ..).
 // out->perm lists slot numbers group by group, in no particular order inside a group or between groups;
 // out->counts / out->offsets are not produced.
@@ -283,6 +295,10 @@ void kn_bucket_scratch(KnCarver ws, int64_t M, int32_t N, int32_t **atomics, int
 struct KnSampleSrc {
     const float *points;   // M*3 or nullptr
     const float *dirs;     // M*3 or nullptr
+    // eval_grouped after the physical re-ordering (kn_reorder_run): the samples in grouped order, 4 words each in two
+    // arrays, (x, y, z, key) and (dx, dy, dz, caller index); then the sorted list is the samples themselves and
+    // `perm` is not read
+    const uint32_t *records, *records_dir;
     const uint32_t *rec;   // per sample: ray << kbits | k   (render)
     const float *rays_o;   // R*3
     const float *rays_d;   // R*3

@@ -165,7 +165,10 @@ __global__ void __launch_bounds__(F32_WAVES *KN_WAVE) __attribute__((amdgpu_wave
     };
 
     auto descriptor = [&](int t) -> KnTile { return tiles[min(t, t_hi - 1)]; };
-    auto sample_index = [&](const KnTile &d) { return perm[d.start + min(lane, d.len - 1)]; };
+    auto sample_index = [&](const KnTile &d) {
+        const int32_t pos = d.start + min(lane, d.len - 1);
+        return src.records ? pos : perm[pos]; // re-ordered records: the sorted list holds the samples themselves
+    };
     KnTile dsc_next = descriptor(t_lo);
     int32_t idx_next = sample_index(dsc_next);
     int32_t net_cur = -1;
@@ -174,7 +177,8 @@ __global__ void __launch_bounds__(F32_WAVES *KN_WAVE) __attribute__((amdgpu_wave
         const KnTile tl = dsc_next;
         const int32_t idx = idx_next;
         float x, y, z, dx, dy, dz, dscale;
-        kn_load_sample(src, idx, x, y, z, dx, dy, dz, dscale);
+        int32_t out_idx;
+        kn_load_sample(src, idx, x, y, z, dx, dy, dz, dscale, out_idx);
         dsc_next = descriptor(t + 1);
         idx_next = sample_index(dsc_next);
         if (tl.net != net_cur) { // uniform
@@ -282,11 +286,11 @@ __global__ void __launch_bounds__(F32_WAVES *KN_WAVE) __attribute__((amdgpu_wave
 #pragma unroll
             for (int c = 0; c < 3; ++c) col[c] = 1.0f / (1.0f + expf(-out[c]));
             if (src.out4) {
-                *(f4 *)(src.out4 + 4 * (int64_t)idx) = (f4){col[0], col[1], col[2], sg};
+                *(f4 *)(src.out4 + 4 * (int64_t)out_idx) = (f4){col[0], col[1], col[2], sg};
             } else {
-                sigma[idx] = sg;
+                sigma[out_idx] = sg;
 #pragma unroll
-                for (int c = 0; c < 3; ++c) rgb[3 * (int64_t)idx + c] = col[c];
+                for (int c = 0; c < 3; ++c) rgb[3 * (int64_t)out_idx + c] = col[c];
             }
         }
     }

@@ -312,17 +312,27 @@ __global__ void __launch_bounds__(WAVES *KN_WAVE) __attribute__((amdgpu_waves_pe
     // issued one tile ahead of the next, so a level's operands have arrived by the time the following level
     // needs them: tile t is computed while the last level of tile t+1, the record of t+2, the index of t+3 and
     // the descriptor of t+4 are in flight.
-    const bool from_rays = src.points == nullptr;
+    const bool from_rays = src.points == nullptr && src.records == nullptr;
+    const bool from_records = src.records != nullptr; // the sorted list holds the samples themselves: no index to follow
     auto descriptor = [&](int t) -> KnTile { return tiles[min(t, t_hi - 1)]; };
     auto sorted_pos = [&](const KnTile &d) { return d.start + min(lane, d.len - 1); };
+    auto sample_at = [&](const KnTile &d) -> int32_t { return from_records ? sorted_pos(d) : perm[sorted_pos(d)]; };
     auto load_record = [&](int32_t i) -> uint32_t { return from_rays ? src.rec[i] : 0u; };
-    struct Raw { float a[3], b[3]; }; // eval: point, direction; render: ray origin, ray direction
+    struct Raw { float a[3], b[3]; int32_t out; }; // eval: point, direction; render: ray origin, ray direction; where the result goes
     auto load_raw = [&](int32_t i, uint32_t r) -> Raw {
         Raw q;
+        if (from_records) { // uniform
+            const u4 h0 = *(const u4 *)(src.records + 4 * (int64_t)i), h1 = *(const u4 *)(src.records_dir + 4 * (int64_t)i);
+#pragma unroll
+            for (int c = 0; c < 3; ++c) { q.a[c] = __uint_as_float(h0[c]); q.b[c] = __uint_as_float(h1[c]); }
+            q.out = (int32_t)h1[3];
+            return q;
+        }
         const float *pa = from_rays ? src.rays_o + 3 * (int64_t)(r >> src.kbits) : src.points + 3 * (int64_t)i;
         const float *pb = from_rays ? src.rays_d + 3 * (int64_t)(r >> src.kbits) : src.dirs + 3 * (int64_t)i;
 #pragma unroll
         for (int c = 0; c < 3; ++c) { q.a[c] = pa[c]; q.b[c] = pb[c]; }
+        q.out = i;
         return q;
     };
     auto finish = [&](const Raw &q, uint32_t r, float &x, float &y, float &z, float &dscale) {
@@ -342,7 +352,7 @@ __global__ void __launch_bounds__(WAVES *KN_WAVE) __attribute__((amdgpu_waves_pe
         else { x = q.a[0]; y = q.a[1]; z = q.a[2]; }
     };
     KnTile dsc0 = descriptor(t_lo), dsc1 = descriptor(t_lo + 1), dsc2 = descriptor(t_lo + 2), dsc3 = descriptor(t_lo + 3);
-    int32_t idx0 = perm[sorted_pos(dsc0)], idx1 = perm[sorted_pos(dsc1)], idx2 = perm[sorted_pos(dsc2)];
+    int32_t idx0 = sample_at(dsc0), idx1 = sample_at(dsc1), idx2 = sample_at(dsc2);
     uint32_t rec0 = load_record(idx0), rec1 = load_record(idx1);
     Raw raw0 = load_raw(idx0, rec0);
     int32_t net_cur = -1;
@@ -386,7 +396,7 @@ __global__ void __launch_bounds__(WAVES *KN_WAVE) __attribute__((amdgpu_waves_pe
             net_cur = tl.net;
         }
         const bool active = lane < tl.len;
-        const int32_t idx = idx0;
+        const int32_t idx = raw0.out;
         float nx, ny, nz, dscale;
         finish(raw0, rec0, nx, ny, nz, dscale);
         const float ndx = raw0.b[0], ndy = raw0.b[1], ndz = raw0.b[2];
@@ -398,7 +408,7 @@ __global__ void __launch_bounds__(WAVES *KN_WAVE) __attribute__((amdgpu_waves_pe
         rec1 = load_record(idx2);
         idx0 = idx1;
         idx1 = idx2;
-        idx2 = perm[sorted_pos(dsc3)];
+        idx2 = sample_at(dsc3);
         dsc0 = dsc1;
         dsc1 = dsc2;
         dsc2 = dsc3;
@@ -655,7 +665,8 @@ __global__ void __launch_bounds__(WAVES *KN_WAVE)
         const int32_t idx = perm[tl.start + min(lane, tl.len - 1)];
         float x, y, z, dx, dy, dz;
         float dscale; // (explicit points: always 1)
-        kn_load_sample(src, idx, x, y, z, dx, dy, dz, dscale);
+        int32_t out_idx; // (= idx: the layer-at-a-time path sorts indices)
+        kn_load_sample(src, idx, x, y, z, dx, dy, dz, dscale, out_idx);
         {
             const float p3[3] = {x, y, z}, d3[3] = {dx, dy, dz};
 #pragma unroll
@@ -809,7 +820,7 @@ int launch(const kn_scene *sc, hipStream_t st, const KnSampleSrc &src, const KnB
     for (int a = 0; a < 3; ++a)
         reach = fmaxf(reach, fmaxf(fabsf(sc->desc.aabb_min[a]), fabsf(sc->desc.aabb_max[a])));
     const bool wrap = !(reach * (256.0f * INV_2PI) < 250.0f);
-    const bool rays = src.points == nullptr;
+    const bool rays = src.points == nullptr && src.records == nullptr;
     const bool strat = src.strat != 0 && rays;
     if (rays && !src.dir_table) return KN_E_INVALID_ARG;
     // explicit points: the plain kernel; render: the ray's encoded direction comes from the table, midpoint or stratified lattice

@@ -218,6 +218,46 @@ def test_eval_grouped_empty_and_permutation_invariance():
     np.testing.assert_array_equal(c2, c1[p])
 
 
+@pytest.mark.parametrize("res,M,mode", [((1, 1, 1), 5_000, "mixed"),         # one network: keys 0 / 1, one pass of one bit
+                                        ((3, 5, 17), 20_000, "mixed"),       # 255 networks + "outside" = 256 keys: one pass of 8 bits
+                                        ((4, 8, 8), 12_289, "mixed"),        # 257 keys: two passes (5 + 4 bits); 3 blocks + 1 record
+                                        ((4, 8, 8), 1, "inside"), ((4, 8, 8), 4096, "inside"), ((4, 8, 8), 4097, "outside"),
+                                        ((16, 16, 16), 70_001, "skewed")])
+def test_eval_grouped_reordering_edge_cases(res, M, mode):
+    """kn_eval_grouped moves the samples themselves into grouped order (a radix sort of 32-byte records, one or two
+    passes by the number of key bits): ids, counts and the stable permutation bit-exact, results within the bar, and
+    equal bit for bit to the evaluation that sorts indices instead (kn_eval_grouped_static)."""
+    import torch
+    sc = scene_dict(res, (-1, -1, -1), (1, 1, 1), 32, "f16", 61)
+    span = {"mixed": 1.15, "inside": 0.999, "outside": 1.0, "skewed": 1.0}[mode]
+    pts = ks.uniform_points(M, 62, lo=(-span,) * 3, hi=(span,) * 3)
+    if mode == "outside":
+        pts = pts + np.float32(3.0)
+        pts[::7] = np.nan
+    if mode == "skewed":        # nine points in ten in a twentieth of the box
+        pts[: 9 * M // 10, 0] = pts[: 9 * M // 10, 0] * np.float32(0.05)
+        pts = pts[ks.rng(63).permutation(M)]
+    dirs = ks.sphere_dirs(M, 64)
+    sel = None if M <= 20_000 else ks.rng(65).choice(M, size=5_000, replace=False)
+    dev = check_eval(sc, pts, dirs, sample=sel)
+    out = dev.eval_grouped(cuda(pts), cuda(dirs), want_aux=True)
+    ref = (torch.empty(M, dtype=torch.float32, device="cuda"), torch.empty((M, 3), dtype=torch.float32, device="cuda"))
+    aux = (torch.empty(M, dtype=torch.int32, device="cuda"), torch.empty(dev.N + 1, dtype=torch.int32, device="cuda"),
+           torch.empty(M, dtype=torch.int32, device="cuda"))
+    dev.eval_grouped_static(cuda(pts), cuda(dirs), ref, aux=aux)
+    torch.cuda.synchronize()
+    for a, b in zip(out, (*ref, *aux)):
+        assert torch.equal(a, b)
+
+
+def test_eval_grouped_reordering_with_sixteen_key_bits():
+    """32^3 networks: keys need 16 bits, two passes of 8."""
+    sc = scene_dict((32, 32, 32), (0, 0, 0), (1, 1, 1), 32, "f16", 66)
+    M = 300_007
+    pts = ks.uniform_points(M, 67, lo=(-0.01,) * 3, hi=(1.01,) * 3)
+    check_eval(sc, pts, ks.sphere_dirs(M, 68), sample=ks.rng(69).choice(M, size=4_000, replace=False))
+
+
 @pytest.mark.parametrize("wdtype,H", [("f16", 32), ("bf16", 32), ("f16", 64), ("bf16", 64)])
 def test_layer_at_a_time_equals_fused_and_oracle(wdtype, H):
     """Sec. 3.5's grouped matrix products, one launch per layer: same operands and order of operations as the fused

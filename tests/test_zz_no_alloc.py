@@ -72,17 +72,25 @@ def test_eval_grouped_static_rejects_what_its_array_cannot_hold():
                                     None) == -1
     assert L.kn_eval_grouped_static(c, None, None, None, None, 0, None, None, None, None, None) == -1
     assert L.kn_eval_grouped_static(None, h, None, None, None, 0, None, None, None, None, None) == -1
-    # the largest size that fits is accepted: find it through kn_workspace_bytes (same sizing)
+    # the largest size that fits is accepted and evaluated: found by bisection on the call's own answer
+    pts, dirs = cuda(ks.uniform_points(big, 77)), cuda(ks.sphere_dirs(big, 78))
+    sg, rgb = torch.empty(big, device="cuda"), torch.empty((big, 3), device="cuda")
+
+    def accepted(m):
+        rc = L.kn_eval_grouped_static(c, h, None, pts.data_ptr(), dirs.data_ptr(), m, sg.data_ptr(), rgb.data_ptr(), None, None, None)
+        assert rc in (0, -6), rc
+        return rc == 0
+
     lo, hi = 1, big
     while lo < hi:
         mid = (lo + hi + 1) // 2
-        if dev.workspace_bytes(max_points=mid) - 256 <= (16 << 20):
+        if accepted(mid):
             lo = mid
         else:
             hi = mid - 1
     assert 700_000 < lo < 900_000
     M = lo
-    pts, dirs = cuda(ks.uniform_points(M, 77)), cuda(ks.sphere_dirs(M, 78))
+    pts, dirs = pts[:M].contiguous(), dirs[:M].contiguous()
     out = (torch.empty(M, device="cuda"), torch.empty((M, 3), device="cuda"))
     dev.eval_grouped_static(pts, dirs, out)
     want = dev.eval_grouped(pts, dirs)
