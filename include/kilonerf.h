@@ -148,10 +148,11 @@ int kn_bucket(kn_ctx *ctx, const kn_scene *scene, void *stream, const int32_t *i
               int32_t *counts /*dev N+1, nullable*/, int32_t *offsets /*dev N+2, nullable*/,
               int32_t *perm /*dev M*/, void *workspace, int64_t workspace_bytes);
 
-/* Eq. 7: (c, sigma) = f_theta(g(x))(x, d) for M points: cell assignment, bucketing, then the
- * fused per-network MLP (encoding + 5 layers) over each bucket.  Outputs in caller order; points
- * outside the AABB get sigma = 0, rgb = 0, id = -1.  cell_id / counts / perm are optional
- * outputs as in kn_cell_ids / kn_bucket. */
+/* Eq. 7: (c, sigma) = f_theta(g(x))(x, d) for M points: cell assignment, ordering by network (Sec. 3.5: the
+ * points themselves are moved into grouped order, by a stable sort), then the fused per-network MLP (encoding +
+ * 5 layers) over each bucket.  Outputs in caller order; points outside the AABB get sigma = 0, rgb = 0,
+ * id = -1.  cell_id / counts / perm are optional outputs as in kn_cell_ids / kn_bucket.  Workspace: about 88 bytes
+ * per point (kn_workspace_bytes). */
 int kn_eval_grouped(kn_ctx *ctx, const kn_scene *scene, void *stream, const float *points /*dev M*3*/,
                     const float *dirs /*dev M*3*/, int64_t M, float *sigma /*dev M*/,
                     float *rgb /*dev M*3*/, int32_t *cell_id /*dev M, nullable*/,
@@ -164,9 +165,10 @@ int kn_eval_grouped(kn_ctx *ctx, const kn_scene *scene, void *stream, const floa
  * runs on holds until the process ends; its address on the context's device is looked up by kn_create.
  * The call allocates nothing (no hipMalloc / hipFree, no events, no library routine that allocates) and records no
  * stage timings; inputs and outputs are the caller's, as in kn_eval_grouped, and the results are the same bits.
- * The context's device must be current (KN_E_INVALID_ARG otherwise).  M is limited to what the array
- * holds: KN_E_STATIC_LIMIT when kn_eval_grouped's workspace for M points would exceed KN_STATIC_SCRATCH_BYTES
- * (the need is about 21 bytes per point + 24 per network: roughly 800,000 points on 4,096 networks).
+ * The context's device must be current (KN_E_INVALID_ARG otherwise).  To make the array go further this call sorts
+ * indices instead of moving the points (slower per point on large batches, the same results), which takes about
+ * 21 bytes per point + 24 per network; M is limited to what the array then holds (roughly 800,000 points on 4,096
+ * networks): KN_E_STATIC_LIMIT beyond.
  * All calls on one GPU share the one array, whose contents do not outlive a call: calls that overlap on a GPU
  * (different streams or threads) race; calls on one stream are ordered as usual. */
 #define KN_STATIC_SCRATCH_BYTES (16u << 20)
