@@ -176,6 +176,27 @@ def isolated_mlp(kn, torch, wdtype, iters=10, skewed=False, layered=True):
     kn.profile_enable(False)
     mlp_ms_g = prof_g["ms_mlp"] / iters
     tflops_g = FLOP_PER_SAMPLE[sc["hidden"]] * M / (mlp_ms_g * 1e-3) / 1e12
+    # the stage call on its own: kn_bucket on the same points' ids (a stable sort of (key, index) pairs)
+    # (outputs and workspace allocated once, the library called directly: the host side must not be what is timed)
+    b_counts = torch.empty(scene.N + 1, dtype=torch.int32, device="cuda")
+    b_offsets = torch.empty(scene.N + 2, dtype=torch.int32, device="cuda")
+    b_perm = torch.empty(M, dtype=torch.int32, device="cuda")
+    b_ws = torch.empty(scene.workspace_bytes(max_points=M), dtype=torch.uint8, device="cuda")
+    ctx_h = kn.default_context().h
+    stream = torch.cuda.current_stream().cuda_stream
+
+    def bucket_calls(n):
+        for _ in range(n):
+            rc = scene.L.kn_bucket(ctx_h, scene.h, stream, ids.data_ptr(), M, b_counts.data_ptr(), b_offsets.data_ptr(), b_perm.data_ptr(),
+                                   b_ws.data_ptr(), b_ws.numel())
+            assert rc == 0, rc
+    bucket_calls(2)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    bucket_calls(4 * iters)
+    torch.cuda.synchronize()
+    bucket_stage_ms = (time.perf_counter() - t0) * 1e3 / (4 * iters)
+    del b_ws, b_perm
     mlp_ms_l = None
     if layered:
         # the comparison point of Sec. 3.5: the same networks one layer at a time (grouped matrix products,
@@ -226,6 +247,12 @@ def isolated_mlp(kn, torch, wdtype, iters=10, skewed=False, layered=True):
                                              "hbm_copy_gbps"),
             "bucket_gbps_algorithmic": 92.0 * M / t_bucket / 1e9,
             "bucket_gbps_at_16_bytes_per_key": 16.0 * M / t_bucket / 1e9,
+            # kn_bucket alone (index sort): key read by the count and by the scatter of each of the two passes, key and
+            # index written by each scatter, index read by the second: 16 B per key and pass pair as in the design doc
+            "kn_bucket_stage": with_measured({"kernel": "kn_bucket: k_ids_to_keys + (k_key_hist + k_digit_scan + k_index_scatter) x2 + k_offsets_tiles",
+                                              "bound": "hbm", "ms": bucket_stage_ms, "achieved": 16.0 * M / (bucket_stage_ms * 1e-3) / 1e9,
+                                              "peak": PEAK_HBM / 1e9, "unit": "GB/s", "frac": 16.0 * M / (bucket_stage_ms * 1e-3) / PEAK_HBM,
+                                              "traffic": None}, "hbm_copy_gbps"),
             "mlp_hbm_gbps_algorithmic": (32.0 + 16.0 + 16.0 + 16.0 + 3.5) * M / (mlp_ms * 1e-3) / 1e9}
 
 

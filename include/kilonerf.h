@@ -167,7 +167,7 @@ int kn_eval_grouped(kn_ctx *ctx, const kn_scene *scene, void *stream, const floa
  * stage timings; inputs and outputs are the caller's, as in kn_eval_grouped, and the results are the same bits.
  * The context's device must be current (KN_E_INVALID_ARG otherwise).  To make the array go further this call sorts
  * indices instead of moving the points (slower per point on large batches, the same results), which takes about
- * 21 bytes per point + 24 per network; M is limited to what the array then holds (roughly 800,000 points on 4,096
+ * 17 bytes per point + 24 per network; M is limited to what the array then holds (roughly 980,000 points on 4,096
  * networks): KN_E_STATIC_LIMIT beyond.
  * All calls on one GPU share the one array, whose contents do not outlive a call: calls that overlap on a GPU
  * (different streams or threads) race; calls on one stream are ordered as usual. */
@@ -286,11 +286,8 @@ int kn_set_render_params(kn_ctx *ctx, int32_t first_wave_samples, int32_t slots_
  *   KN_OPT_GROUP_FUSED_MAX          largest number of networks whose per-network counters kn_render's grouping keeps
  *                                   in LDS one by one (default 8192; 0 is a valid value here: always the hash path;
  *                                   negative restores the default)
- *   KN_OPT_GROUP_HASH_SLOTS         slots of the LDS hash table used beyond that (power of two, 16 .. 2048)
- *   KN_OPT_RADIX_SELF_BASE_BLOCKS   largest number of 4096-key blocks for which the stable bucketing derives its
- *                                   scatter offsets from per-group sums; beyond, the digit table is scanned
- *                                   (default 8192 blocks = 33.5 M keys) */
-typedef enum { KN_OPT_GROUP_FUSED_MAX = 1, KN_OPT_GROUP_HASH_SLOTS = 2, KN_OPT_RADIX_SELF_BASE_BLOCKS = 3 } kn_option;
+ *   KN_OPT_GROUP_HASH_SLOTS         slots of the LDS hash table used beyond that (power of two, 16 .. 2048) */
+typedef enum { KN_OPT_GROUP_FUSED_MAX = 1, KN_OPT_GROUP_HASH_SLOTS = 2 } kn_option;
 int kn_set_option(kn_ctx *ctx, int32_t option, int64_t value);
 
 /* Per-stage device time of kn_render / kn_eval_grouped on this context, measured with HIP events recorded on

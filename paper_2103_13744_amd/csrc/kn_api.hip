@@ -9,8 +9,7 @@
 
 thread_local int g_kn_last_hip_error = 0;
 
-int kn_cell_keys(const kn_scene *sc, hipStream_t st, const float *points, int64_t M, int32_t *ids, int32_t *keys,
-                 int32_t *zero, int64_t n_zero);
+int kn_cell_keys(const kn_scene *sc, hipStream_t st, const float *points, int64_t M, int32_t *ids, int32_t *keys);
 int64_t kn_render_ws_bytes(const kn_scene *sc, int64_t R, int32_t slots_per_ray);
 int kn_mlp_f32_launch(const kn_scene *sc, hipStream_t st, const KnSampleSrc &src, const KnBucketOut &b, int64_t max_tiles,
                       float *sigma, float *rgb);
@@ -62,8 +61,7 @@ KnKnobs kn_knobs(const kn_ctx *c)
 {
     kn_ctx *ctx = const_cast<kn_ctx *>(c); // (the mutex)
     std::lock_guard<std::mutex> lock(ctx->mutex);
-    return KnKnobs{ctx->first_wave_samples, ctx->slots_per_ray, ctx->wave_growth, ctx->group_fused_max, ctx->group_hash_slots,
-                   ctx->radix_self_base_blocks};
+    return KnKnobs{ctx->first_wave_samples, ctx->slots_per_ray, ctx->wave_growth, ctx->group_fused_max, ctx->group_hash_slots};
 }
 
 // (ctx->mutex held)
@@ -181,10 +179,6 @@ extern "C" int kn_set_option(kn_ctx *ctx, int32_t option, int64_t value)
         if (value > 0 && (value < 16 || value > KN_GROUP_HASH_SLOTS_MAX || (value & (value - 1)) != 0)) return KN_E_INVALID_ARG;
         ctx->group_hash_slots = value <= 0 ? KN_GROUP_HASH_SLOTS_MAX : (int32_t)value;
         return KN_OK;
-    case KN_OPT_RADIX_SELF_BASE_BLOCKS:
-        if (value > KN_RADIX_SELF_BASE_BLOCKS) return KN_E_INVALID_ARG;
-        ctx->radix_self_base_blocks = value <= 0 ? KN_RADIX_SELF_BASE_BLOCKS : value;
-        return KN_OK;
     default: return KN_E_INVALID_ARG;
     }
 }
@@ -209,7 +203,6 @@ extern "C" int kn_create(kn_ctx **out, int device_index)
     ctx->wave_growth = KN_DEFAULT_GROWTH;
     ctx->group_fused_max = KN_GROUP_FUSED_MAX_BINS;
     ctx->group_hash_slots = KN_GROUP_HASH_SLOTS_MAX;
-    ctx->radix_self_base_blocks = KN_RADIX_SELF_BASE_BLOCKS;
     ctx->profile = kn_profile{};
     ctx->profile_on = false;
     ctx->only_stage = KN_ST_NONE;
@@ -630,15 +623,10 @@ static int eval_grouped_impl(kn_ctx *ctx, const kn_scene *sc, hipStream_t st, co
     int32_t *keys = ws.carve<int32_t>(M);
     if (!ws.ok()) return KN_E_WORKSPACE;
     tm.begin();
-    const int64_t self_base = kn_knobs(ctx).radix_self_base_blocks;
-    int32_t *scratch = nullptr;
-    int64_t n_scratch = 0;
-    kn_bucket_scratch(ws, M, sc->N, &scratch, &n_scratch);
-    KN_TRY(kn_cell_keys(sc, st, points, M, cell_id, keys, scratch, scratch ? n_scratch : 0));
+    KN_TRY(kn_cell_keys(sc, st, points, M, cell_id, keys));
     tm.mark(KN_ST_CELL);
     KnBucketOut bo;
-    KN_TRY(kn_bucket_run(st, keys, M, nullptr, sc->N, kn_mlp_tile_len(sc), counts, nullptr, perm, ws, &bo, scratch != nullptr,
-                         self_base));
+    KN_TRY(kn_bucket_run(st, keys, M, sc->N, kn_mlp_tile_len(sc), counts, nullptr, perm, ws, &bo));
     if (M == 0) return KN_OK;
     tm.mark(KN_ST_BUCKET);
     KnSampleSrc src{};
@@ -707,15 +695,11 @@ extern "C" int kn_eval_grouped_layered(kn_ctx *ctx, const kn_scene *sc, void *st
     if (!ws.ok()) return KN_E_WORKSPACE;
     KnStageTimer tm(ctx, st);
     tm.begin();
-    int32_t *scratch = nullptr;
-    int64_t n_scratch = 0;
-    kn_bucket_scratch(ws, M, sc->N, &scratch, &n_scratch);
-    KN_TRY(kn_cell_keys(sc, st, points, M, nullptr, keys, scratch, scratch ? n_scratch : 0));
+    KN_TRY(kn_cell_keys(sc, st, points, M, nullptr, keys));
     tm.mark(KN_ST_CELL);
     KnBucketOut bo;
     const int tile_len = kn_mlp_tile_len(sc);
-    KN_TRY(kn_bucket_run(st, keys, M, nullptr, sc->N, tile_len, nullptr, nullptr, nullptr, ws, &bo, scratch != nullptr,
-                         kn_knobs(ctx).radix_self_base_blocks));
+    KN_TRY(kn_bucket_run(st, keys, M, sc->N, tile_len, nullptr, nullptr, nullptr, ws, &bo));
     if (M == 0) return KN_OK;
     tm.mark(KN_ST_BUCKET);
     KnSampleSrc src{};

@@ -46,7 +46,6 @@ constexpr int KN_N_EVENTS = 1024;
 constexpr int KN_DEFAULT_SLOTS = 128, KN_DEFAULT_GROWTH = 32;
 constexpr int KN_GROUP_FUSED_MAX_BINS = 8192; // largest grid whose histogram the grouping's fill pass scans by itself
 constexpr int KN_GROUP_HASH_SLOTS_MAX = 2048; // larger grids: LDS table of the bins a workgroup meets (power of two)
-constexpr int64_t KN_RADIX_SELF_BASE_BLOCKS = 8192; // beyond this the (digit, block) table of a radix pass is scanned
 
 // Everything mutable lives here (the scene is immutable once created).  `mutex` guards all fields below `device`.
 struct kn_ctx {
@@ -56,7 +55,6 @@ struct kn_ctx {
     int32_t first_wave_samples, slots_per_ray, wave_growth;
     // limits that decide between code paths (kn_set_option)
     int32_t group_fused_max, group_hash_slots;
-    int64_t radix_self_base_blocks;
     // stage timing: an event ring; intervals are settled (one stream synchronise, then hipEventElapsedTime for
     // each recorded interval) only when the ring is full, when another stream starts recording, or when the
     // totals are read
@@ -77,7 +75,6 @@ struct kn_ctx {
 // snapshot of the schedule and limits, taken under the mutex at the start of a call
 struct KnKnobs {
     int32_t first_wave_samples, slots_per_ray, wave_growth, group_fused_max, group_hash_slots;
-    int64_t radix_self_base_blocks;
 };
 KnKnobs kn_knobs(const kn_ctx *ctx);
 
@@ -246,13 +243,10 @@ struct KnBucketOut {
     const int32_t *n_tiles; // device scalar
 };
 
-// Sorts `keys` (values in [0, N], N = outside/unused) stably, fills perm/counts/offsets/tiles in
-// workspace memory (or the user's buffers where given).  keys may be overwritten.  If M_dev is
-// given, M is only an upper bound (grid and workspace sizing) and *M_dev the real count.
-// With atomics_zeroed the caller has already cleared the scratch counters that kn_bucket_scratch reports.
-int kn_bucket_run(hipStream_t st, int32_t *keys, int64_t M, const int32_t *M_dev, int32_t N, int32_t tile_len,
-                  int32_t *user_counts, int32_t *user_offsets, int32_t *user_perm, KnCarver &ws,
-                  KnBucketOut *out, bool atomics_zeroed = false, int64_t self_base_blocks = KN_RADIX_SELF_BASE_BLOCKS);
+// Sorts `keys` (values in [0, N], N = outside/unused) stably (kn_reorder.hip), fills perm/counts/offsets/tiles in
+// workspace memory (or the user's buffers where given).  keys is overwritten.
+int kn_bucket_run(hipStream_t st, int32_t *keys, int64_t M, int32_t N, int32_t tile_len, int32_t *user_counts, int32_t *user_offsets,
+                  int32_t *user_perm, KnCarver &ws, KnBucketOut *out);
 // Physical re-ordering of a batch of points by network, for kn_eval_grouped: cell ids and keys (Eq. 6), then a stable
 // radix sort that moves the samples themselves (records[0], records[1]: see KnSampleSrc::records).  out->perm is nullptr;
 // user_ids / user_counts / user_perm (nullable) receive what kn_eval_grouped reports.  M >= 1.
@@ -286,10 +280,6 @@ void kn_group_carve(KnCarver &ws, int64_t slots, int32_t N, KnGroupWs *w);
 int kn_group_run(hipStream_t st, const KnKnobs &knobs, const int32_t *row_keys, const int32_t *cnt, const int32_t *ctl,
                  int64_t max_rows, int32_t N, int32_t tile_len, const KnGroupWs &w, KnBucketOut *out);
 
-// The scratch counters (to be zero before the sort) that kn_bucket_run will carve from `ws` when it
-// is called with a carver in this same state, so that a caller's own kernel can clear them.
-void kn_bucket_scratch(KnCarver ws, int64_t M, int32_t N, int32_t **atomics, int64_t *n_atomics);
-
 // Sample source of the grouped MLP kernels: either explicit points/dirs (eval_grouped) or the
 // packed (ray, k) records of a render wave.
 struct KnSampleSrc {
@@ -321,9 +311,6 @@ int kn_mlp_pack_weights(kn_scene *sc, hipStream_t st);
 int kn_mlp_tile_len(const kn_scene *sc);
 
 int kn_fill_i32(hipStream_t st, int32_t *p, int64_t n, int32_t v);
-int kn_exclusive_scan_i32(hipStream_t st, const int32_t *in, int32_t *out, int64_t n, int32_t *tmp /* kn_scan_tmp_len(n) */,
-                          int32_t *total /*dev, nullable*/);
-int64_t kn_scan_tmp_len(int64_t n);
 
 // Optional per-stage timing with HIP events on the caller's stream (see kn_profile in the header).
 // begin() records a start event, mark(stage) an event that closes an interval charged to `stage`.

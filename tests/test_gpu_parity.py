@@ -574,32 +574,19 @@ def test_render_large_grid_code_paths():
     forced.close()
 
 
-def test_bucket_with_a_scanned_digit_table():
-    """Beyond 8,192 blocks of 4,096 keys the radix passes scan their (digit, block) table instead of deriving offsets
-    from per-group sums; a context with that limit lowered takes the path on a small input.  Same counts, offsets and
-    permutation as the oracle, for one and for two passes."""
-    import paper_2103_13744_amd as kn
-    small = kn.Context()
-    small.set_option(kn.OPT_RADIX_SELF_BASE_BLOCKS, 3)
-    for res, M in (((3, 4, 5), 50_001), ((16, 16, 16), 300_017), ((16, 16, 16), 4096 * 3)):   # the last: exactly at the limit
+def test_bucket_over_more_blocks_than_one_scan_step():
+    """The per-digit scan of the (digit, block) count table takes 1,024 blocks of 4,096 keys at a time: 5 M keys need two
+    steps.  One pass (20 networks) and two (4,096).  Same counts, offsets and permutation as the oracle."""
+    M = 5_000_011
+    for res in ((5, 2, 2), (16, 16, 16)):
         N = int(np.prod(res))
         dev, _ = make_pair(scene_dict(res, (0, 0, 0), (1, 1, 1), 32, "f32", 1))
-        ids = ks.rng(29 + M).integers(-1, N, size=M).astype(np.int32)
+        ids = ks.rng(29 + N).integers(-1, N, size=M).astype(np.int32)
         c, o, p = oracle.bucket(ids, N)
-        for ctx in (small, None):
-            counts, offsets, perm = dev.bucket(cuda(ids), ctx=ctx)
-            np.testing.assert_array_equal(counts.cpu().numpy(), c)
-            np.testing.assert_array_equal(offsets.cpu().numpy(), o)
-            np.testing.assert_array_equal(perm.cpu().numpy(), p)
-    # and through eval_grouped
-    sc = scene_dict((4, 4, 4), (0, 0, 0), (1, 1, 1), 32, "f16", 9)
-    dev, _ = make_pair(sc)
-    pts, dirs = cuda(ks.uniform_points(40_000, 1)), cuda(ks.sphere_dirs(40_000, 2))
-    a = dev.eval_grouped(pts, dirs, want_aux=True)
-    b = dev.eval_grouped(pts, dirs, want_aux=True, ctx=small)
-    for x, y in zip(a, b):
-        np.testing.assert_array_equal(x.cpu().numpy(), y.cpu().numpy())
-    small.close()
+        counts, offsets, perm = dev.bucket(cuda(ids))
+        np.testing.assert_array_equal(counts.cpu().numpy(), c)
+        np.testing.assert_array_equal(offsets.cpu().numpy(), o)
+        np.testing.assert_array_equal(perm.cpu().numpy(), p)
 
 
 def test_two_contexts_with_different_schedules_from_two_threads():

@@ -88,7 +88,7 @@ def test_eval_grouped_static_rejects_what_its_array_cannot_hold():
             lo = mid
         else:
             hi = mid - 1
-    assert 700_000 < lo < 900_000
+    assert 900_000 < lo < 1_050_000
     M = lo
     pts, dirs = pts[:M].contiguous(), dirs[:M].contiguous()
     out = (torch.empty(M, device="cuda"), torch.empty((M, 3), device="cuda"))
