@@ -234,10 +234,13 @@ template <bool BF> __device__ __forceinline__ u4 encode_direction(float rev, u4 
 // H = 64, two wavefronts per SIMD (the matrix-core operands are read straight from the register file either way).
 // STRAT (render with stratified sampling): the lattice points sit at their drawn offsets and the density is
 // scaled by delta_k / step on the way out (see KnSampleSrc).
-// DIRTAB (render): gamma(d) is the same for every sample of a ray, so the render's set-up kernel encodes it once
-// per ray, already in operand order (KnSampleSrc::dir_table), and a lane fetches its 16 bytes instead of computing
-// them (a sixth of the kernel's vector instructions).
-template <int H, bool BF, int WAVES, bool WRAP, bool STRAT, bool DIRTAB>
+// SRC: where the samples come from (a compile-time choice: the width-64 kernel has no register to spare for the
+// paths it does not take).  SRC_RAYS (render): lattice points rebuilt from packed (ray, k) records; gamma(d) is the
+// same for every sample of a ray, so the render's set-up kernel encodes it once per ray, already in operand order
+// (KnSampleSrc::dir_table), and a lane fetches its 16 bytes instead of computing them.  SRC_POINTS: the caller's
+// arrays through the sorted index list `perm`.  SRC_RECORDS: the re-ordered samples themselves (`perm` is not read).
+enum { SRC_RAYS = 0, SRC_POINTS = 1, SRC_RECORDS = 2 };
+template <int H, bool BF, int WAVES, bool WRAP, bool STRAT, int SRC>
 __global__ void __launch_bounds__(WAVES *KN_WAVE) __attribute__((amdgpu_waves_per_eu(H == 32 ? 3 : 2, H == 32 ? 3 : 2)))
     k_mlp_mfma(const uint16_t *__restrict__ packed, KnSampleSrc src, const int32_t *__restrict__ perm,
                const KnTile *__restrict__ tiles, const int32_t *__restrict__ n_tiles, float *__restrict__ sigma,
@@ -312,27 +315,32 @@ __global__ void __launch_bounds__(WAVES *KN_WAVE) __attribute__((amdgpu_waves_pe
     // issued one tile ahead of the next, so a level's operands have arrived by the time the following level
     // needs them: tile t is computed while the last level of tile t+1, the record of t+2, the index of t+3 and
     // the descriptor of t+4 are in flight.
-    const bool from_rays = src.points == nullptr && src.records == nullptr;
-    const bool from_records = src.records != nullptr; // the sorted list holds the samples themselves: no index to follow
+    constexpr bool from_rays = SRC == SRC_RAYS, from_records = SRC == SRC_RECORDS, DIRTAB = SRC == SRC_RAYS;
     auto descriptor = [&](int t) -> KnTile { return tiles[min(t, t_hi - 1)]; };
     auto sorted_pos = [&](const KnTile &d) { return d.start + min(lane, d.len - 1); };
-    auto sample_at = [&](const KnTile &d) -> int32_t { return from_records ? sorted_pos(d) : perm[sorted_pos(d)]; };
-    auto load_record = [&](int32_t i) -> uint32_t { return from_rays ? src.rec[i] : 0u; };
+    auto sample_at = [&](const KnTile &d) -> int32_t {
+        if constexpr (from_records) return sorted_pos(d);
+        else return perm[sorted_pos(d)];
+    };
+    auto load_record = [&](int32_t i) -> uint32_t {
+        if constexpr (from_rays) return src.rec[i];
+        else return 0u;
+    };
     struct Raw { float a[3], b[3]; int32_t out; }; // eval: point, direction; render: ray origin, ray direction; where the result goes
     auto load_raw = [&](int32_t i, uint32_t r) -> Raw {
         Raw q;
-        if (from_records) { // uniform
+        if constexpr (from_records) {
             const u4 h0 = *(const u4 *)(src.records + 4 * (int64_t)i), h1 = *(const u4 *)(src.records_dir + 4 * (int64_t)i);
 #pragma unroll
             for (int c = 0; c < 3; ++c) { q.a[c] = __uint_as_float(h0[c]); q.b[c] = __uint_as_float(h1[c]); }
             q.out = (int32_t)h1[3];
-            return q;
-        }
-        const float *pa = from_rays ? src.rays_o + 3 * (int64_t)(r >> src.kbits) : src.points + 3 * (int64_t)i;
-        const float *pb = from_rays ? src.rays_d + 3 * (int64_t)(r >> src.kbits) : src.dirs + 3 * (int64_t)i;
+        } else {
+            const float *pa = from_rays ? src.rays_o + 3 * (int64_t)(r >> src.kbits) : src.points + 3 * (int64_t)i;
+            const float *pb = from_rays ? src.rays_d + 3 * (int64_t)(r >> src.kbits) : src.dirs + 3 * (int64_t)i;
 #pragma unroll
-        for (int c = 0; c < 3; ++c) { q.a[c] = pa[c]; q.b[c] = pb[c]; }
-        q.out = i;
+            for (int c = 0; c < 3; ++c) { q.a[c] = pa[c]; q.b[c] = pb[c]; }
+            q.out = i;
+        }
         return q;
     };
     auto finish = [&](const Raw &q, uint32_t r, float &x, float &y, float &z, float &dscale) {
@@ -346,7 +354,7 @@ __global__ void __launch_bounds__(WAVES *KN_WAVE) __attribute__((amdgpu_waves_pe
             y = fmaf(t0, q.b[1], q.a[1]);
             z = fmaf(t0, q.b[2], q.a[2]);
             dscale = (t1 - t0) / src.step;
-        } else if (from_rays)
+        } else if constexpr (from_rays)
             kn_lattice_point(q.a[0], q.a[1], q.a[2], q.b[0], q.b[1], q.b[2], src.t_near, src.step,
                              (int32_t)(r & ((1u << src.kbits) - 1u)), x, y, z);
         else { x = q.a[0]; y = q.a[1]; z = q.a[2]; }
@@ -823,10 +831,12 @@ int launch(const kn_scene *sc, hipStream_t st, const KnSampleSrc &src, const KnB
     const bool rays = src.points == nullptr && src.records == nullptr;
     const bool strat = src.strat != 0 && rays;
     if (rays && !src.dir_table) return KN_E_INVALID_ARG;
-    // explicit points: the plain kernel; render: the ray's encoded direction comes from the table, midpoint or stratified lattice
-    auto kernel = !rays ? (wrap ? k_mlp_mfma<H, BF, WAVES, true, false, false> : k_mlp_mfma<H, BF, WAVES, false, false, false>)
-                  : wrap ? (strat ? k_mlp_mfma<H, BF, WAVES, true, true, true> : k_mlp_mfma<H, BF, WAVES, true, false, true>)
-                         : (strat ? k_mlp_mfma<H, BF, WAVES, false, true, true> : k_mlp_mfma<H, BF, WAVES, false, false, true>);
+    // render: the ray's encoded direction comes from the table, midpoint or stratified lattice; else explicit points,
+    // through the index list or re-ordered
+    auto kernel = src.records ? (wrap ? k_mlp_mfma<H, BF, WAVES, true, false, SRC_RECORDS> : k_mlp_mfma<H, BF, WAVES, false, false, SRC_RECORDS>)
+                  : !rays     ? (wrap ? k_mlp_mfma<H, BF, WAVES, true, false, SRC_POINTS> : k_mlp_mfma<H, BF, WAVES, false, false, SRC_POINTS>)
+                  : wrap      ? (strat ? k_mlp_mfma<H, BF, WAVES, true, true, SRC_RAYS> : k_mlp_mfma<H, BF, WAVES, true, false, SRC_RAYS>)
+                              : (strat ? k_mlp_mfma<H, BF, WAVES, false, true, SRC_RAYS> : k_mlp_mfma<H, BF, WAVES, false, false, SRC_RAYS>);
     hipLaunchKernelGGL(kernel, dim3((unsigned)blocks), dim3(WAVES * KN_WAVE), 0, st, (const uint16_t *)sc->packed_w, src, b.perm,
                        b.tiles, b.n_tiles, sigma, rgb);
     KN_CHECK_LAUNCH();
