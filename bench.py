@@ -248,7 +248,7 @@ def isolated_mlp(kn, torch, wdtype, iters=10, skewed=False, layered=True):
             "bucket_gbps_algorithmic": 92.0 * M / t_bucket / 1e9,
             "bucket_gbps_at_16_bytes_per_key": 16.0 * M / t_bucket / 1e9,
             # kn_bucket alone (index sort): key read by the count and by the scatter of each of the two passes, key and
-            # index written by each scatter, index read by the second: 16 B per key and pass pair as in the design doc
+            # index written by each scatter, index read by the second: counted as 16 B per key
             "kn_bucket_stage": with_measured({"kernel": "kn_bucket: k_ids_to_keys + (k_key_hist + k_digit_scan + k_index_scatter) x2 + k_offsets_tiles",
                                               "bound": "hbm", "ms": bucket_stage_ms, "achieved": 16.0 * M / (bucket_stage_ms * 1e-3) / 1e9,
                                               "peak": PEAK_HBM / 1e9, "unit": "GB/s", "frac": 16.0 * M / (bucket_stage_ms * 1e-3) / PEAK_HBM,
