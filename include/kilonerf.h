@@ -308,7 +308,9 @@ typedef struct {
 } kn_profile;
 /* on: 0 = off, 1 = every stage, 2 = only the grouped-MLP kernel, 3 = only the marching kernel (fewer events on
  * the stream: less disturbance of the run that is being timed; mlp_samples / bucket_keys / calls are not
- * gathered in modes 2 and 3, because reading them back would make kn_render wait for the frame) */
+ * gathered in modes 2 and 3, because reading them back would make kn_render wait for the frame).  Modes 1 and 3
+ * time the interval between two events recorded on the stream (launch gaps included); in mode 2 the events take the
+ * start and stop time stamps of the kernel's own dispatch, so ms_mlp is the kernel's execution time. */
 int kn_profile_enable(kn_ctx *ctx, int on);
 int kn_profile_read(kn_ctx *ctx, kn_profile *out /*host*/, int reset);
 

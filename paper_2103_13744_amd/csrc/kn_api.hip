@@ -12,9 +12,9 @@ thread_local int g_kn_last_hip_error = 0;
 int kn_cell_keys(const kn_scene *sc, hipStream_t st, const float *points, int64_t M, int32_t *ids, int32_t *keys);
 int64_t kn_render_ws_bytes(const kn_scene *sc, int64_t R, int32_t slots_per_ray);
 int kn_mlp_f32_launch(const kn_scene *sc, hipStream_t st, const KnSampleSrc &src, const KnBucketOut &b, int64_t max_tiles,
-                      float *sigma, float *rgb);
+                      float *sigma, float *rgb, hipEvent_t ev_start, hipEvent_t ev_stop);
 int kn_mlp_mfma_launch(const kn_scene *sc, hipStream_t st, const KnSampleSrc &src, const KnBucketOut &b, int64_t max_tiles,
-                       float *sigma, float *rgb);
+                       float *sigma, float *rgb, hipEvent_t ev_start, hipEvent_t ev_stop);
 int kn_mlp_mfma_tile_len(const kn_scene *sc);
 int kn_mlp_f32_tile_len(const kn_scene *sc);
 int kn_mlp_f32_pack_weights(kn_scene *sc, hipStream_t st);
@@ -106,10 +106,10 @@ void KnStageTimer::mark(int stage_id)
 {
     if (!on) return;
     std::lock_guard<std::mutex> lock(ctx->mutex);
+    if (ctx->only_stage == KN_ST_MLP) return; // that stage is one kernel: its launch takes the time stamps (kernel_events)
     if (ctx->only_stage != KN_ST_NONE) {
         // the mark before the stage of interest opens its interval; everything else is dropped
-        const bool opens = ctx->only_stage == KN_ST_MLP ? stage_id == KN_ST_BUCKET
-                                                        : (stage_id == KN_ST_NONE || stage_id == KN_ST_SETUP);
+        const bool opens = stage_id == KN_ST_NONE || stage_id == KN_ST_SETUP;
         const bool closes = stage_id == ctx->only_stage;
         if (!opens && !closes) return;
         if (opens) stage_id = KN_ST_NONE;
@@ -124,6 +124,18 @@ void KnStageTimer::mark(int stage_id)
     }
     ctx->event_stage[ctx->n_events] = stage_id;
     (void)hipEventRecord(ctx->events[ctx->n_events++], st);
+}
+bool KnStageTimer::kernel_events(int stage_id, hipEvent_t *start, hipEvent_t *stop)
+{
+    if (!on) return false;
+    std::lock_guard<std::mutex> lock(ctx->mutex);
+    if (ctx->only_stage != stage_id || stage_id != KN_ST_MLP) return false;
+    if (ctx->n_events + 2 > KN_N_EVENTS) (void)settle_events(ctx);
+    ctx->event_stage[ctx->n_events] = KN_ST_NONE;
+    *start = ctx->events[ctx->n_events++];
+    ctx->event_stage[ctx->n_events] = stage_id;
+    *stop = ctx->events[ctx->n_events++];
+    return true;
 }
 void KnStageTimer::add(int64_t mlp_launches, int64_t mlp_samples, int64_t bucket_keys, int64_t calls)
 {
@@ -563,12 +575,12 @@ extern "C" int kn_scene_destroy(kn_scene *sc)
 int kn_mlp_tile_len(const kn_scene *sc) { return sc->desc.wdtype == KN_F32 ? kn_mlp_f32_tile_len(sc) : kn_mlp_mfma_tile_len(sc); }
 
 int kn_mlp_launch(const kn_scene *sc, hipStream_t st, const KnSampleSrc &src, const KnBucketOut &b, int64_t M, float *sigma,
-                  float *rgb)
+                  float *rgb, hipEvent_t ev_start, hipEvent_t ev_stop)
 {
     if (M <= 0) return KN_OK;
     const int64_t max_tiles = kn_max_tiles(M, sc->N, kn_mlp_tile_len(sc));
-    if (sc->desc.wdtype == KN_F32) return kn_mlp_f32_launch(sc, st, src, b, max_tiles, sigma, rgb);
-    return kn_mlp_mfma_launch(sc, st, src, b, max_tiles, sigma, rgb);
+    if (sc->desc.wdtype == KN_F32) return kn_mlp_f32_launch(sc, st, src, b, max_tiles, sigma, rgb, ev_start, ev_stop);
+    return kn_mlp_mfma_launch(sc, st, src, b, max_tiles, sigma, rgb, ev_start, ev_stop);
 }
 
 // workspace of an evaluation that sorts indices (layer-at-a-time path, static scratch entry point) ...
@@ -613,7 +625,9 @@ static int eval_grouped_impl(kn_ctx *ctx, const kn_scene *sc, hipStream_t st, co
         src.records = records[0];
         src.records_dir = records[1];
         src.out4 = out4;
-        KN_TRY(kn_mlp_launch(sc, st, src, bo, M, sigma, rgb));
+        hipEvent_t e0 = nullptr, e1 = nullptr;
+        (void)tm.kernel_events(KN_ST_MLP, &e0, &e1);
+        KN_TRY(kn_mlp_launch(sc, st, src, bo, M, sigma, rgb, e0, e1));
         tm.mark(KN_ST_MLP);
         KN_TRY(kn_reorder_split_results(st, out4, M, sigma, rgb));
         tm.mark(KN_ST_BUCKET); // the way back to the caller's order is charged to the re-ordering

@@ -305,8 +305,10 @@ struct KnSampleSrc {
     const uint16_t *dir_table;
 };
 
+// ev_start / ev_stop (both or neither): HIP events that take the kernel's own start and stop time stamps (the
+// extended launch call: no marker packets on the stream around the kernel)
 int kn_mlp_launch(const kn_scene *sc, hipStream_t st, const KnSampleSrc &src, const KnBucketOut &b,
-                  int64_t M, float *sigma, float *rgb);
+                  int64_t M, float *sigma, float *rgb, hipEvent_t ev_start = nullptr, hipEvent_t ev_stop = nullptr);
 int kn_mlp_pack_weights(kn_scene *sc, hipStream_t st);
 int kn_mlp_tile_len(const kn_scene *sc);
 
@@ -324,6 +326,10 @@ struct KnStageTimer {
     KnStageTimer(kn_ctx *c, hipStream_t s, bool allowed = true);
     void begin() { mark(KN_ST_NONE); }
     void mark(int stage_id);
+    // Where only one stage is being timed and that stage is one kernel (the grouped MLP), the kernel's dispatch takes its
+    // own start and stop time stamps instead of marks around it: the two events for the launch, or false (events
+    // untouched) when `stage_id` is not timed that way.
+    bool kernel_events(int stage_id, hipEvent_t *start, hipEvent_t *stop);
     // totals that are counted, not timed
     void add(int64_t mlp_launches, int64_t mlp_samples, int64_t bucket_keys, int64_t calls);
 };

@@ -26,6 +26,7 @@
 // of the double-angle recurrence in between; all in fp32.
 #include "kn_common.h"
 #include "kn_mlp_shared.h"
+#include <hip/hip_ext.h>
 #include "kn_probe.h"
 
 namespace {
@@ -456,7 +457,7 @@ int kn_mlp_f32_pack_weights(kn_scene *sc, hipStream_t st)
 }
 
 int kn_mlp_f32_launch(const kn_scene *sc, hipStream_t st, const KnSampleSrc &src, const KnBucketOut &b, int64_t max_tiles,
-                      float *sigma, float *rgb)
+                      float *sigma, float *rgb, hipEvent_t ev_start, hipEvent_t ev_stop)
 {
     if (max_tiles <= 0) return KN_OK;
     const float *w = (const float *)sc->packed_w;
@@ -467,10 +468,11 @@ int kn_mlp_f32_launch(const kn_scene *sc, hipStream_t st, const KnSampleSrc &src
     const int64_t fill = H == 32 ? 512 : 256;
     if (blocks > fill) blocks = fill;
     dim3 grid((unsigned)blocks), block(F32_WAVES * KN_WAVE);
-    if (H == 32)
-        hipLaunchKernelGGL(k_mlp_f32<32>, grid, block, 0, st, w, src, b.perm, b.tiles, b.n_tiles, sigma, rgb);
+    auto kernel = H == 32 ? k_mlp_f32<32> : k_mlp_f32<64>;
+    if (ev_start && ev_stop)
+        hipExtLaunchKernelGGL(kernel, grid, block, 0, st, ev_start, ev_stop, 0, w, src, b.perm, b.tiles, b.n_tiles, sigma, rgb);
     else
-        hipLaunchKernelGGL(k_mlp_f32<64>, grid, block, 0, st, w, src, b.perm, b.tiles, b.n_tiles, sigma, rgb);
+        hipLaunchKernelGGL(kernel, grid, block, 0, st, w, src, b.perm, b.tiles, b.n_tiles, sigma, rgb);
     KN_CHECK_LAUNCH();
     return KN_OK;
 }

@@ -40,6 +40,7 @@
 // role.
 #include "kn_common.h"
 #include "kn_dir_encode.h"
+#include <hip/hip_ext.h>
 #include "kn_mlp_shared.h"
 #include "kn_probe.h"
 
@@ -816,7 +817,7 @@ __global__ void __launch_bounds__(WAVES *KN_WAVE)
 
 template <int H, bool BF, int WAVES>
 int launch(const kn_scene *sc, hipStream_t st, const KnSampleSrc &src, const KnBucketOut &b, int64_t max_tiles, float *sigma,
-           float *rgb)
+           float *rgb, hipEvent_t ev_start, hipEvent_t ev_stop)
 {
     int64_t blocks = kn_div_up(max_tiles, WAVES);
     // one workgroup of 4 wavefronts per compute unit and resident wavefront (H = 32: three per SIMD, H = 64: two)
@@ -837,8 +838,12 @@ int launch(const kn_scene *sc, hipStream_t st, const KnSampleSrc &src, const KnB
                   : !rays     ? (wrap ? k_mlp_mfma<H, BF, WAVES, true, false, SRC_POINTS> : k_mlp_mfma<H, BF, WAVES, false, false, SRC_POINTS>)
                   : wrap      ? (strat ? k_mlp_mfma<H, BF, WAVES, true, true, SRC_RAYS> : k_mlp_mfma<H, BF, WAVES, true, false, SRC_RAYS>)
                               : (strat ? k_mlp_mfma<H, BF, WAVES, false, true, SRC_RAYS> : k_mlp_mfma<H, BF, WAVES, false, false, SRC_RAYS>);
-    hipLaunchKernelGGL(kernel, dim3((unsigned)blocks), dim3(WAVES * KN_WAVE), 0, st, (const uint16_t *)sc->packed_w, src, b.perm,
-                       b.tiles, b.n_tiles, sigma, rgb);
+    if (ev_start && ev_stop)
+        hipExtLaunchKernelGGL(kernel, dim3((unsigned)blocks), dim3(WAVES * KN_WAVE), 0, st, ev_start, ev_stop, 0,
+                              (const uint16_t *)sc->packed_w, src, b.perm, b.tiles, b.n_tiles, sigma, rgb);
+    else
+        hipLaunchKernelGGL(kernel, dim3((unsigned)blocks), dim3(WAVES * KN_WAVE), 0, st, (const uint16_t *)sc->packed_w, src, b.perm,
+                           b.tiles, b.n_tiles, sigma, rgb);
     KN_CHECK_LAUNCH();
     return KN_OK;
 }
@@ -964,15 +969,15 @@ int kn_mlp_layered_launch(const kn_scene *sc, hipStream_t st, const KnSampleSrc 
 }
 
 int kn_mlp_mfma_launch(const kn_scene *sc, hipStream_t st, const KnSampleSrc &src, const KnBucketOut &b, int64_t max_tiles,
-                       float *sigma, float *rgb)
+                       float *sigma, float *rgb, hipEvent_t ev_start, hipEvent_t ev_stop)
 {
     if (max_tiles <= 0) return KN_OK;
     const bool bf = sc->desc.wdtype == KN_BF16;
     if (sc->desc.hidden == 32)
-        return bf ? launch<32, true, MLP_WAVES>(sc, st, src, b, max_tiles, sigma, rgb)
-                  : launch<32, false, MLP_WAVES>(sc, st, src, b, max_tiles, sigma, rgb);
+        return bf ? launch<32, true, MLP_WAVES>(sc, st, src, b, max_tiles, sigma, rgb, ev_start, ev_stop)
+                  : launch<32, false, MLP_WAVES>(sc, st, src, b, max_tiles, sigma, rgb, ev_start, ev_stop);
     if (sc->desc.hidden == 64)
-        return bf ? launch<64, true, MLP_WAVES>(sc, st, src, b, max_tiles, sigma, rgb)
-                  : launch<64, false, MLP_WAVES>(sc, st, src, b, max_tiles, sigma, rgb);
+        return bf ? launch<64, true, MLP_WAVES>(sc, st, src, b, max_tiles, sigma, rgb, ev_start, ev_stop)
+                  : launch<64, false, MLP_WAVES>(sc, st, src, b, max_tiles, sigma, rgb, ev_start, ev_stop);
     return KN_E_UNSUPPORTED;
 }

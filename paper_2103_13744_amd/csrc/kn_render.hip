@@ -1259,7 +1259,9 @@ static int render_impl(kn_ctx *ctx, const kn_scene *sc, void *stream, const floa
         KnBucketOut bo;
         KN_TRY(kn_group_run(st, knobs, w.row_keys, w.cnt, ctl, rows_cap, sc->N, tile_len, gw, &bo));
         tm.mark(KN_ST_BUCKET);
-        KN_TRY(kn_mlp_launch(sc, st, src, bo, budget, nullptr, nullptr));
+        hipEvent_t e0 = nullptr, e1 = nullptr;
+        (void)tm.kernel_events(KN_ST_MLP, &e0, &e1);
+        KN_TRY(kn_mlp_launch(sc, st, src, bo, budget, nullptr, nullptr, e0, e1));
         tm.mark(KN_ST_MLP);
         // many rays with few samples each: one lane per ray; few rays with many samples: 16 lanes per ray
         const bool lane_per_ray = s_bound <= 64;
