@@ -198,6 +198,20 @@ __device__ __forceinline__ int32_t skip_to_content(const MarchParams &p, const G
     return min(k, k_hi);
 }
 
+// Largest value among the 16 lanes of a marching group, in every lane of the group.  A group is one row of the
+// data-parallel-primitive network (16 lanes), so four rotations inside the row do it, without the LDS crossbar that
+// general lane exchanges go through.  All 16 lanes of the row must be active.
+__device__ __forceinline__ int32_t group_max(int32_t v)
+{
+    static_assert(MARCH_G == 16, "a marching group is one DPP row");
+    constexpr int ROW_ROR = 0x120; // dpp_ctrl of row_ror:n is 0x120 + n
+    v = max(v, __builtin_amdgcn_update_dpp(v, v, ROW_ROR + 8, 0xf, 0xf, false));
+    v = max(v, __builtin_amdgcn_update_dpp(v, v, ROW_ROR + 4, 0xf, 0xf, false));
+    v = max(v, __builtin_amdgcn_update_dpp(v, v, ROW_ROR + 2, 0xf, 0xf, false));
+    v = max(v, __builtin_amdgcn_update_dpp(v, v, ROW_ROR + 1, 0xf, 0xf, false));
+    return v;
+}
+
 // Cooperative march of one ray by a group of MARCH_G lanes (all lanes of the group call this with
 // the same arguments; gl = lane index inside the group).  Collects up to S kept lattice indices in
 // [k, k_hi), in ascending order, through emit(j, kk, cell).  Returns the number collected and
@@ -291,10 +305,7 @@ __device__ __forceinline__ int32_t march_group(const MarchParams &p, const GridF
         if (full) break;
         // frontier: every index of these chunks was tested or skipped; the farthest jump that starts inside
         // them extends the known-empty range beyond
-        int32_t far = max(reach[0], reach[STEPS - 1]);
-#pragma unroll
-        for (int off = MARCH_G / 2; off > 0; off >>= 1) far = max(far, __shfl_xor(far, off, KN_WAVE));
-        k = max(k + STEPS * MARCH_G, far);
+        k = max(k + STEPS * MARCH_G, group_max(max(reach[0], reach[STEPS - 1])));
     }
     return n;
 }
