@@ -47,20 +47,22 @@ struct MarchParams {
 constexpr int OPT_SPARSE = 1, OPT_STRAT = 2;
 
 // One axis of Eq. 6 without the division when the result cannot depend on it: u' = rel * (1/cell)
-// differs from the correctly rounded quotient by a few ulp; only when u' sits that close to an
-// integer is the division itself evaluated.  Returns floor(quotient) as a float.
-__device__ __forceinline__ float axis_floor(float rel, float cell, float inv_cell)
+// differs from the correctly rounded quotient by a few ulp (less than 4.8e-7 |u'|); only when u' sits that close
+// to an integer is the division itself evaluated.  `guard` is that bound for the largest |u'| that matters,
+// res + 1: beyond it both u' and the quotient are outside [0, res) whatever their last bits are, and callers only
+// ask whether the result is inside that range, and which integer it is if so.  Returns floor(quotient) as a float
+// (for values inside the range; some value outside the range otherwise; NaN and inf stay what they are).
+__device__ __forceinline__ float axis_floor(float rel, float cell, float inv_cell, float guard, float one_minus_guard)
 {
     const float u = rel * inv_cell;
     const float f = floorf(u);
     const float frac = u - f;
-    const float guard = fabsf(u) * 4.8e-7f + 1e-30f;
-    if (frac > guard && (1.0f - frac) > guard) return f; // also false for NaN / inf
-    return floorf(rel / cell);
+    if (frac <= guard || frac >= one_minus_guard) return floorf(rel / cell); // (both false for NaN / inf)
+    return f;
 }
 
 struct GridFast {
-    float bmin[3], cell[3], inv[3], resf[3];
+    float bmin[3], cell[3], inv[3], resf[3], guard[3], one_minus_guard[3];
     int32_t res1, res2;
 };
 
@@ -73,6 +75,8 @@ __device__ __forceinline__ GridFast make_fast(const KnGrid &g)
         f.cell[a] = g.cell[a];
         f.inv[a] = 1.0f / g.cell[a];
         f.resf[a] = (float)g.res[a];
+        f.guard[a] = ((float)g.res[a] + 1.0f) * 4.8e-7f + 1e-30f;
+        f.one_minus_guard[a] = 1.0f - f.guard[a];
     }
     f.res1 = g.res[1];
     f.res2 = g.res[2];
@@ -83,9 +87,9 @@ __device__ __forceinline__ GridFast make_fast(const KnGrid &g)
 __device__ __forceinline__ bool grid_coords_fast(const GridFast &g, float x, float y, float z, int32_t &ix, int32_t &iy,
                                                  int32_t &iz)
 {
-    const float fx = axis_floor(x - g.bmin[0], g.cell[0], g.inv[0]);
-    const float fy = axis_floor(y - g.bmin[1], g.cell[1], g.inv[1]);
-    const float fz = axis_floor(z - g.bmin[2], g.cell[2], g.inv[2]);
+    const float fx = axis_floor(x - g.bmin[0], g.cell[0], g.inv[0], g.guard[0], g.one_minus_guard[0]);
+    const float fy = axis_floor(y - g.bmin[1], g.cell[1], g.inv[1], g.guard[1], g.one_minus_guard[1]);
+    const float fz = axis_floor(z - g.bmin[2], g.cell[2], g.inv[2], g.guard[2], g.one_minus_guard[2]);
     const bool in = (fx >= 0.0f) && (fx < g.resf[0]) && (fy >= 0.0f) && (fy < g.resf[1]) && (fz >= 0.0f) &&
                     (fz < g.resf[2]);
     ix = (int32_t)fx;
@@ -96,9 +100,9 @@ __device__ __forceinline__ bool grid_coords_fast(const GridFast &g, float x, flo
 
 __device__ __forceinline__ int32_t grid_index_fast(const GridFast &g, float x, float y, float z)
 {
-    const float fx = axis_floor(x - g.bmin[0], g.cell[0], g.inv[0]);
-    const float fy = axis_floor(y - g.bmin[1], g.cell[1], g.inv[1]);
-    const float fz = axis_floor(z - g.bmin[2], g.cell[2], g.inv[2]);
+    const float fx = axis_floor(x - g.bmin[0], g.cell[0], g.inv[0], g.guard[0], g.one_minus_guard[0]);
+    const float fy = axis_floor(y - g.bmin[1], g.cell[1], g.inv[1], g.guard[1], g.one_minus_guard[1]);
+    const float fz = axis_floor(z - g.bmin[2], g.cell[2], g.inv[2], g.guard[2], g.one_minus_guard[2]);
     const bool in = (fx >= 0.0f) && (fx < g.resf[0]) && (fy >= 0.0f) && (fy < g.resf[1]) && (fz >= 0.0f) &&
                     (fz < g.resf[2]);
     if (!in) return -1;
