@@ -19,7 +19,8 @@
 
 namespace {
 
-constexpr int MARCH_G = 16;
+constexpr int MARCH_G = 16;    // lanes per ray of the stage kernel and of the blend of long rows
+constexpr int LIST_GROUP = 16; // rows per group in which the blend counts survivors and the next march compacts the list
 
 struct MarchParams {
     KnGrid net, occ;
@@ -202,33 +203,41 @@ __device__ __forceinline__ int32_t skip_to_content(const MarchParams &p, const G
     return min(k, k_hi);
 }
 
-// Largest value among the 16 lanes of a marching group, in every lane of the group.  A group is one row of the
-// data-parallel-primitive network (16 lanes), so four rotations inside the row do it, without the LDS crossbar that
-// general lane exchanges go through.  All 16 lanes of the row must be active.
-__device__ __forceinline__ int32_t group_max(int32_t v)
+// Largest value among the G lanes of a marching group, in every lane of the group.  A group is one row (16 lanes) or
+// half a row (8) of the data-parallel-primitive network, so a few permutations inside the row do it, without the LDS
+// crossbar that general lane exchanges go through.  All lanes of the group must be active.
+template <int G> __device__ __forceinline__ int32_t group_max(int32_t v)
 {
-    static_assert(MARCH_G == 16, "a marching group is one DPP row");
-    constexpr int ROW_ROR = 0x120; // dpp_ctrl of row_ror:n is 0x120 + n
-    v = max(v, __builtin_amdgcn_update_dpp(v, v, ROW_ROR + 8, 0xf, 0xf, false));
-    v = max(v, __builtin_amdgcn_update_dpp(v, v, ROW_ROR + 4, 0xf, 0xf, false));
-    v = max(v, __builtin_amdgcn_update_dpp(v, v, ROW_ROR + 2, 0xf, 0xf, false));
-    v = max(v, __builtin_amdgcn_update_dpp(v, v, ROW_ROR + 1, 0xf, 0xf, false));
+    static_assert(G == 16 || G == 8, "a marching group is a DPP row or half of one");
+    constexpr int ROW_ROR = 0x120;                     // dpp_ctrl of row_ror:n is 0x120 + n
+    constexpr int QUAD_1032 = 0xB1, QUAD_2301 = 0x4E;  // quad_perm:[1,0,3,2], [2,3,0,1]
+    constexpr int ROW_HALF_MIRROR = 0x141;             // lane i of each half row <-> lane 7 - i
+    if constexpr (G == 16) {
+        v = max(v, __builtin_amdgcn_update_dpp(v, v, ROW_ROR + 8, 0xf, 0xf, false));
+        v = max(v, __builtin_amdgcn_update_dpp(v, v, ROW_ROR + 4, 0xf, 0xf, false));
+        v = max(v, __builtin_amdgcn_update_dpp(v, v, ROW_ROR + 2, 0xf, 0xf, false));
+        v = max(v, __builtin_amdgcn_update_dpp(v, v, ROW_ROR + 1, 0xf, 0xf, false));
+    } else {
+        v = max(v, __builtin_amdgcn_update_dpp(v, v, QUAD_1032, 0xf, 0xf, false));
+        v = max(v, __builtin_amdgcn_update_dpp(v, v, QUAD_2301, 0xf, 0xf, false)); // every lane: its quad's largest
+        v = max(v, __builtin_amdgcn_update_dpp(v, v, ROW_HALF_MIRROR, 0xf, 0xf, false)); // ... and the other quad's
+    }
     return v;
 }
 
-// Cooperative march of one ray by a group of MARCH_G lanes (all lanes of the group call this with
+// Cooperative march of one ray by a group of G lanes (all lanes of the group call this with
 // the same arguments; gl = lane index inside the group).  Collects up to S kept lattice indices in
 // [k, k_hi), in ascending order, through emit(j, kk, cell).  Returns the number collected and
 // leaves in k the index to resume at (>= k_hi: the ray is exhausted).
-template <int OPT, typename Emit>
+template <int OPT, int G, typename Emit>
 __device__ __forceinline__ int32_t march_group(const MarchParams &p, const GridFast &gn, const GridFast &go,
                                                const float o[3], const float d[3], int32_t &k, int32_t k_hi, int32_t S,
                                                int gl, uint32_t ray_key, Emit emit)
 {
     constexpr bool STRAT = (OPT & OPT_STRAT) != 0, SPARSE = (OPT & OPT_SPARSE) != 0;
     const int lane = threadIdx.x & (KN_WAVE - 1);
-    const int gshift = lane & ~(MARCH_G - 1);
-    const uint32_t gmask = (MARCH_G == 32) ? 0xffffffffu : ((1u << MARCH_G) - 1u);
+    const int gshift = lane & ~(G - 1);
+    const uint32_t gmask = (G == 32) ? 0xffffffffu : ((1u << G) - 1u);
     const SkipJump sj(p, o, d, STRAT);
     int32_t n = 0;
     constexpr int SKIP_SHIFT = 2;
@@ -239,7 +248,7 @@ __device__ __forceinline__ int32_t march_group(const MarchParams &p, const GridF
         int32_t cell[STEPS], reach[STEPS], kk[STEPS];
 #pragma unroll
         for (int c = 0; c < STEPS; ++c) {
-            kk[c] = k + c * MARCH_G + gl;
+            kk[c] = k + c * G + gl;
             kept[c] = false;
             cell[c] = -1;
             reach[c] = 0; // all lattice indices in [kk, reach) are known not to be kept
@@ -299,7 +308,7 @@ __device__ __forceinline__ int32_t march_group(const MarchParams &p, const GridF
             if (tot > room) {
                 // the first kept sample that did not fit is where the next wave resumes
                 const uint32_t over = (uint32_t)(__ballot(kept[c] && rank == room) >> gshift) & gmask;
-                k = k + c * MARCH_G + (__ffs(over) - 1);
+                k = k + c * G + (__ffs(over) - 1);
                 n = S;
                 full = true;
             } else {
@@ -309,7 +318,7 @@ __device__ __forceinline__ int32_t march_group(const MarchParams &p, const GridF
         if (full) break;
         // frontier: every index of these chunks was tested or skipped; the farthest jump that starts inside
         // them extends the known-empty range beyond
-        k = max(k + STEPS * MARCH_G, group_max(max(reach[0], reach[STEPS - 1])));
+        k = max(k + STEPS * G, group_max<G>(max(reach[0], reach[STEPS - 1])));
     }
     return n;
 }
@@ -333,7 +342,7 @@ __global__ void __launch_bounds__(256)
     int32_t k = max(k_begin ? max(k_begin[r], 0) : 0, k_lo);
     int32_t *row = out_k + r * S;
     const uint32_t ray_key = kn_mix32(p.seed_key + (uint32_t)r);
-    const int32_t n = march_group<OPT>(p, gn, go, o, d, k, k_hi, S, gl, ray_key, [&](int j, int32_t kk, int32_t) { row[j] = kk; });
+    const int32_t n = march_group<OPT, MARCH_G>(p, gn, go, o, d, k, k_hi, S, gl, ray_key, [&](int j, int32_t kk, int32_t) { row[j] = kk; });
     for (int32_t j = n + gl; j < S; j += MARCH_G) row[j] = -1;
     if (gl == 0) {
         out_count[r] = n;
@@ -461,18 +470,21 @@ __global__ void __launch_bounds__(RAY_BLOCK)
     }
 }
 
-// MARCH_G lanes per live ray: collect up to S kept samples into row i of the wave's row buffers.
+// G lanes per live ray: collect up to S kept samples into row i of the wave's row buffers.
 // The workgroup also counts its samples per network in LDS (dynamic LDS: n_bins counters, or a hash table of
 // 2 * hash_slots ints where a counter per network does not fit) and adds what it counted to the global histogram
 // `hist` that the grouping of this wave starts from.
 //
 // From the second wave on (`blk_off` given) the kernel also compacts the live list while it reads it: it runs over
-// the rows of the previous wave's list (`old_ctl`), the survivors among the 16 rows of a workgroup get the new row
-// numbers blk_off[workgroup] + rank (ascending, so the order of the list is kept), and the new list is written to
+// the rows of the previous wave's list (`old_ctl`), the survivors among each group of 16 rows get the new row
+// numbers blk_off[group] + rank (ascending, so the order of the list is kept), and the new list is written to
 // live_out / alive_out.  blk_off comes from k_sum_partials (prefix sums of the survivor counts that the blend of
 // the same 16-row groups left).
 // HASH: the per-network counters are a hash table (large grids), else one counter per network.
-template <bool HASH, int OPT>
+// G: lanes per ray.  The kernel is bound by the latency of an iteration.  8 in the first wave, whose many rays stop
+// after a few dozen samples: a wavefront keeps eight rays in flight, and a ray needs well under twice the iterations it
+// would with 16 lanes (most iterations find few points to keep or none).  16 in later waves (few rays, long rows).
+template <bool HASH, int OPT, int G>
 __global__ void __launch_bounds__(256)
     k_march_wave(MarchParams p, const float *__restrict__ rays_o, const float *__restrict__ rays_d,
                  const int32_t *__restrict__ live, const int32_t *__restrict__ alive, const int32_t *__restrict__ ctl,
@@ -485,28 +497,26 @@ __global__ void __launch_bounds__(256)
     // table keyed by network (keys [hash_slots], then counts [hash_slots]; a power of two)
     extern __shared__ int32_t bins[];
     const int32_t n_lds = HASH ? 2 * hash_slots : n_bins;
-    __shared__ int32_t flags[256 / MARCH_G];
     const int32_t n_in = blk_off ? old_ctl[0] : ctl[0]; // rows of the list that is read
     const int32_t S = ctl[1];
-    if ((int64_t)blockIdx.x * (256 / MARCH_G) >= n_in) return; // the grid is sized for an upper bound of the rows
-    const int32_t i_in = (int32_t)(((int64_t)blockIdx.x * blockDim.x + threadIdx.x) / MARCH_G);
-    const int gl = threadIdx.x & (MARCH_G - 1), grp = threadIdx.x / MARCH_G;
+    constexpr int32_t T = 256;
+    if ((int64_t)blockIdx.x * (T / G) >= n_in) return; // the grid is sized for an upper bound of the rows
+    const int32_t i_in = (int32_t)(((int64_t)blockIdx.x * blockDim.x + threadIdx.x) / G);
+    const int gl = threadIdx.x & (G - 1), lane = threadIdx.x & (KN_WAVE - 1);
     const bool lives = i_in < n_in && alive[i_in] != 0;
     int32_t i = i_in; // row of this ray in the wave's buffers
     if (blk_off) {
-        if (gl == 0) flags[grp] = lives ? 1 : 0;
-        __syncthreads();
-        int32_t rank = 0, any = 0;
-#pragma unroll
-        for (int q = 0; q < 256 / MARCH_G; ++q) {
-            const int32_t f = flags[q];
-            any += f;
-            if (q < grp) rank += f;
-        }
-        if (any == 0) return; // (uniform) all 16 rays of the workgroup have retired
-        i = blk_off[blockIdx.x] + rank;
+        // The list is compacted in groups of LIST_GROUP = 16 rows (blk_off[g]: new row of group g's first survivor).
+        // The 16 lanes of a DPP row fetch the flags of the group their row's ray belongs to (8 lanes per ray: the two
+        // rays of a row are neighbours inside one group).
+        const int32_t g16 = i_in / LIST_GROUP;
+        const int32_t q = LIST_GROUP * g16 + (lane & (LIST_GROUP - 1));
+        const bool f = q < n_in && alive[q] != 0;
+        const uint32_t flags = (uint32_t)(__ballot(f) >> (lane & ~(LIST_GROUP - 1))) & ((1u << LIST_GROUP) - 1u);
+        if (__syncthreads_or(lives ? 1 : 0) == 0) return; // (uniform) every ray of the workgroup has retired
+        if (lives) i = blk_off[g16] + __popc(flags & ((1u << (i_in & (LIST_GROUP - 1))) - 1u));
     }
-    for (int32_t b = threadIdx.x; b < n_lds; b += 256) bins[b] = (HASH && b < hash_slots) ? -1 : 0;
+    for (int32_t b = threadIdx.x; b < n_lds; b += T) bins[b] = (HASH && b < hash_slots) ? -1 : 0;
     __syncthreads();
     // one more sample of network `cell`
     auto count = [&](int32_t cell) {
@@ -543,7 +553,7 @@ __global__ void __launch_bounds__(256)
         int32_t *kr = row_keys + (int64_t)i * S;
         uint32_t *rr = row_rec + (int64_t)i * S;
         const uint32_t ray_key = kn_mix32(p.seed_key + (uint32_t)r);
-        const int32_t n = march_group<OPT>(p, gn, go, o, d, k, k_hi, S, gl, ray_key, [&](int j, int32_t kk, int32_t cell) {
+        const int32_t n = march_group<OPT, G>(p, gn, go, o, d, k, k_hi, S, gl, ray_key, [&](int j, int32_t kk, int32_t cell) {
             kr[j] = cell;
             rr[j] = ((uint32_t)r << kbits) | (uint32_t)kk;
             count(cell);
@@ -556,7 +566,7 @@ __global__ void __launch_bounds__(256)
     // the few bins this workgroup met go to the global histogram
     __syncthreads();
     const int32_t n_slots = HASH ? hash_slots : n_bins;
-    for (int32_t b = threadIdx.x; b < n_slots; b += 256) {
+    for (int32_t b = threadIdx.x; b < n_slots; b += T) {
         const int32_t c = bins[(HASH ? hash_slots : 0) + b];
         if (c) atomicAdd(&hist[HASH ? bins[b] : b], c);
     }
@@ -981,7 +991,6 @@ bool finite_pos(float v) { return isfinite(v) && v > 0.0f; }
 int march_options(const kn_scene *sc, const uint32_t *seed) { return (sc->cell_net ? OPT_SPARSE : 0) | (seed ? OPT_STRAT : 0); }
 using MarchStageFn = decltype(&k_march_stage<0>);
 using RenderInitFn = decltype(&k_render_init<0>);
-using MarchWaveFn = decltype(&k_march_wave<false, 0>);
 MarchStageFn march_stage_kernel(int opt)
 {
     static const MarchStageFn table[4] = {k_march_stage<0>, k_march_stage<1>, k_march_stage<2>, k_march_stage<3>};
@@ -991,12 +1000,20 @@ RenderInitFn render_init_kernel(int opt)
 {
     return (opt & OPT_STRAT) ? k_render_init<OPT_STRAT> : k_render_init<0>; // the table of a sparse grid plays no role here
 }
-MarchWaveFn march_wave_kernel(bool hash, int opt)
+constexpr int MARCH_G_NARROW = 8, MARCH_G_WIDE = 16; // lanes per ray in waves of short rows / of long rows
+using MarchWaveFn = decltype(&k_march_wave<false, 0, MARCH_G_WIDE>);
+MarchWaveFn march_wave_kernel(bool hash, int opt, bool narrow)
 {
-    static const MarchWaveFn table[2][4] = {
-        {k_march_wave<false, 0>, k_march_wave<false, 1>, k_march_wave<false, 2>, k_march_wave<false, 3>},
-        {k_march_wave<true, 0>, k_march_wave<true, 1>, k_march_wave<true, 2>, k_march_wave<true, 3>}};
-    return table[hash ? 1 : 0][opt & 3];
+    static const MarchWaveFn table[2][2][4] = {
+        {{k_march_wave<false, 0, MARCH_G_WIDE>, k_march_wave<false, 1, MARCH_G_WIDE>, k_march_wave<false, 2, MARCH_G_WIDE>,
+          k_march_wave<false, 3, MARCH_G_WIDE>},
+         {k_march_wave<true, 0, MARCH_G_WIDE>, k_march_wave<true, 1, MARCH_G_WIDE>, k_march_wave<true, 2, MARCH_G_WIDE>,
+          k_march_wave<true, 3, MARCH_G_WIDE>}},
+        {{k_march_wave<false, 0, MARCH_G_NARROW>, k_march_wave<false, 1, MARCH_G_NARROW>, k_march_wave<false, 2, MARCH_G_NARROW>,
+          k_march_wave<false, 3, MARCH_G_NARROW>},
+         {k_march_wave<true, 0, MARCH_G_NARROW>, k_march_wave<true, 1, MARCH_G_NARROW>, k_march_wave<true, 2, MARCH_G_NARROW>,
+          k_march_wave<true, 3, MARCH_G_NARROW>}}};
+    return table[narrow ? 1 : 0][hash ? 1 : 0][opt & 3];
 }
 
 } // namespace
@@ -1181,7 +1198,7 @@ static int render_impl(kn_ctx *ctx, const kn_scene *sc, void *stream, const floa
     const KnKnobs knobs = kn_knobs(ctx); // the schedule this call runs with, whatever is set meanwhile
     const int kbits = kbits_for(K > 1 ? K : 2);
     if (R > (1ll << (32 - kbits)) || R > 0x7fffffffLL / knobs.slots_per_ray ||
-        R > 0x7fffffffLL / MARCH_G)
+        R > 0x7fffffffLL / MARCH_G_WIDE)
         return KN_E_UNSUPPORTED; // slot numbers and row * lanes are 32-bit
     if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < kn_render_ws_bytes(sc, R, knobs.slots_per_ray))
         return KN_E_WORKSPACE;
@@ -1252,9 +1269,12 @@ static int render_impl(kn_ctx *ctx, const kn_scene *sc, void *stream, const floa
     // host knows how many rays the previous one left: `rows_cap` is the host's upper bound, which sizes the grids.
     // rows_in: upper bound of the rows of the list the march reads.  From the second wave on that is the previous
     // wave's list, which the kernel compacts on the way (see k_march_wave); the new list is then the current one.
+    int64_t s_bound = first_samples; // host-side upper bound of the samples per ray of the wave being enqueued
     auto march = [&](int64_t rows_in, bool compacting) -> int {
         const int32_t *ctl = w.ctl + 4 * (wave_no & 1), *old_ctl = w.ctl + 4 * ((wave_no + 1) & 1);
-        hipLaunchKernelGGL(march_wave_kernel(march_hash != 0, opt), dim3((unsigned)kn_div_up(rows_in * MARCH_G, 256)), dim3(256),
+        const bool narrow = s_bound <= 64; // short rows (the first wave)
+        const int lanes = narrow ? MARCH_G_NARROW : MARCH_G_WIDE;
+        hipLaunchKernelGGL(march_wave_kernel(march_hash != 0, opt, narrow), dim3((unsigned)kn_div_up(rows_in * lanes, 256)), dim3(256),
                            sizeof(int32_t) * (size_t)(march_hash ? 2 * march_hash : sc->N), st, p, rays_o, rays_d, live, alive,
                            ctl, kbits, rs, w.row_keys, w.row_rec, w.cnt, gw.hist, sc->N, march_hash, old_ctl,
                            compacting ? w.blk_off : (const int32_t *)nullptr, live_next, alive_next);
@@ -1266,7 +1286,6 @@ static int render_impl(kn_ctx *ctx, const kn_scene *sc, void *stream, const floa
         tm.mark(KN_ST_MARCH);
         return KN_OK;
     };
-    int64_t s_bound = first_samples; // host-side upper bound of the samples per ray of the wave being enqueued
     // post: the wave's survivor count and the running totals go to the mailbox (only where the host is going to look:
     // the writes to host memory are part of the kernel that closes the wave)
     auto rest_of_wave = [&](int64_t rows_cap, bool post) -> int {
