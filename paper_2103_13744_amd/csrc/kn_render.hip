@@ -1,9 +1,9 @@
 // Ray marching with empty-space skipping, alpha blending with early ray termination, and the
 // wave loop that ties them to bucketing and the grouped MLP (Sec. 3.1 Eq. 1-4, Sec. 3.4).
 //
-// A wave gives every live ray up to S samples.  Marching is cooperative: a group of MARCH_G lanes
-// owns one ray and tests MARCH_G consecutive lattice points per iteration, so the latency of the
-// dependent index arithmetic + occupancy load is paid once per MARCH_G points.  A coarse skip field
+// A wave gives every live ray up to S samples.  Marching is cooperative: a group of G lanes (8 or 16)
+// owns one ray and tests G consecutive lattice points per iteration, so the latency of the
+// dependent index arithmetic + occupancy load is paid once per G points.  A coarse skip field
 // (Chebyshev distance, in blocks of 4^3 voxels, to the nearest occupied block) lets a group jump
 // over lattice points that provably lie in empty blocks; every point that could be kept is still
 // tested with the exact arithmetic of Eq. 6, so the kept set equals the plain per-point definition.
