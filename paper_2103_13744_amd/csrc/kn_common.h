@@ -196,12 +196,26 @@ __device__ __forceinline__ void kn_lattice_point(float ox, float oy, float oz, f
     z = fmaf(t, dz, oz);
 }
 
-// Block-wide sum and exclusive prefix sum for blocks of up to 1024 threads (shuffles inside a
+// Block-wide sum and exclusive prefix sum for blocks of whole wavefronts, up to 1024 threads (a scan inside each
 // wavefront, `lds` (16 ints) across wavefronts).  Every thread of the block must call them.
+// Inclusive prefix sums over a wavefront whose 64 lanes are all active, with data-parallel-primitive shifts: four
+// steps inside each row of 16 lanes, then the last lane of a row is added to the next row (row_bcast:15 into rows 1
+// and 3) and lane 31 to the upper half (row_bcast:31 into rows 2 and 3).  No trip through the LDS crossbar.
+__device__ __forceinline__ int32_t kn_wave_inclusive_scan(int32_t v)
+{
+    constexpr int ROW_SHR = 0x110, ROW_BCAST15 = 0x142, ROW_BCAST31 = 0x143; // dpp_ctrl encodings
+    v += __builtin_amdgcn_update_dpp(0, v, ROW_SHR + 1, 0xf, 0xf, true);
+    v += __builtin_amdgcn_update_dpp(0, v, ROW_SHR + 2, 0xf, 0xf, true);
+    v += __builtin_amdgcn_update_dpp(0, v, ROW_SHR + 4, 0xf, 0xf, true);
+    v += __builtin_amdgcn_update_dpp(0, v, ROW_SHR + 8, 0xf, 0xf, true);
+    v += __builtin_amdgcn_update_dpp(0, v, ROW_BCAST15, 0xa, 0xf, true);
+    v += __builtin_amdgcn_update_dpp(0, v, ROW_BCAST31, 0xc, 0xf, true);
+    return v;
+}
+// (both block-wide helpers: every thread of the workgroup must call them, from uniform control flow)
 __device__ __forceinline__ int32_t kn_block_sum(int32_t v, int32_t *lds)
 {
-#pragma unroll
-    for (int d = KN_WAVE / 2; d > 0; d >>= 1) v += __shfl_xor(v, d, KN_WAVE);
+    v = __builtin_amdgcn_readlane(kn_wave_inclusive_scan(v), KN_WAVE - 1);
     __syncthreads();
     if ((threadIdx.x & (KN_WAVE - 1)) == 0) lds[threadIdx.x / KN_WAVE] = v;
     __syncthreads();
@@ -212,12 +226,7 @@ __device__ __forceinline__ int32_t kn_block_sum(int32_t v, int32_t *lds)
 __device__ __forceinline__ int32_t kn_block_exclusive_scan(int32_t v, int32_t *lds, int32_t &total)
 {
     const int lane = threadIdx.x & (KN_WAVE - 1), wv = threadIdx.x / KN_WAVE;
-    int32_t inc = v;
-#pragma unroll
-    for (int d = 1; d < KN_WAVE; d <<= 1) {
-        const int32_t o = __shfl_up(inc, d, KN_WAVE);
-        if (lane >= d) inc += o;
-    }
+    const int32_t inc = kn_wave_inclusive_scan(v);
     __syncthreads();
     if (lane == KN_WAVE - 1) lds[wv] = inc;
     __syncthreads();
