@@ -20,7 +20,6 @@ namespace {
 constexpr int GROUP_THREADS = 256;
 constexpr int GROUP_FUSED_MAX_BINS = KN_GROUP_FUSED_MAX_BINS; // largest grid whose histogram the fill pass scans by itself
 constexpr int GROUP_HASH_PROBES = 16;      // slots tried before a bin is handled through global memory instead
-constexpr int GROUP_LIST = 512;            // bins a workgroup can list as touched before it visits all
 
 // tiles of one group: the owner lane has written the first; groups of several tiles are finished by the
 // whole wavefront (every lane of the wavefront must call this, with its own group or nt == 0)
@@ -59,7 +58,7 @@ __global__ void __launch_bounds__(GROUP_THREADS)
 {
     typedef int32_t i4 __attribute__((ext_vector_type(4)));
     extern __shared__ int32_t bins[]; // MODE 2: counters [N], then the wave's histogram [N]; else hash keys, counts [bins_cap] each
-    __shared__ int32_t touched[GROUP_LIST], touched_off[MODE == 2 ? GROUP_LIST : 1], n_touched, scan_lds[GROUP_THREADS / KN_WAVE];
+    __shared__ int32_t scan_lds[GROUP_THREADS / KN_WAVE];
     const int tid = threadIdx.x, lane = tid & (KN_WAVE - 1);
     // the wave's shape comes from device memory (ctl[0] rows of ctl[1] slots): the launch may have been enqueued
     // before it was known.  Lanes per row: enough that a lane meets about two chunks of four keys.
@@ -145,14 +144,21 @@ __global__ void __launch_bounds__(GROUP_THREADS)
 
     // the first rows of the counting sweep are requested before the histogram is staged: one round trip for both
     RowLoad first_rows = fetch_rows(0);
+    int32_t own_sum = 0; // MODE 2: samples in the bins tid, tid + 256, ..., which this thread lays out below
     if constexpr (MODE == 2) {
         for (int32_t b0 = 0; b0 < N; b0 += 8 * GROUP_THREADS) {
             int32_t v[8];
 #pragma unroll
             for (int u = 0; u < 8; ++u) v[u] = hist[min(b0 + u * GROUP_THREADS + tid, N - 1)]; // loads issued together
 #pragma unroll
+            for (int u = 0; u < 8; ++u) // (the counters are cleared while the histogram is on its way)
+                if (b0 + u * GROUP_THREADS + tid < N) bins[b0 + u * GROUP_THREADS + tid] = 0;
+#pragma unroll
             for (int u = 0; u < 8; ++u)
-                if (b0 + u * GROUP_THREADS + tid < N) hcl[b0 + u * GROUP_THREADS + tid] = v[u];
+                if (b0 + u * GROUP_THREADS + tid < N) {
+                    hcl[b0 + u * GROUP_THREADS + tid] = v[u];
+                    own_sum += v[u];
+                }
         }
     }
 
@@ -197,103 +203,58 @@ __global__ void __launch_bounds__(GROUP_THREADS)
                 for (int32_t t = 0; t < len; ++t) perm[pos + t] = (int32_t)slot + t;
             });
     } else {
-    for (int32_t w0 = 0; w0 < N; w0 += bins_cap) { // (a single window: bins_cap = N)
-        const int32_t nb = min(bins_cap, N - w0);
-        for (int32_t b = tid; b < nb; b += GROUP_THREADS) bins[b] = 0;
-        if (tid == 0) n_touched = 0;
+        __syncthreads(); // counters cleared, histogram staged
+        if (nr > 0) sweep(0, N, first_rows, [&](int32_t k, int64_t, int32_t len) { atomicAdd(&bins[k], len); });
         __syncthreads();
-        if (nr > 0) sweep(w0, nb, w0 == 0 ? first_rows : fetch_rows(0), [&](int32_t k, int64_t, int32_t len) { atomicAdd(&bins[k], len); });
-        __syncthreads();
-        int32_t fused_off0 = 0; // MODE 2: offset of the first group this thread laid out
+        // exclusive offsets of all groups: thread t owns the bins t, t + 256, ... and lays them out in a row
+        int32_t total;
+        const int32_t fused_off0 = kn_block_exclusive_scan(own_sum, scan_lds, total);
         {
-            // exclusive offsets of all groups: thread t owns the bins t, t + 256, ... and lays them out in a row;
-            // the touched ones are listed together with their offsets
-            int32_t mine = 0;
-            for (int32_t b = tid; b < N; b += GROUP_THREADS) mine += hcl[b];
-            int32_t total;
-            int32_t off = kn_block_exclusive_scan(mine, scan_lds, total);
-            fused_off0 = off;
-            for (int32_t b0 = 0; b0 < N; b0 += 4 * GROUP_THREADS) { // uniform trip count: ballots inside
-                // four bins per thread and step: the LDS reads are issued together, one list reservation per step
-                int32_t cnt_b[4], hist_b[4];
+            // first position of this workgroup's range inside each group it met: the returning atomics of a thread's
+            // eight bins are in flight together (a workgroup meets few networks: most threads issue none)
+            int32_t off = fused_off0;
+            for (int32_t b0 = 0; b0 < N; b0 += 8 * GROUP_THREADS) {
+                int32_t c[8], h[8], base[8];
 #pragma unroll
-                for (int u = 0; u < 4; ++u) {
+                for (int u = 0; u < 8; ++u) {
                     const int32_t b = b0 + u * GROUP_THREADS + tid;
-                    cnt_b[u] = b < N ? bins[b] : 0;
-                    hist_b[u] = b < N ? hcl[b] : 0;
-                }
-                unsigned long long m[4];
-                int32_t wave_hits = 0;
-#pragma unroll
-                for (int u = 0; u < 4; ++u) {
-                    m[u] = __ballot(cnt_b[u] > 0);
-                    wave_hits += __builtin_popcountll(m[u]);
-                }
-                int32_t at = 0;
-                if (wave_hits) {
-                    if (lane == 0) at = atomicAdd(&n_touched, wave_hits);
-                    at = __shfl(at, 0, KN_WAVE);
+                    c[u] = b < N ? bins[b] : 0;
+                    h[u] = b < N ? hcl[b] : 0;
                 }
 #pragma unroll
-                for (int u = 0; u < 4; ++u) {
-                    const int32_t mine_at = at + __builtin_popcountll(m[u] & ((1ull << lane) - 1ull));
-                    if (cnt_b[u] > 0 && mine_at < GROUP_LIST) {
-                        touched[mine_at] = b0 + u * GROUP_THREADS + tid;
-                        touched_off[mine_at] = off;
-                    }
-                    at += __builtin_popcountll(m[u]);
-                    off += hist_b[u];
+                for (int u = 0; u < 8; ++u) base[u] = c[u] ? atomicAdd(&global[b0 + u * GROUP_THREADS + tid], c[u]) : 0;
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    if (c[u]) bins[b0 + u * GROUP_THREADS + tid] = off + base[u];
+                    off += h[u];
                 }
-            }
-            // tile list: slice k = the bins 256 k .. 256 k + 255, one workgroup per slice (tile positions follow
-            // the same layout order as the offsets)
-            for (int64_t slice = blockIdx.x; slice * GROUP_THREADS < N; slice += gridDim.x) {
-                const int32_t mine_b = (int32_t)slice * GROUP_THREADS + tid;
-                int32_t my_tiles = 0, tiles_before = 0, off_mine = fused_off0;
-                for (int32_t b = tid; b < N; b += GROUP_THREADS) {
-                    const int32_t c = hcl[b];
-                    const int32_t nt = (c + tile_len - 1) / tile_len;
-                    if (b < mine_b) {
-                        tiles_before += nt;
-                        off_mine += c;
-                    }
-                    my_tiles += nt;
-                }
-                const int32_t tpos = kn_block_exclusive_scan(my_tiles, scan_lds, total) + tiles_before;
-                if (slice == 0 && tid == 0) *n_tiles = total;
-                const int32_t c = mine_b < N ? hcl[mine_b] : 0;
-                write_tiles(tiles, mine_b, off_mine, c, (c + tile_len - 1) / tile_len, tpos, tile_len, lane);
             }
         }
-        __syncthreads();
-        const int32_t nt = n_touched;
-        const bool listed = nt <= GROUP_LIST; // otherwise all bins of the window are visited
-        const int32_t n_visit = listed ? nt : nb;
-        {
-            // first position of this workgroup's range inside each group it met
-            if (MODE == 2 && !listed) { // more bins than the list holds: every thread walks the bins it laid out
-                int32_t off = fused_off0;
-                for (int32_t b = tid; b < N; b += GROUP_THREADS) {
-                    const int32_t c = bins[b];
-                    if (c) bins[b] = off + atomicAdd(&global[b], c);
-                    off += hcl[b];
+        // tile list: slice k = the bins 256 k .. 256 k + 255, one workgroup per slice (tile positions follow
+        // the same layout order as the offsets)
+        for (int64_t slice = blockIdx.x; slice * GROUP_THREADS < N; slice += gridDim.x) {
+            const int32_t mine_b = (int32_t)slice * GROUP_THREADS + tid;
+            int32_t my_tiles = 0, tiles_before = 0, off_mine = fused_off0;
+            for (int32_t b = tid; b < N; b += GROUP_THREADS) {
+                const int32_t c = hcl[b];
+                const int32_t nt = (c + tile_len - 1) / tile_len;
+                if (b < mine_b) {
+                    tiles_before += nt;
+                    off_mine += c;
                 }
-            } else {
-                for (int32_t q = tid; q < n_visit; q += GROUP_THREADS) {
-                    const int32_t b = listed ? touched[q] : q;
-                    const int32_t c = bins[b];
-                    if (c) bins[b] = (MODE == 2 ? touched_off[q] : 0) + atomicAdd(&global[w0 + b], c);
-                }
+                my_tiles += nt;
             }
-            __syncthreads();
-            if (nr > 0)
-                sweep(w0, nb, fetch_rows(0), [&](int32_t k, int64_t slot, int32_t len) {
-                    const int32_t pos = atomicAdd(&bins[k], len);
-                    for (int32_t t = 0; t < len; ++t) perm[pos + t] = (int32_t)slot + t;
-                });
+            const int32_t tpos = kn_block_exclusive_scan(my_tiles, scan_lds, total) + tiles_before;
+            if (slice == 0 && tid == 0) *n_tiles = total;
+            const int32_t c = mine_b < N ? hcl[mine_b] : 0;
+            write_tiles(tiles, mine_b, off_mine, c, (c + tile_len - 1) / tile_len, tpos, tile_len, lane);
         }
-        __syncthreads();
-    }
+        __syncthreads(); // every bin this workgroup met holds the absolute position of its first sample
+        if (nr > 0)
+            sweep(0, N, fetch_rows(0), [&](int32_t k, int64_t slot, int32_t len) {
+                const int32_t pos = atomicAdd(&bins[k], len);
+                for (int32_t t = 0; t < len; ++t) perm[pos + t] = (int32_t)slot + t;
+            });
     }
 }
 
