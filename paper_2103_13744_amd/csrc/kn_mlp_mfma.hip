@@ -362,9 +362,16 @@ __global__ void __launch_bounds__(WAVES *KN_WAVE) __attribute__((amdgpu_waves_pe
     };
     KnTile dsc0 = descriptor(t_lo), dsc1 = descriptor(t_lo + 1), dsc2 = descriptor(t_lo + 2), dsc3 = descriptor(t_lo + 3);
     int32_t idx0 = sample_at(dsc0), idx1 = sample_at(dsc1), idx2 = sample_at(dsc2);
+    // Width 32: the first network's weights are requested here, behind the sample indices and in front of the two levels
+    // that depend on them, so that they arrive while those levels are waited for, not after them.  (Width 64 has no
+    // register to spare for the overlap: there the same move costs 9 %.)
+    int32_t net_cur = -1;
+    if constexpr (H == 32) {
+        load_network(dsc0.net);
+        net_cur = dsc0.net;
+    }
     uint32_t rec0 = load_record(idx0), rec1 = load_record(idx1);
     Raw raw0 = load_raw(idx0, rec0);
-    int32_t net_cur = -1;
     // Results of a tile are written in the next iteration, between its wait for the loads issued one iteration
     // earlier and the loads it issues itself: the memory counter is in order, so a store must be older than
     // every load that is going to be waited for, or the wait covers the store's full round trip as well.
