@@ -490,8 +490,8 @@ __global__ void __launch_bounds__(256)
                  const int32_t *__restrict__ live, const int32_t *__restrict__ alive, const int32_t *__restrict__ ctl,
                  int32_t kbits, RayState s, int32_t *__restrict__ row_keys, uint32_t *__restrict__ row_rec,
                  int32_t *__restrict__ cnt, int32_t *__restrict__ hist, int32_t n_bins, int32_t hash_slots,
-                 const int32_t *__restrict__ old_ctl, const int32_t *__restrict__ blk_off, int32_t *__restrict__ live_out,
-                 int32_t *__restrict__ alive_out)
+                 const int32_t *__restrict__ old_ctl, const int32_t *__restrict__ blk_off, const int32_t *__restrict__ grp_list,
+                 int32_t *__restrict__ live_out, int32_t *__restrict__ alive_out)
 {
     // per-network sample counters of the workgroup: one per network (hash_slots = 0: small grids), else a hash
     // table keyed by network (keys [hash_slots], then counts [hash_slots]; a power of two)
@@ -499,23 +499,13 @@ __global__ void __launch_bounds__(256)
     const int32_t n_lds = HASH ? 2 * hash_slots : n_bins;
     const int32_t n_in = blk_off ? old_ctl[0] : ctl[0]; // rows of the list that is read
     const int32_t S = ctl[1];
-    constexpr int32_t T = 256;
-    if ((int64_t)blockIdx.x * (T / G) >= n_in) return; // the grid is sized for an upper bound of the rows
-    const int32_t i_in = (int32_t)(((int64_t)blockIdx.x * blockDim.x + threadIdx.x) / G);
+    constexpr int32_t T = 256, RAYS = T / G; // rays per workgroup
+    constexpr int32_t GROUPS = RAYS / LIST_GROUP; // compaction groups per workgroup
+    static_assert(RAYS % LIST_GROUP == 0, "a workgroup takes whole groups of rows");
     const int gl = threadIdx.x & (G - 1), lane = threadIdx.x & (KN_WAVE - 1);
-    const bool lives = i_in < n_in && alive[i_in] != 0;
-    int32_t i = i_in; // row of this ray in the wave's buffers
-    if (blk_off) {
-        // The list is compacted in groups of LIST_GROUP = 16 rows (blk_off[g]: new row of group g's first survivor).
-        // The 16 lanes of a DPP row fetch the flags of the group their row's ray belongs to (8 lanes per ray: the two
-        // rays of a row are neighbours inside one group).
-        const int32_t g16 = i_in / LIST_GROUP;
-        const int32_t q = LIST_GROUP * g16 + (lane & (LIST_GROUP - 1));
-        const bool f = q < n_in && alive[q] != 0;
-        const uint32_t flags = (uint32_t)(__ballot(f) >> (lane & ~(LIST_GROUP - 1))) & ((1u << LIST_GROUP) - 1u);
-        if (__syncthreads_or(lives ? 1 : 0) == 0) return; // (uniform) every ray of the workgroup has retired
-        if (lives) i = blk_off[g16] + __popc(flags & ((1u << (i_in & (LIST_GROUP - 1))) - 1u));
-    }
+    // (uniform exits: the grid is sized for an upper bound of the rows / of the groups with survivors)
+    const int32_t n_groups = blk_off ? ctl[3] : 0;
+    if (blk_off ? (int64_t)blockIdx.x * GROUPS >= n_groups : (int64_t)blockIdx.x * RAYS >= n_in) return;
     for (int32_t b = threadIdx.x; b < n_lds; b += T) bins[b] = (HASH && b < hash_slots) ? -1 : 0;
     __syncthreads();
     // one more sample of network `cell`
@@ -536,10 +526,13 @@ __global__ void __launch_bounds__(256)
         }
         atomicAdd(&hist[cell], 1); // no slot nearby: straight to the global histogram
     };
-    if (!lives) {
-        // without compaction retired rows stay in the list: they get no samples
-        if (!blk_off && i_in < n_in && gl == 0) cnt[i_in] = 0;
-    } else {
+    // the ray of row i_in of the list that is read (if it lives), into row i of the wave's buffers
+    auto march_ray = [&](int32_t i_in, bool lives, int32_t i) {
+        if (!lives) {
+            // without compaction retired rows stay in the list: they get no samples
+            if (!blk_off && i_in < n_in && gl == 0) cnt[i_in] = 0;
+            return;
+        }
         const int32_t r = live[i_in];
         if (blk_off && gl == 0) {
             live_out[i] = r;
@@ -562,6 +555,24 @@ __global__ void __launch_bounds__(256)
             s.k_next[r] = k;
             cnt[i] = n;
         }
+    };
+    if (!blk_off) {
+        const int32_t i_in = (int32_t)(((int64_t)blockIdx.x * T + threadIdx.x) / G);
+        march_ray(i_in, i_in < n_in && alive[i_in] != 0, i_in);
+    } else {
+        // The list is compacted in groups of LIST_GROUP = 16 rows (blk_off[g]: new row of group g's first survivor), and
+        // the kernel runs over the groups that have survivors (grp_list, ctl[3] of them), so that the workgroups with
+        // work are the first of the grid.  The 16 lanes of a DPP row fetch the flags of the group their row's ray belongs
+        // to (8 lanes per ray: the two rays of a row are neighbours inside one group).
+        const int32_t ray = threadIdx.x / G;                                  // ray of the workgroup
+        const int64_t slot = (int64_t)blockIdx.x * GROUPS + ray / LIST_GROUP; // entry of the group list
+        const int32_t g16 = slot < n_groups ? grp_list[slot] : -1;
+        const int32_t i_in = g16 >= 0 ? LIST_GROUP * g16 + (ray & (LIST_GROUP - 1)) : n_in;
+        const bool lives = i_in < n_in && alive[i_in] != 0;
+        const int32_t q = LIST_GROUP * max(g16, 0) + (lane & (LIST_GROUP - 1));
+        const bool f = g16 >= 0 && q < n_in && alive[q] != 0;
+        const uint32_t flags = (uint32_t)(__ballot(f) >> (lane & ~(LIST_GROUP - 1))) & ((1u << LIST_GROUP) - 1u);
+        march_ray(i_in, lives, lives ? blk_off[g16] + __popc(flags & ((1u << (i_in & (LIST_GROUP - 1))) - 1u)) : 0);
     }
     // the few bins this workgroup met go to the global histogram
     __syncthreads();
@@ -812,13 +823,14 @@ __global__ void __launch_bounds__(1024) k_sum_partials(const int32_t *__restrict
                                                         unsigned long long *__restrict__ counters,
                                                         const int32_t *__restrict__ ctl, int32_t *__restrict__ ctl_next,
                                                         WaveSchedule sched, int32_t *__restrict__ blk_off,
+                                                        int32_t *__restrict__ grp_list,
                                                         unsigned long long *mailbox, unsigned long long seq)
 {
     // This kernel sits alone between the blend and the next wave's march: what counts is its latency.  Every value is
     // requested once, as early as possible, and each thread scans 16 contiguous entries (one 64-byte line) itself.
     constexpr int T = 1024, PER = 16;
     typedef int32_t i4 __attribute__((ext_vector_type(4)));
-    __shared__ int32_t lds[T / KN_WAVE];
+    __shared__ int32_t lds[T / KN_WAVE], lds_with[T / KN_WAVE];
     __shared__ unsigned long long red[2][T / KN_WAVE];
     const int tid = threadIdx.x;
     int32_t rows = 0, slots_per_row = 0, s_sched = 0;
@@ -837,8 +849,11 @@ __global__ void __launch_bounds__(1024) k_sum_partials(const int32_t *__restrict
         ev += (unsigned long long)partials[b];
         bl += (unsigned long long)partials[(int64_t)n_cb + b];
     }
-    // exclusive prefix sums of the survivors per 16-row group: the next wave's march compacts the list with them
-    int32_t survivors = 0;
+    // exclusive prefix sums of the survivors per 16-row group: the next wave's march compacts the list with them.
+    // grp_list: the groups that have survivors, ascending; the next march runs over those only (ctl_next[3] of them),
+    // so that its workgroups with work are the first of its grid and start at once, not spread among four times as
+    // many that find their 16 rows retired.
+    int32_t survivors = 0, live_groups = 0;
     for (int32_t b0 = 0; b0 < n_blocks; b0 += T * PER) {
         const int32_t e0 = b0 + PER * tid;
         const bool full = e0 + PER <= n_blocks;
@@ -853,17 +868,39 @@ __global__ void __launch_bounds__(1024) k_sum_partials(const int32_t *__restrict
 #pragma unroll
             for (int u = 0; u < PER; ++u) v[u] = e0 + u < n_blocks ? surv16[e0 + u] : 0;
         }
-        int32_t sum = 0;
+        int32_t sum = 0, with = 0;
 #pragma unroll
-        for (int u = 0; u < PER; ++u) sum += v[u];
-        int32_t total;
-        int32_t off = survivors + kn_block_exclusive_scan(sum, lds, total);
+        for (int u = 0; u < PER; ++u) {
+            sum += v[u];
+            with += v[u] > 0 ? 1 : 0;
+        }
+        // both prefix sums with one pair of barriers
+        const int32_t inc_sum = kn_wave_inclusive_scan(sum), inc_with = kn_wave_inclusive_scan(with);
+        __syncthreads();
+        if ((tid & (KN_WAVE - 1)) == KN_WAVE - 1) {
+            lds[tid / KN_WAVE] = inc_sum;
+            lds_with[tid / KN_WAVE] = inc_with;
+        }
+        __syncthreads();
+        int32_t total = 0, total_with = 0, off = survivors + inc_sum - sum, at = live_groups + inc_with - with;
+#pragma unroll
+        for (int w = 0; w < T / KN_WAVE; ++w) {
+            const int32_t a = lds[w], b = lds_with[w];
+            total += a;
+            total_with += b;
+            if (w < tid / KN_WAVE) {
+                off += a;
+                at += b;
+            }
+        }
 #pragma unroll
         for (int u = 0; u < PER; ++u) {
             const int32_t c = v[u];
+            if (c > 0) grp_list[at++] = e0 + u;
             v[u] = off;
             off += c;
         }
+        live_groups += total_with;
         if (full) {
 #pragma unroll
             for (int u = 0; u < PER / 4; ++u) *(i4 *)(blk_off + e0 + 4 * u) = (i4){v[4 * u], v[4 * u + 1], v[4 * u + 2], v[4 * u + 3]};
@@ -900,6 +937,7 @@ __global__ void __launch_bounds__(1024) k_sum_partials(const int32_t *__restrict
         // the next wave: the survivors (the live list is compacted in between), schedule value grown
         const int64_t grown = (int64_t)s_sched * sched.growth;
         set_wave(ctl_next, survivors, (int32_t)(grown < sched.K ? grown : sched.K), sched);
+        ctl_next[3] = live_groups;
         // running totals ride along so that the host never has to read the counters back
         if (mailbox) {
             __hip_atomic_store(&mailbox[2], tot_eval, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
@@ -1084,7 +1122,7 @@ static int kbits_for(int32_t K)
 
 // layout of the render workspace
 struct RenderWs {
-    int32_t *partials, *surv16, *blk_sum, *blk_off, *live_a, *live_b, *cnt, *alive_a, *alive_b, *n_live_dev, *row_keys, *ctl;
+    int32_t *partials, *surv16, *blk_sum, *blk_off, *grp_list, *live_a, *live_b, *cnt, *alive_a, *alive_b, *n_live_dev, *row_keys, *ctl;
     uint32_t *row_rec;
     float *T, *C, *out4;
     int32_t *k_next, *k_end;
@@ -1097,7 +1135,8 @@ static void carve_render(KnCarver &ws, int64_t R, int64_t slots, RenderWs &w)
     w.partials = ws.carve<int32_t>(2 * kn_div_up(R, MARCH_G));
     w.surv16 = ws.carve<int32_t>(kn_div_up(R, MARCH_G));
     w.blk_sum = ws.carve<int32_t>(kn_div_up(R, RAY_BLOCK) + 1);
-    w.blk_off = ws.carve<int32_t>(kn_div_up(R * MARCH_G, 256));
+    w.blk_off = ws.carve<int32_t>(kn_div_up(R, LIST_GROUP));
+    w.grp_list = ws.carve<int32_t>(kn_div_up(R, LIST_GROUP));
     w.live_a = ws.carve<int32_t>(R);
     w.live_b = ws.carve<int32_t>(R);
     w.cnt = ws.carve<int32_t>(R);
@@ -1277,7 +1316,7 @@ static int render_impl(kn_ctx *ctx, const kn_scene *sc, void *stream, const floa
         hipLaunchKernelGGL(march_wave_kernel(march_hash != 0, opt, narrow), dim3((unsigned)kn_div_up(rows_in * lanes, 256)), dim3(256),
                            sizeof(int32_t) * (size_t)(march_hash ? 2 * march_hash : sc->N), st, p, rays_o, rays_d, live, alive,
                            ctl, kbits, rs, w.row_keys, w.row_rec, w.cnt, gw.hist, sc->N, march_hash, old_ctl,
-                           compacting ? w.blk_off : (const int32_t *)nullptr, live_next, alive_next);
+                           compacting ? w.blk_off : (const int32_t *)nullptr, w.grp_list, live_next, alive_next);
         KN_CHECK_LAUNCH();
         if (compacting) {
             int32_t *t = live; live = live_next; live_next = t;
@@ -1312,7 +1351,7 @@ static int render_impl(kn_ctx *ctx, const kn_scene *sc, void *stream, const floa
         KN_CHECK_LAUNCH();
         if (post) seq = next_seq();
         hipLaunchKernelGGL(k_sum_partials, dim3(1), dim3(1024), 0, st, w.partials, cblocks, w.surv16, groups, w.counters, ctl,
-                           ctl_next, sched, w.blk_off, post ? mb_dev : (unsigned long long *)nullptr, seq);
+                           ctl_next, sched, w.blk_off, w.grp_list, post ? mb_dev : (unsigned long long *)nullptr, seq);
         KN_CHECK_LAUNCH();
         tm.mark(KN_ST_BLEND);
         tm.add(1, 0, 0, 0);
