@@ -49,24 +49,42 @@ __global__ void __launch_bounds__(RO_THREADS)
     for (int64_t i = (int64_t)blockIdx.x * RO_THREADS + threadIdx.x; i < n_zero; i += (int64_t)gridDim.x * RO_THREADS) zero[i] = 0;
     hist[threadIdx.x] = 0;
     __syncthreads();
-    const int64_t base = (int64_t)blockIdx.x * RO_TILE + threadIdx.x;
-    float p[RO_ROWS][3];
+    // one point: id, key, the zero result of a point without a network, the digit count
+    auto point = [&](int64_t i, float x, float y, float z) -> int32_t {
+        const int32_t id = kn_net_of_cell(cell_net, kn_grid_index(g, x, y, z));
+        const int32_t key = id < 0 ? N : id;
+        if (ids) ids[i] = id;
+        if (id < 0) *(float4 *)(out4 + 4 * i) = make_float4(0.0f, 0.0f, 0.0f, 0.0f); // no network: the result is zero
+        atomicAdd(&hist[(uint32_t)key & digit_mask], 1);
+        return key;
+    };
+    const int64_t tile0 = (int64_t)blockIdx.x * RO_TILE;
+    if (tile0 + RO_TILE <= M && ((uintptr_t)pts & 15) == 0) { // (uniform) a whole tile of a 16-byte aligned array
+        // four consecutive points per thread and step: three 16-byte loads, one 16-byte store of the keys
 #pragma unroll
-    for (int r = 0; r < RO_ROWS; ++r) {
-        const int64_t i = min(base + r * RO_THREADS, M - 1);
+        for (int r = 0; r < RO_ROWS / 4; ++r) {
+            const int64_t i = tile0 + 4 * ((int64_t)r * RO_THREADS + threadIdx.x);
+            const float4 a = *(const float4 *)(pts + 3 * i), b = *(const float4 *)(pts + 3 * i + 4), c = *(const float4 *)(pts + 3 * i + 8);
+            int4 k;
+            k.x = point(i, a.x, a.y, a.z);
+            k.y = point(i + 1, a.w, b.x, b.y);
+            k.z = point(i + 2, b.z, b.w, c.x);
+            k.w = point(i + 3, c.y, c.z, c.w);
+            *(int4 *)(keys + i) = k;
+        }
+    } else {
+        const int64_t base = tile0 + threadIdx.x;
+        float p[RO_ROWS][3];
 #pragma unroll
-        for (int c = 0; c < 3; ++c) p[r][c] = pts[3 * i + c];
-    }
+        for (int r = 0; r < RO_ROWS; ++r) {
+            const int64_t i = min(base + r * RO_THREADS, M - 1);
 #pragma unroll
-    for (int r = 0; r < RO_ROWS; ++r) {
-        const int64_t i = base + r * RO_THREADS;
-        if (i < M) {
-            const int32_t id = kn_net_of_cell(cell_net, kn_grid_index(g, p[r][0], p[r][1], p[r][2]));
-            const int32_t key = id < 0 ? N : id;
-            if (ids) ids[i] = id;
-            keys[i] = key;
-            if (id < 0) *(float4 *)(out4 + 4 * i) = make_float4(0.0f, 0.0f, 0.0f, 0.0f); // no network: the result is zero
-            atomicAdd(&hist[(uint32_t)key & digit_mask], 1);
+            for (int c = 0; c < 3; ++c) p[r][c] = pts[3 * i + c];
+        }
+#pragma unroll
+        for (int r = 0; r < RO_ROWS; ++r) {
+            const int64_t i = base + r * RO_THREADS;
+            if (i < M) keys[i] = point(i, p[r][0], p[r][1], p[r][2]);
         }
     }
     __syncthreads();
