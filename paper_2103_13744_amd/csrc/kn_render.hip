@@ -690,11 +690,8 @@ __global__ void __launch_bounds__(256)
     // thousands of wavefronts would serialise); k_sum_partials adds them up afterwards
     int32_t evaluated = n;
     __shared__ int32_t red[2][256 / KN_WAVE];
-#pragma unroll
-    for (int d = KN_WAVE / 2; d > 0; d >>= 1) {
-        blended += __shfl_down(blended, d, KN_WAVE);
-        evaluated += __shfl_down(evaluated, d, KN_WAVE);
-    }
+    blended = __builtin_amdgcn_readlane(kn_wave_inclusive_scan(blended), KN_WAVE - 1); // (all lanes are back together here)
+    evaluated = __builtin_amdgcn_readlane(kn_wave_inclusive_scan(evaluated), KN_WAVE - 1);
     if (lane == 0) {
         red[0][wave] = evaluated;
         red[1][wave] = blended;
@@ -793,12 +790,9 @@ __global__ void __launch_bounds__(256)
     // block-level sums -> one plain store per block and counter (same-address atomics from tens of
     // thousands of wavefronts would serialise); k_sum_partials adds them up afterwards
     __shared__ int32_t red[3][256 / KN_WAVE];
-#pragma unroll
-    for (int d = KN_WAVE / 2; d > 0; d >>= 1) {
-        blended += __shfl_down(blended, d, KN_WAVE);
-        evaluated += __shfl_down(evaluated, d, KN_WAVE);
-        survivors += __shfl_down(survivors, d, KN_WAVE);
-    }
+    blended = __builtin_amdgcn_readlane(kn_wave_inclusive_scan(blended), KN_WAVE - 1); // (all lanes are back together here)
+    evaluated = __builtin_amdgcn_readlane(kn_wave_inclusive_scan(evaluated), KN_WAVE - 1);
+    survivors = __builtin_amdgcn_readlane(kn_wave_inclusive_scan(survivors), KN_WAVE - 1);
     if ((threadIdx.x & (KN_WAVE - 1)) == 0) {
         red[0][threadIdx.x / KN_WAVE] = evaluated;
         red[1][threadIdx.x / KN_WAVE] = blended;
@@ -911,11 +905,9 @@ __global__ void __launch_bounds__(1024) k_sum_partials(const int32_t *__restrict
         }
         survivors += total;
     }
-#pragma unroll
-    for (int d = KN_WAVE / 2; d > 0; d >>= 1) {
-        ev += __shfl_down(ev, d, KN_WAVE);
-        bl += __shfl_down(bl, d, KN_WAVE);
-    }
+    // (a wave's samples fit 31 bits: the slots of a wave do)
+    ev = (unsigned long long)(uint32_t)__builtin_amdgcn_readlane(kn_wave_inclusive_scan((int32_t)ev), KN_WAVE - 1);
+    bl = (unsigned long long)(uint32_t)__builtin_amdgcn_readlane(kn_wave_inclusive_scan((int32_t)bl), KN_WAVE - 1);
     if ((tid & (KN_WAVE - 1)) == 0) {
         red[0][tid / KN_WAVE] = ev;
         red[1][tid / KN_WAVE] = bl;
