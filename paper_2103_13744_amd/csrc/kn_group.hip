@@ -21,6 +21,9 @@ constexpr int GROUP_THREADS = 256;
 constexpr int GROUP_FUSED_MAX_BINS = KN_GROUP_FUSED_MAX_BINS; // largest grid whose histogram the fill pass scans by itself
 constexpr int GROUP_HASH_PROBES = 16;      // slots tried before a bin is handled through global memory instead
 
+// tiles of c samples; tile_len is a power of two (the host checks it)
+__device__ __forceinline__ int32_t tiles_of(int32_t c, int32_t tile_len) { return (c + tile_len - 1) >> (31 - __builtin_clz(tile_len)); }
+
 // tiles of one group: the owner lane has written the first; groups of several tiles are finished by the
 // whole wavefront (every lane of the wavefront must call this, with its own group or nt == 0)
 __device__ __forceinline__ void write_tiles(KnTile *__restrict__ tiles, int32_t b, int32_t off, int32_t c, int32_t nt,
@@ -31,8 +34,10 @@ __device__ __forceinline__ void write_tiles(KnTile *__restrict__ tiles, int32_t 
     while (big) {
         const int srcl = __builtin_ctzll(big);
         big &= big - 1;
-        const int32_t gb = __shfl(b, srcl, KN_WAVE), go = __shfl(off, srcl, KN_WAVE), gc = __shfl(c, srcl, KN_WAVE);
-        const int32_t gt = __shfl(tpos, srcl, KN_WAVE), gn = __shfl(nt, srcl, KN_WAVE);
+        // (the source lane is the same for the whole wavefront: scalar reads, no lane exchange)
+        const int32_t gb = __builtin_amdgcn_readlane(b, srcl), go = __builtin_amdgcn_readlane(off, srcl),
+                      gc = __builtin_amdgcn_readlane(c, srcl), gt = __builtin_amdgcn_readlane(tpos, srcl),
+                      gn = __builtin_amdgcn_readlane(nt, srcl);
         for (int32_t k = 1 + lane; k < gn; k += KN_WAVE)
             tiles[gt + k] = KnTile{gb, go + k * tile_len, min(tile_len, gc - k * tile_len), 0};
     }
@@ -237,7 +242,7 @@ __global__ void __launch_bounds__(GROUP_THREADS)
             int32_t my_tiles = 0, tiles_before = 0, off_mine = fused_off0;
             for (int32_t b = tid; b < N; b += GROUP_THREADS) {
                 const int32_t c = hcl[b];
-                const int32_t nt = (c + tile_len - 1) / tile_len;
+                const int32_t nt = tiles_of(c, tile_len);
                 if (b < mine_b) {
                     tiles_before += nt;
                     off_mine += c;
@@ -247,7 +252,7 @@ __global__ void __launch_bounds__(GROUP_THREADS)
             const int32_t tpos = kn_block_exclusive_scan(my_tiles, scan_lds, total) + tiles_before;
             if (slice == 0 && tid == 0) *n_tiles = total;
             const int32_t c = mine_b < N ? hcl[mine_b] : 0;
-            write_tiles(tiles, mine_b, off_mine, c, (c + tile_len - 1) / tile_len, tpos, tile_len, lane);
+            write_tiles(tiles, mine_b, off_mine, c, tiles_of(c, tile_len), tpos, tile_len, lane);
         }
         __syncthreads(); // every bin this workgroup met holds the absolute position of its first sample
         if (nr > 0)
@@ -290,7 +295,7 @@ __global__ void __launch_bounds__(1024)
 #pragma unroll
         for (int u = 0; u < PER; ++u) {
             sum_s += c[u];
-            sum_t += (c[u] + tile_len - 1) / tile_len;
+            sum_t += tiles_of(c[u], tile_len);
         }
         int32_t tot_s, tot_t;
         int32_t off = carry_s + kn_block_exclusive_scan(sum_s, lds, tot_s);
@@ -301,7 +306,7 @@ __global__ void __launch_bounds__(1024)
             o[u] = off;
             t[u] = tpos;
             off += c[u];
-            tpos += (c[u] + tile_len - 1) / tile_len;
+            tpos += tiles_of(c[u], tile_len);
         }
         if (full) {
 #pragma unroll
@@ -340,7 +345,7 @@ __global__ void __launch_bounds__(GROUP_THREADS)
         tpos = hist[b];
         hist[b] = 0;
     }
-    write_tiles(tiles, b, off, c, (c + tile_len - 1) / tile_len, tpos, tile_len, lane);
+    write_tiles(tiles, b, off, c, tiles_of(c, tile_len), tpos, tile_len, lane);
 }
 
 } // namespace
@@ -376,7 +381,8 @@ void kn_group_carve(KnCarver &ws, int64_t slots, int32_t N, KnGroupWs *w) { carv
 int kn_group_run(hipStream_t st, const KnKnobs &knobs, const int32_t *row_keys, const int32_t *cnt, const int32_t *ctl,
                  int64_t max_rows, int32_t N, int32_t tile_len, const KnGroupWs &w, KnBucketOut *out)
 {
-    if (!ctl || max_rows < 0 || max_rows > 0x7fffffffLL || N < 1 || tile_len < 64) return KN_E_INVALID_ARG;
+    if (!ctl || max_rows < 0 || max_rows > 0x7fffffffLL || N < 1 || tile_len < 64 || (tile_len & (tile_len - 1)) != 0)
+        return KN_E_INVALID_ARG; // (tile counts are taken with a shift)
     if (!w.hist || !w.cursor || !w.n_tiles || !w.perm || !w.tiles) return KN_E_WORKSPACE;
     const bool fused = kn_group_fused(knobs, N);
     const int32_t bins_cap = fused ? N : knobs.group_hash_slots; // direct counters, or hash slots
