@@ -1319,7 +1319,9 @@ static int render_impl(kn_ctx *ctx, const kn_scene *sc, void *stream, const floa
     };
     // post: the wave's survivor count and the running totals go to the mailbox (only where the host is going to look:
     // the writes to host memory are part of the kernel that closes the wave)
-    auto rest_of_wave = [&](int64_t rows_cap, bool post) -> int {
+    // closing: false when the wave is known to be the last and nobody is going to read its sums (they feed the next
+    // wave's control block and list compaction, and the counters): the kernel that adds them up is then left out
+    auto rest_of_wave = [&](int64_t rows_cap, bool post, bool closing) -> int {
         int32_t *ctl = w.ctl + 4 * (wave_no & 1), *ctl_next = w.ctl + 4 * ((wave_no + 1) & 1);
         KnBucketOut bo;
         KN_TRY(kn_group_run(st, knobs, w.row_keys, w.cnt, ctl, rows_cap, sc->N, tile_len, gw, &bo));
@@ -1341,10 +1343,12 @@ static int render_impl(kn_ctx *ctx, const kn_scene *sc, void *stream, const floa
                                w.out4, step, term_eps, bg[0], bg[1], bg[2], rs, rgb_out, alive, w.partials, w.surv16, gw.hist,
                                fused_hist ? (int32_t)n_hist : 0, wave_no == 0 ? 1 : 0);
         KN_CHECK_LAUNCH();
-        if (post) seq = next_seq();
-        hipLaunchKernelGGL(k_sum_partials, dim3(1), dim3(1024), 0, st, w.partials, cblocks, w.surv16, groups, w.counters, ctl,
-                           ctl_next, sched, w.blk_off, w.grp_list, post ? mb_dev : (unsigned long long *)nullptr, seq);
-        KN_CHECK_LAUNCH();
+        if (closing) {
+            if (post) seq = next_seq();
+            hipLaunchKernelGGL(k_sum_partials, dim3(1), dim3(1024), 0, st, w.partials, cblocks, w.surv16, groups, w.counters, ctl,
+                               ctl_next, sched, w.blk_off, w.grp_list, post ? mb_dev : (unsigned long long *)nullptr, seq);
+            KN_CHECK_LAUNCH();
+        }
         tm.mark(KN_ST_BLEND);
         tm.add(1, 0, 0, 0);
         ++wave_no;
@@ -1376,7 +1380,7 @@ static int render_impl(kn_ctx *ctx, const kn_scene *sc, void *stream, const floa
             if (wave_index == 1 && blind_second) return !second_wave_ends_it;
             return true;
         };
-        KN_TRY(rest_of_wave(first, host_reads(0)));
+        KN_TRY(rest_of_wave(first, host_reads(0), true));
         int64_t list_cap = first; // upper bound of the length of the current live list
         while (true) {
             if (wave_no == 2 && second_wave_ends_it && !want_counts) break;
@@ -1391,7 +1395,10 @@ static int render_impl(kn_ctx *ctx, const kn_scene *sc, void *stream, const floa
             tm.begin();
             KN_TRY(march(list_cap, true)); // reads (and compacts) the old list
             list_cap = next_cap;
-            KN_TRY(rest_of_wave(list_cap, host_reads(wave_no)));
+            // (the second wave, enqueued blindly, when it ends every ray and the frame's counters are not wanted: see the
+            // loop's first line)
+            const bool last_for_sure = wave_no == 1 && second_wave_ends_it && !want_counts;
+            KN_TRY(rest_of_wave(list_cap, host_reads(wave_no), !last_for_sure));
         }
     }
     if (tm.counts || stats) {
