@@ -583,15 +583,17 @@ __global__ void __launch_bounds__(256)
     }
 }
 
-// Eq. 2-4 over this wave's samples, early termination, retiring of finished rays.  A wavefront owns 64 consecutive
-// rows.  Its lanes fetch the rows' next BLEND_CHUNK samples together (BLEND_CHUNK lanes per row and request,
+// Eq. 2-4 over this wave's samples, early termination, retiring of finished rays.  A wavefront owns 32 consecutive
+// rows (the kernel waits for its loads most of the time: with 64 rows per wavefront, half as many wavefronts, it
+// takes 1.4 us longer; with 16 rows 0.4).  Its lanes fetch the rows' next BLEND_CHUNK samples together (BLEND_CHUNK lanes per row and request,
 // consecutive addresses) and turn densities into alphas; the values go through LDS to the lane that owns the row, which runs
 // the blend as the sequential recurrence of the definition: one lane per ray, the same operation order for every
 // wave cut.  (Blending with 16 lanes per ray, all of them stepping through the recurrence on broadcast values, cost
 // 16 times the instructions.)
 // (16 samples per request: 70 KiB of LDS per workgroup, two wavefronts per SIMD, 3 us slower per frame; 4: too few loads in flight)
 constexpr int BLEND_CHUNK = 8;
-constexpr int BLEND_ROWS = 256; // rows per workgroup
+constexpr int BLEND_WAVE_ROWS = 32;                         // rows per wavefront: its first lanes own one each
+constexpr int BLEND_ROWS = (256 / KN_WAVE) * BLEND_WAVE_ROWS; // rows per workgroup
 __global__ void __launch_bounds__(256)
     k_composite_wave(const int32_t *__restrict__ live, const int32_t *__restrict__ ctl, int32_t rows_cap,
                      const int32_t *__restrict__ cnt, const float *__restrict__ out4, float step, float eps, float bg0,
@@ -603,15 +605,16 @@ __global__ void __launch_bounds__(256)
     // counters of the grouping that the next wave expects to be zero
     for (int64_t z = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; z < n_zero; z += (int64_t)gridDim.x * blockDim.x) zero[z] = 0;
     typedef float f4 __attribute__((ext_vector_type(4)));
-    __shared__ f4 stage[256 / KN_WAVE][KN_WAVE][BLEND_CHUNK + 1]; // + 1: the owner lanes' reads spread over the banks
+    __shared__ f4 stage[256 / KN_WAVE][BLEND_WAVE_ROWS][BLEND_CHUNK + 1]; // + 1: the owner lanes' reads spread over the banks
     const int32_t n_live = ctl[0], S = ctl[1];
     const int wave = threadIdx.x / KN_WAVE, lane = threadIdx.x & (KN_WAVE - 1);
-    const int32_t row0 = (int32_t)blockIdx.x * BLEND_ROWS + wave * KN_WAVE; // first row of this wavefront
+    const int32_t row0 = (int32_t)blockIdx.x * BLEND_ROWS + wave * BLEND_WAVE_ROWS; // first row of this wavefront
+    const bool owner = lane < BLEND_WAVE_ROWS;
     const int32_t i = row0 + lane;
     // the grid covers rows_cap >= n_live rows; the flags of the rows beyond the list are cleared so that the next
     // wave's compaction can run over the same upper bound
-    if (i >= n_live && i < rows_cap) alive[i] = 0;
-    const bool mine = i < n_live && alive[i] != 0;
+    if (owner && i >= n_live && i < rows_cap) alive[i] = 0;
+    const bool mine = owner && i < n_live && alive[i] != 0;
     const int32_t r = mine ? live[i] : 0;
     const int32_t n = mine ? cnt[i] : 0;
     float T = 1.0f, c0 = 0.0f, c1 = 0.0f, c2 = 0.0f; // the state of a ray before its first wave
@@ -623,12 +626,13 @@ __global__ void __launch_bounds__(256)
     }
     bool dead = false;
     int32_t blended = 0;
+    constexpr int LOADS = BLEND_WAVE_ROWS / (KN_WAVE / BLEND_CHUNK); // requests per lane and chunk
     const int sub = lane / BLEND_CHUNK, jl = lane % BLEND_CHUNK; // loader role: rows sub, sub + 64 / BLEND_CHUNK, ...; sample jl of the chunk
     for (int32_t j0 = 0; __ballot(mine && !dead && j0 < n) != 0ull; j0 += BLEND_CHUNK) {
         // fetch: KN_WAVE / BLEND_CHUNK rows per request, all requests issued before the first use
-        f4 v[BLEND_CHUNK];
+        f4 v[LOADS];
 #pragma unroll
-        for (int q = 0; q < BLEND_CHUNK; ++q) {
+        for (int q = 0; q < LOADS; ++q) {
             const int rl = q * (KN_WAVE / BLEND_CHUNK) + sub;        // row of the wavefront this lane loads for
             const int32_t n_l = __shfl(n, rl, KN_WAVE);
             const int32_t gone = __shfl((int32_t)dead, rl, KN_WAVE);
@@ -639,7 +643,7 @@ __global__ void __launch_bounds__(256)
         }
         __builtin_amdgcn_wave_barrier(); // the owners have finished reading the previous chunk
 #pragma unroll
-        for (int q = 0; q < BLEND_CHUNK; ++q) {
+        for (int q = 0; q < LOADS; ++q) {
             v[q][3] = 1.0f - expf(-v[q][3] * step); // alpha (Eq. 4)
             stage[wave][q * (KN_WAVE / BLEND_CHUNK) + sub][jl] = v[q];
         }
@@ -681,7 +685,7 @@ __global__ void __launch_bounds__(256)
     // survivors per group of 16 rows (the next wave's march compacts the list in those groups)
     {
         const unsigned long long sv = __ballot(lives);
-        if (lane < KN_WAVE / MARCH_G) {
+        if (lane < BLEND_WAVE_ROWS / MARCH_G) {
             const int32_t grp = row0 / MARCH_G + lane;
             if ((int64_t)grp * MARCH_G < rows_cap) surv16[grp] = __builtin_popcountll((sv >> (MARCH_G * lane)) & ((1ull << MARCH_G) - 1ull));
         }
