@@ -209,7 +209,43 @@ __global__ void __launch_bounds__(GROUP_THREADS)
             });
     } else {
         __syncthreads(); // counters cleared, histogram staged
-        if (nr > 0) sweep(0, N, first_rows, [&](int32_t k, int64_t, int32_t len) { atomicAdd(&bins[k], len); });
+        // heads and lengths of the runs of equal keys among the eight samples of a lane's two chunks (straight-line code)
+        auto runs8 = [&](i4 va, i4 vb, int32_t ja, int32_t jb, int32_t c, int32_t (&key)[8], int32_t (&len)[8], bool (&valid)[8],
+                         bool (&head)[8]) {
+#pragma unroll
+            for (int q = 0; q < 8; ++q) {
+                key[q] = q < 4 ? va[q] : vb[q - 4];
+                valid[q] = (q < 4 ? ja + q : jb + q - 4) < c && (uint32_t)key[q] < (uint32_t)N;
+            }
+#pragma unroll
+            for (int q = 0; q < 8; ++q) head[q] = valid[q] && ((q & 3) == 0 || !valid[q - 1] || key[q - 1] != key[q]);
+#pragma unroll
+            for (int q = 7; q >= 0; --q) len[q] = valid[q] ? 1 + (((q & 3) != 3 && valid[q + 1] && !head[q + 1]) ? len[q + 1] : 0) : 0;
+        };
+        // f(current row set, its two chunks, their first sample numbers) for every pair of chunks of the workgroup's rows
+        auto pairs = [&](RowLoad next /* = fetch_rows(0) */, auto &&f) {
+            for (int32_t rs = 0; rs < nr; rs += rows_per_set) {
+                const RowLoad cur = next;
+                if (rs + rows_per_set < nr) next = fetch_rows(rs + rows_per_set);
+                i4 va = cur.va, vb = cur.vb;
+                for (int32_t ch = g; 4 * ch < cur.c; ch += 2 * G) {
+                    if (ch != g) { // rows longer than two chunks per lane
+                        va = load_chunk(cur.base, ch);
+                        vb = load_chunk(cur.base, ch + G);
+                    }
+                    f(cur, va, vb, 4 * ch, 4 * (ch + G));
+                }
+            }
+        };
+        if (nr > 0)
+            pairs(first_rows, [&](const RowLoad &cur, i4 va, i4 vb, int32_t ja, int32_t jb) {
+                int32_t key[8], len[8];
+                bool valid[8], head[8];
+                runs8(va, vb, ja, jb, cur.c, key, len, valid, head);
+#pragma unroll
+                for (int q = 0; q < 8; ++q)
+                    if (head[q]) atomicAdd(&bins[key[q]], len[q]);
+            });
         __syncthreads();
         // exclusive offsets of all groups: thread t owns the bins t, t + 256, ... and lays them out in a row
         int32_t total;
@@ -255,45 +291,23 @@ __global__ void __launch_bounds__(GROUP_THREADS)
             write_tiles(tiles, mine_b, off_mine, c, tiles_of(c, tile_len), tpos, tile_len, lane);
         }
         __syncthreads(); // every bin this workgroup met holds the absolute position of its first sample
-        // Filling sweep.  The eight samples of a lane's two chunks in straight-line code: the first sample of every run of
-        // equal keys takes the run's place with one returning LDS atomic, and all of those are issued before the first
-        // result is used (taken run by run, each atomic's latency sat in front of the next).
-        auto fill = [&](i4 va, i4 vb, int64_t base, int32_t ja, int32_t jb, int32_t c) {
-            int32_t key[8], len[8], pos[8];
-            bool valid[8], head[8];
+        // Filling sweep: the first sample of every run takes the run's place with one returning LDS atomic, and all of
+        // a lane's are issued before the first result is used (taken run by run, each atomic's latency sat in front of
+        // the next).
+        if (nr > 0)
+            pairs(fetch_rows(0), [&](const RowLoad &cur, i4 va, i4 vb, int32_t ja, int32_t jb) {
+                int32_t key[8], len[8], pos[8];
+                bool valid[8], head[8];
+                runs8(va, vb, ja, jb, cur.c, key, len, valid, head);
 #pragma unroll
-            for (int q = 0; q < 8; ++q) {
-                key[q] = q < 4 ? va[q] : vb[q - 4];
-                valid[q] = (q < 4 ? ja + q : jb + q - 4) < c && (uint32_t)key[q] < (uint32_t)N;
-            }
+                for (int q = 0; q < 8; ++q) pos[q] = head[q] ? atomicAdd(&bins[key[q]], len[q]) : 0;
 #pragma unroll
-            for (int q = 0; q < 8; ++q) head[q] = valid[q] && ((q & 3) == 0 || !valid[q - 1] || key[q - 1] != key[q]);
+                for (int q = 0; q < 8; ++q)
+                    if (valid[q] && !head[q]) pos[q] = pos[q - 1] + 1;
 #pragma unroll
-            for (int q = 7; q >= 0; --q) len[q] = valid[q] ? 1 + (((q & 3) != 3 && valid[q + 1] && !head[q + 1]) ? len[q + 1] : 0) : 0;
-#pragma unroll
-            for (int q = 0; q < 8; ++q) pos[q] = head[q] ? atomicAdd(&bins[key[q]], len[q]) : 0;
-#pragma unroll
-            for (int q = 0; q < 8; ++q)
-                if (valid[q] && !head[q]) pos[q] = pos[q - 1] + 1;
-#pragma unroll
-            for (int q = 0; q < 8; ++q)
-                if (valid[q]) perm[pos[q]] = (int32_t)(base + (q < 4 ? ja + q : jb + q - 4));
-        };
-        if (nr > 0) {
-            RowLoad next = fetch_rows(0);
-            for (int32_t rs = 0; rs < nr; rs += rows_per_set) {
-                const RowLoad cur = next;
-                if (rs + rows_per_set < nr) next = fetch_rows(rs + rows_per_set);
-                i4 va = cur.va, vb = cur.vb;
-                for (int32_t ch = g; 4 * ch < cur.c; ch += 2 * G) {
-                    if (ch != g) { // rows longer than two chunks per lane
-                        va = load_chunk(cur.base, ch);
-                        vb = load_chunk(cur.base, ch + G);
-                    }
-                    fill(va, vb, cur.base, 4 * ch, 4 * (ch + G), cur.c);
-                }
-            }
-        }
+                for (int q = 0; q < 8; ++q)
+                    if (valid[q]) perm[pos[q]] = (int32_t)(cur.base + (q < 4 ? ja + q : jb + q - 4));
+            });
     }
 }
 
