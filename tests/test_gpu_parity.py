@@ -523,6 +523,21 @@ def test_render_config5_small():
     render_check(cfg)
 
 
+def test_render_without_counts_equals_render_with_counts():
+    """A frame whose second wave is known to be the last leaves out the sums that close a wave unless the caller asks
+    for the frame's counts: the image must not depend on that."""
+    cfg = configs.config3(80, 80)
+    dev, _ = make_pair(cfg["scene"])
+    o, d = cuda(cfg["rays_o"]), cuda(cfg["rays_d"])
+    args = (cfg["t_near"], cfg["step"], cfg["K"], cfg["term_eps"], cfg["bg"])
+    plain = [dev.render(o, d, *args).cpu().numpy() for _ in range(3)]
+    counted, st = dev.render(o, d, *args, want_stats=True)
+    assert st["waves"] == 2
+    for img in plain:
+        np.testing.assert_array_equal(img, counted.cpu().numpy())
+    np.testing.assert_array_equal(dev.render(o, d, *args).cpu().numpy(), plain[0])  # and again after a counted frame
+
+
 def test_render_is_independent_of_wave_cut_and_deterministic():
     import paper_2103_13744_amd as kn
     cfg = configs.config3(80, 80)
