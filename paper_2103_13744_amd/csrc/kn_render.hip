@@ -506,6 +506,36 @@ __global__ void __launch_bounds__(256)
     // (uniform exits: the grid is sized for an upper bound of the rows / of the groups with survivors)
     const int32_t n_groups = blk_off ? ctl[3] : 0;
     if (blk_off ? (int64_t)blockIdx.x * GROUPS >= n_groups : (int64_t)blockIdx.x * RAYS >= n_in) return;
+    // Which ray this lane group marches, and its data, are requested before the counters are cleared: the dependent
+    // loads (list entry -> ray number -> ray, resume point) are then in flight during the clearing and its barrier.
+    int32_t i_in; // this ray's row in the list that is read
+    bool lives;
+    int32_t i;    // its row in the wave's buffers
+    if (!blk_off) {
+        i_in = (int32_t)(((int64_t)blockIdx.x * T + threadIdx.x) / G);
+        lives = i_in < n_in && alive[i_in] != 0;
+        i = i_in;
+    } else {
+        // The list is compacted in groups of LIST_GROUP = 16 rows (blk_off[g]: new row of group g's first survivor), and
+        // the kernel runs over the groups that have survivors (grp_list, ctl[3] of them), so that the workgroups with
+        // work are the first of the grid.  The 16 lanes of a DPP row fetch the flags of the group their row's ray belongs
+        // to (8 lanes per ray: the two rays of a row are neighbours inside one group).
+        const int32_t ray = threadIdx.x / G;                                  // ray of the workgroup
+        const int64_t slot = (int64_t)blockIdx.x * GROUPS + ray / LIST_GROUP; // entry of the group list
+        const int32_t g16 = slot < n_groups ? grp_list[slot] : -1;
+        i_in = g16 >= 0 ? LIST_GROUP * g16 + (ray & (LIST_GROUP - 1)) : n_in;
+        lives = i_in < n_in && alive[i_in] != 0;
+        const int32_t q = LIST_GROUP * max(g16, 0) + (lane & (LIST_GROUP - 1));
+        const bool f = g16 >= 0 && q < n_in && alive[q] != 0;
+        const uint32_t flags = (uint32_t)(__ballot(f) >> (lane & ~(LIST_GROUP - 1))) & ((1u << LIST_GROUP) - 1u);
+        i = lives ? blk_off[g16] + __popc(flags & ((1u << (i_in & (LIST_GROUP - 1))) - 1u)) : 0;
+    }
+    // (every lane loads: a retired or absent row reads the data of a valid list entry and drops it)
+    const int32_t r = live[min(i_in, n_in - 1)];
+    const float o[3] = {rays_o[3 * (int64_t)r], rays_o[3 * (int64_t)r + 1], rays_o[3 * (int64_t)r + 2]};
+    const float d[3] = {rays_d[3 * (int64_t)r], rays_d[3 * (int64_t)r + 1], rays_d[3 * (int64_t)r + 2]};
+    int32_t k = s.k_next[r];
+    const int32_t k_hi = s.k_end[r];
     for (int32_t b = threadIdx.x; b < n_lds; b += T) bins[b] = (HASH && b < hash_slots) ? -1 : 0;
     __syncthreads();
     // one more sample of network `cell`
@@ -526,23 +556,15 @@ __global__ void __launch_bounds__(256)
         }
         atomicAdd(&hist[cell], 1); // no slot nearby: straight to the global histogram
     };
-    // the ray of row i_in of the list that is read (if it lives), into row i of the wave's buffers
-    auto march_ray = [&](int32_t i_in, bool lives, int32_t i) {
-        if (!lives) {
-            // without compaction retired rows stay in the list: they get no samples
-            if (!blk_off && i_in < n_in && gl == 0) cnt[i_in] = 0;
-            return;
-        }
-        const int32_t r = live[i_in];
+    if (!lives) {
+        // without compaction retired rows stay in the list: they get no samples
+        if (!blk_off && i_in < n_in && gl == 0) cnt[i_in] = 0;
+    } else {
         if (blk_off && gl == 0) {
             live_out[i] = r;
             alive_out[i] = 1;
         }
-        const float o[3] = {rays_o[3 * (int64_t)r], rays_o[3 * (int64_t)r + 1], rays_o[3 * (int64_t)r + 2]};
-        const float d[3] = {rays_d[3 * (int64_t)r], rays_d[3 * (int64_t)r + 1], rays_d[3 * (int64_t)r + 2]};
         const GridFast gn = make_fast(p.net), go = make_fast(p.occ);
-        int32_t k = s.k_next[r];
-        const int32_t k_hi = s.k_end[r];
         int32_t *kr = row_keys + (int64_t)i * S;
         uint32_t *rr = row_rec + (int64_t)i * S;
         const uint32_t ray_key = kn_mix32(p.seed_key + (uint32_t)r);
@@ -555,24 +577,6 @@ __global__ void __launch_bounds__(256)
             s.k_next[r] = k;
             cnt[i] = n;
         }
-    };
-    if (!blk_off) {
-        const int32_t i_in = (int32_t)(((int64_t)blockIdx.x * T + threadIdx.x) / G);
-        march_ray(i_in, i_in < n_in && alive[i_in] != 0, i_in);
-    } else {
-        // The list is compacted in groups of LIST_GROUP = 16 rows (blk_off[g]: new row of group g's first survivor), and
-        // the kernel runs over the groups that have survivors (grp_list, ctl[3] of them), so that the workgroups with
-        // work are the first of the grid.  The 16 lanes of a DPP row fetch the flags of the group their row's ray belongs
-        // to (8 lanes per ray: the two rays of a row are neighbours inside one group).
-        const int32_t ray = threadIdx.x / G;                                  // ray of the workgroup
-        const int64_t slot = (int64_t)blockIdx.x * GROUPS + ray / LIST_GROUP; // entry of the group list
-        const int32_t g16 = slot < n_groups ? grp_list[slot] : -1;
-        const int32_t i_in = g16 >= 0 ? LIST_GROUP * g16 + (ray & (LIST_GROUP - 1)) : n_in;
-        const bool lives = i_in < n_in && alive[i_in] != 0;
-        const int32_t q = LIST_GROUP * max(g16, 0) + (lane & (LIST_GROUP - 1));
-        const bool f = g16 >= 0 && q < n_in && alive[q] != 0;
-        const uint32_t flags = (uint32_t)(__ballot(f) >> (lane & ~(LIST_GROUP - 1))) & ((1u << LIST_GROUP) - 1u);
-        march_ray(i_in, lives, lives ? blk_off[g16] + __popc(flags & ((1u << (i_in & (LIST_GROUP - 1))) - 1u)) : 0);
     }
     // the few bins this workgroup met go to the global histogram
     __syncthreads();
