@@ -642,8 +642,10 @@ __global__ void __launch_bounds__(256)
             const int32_t gone = __shfl((int32_t)dead, rl, KN_WAVE);
             const bool need = j0 + jl < n_l && !gone;
             const int64_t at = (int64_t)min(row0 + rl, n_live - 1) * S + min(j0 + jl, S - 1); // always a slot of the wave
-            v[q] = ((const f4 *)out4)[at];
-            if (!need) v[q] = (f4){0.0f, 0.0f, 0.0f, 0.0f};
+            // (only what the blend will use is requested: the kernel moves data at the rate of a device copy, and the
+            // samples behind a ray's termination point are a third of the wave's)
+            v[q] = (f4){0.0f, 0.0f, 0.0f, 0.0f};
+            if (need) v[q] = ((const f4 *)out4)[at];
         }
         __builtin_amdgcn_wave_barrier(); // the owners have finished reading the previous chunk
 #pragma unroll
