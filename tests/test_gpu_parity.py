@@ -250,6 +250,28 @@ def test_eval_grouped_reordering_edge_cases(res, M, mode):
         assert torch.equal(a, b)
 
 
+def test_eval_grouped_on_arrays_that_start_off_a_sixteen_byte_boundary():
+    """Points and directions are fp32 arrays with 4-byte alignment as far as the interface goes; the key kernel reads
+    whole tiles of an aligned array 16 bytes at a time and anything else element by element.  Same results either way."""
+    import torch
+    sc = scene_dict((5, 4, 6), (-1, -1, -1), (1, 1, 1), 32, "f16", 71)
+    dev, _ = make_pair(sc)
+    M = 3 * 4096 + 17
+    pts, dirs = ks.uniform_points(M, 72, lo=(-1.05,) * 3, hi=(1.05,) * 3), ks.sphere_dirs(M, 73)
+    want = dev.eval_grouped(cuda(pts), cuda(dirs), want_aux=True)
+    for shift in (1, 2, 3):                                      # floats in front of the arrays
+        flat_p = torch.zeros(3 * M + shift, dtype=torch.float32, device="cuda")
+        flat_d = torch.zeros(3 * M + shift, dtype=torch.float32, device="cuda")
+        p_off, d_off = flat_p[shift:].view(M, 3), flat_d[shift:].view(M, 3)
+        p_off.copy_(cuda(pts))
+        d_off.copy_(cuda(dirs))
+        assert p_off.data_ptr() % 16 == 4 * shift and p_off.is_contiguous()
+        got = dev.eval_grouped(p_off, d_off, want_aux=True)
+        torch.cuda.synchronize()
+        for a, b in zip(got, want):
+            assert torch.equal(a, b)
+
+
 def test_eval_grouped_reordering_with_sixteen_key_bits():
     """32^3 networks: keys need 16 bits, two passes of 8."""
     sc = scene_dict((32, 32, 32), (0, 0, 0), (1, 1, 1), 32, "f16", 66)
