@@ -9,6 +9,12 @@ Sums are kept in fp64 (an fp32 accumulator differs from that by about 1e-7 relat
 below a 16-bit rounding); the density and the colour are not rounded.  It says nothing about any kernel's
 internals beyond "operands are 16 bit, sums are not", and shares no code with the HIP path.
 
+`fold=True` is the same model for an evaluation that takes layer 3's feature vector and layer 4 as one affine map:
+Sec. 3.2 puts no activation between them, so W4f^T (W3f^T h2 + b3f) + W4d^T gamma(d) + b4 equals
+(W3f W4f)^T h2 + W4d^T gamma(d) + (b4 + W4f^T b3f).  The operands of that product are h2, gamma(d), the matrix
+W3f W4f and the bias b4 + W4f^T b3f, the last two rounded to the storage type like every other operand; the feature
+vector itself is then never rounded.
+
 Uses: tests compare it with the fp64 oracle to measure how much of an error budget rounding alone takes (the
 answer depends on the scene: a density error is multiplied by the sample spacing in Eq. 4), and compare the HIP
 path with it at a far tighter tolerance than the 16-bit bar allows against the fp64 oracle.
@@ -54,8 +60,9 @@ def _layers(w: np.ndarray, H: int, L_pos: int, L_dir: int):
     return out
 
 
-def mlp_one_network(w, H: int, x, d, dtype: str, L_pos: int = 10, L_dir: int = 4):
-    """One network (its P canonical parameters, already representable in `dtype`) on M inputs -> sigma (M), rgb (M, 3)."""
+def mlp_one_network(w, H: int, x, d, dtype: str, L_pos: int = 10, L_dir: int = 4, fold: bool = False):
+    """One network (its P canonical parameters, already representable in `dtype`) on M inputs -> sigma (M), rgb (M, 3).
+    fold: feature layer and layer 4 as one affine map of the second hidden vector (see the module's header)."""
     (W1, b1), (W2, b2), (W3, b3), (W4, b4), (W5, b5) = _layers(np.asarray(w), H, L_pos, L_dir)
     rnd = lambda a: round_operand(a, dtype)
     gx = rnd(_gamma(np.asarray(x, np.float32).reshape(-1, 3), L_pos))
@@ -64,20 +71,24 @@ def mlp_one_network(w, H: int, x, d, dtype: str, L_pos: int = 10, L_dir: int = 4
     h2 = rnd(np.maximum(h1 @ W2 + b2, 0.0))
     o3 = h2 @ W3 + b3
     sigma = np.maximum(o3[:, 0], 0.0)
-    feat = rnd(o3[:, 1:])
-    h4 = rnd(np.maximum(np.concatenate([feat, gd], axis=1) @ W4 + b4, 0.0))
+    if fold:
+        W34, b34 = rnd(W3[:, 1:] @ W4[:H]), rnd(b4 + b3[1:] @ W4[:H])
+        h4 = rnd(np.maximum(h2 @ W34 + gd @ W4[H:] + b34, 0.0))
+    else:
+        feat = rnd(o3[:, 1:])
+        h4 = rnd(np.maximum(np.concatenate([feat, gd], axis=1) @ W4 + b4, 0.0))
     rgb = 1.0 / (1.0 + np.exp(-(h4 @ W5 + b5)))
     return sigma, rgb
 
 
-def eval_points(weights, H: int, ids, points, dirs, dtype: str):
+def eval_points(weights, H: int, ids, points, dirs, dtype: str, fold: bool = False):
     """eval_grouped under the rounding model: `ids` are the network ids of the points (-1: none -> zeros)."""
     ids = np.asarray(ids)
     M = len(ids)
     sigma, rgb = np.zeros(M), np.zeros((M, 3))
     for n in np.unique(ids[ids >= 0]):
         sel = np.nonzero(ids == n)[0]
-        sigma[sel], rgb[sel] = mlp_one_network(weights[n], H, points[sel], dirs[sel], dtype)
+        sigma[sel], rgb[sel] = mlp_one_network(weights[n], H, points[sel], dirs[sel], dtype, fold=fold)
     return sigma, rgb
 
 

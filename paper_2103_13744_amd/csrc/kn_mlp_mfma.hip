@@ -23,7 +23,14 @@
 //                       g = 3: kb 0: x f8, x f9, y f8, y f9 (sin, cos each);
 //                              kb 1: z f8, z f9, then x, y, z, 1 (the 1 multiplies the bias b1)
 //   gamma(d), 32 slots: g < 3: axis g, frequency j/2, sin/cos;  g = 3: dx, dy, dz, 1 (bias b4), 0 x 4
-// Biases b1 and b4 ride in the constant-1 slots; b2, b3, b5 initialise the accumulators.
+// Biases b1 and b4 ride in the constant-1 slots; b2, b5 and the density bias initialise the accumulators.
+//
+// Feature layer.  Layer 3's feature vector has no activation (Sec. 3.2: it is handed to the last hidden layer together
+// with gamma(d)), so feature layer and layer 4 are one affine map of the second hidden vector h2:
+//   W4f^T (W3f^T h2 + b3f) + W4d^T gamma(d) + b4 = (W3f W4f)^T h2 + W4d^T gamma(d) + (b4 + W4f^T b3f).
+// k_pack_weights forms W3f W4f and the bias once per scene (fp32 sums, rounded to the scene's 16-bit type like every
+// other operand), and the kernels evaluate layer 4 on h2 directly: per 16 samples H/16 * H/32 MFMAs and H/8 conversions
+// fewer, and the feature vector is never rounded to 16 bit.  Layer 3 proper is then the density row alone.
 //
 // Density and colour.  Layer 3's density row and layer 5's three colour rows would each waste a
 // 16-row output tile.  Instead four sample tiles (64 samples) share one extra accumulator: for
@@ -67,12 +74,12 @@ template <int H> struct Lay {
     static constexpr int HT = H / 16, HK = H / 32;
     static constexpr int L1 = 0;                          // (t, kb) -> L1 + 2t + kb
     static constexpr int L2 = L1 + 2 * HT;                // (t, kb) -> L2 + t*HK + kb
-    static constexpr int L3 = L2 + HT * HK;               // feature rows
-    static constexpr int LS = L3 + HT * HK;               // density row, (kb)
-    static constexpr int L4 = LS + HK;                    // (t, kb) -> L4 + t*(HK+1) + kb, kb = HK: gamma(d)
+    static constexpr int LS = L2 + HT * HK;               // density row of layer 3, (kb)
+    static constexpr int L4 = LS + HK;                    // (t, kb) -> L4 + t*(HK+1) + kb; kb < HK: h2 through the folded
+                                                          // feature layer, kb = HK: gamma(d)
     static constexpr int L5 = L4 + HT * (HK + 1);         // colour rows, (kb)
     static constexpr int NBLK = L5 + HK;
-    static constexpr int TAIL_FLOATS = 2 * H + 4;         // b2[H], b3 feature[H], b5[3], b3 density
+    static constexpr int TAIL_FLOATS = H + 4;             // b2[H], b5[3], b3 density
     static constexpr int HALFS = NBLK * 512 + TAIL_FLOATS * 2;
     // canonical offsets
     static constexpr int oW1 = 0, ob1 = 63 * H, oW2 = ob1 + H, ob2 = oW2 + H * H, oW3 = ob2 + H,
@@ -99,7 +106,9 @@ __host__ __device__ inline int dir_row(int g, int j)
     return j == 3 ? -1 : -2;
 }
 
-// source element (canonical index) of packed 16-bit element e of one network; -1 = zero
+// source element (canonical index) of packed 16-bit element e of one network; -1 = zero; FOLD_ROW - (k * H + col):
+// element (k, col) of the product of feature layer and layer 4; FOLD_BIAS - col: element col of the folded bias
+constexpr int FOLD_ROW = -2, FOLD_BIAS = -2 - 64 * 64;
 template <int H> __device__ int pack_source(int e)
 {
     using L = Lay<H>;
@@ -108,13 +117,9 @@ template <int H> __device__ int pack_source(int e)
         const int t = (blk - L::L1) >> 1, kb = (blk - L::L1) & 1, col = 16 * t + m, r = l1_row(kb, g, j);
         return r < 63 ? L::oW1 + r * H + col : L::ob1 + col;
     }
-    if (blk < L::L3) {
+    if (blk < L::LS) {
         const int t = (blk - L::L2) / L::HK, kb = (blk - L::L2) % L::HK;
         return L::oW2 + hid_feat(kb, g, j) * H + 16 * t + m;
-    }
-    if (blk < L::LS) {
-        const int t = (blk - L::L3) / L::HK, kb = (blk - L::L3) % L::HK;
-        return L::oW3 + hid_feat(kb, g, j) * (H + 1) + 1 + 16 * t + m;
     }
     if (blk < L::L4) {
         const int kb = blk - L::LS;
@@ -122,10 +127,10 @@ template <int H> __device__ int pack_source(int e)
     }
     if (blk < L::L5) {
         const int t = (blk - L::L4) / (L::HK + 1), kb = (blk - L::L4) % (L::HK + 1), col = 16 * t + m;
-        if (kb < L::HK) return L::oW4 + hid_feat(kb, g, j) * H + col;
+        if (kb < L::HK) return FOLD_ROW - (hid_feat(kb, g, j) * H + col); // column `col` of row hid_feat of W3f W4f
         const int r = dir_row(g, j);
         if (r == -2) return -1;
-        return r == -1 ? L::ob4 + col : L::oW4 + (H + r) * H + col;
+        return r == -1 ? FOLD_BIAS - col : L::oW4 + (H + r) * H + col;     // b4 + W4f^T b3f
     }
     const int kb = blk - L::L5;
     return (m & 3) < 3 ? L::oW5 + hid_feat(kb, g, j) * 3 + (m & 3) : -1;
@@ -135,8 +140,7 @@ template <int H> __device__ int tail_source(int q)
 {
     using L = Lay<H>;
     if (q < H) return L::ob2 + q;
-    if (q < 2 * H) return L::ob3 + 1 + (q - H);
-    if (q < 2 * H + 3) return L::ob5 + (q - 2 * H);
+    if (q < H + 3) return L::ob5 + (q - H);
     return L::ob3;
 }
 
@@ -146,8 +150,19 @@ __device__ __forceinline__ float half_bits_to_float(uint16_t v, bool bf)
     return (float)__builtin_bit_cast(_Float16, v);
 }
 
+// fp32 -> the scene's 16-bit type, round to nearest even
+__device__ __forceinline__ uint16_t float_to_half_bits(float v, bool bf)
+{
+    if (!bf) return __builtin_bit_cast(uint16_t, (_Float16)v);
+    const uint32_t u = __float_as_uint(v);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)0x7fc0; // NaN
+    return (uint16_t)((u + 0x7fffu + ((u >> 16) & 1u)) >> 16);
+}
+
+// `overflow`: set when a folded element leaves the range of the 16-bit type although its factors are finite
 template <int H>
-__global__ void k_pack_weights(const uint16_t *__restrict__ w, int64_t P, int32_t N, bool bf, uint16_t *__restrict__ packed)
+__global__ void k_pack_weights(const uint16_t *__restrict__ w, int64_t P, int32_t N, bool bf, uint16_t *__restrict__ packed,
+                               int32_t *__restrict__ overflow)
 {
     using L = Lay<H>;
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -159,13 +174,29 @@ __global__ void k_pack_weights(const uint16_t *__restrict__ w, int64_t P, int32_
     uint16_t *dst = packed + net * (int64_t)L::HALFS;
     if (e < L::NBLK * 512) {
         const int s = pack_source<H>(e);
-        dst[e] = s < 0 ? (uint16_t)0 : src[s];
+        if (s >= -1) {
+            dst[e] = s < 0 ? (uint16_t)0 : src[s];
+        } else {
+            // feature layer folded into layer 4 (Sec. 3.2: no activation between them): sum over the feature index f of
+            // (row k of W3's feature columns, or b3's feature part) times W4's feature row f, fp32, in index order
+            const bool bias = s <= FOLD_BIAS;
+            const int k = bias ? 0 : (FOLD_ROW - s) / H, col = bias ? FOLD_BIAS - s : (FOLD_ROW - s) % H;
+            float acc = bias ? half_bits_to_float(src[L::ob4 + col], bf) : 0.0f;
+            for (int f = 0; f < H; ++f) {
+                const float a = half_bits_to_float(bias ? src[L::ob3 + 1 + f] : src[L::oW3 + k * (H + 1) + 1 + f], bf);
+                acc = fmaf(a, half_bits_to_float(src[L::oW4 + f * H + col], bf), acc);
+            }
+            const uint16_t r = float_to_half_bits(acc, bf);
+            if (isfinite(acc) && !isfinite(half_bits_to_float(r, bf))) atomicOr(overflow, 1);
+            dst[e] = r;
+        }
     } else {
         const int q = e - L::NBLK * 512;
         const float v = half_bits_to_float(src[tail_source<H>(q)], bf);
         ((float *)(dst + L::NBLK * 512))[q] = v;
     }
 }
+__global__ void k_clear_flag(int32_t *flag) { *flag = 0; }
 
 // ---------------------------------------------------------------------------------------------
 template <bool BF> __device__ __forceinline__ f4 mfma(u4 a, u4 b, f4 c)
@@ -231,7 +262,7 @@ template <bool BF> __device__ __forceinline__ u4 encode_direction(float rev, u4 
                 pk<BF>(s[2], m[2]), pk<BF>(s[3], m[3])};
 }
 
-// Weights stay in registers: 14 blocks (56 VGPRs) for H = 32, three wavefronts per SIMD; 40 blocks (160 VGPRs) for
+// Weights stay in registers: 12 blocks (48 VGPRs) for H = 32, three wavefronts per SIMD; 32 blocks (128 VGPRs) for
 // H = 64, two wavefronts per SIMD (the matrix-core operands are read straight from the register file either way).
 // STRAT (render with stratified sampling): the lattice points sit at their drawn offsets and the density is
 // scaled by delta_k / step on the way out (see KnSampleSrc).
@@ -288,7 +319,7 @@ __global__ void __launch_bounds__(WAVES *KN_WAVE) __attribute__((amdgpu_waves_pe
     // accumulator, fed by the unmasked blocks (whose rows repeat with period four), and lane group g keeps tile g.
     constexpr bool SHARED_OUT = H == 32;
     u4 a_sig[SHARED_OUT ? 4 : 1][HK], a_col[SHARED_OUT ? 4 : 1][HK];
-    f4 bias2[HT], bias3[HT], bias_out;
+    f4 bias2[HT], bias_out;
     auto load_network = [&](int32_t net) {
         const u4 *__restrict__ wp = (const u4 *)(packed + (int64_t)net * L::HALFS);
 #pragma unroll
@@ -304,11 +335,8 @@ __global__ void __launch_bounds__(WAVES *KN_WAVE) __attribute__((amdgpu_waves_pe
         }
         const float *__restrict__ tail = (const float *)(wp + NBLK * KN_WAVE);
 #pragma unroll
-        for (int t = 0; t < HT; ++t) {
-            bias2[t] = *(const f4 *)(tail + 16 * t + 4 * g);
-            bias3[t] = *(const f4 *)(tail + H + 16 * t + 4 * g);
-        }
-        bias_out = *(const f4 *)(tail + 2 * H);
+        for (int t = 0; t < HT; ++t) bias2[t] = *(const f4 *)(tail + 16 * t + 4 * g);
+        bias_out = *(const f4 *)(tail + H);
     };
 
     // Input pipeline.  A sample's inputs sit behind a chain of dependent loads (tile descriptor -> sorted
@@ -393,19 +421,18 @@ __global__ void __launch_bounds__(WAVES *KN_WAVE) __attribute__((amdgpu_waves_pe
 
     // The hardware issues from the oldest ready wavefront first, so the wavefronts that share a SIMD would finish
     // one after the other and the last one would run alone; a wavefront lowers its own issue priority as it gets
-    // through its range (in quarters), which lets the ones behind catch up and ends all of them together.
-    const int quarter = max((t_hi - t_lo + 3) >> 2, 1);
-    int next_drop = t_lo + quarter, prio = 3;
+    // through its range, which lets the ones behind catch up and ends all of them together.  The steps are at a half,
+    // a quarter and an eighth of the range to go: what the wavefronts drift apart after the last step is what they end
+    // apart (time stamps per tile: with steps at the quarters of the range the ends of a SIMD's three wavefronts lay
+    // 9 us apart in a 58 us launch, with these 6.5).
+    const int n_t = t_hi - t_lo;
+    const int drop_to_2 = t_hi - (n_t >> 1), drop_to_1 = t_hi - (n_t >> 2), drop_to_0 = t_hi - (n_t >> 3);
     __builtin_amdgcn_s_setprio(3);
 
     for (int t = t_lo; t < t_hi; ++t) {
-        if (t == next_drop) { // uniform
-            next_drop += quarter;
-            --prio;
-            if (prio == 2) __builtin_amdgcn_s_setprio(2);
-            else if (prio == 1) __builtin_amdgcn_s_setprio(1);
-            else __builtin_amdgcn_s_setprio(0);
-        }
+        if (t == drop_to_2) __builtin_amdgcn_s_setprio(2); // (uniform; the lowest wins where steps coincide)
+        if (t == drop_to_1) __builtin_amdgcn_s_setprio(1);
+        if (t == drop_to_0) __builtin_amdgcn_s_setprio(0);
         const KnTile tl = dsc0;
         if (tl.net != net_cur) { // uniform
             load_network(tl.net);
@@ -484,20 +511,14 @@ __global__ void __launch_bounds__(WAVES *KN_WAVE) __attribute__((amdgpu_waves_pe
                     for (int kb = 0; kb < HK; ++kb) acc[t] = mfma<BF>(A(L::L2 + t * HK + kb), Bh[kb], acc[t]);
                 }
                 pack_acts<H, BF, true>(acc, Bh);
-                // layer 3: H -> feature (no activation) and density (row 4u+3 of the shared tile)
-#pragma unroll
-                for (int t = 0; t < HT; ++t) {
-                    acc[t] = bias3[t];
-#pragma unroll
-                    for (int kb = 0; kb < HK; ++kb) acc[t] = mfma<BF>(A(L::L3 + t * HK + kb), Bh[kb], acc[t]);
-                }
+                // layer 3: the density (row 4u+3 of the shared tile); its feature vector is folded into layer 4
 #pragma unroll
                 for (int kb = 0; kb < HK; ++kb) {
                     if constexpr (SHARED_OUT) outs[0] = mfma<BF>(a_sig[u][kb], Bh[kb], outs[0]);
                     else outs[u] = mfma<BF>(A(L::LS + kb), Bh[kb], outs[u]);
                 }
-                pack_acts<H, BF, false>(acc, Bh);
-                // layer 4: [feature, gamma(d)] -> H, ReLU (bias through the constant-1 slot)
+                // layer 4: [second hidden vector through the folded feature layer, gamma(d)] -> H, ReLU (bias through
+                // the constant-1 slot)
 #pragma unroll
                 for (int t = 0; t < HT; ++t) {
                     acc[t] = mfma<BF>(A(L::L4 + t * (HK + 1) + HK), Bd, zero4);
@@ -575,7 +596,7 @@ __global__ void __launch_bounds__(WAVES *KN_WAVE) __attribute__((amdgpu_waves_pe
         const float *__restrict__ tail = (const float *)(wp + L::NBLK * KN_WAVE);
 #pragma unroll
         for (int t = 0; t < HT; ++t) bias2[t] = *(const f4 *)(tail + 16 * t + 4 * g);
-        bias_sig = tail[2 * H + 3];
+        bias_sig = tail[H + 3];
     };
     int32_t net_loaded = -1;
 
@@ -713,9 +734,9 @@ __global__ void __launch_bounds__(WAVES *KN_WAVE)
     }
 }
 
-// LAYER 1..5 of Sec. 3.2: 1: gamma(x) -> ha; 2: ha -> hb; 3: hb -> ha (feature) and the density; 4: [ha, gamma(d)] -> hb;
-// 5: hb -> colour.  Tiles are dealt out as in k_mlp_mfma (a contiguous range per wavefront, weights re-fetched when
-// the network changes).
+// LAYER 1..5 of Sec. 3.2: 1: gamma(x) -> ha; 2: ha -> hb; 3: hb -> the density (its feature vector is folded into layer
+// 4, as in the fused kernel); 4: [hb, gamma(d)] -> ha; 5: ha -> colour.  Tiles are dealt out as in k_mlp_mfma (a
+// contiguous range per wavefront, weights re-fetched when the network changes).
 template <int H, bool BF, int WAVES, int LAYER>
 __global__ void __launch_bounds__(WAVES *KN_WAVE)
     k_layer(const uint16_t *__restrict__ packed, const int32_t *__restrict__ perm, const KnTile *__restrict__ tiles,
@@ -724,12 +745,12 @@ __global__ void __launch_bounds__(WAVES *KN_WAVE)
     using L = Lay<H>;
     constexpr int HT = L::HT, HK = L::HK;
     constexpr int NB = LAYER == 1 ? 2 : (LAYER == 4 ? HK + 1 : HK); // input blocks
-    constexpr int NT = LAYER == 5 ? 0 : HT;                          // output tiles of the layer proper
-    constexpr int W0 = LAYER == 1 ? L::L1 : (LAYER == 2 ? L::L2 : (LAYER == 3 ? L::L3 : (LAYER == 4 ? L::L4 : L::L5)));
-    constexpr bool HEAD = LAYER == 3 || LAYER == 5;                  // has a density / colour head
+    constexpr int NT = (LAYER == 3 || LAYER == 5) ? 0 : HT;          // output tiles of the layer proper
+    constexpr int W0 = LAYER == 1 ? L::L1 : (LAYER == 2 ? L::L2 : L::L4);
+    constexpr bool HEAD = LAYER == 3 || LAYER == 5;                  // a density / colour head
     constexpr int WH = LAYER == 3 ? L::LS : L::L5;
-    const uint16_t *__restrict__ in = LAYER == 1 ? buf.x0 : ((LAYER == 2 || LAYER == 4) ? buf.ha : buf.hb);
-    uint16_t *__restrict__ out = (LAYER == 1 || LAYER == 3) ? buf.ha : buf.hb;
+    const uint16_t *__restrict__ in = LAYER == 1 ? buf.x0 : ((LAYER == 2 || LAYER == 5) ? buf.ha : buf.hb);
+    uint16_t *__restrict__ out = (LAYER == 1 || LAYER == 4) ? buf.ha : buf.hb;
     constexpr int IN_COLS = LAYER == 1 ? 64 : H;
 
     const int wave = threadIdx.x / KN_WAVE, lane = threadIdx.x & (KN_WAVE - 1);
@@ -756,10 +777,9 @@ __global__ void __launch_bounds__(WAVES *KN_WAVE)
 #pragma unroll
         for (int t = 0; t < NT; ++t) {
             if constexpr (LAYER == 2) bias[t] = *(const f4 *)(tail + 16 * t + 4 * g);
-            else if constexpr (LAYER == 3) bias[t] = *(const f4 *)(tail + H + 16 * t + 4 * g);
             else bias[t] = zero4; // layers 1 and 4: the bias rides in a constant-1 input slot
         }
-        if constexpr (HEAD) bias_head = *(const f4 *)(tail + 2 * H); // (b5, density bias)
+        if constexpr (HEAD) bias_head = *(const f4 *)(tail + H); // (b5, density bias)
     };
     int32_t net_cur = -1;
     for (int t = t_lo; t < t_hi; ++t) {
@@ -793,7 +813,7 @@ __global__ void __launch_bounds__(WAVES *KN_WAVE)
                     }
                 }
                 u4 Bh[HK];
-                pack_acts<H, BF, LAYER != 3>(acc, Bh);
+                pack_acts<H, BF, true>(acc, Bh);
                 if (16 * u + n < tl.len) {
                     const int64_t orow = tl.start + 16 * u + n;
 #pragma unroll
@@ -860,13 +880,16 @@ int launch(const kn_scene *sc, hipStream_t st, const KnSampleSrc &src, const KnB
 int kn_mlp_mfma_tile_len(const kn_scene *) { return MLP_TILE_LEN; }
 
 // bytes of the slot-order weights of N networks of width H (0: no kernel for that width)
+// (+ one status word behind the last network, for kn_mlp_pack_weights)
 int64_t kn_mlp_packed_bytes(int32_t H, int64_t N)
 {
     if (H != 32 && H != 64) return 0;
-    return (int64_t)(H == 32 ? Lay<32>::HALFS : Lay<64>::HALFS) * 2 * N;
+    return kn_align_up((int64_t)(H == 32 ? Lay<32>::HALFS : Lay<64>::HALFS) * 2 * N, 256) + 256;
 }
 
-// fills sc->packed_w (kn_mlp_packed_bytes bytes, assigned by the caller)
+// fills sc->packed_w (kn_mlp_packed_bytes bytes, assigned by the caller) and waits for it.  KN_E_UNSUPPORTED when the
+// product of a network's feature layer and layer 4 leaves the range of the scene's 16-bit type (fp16 weights whose
+// products sum beyond 65504: the folded layer cannot carry them).
 int kn_mlp_pack_weights(kn_scene *sc, hipStream_t st)
 {
     const int H = sc->desc.hidden;
@@ -879,14 +902,20 @@ int kn_mlp_pack_weights(kn_scene *sc, hipStream_t st)
     const int64_t blocks = kn_div_up(total, 256);
     if (blocks > 0x7fffffffLL) return KN_E_UNSUPPORTED;
     const uint16_t *w = (const uint16_t *)sc->desc.weights;
+    int32_t *flag = (int32_t *)((char *)sc->packed_w + kn_align_up(halfs * 2 * sc->N, 256));
+    hipLaunchKernelGGL(k_clear_flag, dim3(1), dim3(1), 0, st, flag);
+    KN_CHECK_LAUNCH();
     if (H == 32)
         hipLaunchKernelGGL(k_pack_weights<32>, dim3((unsigned)blocks), dim3(256), 0, st, w, sc->P, sc->N, bf,
-                           (uint16_t *)sc->packed_w);
+                           (uint16_t *)sc->packed_w, flag);
     else
         hipLaunchKernelGGL(k_pack_weights<64>, dim3((unsigned)blocks), dim3(256), 0, st, w, sc->P, sc->N, bf,
-                           (uint16_t *)sc->packed_w);
+                           (uint16_t *)sc->packed_w, flag);
     KN_CHECK_LAUNCH();
-    return KN_OK;
+    int32_t overflow = 0;
+    KN_HIP(hipMemcpyAsync(&overflow, flag, sizeof(overflow), hipMemcpyDeviceToHost, st));
+    KN_HIP(hipStreamSynchronize(st));
+    return overflow ? KN_E_UNSUPPORTED : KN_OK;
 }
 
 int kn_probe_mfma_launch(const kn_scene *sc, hipStream_t st, const KnProbeJob &job)

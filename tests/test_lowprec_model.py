@@ -44,6 +44,9 @@ def test_model_without_rounding_is_the_oracle():
         sm, cm = lowprec.eval_points(sc["weights"], H, ids, pts, dirs, "f32")
         assert np.abs(sm - so).max() < 2e-5 and np.abs(cm - co).max() < 1e-6
         assert np.all(sm[ids < 0] == 0) and (ids < 0).sum() > 50
+        # feature layer and layer 4 taken as one affine map (no activation between them, Sec. 3.2): the same function
+        sf, cf = lowprec.eval_points(sc["weights"], H, ids, pts, dirs, "f32", fold=True)
+        assert np.array_equal(sf, sm) and 0 < np.abs(cf - cm).max() < 1e-6 and np.abs(cf - co).max() < 1e-6
     want, _, mg = orc.extract_occupancy((8, 12, 8), 5.0)
     occ, m = lowprec.extract_occupancy(orc, sc["weights"], 64, "f32", (8, 12, 8), 5.0)
     far = mg.ravel() > 1e-4
@@ -68,6 +71,11 @@ def test_density_rounding_error_is_a_fraction_of_the_density_unit():
             sc16[dt] = e.max()
             assert rho / 4 < e.max() < 1.25 * rho, (dt, unit, e.max())
             assert np.abs(cm - co).max() < (8e-3 if dt == "bf16" else 1e-3)
+            # with the feature layer folded into layer 4 the rounding of the product matrix takes the place of the
+            # rounding of the feature vector: the same density, a colour error of the same size
+            sf, cf = lowprec.eval_points(sc["weights"], 32, ids, pts, dirs, dt, fold=True)
+            assert np.array_equal(sf, sm) and np.abs(cf - co).max() < (8e-3 if dt == "bf16" else 1e-3)
+            assert 0.5 < np.abs(cf - co).mean() / np.abs(cm - co).mean() < 1.5
         assert 4 < sc16["bf16"] / sc16["f16"] < 16         # three more bits
 
 
