@@ -93,7 +93,7 @@ def test_host_side_argument_validation(lib):
     f32_small = n.value
     assert f32_small >= 8 * 124 * 64 * 4 + 64 ** 3 // 8 + 2 * 16 ** 3      # weight image, occupancy bits, skip field twice
     d.wdtype, d.res[:] = 1, [16, 16, 16]
-    assert lib.kn_scene_bytes(C.byref(d), C.byref(n)) == 0 and n.value >= 4096 * (14 * 1024 + 68 * 4)
+    assert lib.kn_scene_bytes(C.byref(d), C.byref(n)) == 0 and n.value >= 4096 * (12 * 1024 + 36 * 4)
     out = C.c_int64()
     assert lib.kn_create(None, 0) == -1
     assert lib.kn_destroy(None) == 0
