@@ -120,6 +120,10 @@ int kn_destroy(kn_ctx *ctx);
  * library allocates itself (hipMalloc; the only allocation of device memory in the library).  The descriptor's own
  * buffers (weights, occupancy, cell_net) may be released once the call has returned: it waits for `stream`
  * because it reads the skip field back to find the box around the occupied voxels.
+ * 16-bit scenes: Sec. 3.2 puts no activation between layer 3's feature vector and layer 4, and the library evaluates
+ * the two as one affine map, W3f W4f and b4 + W4f^T b3f, formed here in fp32 and rounded to the scene's type (the
+ * result is Eq. 7 up to the rounding that 16-bit operands have anyway).  KN_E_UNSUPPORTED if an element of that
+ * product is finite but beyond the type's range (fp16: 65504): such networks belong in bf16 or fp32 scenes.
  */
 int kn_scene_bytes(const kn_scene_desc *desc, int64_t *out_bytes);
 int kn_scene_create(kn_ctx *ctx, const kn_scene_desc *desc, void *stream, void *buffer /*dev, nullable*/,

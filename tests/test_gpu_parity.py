@@ -185,6 +185,26 @@ def test_matrix_core_kernel_follows_the_rounding_model(wdtype, H, unit):
     assert q(np.abs(c_g - c_m)) <= {"bf16": 2e-3, "f16": 5e-4}[wdtype]
 
 
+def test_folded_feature_layer_out_of_fp16_range_is_refused():
+    """The 16-bit kernels take layer 3's feature vector and layer 4 as one affine map (Sec. 3.2 puts no activation between
+    them) whose matrix is rounded to the scene's type.  fp16 weights whose products sum beyond 65504 cannot be carried
+    that way: scene creation refuses them; the same numbers in bf16 (fp32's range) make a scene."""
+    import paper_2103_13744_amd as kn
+    H = 32
+    sc = scene_dict((2, 1, 1), (0, 0, 0), (1, 1, 1), H, "f16", 151)
+    P = sc["weights"].shape[1]
+    oW3 = 63 * H + H + H * H + H
+    oW4 = oW3 + H * (H + 1) + (H + 1)
+    w = sc["weights"].copy()
+    w[1, oW3:oW3 + H * (H + 1)] = 60.0                  # network 1: every feature weight 60, every layer-4 weight 60:
+    w[1, oW4:oW4 + (H + 27) * H] = 60.0                 # 32 x 3600 = 115,200 per element of the product
+    assert oW4 + (H + 27) * H + H + 3 * H + 3 == P
+    with pytest.raises(kn.KnError, match="-2|unsupported|UNSUPPORTED"):
+        make_pair(dict(sc, weights=w))
+    make_pair(dict(sc, weights=w, wdtype="bf16"))       # 60 is a bf16 number as well
+    make_pair(sc)
+
+
 def test_eval_grouped_matrix_cores_large_box():
     # coordinates large enough that 2^9 p leaves the range the sine hardware reduces by itself (f16 only: the
     # raw coordinates are network inputs too, and rounding 45.0 to bf16 alone costs more than the tolerance)
