@@ -273,7 +273,7 @@ template <bool BF> __device__ __forceinline__ u4 encode_direction(float rev, u4 
 // arrays through the sorted index list `perm`.  SRC_RECORDS: the re-ordered samples themselves (`perm` is not read).
 enum { SRC_RAYS = 0, SRC_POINTS = 1, SRC_RECORDS = 2 };
 template <int H, bool BF, int WAVES, bool WRAP, bool STRAT, int SRC>
-__global__ void __launch_bounds__(WAVES *KN_WAVE) __attribute__((amdgpu_waves_per_eu(H == 32 ? 3 : 2, H == 32 ? 3 : 2)))
+__global__ void __launch_bounds__(WAVES *KN_WAVE) __attribute__((amdgpu_waves_per_eu(H == 32 ? 4 : 2, H == 32 ? 4 : 2)))
     k_mlp_mfma(const uint16_t *__restrict__ packed, KnSampleSrc src, const int32_t *__restrict__ perm,
                const KnTile *__restrict__ tiles, const int32_t *__restrict__ n_tiles, float *__restrict__ sigma,
                float *__restrict__ rgb)
@@ -313,12 +313,15 @@ __global__ void __launch_bounds__(WAVES *KN_WAVE) __attribute__((amdgpu_waves_pe
     auto A = [&](int b) -> u4 {
         return areg[b];
     };
-    // Density / colour rows.  H = 32: one accumulator shared by the four sample tiles, fed through copies of the
-    // density / colour blocks restricted to the four output rows of tile u (made once per network).  H = 64: the
-    // copies would cost 64 registers and the second wavefront per SIMD with them; there every tile has its own
-    // accumulator, fed by the unmasked blocks (whose rows repeat with period four), and lane group g keeps tile g.
+    // Density / colour rows.  H = 32: two accumulators shared by the four sample tiles (one fed with h2, one with h4),
+    // through copies of one block that holds the density row and the colour rows side by side (they are disjoint rows of
+    // period four in their blocks), restricted to the four output rows of tile u and made once per network: the
+    // density accumulator's colour rows and the colour accumulator's density row hold sums nobody reads.  (Separate
+    // masked copies of the two blocks cost 16 registers more, which is the fourth wavefront per SIMD.)  H = 64: the
+    // copies would cost the second wavefront per SIMD; there every tile has its own accumulator, fed by the
+    // unmasked blocks (whose rows repeat with period four), and lane group g keeps tile g.
     constexpr bool SHARED_OUT = H == 32;
-    u4 a_sig[SHARED_OUT ? 4 : 1][HK], a_col[SHARED_OUT ? 4 : 1][HK];
+    u4 a_out[SHARED_OUT ? 4 : 1][HK];
     f4 bias2[HT], bias_out;
     auto load_network = [&](int32_t net) {
         const u4 *__restrict__ wp = (const u4 *)(packed + (int64_t)net * L::HALFS);
@@ -329,8 +332,7 @@ __global__ void __launch_bounds__(WAVES *KN_WAVE) __attribute__((amdgpu_waves_pe
             for (int u = 0; u < 4; ++u)
 #pragma unroll
                 for (int kb = 0; kb < HK; ++kb) {
-                    a_sig[u][kb] = mrow == u ? areg[L::LS + kb] : zero_u4;
-                    a_col[u][kb] = mrow == u ? areg[L::L5 + kb] : zero_u4;
+                    a_out[u][kb] = mrow == u ? (areg[L::LS + kb] | areg[L::L5 + kb]) : zero_u4;
                 }
         }
         const float *__restrict__ tail = (const float *)(wp + NBLK * KN_WAVE);
@@ -474,9 +476,9 @@ __global__ void __launch_bounds__(WAVES *KN_WAVE) __attribute__((amdgpu_waves_pe
         __builtin_amdgcn_wave_barrier();
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 
-        f4 outs[SHARED_OUT ? 1 : 4];
+        f4 outs[4], out_sig = bias_out, out_col = bias_out; // (per tile: width 64; shared: width 32)
 #pragma unroll
-        for (int u = 0; u < (SHARED_OUT ? 1 : 4); ++u) outs[u] = bias_out;
+        for (int u = 0; u < 4; ++u) outs[u] = bias_out;
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
             { // all four sample tiles are always computed: straight-line code lets the scheduler interleave them
@@ -514,7 +516,7 @@ __global__ void __launch_bounds__(WAVES *KN_WAVE) __attribute__((amdgpu_waves_pe
                 // layer 3: the density (row 4u+3 of the shared tile); its feature vector is folded into layer 4
 #pragma unroll
                 for (int kb = 0; kb < HK; ++kb) {
-                    if constexpr (SHARED_OUT) outs[0] = mfma<BF>(a_sig[u][kb], Bh[kb], outs[0]);
+                    if constexpr (SHARED_OUT) out_sig = mfma<BF>(a_out[u][kb], Bh[kb], out_sig);
                     else outs[u] = mfma<BF>(A(L::LS + kb), Bh[kb], outs[u]);
                 }
                 // layer 4: [second hidden vector through the folded feature layer, gamma(d)] -> H, ReLU (bias through
@@ -529,7 +531,7 @@ __global__ void __launch_bounds__(WAVES *KN_WAVE) __attribute__((amdgpu_waves_pe
                 // layer 5: H -> colour rows 4u+0..2 of the shared tile
 #pragma unroll
                 for (int kb = 0; kb < HK; ++kb) {
-                    if constexpr (SHARED_OUT) outs[0] = mfma<BF>(a_col[u][kb], Bh[kb], outs[0]);
+                    if constexpr (SHARED_OUT) out_col = mfma<BF>(a_out[u][kb], Bh[kb], out_col);
                     else outs[u] = mfma<BF>(A(L::L5 + kb), Bh[kb], outs[u]);
                 }
             }
@@ -542,7 +544,7 @@ __global__ void __launch_bounds__(WAVES *KN_WAVE) __attribute__((amdgpu_waves_pe
         // output activations; the store itself is issued at the top of the next iteration (see write_out).
         // Either way lane l ends up with sample l of the 64.
         {
-            f4 out = outs[0];
+            f4 out = (f4){out_col[0], out_col[1], out_col[2], out_sig[3]};
             if constexpr (!SHARED_OUT) out = g == 0 ? outs[0] : (g == 1 ? outs[1] : (g == 2 ? outs[2] : outs[3]));
             float sg = fmaxf(out[3], 0.0f);
             if constexpr (STRAT) sg *= dscale;
@@ -847,8 +849,8 @@ int launch(const kn_scene *sc, hipStream_t st, const KnSampleSrc &src, const KnB
            float *rgb, hipEvent_t ev_start, hipEvent_t ev_stop)
 {
     int64_t blocks = kn_div_up(max_tiles, WAVES);
-    // one workgroup of 4 wavefronts per compute unit and resident wavefront (H = 32: three per SIMD, H = 64: two)
-    const int fill = 256 * (H == 32 ? 3 : 2);
+    // one workgroup of 4 wavefronts per compute unit and resident wavefront (H = 32: four per SIMD, H = 64: two)
+    const int fill = 256 * (H == 32 ? 4 : 2);
     if (blocks > fill) blocks = fill;
     // positions are only ever evaluated inside the grid's box: its largest coordinate bounds the encoding's
     // largest argument, 2^8 |p| / (2 pi) revolutions at the highest restart frequency
