@@ -262,7 +262,7 @@ template <bool BF> __device__ __forceinline__ u4 encode_direction(float rev, u4 
                 pk<BF>(s[2], m[2]), pk<BF>(s[3], m[3])};
 }
 
-// Weights stay in registers: 12 blocks (48 VGPRs) for H = 32, three wavefronts per SIMD; 32 blocks (128 VGPRs) for
+// Weights stay in registers: 12 blocks (48 VGPRs) for H = 32, four wavefronts per SIMD; 32 blocks (128 VGPRs) for
 // H = 64, two wavefronts per SIMD (the matrix-core operands are read straight from the register file either way).
 // STRAT (render with stratified sampling): the lattice points sit at their drawn offsets and the density is
 // scaled by delta_k / step on the way out (see KnSampleSrc).
@@ -425,7 +425,7 @@ __global__ void __launch_bounds__(WAVES *KN_WAVE) __attribute__((amdgpu_waves_pe
     // one after the other and the last one would run alone; a wavefront lowers its own issue priority as it gets
     // through its range, which lets the ones behind catch up and ends all of them together.  The steps are at a half,
     // a quarter and an eighth of the range to go: what the wavefronts drift apart after the last step is what they end
-    // apart (time stamps per tile: with steps at the quarters of the range the ends of a SIMD's three wavefronts lay
+    // apart (time stamps per tile: with steps at the quarters of the range the ends of a SIMD's wavefronts (three at the time) lay
     // 9 us apart in a 58 us launch, with these 6.5).
     const int n_t = t_hi - t_lo;
     const int drop_to_2 = t_hi - (n_t >> 1), drop_to_1 = t_hi - (n_t >> 2), drop_to_0 = t_hi - (n_t >> 3);
