@@ -33,12 +33,11 @@
 // fewer, and the feature vector is never rounded to 16 bit.  Layer 3 proper is then the density row alone.
 //
 // Density and colour.  Layer 3's density row and layer 5's three colour rows would each waste a
-// 16-row output tile.  Instead four sample tiles (64 samples) share one extra accumulator: for
-// sample tile u the density row is placed at row 4u+3 and the colour rows at 4u+0..2 (the weight
-// block is masked to those rows), and all eight MFMAs accumulate into the same tile.  Afterwards
+// 16-row output tile.  Instead four sample tiles (64 samples) share two extra accumulators: for
+// sample tile u the density row sits at row 4u+3 and the colour rows at 4u+0..2 of one weight block
+// (masked to those four rows); the block multiplies h2 into the first accumulator, whose rows 4u+3
+// are the densities, and h4 into the second, whose rows 4u+0..2 are the colours.  Afterwards
 // lane l holds (r, g, b, sigma) pre-activations of sample l of the 64, one sample per lane.
-// (Width 64 keeps one such accumulator per sample tile instead and uses the unmasked blocks, whose rows repeat
-// with period four: the masked copies would cost the registers that the second wavefront per SIMD needs.)
 //
 // Encoding.  sin/cos of 2^f * p come from v_sin_f32 / v_cos_f32 at three "restart" frequencies
 // per lane and the double-angle recurrence in between (fp32), which is far inside the 16-bit
@@ -313,28 +312,23 @@ __global__ void __launch_bounds__(WAVES *KN_WAVE) __attribute__((amdgpu_waves_pe
     auto A = [&](int b) -> u4 {
         return areg[b];
     };
-    // Density / colour rows.  H = 32: two accumulators shared by the four sample tiles (one fed with h2, one with h4),
-    // through copies of one block that holds the density row and the colour rows side by side (they are disjoint rows of
+    // Density / colour rows: two accumulators shared by the four sample tiles (one fed with h2, one with h4), through
+    // copies of one block that holds the density row and the colour rows side by side (they are disjoint rows of
     // period four in their blocks), restricted to the four output rows of tile u and made once per network: the
     // density accumulator's colour rows and the colour accumulator's density row hold sums nobody reads.  (Separate
-    // masked copies of the two blocks cost 16 registers more, which is the fourth wavefront per SIMD.)  H = 64: the
-    // copies would cost the second wavefront per SIMD; there every tile has its own accumulator, fed by the
-    // unmasked blocks (whose rows repeat with period four), and lane group g keeps tile g.
-    constexpr bool SHARED_OUT = H == 32;
-    u4 a_out[SHARED_OUT ? 4 : 1][HK];
+    // masked copies of the two blocks cost 16 registers more at H = 32, which is the fourth wavefront per SIMD; an
+    // accumulator per sample tile fed by the unmasked blocks, with lane group g keeping tile g, is 7 % slower at either
+    // width.)
+    u4 a_out[4][HK];
     f4 bias2[HT], bias_out;
     auto load_network = [&](int32_t net) {
         const u4 *__restrict__ wp = (const u4 *)(packed + (int64_t)net * L::HALFS);
 #pragma unroll
         for (int b = 0; b < NBLK; ++b) areg[b] = wp[b * KN_WAVE + lane];
-        if constexpr (SHARED_OUT) {
 #pragma unroll
-            for (int u = 0; u < 4; ++u)
+        for (int u = 0; u < 4; ++u)
 #pragma unroll
-                for (int kb = 0; kb < HK; ++kb) {
-                    a_out[u][kb] = mrow == u ? (areg[L::LS + kb] | areg[L::L5 + kb]) : zero_u4;
-                }
-        }
+            for (int kb = 0; kb < HK; ++kb) a_out[u][kb] = mrow == u ? (areg[L::LS + kb] | areg[L::L5 + kb]) : zero_u4;
         const float *__restrict__ tail = (const float *)(wp + NBLK * KN_WAVE);
 #pragma unroll
         for (int t = 0; t < HT; ++t) bias2[t] = *(const f4 *)(tail + 16 * t + 4 * g);
@@ -476,9 +470,7 @@ __global__ void __launch_bounds__(WAVES *KN_WAVE) __attribute__((amdgpu_waves_pe
         __builtin_amdgcn_wave_barrier();
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 
-        f4 outs[4], out_sig = bias_out, out_col = bias_out; // (per tile: width 64; shared: width 32)
-#pragma unroll
-        for (int u = 0; u < 4; ++u) outs[u] = bias_out;
+        f4 out_sig = bias_out, out_col = bias_out;
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
             { // all four sample tiles are always computed: straight-line code lets the scheduler interleave them
@@ -515,10 +507,7 @@ __global__ void __launch_bounds__(WAVES *KN_WAVE) __attribute__((amdgpu_waves_pe
                 pack_acts<H, BF, true>(acc, Bh);
                 // layer 3: the density (row 4u+3 of the shared tile); its feature vector is folded into layer 4
 #pragma unroll
-                for (int kb = 0; kb < HK; ++kb) {
-                    if constexpr (SHARED_OUT) out_sig = mfma<BF>(a_out[u][kb], Bh[kb], out_sig);
-                    else outs[u] = mfma<BF>(A(L::LS + kb), Bh[kb], outs[u]);
-                }
+                for (int kb = 0; kb < HK; ++kb) out_sig = mfma<BF>(a_out[u][kb], Bh[kb], out_sig);
                 // layer 4: [second hidden vector through the folded feature layer, gamma(d)] -> H, ReLU (bias through
                 // the constant-1 slot)
 #pragma unroll
@@ -530,10 +519,7 @@ __global__ void __launch_bounds__(WAVES *KN_WAVE) __attribute__((amdgpu_waves_pe
                 pack_acts<H, BF, true>(acc, Bh);
                 // layer 5: H -> colour rows 4u+0..2 of the shared tile
 #pragma unroll
-                for (int kb = 0; kb < HK; ++kb) {
-                    if constexpr (SHARED_OUT) out_col = mfma<BF>(a_out[u][kb], Bh[kb], out_col);
-                    else outs[u] = mfma<BF>(A(L::L5 + kb), Bh[kb], outs[u]);
-                }
+                for (int kb = 0; kb < HK; ++kb) out_col = mfma<BF>(a_out[u][kb], Bh[kb], out_col);
             }
         }
         __builtin_amdgcn_wave_barrier(); // staging buffer is rewritten by the next iteration
@@ -542,10 +528,9 @@ __global__ void __launch_bounds__(WAVES *KN_WAVE) __attribute__((amdgpu_waves_pe
         dsc3 = descriptor(t + 4);
 
         // output activations; the store itself is issued at the top of the next iteration (see write_out).
-        // Either way lane l ends up with sample l of the 64.
+        // Lane l holds sample l of the 64.
         {
-            f4 out = (f4){out_col[0], out_col[1], out_col[2], out_sig[3]};
-            if constexpr (!SHARED_OUT) out = g == 0 ? outs[0] : (g == 1 ? outs[1] : (g == 2 ? outs[2] : outs[3]));
+            const f4 out = (f4){out_col[0], out_col[1], out_col[2], out_sig[3]};
             float sg = fmaxf(out[3], 0.0f);
             if constexpr (STRAT) sg *= dscale;
             float col[3];
