@@ -425,6 +425,10 @@ __global__ void __launch_bounds__(WAVES *KN_WAVE) __attribute__((amdgpu_waves_pe
     const int drop_to_2 = t_hi - (n_t >> 1), drop_to_1 = t_hi - (n_t >> 2), drop_to_0 = t_hi - (n_t >> 3);
     __builtin_amdgcn_s_setprio(3);
 
+    // (render) gamma(d) fragment of the first sample tile of the tile that comes next: requested at the end of the
+    // tile before it
+    u4 Bd_first = zero_u4;
+    if constexpr (DIRTAB) Bd_first = *(const u4 *)(src.dir_table + ((int64_t)__shfl((int)(rec0 >> src.kbits), n, KN_WAVE) * 4 + g) * 8);
     for (int t = t_lo; t < t_hi; ++t) {
         if (t == drop_to_2) __builtin_amdgcn_s_setprio(2); // (uniform; the lowest wins where steps coincide)
         if (t == drop_to_1) __builtin_amdgcn_s_setprio(1);
@@ -471,6 +475,7 @@ __global__ void __launch_bounds__(WAVES *KN_WAVE) __attribute__((amdgpu_waves_pe
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 
         f4 out_sig = bias_out, out_col = bias_out;
+        u4 Bd_ahead = Bd_first;
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
             { // all four sample tiles are always computed: straight-line code lets the scheduler interleave them
@@ -480,11 +485,16 @@ __global__ void __launch_bounds__(WAVES *KN_WAVE) __attribute__((amdgpu_waves_pe
                 encode_position<BF, WRAP>(ang, ident, m3, Bx);
                 u4 Bd;
                 if constexpr (DIRTAB) {
-                    // (the element is copied to a scalar first: a bit cast applied to the vector element itself read
-                    // the vector's first element in the generated code)
-                    const float ray_word = ang[3];
-                    const uint32_t ray_of_sample = __float_as_uint(ray_word);
-                    Bd = *(const u4 *)(src.dir_table + ((int64_t)ray_of_sample * 4 + g) * 8);
+                    // The fragment of sample tile u was requested a whole sample tile ago; the one of tile u + 1 is requested
+                    // here (the ray's number travels in the fourth word of the staged angles), and nothing may be
+                    // scheduled across that point: left to itself the compiler puts such a gather a few instructions in
+                    // front of its use, and the wavefront then waits for a round trip to the L2 per sample tile.
+                    Bd = Bd_ahead;
+                    if (u < 3) {
+                        const float ray_word = stage[wave][g][0][16 * (u + 1) + n][3];
+                        Bd_ahead = *(const u4 *)(src.dir_table + ((int64_t)__float_as_uint(ray_word) * 4 + g) * 8);
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
                 } else {
                     Bd = encode_direction<BF>(ang[3], ident, m3);
                 }
@@ -521,6 +531,11 @@ __global__ void __launch_bounds__(WAVES *KN_WAVE) __attribute__((amdgpu_waves_pe
 #pragma unroll
                 for (int kb = 0; kb < HK; ++kb) out_col = mfma<BF>(a_out[u][kb], Bh[kb], out_col);
             }
+        }
+        if constexpr (DIRTAB) { // first direction fragment of the next tile: its sample n's ray is known to lane n
+            const uint32_t ray_next = (uint32_t)__shfl((int)(rec0 >> src.kbits), n, KN_WAVE);
+            Bd_first = *(const u4 *)(src.dir_table + ((int64_t)ray_next * 4 + g) * 8);
+            __builtin_amdgcn_sched_barrier(0);
         }
         __builtin_amdgcn_wave_barrier(); // staging buffer is rewritten by the next iteration
         // The next descriptor comes through the scalar cache, which shares its counter with LDS: fetched here,
