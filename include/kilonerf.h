@@ -230,8 +230,8 @@ int kn_composite_deltas(void *stream, const float *sigma /*dev*/, const float *r
  * waves from near to far; rays whose transmittance fell below term_eps, or that ran out of
  * lattice points, drop out between waves.  The result per ray equals the sequential definition
  * (march, evaluate, blend, stop at T < term_eps) regardless of how waves are cut.
- * R*2^ceil(log2 K) must be <= 2^32 and R times the slot budget per ray (kn_set_render_params; 128 unless set)
- * must be below 2^31: KN_E_UNSUPPORTED beyond.  The call enqueues the first two waves without looking at their outcome
+ * R*2^ceil(log2 K) must be <= 2^32, R times the slot budget per ray (kn_set_render_params; 128 unless set)
+ * below 2^31, and R <= 2^26: KN_E_UNSUPPORTED beyond.  The call enqueues the first two waves without looking at their outcome
  * (their shape is computed on the device) and reads the count of surviving rays on the host only to decide
  * about further waves; when it returns, the last wave has been enqueued but `stream` may still be running
  * (it does not wait at all when the slot budget guarantees that the second wave ends every ray and `stats`

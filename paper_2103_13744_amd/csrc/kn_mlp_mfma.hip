@@ -426,9 +426,10 @@ __global__ void __launch_bounds__(WAVES *KN_WAVE) __attribute__((amdgpu_waves_pe
     __builtin_amdgcn_s_setprio(3);
 
     // (render) gamma(d) fragment of the first sample tile of the tile that comes next: requested at the end of the
-    // tile before it
+    // tile before it.  (Fragments are addressed with a 32-bit byte offset from the table's start, 64 bytes per ray: one
+    // instruction instead of four per gather; kn_render limits the number of rays to 2^26.)
     u4 Bd_first = zero_u4;
-    if constexpr (DIRTAB) Bd_first = *(const u4 *)(src.dir_table + ((int64_t)__shfl((int)(rec0 >> src.kbits), n, KN_WAVE) * 4 + g) * 8);
+    if constexpr (DIRTAB) Bd_first = *(const u4 *)((const char *)src.dir_table + ((uint32_t)__shfl((int)(rec0 >> src.kbits), n, KN_WAVE) * 64u + (uint32_t)g * 16u));
     for (int t = t_lo; t < t_hi; ++t) {
         if (t == drop_to_2) __builtin_amdgcn_s_setprio(2); // (uniform; the lowest wins where steps coincide)
         if (t == drop_to_1) __builtin_amdgcn_s_setprio(1);
@@ -492,7 +493,7 @@ __global__ void __launch_bounds__(WAVES *KN_WAVE) __attribute__((amdgpu_waves_pe
                     Bd = Bd_ahead;
                     if (u < 3) {
                         const float ray_word = stage[wave][g][0][16 * (u + 1) + n][3];
-                        Bd_ahead = *(const u4 *)(src.dir_table + ((int64_t)__float_as_uint(ray_word) * 4 + g) * 8);
+                        Bd_ahead = *(const u4 *)((const char *)src.dir_table + (__float_as_uint(ray_word) * 64u + (uint32_t)g * 16u));
                         __builtin_amdgcn_sched_barrier(0);
                     }
                 } else {
@@ -534,7 +535,7 @@ __global__ void __launch_bounds__(WAVES *KN_WAVE) __attribute__((amdgpu_waves_pe
         }
         if constexpr (DIRTAB) { // first direction fragment of the next tile: its sample n's ray is known to lane n
             const uint32_t ray_next = (uint32_t)__shfl((int)(rec0 >> src.kbits), n, KN_WAVE);
-            Bd_first = *(const u4 *)(src.dir_table + ((int64_t)ray_next * 4 + g) * 8);
+            Bd_first = *(const u4 *)((const char *)src.dir_table + (ray_next * 64u + (uint32_t)g * 16u));
             __builtin_amdgcn_sched_barrier(0);
         }
         __builtin_amdgcn_wave_barrier(); // staging buffer is rewritten by the next iteration

@@ -1238,9 +1238,8 @@ static int render_impl(kn_ctx *ctx, const kn_scene *sc, void *stream, const floa
     if (R == 0) return KN_OK;
     const KnKnobs knobs = kn_knobs(ctx); // the schedule this call runs with, whatever is set meanwhile
     const int kbits = kbits_for(K > 1 ? K : 2);
-    if (R > (1ll << (32 - kbits)) || R > 0x7fffffffLL / knobs.slots_per_ray ||
-        R > 0x7fffffffLL / MARCH_G_WIDE)
-        return KN_E_UNSUPPORTED; // slot numbers and row * lanes are 32-bit
+    if (R > (1ll << (32 - kbits)) || R > 0x7fffffffLL / knobs.slots_per_ray || R > (1ll << 26))
+        return KN_E_UNSUPPORTED; // slot numbers, row * lanes and byte offsets into the table of encoded directions are 32-bit
     if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < kn_render_ws_bytes(sc, R, knobs.slots_per_ray))
         return KN_E_WORKSPACE;
 

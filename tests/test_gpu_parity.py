@@ -185,6 +185,33 @@ def test_matrix_core_kernel_follows_the_rounding_model(wdtype, H, unit):
     assert q(np.abs(c_g - c_m)) <= {"bf16": 2e-3, "f16": 5e-4}[wdtype]
 
 
+def test_render_refuses_more_rays_than_its_32_bit_indices_hold():
+    """kn_render's limits on the number of rays (packed (ray, k) records, slot numbers, byte offsets into the table of
+    encoded directions): one ray beyond a limit is KN_E_UNSUPPORTED (-2), at the limit the call goes on to its next check
+    (the workspace, which is too small here: -3).  Nothing is launched either way."""
+    import ctypes as C
+    import torch
+    import paper_2103_13744_amd as kn
+    sc = scene_dict((1, 1, 1), (0, 0, 0), (1, 1, 1), 32, "f16", 171)
+    dev, _ = make_pair(sc)
+    L = kn.load_library()
+    buf = torch.zeros(1024, dtype=torch.float32, device="cuda")
+    ws = torch.zeros(4096, dtype=torch.uint8, device="cuda")
+    bg = (C.c_float * 3)(0, 0, 0)
+
+    def call(R, K):
+        return L.kn_render(dev._ctx(None), dev.h, None, C.c_void_p(buf.data_ptr()), C.c_void_p(buf.data_ptr()), C.c_int64(R),
+                           C.c_float(0.0), C.c_float(0.1), C.c_int32(K), C.c_float(0.0), C.byref(bg), C.c_void_p(buf.data_ptr()), None,
+                           C.c_void_p(ws.data_ptr()), C.c_int64(ws.numel()))
+    assert call(2 ** 23, 512) == -3 and call(2 ** 23 + 1, 512) == -2            # ray << 9 | k in 32 bits
+    assert call((2 ** 31 - 1) // 128, 2) == -3 and call((2 ** 31 - 1) // 128 + 1, 2) == -2     # 128 slots per ray
+    kn.set_render_params(0, 16, 0)
+    try:
+        assert call(2 ** 26, 2) == -3 and call(2 ** 26 + 1, 2) == -2            # 64 bytes of encoded direction per ray
+    finally:
+        kn.set_render_params(0, 0, 0)
+
+
 def test_folded_feature_layer_out_of_fp16_range_is_refused():
     """The 16-bit kernels take layer 3's feature vector and layer 4 as one affine map (Sec. 3.2 puts no activation between
     them) whose matrix is rounded to the scene's type.  fp16 weights whose products sum beyond 65504 cannot be carried
