@@ -48,8 +48,8 @@ def cpu_model():
 FLOP_PER_SAMPLE = {32: 12160, 64: 36608}
 FLOP_PER_SAMPLE_EXECUTED_16BIT = {32: 10112, 64: 28416}
 # vector-ALU issue slots of the render variant of k_mlp_mfma per 16 samples, counted in the generated code of its main
-# loop (281 / 383 vector instructions per 64 samples, 30 of them transcendental and counted twice)
-VALU_SLOTS_PER_16_SAMPLES = {32: 78, 64: 103}
+# loop (269 / 363 vector instructions per 64 samples, 30 of them transcendental and counted twice)
+VALU_SLOTS_PER_16_SAMPLES = {32: 75, 64: 98}
 
 
 TRAFFIC_FILE = "profiles/hbm_traffic_cfg3_f16.txt"
