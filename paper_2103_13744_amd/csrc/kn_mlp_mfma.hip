@@ -586,6 +586,10 @@ __global__ void __launch_bounds__(WAVES *KN_WAVE) __attribute__((amdgpu_waves_pe
     if (t_lo >= t_hi) return;
 
     u4 a1[2 * HT], a2[HT * HK], a_sig[HK];
+    // (width 32: the density block restricted to the rows of sample tile u, made once per network; at width 64 the copies
+    // would cost the third wavefront per SIMD, and the block is masked where it is used)
+    constexpr bool MASKED_COPIES = H == 32;
+    u4 a_sig_of[MASKED_COPIES ? 4 : 1][HK];
     f4 bias2[HT];
     float bias_sig = 0.0f;
     auto load_network = [&](int32_t net) {
@@ -596,6 +600,12 @@ __global__ void __launch_bounds__(WAVES *KN_WAVE) __attribute__((amdgpu_waves_pe
         for (int b = 0; b < HT * HK; ++b) a2[b] = wp[(L::L2 + b) * KN_WAVE + lane];
 #pragma unroll
         for (int kb = 0; kb < HK; ++kb) a_sig[kb] = wp[(L::LS + kb) * KN_WAVE + lane];
+        if constexpr (MASKED_COPIES) {
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+#pragma unroll
+                for (int kb = 0; kb < HK; ++kb) a_sig_of[u][kb] = mrow == u ? a_sig[kb] : zero_u4;
+        }
         const float *__restrict__ tail = (const float *)(wp + L::NBLK * KN_WAVE);
 #pragma unroll
         for (int t = 0; t < HT; ++t) bias2[t] = *(const f4 *)(tail + 16 * t + 4 * g);
@@ -663,7 +673,10 @@ __global__ void __launch_bounds__(WAVES *KN_WAVE) __attribute__((amdgpu_waves_pe
                 }
                 pack_acts<H, BF, true>(acc, Bh);
 #pragma unroll
-                for (int kb = 0; kb < HK; ++kb) out = mfma<BF>(mrow == u ? a_sig[kb] : zero_u4, Bh[kb], out);
+                for (int kb = 0; kb < HK; ++kb) {
+                    if constexpr (MASKED_COPIES) out = mfma<BF>(a_sig_of[u][kb], Bh[kb], out);
+                    else out = mfma<BF>(mrow == u ? a_sig[kb] : zero_u4, Bh[kb], out);
+                }
             }
             if (todo && net == nsel) {
                 sg = fmaxf(out[3], 0.0f);
