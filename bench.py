@@ -52,6 +52,7 @@ FLOP_PER_SAMPLE_EXECUTED_16BIT = {32: 10112, 64: 28416}
 VALU_SLOTS_PER_16_SAMPLES = {32: 75, 64: 98}
 
 
+EVENTS_EVERY = 5  # frames of the timed region per frame that carries the dominant kernel's HIP events (coprime to the 8 poses: every pose is timed)
 TRAFFIC_FILE = "profiles/hbm_traffic_cfg3_f16.txt"
 
 
@@ -367,7 +368,8 @@ def measure_render(kn, torch, np, configs, cfg, wdtype, steps, warmup, poses, tr
         scene.render(*rays[i % n_p], *args, out=out)
     torch.cuda.synchronize()
 
-    def run_frames(profile_mode):
+    def run_frames(profile_mode, every=1):
+        kn.default_context().set_option(kn.OPT_PROFILE_EVERY, every)
         kn.profile_enable(profile_mode)
         kn.profile_read(reset=True)
         torch.cuda.synchronize()
@@ -378,6 +380,7 @@ def measure_render(kn, torch, np, configs, cfg, wdtype, steps, warmup, poses, tr
         dt_ = time.perf_counter() - t0
         prof = kn.profile_read(reset=True)
         kn.profile_enable(0)
+        kn.default_context().set_option(kn.OPT_PROFILE_EVERY, 1)
         return dt_, prof
 
     # untimed: frames with HIP events around every stage, to find the kernel that takes the most time
@@ -386,62 +389,73 @@ def measure_render(kn, torch, np, configs, cfg, wdtype, steps, warmup, poses, tr
     dominant = max(("ms_march", "ms_bucket", "ms_mlp", "ms_blend"), key=lambda k: stage_ms[k])
     # timed region: HIP events (recorded by the library on the stream it launches on) only around the dominant
     # kernel, so that the measurement disturbs the frame as little as possible
+    # ... and only on one frame in EVENTS_EVERY (an event pair costs about 5 us on the stream): the kernel's average launch
+    # is taken over the launches of those frames, the samples counted are theirs
     mode = {"ms_mlp": 2, "ms_march": 3}.get(dominant, 1)
-    dt_s, prof = run_frames(mode)
+    dt_s, prof = run_frames(mode, EVENTS_EVERY)
     dt_plain_s, _ = run_frames(0)  # the same frames without any events, for reference
 
     blended = sum(stats[i % n_p]["samples_blended"] for i in range(steps))
     evaluated = sum(stats[i % n_p]["samples_evaluated"] for i in range(steps))
     waves = sum(stats[i % n_p]["waves"] for i in range(steps))
     launches = waves  # one launch of each per-wave kernel per wave
+    timed = range(0, steps, EVENTS_EVERY)  # the frames of the timed region that carried events
+    timed_counts = {"evaluated": sum(stats[i % n_p]["samples_evaluated"] for i in timed),
+                    "blended": sum(stats[i % n_p]["samples_blended"] for i in timed),
+                    "launches": sum(stats[i % n_p]["waves"] for i in timed), "frames": len(timed)}
+    all_counts = {"evaluated": evaluated, "blended": blended, "launches": launches, "frames": steps}
     H = sc["hidden"]
     f32 = wdtype == "f32"
     mfma_peak = PEAK_MFMA_F32 if f32 else PEAK_MFMA_16BIT
     mfma_key = {"f32": "mfma_f32_tflops", "f16": "mfma_f16_tflops", "bf16": "mfma_bf16_tflops"}[wdtype]
 
-    def roof_mlp(p):
+    def roof_mlp(p, n=None):
+        n = n or all_counts
         s_ = p["ms_mlp"] * 1e-3
-        tf = FLOP_PER_SAMPLE[H] * evaluated / s_ / 1e12 if s_ > 0 else 0.0
+        tf = FLOP_PER_SAMPLE[H] * n["evaluated"] / s_ / 1e12 if s_ > 0 else 0.0
         r = {"kernel": "k_mlp_f32 (fused grouped MLP, fp32 MFMA)" if f32 else "k_mlp_mfma (fused grouped MLP)", "bound": "mfma",
              "achieved": tf, "peak": mfma_peak / 1e12, "unit": "TFLOP/s", "frac": tf * 1e12 / mfma_peak,
-             "traffic": traffic.get("k_mlp_mfma"), "avg_launch_ms": p["ms_mlp"] / max(launches, 1), "launches": launches,
-             "samples_per_launch": evaluated / max(launches, 1),
+             "traffic": traffic.get("k_mlp_mfma"), "avg_launch_ms": p["ms_mlp"] / max(n["launches"], 1), "launches": n["launches"],
+             "frames_with_events": n["frames"], "samples_per_launch": n["evaluated"] / max(n["launches"], 1),
              # the same kernel on the samples the method itself evaluates (those in front of the termination point)
-             "achieved_on_blended_samples": tf * blended / max(evaluated, 1)}
+             "achieved_on_blended_samples": tf * n["blended"] / max(n["evaluated"], 1)}
         r["flop_per_sample"] = FLOP_PER_SAMPLE[H]
         r["flop_per_sample_executed"] = FLOP_PER_SAMPLE[H] if f32 else FLOP_PER_SAMPLE_EXECUTED_16BIT[H]
         if not f32:
             # second view: its vector-ALU issue slots (counted in the generated code, transcendental instructions
             # twice) against what 1024 SIMDs can issue at 2.4 GHz, one slot per 4 cycles
-            slots = VALU_SLOTS_PER_16_SAMPLES[H] / 16.0 * evaluated
+            slots = VALU_SLOTS_PER_16_SAMPLES[H] / 16.0 * n["evaluated"]
             r["valu_issue_frac"] = slots / (s_ * 1024 * 2.4e9 / 4.0) if s_ > 0 else 0.0
         return with_measured(r, mfma_key)
 
-    def roof_hbm(p, key, kernel, nbytes, traffic_key):
+    def roof_hbm(p, key, kernel, nbytes, traffic_key, n):
         s_ = p[key] * 1e-3
         return with_measured({"kernel": kernel, "bound": "hbm", "achieved": nbytes / s_ / 1e9 if s_ > 0 else 0.0,
                               "peak": PEAK_HBM / 1e9, "unit": "GB/s", "frac": nbytes / s_ / PEAK_HBM if s_ > 0 else 0.0,
-                              "traffic": traffic.get(traffic_key), "avg_launch_ms": p[key] / max(launches, 1),
-                              "launches": launches}, "hbm_copy_gbps")
+                              "traffic": traffic.get(traffic_key), "avg_launch_ms": p[key] / max(n["launches"], 1),
+                              "launches": n["launches"], "frames_with_events": n["frames"]}, "hbm_copy_gbps")
 
-    def roof_march(p):
+    def roof_march(p, n=None):
+        n = n or all_counts
         # algorithmic bytes: 24 B per ray read + the packed occupancy grid read, once per frame, and 8 B (key,
         # record) written per kept sample
         occ_bytes = 0 if occ is None else int(np.prod(occ.shape)) / 8
-        return roof_hbm(p, "ms_march", "k_march_wave (march + empty-space skipping)", steps * (occ_bytes + 24.0 * R) + 8.0 * evaluated,
-                        "k_march_wave")
+        return roof_hbm(p, "ms_march", "k_march_wave (march + empty-space skipping)",
+                        n["frames"] * (occ_bytes + 24.0 * R) + 8.0 * n["evaluated"], "k_march_wave", n)
 
     def roof_group(p):
         # algorithmic bytes: every sample's key is read twice (count, fill) and its slot number written: 12 B
-        return roof_hbm(p, "ms_bucket", "k_group_pass (order-free grouping by network)", 12.0 * evaluated, "k_group_pass")
+        return roof_hbm(p, "ms_bucket", "k_group_pass (order-free grouping by network)", 12.0 * evaluated, "k_group_pass", all_counts)
 
     def roof_blend(p):
         # algorithmic bytes: 16 B read per evaluated sample, 12 B written per ray of the frame; the per-ray state of the
         # live rays (32 B per wave) is not credited here
         return roof_hbm(p, "ms_blend", "k_composite_wave / k_composite_group (blend, early termination)",
-                        16.0 * evaluated + 12.0 * R * steps, "k_composite_wave")
+                        16.0 * evaluated + 12.0 * R * steps, "k_composite_wave", all_counts)
 
-    roofline = roof_mlp(prof) if dominant == "ms_mlp" else roof_march(prof) if dominant == "ms_march" else roof_mlp(prof_all)
+    roofline = (roof_mlp(prof, timed_counts) if dominant == "ms_mlp" else roof_march(prof, timed_counts) if dominant == "ms_march"
+                else roof_mlp(prof_all))
+    roofline["events_on_one_frame_in"] = EVENTS_EVERY
     res = {
         "value": blended / dt_s, "unit": "samples/s", "steps": steps, "warmup": warmup, "ms_per_step": dt_s * 1e3 / steps,
         "dtype": wdtype, "frames_per_sec": steps / dt_s,

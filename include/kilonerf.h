@@ -291,8 +291,12 @@ int kn_set_render_params(kn_ctx *ctx, int32_t first_wave_samples, int32_t slots_
  *   KN_OPT_GROUP_FUSED_MAX          largest number of networks whose per-network counters kn_render's grouping keeps
  *                                   in LDS one by one (default 8192; 0 is a valid value here: always the hash path;
  *                                   negative restores the default)
- *   KN_OPT_GROUP_HASH_SLOTS         slots of the LDS hash table used beyond that (power of two, 16 .. 2048) */
-typedef enum { KN_OPT_GROUP_FUSED_MAX = 1, KN_OPT_GROUP_HASH_SLOTS = 2 } kn_option;
+ *   KN_OPT_GROUP_HASH_SLOTS         slots of the LDS hash table used beyond that (power of two, 16 .. 2048)
+ * and one setting of the stage timing (kn_profile_enable):
+ *   KN_OPT_PROFILE_EVERY            events are recorded on one call in this many, counted from the moment timing is
+ *                                   switched on or this option is set (default 1: every call); a benchmark that times
+ *                                   a run of frames disturbs it less that way */
+typedef enum { KN_OPT_GROUP_FUSED_MAX = 1, KN_OPT_GROUP_HASH_SLOTS = 2, KN_OPT_PROFILE_EVERY = 3 } kn_option;
 int kn_set_option(kn_ctx *ctx, int32_t option, int64_t value);
 
 /* Per-stage device time of kn_render / kn_eval_grouped on this context, measured with HIP events recorded on

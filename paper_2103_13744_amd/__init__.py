@@ -133,7 +133,7 @@ def params_per_net(hidden: int, L_pos: int = 10, L_dir: int = 4) -> int:
     return int(load_library().kn_params_per_net(hidden, L_pos, L_dir))
 
 
-OPT_GROUP_FUSED_MAX, OPT_GROUP_HASH_SLOTS = 1, 2
+OPT_GROUP_FUSED_MAX, OPT_GROUP_HASH_SLOTS, OPT_PROFILE_EVERY = 1, 2, 3
 
 
 class Context:

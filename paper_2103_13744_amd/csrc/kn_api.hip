@@ -92,7 +92,7 @@ KnStageTimer::KnStageTimer(kn_ctx *c, hipStream_t s, bool allowed) : ctx(c), st(
 {
     if (!allowed || !ctx) return;
     std::lock_guard<std::mutex> lock(ctx->mutex);
-    on = ctx->profile_on;
+    on = ctx->profile_on && (ctx->profile_call++ % ctx->profile_every) == 0;
     if (on && !ctx->events_ready) {
         for (auto &e : ctx->events)
             if (hipEventCreate(&e) != hipSuccess) on = false;
@@ -153,6 +153,7 @@ extern "C" int kn_profile_enable(kn_ctx *ctx, int on)
     std::lock_guard<std::mutex> lock(ctx->mutex);
     if (ctx->profile_on) (void)settle_events(ctx);
     ctx->profile_on = on != 0;
+    ctx->profile_call = 0;
     ctx->only_stage = on == 2 ? KN_ST_MLP : on == 3 ? KN_ST_MARCH : KN_ST_NONE;
     return KN_OK;
 }
@@ -191,6 +192,11 @@ extern "C" int kn_set_option(kn_ctx *ctx, int32_t option, int64_t value)
         if (value > 0 && (value < 16 || value > KN_GROUP_HASH_SLOTS_MAX || (value & (value - 1)) != 0)) return KN_E_INVALID_ARG;
         ctx->group_hash_slots = value <= 0 ? KN_GROUP_HASH_SLOTS_MAX : (int32_t)value;
         return KN_OK;
+    case KN_OPT_PROFILE_EVERY:
+        if (value > 0x7fffffffLL) return KN_E_INVALID_ARG;
+        ctx->profile_every = value <= 0 ? 1 : (int32_t)value;
+        ctx->profile_call = 0;
+        return KN_OK;
     default: return KN_E_INVALID_ARG;
     }
 }
@@ -217,6 +223,8 @@ extern "C" int kn_create(kn_ctx **out, int device_index)
     ctx->group_hash_slots = KN_GROUP_HASH_SLOTS_MAX;
     ctx->profile = kn_profile{};
     ctx->profile_on = false;
+    ctx->profile_every = 1;
+    ctx->profile_call = 0;
     ctx->only_stage = KN_ST_NONE;
     ctx->n_events = 0;
     ctx->event_stream = nullptr;

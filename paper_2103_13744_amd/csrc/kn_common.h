@@ -60,6 +60,8 @@ struct kn_ctx {
     // totals are read
     kn_profile profile;
     bool profile_on;
+    int32_t profile_every; // events on one call in this many (kn_set_option)
+    int64_t profile_call;  // calls seen since profiling was switched on
     int only_stage;       // KN_ST_NONE, or the one stage that is being timed (then sample counts are not gathered)
     hipEvent_t events[KN_N_EVENTS];
     int event_stage[KN_N_EVENTS];

@@ -212,6 +212,28 @@ def test_render_refuses_more_rays_than_its_32_bit_indices_hold():
         kn.set_render_params(0, 0, 0)
 
 
+def test_stage_timing_on_one_call_in_n():
+    """KN_OPT_PROFILE_EVERY: events are recorded on one call in n, counted from the moment timing is switched on; the
+    results do not depend on it."""
+    import paper_2103_13744_amd as kn
+    sc = scene_dict((2, 2, 2), (0, 0, 0), (1, 1, 1), 32, "f16", 181)
+    dev, _ = make_pair(sc)
+    ctx = kn.Context()
+    pts, dirs = cuda(ks.uniform_points(5000, 182)), cuda(ks.sphere_dirs(5000, 183))
+    want = dev.eval_grouped(pts, dirs)
+    for every, timed in ((1, 7), (3, 3), (0, 7), (100, 1)):
+        ctx.set_option(kn.OPT_PROFILE_EVERY, every)
+        ctx.profile_enable(1)
+        for _ in range(7):
+            got = dev.eval_grouped(pts, dirs, ctx=ctx)
+        prof = ctx.profile_read()
+        ctx.profile_enable(0)
+        assert prof["calls"] == timed and prof["mlp_launches"] == timed and prof["ms_mlp"] > 0
+        assert all(bool((a == b).all()) for a, b in zip(got, want))
+    with pytest.raises(kn.KnError):
+        ctx.set_option(kn.OPT_PROFILE_EVERY, 2 ** 31)
+
+
 def test_folded_feature_layer_out_of_fp16_range_is_refused():
     """The 16-bit kernels take layer 3's feature vector and layer 4 as one affine map (Sec. 3.2 puts no activation between
     them) whose matrix is rounded to the scene's type.  fp16 weights whose products sum beyond 65504 cannot be carried
