@@ -14,6 +14,7 @@
 //
 // Input is the wave's row layout: row i holds cnt[i] samples in slots i*S .. i*S + cnt[i] - 1.
 #include "kn_common.h"
+#include <type_traits>
 
 namespace {
 
@@ -91,14 +92,19 @@ __global__ void __launch_bounds__(GROUP_THREADS)
 
     int32_t *hcl = bins + bins_cap; // MODE 2: the wave's histogram [N]
 
-    // four keys of chunk ch of the row at `base` (unconditional, clamped inside the row buffer)
-    auto load_chunk = [&](int64_t base, int32_t ch) -> i4 {
+    // four keys of chunk ch of the row at `base` (unconditional, clamped inside the row buffer).  VEC (rows start on
+    // 16-byte boundaries) is a compile-time choice: with a branch around the loads the compiler cannot count the loads in
+    // flight, and waits for all of them wherever it waits for one, which undoes every prefetch below.
+    auto load_chunk = [&](auto VEC, int64_t base, int32_t ch) -> i4 {
         const int32_t c = min(ch, row_chunks - 1);
-        if (vec) return *(const i4 *)(row_keys + base + 4 * c);
-        i4 v;
+        if constexpr (decltype(VEC)::value) {
+            return *(const i4 *)(row_keys + base + 4 * c);
+        } else {
+            i4 v;
 #pragma unroll
-        for (int q = 0; q < 4; ++q) v[q] = row_keys[base + min(4 * c + q, S - 1)];
-        return v;
+            for (int q = 0; q < 4; ++q) v[q] = row_keys[base + min(4 * c + q, S - 1)];
+            return v;
+        }
     };
     // runs of equal keys among the (up to four) samples j0.. of a chunk; f(key, first j, length) per run
     auto chunk_runs = [&](i4 v, int32_t j0, int32_t c, int32_t w0, int32_t nb, auto &&f) {
@@ -121,34 +127,33 @@ __global__ void __launch_bounds__(GROUP_THREADS)
     // One pass over the rows of the workgroup.  The sample count and the first two chunks of the next set of rows
     // are fetched before the current set is processed, so that only the first set waits for memory.
     struct RowLoad { int32_t c; int64_t base; i4 va, vb; };
-    auto fetch_rows = [&](int32_t rs) -> RowLoad {
+    auto fetch_rows = [&](auto VEC, int32_t rs) -> RowLoad {
         RowLoad q;
         const int32_t row = rs + sub;
         const int32_t i = max(r0 + min(row, nr - 1), 0); // (a workgroup without rows reads row 0 and ignores it)
         q.base = (int64_t)i * S;
-        q.c = row < nr ? cnt[i] : 0;
-        q.va = load_chunk(q.base, g);
-        q.vb = load_chunk(q.base, g + G);
+        const int32_t c = cnt[i]; // (every lane loads: rows beyond the workgroup's share read its last row and drop it)
+        q.c = row < nr ? c : 0;
+        q.va = load_chunk(VEC, q.base, g);
+        q.vb = load_chunk(VEC, q.base, g + G);
         return q;
     };
-    auto sweep = [&](int32_t w0, int32_t nb, RowLoad next /* = fetch_rows(0) */, auto &&f) {
+    auto sweep = [&](auto VEC, int32_t w0, int32_t nb, RowLoad next /* = fetch_rows(0) */, auto &&f) {
         for (int32_t rs = 0; rs < nr; rs += rows_per_set) {
             const RowLoad cur = next;
-            if (rs + rows_per_set < nr) next = fetch_rows(rs + rows_per_set);
-            i4 va = cur.va, vb = cur.vb;
-            for (int32_t ch = g; 4 * ch < cur.c; ch += 2 * G) {
-                if (ch != g) { // rows longer than two chunks per lane
-                    va = load_chunk(cur.base, ch);
-                    vb = load_chunk(cur.base, ch + G);
-                }
+            next = fetch_rows(VEC, rs + rows_per_set); // (unconditional: past the last set it reads the last row again)
+            auto both = [&](i4 va, i4 vb, int32_t ch) {
                 chunk_runs(va, 4 * ch, cur.c, w0, nb, [&](int32_t k, int32_t j, int32_t len) { f(k, cur.base + j, len); });
                 chunk_runs(vb, 4 * (ch + G), cur.c, w0, nb, [&](int32_t k, int32_t j, int32_t len) { f(k, cur.base + j, len); });
-            }
+            };
+            if (4 * g < cur.c) both(cur.va, cur.vb, g);
+            for (int32_t ch = g + 2 * G; 4 * ch < cur.c; ch += 2 * G) // rows longer than two chunks per lane
+                both(load_chunk(VEC, cur.base, ch), load_chunk(VEC, cur.base, ch + G), ch);
         }
     };
 
     // the first rows of the counting sweep are requested before the histogram is staged: one round trip for both
-    RowLoad first_rows = fetch_rows(0);
+    RowLoad first_rows = vec ? fetch_rows(std::true_type{}, 0) : fetch_rows(std::false_type{}, 0);
     int32_t own_sum = 0; // MODE 2: samples in the bins tid, tid + 256, ..., which this thread lays out below
     if constexpr (MODE == 2) {
         for (int32_t b0 = 0; b0 < N; b0 += 8 * GROUP_THREADS) {
@@ -188,11 +193,14 @@ __global__ void __launch_bounds__(GROUP_THREADS)
             }
             return -1;
         };
-        if (nr > 0)
-            sweep(0, N, first_rows, [&](int32_t k, int64_t, int32_t len) {
-                const int32_t sl = slot_of(k);
-                if (sl >= 0) atomicAdd(&hcnt[sl], len);
-            });
+        auto count = [&](int32_t k, int64_t, int32_t len) {
+            const int32_t sl = slot_of(k);
+            if (sl >= 0) atomicAdd(&hcnt[sl], len);
+        };
+        if (nr > 0) {
+            if (vec) sweep(std::true_type{}, 0, N, first_rows, count);
+            else sweep(std::false_type{}, 0, N, first_rows, count);
+        }
         __syncthreads();
         for (int32_t q = tid; q < bins_cap; q += GROUP_THREADS) {
             const int32_t k = hkeys[q], c = hcnt[q];
@@ -201,12 +209,15 @@ __global__ void __launch_bounds__(GROUP_THREADS)
             }
         }
         __syncthreads();
-        if (nr > 0)
-            sweep(0, N, fetch_rows(0), [&](int32_t k, int64_t slot, int32_t len) {
-                const int32_t sl = slot_of(k);
-                const int32_t pos = sl >= 0 ? atomicAdd(&hcnt[sl], len) : atomicAdd(&global[k], len);
-                for (int32_t t = 0; t < len; ++t) perm[pos + t] = (int32_t)slot + t;
-            });
+        auto fill = [&](int32_t k, int64_t slot, int32_t len) {
+            const int32_t sl = slot_of(k);
+            const int32_t pos = sl >= 0 ? atomicAdd(&hcnt[sl], len) : atomicAdd(&global[k], len);
+            for (int32_t t = 0; t < len; ++t) perm[pos + t] = (int32_t)slot + t;
+        };
+        if (nr > 0) {
+            if (vec) sweep(std::true_type{}, 0, N, fetch_rows(std::true_type{}, 0), fill);
+            else sweep(std::false_type{}, 0, N, fetch_rows(std::false_type{}, 0), fill);
+        }
     } else {
         __syncthreads(); // counters cleared, histogram staged
         // heads and lengths of the runs of equal keys among the eight samples of a lane's two chunks (straight-line code)
@@ -223,29 +234,27 @@ __global__ void __launch_bounds__(GROUP_THREADS)
             for (int q = 7; q >= 0; --q) len[q] = valid[q] ? 1 + (((q & 3) != 3 && valid[q + 1] && !head[q + 1]) ? len[q + 1] : 0) : 0;
         };
         // f(current row set, its two chunks, their first sample numbers) for every pair of chunks of the workgroup's rows
-        auto pairs = [&](RowLoad next /* = fetch_rows(0) */, auto &&f) {
+        auto pairs = [&](auto VEC, RowLoad next /* = fetch_rows(0) */, auto &&f) {
             for (int32_t rs = 0; rs < nr; rs += rows_per_set) {
                 const RowLoad cur = next;
-                if (rs + rows_per_set < nr) next = fetch_rows(rs + rows_per_set);
-                i4 va = cur.va, vb = cur.vb;
-                for (int32_t ch = g; 4 * ch < cur.c; ch += 2 * G) {
-                    if (ch != g) { // rows longer than two chunks per lane
-                        va = load_chunk(cur.base, ch);
-                        vb = load_chunk(cur.base, ch + G);
-                    }
-                    f(cur, va, vb, 4 * ch, 4 * (ch + G));
-                }
+                next = fetch_rows(VEC, rs + rows_per_set); // (unconditional: past the last set it reads the last row again)
+                if (4 * g < cur.c) f(cur, cur.va, cur.vb, 4 * g, 4 * (g + G));
+                for (int32_t ch = g + 2 * G; 4 * ch < cur.c; ch += 2 * G) // rows longer than two chunks per lane
+                    f(cur, load_chunk(VEC, cur.base, ch), load_chunk(VEC, cur.base, ch + G), 4 * ch, 4 * (ch + G));
             }
         };
-        if (nr > 0)
-            pairs(first_rows, [&](const RowLoad &cur, i4 va, i4 vb, int32_t ja, int32_t jb) {
-                int32_t key[8], len[8];
-                bool valid[8], head[8];
-                runs8(va, vb, ja, jb, cur.c, key, len, valid, head);
+        auto count = [&](const RowLoad &cur, i4 va, i4 vb, int32_t ja, int32_t jb) {
+            int32_t key[8], len[8];
+            bool valid[8], head[8];
+            runs8(va, vb, ja, jb, cur.c, key, len, valid, head);
 #pragma unroll
-                for (int q = 0; q < 8; ++q)
-                    if (head[q]) atomicAdd(&bins[key[q]], len[q]);
-            });
+            for (int q = 0; q < 8; ++q)
+                if (head[q]) atomicAdd(&bins[key[q]], len[q]);
+        };
+        if (nr > 0) {
+            if (vec) pairs(std::true_type{}, first_rows, count);
+            else pairs(std::false_type{}, first_rows, count);
+        }
         __syncthreads();
         // exclusive offsets of all groups: thread t owns the bins t, t + 256, ... and lays them out in a row
         int32_t total;
@@ -294,20 +303,23 @@ __global__ void __launch_bounds__(GROUP_THREADS)
         // Filling sweep: the first sample of every run takes the run's place with one returning LDS atomic, and all of
         // a lane's are issued before the first result is used (taken run by run, each atomic's latency sat in front of
         // the next).
-        if (nr > 0)
-            pairs(fetch_rows(0), [&](const RowLoad &cur, i4 va, i4 vb, int32_t ja, int32_t jb) {
-                int32_t key[8], len[8], pos[8];
-                bool valid[8], head[8];
-                runs8(va, vb, ja, jb, cur.c, key, len, valid, head);
+        auto fill = [&](const RowLoad &cur, i4 va, i4 vb, int32_t ja, int32_t jb) {
+            int32_t key[8], len[8], pos[8];
+            bool valid[8], head[8];
+            runs8(va, vb, ja, jb, cur.c, key, len, valid, head);
 #pragma unroll
-                for (int q = 0; q < 8; ++q) pos[q] = head[q] ? atomicAdd(&bins[key[q]], len[q]) : 0;
+            for (int q = 0; q < 8; ++q) pos[q] = head[q] ? atomicAdd(&bins[key[q]], len[q]) : 0;
 #pragma unroll
-                for (int q = 0; q < 8; ++q)
-                    if (valid[q] && !head[q]) pos[q] = pos[q - 1] + 1;
+            for (int q = 0; q < 8; ++q)
+                if (valid[q] && !head[q]) pos[q] = pos[q - 1] + 1;
 #pragma unroll
-                for (int q = 0; q < 8; ++q)
-                    if (valid[q]) perm[pos[q]] = (int32_t)(cur.base + (q < 4 ? ja + q : jb + q - 4));
-            });
+            for (int q = 0; q < 8; ++q)
+                if (valid[q]) perm[pos[q]] = (int32_t)(cur.base + (q < 4 ? ja + q : jb + q - 4));
+        };
+        if (nr > 0) {
+            if (vec) pairs(std::true_type{}, fetch_rows(std::true_type{}, 0), fill);
+            else pairs(std::false_type{}, fetch_rows(std::false_type{}, 0), fill);
+        }
     }
 }
 
