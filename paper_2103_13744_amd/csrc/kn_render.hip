@@ -618,9 +618,13 @@ __global__ void __launch_bounds__(256)
     // the grid covers rows_cap >= n_live rows; the flags of the rows beyond the list are cleared so that the next
     // wave's compaction can run over the same upper bound
     if (owner && i >= n_live && i < rows_cap) alive[i] = 0;
-    const bool mine = owner && i < n_live && alive[i] != 0;
-    const int32_t r = mine ? live[i] : 0;
-    const int32_t n = mine ? cnt[i] : 0;
+    // (flag, ray number and sample count of the row are requested together, from a valid row whatever the lane: taken one
+    // after the other, each behind the test of the one before, they were three round trips in front of the first samples)
+    const int32_t i_safe = max(min(i, n_live - 1), 0);
+    const int32_t alive_i = alive[i_safe], live_i = live[i_safe], cnt_i = cnt[i_safe];
+    const bool mine = owner && i < n_live && alive_i != 0;
+    const int32_t r = mine ? live_i : 0;
+    const int32_t n = mine ? cnt_i : 0;
     float T = 1.0f, c0 = 0.0f, c1 = 0.0f, c2 = 0.0f; // the state of a ray before its first wave
     if (mine && !first_wave) {
         T = s.T[r];
@@ -738,10 +742,15 @@ __global__ void __launch_bounds__(256)
     int32_t blended = 0, evaluated = 0, survivors = 0;
     // the grid covers rows_cap >= n_live rows; the flags of the rows beyond the list are cleared so that the
     // compaction that follows can run over the same upper bound
+    // (flag, ray number, sample count and the first samples of the row are requested together, from a valid row whatever
+    // the lane: one round trip in front of the loop instead of three)
+    const int32_t i_safe = max(min(i, n_live - 1), 0);
+    const int32_t alive_i = alive[i_safe], live_i = live[i_safe], cnt_i = cnt[i_safe];
+    const f4 first = ((const f4 *)out4)[(int64_t)i_safe * S + min(gl, S - 1)];
     if (i >= n_live && i < rows_cap && gl == 0) alive[i] = 0;
-    if (i < n_live && alive[i]) {
-        const int32_t r = live[i];
-        const int32_t n = cnt[i];
+    if (i < n_live && alive_i) {
+        const int32_t r = live_i;
+        const int32_t n = cnt_i;
         const f4 *smp = (const f4 *)out4 + (int64_t)i * S; // row i of the wave's slots
         float T = 1.0f, c0 = 0.0f, c1 = 0.0f, c2 = 0.0f; // the state of a ray before its first wave
         if (!first_wave) {
@@ -751,7 +760,7 @@ __global__ void __launch_bounds__(256)
             c2 = s.C[3 * (int64_t)r + 2];
         }
         bool dead = false;
-        f4 v_next = gl < n ? smp[gl] : (f4){0.0f, 0.0f, 0.0f, 0.0f};
+        f4 v_next = gl < n ? first : (f4){0.0f, 0.0f, 0.0f, 0.0f};
         for (int32_t j0 = 0; j0 < n && !dead; j0 += MARCH_G) {
             f4 v = v_next;
             // the following 16 samples are requested before these are blended (clamped address: always a valid slot of
