@@ -362,16 +362,18 @@ struct RayState {
 constexpr int RAY_BLOCK = 256;  // threads per block of the two set-up kernels
 
 // Sum over the blocks in front of this one of per-block counts written by the previous kernel
-// (each thread takes a strided share; the loads are independent).
+// (each thread takes a strided share; twelve loads of a thread are in flight together: one round trip for the 2,500
+// blocks of an 800x800 frame, where batches of four were three).
 __device__ __forceinline__ int32_t prefix_of_block_sums(const int32_t *__restrict__ blk_sum, int32_t *lds)
 {
+    constexpr int BATCH = 12;
     int32_t acc = 0;
-    for (int b0 = 0; b0 < (int)blockIdx.x; b0 += RAY_BLOCK * 4) {
-        int32_t v[4];
+    for (int b0 = 0; b0 < (int)blockIdx.x; b0 += RAY_BLOCK * BATCH) {
+        int32_t v[BATCH];
 #pragma unroll
-        for (int u = 0; u < 4; ++u) v[u] = blk_sum[min(b0 + u * RAY_BLOCK + (int)threadIdx.x, (int)blockIdx.x)];
+        for (int u = 0; u < BATCH; ++u) v[u] = blk_sum[min(b0 + u * RAY_BLOCK + (int)threadIdx.x, (int)blockIdx.x)];
 #pragma unroll
-        for (int u = 0; u < 4; ++u)
+        for (int u = 0; u < BATCH; ++u)
             if (b0 + u * RAY_BLOCK + (int)threadIdx.x < (int)blockIdx.x) acc += v[u];
     }
     return kn_block_sum(acc, lds);
@@ -455,8 +457,8 @@ __global__ void __launch_bounds__(RAY_BLOCK)
 {
     __shared__ int32_t lds[RAY_BLOCK / KN_WAVE];
     const int64_t r = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int32_t a = r < R ? alive[r] : 0; // (requested in front of the block sums: one round trip for both)
     const int32_t before = prefix_of_block_sums(blk_sum, lds);
-    const int32_t a = r < R ? alive[r] : 0;
     int32_t total;
     const int32_t pos = before + kn_block_exclusive_scan(a, lds, total);
     if (a) {
