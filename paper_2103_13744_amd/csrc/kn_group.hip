@@ -259,6 +259,9 @@ __global__ void __launch_bounds__(GROUP_THREADS)
         // exclusive offsets of all groups: thread t owns the bins t, t + 256, ... and lays them out in a row
         int32_t total;
         const int32_t fused_off0 = kn_block_exclusive_scan(own_sum, scan_lds, total);
+        // the first rows of the filling sweep are requested in front of the reservation's atomics: their round trip runs
+        // under the atomics' longer one
+        const RowLoad fill_first = vec ? fetch_rows(std::true_type{}, 0) : fetch_rows(std::false_type{}, 0);
         {
             // first position of this workgroup's range inside each group it met: the returning atomics of a thread's
             // eight bins are in flight together (a workgroup meets few networks: most threads issue none)
@@ -317,8 +320,8 @@ __global__ void __launch_bounds__(GROUP_THREADS)
                 if (valid[q]) perm[pos[q]] = (int32_t)(cur.base + (q < 4 ? ja + q : jb + q - 4));
         };
         if (nr > 0) {
-            if (vec) pairs(std::true_type{}, fetch_rows(std::true_type{}, 0), fill);
-            else pairs(std::false_type{}, fetch_rows(std::false_type{}, 0), fill);
+            if (vec) pairs(std::true_type{}, fill_first, fill);
+            else pairs(std::false_type{}, fill_first, fill);
         }
     }
 }
