@@ -202,11 +202,24 @@ __global__ void __launch_bounds__(GROUP_THREADS)
             else sweep(std::false_type{}, 0, N, first_rows, count);
         }
         __syncthreads();
-        for (int32_t q = tid; q < bins_cap; q += GROUP_THREADS) {
-            const int32_t k = hkeys[q], c = hcnt[q];
-            if (k >= 0 && c > 0) {
-                hcnt[q] = atomicAdd(&global[k], c); // first position of this workgroup's range inside the group
+        // the first rows of the filling sweep are requested in front of the reservation's atomics: their round trip runs
+        // under the atomics' longer one
+        const RowLoad fill_first = vec ? fetch_rows(std::true_type{}, 0) : fetch_rows(std::false_type{}, 0);
+        // first position of this workgroup's range inside each group it met: the returning atomics of a thread's eight
+        // table slots are in flight together
+        for (int32_t q0 = 0; q0 < bins_cap; q0 += 8 * GROUP_THREADS) {
+            int32_t k[8], c[8], base[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int32_t q = q0 + u * GROUP_THREADS + tid;
+                k[u] = q < bins_cap ? hkeys[q] : -1;
+                c[u] = q < bins_cap ? hcnt[q] : 0;
             }
+#pragma unroll
+            for (int u = 0; u < 8; ++u) base[u] = (k[u] >= 0 && c[u] > 0) ? atomicAdd(&global[k[u]], c[u]) : 0;
+#pragma unroll
+            for (int u = 0; u < 8; ++u)
+                if (k[u] >= 0 && c[u] > 0) hcnt[q0 + u * GROUP_THREADS + tid] = base[u];
         }
         __syncthreads();
         auto fill = [&](int32_t k, int64_t slot, int32_t len) {
@@ -215,8 +228,8 @@ __global__ void __launch_bounds__(GROUP_THREADS)
             for (int32_t t = 0; t < len; ++t) perm[pos + t] = (int32_t)slot + t;
         };
         if (nr > 0) {
-            if (vec) sweep(std::true_type{}, 0, N, fetch_rows(std::true_type{}, 0), fill);
-            else sweep(std::false_type{}, 0, N, fetch_rows(std::false_type{}, 0), fill);
+            if (vec) sweep(std::true_type{}, 0, N, fill_first, fill);
+            else sweep(std::false_type{}, 0, N, fill_first, fill);
         }
     } else {
         __syncthreads(); // counters cleared, histogram staged
