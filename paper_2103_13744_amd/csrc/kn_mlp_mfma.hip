@@ -403,7 +403,7 @@ __global__ void __launch_bounds__(WAVES *KN_WAVE) __attribute__((amdgpu_waves_pe
     int32_t pend_idx = -1;
     auto write_out = [&]() {
         if (pend_idx >= 0) {
-            if (src.out4) {
+            if constexpr (SRC != SRC_POINTS) { // (the staging array of the render / of the re-ordered evaluation)
                 *(f4 *)(src.out4 + 4 * (int64_t)pend_idx) = pend;
             } else {
                 sigma[pend_idx] = pend[3];
@@ -875,6 +875,7 @@ int launch(const kn_scene *sc, hipStream_t st, const KnSampleSrc &src, const KnB
     const bool rays = src.points == nullptr && src.records == nullptr;
     const bool strat = src.strat != 0 && rays;
     if (rays && !src.dir_table) return KN_E_INVALID_ARG;
+    if ((src.out4 != nullptr) != (rays || src.records != nullptr)) return KN_E_INVALID_ARG; // where the results go is part of the kernel variant
     // render: the ray's encoded direction comes from the table, midpoint or stratified lattice; else explicit points,
     // through the index list or re-ordered
     auto kernel = src.records ? (wrap ? k_mlp_mfma<H, BF, WAVES, true, false, SRC_RECORDS> : k_mlp_mfma<H, BF, WAVES, false, false, SRC_RECORDS>)
